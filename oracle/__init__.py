@@ -1,0 +1,10 @@
+"""CPU oracle for tree verification (test infrastructure, not a product path).
+
+Plain, slow, fp64 NumPy restatements of what the verification step of the
+paper computes (Section 2.1 steps 2-3; the tree attention mask of Section
+3.1.2 / Fig. "tree attention mask").  Only tests, the smoke check and the
+benchmark's CPU-baseline leg may import this package; it shares no code with
+the HIP library and never calls it.
+"""
+from .tree_attention import ancestor_sets, tree_verify_attention  # noqa: F401
+from .accept_path import accept_path, AcceptResult  # noqa: F401
