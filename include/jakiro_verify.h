@@ -1,0 +1,171 @@
+/*
+ * libjakiro_verify -- tree verification for Jakiro-style speculative decoding
+ * on AMD MI355X (gfx950).  C ABI: plain pointers and sizes only.
+ *
+ * The two calls follow the verification and refinement steps of speculative
+ * decoding as the paper states them (Section 2.1, steps 2 and 3), applied to
+ * the draft token TREE that Jakiro's two experts build (Section 3.1.2: at
+ * every depth each activated expert proposes its own top-k candidates, the
+ * higher-scoring expert's on the left; candidates are verified together
+ * through a tree attention mask):
+ *
+ *   jk_tree_verify_attention  the attention of the target model's single
+ *       verification pass: every tree node attends to the committed KV prefix,
+ *       to itself and to its tree ancestors, and to nothing else, so that each
+ *       node's result equals what ordinary decoding of its root-to-node path
+ *       would give.
+ *   jk_accept_path            the acceptance walk: greedy ("strict top-1
+ *       verification", Section 3.2) or speculative sampling (accept with
+ *       probability min(1, p/q); on rejection continue with
+ *       norm(max(0, p - q)), Section 2.1), returning the accepted
+ *       root-to-leaf path and the extra ("bonus") token.
+ *
+ * Conventions
+ *   - "device" pointers are HIP device memory of the current device; "host"
+ *     pointers are ordinary host memory.  The caller owns every buffer.  The
+ *     library allocates no device memory and keeps no state between calls;
+ *     scratch comes from the caller's workspace (sizes from the *_workspace
+ *     functions; 256-byte aligned).
+ *   - Calls enqueue work on `hip_stream` (a hipStream_t, NULL = default
+ *     stream) and return without synchronising.  Outputs are valid once the
+ *     stream has reached that point.  Calls that share a workspace must be
+ *     ordered on one stream.
+ *   - Errors are return codes only.  On any code other than JK_OK nothing was
+ *     launched and no output was written.
+ *   - Trees: parent[i] is the tree parent of node i, -1 for a child of the
+ *     committed prefix (several such nodes are allowed), and -1 <= parent[i] < i
+ *     (any topological numbering, e.g. BFS).  Children of one parent are
+ *     ordered left to right by increasing index.  The array lives on the
+ *     device, so the library cannot check it: a node whose entry violates the
+ *     rule is treated as having parent -1.  jk_validate_tree checks a host copy.
+ */
+#ifndef JAKIRO_VERIFY_H
+#define JAKIRO_VERIFY_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  JK_OK = 0,
+  JK_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, bad stride, bad scale/temperature */
+  JK_ERR_BAD_TREE = 2,    /* jk_validate_tree only */
+  JK_ERR_UNSUPPORTED = 3, /* shape outside the supported set (see each call) */
+  JK_ERR_WORKSPACE = 4,   /* workspace missing, misaligned or too small */
+  JK_ERR_HIP = 5          /* a HIP runtime call failed (launch configuration, bad stream) */
+} jk_status;
+
+typedef enum { JK_BF16 = 0, JK_F32 = 1 } jk_dtype;
+typedef enum { JK_GREEDY = 0, JK_SAMPLE = 1 } jk_mode;
+
+#define JK_MAX_TREE 128 /* largest supported number of tree nodes */
+
+/* Shape and layout of one attention call.  Strides are in ELEMENTS; the
+ * innermost (head_dim) index is contiguous; for JK_BF16 every base pointer
+ * and every stride must be a multiple of 8 elements (16 bytes), for JK_F32 a
+ * multiple of 4 elements.
+ *   q, out           [batch, n_tree, n_q_heads, head_dim]   (q_stride_* and o_stride_*)
+ *   k_cache, v_cache [batch, capacity >= max_prefix_len, n_kv_heads, head_dim]
+ *   k_tree, v_tree   [batch, n_tree, n_kv_heads, head_dim]
+ * Query head h uses KV head h / (n_q_heads / n_kv_heads) (consecutive heads share). */
+typedef struct {
+  int32_t batch, n_tree, n_q_heads, n_kv_heads, head_dim;
+  int64_t q_stride_b, q_stride_t, q_stride_h;
+  int64_t kc_stride_b, kc_stride_l, kc_stride_h;
+  int64_t kt_stride_b, kt_stride_t, kt_stride_h;
+  int64_t o_stride_b, o_stride_t, o_stride_h;
+  float scale;    /* softmax scale; 0 selects 1/sqrt(head_dim); must not be negative */
+  int32_t dtype;  /* jk_dtype of q, k, v and out */
+} jk_attn_desc;
+
+/* Bytes of workspace jk_tree_verify_attention needs for this shape and this
+ * upper bound on the prefix length.  Returns 0 for an invalid descriptor. */
+size_t jk_tree_verify_attention_workspace(const jk_attn_desc* desc, int32_t max_prefix_len);
+
+/* Tree-masked verification attention (Section 2.1 step 2; Section 3.1.2 tree mask).
+ *
+ * For every sequence b, node i and query head h:
+ *     keys   = cache positions 0 .. prefix_len[b]-1  and  tree nodes {i, parent[i], parent[parent[i]], ...}
+ *     out[b,i,h,:] = softmax_j(scale * <q[b,i,h,:], k_j>) . v_j
+ *
+ *   q, k_cache, v_cache, k_tree, v_tree   device, read only, layouts above
+ *   parent       device int32 [batch, n_tree]
+ *   prefix_len   device int32 [batch]; values are clamped to [0, max_prefix_len]
+ *   max_prefix_len  host scalar: upper bound on prefix_len[], at most the cache
+ *                capacity; it sizes the launch and the workspace.  (The lengths
+ *                themselves stay on the device so that a decoding loop never
+ *                needs a host round trip between its steps.)
+ *   out          device, written; same dtype as q
+ *   workspace    device, >= jk_tree_verify_attention_workspace(desc, max_prefix_len) bytes
+ *
+ * Supported: JK_BF16 with head_dim 64 or 128 (MFMA path), JK_F32 with
+ * head_dim <= 256 and a multiple of 4 (plain-ALU path); 1 <= n_tree <= JK_MAX_TREE;
+ * n_q_heads a multiple of n_kv_heads.  Value rows of tree nodes that a query
+ * cannot see must be finite (they are multiplied by an exact zero); their key
+ * rows, and anything in the cache beyond prefix_len, are never used.
+ * Accumulation is fp32; JK_BF16 rounds the softmax weights to bf16 before the
+ * value product. */
+jk_status jk_tree_verify_attention(const jk_attn_desc* desc, const void* q, const void* k_cache,
+                                   const void* v_cache, const void* k_tree, const void* v_tree,
+                                   const int32_t* parent, const int32_t* prefix_len,
+                                   int32_t max_prefix_len, void* out, void* workspace,
+                                   size_t workspace_bytes, void* hip_stream);
+
+/* Bytes of workspace jk_accept_path needs.  Returns 0 for invalid sizes. */
+size_t jk_accept_path_workspace(int32_t batch, int32_t n_tree, int32_t vocab, int32_t mode);
+
+/* Acceptance walk over the verified tree (Section 2.1 steps 2-3; Section 3.2
+ * for greedy).  Logits row 0 is the target's distribution after the committed
+ * prefix, row k+1 the one after tree node k; node k is judged with its
+ * parent's row.  Starting at the prefix (c = -1):
+ *   JK_GREEDY  t* = argmax of row c+1 (lowest id on ties); move to the first
+ *              (left-most) child of c whose token is t*; stop when there is
+ *              none; the bonus token is that last t*.
+ *   JK_SAMPLE  p = softmax(row c+1 / temperature); children of c are tried
+ *              left to right: child k with token x is accepted iff
+ *              uniforms[k] * draft_probs[k][x] < p[x]; after a rejection p
+ *              becomes max(0, p - draft_probs[k]) renormalised (kept if that
+ *              sums to zero).  Stop when no child is accepted; the bonus token
+ *              is the smallest v whose cumulative p exceeds uniforms[n_tree]
+ *              times the total.
+ *
+ *   tree_tokens   device int32 [batch, n_tree]
+ *   parent        device int32 [batch, n_tree]
+ *   target_logits device fp32  [batch, n_tree+1, vocab], finite or -inf
+ *   temperature   > 0; ignored by JK_GREEDY
+ *   draft_probs   device fp32  [batch, n_tree, vocab]; required by JK_SAMPLE, else may be NULL
+ *   uniforms      device fp32  [batch, n_tree+1] in [0,1); required by JK_SAMPLE
+ *   out_path        device int32 [batch, max_depth]: accepted node ids, root-most first, -1 padded
+ *   out_accept_len  device int32 [batch]: number of accepted nodes (capped at max_depth)
+ *   out_bonus_token device int32 [batch]
+ *   workspace     device, >= jk_accept_path_workspace(...) bytes
+ *
+ * Supported: 1 <= n_tree <= JK_MAX_TREE, vocab >= 1, max_depth >= 1.
+ * All sampling arithmetic (softmax, residuals, cumulative sums) is fp64, so a
+ * decision can differ from exact arithmetic only when its two sides agree to
+ * about 1e-13 relative. */
+jk_status jk_accept_path(int32_t batch, int32_t n_tree, int32_t vocab, int32_t max_depth,
+                         const int32_t* tree_tokens, const int32_t* parent,
+                         const float* target_logits, int32_t mode, float temperature,
+                         const float* draft_probs, const float* uniforms, int32_t* out_path,
+                         int32_t* out_accept_len, int32_t* out_bonus_token, void* workspace,
+                         size_t workspace_bytes, void* hip_stream);
+
+/* Host-side check of a tree held in host memory: JK_OK, JK_ERR_BAD_TREE
+ * (some parent[i] outside [-1, i-1]) or JK_ERR_INVALID_ARG (null, n outside
+ * [1, JK_MAX_TREE]). */
+jk_status jk_validate_tree(const int32_t* parent_host, int32_t n_tree);
+
+/* Static, NUL-terminated description of a status code. */
+const char* jk_status_string(int32_t status);
+
+/* Library version, "major.minor". */
+const char* jk_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* JAKIRO_VERIFY_H */

@@ -1,0 +1,11 @@
+"""MI355X-native tree verification for Jakiro-style speculative decoding.
+
+Thin Python binding over the C-ABI library libjakiro_verify.so (hand-written
+HIP kernels for gfx950).  Every step of the computation runs in those kernels;
+this package only marshals arguments.  There is no CPU fallback: importing the
+binding functions without the built library raises.
+"""
+from .binding import (  # noqa: F401
+    JK_BF16, JK_F32, JK_GREEDY, JK_SAMPLE, JakiroError, accept_path, accept_path_workspace, lib,
+    library_path, tree_verify_attention, tree_verify_attention_workspace, validate_tree, version,
+)

@@ -1,0 +1,197 @@
+"""ctypes binding of libjakiro_verify (argument marshalling only).
+
+Function names and argument meaning follow include/jakiro_verify.h.  Tensors
+are torch tensors on the ROCm device; torch is used for device memory and the
+current stream, nothing else.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libjakiro_verify.so")
+
+JK_BF16, JK_F32 = 0, 1
+JK_GREEDY, JK_SAMPLE = 0, 1
+MAX_TREE = 128
+
+
+class JakiroError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {lib().jk_status_string(status).decode()} (status {status})")
+
+
+class AttnDesc(ctypes.Structure):
+    _fields_ = [
+        ("batch", ctypes.c_int32), ("n_tree", ctypes.c_int32), ("n_q_heads", ctypes.c_int32),
+        ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+        ("q_stride_b", ctypes.c_int64), ("q_stride_t", ctypes.c_int64), ("q_stride_h", ctypes.c_int64),
+        ("kc_stride_b", ctypes.c_int64), ("kc_stride_l", ctypes.c_int64), ("kc_stride_h", ctypes.c_int64),
+        ("kt_stride_b", ctypes.c_int64), ("kt_stride_t", ctypes.c_int64), ("kt_stride_h", ctypes.c_int64),
+        ("o_stride_b", ctypes.c_int64), ("o_stride_t", ctypes.c_int64), ("o_stride_h", ctypes.c_int64),
+        ("scale", ctypes.c_float), ("dtype", ctypes.c_int32),
+    ]
+
+
+_lib = None
+
+EXPORTS = ("jk_tree_verify_attention_workspace", "jk_tree_verify_attention", "jk_accept_path_workspace",
+           "jk_accept_path", "jk_validate_tree", "jk_status_string", "jk_version")
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded library; raises if it has not been built (no fallback path exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise RuntimeError(f"{_LIB_PATH} is missing: build it with "
+                               "`python -m paper_2502_06282_amd.build` (needs hipcc)")
+        l = ctypes.CDLL(_LIB_PATH)
+        vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+        l.jk_tree_verify_attention_workspace.restype = sz
+        l.jk_tree_verify_attention_workspace.argtypes = [ctypes.POINTER(AttnDesc), i32]
+        l.jk_tree_verify_attention.restype = i32
+        l.jk_tree_verify_attention.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp, vp, i32,
+                                               vp, vp, sz, vp]
+        l.jk_accept_path_workspace.restype = sz
+        l.jk_accept_path_workspace.argtypes = [i32, i32, i32, i32]
+        l.jk_accept_path.restype = i32
+        l.jk_accept_path.argtypes = [i32, i32, i32, i32, vp, vp, vp, i32, ctypes.c_float, vp, vp, vp, vp,
+                                     vp, vp, sz, vp]
+        l.jk_validate_tree.restype = i32
+        l.jk_validate_tree.argtypes = [ctypes.POINTER(ctypes.c_int32), i32]
+        l.jk_status_string.restype = ctypes.c_char_p
+        l.jk_status_string.argtypes = [i32]
+        l.jk_version.restype = ctypes.c_char_p
+        l.jk_version.argtypes = []
+        _lib = l
+    return _lib
+
+
+def version() -> str:
+    return lib().jk_version().decode()
+
+
+def validate_tree(parent) -> int:
+    """Status code of jk_validate_tree for a host sequence of ints."""
+    arr = (ctypes.c_int32 * len(parent))(*[int(x) for x in parent])
+    return int(lib().jk_validate_tree(arr, len(parent)))
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream_handle(stream) -> Optional[int]:
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream or None
+
+
+def _make_desc(q, k_cache, k_tree, out, scale: float) -> AttnDesc:
+    import torch
+    B, T, Hq, D = q.shape
+    Hkv = k_tree.shape[2]
+    if q.dtype == torch.bfloat16:
+        dt = JK_BF16
+    elif q.dtype == torch.float32:
+        dt = JK_F32
+    else:
+        raise TypeError("q must be bfloat16 or float32")
+    for t in (q, k_cache, k_tree, out):
+        if t is not None and t.stride(-1) != 1 and t.shape[-1] > 1:
+            raise ValueError("head_dim must be the contiguous innermost axis")
+    kc = k_cache.stride() if k_cache is not None else (0, 0, 0, 1)
+    return AttnDesc(B, T, Hq, Hkv, D, q.stride(0), q.stride(1), q.stride(2), kc[0], kc[1], kc[2],
+                    k_tree.stride(0), k_tree.stride(1), k_tree.stride(2),
+                    out.stride(0), out.stride(1), out.stride(2), float(scale), dt)
+
+
+def tree_verify_attention_workspace(q, k_cache, k_tree, max_prefix_len: int, scale: float = 0.0) -> int:
+    d = _make_desc(q, k_cache, k_tree, q, scale)
+    return int(lib().jk_tree_verify_attention_workspace(ctypes.byref(d), int(max_prefix_len)))
+
+
+def tree_verify_attention(q, k_cache, v_cache, k_tree, v_tree, parent, prefix_len,
+                          max_prefix_len: Optional[int] = None, scale: float = 0.0, out=None,
+                          workspace=None, stream=None):
+    """jk_tree_verify_attention.  q [B,T,Hq,D]; k_cache, v_cache [B,Lcap,Hkv,D] (same strides);
+    k_tree, v_tree [B,T,Hkv,D] (same strides); parent int32 [B,T]; prefix_len int32 [B], all on
+    the device.  Returns out [B,T,Hq,D] (allocated unless given).  Asynchronous on `stream`
+    (default: torch's current stream)."""
+    import torch
+    if k_cache is not None and k_cache.shape[1] == 0:  # an empty cache has no meaningful strides
+        k_cache = v_cache = None
+    if max_prefix_len is None:
+        max_prefix_len = 0 if k_cache is None else int(k_cache.shape[1])
+    if out is None:
+        out = torch.empty_like(q, memory_format=torch.contiguous_format)
+    if k_cache is not None and (k_cache.stride() != v_cache.stride() or k_cache.shape != v_cache.shape):
+        raise ValueError("k_cache and v_cache must share shape and strides")
+    if k_tree.stride() != v_tree.stride() or k_tree.shape != v_tree.shape:
+        raise ValueError("k_tree and v_tree must share shape and strides")
+    if parent.dtype != torch.int32 or prefix_len.dtype != torch.int32:
+        raise TypeError("parent and prefix_len must be int32")
+    if not (parent.is_contiguous() and prefix_len.is_contiguous()):
+        raise ValueError("parent and prefix_len must be contiguous")
+    d = _make_desc(q, k_cache, k_tree, out, scale)
+    need = int(lib().jk_tree_verify_attention_workspace(ctypes.byref(d), int(max_prefix_len)))
+    if need == 0:
+        raise JakiroError(3, "jk_tree_verify_attention_workspace")
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    st = lib().jk_tree_verify_attention(ctypes.byref(d), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(k_tree),
+                                        _ptr(v_tree), _ptr(parent), _ptr(prefix_len), int(max_prefix_len),
+                                        _ptr(out), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                        _stream_handle(stream))
+    if st != 0:
+        raise JakiroError(st, "jk_tree_verify_attention")
+    return out
+
+
+def accept_path_workspace(batch: int, n_tree: int, vocab: int, mode: int) -> int:
+    return int(lib().jk_accept_path_workspace(batch, n_tree, vocab, mode))
+
+
+def accept_path(tree_tokens, parent, target_logits, mode: int = JK_GREEDY, temperature: float = 1.0,
+                draft_probs=None, uniforms=None, max_depth: Optional[int] = None, workspace=None,
+                stream=None) -> Tuple["torch.Tensor", "torch.Tensor", "torch.Tensor"]:
+    """jk_accept_path.  tree_tokens, parent int32 [B,N]; target_logits fp32 [B,N+1,V] contiguous;
+    sampling also needs draft_probs fp32 [B,N,V] and uniforms fp32 [B,N+1].
+    Returns (path [B,max_depth], accept_len [B], bonus_token [B]) int32 device tensors."""
+    import torch
+    B, N = tree_tokens.shape
+    V = target_logits.shape[-1]
+    if max_depth is None:
+        max_depth = N
+    for t in (tree_tokens, parent):
+        if t.dtype != torch.int32 or not t.is_contiguous():
+            raise TypeError("tree_tokens and parent must be contiguous int32")
+    for t in (target_logits, draft_probs, uniforms):
+        if t is not None and (t.dtype != torch.float32 or not t.is_contiguous()):
+            raise TypeError("logits, draft_probs and uniforms must be contiguous float32")
+    if target_logits.shape != (B, N + 1, V):
+        raise ValueError("target_logits must be [B, N+1, V]")
+    dev = tree_tokens.device
+    path = torch.empty((B, max_depth), dtype=torch.int32, device=dev)
+    alen = torch.empty((B,), dtype=torch.int32, device=dev)
+    bonus = torch.empty((B,), dtype=torch.int32, device=dev)
+    need = accept_path_workspace(B, N, V, mode)
+    if need == 0:
+        raise JakiroError(3, "jk_accept_path_workspace")
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    st = lib().jk_accept_path(B, N, V, int(max_depth), _ptr(tree_tokens), _ptr(parent), _ptr(target_logits),
+                              int(mode), float(temperature), _ptr(draft_probs), _ptr(uniforms), _ptr(path),
+                              _ptr(alen), _ptr(bonus), _ptr(workspace),
+                              workspace.numel() * workspace.element_size(), _stream_handle(stream))
+    if st != 0:
+        raise JakiroError(st, "jk_accept_path")
+    return path, alen, bonus

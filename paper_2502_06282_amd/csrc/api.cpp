@@ -1,0 +1,201 @@
+// C-ABI entry points of libjakiro_verify: argument checks, launch planning,
+// kernel launches.  No device memory is allocated here and nothing synchronises.
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+
+#include "jk_internal.h"
+
+namespace jk {
+
+namespace {
+int device_cu_count() {
+  static int cus = 0;  // same value whoever writes it first
+  if (cus == 0) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+      cus = n;
+    else
+      cus = 256;
+  }
+  return cus;
+}
+
+bool desc_ok(const jk_attn_desc& d) {
+  if (d.batch < 1 || d.n_tree < 1 || d.n_tree > JK_MAX_TREE) return false;
+  if (d.n_q_heads < 1 || d.n_kv_heads < 1 || d.n_q_heads % d.n_kv_heads) return false;
+  if (d.dtype != JK_BF16 && d.dtype != JK_F32) return false;
+  if (!(d.scale >= 0.f) || !std::isfinite(d.scale)) return false;
+  return true;
+}
+bool shape_supported(const jk_attn_desc& d) {
+  if (d.dtype == JK_BF16) return d.head_dim == 64 || d.head_dim == 128;
+  return d.head_dim >= 4 && d.head_dim <= 256 && d.head_dim % 4 == 0;
+}
+}  // namespace
+
+bool make_attn_plan(const jk_attn_desc& d, int max_prefix_len, AttnPlan* pl) {
+  if (!desc_ok(d) || !shape_supported(d) || max_prefix_len < 0) return false;
+  const int G = d.n_q_heads / d.n_kv_heads;
+  pl->m_rows = d.n_tree * G;
+  const long long units = (long long)d.batch * d.n_kv_heads;
+  if (d.dtype == JK_BF16) {
+    if (pl->m_rows <= 64) { pl->wm = 1; pl->wn = 4; }
+    else if (pl->m_rows <= 128) { pl->wm = 2; pl->wn = 2; }
+    else { pl->wm = 4; pl->wn = 1; }
+    pl->q_rows = 64 * pl->wm;
+    pl->n_qtiles = (pl->m_rows + pl->q_rows - 1) / pl->q_rows;
+    pl->m_pad = pl->n_qtiles * pl->q_rows;
+    // enough workgroups to occupy every CU once, each keeping at least one round of tiles
+    const int n_tiles = (max_prefix_len + kTileKeys - 1) / kTileKeys + (d.n_tree + kTileKeys - 1) / kTileKeys;
+    const long long wgs = units * pl->n_qtiles;
+    long long s = (device_cu_count() + wgs - 1) / wgs;
+    const int max_by_tiles = n_tiles / (2 * pl->wn) > 0 ? n_tiles / (2 * pl->wn) : 1;
+    if (s > max_by_tiles) s = max_by_tiles;
+    if (s > kMaxSplits) s = kMaxSplits;
+    if (s < 1) s = 1;
+    if (const char* e = std::getenv("JK_ATTN_SPLITS")) {  // tuning override
+      const int v = std::atoi(e);
+      if (v >= 1 && v <= kMaxSplits) s = v;
+    }
+    pl->splits = (int)s;
+  } else {
+    pl->wm = pl->wn = 1;
+    pl->q_rows = 1;
+    pl->n_qtiles = pl->m_rows;
+    pl->m_pad = pl->m_rows;
+    const long long keys = (long long)max_prefix_len + d.n_tree;
+    long long s = (keys + 1023) / 1024;  // each fp32 workgroup holds at most 1024 scores
+    if (s > 65535) return false;
+    pl->splits = (int)s;
+  }
+  auto up = [](size_t x) { return (x + 255) / 256 * 256; };
+  const size_t rows = (size_t)units * pl->splits * pl->m_pad;
+  const bool need_parts = (d.dtype == JK_F32) || pl->splits > 1;
+  pl->part_o_bytes = need_parts ? up(rows * d.head_dim * sizeof(float)) : 0;
+  pl->part_ml_bytes = need_parts ? up(rows * sizeof(float2)) : 0;
+  pl->total_bytes = pl->part_o_bytes + pl->part_ml_bytes;
+  if (pl->total_bytes == 0) pl->total_bytes = 256;  // never ask the caller for a zero-byte buffer
+  return true;
+}
+
+}  // namespace jk
+
+using namespace jk;
+
+extern "C" {
+
+size_t jk_tree_verify_attention_workspace(const jk_attn_desc* desc, int32_t max_prefix_len) {
+  AttnPlan pl;
+  if (!desc || !make_attn_plan(*desc, max_prefix_len, &pl)) return 0;
+  return pl.total_bytes;
+}
+
+jk_status jk_tree_verify_attention(const jk_attn_desc* desc, const void* q, const void* k_cache,
+                                   const void* v_cache, const void* k_tree, const void* v_tree,
+                                   const int32_t* parent, const int32_t* prefix_len, int32_t max_prefix_len,
+                                   void* out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!desc || !q || !k_tree || !v_tree || !parent || !prefix_len || !out) return JK_ERR_INVALID_ARG;
+  if (max_prefix_len < 0) return JK_ERR_INVALID_ARG;
+  if (max_prefix_len > 0 && (!k_cache || !v_cache)) return JK_ERR_INVALID_ARG;
+  const jk_attn_desc& d = *desc;
+  if (!desc_ok(d)) return JK_ERR_INVALID_ARG;
+  if (!shape_supported(d)) return JK_ERR_UNSUPPORTED;
+  const int64_t align = (d.dtype == JK_BF16) ? 8 : 4;
+  const size_t es = (d.dtype == JK_BF16) ? 2 : 4;
+  const int64_t strides[] = {d.q_stride_b, d.q_stride_t, d.q_stride_h, d.kc_stride_b, d.kc_stride_l,
+                             d.kc_stride_h, d.kt_stride_b, d.kt_stride_t, d.kt_stride_h, d.o_stride_b,
+                             d.o_stride_t, d.o_stride_h};
+  for (int64_t s : strides)
+    if (s < 0 || s % align) return JK_ERR_INVALID_ARG;
+  if (d.q_stride_t < d.head_dim && d.n_tree > 1) return JK_ERR_INVALID_ARG;
+  const void* ptrs[] = {q, k_cache, v_cache, k_tree, v_tree, out};
+  for (const void* p : ptrs)
+    if (reinterpret_cast<uintptr_t>(p) % (align * es)) return JK_ERR_INVALID_ARG;
+
+  AttnPlan pl;
+  if (!make_attn_plan(d, max_prefix_len, &pl)) return JK_ERR_UNSUPPORTED;
+  if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256) return JK_ERR_WORKSPACE;
+  if (workspace_bytes < pl.total_bytes) return JK_ERR_WORKSPACE;
+
+  AttnArgs a;
+  a.q = q; a.k_cache = k_cache; a.v_cache = v_cache; a.k_tree = k_tree; a.v_tree = v_tree;
+  a.parent = parent; a.prefix_len = prefix_len; a.out = out;
+  a.part_o = reinterpret_cast<float*>(workspace);
+  a.part_ml = reinterpret_cast<float2*>(static_cast<char*>(workspace) + pl.part_o_bytes);
+  a.d = d;
+  a.max_prefix_len = max_prefix_len;
+  const float scale = d.scale > 0.f ? d.scale : 1.0f / std::sqrt((float)d.head_dim);
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  hipError_t e;
+  if (d.dtype == JK_BF16) {
+    a.scale_log2 = scale * 1.44269504088896340736f;
+    e = launch_tva_bf16(a, pl, stream);
+    if (e == hipSuccess && pl.splits > 1) e = launch_tva_combine(a, pl, stream);
+  } else {
+    a.scale_log2 = scale;  // the fp32 path works in natural units
+    e = launch_tva_f32(a, pl, stream);
+    if (e == hipSuccess) e = launch_tva_combine(a, pl, stream);
+  }
+  return e == hipSuccess ? JK_OK : JK_ERR_HIP;
+}
+
+size_t jk_accept_path_workspace(int32_t batch, int32_t n_tree, int32_t vocab, int32_t mode) {
+  if (batch < 1 || n_tree < 1 || n_tree > JK_MAX_TREE || vocab < 1) return 0;
+  if (mode != JK_GREEDY && mode != JK_SAMPLE) return 0;
+  return accept_workspace_bytes(batch, n_tree, vocab, mode);
+}
+
+jk_status jk_accept_path(int32_t batch, int32_t n_tree, int32_t vocab, int32_t max_depth,
+                         const int32_t* tree_tokens, const int32_t* parent, const float* target_logits,
+                         int32_t mode, float temperature, const float* draft_probs, const float* uniforms,
+                         int32_t* out_path, int32_t* out_accept_len, int32_t* out_bonus_token, void* workspace,
+                         size_t workspace_bytes, void* hip_stream) {
+  if (batch < 1 || vocab < 1 || max_depth < 1) return JK_ERR_INVALID_ARG;
+  if (n_tree < 1) return JK_ERR_INVALID_ARG;
+  if (n_tree > JK_MAX_TREE) return JK_ERR_UNSUPPORTED;
+  if (mode != JK_GREEDY && mode != JK_SAMPLE) return JK_ERR_INVALID_ARG;
+  if (!tree_tokens || !parent || !target_logits || !out_path || !out_accept_len || !out_bonus_token)
+    return JK_ERR_INVALID_ARG;
+  if (reinterpret_cast<uintptr_t>(target_logits) % 16) return JK_ERR_INVALID_ARG;
+  if ((long long)batch * (n_tree + 1) > 65535) return JK_ERR_UNSUPPORTED;
+  if (mode == JK_SAMPLE) {
+    if (!draft_probs || !uniforms) return JK_ERR_INVALID_ARG;
+    if (!(temperature > 0.f) || !std::isfinite(temperature)) return JK_ERR_INVALID_ARG;
+  }
+  const size_t need = accept_workspace_bytes(batch, n_tree, vocab, mode);
+  if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256) return JK_ERR_WORKSPACE;
+  if (workspace_bytes < need) return JK_ERR_WORKSPACE;
+  AcceptArgs a;
+  a.batch = batch; a.n_tree = n_tree; a.vocab = vocab; a.max_depth = max_depth; a.mode = mode;
+  a.temperature = temperature;
+  a.tokens = tree_tokens; a.parent = parent; a.logits = target_logits;
+  a.draft_probs = draft_probs; a.uniforms = uniforms;
+  a.out_path = out_path; a.out_len = out_accept_len; a.out_bonus = out_bonus_token;
+  a.workspace = workspace;
+  return launch_accept(a, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? JK_OK : JK_ERR_HIP;
+}
+
+jk_status jk_validate_tree(const int32_t* parent_host, int32_t n_tree) {
+  if (!parent_host || n_tree < 1 || n_tree > JK_MAX_TREE) return JK_ERR_INVALID_ARG;
+  for (int32_t i = 0; i < n_tree; ++i)
+    if (parent_host[i] < -1 || parent_host[i] >= i) return JK_ERR_BAD_TREE;
+  return JK_OK;
+}
+
+const char* jk_status_string(int32_t status) {
+  switch (status) {
+    case JK_OK: return "ok";
+    case JK_ERR_INVALID_ARG: return "invalid argument";
+    case JK_ERR_BAD_TREE: return "parent[] violates -1 <= parent[i] < i";
+    case JK_ERR_UNSUPPORTED: return "unsupported shape";
+    case JK_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case JK_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+const char* jk_version(void) { return "0.1"; }
+
+}  // extern "C"

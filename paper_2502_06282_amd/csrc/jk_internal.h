@@ -1,0 +1,58 @@
+// Internal declarations shared by the library's translation units (not installed).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "jakiro_verify.h"
+
+namespace jk {
+
+constexpr int kWaveSize = 64;
+constexpr int kTileKeys = 32;      // keys per attention tile (one MFMA M-block)
+constexpr int kMaxSplits = 64;     // upper bound on KV splits per (sequence, KV head)
+
+// How one attention call is cut into workgroups.  Derived on the host from the
+// descriptor and the prefix bound only, so that the workspace query and the
+// launch always agree.
+struct AttnPlan {
+  int wm;          // waves along the query-row axis (64 rows each)
+  int wn;          // waves along the key axis (each takes every wn-th tile)
+  int q_rows;      // query rows per workgroup = 64 * wm
+  int n_qtiles;    // workgroups along the query-row axis
+  int m_rows;      // T * G query rows per KV head
+  int m_pad;       // n_qtiles * q_rows
+  int splits;      // KV splits
+  size_t part_o_bytes, part_ml_bytes, total_bytes;
+};
+
+bool make_attn_plan(const jk_attn_desc& d, int max_prefix_len, AttnPlan* plan);
+
+struct AttnArgs {
+  const void *q, *k_cache, *v_cache, *k_tree, *v_tree;
+  const int32_t* parent;
+  const int32_t* prefix_len;
+  void* out;
+  float* part_o;    // [B*Hkv][splits][m_pad][D]
+  float2* part_ml;  // [B*Hkv][splits][m_pad]  (running max in log2 units, sum)
+  jk_attn_desc d;
+  int max_prefix_len;
+  float scale_log2;  // softmax scale * log2(e)
+};
+
+hipError_t launch_tva_bf16(const AttnArgs& a, const AttnPlan& p, hipStream_t stream);
+hipError_t launch_tva_f32(const AttnArgs& a, const AttnPlan& p, hipStream_t stream);
+hipError_t launch_tva_combine(const AttnArgs& a, const AttnPlan& p, hipStream_t stream);
+
+struct AcceptArgs {
+  int batch, n_tree, vocab, max_depth, mode;
+  float temperature;
+  const int32_t *tokens, *parent;
+  const float *logits, *draft_probs, *uniforms;
+  int32_t *out_path, *out_len, *out_bonus;
+  void* workspace;
+};
+size_t accept_workspace_bytes(int batch, int n_tree, int vocab, int mode);
+hipError_t launch_accept(const AcceptArgs& a, hipStream_t stream);
+
+}  // namespace jk

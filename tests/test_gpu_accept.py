@@ -1,0 +1,168 @@
+"""GPU parity: jk_accept_path (through the C ABI) against the oracle: accepted path,
+accepted length and bonus token must be bit-exact on identical logits / uniforms.
+Sampling decisions are thresholds on rounded sums.  The kernels do all sampling
+arithmetic in fp64 like the oracle, so the two sides differ by summation order
+only (~1e-13 relative); a seed is compared when every decision on the oracle's
+walk has a relative margin above 1e-9, which the inverse-CDF draw (steps of
+~1/vocab) still leaves to practically every seed.  Seeds below the margin are
+counted and reported, never silently dropped."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2502_06282_amd as jk
+from oracle import accept_path as oracle_accept
+from workloads import CONFIGS, accept_inputs, tree_for_config
+
+pytestmark = pytest.mark.gpu
+MARGIN = 1e-9
+
+
+def _gpu_accept(a, par, mode, temperature=1.0, max_depth=None):
+    dev = torch.device("cuda")
+    t = lambda v: None if v is None else torch.from_numpy(np.ascontiguousarray(v)).to(dev)
+    path, alen, bonus = jk.accept_path(t(a["tokens"]), t(par.astype(np.int32)), t(a["logits"]),
+                                       jk.JK_GREEDY if mode == "greedy" else jk.JK_SAMPLE, temperature,
+                                       t(a["draft_probs"]), t(a["uniforms"]), max_depth=max_depth)
+    torch.cuda.synchronize()
+    return path.cpu().numpy(), alen.cpu().numpy(), bonus.cpu().numpy()
+
+
+def _compare(a, par, mode, temperature=1.0):
+    path, alen, bonus = _gpu_accept(a, par, mode, temperature)
+    skipped = 0
+    for b in range(par.shape[0]):
+        r = oracle_accept(a["tokens"][b], par[b], a["logits"][b], mode,
+                          None if a["draft_probs"] is None else a["draft_probs"][b],
+                          None if a["uniforms"] is None else a["uniforms"][b], temperature)
+        if mode == "sample" and r.min_margin <= MARGIN:
+            skipped += 1
+            continue
+        assert alen[b] == r.accept_len
+        assert path[b, : alen[b]].tolist() == r.path
+        assert (path[b, alen[b]:] == -1).all()
+        assert bonus[b] == r.bonus_token
+    return skipped
+
+
+def test_c1_greedy():
+    cfg = CONFIGS["c1_tiny"]
+    par = tree_for_config(cfg)
+    _compare(accept_inputs(cfg, par), par, "greedy")
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_c2_greedy_full_vocab(seed):
+    cfg = CONFIGS["c2_vicuna7b"]
+    par = tree_for_config(cfg, seed=seed)
+    a = accept_inputs(cfg, par, seed=seed)
+    _compare(a, par, "greedy")
+    path, alen, bonus = _gpu_accept(a, par, "greedy")
+    stop = path[0, alen[0] - 1] if alen[0] else -1
+    assert bonus[0] == a["top_token"][0, stop + 1]          # the planted top-1, known without an argmax
+
+
+def test_c4_greedy_batched():
+    cfg = CONFIGS["c4_llama2_13b"]
+    par = tree_for_config(cfg)
+    _compare(accept_inputs(cfg, par), par, "greedy")
+
+
+@pytest.mark.parametrize("V", [1, 3, 4095, 4096, 4097, 10001])
+def test_greedy_odd_vocab_sizes(V):
+    cfg = CONFIGS["c2_vicuna7b"].with_(vocab=V, batch=2, hit_prob=0.7 if V > 20 else 0.0)
+    par = tree_for_config(cfg)
+    _compare(accept_inputs(cfg, par), par, "greedy")
+
+
+def test_greedy_ties_and_minus_inf():
+    N, V = 5, 9000
+    par = np.array([[-1, 0, 0, 1, 3]], dtype=np.int32)
+    logits = np.full((1, N + 1, V), -np.inf, dtype=np.float32)
+    logits[0, 0, [7000, 4100, 8999]] = 2.0         # tie -> 4100
+    logits[0, 1, [5, 4096]] = 1.0                   # tie -> 5
+    logits[0, 2, 8191] = 0.0
+    logits[0, 4, 1] = -1e30
+    tokens = np.array([[4100, 4096, 5, 8191, 0]], dtype=np.int32)
+    a = {"tokens": tokens, "logits": logits, "draft_probs": None, "uniforms": None}
+    _compare(a, par, "greedy")
+    path, alen, bonus = _gpu_accept(a, par, "greedy")
+    assert path[0, :alen[0]].tolist() == [0, 2] and bonus[0] == 0    # row 3 is all -inf -> id 0
+
+
+def test_greedy_first_child_chain_and_max_depth_cap():
+    cfg = CONFIGS["c2_vicuna7b"].with_(vocab=2000, hit_prob=1.0)
+    par = tree_for_config(cfg)
+    a = accept_inputs(cfg, par)
+    _compare(a, par, "greedy")
+    path, alen, bonus = _gpu_accept(a, par, "greedy")
+    # with a hit at every first child the walk follows first children down to a leaf
+    c, expect = -1, []
+    while True:
+        kids = np.nonzero(par[0] == c)[0]
+        if len(kids) == 0:
+            break
+        c = int(kids[0]); expect.append(c)
+    assert path[0, :alen[0]].tolist() == expect and len(expect) >= 2
+    path2, alen2, bonus2 = _gpu_accept(a, par, "greedy", max_depth=1)
+    assert alen2[0] == 1 and path2.shape == (1, 1) and path2[0, 0] == path[0, 0] and bonus2[0] == bonus[0]
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_sample_small_vocab(seed):
+    cfg = CONFIGS["c3_llama3_8b"].with_(vocab=5000, batch=3)
+    par = tree_for_config(cfg, seed=seed)
+    a = accept_inputs(cfg, par, seed=seed)
+    skipped = _compare(a, par, "sample")
+    assert skipped == 0
+
+
+def test_sample_q_close_to_p_walks_deep():
+    """Draft distributions near the target's: many accepts, residual passes in between."""
+    cfg = CONFIGS["c3_llama3_8b"].with_(vocab=3001, batch=4)
+    rng = np.random.default_rng(5)
+    par = tree_for_config(cfg, seed=5)
+    a = accept_inputs(cfg, par, seed=5)
+    lg = a["logits"]
+    q = a["draft_probs"]
+    for b in range(4):
+        for k in range(cfg.n_tree):
+            z = lg[b, par[b, k] + 1].astype(np.float64) + rng.standard_normal(cfg.vocab) * 0.7
+            e = np.exp(z - z.max())
+            qq = (e / e.sum()).astype(np.float32)
+            q[b, k] = qq
+            cdf = np.cumsum(qq, dtype=np.float64)
+            a["tokens"][b, k] = min(int(np.searchsorted(cdf, rng.random() * cdf[-1], side="right")), cfg.vocab - 1)
+    skipped = _compare(a, par, "sample")
+    _, alen, _ = _gpu_accept(a, par, "sample")
+    assert alen.max() >= 2 and skipped == 0
+
+
+def test_sample_temperature():
+    cfg = CONFIGS["c3_llama3_8b"].with_(vocab=4000, batch=2)
+    par = tree_for_config(cfg, seed=9)
+    a = accept_inputs(cfg, par, seed=9)
+    for temp in (0.5, 2.0):
+        _compare(a, par, "sample", temperature=temp)
+
+
+def test_c3_sample_full_vocab():
+    cfg = CONFIGS["c3_llama3_8b"]
+    par = tree_for_config(cfg)
+    a = accept_inputs(cfg, par)
+    assert _compare(a, par, "sample") == 0, "default seed must be admissible (margin > 1e-9)"
+
+
+def test_argument_errors():
+    dev = torch.device("cuda")
+    tok = torch.zeros(1, 4, dtype=torch.int32, device=dev)
+    lg = torch.zeros(1, 5, 100, dtype=torch.float32, device=dev)
+    with pytest.raises(jk.JakiroError) as e:
+        jk.accept_path(tok, tok, lg, jk.JK_SAMPLE)            # no draft_probs
+    assert e.value.status == 1
+    with pytest.raises(jk.JakiroError) as e:
+        jk.accept_path(tok, tok, lg, jk.JK_SAMPLE, 0.0, lg[:, :4].contiguous(), lg[:, :, 0].contiguous())
+    assert e.value.status == 1
+    with pytest.raises(jk.JakiroError) as e:
+        jk.accept_path(tok, tok, lg, jk.JK_GREEDY, workspace=torch.empty(16, dtype=torch.uint8, device=dev))
+    assert e.value.status == 4

@@ -1,0 +1,214 @@
+"""GPU parity: jk_tree_verify_attention (through the C ABI) against the fp64 oracle,
+element by element on the same seeded inputs.  Tolerances: 2e-2 max-abs for bf16
+inputs, 1e-5 for fp32 inputs; bf16 cases with O(1) outputs also bound the error
+relative to max|out| (bf16 output rounding 2^-9 plus bf16 softmax weights)."""
+import numpy as np
+import pytest
+import torch
+
+from workloads import CONFIGS, attention_inputs, coin_tree, round_to_bf16, tree_for_config, two_expert_tree
+
+pytestmark = pytest.mark.gpu
+
+from gpu_util import check_attention, gpu_attention  # noqa: E402
+
+BF16_TOL, F32_TOL = 2e-2, 1e-5
+
+
+def _cfg(base, **kw):
+    return CONFIGS[base].with_(**kw)
+
+
+def test_c1_tiny_fp32():
+    cfg = CONFIGS["c1_tiny"]
+    par = tree_for_config(cfg)
+    check_attention(attention_inputs(cfg), par, [cfg.prefix_len], "f32", F32_TOL)
+
+
+@pytest.mark.parametrize("L", [0, 1, 7, 128, 1000, 1025, 2500])
+def test_fp32_prefix_lengths(L):
+    cfg = _cfg("c1_tiny", prefix_len=L, n_q_heads=4, n_kv_heads=2)
+    par = tree_for_config(cfg, seed=L)
+    check_attention(attention_inputs(cfg, seed=L), par, [L], "f32", F32_TOL)
+
+
+def test_fp32_batched_ragged_and_wide_tree():
+    cfg = _cfg("c5_llama2_70b", batch=3, n_q_heads=4, n_kv_heads=2, head_dim=32, prefix_len=300, dtype="f32",
+               input_scale=1.0)
+    par = tree_for_config(cfg)
+    x = attention_inputs(cfg)
+    check_attention(x, par, [300, 17, 0], "f32", F32_TOL)
+
+
+# (name, Hq, Hkv, D, L, T-config, unscaled?)
+BF16_CASES = [
+    ("mha_small", 4, 4, 128, 100, "c2_vicuna7b", True),
+    ("mha_ragged", 2, 2, 128, 1021, "c2_vicuna7b", True),
+    ("gqa2", 4, 2, 128, 333, "c2_vicuna7b", True),
+    ("gqa4", 8, 2, 128, 515, "c3_llama3_8b", True),
+    ("gqa8_t100", 8, 1, 128, 700, "c5_llama2_70b", True),
+    ("d64_mha", 4, 4, 64, 257, "c2_vicuna7b", True),
+    ("d64_gqa4", 8, 2, 64, 96, "c2_vicuna7b", True),
+    ("scaled_inputs", 8, 2, 128, 515, "c3_llama3_8b", False),
+]
+
+
+@pytest.mark.parametrize("name,Hq,Hkv,D,L,base,unscaled", BF16_CASES, ids=[c[0] for c in BF16_CASES])
+def test_bf16_shapes(name, Hq, Hkv, D, L, base, unscaled):
+    cfg = _cfg(base, batch=2, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=D, prefix_len=L)
+    par = tree_for_config(cfg)
+    x = attention_inputs(cfg, scale_mult=(np.sqrt(128.0) if unscaled else 1.0))
+    check_attention(x, par, [L, max(0, L - 3)], "bf16", BF16_TOL, rel_tol=1.5e-2)
+
+
+@pytest.mark.parametrize("L", [0, 1, 7, 31, 32, 33])
+def test_bf16_tiny_prefixes_tree_dominates(L):
+    cfg = _cfg("c3_llama3_8b", prefix_len=L, n_q_heads=8, n_kv_heads=2)
+    par = tree_for_config(cfg, seed=10 + L)
+    x = attention_inputs(cfg, seed=10 + L, scale_mult=np.sqrt(128.0))
+    check_attention(x, par, [L], "bf16", BF16_TOL, rel_tol=1.5e-2)
+
+
+@pytest.mark.parametrize("T", [1, 2, 31, 32, 33, 64, 65, 127, 128])
+def test_bf16_tree_sizes(T):
+    rng = np.random.default_rng(T)
+    # random topological tree of T nodes, bushy near the root
+    par = np.array([-1] + [int(rng.integers(-1, i)) for i in range(1, T)], dtype=np.int32)[None]
+    cfg = _cfg("c3_llama3_8b", n_tree=T, prefix_len=70, n_q_heads=4, n_kv_heads=2)
+    x = attention_inputs(cfg, seed=T, scale_mult=np.sqrt(128.0))
+    check_attention(x, par, [70], "bf16", BF16_TOL, rel_tol=1.5e-2)
+
+
+def test_bf16_chain_and_star_trees():
+    cfg = _cfg("c3_llama3_8b", n_tree=40, prefix_len=50, n_q_heads=4, n_kv_heads=2, batch=2)
+    par = np.stack([np.arange(-1, 39), np.full(40, -1)]).astype(np.int32)
+    x = attention_inputs(cfg, scale_mult=np.sqrt(128.0))
+    check_attention(x, par, [50, 50], "bf16", BF16_TOL, rel_tol=1.5e-2)
+
+
+def test_bf16_peaked_softmax():
+    # Q x8: softmax nearly one-hot, exercises the running-max rescale
+    cfg = _cfg("c3_llama3_8b", prefix_len=600, n_q_heads=8, n_kv_heads=2)
+    par = tree_for_config(cfg)
+    x = attention_inputs(cfg, scale_mult=np.sqrt(128.0))
+    x["q"] = round_to_bf16(x["q"] * 8.0)
+    check_attention(x, par, [600], "bf16", BF16_TOL, rel_tol=2e-2)
+
+
+def test_bf16_custom_scale_and_strided_cache():
+    import paper_2502_06282_amd as jk
+    from oracle import tree_verify_attention as oracle_attention
+    cfg = _cfg("c3_llama3_8b", prefix_len=200, n_q_heads=8, n_kv_heads=2)
+    par = tree_for_config(cfg)
+    x = attention_inputs(cfg, scale_mult=np.sqrt(128.0))
+    ref = oracle_attention(**x, parent=par, prefix_len=[150], scale=0.05)
+    # cache stored head-major with spare capacity: [B, Hkv, Lcap, D] viewed as [B, Lcap, Hkv, D]
+    dev = torch.device("cuda")
+    kc = torch.zeros(1, 2, 256, 128, dtype=torch.bfloat16, device=dev)
+    vc = torch.zeros_like(kc)
+    kc[:, :, :200] = torch.from_numpy(x["k_cache"]).to(dev).to(torch.bfloat16).permute(0, 2, 1, 3)
+    vc[:, :, :200] = torch.from_numpy(x["v_cache"]).to(dev).to(torch.bfloat16).permute(0, 2, 1, 3)
+    f = lambda n: torch.from_numpy(x[n]).to(dev).to(torch.bfloat16)
+    out = jk.tree_verify_attention(f("q"), kc.permute(0, 2, 1, 3), vc.permute(0, 2, 1, 3), f("k_tree"), f("v_tree"),
+                                   torch.from_numpy(par).to(dev), torch.tensor([150], dtype=torch.int32, device=dev),
+                                   scale=0.05)
+    torch.cuda.synchronize()
+    err = np.abs(out.float().cpu().numpy() - ref).max()
+    assert err <= BF16_TOL and err / np.abs(ref).max() <= 1.5e-2
+
+
+def test_bf16_sibling_independence_bitwise():
+    """Nodes outside a query's ancestor set cannot change its output: their K rows
+    may hold anything (NaN), their V rows anything finite; results stay bit-identical."""
+    cfg = _cfg("c3_llama3_8b", prefix_len=90, n_q_heads=8, n_kv_heads=2)
+    par = tree_for_config(cfg)
+    x = attention_inputs(cfg, scale_mult=np.sqrt(128.0))
+    base = gpu_attention(x, par, [90], "bf16")
+    from oracle import ancestor_sets
+    anc = ancestor_sets(par[0])
+    T = cfg.n_tree
+    for i in [T - 1, T // 2, 3]:
+        y = {k: v.copy() for k, v in x.items()}
+        others = [j for j in range(T) if j not in anc[i]]
+        y["k_tree"][0, others] = np.nan
+        y["v_tree"][0, others] = 3.0e38
+        got = gpu_attention(y, par, [90], "bf16")
+        np.testing.assert_array_equal(got[0, i], base[0, i])
+    # beyond prefix_len the cache is never read
+    y = {k: v.copy() for k, v in x.items()}
+    y["k_cache"][0, 60:] = np.nan
+    y["v_cache"][0, 60:] = np.nan
+    a = gpu_attention(y, par, [60], "bf16")
+    z = {k: v.copy() for k, v in x.items()}
+    b = gpu_attention(z, par, [60], "bf16")
+    np.testing.assert_array_equal(a, b)
+
+
+def test_bf16_split_invariance(monkeypatch):
+    """The number of KV splits changes only fp32 rounding."""
+    cfg = _cfg("c3_llama3_8b", prefix_len=2000, n_q_heads=8, n_kv_heads=2)
+    par = tree_for_config(cfg)
+    x = attention_inputs(cfg, scale_mult=np.sqrt(128.0))
+    outs = []
+    for s in ("1", "3", "8", "31"):
+        monkeypatch.setenv("JK_ATTN_SPLITS", s)
+        outs.append(gpu_attention(x, par, [2000], "bf16"))
+    for o in outs[1:]:
+        assert np.abs(o - outs[0]).max() <= 2.0 ** -7 * np.abs(outs[0]).max()
+
+
+def test_c2_full_size_sampled_rows():
+    """Config 2 at full size in the benchmark's launch configuration; the oracle
+    checks a sample of (node, head) rows one by one."""
+    cfg = CONFIGS["c2_vicuna7b"]
+    par = tree_for_config(cfg)
+    x = attention_inputs(cfg)
+    got = gpu_attention(x, par, [cfg.prefix_len], "bf16")
+    from oracle import tree_verify_attention as oracle_attention
+    rng = np.random.default_rng(0)
+    for _ in range(12):
+        i, h = int(rng.integers(cfg.n_tree)), int(rng.integers(cfg.n_q_heads))
+        sub = {"q": x["q"][:, :, h:h + 1], "k_cache": x["k_cache"][:, :, h:h + 1], "v_cache": x["v_cache"][:, :, h:h + 1],
+               "k_tree": x["k_tree"][:, :, h:h + 1], "v_tree": x["v_tree"][:, :, h:h + 1]}
+        ref = oracle_attention(**sub, parent=par, prefix_len=[cfg.prefix_len])
+        assert np.abs(got[0, i, h] - ref[0, i, 0]).max() <= BF16_TOL
+        assert np.abs(got[0, i, h] - ref[0, i, 0]).max() <= 2e-2 * np.abs(ref[0, :, 0]).max() + 1e-6
+
+
+def test_c3_full_size_sampled_rows():
+    cfg = CONFIGS["c3_llama3_8b"]
+    par = tree_for_config(cfg)
+    x = attention_inputs(cfg, scale_mult=np.sqrt(128.0))
+    got = gpu_attention(x, par, [cfg.prefix_len], "bf16")
+    from oracle import tree_verify_attention as oracle_attention
+    rng = np.random.default_rng(1)
+    G = cfg.group
+    for _ in range(6):
+        kv = int(rng.integers(cfg.n_kv_heads))
+        hs = slice(kv * G, kv * G + G)
+        sub = {"q": x["q"][:, :, hs], "k_cache": x["k_cache"][:, :, kv:kv + 1], "v_cache": x["v_cache"][:, :, kv:kv + 1],
+               "k_tree": x["k_tree"][:, :, kv:kv + 1], "v_tree": x["v_tree"][:, :, kv:kv + 1]}
+        ref = oracle_attention(**sub, parent=par, prefix_len=[cfg.prefix_len])
+        err = np.abs(got[0, :, hs] - ref[0]).max()
+        assert err <= BF16_TOL and err <= 1.5e-2 * np.abs(ref).max()
+
+
+def test_argument_errors():
+    import paper_2502_06282_amd as jk
+    dev = torch.device("cuda")
+    q = torch.zeros(1, 4, 2, 128, dtype=torch.bfloat16, device=dev)
+    kc = torch.zeros(1, 8, 2, 128, dtype=torch.bfloat16, device=dev)
+    kt = torch.zeros(1, 4, 2, 128, dtype=torch.bfloat16, device=dev)
+    par = torch.tensor([[-1, 0, 0, 1]], dtype=torch.int32, device=dev)
+    pl = torch.tensor([8], dtype=torch.int32, device=dev)
+    with pytest.raises(jk.JakiroError) as e:
+        jk.tree_verify_attention(q, kc, kc, kt, kt, par, pl, scale=-1.0)
+    assert e.value.status in (1, 3)
+    ws = torch.empty(256, dtype=torch.uint8, device=dev)
+    with pytest.raises(jk.JakiroError) as e:
+        jk.tree_verify_attention(q, kc, kc, kt, kt, par, pl, workspace=ws[1:])
+    assert e.value.status == 4
+    q96 = torch.zeros(1, 4, 2, 96, dtype=torch.bfloat16, device=dev)
+    with pytest.raises(jk.JakiroError) as e:
+        jk.tree_verify_attention(q96, q96, q96, q96, q96, par, pl)
+    assert e.value.status == 3

@@ -1,0 +1,70 @@
+"""The C-ABI library loads and exports every symbol include/jakiro_verify.h declares;
+host-only entry points behave (no GPU needed, no compute calls)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2502_06282_amd as jk
+from paper_2502_06282_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(jk.library_path()):
+        from paper_2502_06282_amd import build
+        build.build()
+    return jk.lib()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "jakiro_verify.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(jk_[a-z_]+)\s*\(", header))
+    assert declared == set(binding.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_status_strings_and_version(lib):
+    assert jk.version() == "0.1"
+    seen = {lib.jk_status_string(i).decode() for i in range(6)}
+    assert len(seen) == 6 and lib.jk_status_string(99).decode() == "unknown status"
+
+
+def test_validate_tree(lib):
+    assert jk.validate_tree([-1, 0, 0, 1]) == 0
+    assert jk.validate_tree([-1, -1, -1]) == 0
+    assert jk.validate_tree([0]) == 2
+    assert jk.validate_tree([-1, 1]) == 2
+    assert jk.validate_tree([-2]) == 2
+    assert jk.validate_tree([-1] * 129) == 1
+    assert lib.jk_validate_tree(None, 3) == 1
+
+
+def test_workspace_queries_are_host_only(lib):
+    d = binding.AttnDesc(1, 60, 32, 8, 128, 0, 4096, 128, 0, 1024, 128, 0, 1024, 128, 0, 4096, 128, 0.0, 0)
+    n = lib.jk_tree_verify_attention_workspace(ctypes.byref(d), 4096)
+    assert n > 0 and n % 256 == 0
+    d.head_dim = 96
+    assert lib.jk_tree_verify_attention_workspace(ctypes.byref(d), 4096) == 0
+    d.head_dim = 128; d.n_tree = 129
+    assert lib.jk_tree_verify_attention_workspace(ctypes.byref(d), 4096) == 0
+    assert lib.jk_tree_verify_attention_workspace(None, 4096) == 0
+    g = lib.jk_accept_path_workspace(1, 60, 32000, 0)
+    s = lib.jk_accept_path_workspace(1, 60, 32000, 1)
+    assert 0 < g < s
+    assert lib.jk_accept_path_workspace(1, 0, 32000, 0) == 0
+    assert lib.jk_accept_path_workspace(1, 60, 32000, 7) == 0
+
+
+def test_null_arguments_are_rejected_before_any_launch(lib):
+    d = binding.AttnDesc(1, 4, 2, 2, 128, 0, 256, 128, 0, 256, 128, 0, 256, 128, 0, 256, 128, 0.0, 0)
+    st = lib.jk_tree_verify_attention(ctypes.byref(d), None, None, None, None, None, None, None, 0, None, None, 0,
+                                      None)
+    assert st == 1
+    st = lib.jk_accept_path(1, 4, 100, 4, None, None, None, 0, 1.0, None, None, None, None, None, None, 0, None)
+    assert st == 1
