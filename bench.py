@@ -1,0 +1,224 @@
+#!/usr/bin/env python3
+"""Benchmark of the tree-verification hot path on one MI355X.
+
+A "step" is one verification step of speculative decoding at the LLaMA3-8B
+shape (workload c3_llama3_8b): the tree-masked attention of all `--layers`
+transformer layers (32 distinct bf16 KV caches, 4096-token prefix, 60-node
+two-expert draft tree, 32 query / 8 KV heads, head_dim 128) followed by one
+acceptance walk over [61, 128256] fp32 logits (temperature-1 speculative
+sampling).  Inputs are synthetic, seeded, and resident in HBM before the timed
+region.  The KV ring (layers x 16.8 MB = 537 MB at 32 layers) is larger than
+the 256 MB Infinity Cache, so every attention call streams its KV from HBM.
+
+Prints one JSON line.  `value` is the attention's algorithmic bytes per second
+(KV prefix + tree K/V + Q + O, 18 006 016 B per call) over the time the step
+spends in attention calls; `ms_per_step` covers the whole step.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+# HBM bytes per attention launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by the
+# same counters' reading for a device copy of known size (see profiles/): {workload: bytes} or None.
+MEASURED_TRAFFIC = {"c3_llama3_8b": None}
+
+
+def attn_bytes(cfg) -> int:
+    es = 2 if cfg.dtype == "bf16" else 4
+    L, T, Hq, Hkv, D = cfg.prefix_len, cfg.n_tree, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    return cfg.batch * (2 * L * Hkv * D * es + 2 * T * Hkv * D * es + 2 * T * Hq * D * es)
+
+
+def cpu_baseline(cfg, par, x, acc):
+    """Oracle (as is, one thread) on a bounded sample: the attention of 2 of the 8 KV
+    heads of one layer, and one acceptance walk.  Reported in the metric's unit."""
+    import numpy as np
+    from oracle import accept_path as o_accept, tree_verify_attention as o_attn
+    try:
+        from threadpoolctl import threadpool_limits
+    except Exception:  # pragma: no cover
+        threadpool_limits = None
+    G = cfg.group
+    nkv = 2
+    sub = {"q": x["q"][:, :, : nkv * G], "k_cache": x["k_cache"][:, :, :nkv], "v_cache": x["v_cache"][:, :, :nkv],
+           "k_tree": x["k_tree"][:, :, :nkv], "v_tree": x["v_tree"][:, :, :nkv]}
+
+    def run():
+        t0 = time.perf_counter()
+        o_attn(**sub, parent=par, prefix_len=[cfg.prefix_len] * cfg.batch)
+        t1 = time.perf_counter()
+        o_accept(acc["tokens"][0], par[0], acc["logits"][0], cfg.mode,
+                 None if acc["draft_probs"] is None else acc["draft_probs"][0],
+                 None if acc["uniforms"] is None else acc["uniforms"][0])
+        t2 = time.perf_counter()
+        return t1 - t0, t2 - t1
+
+    if threadpool_limits is not None:
+        with threadpool_limits(limits=1):
+            t_attn, t_acc = run()
+    else:
+        t_attn, t_acc = run()
+    frac = nkv / cfg.n_kv_heads
+    return {
+        "value": attn_bytes(cfg) * frac / t_attn / 1e9,
+        "unit": "GB/s",
+        "cores": 1,
+        "kind": "oracle",
+        "sample": f"attention oracle on {nkv} of {cfg.n_kv_heads} KV heads of one layer ({t_attn:.2f} s) "
+                  f"+ one acceptance walk ({t_acc:.2f} s)",
+        "accept_nodes_per_s": cfg.n_tree / t_acc,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--layers", type=int, default=32)
+    ap.add_argument("--workload", default="c3_llama3_8b")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="issue every library call from Python instead of "
+                    "replaying the step's two HIP graphs")
+    ap.add_argument("--copy-calibration", type=int, default=0,
+                    help="also run this many 256 MiB device copies (reference kernel for --pmc runs)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (--gpus 1); there is no multi-GPU path to time")
+
+    import numpy as np
+    import torch
+
+    import paper_2502_06282_amd as jk
+    from workloads import CONFIGS, accept_inputs, attention_inputs, tree_for_config
+
+    jk.lib()  # fail loudly if the HIP library is missing
+    cfg = CONFIGS[args.workload]
+    dev = torch.device("cuda:0")
+    tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    par = tree_for_config(cfg)
+    parent = torch.from_numpy(par).to(dev)
+    plen = torch.full((cfg.batch,), cfg.prefix_len, dtype=torch.int32, device=dev)
+
+    layers = []
+    x0 = None
+    for l in range(args.layers):
+        x = attention_inputs(cfg, layer=l)
+        if l == 0:
+            x0 = x
+        layers.append({k: torch.from_numpy(v).to(dev).to(tdt) for k, v in x.items()})
+    acc = accept_inputs(cfg, par)
+    mode = jk.JK_GREEDY if cfg.mode == "greedy" else jk.JK_SAMPLE
+    tokens = torch.from_numpy(acc["tokens"]).to(dev)
+    logits = torch.from_numpy(acc["logits"]).to(dev)
+    draft = None if acc["draft_probs"] is None else torch.from_numpy(acc["draft_probs"]).to(dev)
+    unif = None if acc["uniforms"] is None else torch.from_numpy(acc["uniforms"]).to(dev)
+
+    out = torch.empty_like(layers[0]["q"])
+    ws_attn = torch.empty(jk.tree_verify_attention_workspace(layers[0]["q"], layers[0]["k_cache"],
+                                                             layers[0]["k_tree"], cfg.prefix_len),
+                          dtype=torch.uint8, device=dev)
+    ws_acc = torch.empty(jk.accept_path_workspace(cfg.batch, cfg.n_tree, cfg.vocab, mode), dtype=torch.uint8,
+                         device=dev)
+
+    o_path = torch.empty((cfg.batch, cfg.depth), dtype=torch.int32, device=dev)
+    o_len = torch.empty((cfg.batch,), dtype=torch.int32, device=dev)
+    o_bonus = torch.empty((cfg.batch,), dtype=torch.int32, device=dev)
+    attn_calls = [jk.prepare_tree_verify_attention(lyr["q"], lyr["k_cache"], lyr["v_cache"], lyr["k_tree"],
+                                                   lyr["v_tree"], parent, plen, out, ws_attn,
+                                                   max_prefix_len=cfg.prefix_len) for lyr in layers]
+    acc_call = jk.prepare_accept_path(tokens, parent, logits, mode, 1.0, draft, unif, o_path, o_len, o_bonus, ws_acc)
+    res = (o_path, o_len, o_bonus)
+
+    def attention_eager():
+        for c in attn_calls:
+            c.launch()
+
+    attention_pass, accept_pass = attention_eager, acc_call.launch
+    if not args.no_graph:
+        # one HIP graph per phase: the step's launches replay without per-call host work,
+        # as a serving loop would issue them
+        attention_eager(); acc_call.launch()
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        g_attn, g_acc = torch.cuda.CUDAGraph(), torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g_attn, stream=side):
+            attention_eager()
+        with torch.cuda.graph(g_acc, stream=side):
+            acc_call.launch()
+        attention_pass, accept_pass = g_attn.replay, g_acc.replay
+
+    for _ in range(args.warmup):
+        attention_pass()
+        accept_pass()
+    torch.cuda.synchronize()
+
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        ev[s][0].record()
+        attention_pass()
+        ev[s][1].record()
+        accept_pass()
+        ev[s][2].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    t_attn_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / args.steps
+    t_acc_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / args.steps
+    ms_per_step = wall * 1e3 / args.steps
+    per_call_us = t_attn_ms * 1e3 / args.layers
+    bytes_call = attn_bytes(cfg)
+    gbps = bytes_call / (per_call_us * 1e-6) / 1e9
+
+    for _ in range(args.copy_calibration):
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+    torch.cuda.synchronize()
+
+    line = {
+        "metric": "tree_verify_attention_hbm_GBps",
+        "value": round(gbps, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16" if cfg.dtype == "bf16" else "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: B{cfg.batch} Hq{cfg.n_q_heads} Hkv{cfg.n_kv_heads} D{cfg.head_dim} "
+                               f"prefix{cfg.prefix_len} tree{cfg.n_tree} vocab{cfg.vocab} {cfg.mode}",
+                   "layers": args.layers, "attention_calls_per_step": args.layers, "accept_calls_per_step": 1,
+                   "launch": "eager" if args.no_graph else "hip_graph"},
+        "percent_of_hbm_peak": round(100.0 * gbps / HBM_PEAK_GBPS, 2),
+        "verify_steps_per_s": round(1e3 / ms_per_step, 1),
+        "attention_us_per_call": round(per_call_us, 3),
+        "accept_us_per_call": round(t_acc_ms * 1e3, 2),
+        "accept_nodes_per_s": round(cfg.batch * cfg.n_tree / (t_acc_ms * 1e-3), 1),
+        "accept_len": [int(v) for v in res[1].cpu().tolist()],
+        "roofline": {"bound": "hbm", "achieved": round(gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(gbps / HBM_PEAK_GBPS, 4), "traffic": MEASURED_TRAFFIC.get(cfg.name),
+                     "kernel": "tva_bf16_kernel (+ tva_combine_kernel): time per jk_tree_verify_attention call",
+                     "algorithmic_bytes_per_launch": bytes_call},
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(cfg, par, x0, acc)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

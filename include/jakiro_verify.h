@@ -102,7 +102,8 @@ size_t jk_tree_verify_attention_workspace(const jk_attn_desc* desc, int32_t max_
  *   workspace    device, >= jk_tree_verify_attention_workspace(desc, max_prefix_len) bytes
  *
  * Supported: JK_BF16 with head_dim 64 or 128 (MFMA path), JK_F32 with
- * head_dim <= 256 and a multiple of 4 (plain-ALU path); 1 <= n_tree <= JK_MAX_TREE;
+ * head_dim <= 256 and a multiple of 4 and max_prefix_len + n_tree <= 65536
+ * (plain-ALU path); 1 <= n_tree <= JK_MAX_TREE;
  * n_q_heads a multiple of n_kv_heads.  Value rows of tree nodes that a query
  * cannot see must be finite (they are multiplied by an exact zero); their key
  * rows, and anything in the cache beyond prefix_len, are never used.

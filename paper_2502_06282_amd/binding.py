@@ -195,3 +195,46 @@ def accept_path(tree_tokens, parent, target_logits, mode: int = JK_GREEDY, tempe
     if st != 0:
         raise JakiroError(st, "jk_accept_path")
     return path, alen, bonus
+
+
+class PreparedCall:
+    """A C-ABI call with its arguments marshalled once.  `launch()` issues exactly that one
+    library call on the given (default: torch's current) stream: what a decoding loop, or a
+    HIP-graph capture of it, calls per step.  Holds references to every tensor it points to."""
+
+    def __init__(self, fn, where, args, stream_index, keep):
+        self._fn, self._where, self._args, self._si, self._keep = fn, where, list(args), stream_index, keep
+
+    def launch(self, stream=None) -> None:
+        self._args[self._si] = _stream_handle(stream)
+        st = self._fn(*self._args)
+        if st != 0:
+            raise JakiroError(st, self._where)
+
+
+def prepare_tree_verify_attention(q, k_cache, v_cache, k_tree, v_tree, parent, prefix_len, out, workspace,
+                                  max_prefix_len: Optional[int] = None, scale: float = 0.0) -> PreparedCall:
+    """Same arguments as tree_verify_attention with out and workspace given; nothing is launched."""
+    if k_cache is not None and k_cache.shape[1] == 0:
+        k_cache = v_cache = None
+    if max_prefix_len is None:
+        max_prefix_len = 0 if k_cache is None else int(k_cache.shape[1])
+    d = _make_desc(q, k_cache, k_tree, out, scale)
+    args = [ctypes.byref(d), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(k_tree), _ptr(v_tree), _ptr(parent),
+            _ptr(prefix_len), int(max_prefix_len), _ptr(out), _ptr(workspace),
+            workspace.numel() * workspace.element_size(), None]
+    return PreparedCall(lib().jk_tree_verify_attention, "jk_tree_verify_attention", args, 12,
+                        (d, q, k_cache, v_cache, k_tree, v_tree, parent, prefix_len, out, workspace))
+
+
+def prepare_accept_path(tree_tokens, parent, target_logits, mode, temperature, draft_probs, uniforms, out_path,
+                        out_accept_len, out_bonus_token, workspace) -> PreparedCall:
+    """Same arguments as accept_path with outputs and workspace given; nothing is launched."""
+    B, N = tree_tokens.shape
+    V = target_logits.shape[-1]
+    args = [B, N, V, int(out_path.shape[1]), _ptr(tree_tokens), _ptr(parent), _ptr(target_logits), int(mode),
+            float(temperature), _ptr(draft_probs), _ptr(uniforms), _ptr(out_path), _ptr(out_accept_len),
+            _ptr(out_bonus_token), _ptr(workspace), workspace.numel() * workspace.element_size(), None]
+    return PreparedCall(lib().jk_accept_path, "jk_accept_path", args, 16,
+                        (tree_tokens, parent, target_logits, draft_probs, uniforms, out_path, out_accept_len,
+                         out_bonus_token, workspace))

@@ -41,25 +41,40 @@ bool make_attn_plan(const jk_attn_desc& d, int max_prefix_len, AttnPlan* pl) {
   pl->m_rows = d.n_tree * G;
   const long long units = (long long)d.batch * d.n_kv_heads;
   if (d.dtype == JK_BF16) {
-    if (pl->m_rows <= 64) { pl->wm = 1; pl->wn = 4; }
-    else if (pl->m_rows <= 128) { pl->wm = 2; pl->wn = 2; }
-    else { pl->wm = 4; pl->wn = 1; }
-    pl->q_rows = 64 * pl->wm;
-    pl->n_qtiles = (pl->m_rows + pl->q_rows - 1) / pl->q_rows;
-    pl->m_pad = pl->n_qtiles * pl->q_rows;
-    // enough workgroups to occupy every CU once, each keeping at least one round of tiles
+    // Candidates: 4x1, 2x2 or 1x4 waves (query rows x key interleave) per workgroup.  Fewer
+    // rows per workgroup means more workgroups per KV head without more KV splits: the K/V
+    // stream is then re-read by the row tiles (from L2, they run side by side on one XCD)
+    // instead of fp32 partial outputs being written and read back once per split.
     const int n_tiles = (max_prefix_len + kTileKeys - 1) / kTileKeys + (d.n_tree + kTileKeys - 1) / kTileKeys;
-    const long long wgs = units * pl->n_qtiles;
-    long long s = (device_cu_count() + wgs - 1) / wgs;
-    const int max_by_tiles = n_tiles / (2 * pl->wn) > 0 ? n_tiles / (2 * pl->wn) : 1;
-    if (s > max_by_tiles) s = max_by_tiles;
-    if (s > kMaxSplits) s = kMaxSplits;
-    if (s < 1) s = 1;
-    if (const char* e = std::getenv("JK_ATTN_SPLITS")) {  // tuning override
-      const int v = std::atoi(e);
-      if (v >= 1 && v <= kMaxSplits) s = v;
+    const double kv_bytes = 2.0 * (max_prefix_len + d.n_tree) * d.head_dim * 2.0;
+    const int cus = device_cu_count();
+    int forced_wm = 0, forced_s = 0;
+    if (const char* e = std::getenv("JK_ATTN_WM")) forced_wm = std::atoi(e);       // tuning overrides
+    if (const char* e = std::getenv("JK_ATTN_SPLITS")) forced_s = std::atoi(e);
+    double best_cost = 0.0;
+    bool have = false;
+    for (int wm = 4; wm >= 1; wm >>= 1) {
+      if (forced_wm ? wm != forced_wm : (wm > 1 && pl->m_rows <= 32 * wm)) continue;  // mostly padding rows
+      const int wn = 4 / wm;
+      const int q_rows = 64 * wm;
+      const int n_qtiles = (pl->m_rows + q_rows - 1) / q_rows;
+      const long long wgs = units * n_qtiles;
+      long long s = (cus + wgs - 1) / wgs;
+      const int max_by_tiles = n_tiles / (2 * wn) > 0 ? n_tiles / (2 * wn) : 1;  // >= 2 rounds per split
+      if (s > max_by_tiles) s = max_by_tiles;
+      if (s > kMaxSplits) s = kMaxSplits;
+      if (forced_s >= 1 && forced_s <= kMaxSplits) s = forced_s;
+      const double partial = s > 1 ? 2.0 * s * pl->m_rows * d.head_dim * 4.0 : 0.0;
+      const double fill = (double)(wgs * s < cus ? wgs * s : cus) / cus;  // idle CUs cost time too
+      const double cost = (kv_bytes * (1.0 + 0.25 * (n_qtiles - 1)) + partial) / fill;
+      if (!have || cost < best_cost) {
+        have = true;
+        best_cost = cost;
+        pl->wm = wm; pl->wn = wn; pl->q_rows = q_rows; pl->n_qtiles = n_qtiles; pl->splits = (int)s;
+      }
     }
-    pl->splits = (int)s;
+    if (!have) return false;
+    pl->m_pad = pl->n_qtiles * pl->q_rows;
   } else {
     pl->wm = pl->wn = 1;
     pl->q_rows = 1;
@@ -67,7 +82,7 @@ bool make_attn_plan(const jk_attn_desc& d, int max_prefix_len, AttnPlan* pl) {
     pl->m_pad = pl->m_rows;
     const long long keys = (long long)max_prefix_len + d.n_tree;
     long long s = (keys + 1023) / 1024;  // each fp32 workgroup holds at most 1024 scores
-    if (s > 65535) return false;
+    if (s > kMaxSplits) return false;  // fp32 path: at most 64 * 1024 keys
     pl->splits = (int)s;
   }
   auto up = [](size_t x) { return (x + 255) / 256 * 256; };

@@ -19,39 +19,68 @@ struct CParams {
   long long o_sb, o_st, o_sh;
 };
 
-// LOG2: running maxima are in log2 units (bf16 path) rather than natural units (fp32 path).
+// One workgroup per query row.  Thread (sg, d4) sums every NG-th split for four output
+// columns, so the loads of a row's splits are all in flight together; the NG partial sums
+// meet in LDS.  LOG2: running maxima are in log2 units (bf16 path) rather than natural
+// units (fp32 path).
 template <bool LOG2, bool OUT_BF16>
 __global__ __launch_bounds__(256) void tva_combine_kernel(CParams p) {
-  const int d4n = p.D / 4;
-  const long long item = (long long)blockIdx.x * 256 + threadIdx.x;
-  const long long n_items = (long long)p.B * p.Hkv * p.M * d4n;
-  if (item >= n_items) return;
-  const int d4 = (int)(item % d4n);
-  long long r = item / d4n;
+  __shared__ float s_m[kMaxSplits], s_w[kMaxSplits];
+  __shared__ float4 s_acc[256];
+  __shared__ float s_l;
+  const int tid = threadIdx.x;
+  const int d4n = p.D / 4;        // 16..64 threads cover a row
+  const int ng = 256 / d4n;       // split groups
+  const int d4 = tid % d4n, sg = tid / d4n;
+  const long long r = blockIdx.x;  // (b * Hkv + kv) * M + m
   const int m = (int)(r % p.M);
-  const long long unit = r / p.M;  // b * Hkv + kv
+  const long long unit = r / p.M;
   const int kv = (int)(unit % p.Hkv);
   const int b = (int)(unit / p.Hkv);
-
   const long long row0 = unit * p.splits * p.m_pad + m;
-  float mx = -INFINITY;
-  for (int s = 0; s < p.splits; ++s) mx = fmaxf(mx, p.part_ml[row0 + (long long)s * p.m_pad].x);
-  const float mx_use = (mx == -INFINITY) ? 0.f : mx;
-  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-  float l = 0.f;
-  for (int s = 0; s < p.splits; ++s) {
-    const long long prow = row0 + (long long)s * p.m_pad;
-    const float2 ml = p.part_ml[prow];
-    if (ml.y == 0.f) continue;  // empty split (or one that saw no visible key)
-    const float w = LOG2 ? __builtin_amdgcn_exp2f(ml.x - mx_use) : expf(ml.x - mx_use);
-    const float4 o = *reinterpret_cast<const float4*>(p.part_o + prow * p.D + 4 * d4);
-    acc.x = fmaf(o.x, w, acc.x);
-    acc.y = fmaf(o.y, w, acc.y);
-    acc.z = fmaf(o.z, w, acc.z);
-    acc.w = fmaf(o.w, w, acc.w);
-    l = fmaf(ml.y, w, l);
+
+  float my_l = 0.f;
+  if (tid < p.splits) {
+    const float2 ml = p.part_ml[row0 + (long long)tid * p.m_pad];
+    s_m[tid] = ml.y > 0.f ? ml.x : -INFINITY;  // an empty split carries no weight
+    my_l = ml.y;
   }
-  const float inv = 1.f / l;
+  __syncthreads();
+  float mx = -INFINITY;
+  for (int s = 0; s < p.splits; ++s) mx = fmaxf(mx, s_m[s]);
+  const float mx_use = (mx == -INFINITY) ? 0.f : mx;
+  float lw = 0.f;
+  if (tid < p.splits) {
+    const float w = LOG2 ? __builtin_amdgcn_exp2f(s_m[tid] - mx_use) : expf(s_m[tid] - mx_use);
+    s_w[tid] = w;
+    lw = my_l * w;
+  }
+  if (tid < 64) {  // splits <= 64 all live in the first wave
+    for (int o = 32; o > 0; o >>= 1) lw += __shfl_xor(lw, o);
+    if (tid == 0) s_l = lw;
+  }
+  __syncthreads();
+
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (sg < ng) {
+    for (int s = sg; s < p.splits; s += ng) {
+      const float w = s_w[s];
+      if (w == 0.f) continue;
+      const float4 o = *reinterpret_cast<const float4*>(p.part_o + (row0 + (long long)s * p.m_pad) * p.D + 4 * d4);
+      acc.x = fmaf(o.x, w, acc.x);
+      acc.y = fmaf(o.y, w, acc.y);
+      acc.z = fmaf(o.z, w, acc.z);
+      acc.w = fmaf(o.w, w, acc.w);
+    }
+  }
+  s_acc[tid] = acc;
+  __syncthreads();
+  if (sg != 0) return;
+  for (int g2 = 1; g2 < ng; ++g2) {
+    const float4 o = s_acc[g2 * d4n + d4];
+    acc.x += o.x; acc.y += o.y; acc.z += o.z; acc.w += o.w;
+  }
+  const float inv = 1.f / s_l;
   const int node = m / p.G, hg = m % p.G;
   const long long off = b * p.o_sb + node * p.o_st + (long long)(kv * p.G + hg) * p.o_sh + 4 * d4;
   if (OUT_BF16) {
@@ -81,8 +110,7 @@ hipError_t launch_tva_combine(const AttnArgs& a, const AttnPlan& pl, hipStream_t
   cp.B = d.batch; cp.Hkv = d.n_kv_heads; cp.G = d.n_q_heads / d.n_kv_heads;
   cp.M = pl.m_rows; cp.m_pad = pl.m_pad; cp.D = d.head_dim; cp.splits = pl.splits;
   cp.o_sb = d.o_stride_b; cp.o_st = d.o_stride_t; cp.o_sh = d.o_stride_h;
-  const long long n_items = (long long)d.batch * d.n_kv_heads * pl.m_rows * (d.head_dim / 4);
-  const unsigned grid = (unsigned)((n_items + 255) / 256);
+  const unsigned grid = (unsigned)((long long)d.batch * d.n_kv_heads * pl.m_rows);
   if (d.dtype == JK_BF16)
     hipLaunchKernelGGL((tva_combine_kernel<true, true>), dim3(grid), dim3(256), 0, stream, cp);
   else
