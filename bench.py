@@ -130,6 +130,7 @@ def main():
                           dtype=torch.uint8, device=dev)
     ws_acc = torch.empty(jk.accept_path_workspace(cfg.batch, cfg.n_tree, cfg.vocab, mode), dtype=torch.uint8,
                          device=dev)
+    jk.workspace_init(ws_acc)
 
     o_path = torch.empty((cfg.batch, cfg.depth), dtype=torch.int32, device=dev)
     o_len = torch.empty((cfg.batch,), dtype=torch.int32, device=dev)

@@ -25,7 +25,10 @@
  *     pointers are ordinary host memory.  The caller owns every buffer.  The
  *     library allocates no device memory and keeps no state between calls;
  *     scratch comes from the caller's workspace (sizes from the *_workspace
- *     functions; 256-byte aligned).
+ *     functions; 256-byte aligned).  A workspace handed to jk_accept_path must
+ *     have been zero-filled once (jk_workspace_init, or any other means) before
+ *     its first use; after that it can be reused for any number of calls of any
+ *     shape it is large enough for.
  *   - Calls enqueue work on `hip_stream` (a hipStream_t, NULL = default
  *     stream) and return without synchronising.  Outputs are valid once the
  *     stream has reached that point.  Calls that share a workspace must be
@@ -144,7 +147,11 @@ size_t jk_accept_path_workspace(int32_t batch, int32_t n_tree, int32_t vocab, in
  *   out_bonus_token device int32 [batch]
  *   workspace     device, >= jk_accept_path_workspace(...) bytes
  *
- * Supported: 1 <= n_tree <= JK_MAX_TREE, vocab >= 1, max_depth >= 1.
+ * Supported: 1 <= n_tree <= JK_MAX_TREE, vocab >= 1, max_depth >= 1.  Token ids
+ * outside [0, vocab) are clamped into the range.  JK_SAMPLE runs several
+ * workgroups per tree that wait for each other; the wait is bounded, and if it
+ * ever expires (the device is too busy to keep them resident together)
+ * out_accept_len and out_bonus_token are set to -1 for that tree.
  * All sampling arithmetic (softmax, residuals, cumulative sums) is fp64, so a
  * decision can differ from exact arithmetic only when its two sides agree to
  * about 1e-13 relative. */
@@ -154,6 +161,13 @@ jk_status jk_accept_path(int32_t batch, int32_t n_tree, int32_t vocab, int32_t m
                          const float* draft_probs, const float* uniforms, int32_t* out_path,
                          int32_t* out_accept_len, int32_t* out_bonus_token, void* workspace,
                          size_t workspace_bytes, void* hip_stream);
+
+/* Zero-fills a workspace with a small kernel on `hip_stream` (safe under HIP-graph
+ * capture).  Needed once per workspace before its first jk_accept_path call: the
+ * cooperative sampling walk synchronises its workgroups through tagged words in
+ * the workspace and relies on tags only ever growing.  Returns JK_ERR_WORKSPACE for
+ * a null or misaligned pointer. */
+jk_status jk_workspace_init(void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Host-side check of a tree held in host memory: JK_OK, JK_ERR_BAD_TREE
  * (some parent[i] outside [-1, i-1]) or JK_ERR_INVALID_ARG (null, n outside

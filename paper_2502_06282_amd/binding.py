@@ -39,7 +39,7 @@ class AttnDesc(ctypes.Structure):
 _lib = None
 
 EXPORTS = ("jk_tree_verify_attention_workspace", "jk_tree_verify_attention", "jk_accept_path_workspace",
-           "jk_accept_path", "jk_validate_tree", "jk_status_string", "jk_version")
+           "jk_accept_path", "jk_workspace_init", "jk_validate_tree", "jk_status_string", "jk_version")
 
 
 def library_path() -> str:
@@ -65,6 +65,8 @@ def lib() -> ctypes.CDLL:
         l.jk_accept_path.restype = i32
         l.jk_accept_path.argtypes = [i32, i32, i32, i32, vp, vp, vp, i32, ctypes.c_float, vp, vp, vp, vp,
                                      vp, vp, sz, vp]
+        l.jk_workspace_init.restype = i32
+        l.jk_workspace_init.argtypes = [vp, sz, vp]
         l.jk_validate_tree.restype = i32
         l.jk_validate_tree.argtypes = [ctypes.POINTER(ctypes.c_int32), i32]
         l.jk_status_string.restype = ctypes.c_char_p
@@ -160,6 +162,14 @@ def accept_path_workspace(batch: int, n_tree: int, vocab: int, mode: int) -> int
     return int(lib().jk_accept_path_workspace(batch, n_tree, vocab, mode))
 
 
+def workspace_init(workspace, stream=None) -> None:
+    """jk_workspace_init: zero-fill a workspace tensor on `stream` (once, before its first accept_path)."""
+    st = lib().jk_workspace_init(_ptr(workspace), workspace.numel() * workspace.element_size(),
+                                 _stream_handle(stream))
+    if st != 0:
+        raise JakiroError(st, "jk_workspace_init")
+
+
 def accept_path(tree_tokens, parent, target_logits, mode: int = JK_GREEDY, temperature: float = 1.0,
                 draft_probs=None, uniforms=None, max_depth: Optional[int] = None, workspace=None,
                 stream=None) -> Tuple["torch.Tensor", "torch.Tensor", "torch.Tensor"]:
@@ -187,7 +197,7 @@ def accept_path(tree_tokens, parent, target_logits, mode: int = JK_GREEDY, tempe
     if need == 0:
         raise JakiroError(3, "jk_accept_path_workspace")
     if workspace is None:
-        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+        workspace = torch.zeros(need, dtype=torch.uint8, device=dev)  # must start zero-filled
     st = lib().jk_accept_path(B, N, V, int(max_depth), _ptr(tree_tokens), _ptr(parent), _ptr(target_logits),
                               int(mode), float(temperature), _ptr(draft_probs), _ptr(uniforms), _ptr(path),
                               _ptr(alen), _ptr(bonus), _ptr(workspace),

@@ -20,6 +20,8 @@
 //                       prefix sum over the final distribution.  All sampling
 //                       arithmetic is fp64: the inverse-CDF draw resolves steps
 //                       of ~1/vocab, which fp32 terms cannot do reproducibly
+#include <cstdlib>
+
 #include "jk_internal.h"
 
 namespace jk {
@@ -219,7 +221,7 @@ __global__ __launch_bounds__(kWalkThreads) void walk_sample_kernel(WalkParams p)
     for (int j = k; j < N; ++j)
       if (par_s[j] == c) { child = j; break; }
     if (child < 0) break;
-    const int x = tok[child];
+    const int x = min(max(tok[child], 0), V - 1);  // a token id outside the vocabulary must not fault
     const float* qk = p.draft + ((long long)b * N + child) * V;
     const double lhs = (double)uni[child] * (double)qk[x];
     const double rhs = prob(x);
@@ -298,7 +300,7 @@ __global__ __launch_bounds__(kWalkThreads) void walk_sample_kernel(WalkParams p)
 }
 
 struct WsLayout {
-  size_t pmax, pidx, psum, resid, total;
+  size_t coop, pmax, pidx, psum, resid, total;
 };
 WsLayout ws_layout(int batch, int n_tree, int vocab, int mode) {
   WsLayout w{};
@@ -306,6 +308,9 @@ WsLayout ws_layout(int batch, int n_tree, int vocab, int mode) {
   const size_t slots = rows * n_chunks(vocab);
   auto up = [](size_t x) { return (x + 255) / 256 * 256; };
   size_t off = 0;
+  // the exchange table of the cooperative walk comes first: its per-tree epoch words keep
+  // their place whatever the other sizes are, so a workspace needs zeroing only once
+  w.coop = off; off += (mode == JK_SAMPLE) ? up(accept_coop_bytes(batch)) : 0;
   w.pmax = off; off += up(slots * sizeof(float));
   w.pidx = off; off += up(slots * sizeof(int));
   w.psum = off; off += (mode == JK_SAMPLE) ? up(slots * sizeof(double)) : 0;
@@ -337,6 +342,12 @@ hipError_t launch_accept(const AcceptArgs& a, hipStream_t stream) {
     hipLaunchKernelGGL(walk_greedy_kernel, dim3(a.batch), dim3(128), 0, stream, a.n_tree, nch, a.max_depth,
                        a.tokens, a.parent, pmax, pidx, a.out_path, a.out_len, a.out_bonus);
     return hipGetLastError();
+  }
+  {
+    int W = 0, slice = 0;
+    const char* force = std::getenv("JK_ACCEPT_SINGLE");  // tuning/testing: force the one-workgroup walk
+    if (!(force && force[0] == '1') && accept_coop_plan(a.batch, a.vocab, device_cu_count(), &W, &slice))
+      return launch_accept_coop(a, ws + w.coop, W, slice, stream);
   }
   const double temp = (double)a.temperature;
   hipLaunchKernelGGL(row_reduce_kernel<true>, grid, dim3(256), 0, stream, a.logits, a.vocab, temp, pmax, pidx,

@@ -1,0 +1,337 @@
+// Speculative-sampling acceptance walk, cooperative version (gfx950).
+//
+// Same rule as the single-workgroup walk (Section 2.1 steps 2-3 of the paper:
+// accept with probability min(1, p/q), continue with norm(max(0, p - q)) after
+// a rejection; siblings tried left to right, Section 3.1.2), spread over W
+// workgroups per tree.  Workgroup w owns the vocabulary slice
+// [w*SL, (w+1)*SL) and keeps the current distribution of that slice in LDS as
+// fp64, so that a rejection only streams the rejected node's draft
+// distribution from HBM.  Logits rows are read lazily: only the rows of nodes
+// the walk actually reaches (at most depth+1 of the N+1 rows).
+//
+// Every workgroup follows the same control flow.  Scalars that depend on the
+// whole vocabulary (row maximum and normaliser, residual mass, cumulative sums
+// for the final draw) are exchanged through a small table in the workspace:
+// each workgroup publishes its partial under a tag that is unique to the call
+// and the exchange number, then reads the W partials once all tags have
+// appeared.  All workgroups reduce the same values in the same order, so they
+// take identical decisions.  Waiting is bounded: if a partner never shows up
+// (the W workgroups of a tree are not all resident) the walk gives up and
+// reports accept_len = -1 instead of hanging.
+#include "jk_internal.h"
+
+namespace jk {
+namespace {
+
+constexpr int kCoopThreads = 256;
+constexpr unsigned kSpinLimit = 1u << 22;  // polls before giving up (seconds)
+
+struct Slot {  // 32 bytes
+  unsigned long long tag;
+  double a, b;
+  unsigned long long pad;
+};
+
+struct CoopParams {
+  int n_tree, vocab, max_depth, W, slice;
+  double temp;
+  const int *tokens, *parent;
+  const float *logits, *draft, *uniforms;
+  unsigned long long* epoch;  // [batch] workspace words, each bumped once per call by its tree
+  Slot* slots;                // [batch][2][W]
+  int *out_path, *out_len, *out_bonus;
+};
+
+__device__ __forceinline__ double block_sum(double v, double* red) {
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return (red[0] + red[1]) + (red[2] + red[3]);
+}
+__device__ __forceinline__ double block_max(double v, double* red) {
+  for (int o = 32; o > 0; o >>= 1) v = fmax(v, __shfl_xor(v, o));
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return fmax(fmax(red[0], red[1]), fmax(red[2], red[3]));
+}
+
+__global__ __launch_bounds__(kCoopThreads) void walk_sample_coop_kernel(CoopParams p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  double* cur = reinterpret_cast<double*>(smem);   // [slice] current distribution of my slice
+  double* nxt = cur + p.slice;                     // [slice] candidate residual
+  __shared__ double red[4];
+  __shared__ double xa[64], xb[64];                // the W partials of an exchange
+  __shared__ int par_s[JK_MAX_TREE];
+  __shared__ int s_fail, s_found;
+  __shared__ double rej_s[JK_MAX_TREE];            // residual masses of the rejected siblings at this node
+  __shared__ int rej_k[JK_MAX_TREE];
+
+  const int tid = threadIdx.x;
+  const int W = p.W;
+  const int b = blockIdx.x / W, w = blockIdx.x % W;
+  const int N = p.n_tree, V = p.vocab, rows = N + 1;
+  const int v_lo = min(V, w * p.slice), v_hi = min(V, v_lo + p.slice);
+  const int n_mine = v_hi - v_lo;
+
+  if (tid < N) {
+    const int pa = p.parent[(long long)b * N + tid];
+    par_s[tid] = (pa >= -1 && pa < tid) ? pa : -1;
+  }
+  if (tid == 0) s_fail = 0;
+  const unsigned long long epoch = __hip_atomic_load(p.epoch + b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __syncthreads();
+
+  const int* tok = p.tokens + (long long)b * N;
+  const float* uni = p.uniforms + (long long)b * rows;
+  Slot* slots = p.slots + (long long)b * 2 * 64;
+  unsigned n_exch = 0;
+
+  // all-gather of one (a, b) pair per workgroup; results in xa[0..W), xb[0..W)
+  auto exchange = [&](double a, double bb) {
+    ++n_exch;
+    const unsigned long long tag = ((epoch + 1) << 20) | n_exch;
+    Slot* tab = slots + (n_exch & 1) * W;
+    if (tid == 0) {
+      tab[w].a = a;
+      tab[w].b = bb;
+      __threadfence();
+      __hip_atomic_store(&tab[w].tag, tag, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    if (tid < W) {
+      unsigned spins = 0;
+      while (__hip_atomic_load(&tab[tid].tag, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) != tag) {
+        if (++spins > kSpinLimit || s_fail) { s_fail = 1; break; }
+        __builtin_amdgcn_s_sleep(2);
+      }
+      __threadfence();
+      xa[tid] = __hip_atomic_load(&tab[tid].a, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      xb[tid] = __hip_atomic_load(&tab[tid].b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+  };
+
+  double row_m = 0.0, row_z = 1.0;  // max of row/T and sum of exp(row/T - max) of the current row
+  const float* row = nullptr;
+
+  // softmax of logits row r over my slice into cur[]; (row_m, row_z) for everybody
+  auto load_row = [&](int r) {
+    row = p.logits + ((long long)b * rows + r) * V;
+    double lm = -INFINITY;
+    for (int i = tid; i < n_mine; i += kCoopThreads) {
+      const double z = (double)row[v_lo + i] / p.temp;
+      cur[i] = z;
+      lm = fmax(lm, z);
+    }
+    const double m_w = block_max(lm, red);
+    const double m_use = (m_w == -INFINITY) ? 0.0 : m_w;
+    double ls = 0.0;
+    for (int i = tid; i < n_mine; i += kCoopThreads) {
+      const double e = exp(cur[i] - m_use);
+      cur[i] = e;
+      ls += e;
+    }
+    const double z_w = block_sum(ls, red);
+    exchange(m_w, z_w);
+    double M = -INFINITY;
+    for (int i = 0; i < W; ++i) M = fmax(M, xa[i]);
+    const double M_use = (M == -INFINITY) ? 0.0 : M;
+    double Z = 0.0;
+    for (int i = 0; i < W; ++i)
+      if (xa[i] != -INFINITY) Z += xb[i] * exp(xa[i] - M_use);
+    row_m = M_use;
+    row_z = Z;
+    const double sc = exp(m_use - M_use) / Z;
+    for (int i = tid; i < n_mine; i += kCoopThreads) cur[i] *= sc;
+    __syncthreads();
+  };
+
+  int c = -1, len = 0, k = 0, n_rej = 0;
+  load_row(0);
+  while (!s_fail) {
+    int child = -1;
+    for (int j = k; j < N; ++j)
+      if (par_s[j] == c) { child = j; break; }
+    if (child < 0) break;
+    const int x = min(max(tok[child], 0), V - 1);  // a token id outside the vocabulary must not fault
+    const float* qk = p.draft + ((long long)b * N + child) * V;
+    // probability of token x under the current distribution: the same chain of operations in
+    // every workgroup (global data only), so that all take the same decision
+    double px = exp((double)row[x] / p.temp - row_m) / row_z;
+    for (int i = 0; i < n_rej; ++i) {
+      const float* qi = p.draft + ((long long)b * N + rej_k[i]) * V;
+      px = fmax(0.0, px - (double)qi[x]) / rej_s[i];
+    }
+    const double lhs = (double)uni[child] * (double)qk[x];
+    if (lhs < px) {
+      if (len < p.max_depth && tid == 0 && w == 0) p.out_path[(long long)b * p.max_depth + len] = child;
+      ++len;
+      c = child;
+      k = child + 1;
+      n_rej = 0;
+      load_row(c + 1);
+      continue;
+    }
+    // rejected: candidate residual of my slice and its mass
+    double part = 0.0;
+    for (int i = tid; i < n_mine; i += kCoopThreads) {
+      const double r = fmax(0.0, cur[i] - (double)qk[v_lo + i]);
+      nxt[i] = r;
+      part += r;
+    }
+    const double s_w = block_sum(part, red);
+    exchange(s_w, 0.0);
+    double s = 0.0;
+    for (int i = 0; i < W; ++i) s += xa[i];
+    if (s > 0.0) {
+      for (int i = tid; i < n_mine; i += kCoopThreads) cur[i] = nxt[i] / s;
+      if (tid == 0) { rej_k[n_rej] = child; rej_s[n_rej] = s; }
+      ++n_rej;
+      __syncthreads();
+    }
+    k = child + 1;
+  }
+
+  // ---- final draw: smallest v whose cumulative probability exceeds u * total
+  if (!s_fail) {
+    double part = 0.0;
+    int last_pos = -1;
+    // contiguous segments per thread so that the in-slice order is the vocabulary order
+    const int seg = (n_mine + kCoopThreads - 1) / kCoopThreads;
+    const int i0 = min(n_mine, tid * seg), i1 = min(n_mine, i0 + seg);
+    for (int i = i0; i < i1; ++i) {
+      part += cur[i];
+      if (cur[i] > 0.0) last_pos = v_lo + i;
+    }
+    // scan of the 256 segment sums: wave scan, then wave offsets.  A thread's interval is
+    // [off + excl, off + incl) with excl taken from its left neighbour's incl, so that the
+    // intervals of threads, waves and workgroups tile [0, total) exactly, rounding included.
+    double incl = part;
+    for (int o = 1; o < 64; o <<= 1) {
+      const double t = __shfl_up(incl, o);
+      if ((tid & 63) >= o) incl += t;
+    }
+    double excl = __shfl_up(incl, 1);
+    if ((tid & 63) == 0) excl = 0.0;
+    __syncthreads();
+    if ((tid & 63) == 63) red[tid >> 6] = incl;
+    int lp = last_pos;
+    for (int o = 32; o > 0; o >>= 1) lp = max(lp, __shfl_xor(lp, o));
+    __shared__ int s_lp[4];
+    if ((tid & 63) == 0) s_lp[tid >> 6] = lp;
+    __syncthreads();
+    double woff = 0.0;
+    for (int i = 0; i < (tid >> 6); ++i) woff += red[i];
+    const double t_w = ((red[0] + red[1]) + red[2]) + red[3];
+    const int lp_w = max(max(s_lp[0], s_lp[1]), max(s_lp[2], s_lp[3]));
+    exchange(t_w, (double)lp_w);
+    if (!s_fail) {
+      double before = 0.0, total = 0.0;
+      int last_any = -1;
+      for (int i = 0; i < W; ++i) {
+        if (i < w) before += xa[i];
+        total += xa[i];
+        last_any = max(last_any, (int)xb[i]);
+      }
+      const double target = (double)uni[N] * total;
+      if (tid == 0) s_found = -1;
+      __syncthreads();
+      // is the crossing inside my segment?
+      const double lo = before + (woff + excl), hi = before + (woff + incl);
+      if (i1 > i0 && lo <= target && hi > target) {
+        double run = lo;
+        int found = -1;
+        for (int i = i0; i < i1; ++i) {
+          run += cur[i];
+          if (run > target) { found = v_lo + i; break; }
+        }
+        if (found < 0) found = v_lo + i1 - 1;  // rounding between the scanned and the re-added sums
+        atomicMax(&s_found, found);
+      }
+      __syncthreads();
+      const bool mine = s_found >= 0;
+      // nobody crosses (u * total not below the last cumulative value): largest v with p > 0.
+      // Decided identically everywhere: workgroup w' owns the crossing iff
+      // before(w') <= target < before(w') + t(w'); sums of the same numbers in the same order.
+      bool any = false;
+      {
+        double acc = 0.0;
+        for (int i = 0; i < W; ++i) {
+          if (acc <= target && acc + xa[i] > target) any = true;
+          acc += xa[i];
+        }
+      }
+      if (tid == 0) {
+        const int capped = len < p.max_depth ? len : p.max_depth;
+        if (mine || (!any && w == 0)) {
+          p.out_bonus[b] = mine ? s_found : (last_any < 0 ? 0 : last_any);
+        }
+        if (w == 0) {
+          for (int i = capped; i < p.max_depth; ++i) p.out_path[(long long)b * p.max_depth + i] = -1;
+          p.out_len[b] = capped;
+        }
+      }
+    }
+  }
+  if (s_fail && tid == 0 && w == 0) {
+    p.out_len[b] = -1;
+    p.out_bonus[b] = -1;
+  }
+  // every workgroup of this tree read the epoch before its first exchange, and nobody gets
+  // here before having exchanged with all of them: safe to advance it for the next call
+  if (tid == 0 && w == 0)
+    __hip_atomic_store(p.epoch + b, epoch + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+}  // namespace
+
+static size_t coop_header_bytes(int batch) { return ((size_t)batch * 8 + 255) / 256 * 256; }
+
+size_t accept_coop_bytes(int batch) { return coop_header_bytes(batch) + (size_t)batch * 2 * 64 * sizeof(Slot); }
+
+bool accept_coop_plan(int batch, int vocab, int cus, int* W, int* slice) {
+  int w = (2 * cus) / batch;
+  if (w > 64) w = 64;
+  if (w < 1) return false;
+  const int sl = (vocab + w - 1) / w;
+  if (sl > 4096) return false;  // 2 x 4096 doubles of LDS per workgroup
+  *W = w;
+  *slice = sl;
+  return true;
+}
+
+hipError_t launch_accept_coop(const AcceptArgs& a, void* coop_ws, int W, int slice, hipStream_t stream) {
+  CoopParams cp;
+  cp.n_tree = a.n_tree; cp.vocab = a.vocab; cp.max_depth = a.max_depth; cp.W = W; cp.slice = slice;
+  cp.temp = (double)a.temperature;
+  cp.tokens = a.tokens; cp.parent = a.parent;
+  cp.logits = a.logits; cp.draft = a.draft_probs; cp.uniforms = a.uniforms;
+  cp.epoch = static_cast<unsigned long long*>(coop_ws);
+  cp.slots = reinterpret_cast<Slot*>(static_cast<char*>(coop_ws) + coop_header_bytes(a.batch));
+  cp.out_path = a.out_path; cp.out_len = a.out_len; cp.out_bonus = a.out_bonus;
+  const size_t lds = (size_t)2 * slice * sizeof(double);
+  static bool lds_limit_raised = false;
+  if (!lds_limit_raised) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(walk_sample_coop_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 2 * 4096 * 8);
+    if (e != hipSuccess) return e;
+    lds_limit_raised = true;
+  }
+  hipLaunchKernelGGL(walk_sample_coop_kernel, dim3(a.batch * W), dim3(kCoopThreads), lds, stream, cp);
+  return hipGetLastError();
+}
+
+// zero fill as a kernel (safe inside HIP-graph capture, unlike a memset node)
+__global__ void zero_fill_kernel(unsigned long long* p, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0ull;
+}
+hipError_t launch_zero_fill(void* p, size_t bytes, hipStream_t stream) {
+  const size_t n = bytes / 8;
+  if (n == 0) return hipSuccess;
+  const unsigned grid = (unsigned)((n + 255) / 256 < 1024 ? (n + 255) / 256 : 1024);
+  hipLaunchKernelGGL(zero_fill_kernel, dim3(grid), dim3(256), 0, stream, static_cast<unsigned long long*>(p), n);
+  return hipGetLastError();
+}
+
+}  // namespace jk

@@ -8,7 +8,6 @@
 
 namespace jk {
 
-namespace {
 int device_cu_count() {
   static int cus = 0;  // same value whoever writes it first
   if (cus == 0) {
@@ -22,6 +21,7 @@ int device_cu_count() {
   return cus;
 }
 
+namespace {
 bool desc_ok(const jk_attn_desc& d) {
   if (d.batch < 1 || d.n_tree < 1 || d.n_tree > JK_MAX_TREE) return false;
   if (d.n_q_heads < 1 || d.n_kv_heads < 1 || d.n_q_heads % d.n_kv_heads) return false;
@@ -41,31 +41,35 @@ bool make_attn_plan(const jk_attn_desc& d, int max_prefix_len, AttnPlan* pl) {
   pl->m_rows = d.n_tree * G;
   const long long units = (long long)d.batch * d.n_kv_heads;
   if (d.dtype == JK_BF16) {
-    // Candidates: 4x1, 2x2 or 1x4 waves (query rows x key interleave) per workgroup.  Fewer
-    // rows per workgroup means more workgroups per KV head without more KV splits: the K/V
-    // stream is then re-read by the row tiles (from L2, they run side by side on one XCD)
-    // instead of fp32 partial outputs being written and read back once per split.
+    // Candidates: 4x1 or 2x2 waves (32-row blocks x key interleave) per workgroup; two
+    // workgroups fit a CU.  Fewer rows per workgroup means more workgroups per KV head without
+    // more KV splits: the K/V stream is then re-read by the row tiles (from L2, they run side
+    // by side on one XCD) instead of fp32 partial outputs being written and read back once
+    // per split.
     const int n_tiles = (max_prefix_len + kTileKeys - 1) / kTileKeys + (d.n_tree + kTileKeys - 1) / kTileKeys;
     const double kv_bytes = 2.0 * (max_prefix_len + d.n_tree) * d.head_dim * 2.0;
-    const int cus = device_cu_count();
+    const int slots = 2 * device_cu_count();  // resident workgroups
     int forced_wm = 0, forced_s = 0;
     if (const char* e = std::getenv("JK_ATTN_WM")) forced_wm = std::atoi(e);       // tuning overrides
     if (const char* e = std::getenv("JK_ATTN_SPLITS")) forced_s = std::atoi(e);
+    if (forced_wm != 4 && forced_wm != 2) forced_wm = 0;
     double best_cost = 0.0;
     bool have = false;
-    for (int wm = 4; wm >= 1; wm >>= 1) {
-      if (forced_wm ? wm != forced_wm : (wm > 1 && pl->m_rows <= 32 * wm)) continue;  // mostly padding rows
+    for (int wm = 4; wm >= 2; wm >>= 1) {
+      if (forced_wm ? wm != forced_wm : (wm > 2 && pl->m_rows <= 16 * wm)) continue;  // mostly padding rows
       const int wn = 4 / wm;
-      const int q_rows = 64 * wm;
+      const int q_rows = 32 * wm;
       const int n_qtiles = (pl->m_rows + q_rows - 1) / q_rows;
       const long long wgs = units * n_qtiles;
-      long long s = (cus + wgs - 1) / wgs;
+      long long s = (slots + wgs - 1) / wgs;
       const int max_by_tiles = n_tiles / (2 * wn) > 0 ? n_tiles / (2 * wn) : 1;  // >= 2 rounds per split
       if (s > max_by_tiles) s = max_by_tiles;
       if (s > kMaxSplits) s = kMaxSplits;
       if (forced_s >= 1 && forced_s <= kMaxSplits) s = forced_s;
-      const double partial = s > 1 ? 2.0 * s * pl->m_rows * d.head_dim * 4.0 : 0.0;
-      const double fill = (double)(wgs * s < cus ? wgs * s : cus) / cus;  // idle CUs cost time too
+      // partial outputs are written, flushed at the kernel boundary and read back: weigh them double
+      const double partial = s > 1 ? 4.0 * s * pl->m_rows * d.head_dim * 4.0 : 0.0;
+      // one workgroup per CU already reaches most of the throughput; the second hides latencies
+      const double fill = 0.5 + 0.5 * (double)(wgs * s < slots ? wgs * s : slots) / slots;
       const double cost = (kv_bytes * (1.0 + 0.25 * (n_qtiles - 1)) + partial) / fill;
       if (!have || cost < best_cost) {
         have = true;
@@ -190,6 +194,13 @@ jk_status jk_accept_path(int32_t batch, int32_t n_tree, int32_t vocab, int32_t m
   a.out_path = out_path; a.out_len = out_accept_len; a.out_bonus = out_bonus_token;
   a.workspace = workspace;
   return launch_accept(a, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? JK_OK : JK_ERR_HIP;
+}
+
+jk_status jk_workspace_init(void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256) return JK_ERR_WORKSPACE;
+  return launch_zero_fill(workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream)) == hipSuccess
+             ? JK_OK
+             : JK_ERR_HIP;
 }
 
 jk_status jk_validate_tree(const int32_t* parent_host, int32_t n_tree) {

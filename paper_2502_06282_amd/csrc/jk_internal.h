@@ -16,9 +16,9 @@ constexpr int kMaxSplits = 64;     // upper bound on KV splits per (sequence, KV
 // descriptor and the prefix bound only, so that the workspace query and the
 // launch always agree.
 struct AttnPlan {
-  int wm;          // waves along the query-row axis (64 rows each)
+  int wm;          // waves along the query-row axis (32 rows each)
   int wn;          // waves along the key axis (each takes every wn-th tile)
-  int q_rows;      // query rows per workgroup = 64 * wm
+  int q_rows;      // query rows per workgroup = 32 * wm
   int n_qtiles;    // workgroups along the query-row axis
   int m_rows;      // T * G query rows per KV head
   int m_pad;       // n_qtiles * q_rows
@@ -54,5 +54,12 @@ struct AcceptArgs {
 };
 size_t accept_workspace_bytes(int batch, int n_tree, int vocab, int mode);
 hipError_t launch_accept(const AcceptArgs& a, hipStream_t stream);
+int device_cu_count();
+
+// cooperative sampling walk (several workgroups per tree)
+size_t accept_coop_bytes(int batch);
+bool accept_coop_plan(int batch, int vocab, int cus, int* W, int* slice);
+hipError_t launch_accept_coop(const AcceptArgs& a, void* coop_ws, int W, int slice, hipStream_t stream);
+hipError_t launch_zero_fill(void* p, size_t bytes, hipStream_t stream);
 
 }  // namespace jk

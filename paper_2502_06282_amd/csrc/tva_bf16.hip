@@ -8,10 +8,11 @@
 // Mapping.  The G query heads that share one KV head and the T tree nodes are
 // packed into one matrix of M = T*G query rows (row m = node m/G, head m%G), so
 // a KV head's K/V stream is read once for all of them.  One workgroup (4
-// waves) owns 64*WM query rows of one (sequence, KV head) and one split of the
-// key range; the key range (prefix tiles, then tree tiles, 32 keys each) is
+// waves; two workgroups share a CU, so that one's loads, prologue and epilogue
+// overlap the other's arithmetic) owns 32*WM query rows of one (sequence, KV head) and one split of
+// the key range; the key range (prefix tiles, then tree tiles, 32 keys each) is
 // cut into `splits` contiguous pieces.  Waves are arranged WM x WN: wave
-// (wm, wn) holds query rows [64*wm, 64*wm+64) and processes every WN-th tile.
+// (wm, wn) holds query rows [32*wm, 32*wm+32) and processes every WN-th tile.
 //
 // Per tile and wave, with everything transposed so that a lane owns one query
 // row:   S^T = K . Q^T   (v_mfma_f32_32x32x16_bf16, A = K rows from LDS,
@@ -22,7 +23,7 @@
 // ancestor set per node, built in LDS by the workgroups that own tree tiles.
 //
 // K/V travel HBM -> LDS directly (global_load_lds_dwordx4: 16 bytes per lane,
-// 16 lanes per 256-byte row) into a ring of 8 tiles, several rounds in flight;
+// 16 lanes per 256-byte row) into a ring of 4 tiles, rounds ahead in flight;
 // each lane fetches the 16-byte chunk that the XOR swizzle maps to its LDS
 // slot, so that both the 128-bit K reads and the transpose V reads are free of
 // bank conflicts.
@@ -39,6 +40,11 @@ typedef short shortx8 __attribute__((ext_vector_type(8)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));  // native vector: plain loads/stores, no struct copies
 
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
+
+constexpr int kThreads = 256;
+constexpr int kWaves = 4;       // one wave per SIMD; two workgroups share a CU
+constexpr int kWaveRows = 32;   // query rows per wave
+constexpr int kRingTiles = 4;   // K+V tiles resident in LDS (64 KB at head_dim 128)
 
 struct KParams {
   const uint16_t *q, *kc, *vc, *kt, *vt;
@@ -68,18 +74,13 @@ struct Geo {
   static constexpr int ROW_BYTES = D * 2;
   static constexpr int TILE_BYTES = kTileKeys * ROW_BYTES;
   static constexpr int CPR = D / 8;               // 16-byte chunks per row
-  static constexpr int NCH = kTileKeys * CPR / 256;  // chunks per thread per tile and tensor
   static constexpr int DK = D / 16;               // k-steps of Q.K^T
   static constexpr int DB = D / 32;               // 32-wide d blocks of the output
   static constexpr int O_LD = D + 4;              // padded row of the epilogue buffer (floats)
+  static constexpr int NB = TILE_BYTES / 1024;    // 1 KB transfers per tile and tensor
+  static constexpr int DMA_PER_TILE = 2 * NB / kWaves;  // transfers each wave issues per tile
   __device__ static __forceinline__ int kswz(int row) { return (row / (16 / CPR)) % CPR; }
   __device__ static __forceinline__ int vswz(int row) { return (row / (4 / DB)) % DB; }
-  // byte offset inside a K tile of logical 16-byte chunk c of row r
-  __device__ static __forceinline__ int koff(int r, int c) { return r * ROW_BYTES + ((c ^ kswz(r)) << 4); }
-  // V tile: 64-byte blocks are swizzled, the 4 chunks inside a block keep their order
-  __device__ static __forceinline__ int voff(int r, int c) {
-    return r * ROW_BYTES + ((((c >> 2) ^ vswz(r)) << 2 | (c & 3)) << 4);
-  }
 };
 
 // 16 bytes per lane straight from global memory into LDS (global_load_lds_dwordx4): lane l
@@ -93,8 +94,8 @@ __device__ __forceinline__ void dma16(const void* gptr, unsigned lds_base) {
                : "memory", "m0");
 }
 
-// Wait until at most n of this wave's transfers are still in flight (they complete in
-// issue order).  The count must be an immediate, hence the switch.
+// Wait until at most `rounds_behind` rounds of this wave's transfers are still in flight
+// (they complete in issue order).  The count must be an immediate, hence the switch.
 template <int STEP>
 __device__ __forceinline__ void wait_dma(int rounds_behind) {
   // s_waitcnt immediate on gfx9: vmcnt in bits [3:0] and [15:14]; expcnt/lgkmcnt left at their maxima
@@ -111,7 +112,7 @@ __device__ __forceinline__ void wait_dma(int rounds_behind) {
 #undef JK_VM
 }
 
-// Everything a thread needs to fetch its chunks of a tile.
+// Everything a wave needs to fetch its chunks of a tile.
 struct TileSrc {
   const uint16_t *kc, *vc, *kt, *vt;  // bases of this (sequence, KV head)
   long long kc_sl, kt_st;             // row strides (elements)
@@ -121,33 +122,37 @@ struct TileSrc {
 // Where a lane's 16-byte chunks sit inside a tile.  A wave-level transfer fills 1 KB =
 // 64/CPR consecutive tile rows; lane l writes physical chunk l%CPR of row blk*(64/CPR) +
 // l/CPR and fetches the logical chunk that the swizzle maps there, so the tile arrives
-// already swizzled.
+// already swizzled.  The 2*NB transfers of a tile (NB for K, then NB for V) are dealt
+// to the 8 waves in order.
 template <int D>
 struct LaneChunks {
-  static constexpr int NIK = Geo<D>::TILE_BYTES / 1024 / 4;  // transfers per wave, tile and tensor
-  int row[NIK];         // tile row
-  int kcol[NIK];        // element offset of the K chunk inside the row
-  int vcol[NIK];        // element offset of the V chunk inside the row
-  long long koff[NIK];  // row * cache row stride + kcol: offset inside a full prefix tile
-  long long voff[NIK];
-  unsigned lds[NIK];    // byte offset of the 1 KB block inside a tile
+  static constexpr int N = Geo<D>::DMA_PER_TILE;
+  int row[N];              // tile row
+  int col[N];              // element offset of the chunk inside the row
+  const uint16_t* full[N]; // address of the chunk inside prefix tile 0 (K or V cache)
+  const uint16_t* cache[N];  // K or V cache base of this (sequence, KV head)
+  const uint16_t* tree[N];   // K or V tree base
+  unsigned lds[N];         // byte offset inside the K+V tile pair
 };
 
 template <int D>
-__device__ __forceinline__ void lane_chunks(LaneChunks<D>& lc, int wave, int lane, long long kc_sl) {
+__device__ __forceinline__ void lane_chunks(LaneChunks<D>& lc, int wave, int lane, const TileSrc& ts) {
   using G_ = Geo<D>;
   constexpr int RPB = 64 / G_::CPR;
 #pragma unroll
-  for (int i = 0; i < LaneChunks<D>::NIK; ++i) {
-    const int blk = wave * LaneChunks<D>::NIK + i;
+  for (int i = 0; i < LaneChunks<D>::N; ++i) {
+    const int id = wave * LaneChunks<D>::N + i;  // 0 .. 2*NB-1
+    const int is_v = id / G_::NB, blk = id % G_::NB;
     const int row = blk * RPB + lane / G_::CPR;
     const int pc = lane % G_::CPR;
+    const int kc = pc ^ G_::kswz(row);                                  // K: 16-byte chunks swizzled
+    const int vc = (((pc >> 2) ^ G_::vswz(row)) << 2) | (pc & 3);       // V: 64-byte blocks swizzled
     lc.row[i] = row;
-    lc.kcol[i] = (pc ^ G_::kswz(row)) * 8;
-    lc.vcol[i] = ((((pc >> 2) ^ G_::vswz(row)) << 2) | (pc & 3)) * 8;
-    lc.koff[i] = (long long)row * kc_sl + lc.kcol[i];
-    lc.voff[i] = (long long)row * kc_sl + lc.vcol[i];
-    lc.lds[i] = blk * 1024;
+    lc.col[i] = (is_v ? vc : kc) * 8;
+    lc.cache[i] = is_v ? ts.vc : ts.kc;
+    lc.tree[i] = is_v ? ts.vt : ts.kt;
+    lc.full[i] = lc.cache[i] + (long long)row * ts.kc_sl + lc.col[i];
+    lc.lds[i] = is_v * G_::TILE_BYTES + blk * 1024;
   }
 }
 
@@ -155,185 +160,171 @@ __device__ __forceinline__ void lane_chunks(LaneChunks<D>& lc, int wave, int lan
 template <int D, int WN>
 __device__ __forceinline__ void dma_round(int r, const TileSrc& ts, const LaneChunks<D>& lc, unsigned slot) {
   using G_ = Geo<D>;
-  constexpr int NIK = LaneChunks<D>::NIK;
+  constexpr int N = LaneChunks<D>::N;
+  const int t0 = ts.t_begin + r * WN;
+  if ((t0 + WN) * kTileKeys <= ts.L) {
+    // every tile of the round is a full prefix tile: one scalar offset per tile plus the
+    // lane's precomputed address
+    const long long tile_elems = (long long)kTileKeys * ts.kc_sl;
+    long long off = (long long)t0 * tile_elems;
 #pragma unroll
+    for (int w = 0; w < WN; ++w) {
+#pragma unroll
+      for (int i = 0; i < N; ++i) dma16(lc.full[i] + off, slot + w * 2 * G_::TILE_BYTES + lc.lds[i]);
+      off += tile_elems;
+    }
+    return;
+  }
+#pragma unroll 1
   for (int w = 0; w < WN; ++w) {
-    int t = ts.t_begin + r * WN + w;
+    int t = t0 + w;
     if (t >= ts.t_end) t = ts.t_end - 1;  // duplicate of a real tile, never consumed
-    const unsigned kdst = slot + (w * 2 + 0) * G_::TILE_BYTES, vdst = slot + (w * 2 + 1) * G_::TILE_BYTES;
-    if ((t + 1) * kTileKeys <= ts.L) {
-      // full prefix tile: one scalar tile offset plus the lane's precomputed offsets
-      const long long tile_off = (long long)t * kTileKeys * ts.kc_sl;
+    const unsigned dst = slot + w * 2 * G_::TILE_BYTES;
+    // ragged last prefix tile or tree tile: rows past the end re-read the last valid row
+    const bool tree = t >= ts.n_ptiles;
+    const int key0 = (tree ? t - ts.n_ptiles : t) * kTileKeys;
+    const int last = (tree ? ts.T : ts.L) - 1 - key0;  // >= 0 (and >= 31 for a full prefix tile)
+    const long long rs = tree ? ts.kt_st : ts.kc_sl;
 #pragma unroll
-      for (int i = 0; i < NIK; ++i) {
-        dma16(ts.kc + tile_off + lc.koff[i], kdst + lc.lds[i]);
-        dma16(ts.vc + tile_off + lc.voff[i], vdst + lc.lds[i]);
-      }
-    } else {
-      // ragged last prefix tile or tree tile: rows past the end re-read the last valid row
-      const bool tree = t >= ts.n_ptiles;
-      const int key0 = (tree ? t - ts.n_ptiles : t) * kTileKeys;
-      const int last = (tree ? ts.T : ts.L) - 1 - key0;  // >= 0
-      const uint16_t* kb = tree ? ts.kt : ts.kc;
-      const uint16_t* vb = tree ? ts.vt : ts.vc;
-      const long long rs = tree ? ts.kt_st : ts.kc_sl;
-#pragma unroll
-      for (int i = 0; i < NIK; ++i) {
-        const int rr = lc.row[i] < last ? lc.row[i] : last;
-        const long long rowoff = (long long)(key0 + rr) * rs;
-        dma16(kb + rowoff + lc.kcol[i], kdst + lc.lds[i]);
-        dma16(vb + rowoff + lc.vcol[i], vdst + lc.lds[i]);
-      }
+    for (int i = 0; i < N; ++i) {
+      const uint16_t* base = tree ? lc.tree[i] : lc.cache[i];
+      const int rr = lc.row[i] < last ? lc.row[i] : last;
+      dma16(base + (long long)(key0 + rr) * rs + lc.col[i], dst + lc.lds[i]);
     }
   }
 }
 
-// Per-wave state of the online softmax and the output accumulation.
+// Per-wave state of the online softmax and the output accumulation (32 query rows).
 template <int D>
 struct WaveState {
-  bf16x8 q[2][Geo<D>::DK];
-  floatx16 o[2][Geo<D>::DB];
-  float m[2], l[2];
+  bf16x8 q[Geo<D>::DK];
+  floatx16 o[Geo<D>::DB];
+  float m, l;
 };
 
-// One 32-key tile against the wave's 64 query rows.  mask_mode: 0 none, 1 ragged prefix
-// tail (keys >= nvalid hidden), 2 tree tile (bits[qb] = visibility of the tile's 32 keys).
+// One 32-key tile against the wave's 32 query rows.  mask_mode: 0 none, 1 ragged prefix
+// tail (keys >= nvalid hidden), 2 tree tile (bits = visibility of the tile's 32 keys).
 template <int D>
 __device__ __forceinline__ void compute_tile(WaveState<D>& st, const unsigned char* kt_s,
                                              const unsigned char* vt_s, int mask_mode, int nvalid,
-                                             unsigned int bits0, unsigned int bits1, float scale_log2,
-                                             int lane) {
+                                             unsigned int bits, float scale_log2, int lane) {
   using G_ = Geo<D>;
   constexpr int DK = G_::DK, DB = G_::DB;
-  // The lane id is laundered through an empty asm so that the two dozen LDS addresses below
-  // are recomputed per tile (a few ALU operations) instead of being hoisted out of the tile
-  // loop, where they would push the register demand past the 256 directly usable vector
-  // registers and force the Q operands out into accumulation registers.
-  asm volatile("" : "+v"(lane));
   const int c32 = lane & 31, g = lane >> 5;
   // ---- S^T = K . Q^T
-  floatx16 sacc[2];
+  floatx16 sacc;
 #pragma unroll
-  for (int qb = 0; qb < 2; ++qb)
+  for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
+  {
+    const unsigned char* krow = kt_s + c32 * G_::ROW_BYTES;
+    const int x = G_::kswz(c32);
 #pragma unroll
-    for (int i = 0; i < 16; ++i) sacc[qb][i] = 0.f;
-#pragma unroll
-  for (int ks = 0; ks < DK; ++ks) {
-    const bf16x8 a = *reinterpret_cast<const bf16x8*>(kt_s + G_::koff(c32, 2 * ks + g));
-#pragma unroll
-    for (int qb = 0; qb < 2; ++qb)
-      sacc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, st.q[qb][ks], sacc[qb], 0, 0, 0);
+    for (int ks = 0; ks < DK; ++ks) {
+      const bf16x8 a = *reinterpret_cast<const bf16x8*>(krow + (((2 * ks + g) ^ x) << 4));
+      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, st.q[ks], sacc, 0, 0, 0);
+    }
   }
   // ---- masks: register i of a lane is key 8*(i/4) + 4*g + i%4 of the tile
   if (mask_mode == 2) {
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-      const unsigned int bits = qb ? bits1 : bits0;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int kk = 8 * (i / 4) + 4 * g + (i % 4);
-        if (!((bits >> kk) & 1u)) sacc[qb][i] = -INFINITY;
-      }
+    for (int i = 0; i < 16; ++i) {
+      const int kk = 8 * (i / 4) + 4 * g + (i % 4);
+      if (!((bits >> kk) & 1u)) sacc[i] = -INFINITY;
     }
   } else if (mask_mode == 1) {
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int kk = 8 * (i / 4) + 4 * g + (i % 4);
-        if (kk >= nvalid) sacc[qb][i] = -INFINITY;
-      }
+    for (int i = 0; i < 16; ++i) {
+      const int kk = 8 * (i / 4) + 4 * g + (i % 4);
+      if (kk >= nvalid) sacc[i] = -INFINITY;
+    }
   }
   // ---- online softmax; probabilities become bf16 B operands of the value product.
   // The reference maximum m of a row moves only when the tile's maximum exceeds it by more
   // than kLazy (in log2 units): weights then stay below 2^kLazy, harmless in fp32/bf16, and
-  // the rescale of the 64x128 accumulators (which live in accumulation registers and are
-  // costly to touch from the vector ALU) becomes rare.  The result is unchanged: weights,
-  // their sum and the accumulators all carry the same reference.
+  // the rescale of the accumulators (which live in accumulation registers and are costly
+  // to touch from the vector ALU) becomes rare.  The result is unchanged: weights, their
+  // sum and the accumulators all carry the same reference.
   constexpr float kLazy = 8.f;
-  bf16x8 pb[2][2];
-  float alpha[2];
-  bool moved = false;
+  bf16x8 pb[2];
+  float tmax = fmaxf(sacc[0], sacc[1]);
 #pragma unroll
-  for (int qb = 0; qb < 2; ++qb) {
-    float tmax = sacc[qb][0];
+  for (int i = 2; i < 16; ++i) tmax = fmaxf(tmax, sacc[i]);
+  tmax = half_swap_max(tmax) * scale_log2;
+  const float m_old = st.m;
+  const bool up = tmax > m_old + kLazy;  // false for tmax = -inf; true for the first visible key
+  const float m_ref = up ? tmax : m_old;
+  const float m_use = (m_ref == -INFINITY) ? 0.f : m_ref;
+  const float alpha = up ? fast_exp2(m_old - m_use) : 1.f;
+  const bool moved = up && (m_old != -INFINITY);  // accumulators are still zero before the first key
+  st.m = m_ref;
+  float lsum = 0.f;
 #pragma unroll
-    for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, sacc[qb][i]);
-    tmax = half_swap_max(tmax) * scale_log2;
-    const float m_old = st.m[qb];
-    const bool up = tmax > m_old + kLazy;  // false for tmax = -inf; true for the first visible key
-    const float m_ref = up ? tmax : m_old;
-    const float m_use = (m_ref == -INFINITY) ? 0.f : m_ref;
-    alpha[qb] = up ? fast_exp2(m_old - m_use) : 1.f;
-    moved |= up && (m_old != -INFINITY);   // accumulators are still zero before the first key
-    st.m[qb] = m_ref;
-    float lsum = 0.f;
-    float pr[16];
+  for (int j = 0; j < 2; ++j)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      pr[i] = fast_exp2(fmaf(sacc[qb][i], scale_log2, -m_use));
-      lsum += pr[i];
+    for (int e = 0; e < 8; ++e) {
+      const float pr = fast_exp2(fmaf(sacc[8 * j + e], scale_log2, -m_use));
+      lsum += pr;
+      pb[j][e] = (__bf16)pr;
     }
-    st.l[qb] = fmaf(st.l[qb], alpha[qb], lsum);
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int e = 0; e < 8; ++e) pb[qb][j][e] = (__bf16)pr[8 * j + e];
-  }
+  st.l = fmaf(st.l, alpha, lsum);
   if (__any(moved)) {
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb)
+    for (int db = 0; db < DB; ++db)
 #pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) st.o[qb][db][i] *= alpha[qb];
+      for (int i = 0; i < 16; ++i) st.o[db][i] *= alpha;
   }
-  // ---- O^T += V^T . P^T ; contraction index 4*q'+r of MFMA j is key 16*j + 8*q' + 4*g + r
-  const int jj = (lane & 15) >> 2, cc = lane & 3, h16 = (lane & 31) >> 4;
+  // ---- O^T += V^T . P^T ; contraction index 4*q'+r of MFMA j is key 16*j + 8*q' + 4*g + r.
+  // Transpose read: the 16 lanes of a group address 4 keys x 32 bytes; lane i of the group
+  // receives d-column i of those 4 keys.
+  {
+    const int jj = (lane & 15) >> 2, cc = lane & 3, h16 = (lane & 31) >> 4;
+    const int key_lo = 4 * g + jj;  // + 16*j + 8*q'
+    const unsigned char* vrow = vt_s + key_lo * G_::ROW_BYTES + 32 * h16 + 8 * cc;
+    const int sw = G_::vswz(key_lo);  // keys 8 and 16 apart share it
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
+    for (int j = 0; j < 2; ++j) {
 #pragma unroll
-    for (int db = 0; db < DB; ++db) {
-      shortx4 v0, v1;
-      {
-        const int key = 16 * j + 4 * g + jj;
-        const unsigned char* ad = vt_s + key * G_::ROW_BYTES + ((db ^ G_::vswz(key)) << 6) + 32 * h16 + 8 * cc;
-        v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(shortx4, ad));
+      for (int db = 0; db < DB; ++db) {
+        const unsigned char* ad = vrow + ((db ^ sw) << 6) + (16 * j) * G_::ROW_BYTES;
+        const shortx4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(shortx4, ad));
+        const shortx4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(shortx4, ad + 8 * G_::ROW_BYTES));
+        const shortx8 v01 = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
+        st.o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, v01), pb[j], st.o[db], 0, 0, 0);
       }
-      {
-        const int key = 16 * j + 8 + 4 * g + jj;
-        const unsigned char* ad = vt_s + key * G_::ROW_BYTES + ((db ^ G_::vswz(key)) << 6) + 32 * h16 + 8 * cc;
-        v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(shortx4, ad));
-      }
-      const shortx8 v01 = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
-      const bf16x8 a = __builtin_bit_cast(bf16x8, v01);
-#pragma unroll
-      for (int qb = 0; qb < 2; ++qb)
-        st.o[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[qb][j], st.o[qb][db], 0, 0, 0);
     }
   }
 }
 
-template <int D, int WM, int WN, int NR>
-__global__ __launch_bounds__(256, 1) void tva_bf16_kernel(const KParams p) {
+#ifdef JK_TIMING
+__device__ unsigned long long g_jk_ts[4096 * 8];
+#define JK_TS(i) do { if (threadIdx.x == 0) g_jk_ts[blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
+#else
+#define JK_TS(i) do { } while (0)
+#endif
+
+template <int D, int WM, int WN>
+__global__ __launch_bounds__(kThreads, 2) void tva_bf16_kernel(const KParams p) {
   using G_ = Geo<D>;
-  constexpr int NCH = G_::NCH, DK = G_::DK, DB = G_::DB;
-  constexpr int QROWS = 64 * WM;
+  constexpr int DK = G_::DK, DB = G_::DB;
+  constexpr int NR = kRingTiles / WN;                // rounds resident in the ring
+  constexpr int QROWS = kWaveRows * WM;
   constexpr int TILE_BYTES = G_::TILE_BYTES;
   constexpr int STAGE_BYTES = WN * 2 * TILE_BYTES;   // one round: WN tiles of K and V
   constexpr int RING_BYTES = NR * STAGE_BYTES;
-  constexpr int DMA_PER_ROUND = WN * 2 * (TILE_BYTES / 1024 / 4);  // transfers a wave issues per round
-  constexpr int OBUF_BYTES = 4 * 64 * G_::O_LD * 4;
+  constexpr int DMA_PER_ROUND = WN * G_::DMA_PER_TILE;  // transfers a wave issues per round
+  constexpr int OBUF_BYTES = kWaves * kWaveRows * G_::O_LD * 4;
   constexpr int UNION_BYTES = RING_BYTES > OBUF_BYTES ? RING_BYTES : OBUF_BYTES;
-  static_assert(NR >= 2 && NR <= 8 && (NR - 2) * DMA_PER_ROUND <= 63, "ring depth");
+  static_assert(WM * WN == kWaves && NR >= 2 && (NR - 2) * DMA_PER_ROUND <= 63, "wave arrangement");
 
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   unsigned char* ring = smem;
-  float* obuf = reinterpret_cast<float*>(smem);                            // [WN][QROWS][O_LD], after the loop
-  float2* mlbuf = reinterpret_cast<float2*>(smem + UNION_BYTES);           // [WN][QROWS]
-  unsigned long long* anc = reinterpret_cast<unsigned long long*>(smem + UNION_BYTES + 4 * 64 * 8);  // [128][2]
-  int* par_s = reinterpret_cast<int*>(smem + UNION_BYTES + 4 * 64 * 8 + JK_MAX_TREE * 16);           // [128]
+  float* obuf = reinterpret_cast<float*>(smem);                                  // [WN][QROWS][O_LD], after the loop
+  float2* mlbuf = reinterpret_cast<float2*>(smem + UNION_BYTES);                 // [WN][QROWS]
+  unsigned long long* anc =
+      reinterpret_cast<unsigned long long*>(smem + UNION_BYTES + kWaves * kWaveRows * 8);  // [128][2]
+  int* par_s = reinterpret_cast<int*>(smem + UNION_BYTES + kWaves * kWaveRows * 8 + JK_MAX_TREE * 16);  // [128]
 
+  JK_TS(0);
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -363,13 +354,14 @@ __global__ __launch_bounds__(256, 1) void tva_bf16_kernel(const KParams p) {
 
   int L = p.prefix_len[b];
   L = L < 0 ? 0 : (L > p.max_prefix ? p.max_prefix : L);
+  JK_TS(1);
   TileSrc ts;
   ts.L = L;
   ts.T = T;
   ts.n_ptiles = (L + kTileKeys - 1) / kTileKeys;
   const int nt = ts.n_ptiles + (T + kTileKeys - 1) / kTileKeys;
-  ts.t_begin = (int)((long long)split * nt / splits);
-  ts.t_end = (int)((long long)(split + 1) * nt / splits);
+  ts.t_begin = (int)((unsigned)split * (unsigned)nt / (unsigned)splits);  // nt < 2^25, splits <= 64
+  ts.t_end = (int)((unsigned)(split + 1) * (unsigned)nt / (unsigned)splits);
   ts.kc = p.kc + b * p.kc_sb + (long long)kv * p.kc_sh;
   ts.vc = p.vc + b * p.kc_sb + (long long)kv * p.kc_sh;
   ts.kt = p.kt + b * p.kt_sb + (long long)kv * p.kt_sh;
@@ -378,40 +370,38 @@ __global__ __launch_bounds__(256, 1) void tva_bf16_kernel(const KParams p) {
   ts.kt_st = p.kt_st;
   const int n_rounds = (ts.t_end - ts.t_begin + WN - 1) / WN;
 
-  // ---- ancestor sets (only workgroups that reach tree tiles need them)
+  // ---- ordinary loads first (parent, Q): they are older than every K/V transfer, so the
+  // compiler's waits for them never include a transfer
   const bool has_tree = ts.t_end > ts.n_ptiles;
   int my_parent = -1;
   if (has_tree && tid < T) my_parent = p.parent[(long long)b * T + tid];
 
-  // ---- this wave's 64 query rows as MFMA B operands (lane: row c32, 8 consecutive d)
   WaveState<D> st;
-  const int row_base = qtile * QROWS + wm * 64;  // first row (within the KV head's M rows)
-  int node_of[2];
-#pragma unroll
-  for (int qb = 0; qb < 2; ++qb) {
-    const int m = row_base + qb * 32 + c32;
-    const bool ok = m < M;
-    const int mm = ok ? m : M - 1;
-    const int node = mm / G, hg = mm % G;
-    node_of[qb] = node;
-    const uint16_t* src = p.q + b * p.q_sb + node * p.q_st + (long long)(kv * G + hg) * p.q_sh + 8 * g;
+  const int m_row = qtile * QROWS + wm * kWaveRows + c32;  // this lane's query row
+  const bool row_ok = m_row < M;
+  const int mm = row_ok ? m_row : M - 1;
+  const int my_node = mm / G;
+  {
+    const uint16_t* src = p.q + b * p.q_sb + my_node * p.q_st + (long long)(kv * G + mm % G) * p.q_sh + 8 * g;
 #pragma unroll
     for (int ks = 0; ks < DK; ++ks) {
       u32x4 v = *reinterpret_cast<const u32x4*>(src + ks * 16);  // clamped row: always in bounds
-      if (!ok) v = u32x4{0u, 0u, 0u, 0u};
-      st.q[qb][ks] = __builtin_bit_cast(bf16x8, v);
+      if (!row_ok) v = u32x4{0u, 0u, 0u, 0u};
+      st.q[ks] = __builtin_bit_cast(bf16x8, v);
     }
   }
-  // ---- start the K/V stream: NR-1 rounds in flight.  The ordinary loads above (Q, parent)
-  // are older than every transfer, so the compiler's waits for them never wait for a transfer
-  // that was issued later... but a wait placed after this point does: hence they come first.
+
+  JK_TS(2);
+  // ---- start the K/V stream: NR-1 rounds in flight
   const unsigned ring_addr = (unsigned)(size_t)LDS_PTR(unsigned char, ring);
   LaneChunks<D> lc;
-  lane_chunks<D>(lc, wave, lane, ts.kc_sl);
+  lane_chunks<D>(lc, wave, lane, ts);
 #pragma unroll
   for (int r = 0; r < NR - 1; ++r)
     if (r < n_rounds) dma_round<D, WN>(r, ts, lc, ring_addr + r * STAGE_BYTES);
 
+  JK_TS(3);
+  // ---- ancestor sets (only workgroups that reach tree tiles need them)
   if (has_tree) {
     if (tid < T) par_s[tid] = (my_parent >= -1 && my_parent < tid) ? my_parent : -1;
     __syncthreads();
@@ -429,14 +419,11 @@ __global__ __launch_bounds__(256, 1) void tva_bf16_kernel(const KParams p) {
   }
 
 #pragma unroll
-  for (int qb = 0; qb < 2; ++qb) {
+  for (int db = 0; db < DB; ++db)
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) st.o[qb][db][i] = 0.f;
-    st.m[qb] = -INFINITY;
-    st.l[qb] = 0.f;
-  }
+    for (int i = 0; i < 16; ++i) st.o[db][i] = 0.f;
+  st.m = -INFINITY;
+  st.l = 0.f;
 
   // ---- main loop.  Round r lives in ring slot r % NR.  Before the barrier a wave waits for
   // its own transfers of round r; after the barrier every wave's have landed, and every wave
@@ -445,49 +432,49 @@ __global__ __launch_bounds__(256, 1) void tva_bf16_kernel(const KParams p) {
     const int ahead = n_rounds - 1 - r;  // rounds issued after r: min(NR-2, ahead)
     wait_dma<DMA_PER_ROUND>(ahead < NR - 2 ? ahead : NR - 2);
     __syncthreads();
+    if (r == 0) JK_TS(4);
     if (r + NR - 1 < n_rounds)
       dma_round<D, WN>(r + NR - 1, ts, lc, ring_addr + ((r + NR - 1) % NR) * STAGE_BYTES);
     const int t = ts.t_begin + r * WN + wn;
     if (t < ts.t_end) {
       int mode = 0, nvalid = kTileKeys;
-      unsigned int bits0 = 0, bits1 = 0;
+      unsigned int bits = 0;
       if (t >= ts.n_ptiles) {
         const int tt = t - ts.n_ptiles;
         mode = 2;
-        bits0 = (unsigned int)(anc[2 * node_of[0] + (tt >> 1)] >> ((tt & 1) * 32));
-        bits1 = (unsigned int)(anc[2 * node_of[1] + (tt >> 1)] >> ((tt & 1) * 32));
+        bits = (unsigned int)(anc[2 * my_node + (tt >> 1)] >> ((tt & 1) * 32));
       } else {
         nvalid = L - t * kTileKeys;
         mode = nvalid < kTileKeys ? 1 : 0;
       }
       const unsigned char* kt_s = ring + (r % NR) * STAGE_BYTES + wn * 2 * TILE_BYTES;
-      compute_tile<D>(st, kt_s, kt_s + TILE_BYTES, mode, nvalid, bits0, bits1, scale_log2, lane);
+      compute_tile<D>(st, kt_s, kt_s + TILE_BYTES, mode, nvalid, bits, scale_log2, lane);
     }
   }
+  JK_TS(5);
   __syncthreads();  // every wave is done with the ring before it becomes the epilogue buffer
 
   // ---- epilogue: O^T and (max, sum) of each wave into LDS
-#pragma unroll
-  for (int qb = 0; qb < 2; ++qb) {
-    const float l_tot = half_swap_sum(st.l[qb]);
-    const int row = wm * 64 + qb * 32 + c32;
+  {
+    const float l_tot = half_swap_sum(st.l);
+    const int row = wm * kWaveRows + c32;
     float* orow = obuf + ((size_t)wn * QROWS + row) * G_::O_LD;
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4) {
-        float4 v = make_float4(st.o[qb][db][4 * q4], st.o[qb][db][4 * q4 + 1], st.o[qb][db][4 * q4 + 2],
-                               st.o[qb][db][4 * q4 + 3]);
+        float4 v = make_float4(st.o[db][4 * q4], st.o[db][4 * q4 + 1], st.o[db][4 * q4 + 2], st.o[db][4 * q4 + 3]);
         *reinterpret_cast<float4*>(orow + 32 * db + 8 * q4 + 4 * g) = v;
       }
-    if (g == 0) mlbuf[wn * QROWS + row] = make_float2(st.m[qb], l_tot);
+    if (g == 0) mlbuf[wn * QROWS + row] = make_float2(st.m, l_tot);
   }
   __syncthreads();
 
+  JK_TS(6);
   // ---- merge the WN key-interleaved waves, then write the split's partial (or the result)
   constexpr int D4 = D / 4;
   const long long unit = (long long)(b * p.Hkv + kv);
-  for (int it = tid; it < QROWS * D4; it += 256) {
+  for (int it = tid; it < QROWS * D4; it += kThreads) {
     const int row = it / D4, d4 = it % D4;
     const int m = qtile * QROWS + row;
     if (m >= M) continue;
@@ -527,17 +514,18 @@ __global__ __launch_bounds__(256, 1) void tva_bf16_kernel(const KParams p) {
       if (d4 == 0) p.part_ml[prow] = make_float2(mx, lsum);
     }
   }
+  JK_TS(7);
 }
 
-template <int D, int WM, int WN, int NR>
+template <int D, int WM, int WN>
 hipError_t launch_one(const KParams& kp, hipStream_t stream) {
   using G_ = Geo<D>;
-  constexpr int RING_BYTES = NR * WN * 2 * G_::TILE_BYTES;
-  constexpr int OBUF_BYTES = 4 * 64 * G_::O_LD * 4;
+  constexpr int RING_BYTES = kRingTiles * 2 * G_::TILE_BYTES;
+  constexpr int OBUF_BYTES = kWaves * kWaveRows * G_::O_LD * 4;
   constexpr int UNION_BYTES = RING_BYTES > OBUF_BYTES ? RING_BYTES : OBUF_BYTES;
-  constexpr int SMEM = UNION_BYTES + 4 * 64 * 8 + JK_MAX_TREE * 16 + JK_MAX_TREE * 4;
-  static_assert(SMEM <= 160 * 1024, "LDS budget");
-  auto kern = tva_bf16_kernel<D, WM, WN, NR>;
+  constexpr int SMEM = UNION_BYTES + kWaves * kWaveRows * 8 + JK_MAX_TREE * 16 + JK_MAX_TREE * 4;
+  static_assert(2 * SMEM <= 160 * 1024, "LDS budget: two workgroups per CU");
+  auto kern = tva_bf16_kernel<D, WM, WN>;
   static bool lds_limit_raised = false;  // idempotent, so a race between host threads is harmless
   if (!lds_limit_raised) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -545,11 +533,17 @@ hipError_t launch_one(const KParams& kp, hipStream_t stream) {
     if (e != hipSuccess) return e;
     lds_limit_raised = true;
   }
-  hipLaunchKernelGGL(kern, dim3(kp.total_wgs), dim3(256), SMEM, stream, kp);
+  hipLaunchKernelGGL(kern, dim3(kp.total_wgs), dim3(kThreads), SMEM, stream, kp);
   return hipGetLastError();
 }
 
 }  // namespace
+
+#ifdef JK_TIMING
+extern "C" int jk_debug_read_timing(unsigned long long* host, size_t n) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_jk_ts), n * sizeof(unsigned long long));
+}
+#endif
 
 hipError_t launch_tva_bf16(const AttnArgs& a, const AttnPlan& pl, hipStream_t stream) {
   KParams kp;
@@ -577,13 +571,10 @@ hipError_t launch_tva_bf16(const AttnArgs& a, const AttnPlan& pl, hipStream_t st
 
   const int key = d.head_dim * 100 + pl.wm * 10 + pl.wn;
   switch (key) {
-    // ring depth: 8 tiles of K+V (128 KB at head_dim 128) whatever the wave arrangement
-    case 12841: return launch_one<128, 4, 1, 8>(kp, stream);
-    case 12822: return launch_one<128, 2, 2, 4>(kp, stream);
-    case 12814: return launch_one<128, 1, 4, 2>(kp, stream);
-    case 6441: return launch_one<64, 4, 1, 8>(kp, stream);
-    case 6422: return launch_one<64, 2, 2, 4>(kp, stream);
-    case 6414: return launch_one<64, 1, 4, 2>(kp, stream);
+    case 12841: return launch_one<128, 4, 1>(kp, stream);
+    case 12822: return launch_one<128, 2, 2>(kp, stream);
+    case 6441: return launch_one<64, 4, 1>(kp, stream);
+    case 6422: return launch_one<64, 2, 2>(kp, stream);
     default: return hipErrorInvalidValue;
   }
 }

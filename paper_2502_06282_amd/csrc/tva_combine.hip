@@ -19,68 +19,82 @@ struct CParams {
   long long o_sb, o_st, o_sh;
 };
 
-// One workgroup per query row.  Thread (sg, d4) sums every NG-th split for four output
-// columns, so the loads of a row's splits are all in flight together; the NG partial sums
-// meet in LDS.  LOG2: running maxima are in log2 units (bf16 path) rather than natural
-// units (fp32 path).
+// A workgroup merges up to 4 consecutive query rows.  A row is
+// covered by two groups of D/4 threads; each thread sums every other split for four output
+// columns with up to four loads in flight, and the two halves meet in LDS.  LOG2: running
+// maxima are in log2 units (bf16 path) rather than natural units (fp32 path).
 template <bool LOG2, bool OUT_BF16>
 __global__ __launch_bounds__(256) void tva_combine_kernel(CParams p) {
-  __shared__ float s_m[kMaxSplits], s_w[kMaxSplits];
+  __shared__ float s_w[256];      // [row in workgroup][split] weights, splits padded to a power of two
+  __shared__ float s_l[256];
   __shared__ float4 s_acc[256];
-  __shared__ float s_l;
   const int tid = threadIdx.x;
-  const int d4n = p.D / 4;        // 16..64 threads cover a row
-  const int ng = 256 / d4n;       // split groups
-  const int d4 = tid % d4n, sg = tid / d4n;
-  const long long r = blockIdx.x;  // (b * Hkv + kv) * M + m
-  const int m = (int)(r % p.M);
-  const long long unit = r / p.M;
-  const int kv = (int)(unit % p.Hkv);
-  const int b = (int)(unit / p.Hkv);
-  const long long row0 = unit * p.splits * p.m_pad + m;
+  const int d4n = p.D / 4;
+  const int tpr = 2 * d4n;                          // threads per row
+  const int rpw = 256 / (tpr > 64 ? tpr : 64);      // rows per workgroup (at most 4)
+  const int spad = 256 / rpw;                       // weight slots per row: 64 or more, >= splits
+  const long long n_rows = (long long)p.B * p.Hkv * p.M;
 
-  float my_l = 0.f;
-  if (tid < p.splits) {
-    const float2 ml = p.part_ml[row0 + (long long)tid * p.m_pad];
-    s_m[tid] = ml.y > 0.f ? ml.x : -INFINITY;  // an empty split carries no weight
-    my_l = ml.y;
-  }
-  __syncthreads();
-  float mx = -INFINITY;
-  for (int s = 0; s < p.splits; ++s) mx = fmaxf(mx, s_m[s]);
-  const float mx_use = (mx == -INFINITY) ? 0.f : mx;
-  float lw = 0.f;
-  if (tid < p.splits) {
-    const float w = LOG2 ? __builtin_amdgcn_exp2f(s_m[tid] - mx_use) : expf(s_m[tid] - mx_use);
-    s_w[tid] = w;
-    lw = my_l * w;
-  }
-  if (tid < 64) {  // splits <= 64 all live in the first wave
+  // weights of every (row, split) of this workgroup: one thread each
+  {
+    const int rr = tid / spad, sp = tid % spad;
+    const long long r = (long long)blockIdx.x * rpw + rr;
+    float m = -INFINITY, l = 0.f;
+    if (r < n_rows && sp < p.splits) {
+      const long long unit = r / p.M;
+      const float2 ml = p.part_ml[(unit * p.splits + sp) * p.m_pad + (r % p.M)];
+      if (ml.y > 0.f) { m = ml.x; l = ml.y; }  // an empty split carries no weight
+    }
+    float mx = m;
+    // the (at most 64) real splits of a row sit in one wave: slots are 64-aligned
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+    const float mx_use = (mx == -INFINITY) ? 0.f : mx;
+    const float w = LOG2 ? __builtin_amdgcn_exp2f(m - mx_use) : expf(m - mx_use);
+    float lw = l * w;
     for (int o = 32; o > 0; o >>= 1) lw += __shfl_xor(lw, o);
-    if (tid == 0) s_l = lw;
+    s_w[tid] = w;
+    if (sp == 0) s_l[rr] = lw;
   }
   __syncthreads();
 
+  const int rr = tid / tpr, half = (tid % tpr) / d4n, d4 = tid % d4n;
+  const long long r = (long long)blockIdx.x * rpw + rr;
+  const bool live = rr < rpw && r < n_rows;
+  const long long unit = live ? r / p.M : 0;
+  const int m = live ? (int)(r % p.M) : 0;
+  const long long row0 = unit * p.splits * p.m_pad + m;
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-  if (sg < ng) {
-    for (int s = sg; s < p.splits; s += ng) {
-      const float w = s_w[s];
-      if (w == 0.f) continue;
-      const float4 o = *reinterpret_cast<const float4*>(p.part_o + (row0 + (long long)s * p.m_pad) * p.D + 4 * d4);
-      acc.x = fmaf(o.x, w, acc.x);
-      acc.y = fmaf(o.y, w, acc.y);
-      acc.z = fmaf(o.z, w, acc.z);
-      acc.w = fmaf(o.w, w, acc.w);
+  if (live) {
+    for (int s0 = half; s0 < p.splits; s0 += 8) {
+      float4 o[4];
+      float w[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int sp = s0 + 2 * u;
+        w[u] = sp < p.splits ? s_w[rr * spad + sp] : 0.f;
+        o[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (w[u] != 0.f)
+          o[u] = *reinterpret_cast<const float4*>(p.part_o + (row0 + (long long)sp * p.m_pad) * p.D + 4 * d4);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        acc.x = fmaf(o[u].x, w[u], acc.x);
+        acc.y = fmaf(o[u].y, w[u], acc.y);
+        acc.z = fmaf(o[u].z, w[u], acc.z);
+        acc.w = fmaf(o[u].w, w[u], acc.w);
+      }
     }
   }
   s_acc[tid] = acc;
   __syncthreads();
-  if (sg != 0) return;
-  for (int g2 = 1; g2 < ng; ++g2) {
-    const float4 o = s_acc[g2 * d4n + d4];
+  if (!live || half != 0) return;
+  {
+    const float4 o = s_acc[tid + d4n];
     acc.x += o.x; acc.y += o.y; acc.z += o.z; acc.w += o.w;
   }
-  const float inv = 1.f / s_l;
+  const float inv = 1.f / s_l[rr];
+  const int kv = (int)(unit % p.Hkv);
+  const int b = (int)(unit / p.Hkv);
   const int node = m / p.G, hg = m % p.G;
   const long long off = b * p.o_sb + node * p.o_st + (long long)(kv * p.G + hg) * p.o_sh + 4 * d4;
   if (OUT_BF16) {
@@ -110,7 +124,9 @@ hipError_t launch_tva_combine(const AttnArgs& a, const AttnPlan& pl, hipStream_t
   cp.B = d.batch; cp.Hkv = d.n_kv_heads; cp.G = d.n_q_heads / d.n_kv_heads;
   cp.M = pl.m_rows; cp.m_pad = pl.m_pad; cp.D = d.head_dim; cp.splits = pl.splits;
   cp.o_sb = d.o_stride_b; cp.o_st = d.o_stride_t; cp.o_sh = d.o_stride_h;
-  const unsigned grid = (unsigned)((long long)d.batch * d.n_kv_heads * pl.m_rows);
+  const int tpr = 2 * (d.head_dim / 4);
+  const int rpw = 256 / (tpr > 64 ? tpr : 64);
+  const unsigned grid = (unsigned)(((long long)d.batch * d.n_kv_heads * pl.m_rows + rpw - 1) / rpw);
   if (d.dtype == JK_BF16)
     hipLaunchKernelGGL((tva_combine_kernel<true, true>), dim3(grid), dim3(256), 0, stream, cp);
   else

@@ -164,5 +164,64 @@ def test_argument_errors():
         jk.accept_path(tok, tok, lg, jk.JK_SAMPLE, 0.0, lg[:, :4].contiguous(), lg[:, :, 0].contiguous())
     assert e.value.status == 1
     with pytest.raises(jk.JakiroError) as e:
-        jk.accept_path(tok, tok, lg, jk.JK_GREEDY, workspace=torch.empty(16, dtype=torch.uint8, device=dev))
+        jk.accept_path(tok, tok, lg, jk.JK_GREEDY, workspace=torch.zeros(16, dtype=torch.uint8, device=dev))
     assert e.value.status == 4
+
+
+def test_sample_single_workgroup_walk_agrees(monkeypatch):
+    """The one-workgroup walk (used when the cooperative one does not fit) gives the same answers."""
+    cfg = CONFIGS["c3_llama3_8b"].with_(vocab=6000, batch=2)
+    par = tree_for_config(cfg, seed=3)
+    a = accept_inputs(cfg, par, seed=3)
+    coop = _gpu_accept(a, par, "sample")
+    monkeypatch.setenv("JK_ACCEPT_SINGLE", "1")
+    single = _gpu_accept(a, par, "sample")
+    for x, y in zip(coop, single):
+        assert (x == y).all()
+    _compare(a, par, "sample")
+
+
+def test_sample_workspace_reuse_across_shapes_and_graph_replay():
+    """One zero-initialised workspace serves calls of different shapes, and a captured HIP
+    graph of the call replays correctly (every replay checked against the eager result)."""
+    dev = torch.device("cuda")
+    big = CONFIGS["c3_llama3_8b"].with_(vocab=9000, batch=3)
+    small = CONFIGS["c5_llama2_70b"].with_(vocab=2500, batch=1, n_tree=40, depth=5)
+    ws = torch.empty(jk.accept_path_workspace(3, 60, 9000, jk.JK_SAMPLE), dtype=torch.uint8, device=dev)
+    jk.workspace_init(ws)
+    t = lambda v: torch.from_numpy(np.ascontiguousarray(v)).to(dev)
+    results = {}
+    for name, cfg in (("big", big), ("small", small), ("big2", big)):
+        par = tree_for_config(cfg, seed=11)
+        a = accept_inputs(cfg, par, seed=11)
+        path, alen, bonus = jk.accept_path(t(a["tokens"]), t(par), t(a["logits"]), jk.JK_SAMPLE, 1.0,
+                                           t(a["draft_probs"]), t(a["uniforms"]), workspace=ws)
+        torch.cuda.synchronize()
+        results[name] = (path.cpu().numpy(), alen.cpu().numpy(), bonus.cpu().numpy())
+        for b in range(par.shape[0]):
+            r = oracle_accept(a["tokens"][b], par[b], a["logits"][b], "sample", a["draft_probs"][b], a["uniforms"][b])
+            if r.min_margin > MARGIN:
+                assert alen.cpu()[b] == r.accept_len and bonus.cpu()[b] == r.bonus_token
+    assert all((x == y).all() for x, y in zip(results["big"], results["big2"]))
+    # graph replay of the last configuration
+    cfg = big
+    par = tree_for_config(cfg, seed=11)
+    a = accept_inputs(cfg, par, seed=11)
+    o_path = torch.empty((3, 60), dtype=torch.int32, device=dev)
+    o_len = torch.empty(3, dtype=torch.int32, device=dev)
+    o_bonus = torch.empty(3, dtype=torch.int32, device=dev)
+    call = jk.prepare_accept_path(t(a["tokens"]), t(par), t(a["logits"]), jk.JK_SAMPLE, 1.0, t(a["draft_probs"]),
+                                  t(a["uniforms"]), o_path, o_len, o_bonus, ws)
+    call.launch()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=torch.cuda.Stream()):
+        call.launch()
+    for _ in range(3):
+        o_len.fill_(-7); o_bonus.fill_(-7)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert (o_len.cpu().numpy() == results["big"][1]).all() and (o_bonus.cpu().numpy() == results["big"][2]).all()
+        call.launch()                      # eager work between replays
+        torch.cuda.synchronize()
