@@ -128,6 +128,7 @@ def main():
     ws_attn = torch.empty(jk.tree_verify_attention_workspace(layers[0]["q"], layers[0]["k_cache"],
                                                              layers[0]["k_tree"], cfg.prefix_len),
                           dtype=torch.uint8, device=dev)
+    jk.workspace_init(ws_attn)
     ws_acc = torch.empty(jk.accept_path_workspace(cfg.batch, cfg.n_tree, cfg.vocab, mode), dtype=torch.uint8,
                          device=dev)
     jk.workspace_init(ws_acc)

@@ -148,7 +148,7 @@ def tree_verify_attention(q, k_cache, v_cache, k_tree, v_tree, parent, prefix_le
     if need == 0:
         raise JakiroError(3, "jk_tree_verify_attention_workspace")
     if workspace is None:
-        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+        workspace = torch.zeros(need, dtype=torch.uint8, device=q.device)  # must start zero-filled
     st = lib().jk_tree_verify_attention(ctypes.byref(d), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(k_tree),
                                         _ptr(v_tree), _ptr(parent), _ptr(prefix_len), int(max_prefix_len),
                                         _ptr(out), _ptr(workspace), workspace.numel() * workspace.element_size(),

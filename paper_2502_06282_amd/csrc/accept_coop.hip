@@ -26,10 +26,12 @@ namespace {
 constexpr int kCoopThreads = 256;
 constexpr unsigned kSpinLimit = 1u << 22;  // polls before giving up (seconds)
 
+// One workgroup's contribution to an exchange: two doubles, cut into four 32-bit halves,
+// each stored in a 64-bit word together with the exchange's 32-bit tag.  A word is written
+// and read with one 64-bit access, so a reader that sees the tag also sees the half that
+// belongs to it: no fences and no ordering between the words are needed.
 struct Slot {  // 32 bytes
-  unsigned long long tag;
-  double a, b;
-  unsigned long long pad;
+  unsigned long long word[4];
 };
 
 struct CoopParams {
@@ -63,6 +65,7 @@ __global__ __launch_bounds__(kCoopThreads) void walk_sample_coop_kernel(CoopPara
   double* nxt = cur + p.slice;                     // [slice] candidate residual
   __shared__ double red[4];
   __shared__ double xa[64], xb[64];                // the W partials of an exchange
+  __shared__ unsigned xh[256];                     // their 32-bit halves as they arrive
   __shared__ int par_s[JK_MAX_TREE];
   __shared__ int s_fail, s_found;
   __shared__ double rej_s[JK_MAX_TREE];            // residual masses of the rejected siblings at this node
@@ -88,26 +91,34 @@ __global__ __launch_bounds__(kCoopThreads) void walk_sample_coop_kernel(CoopPara
   Slot* slots = p.slots + (long long)b * 2 * 64;
   unsigned n_exch = 0;
 
-  // all-gather of one (a, b) pair per workgroup; results in xa[0..W), xb[0..W)
+  // all-gather of one (a, b) pair per workgroup; results in xa[0..W), xb[0..W).
+  // Tags: 22 bits of call epoch, 10 bits of exchange number (at most N + depth + 2 < 1024 per
+  // call).  Both tables are rewritten by every call (a call has at least two exchanges), so
+  // a stale word is at most one epoch old and can never carry the current tag.
   auto exchange = [&](double a, double bb) {
     ++n_exch;
-    const unsigned long long tag = ((epoch + 1) << 20) | n_exch;
+    const unsigned tag = (unsigned)(((epoch + 1) & 0x3FFFFFull) << 10) | (n_exch & 0x3FFu);
     Slot* tab = slots + (n_exch & 1) * W;
-    if (tid == 0) {
-      tab[w].a = a;
-      tab[w].b = bb;
-      __threadfence();
-      __hip_atomic_store(&tab[w].tag, tag, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    if (tid < 4) {
+      const unsigned long long bits = (unsigned long long)__double_as_longlong(tid < 2 ? a : bb);
+      const unsigned half = (unsigned)(bits >> (32 * (tid & 1)));
+      __hip_atomic_store(&tab[w].word[tid], ((unsigned long long)tag << 32) | half, __ATOMIC_RELAXED,
+                         __HIP_MEMORY_SCOPE_AGENT);
     }
-    if (tid < W) {
+    if (tid < 4 * W) {
+      unsigned long long* src = &tab[tid >> 2].word[tid & 3];
+      unsigned long long v;
       unsigned spins = 0;
-      while (__hip_atomic_load(&tab[tid].tag, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) != tag) {
-        if (++spins > kSpinLimit || s_fail) { s_fail = 1; break; }
-        __builtin_amdgcn_s_sleep(2);
+      while ((unsigned)((v = __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) >> 32) != tag) {
+        if (++spins > kSpinLimit || s_fail) { s_fail = 1; v = 0; break; }
+        __builtin_amdgcn_s_sleep(1);
       }
-      __threadfence();
-      xa[tid] = __hip_atomic_load(&tab[tid].a, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      xb[tid] = __hip_atomic_load(&tab[tid].b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      xh[tid] = (unsigned)v;
+    }
+    __syncthreads();
+    if (tid < W) {
+      xa[tid] = __longlong_as_double((long long)(((unsigned long long)xh[4 * tid + 1] << 32) | xh[4 * tid]));
+      xb[tid] = __longlong_as_double((long long)(((unsigned long long)xh[4 * tid + 3] << 32) | xh[4 * tid + 2]));
     }
     __syncthreads();
   };

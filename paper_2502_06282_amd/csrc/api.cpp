@@ -36,7 +36,7 @@ bool shape_supported(const jk_attn_desc& d) {
 }  // namespace
 
 bool make_attn_plan(const jk_attn_desc& d, int max_prefix_len, AttnPlan* pl) {
-  if (!desc_ok(d) || !shape_supported(d) || max_prefix_len < 0) return false;
+  if (!desc_ok(d) || !shape_supported(d) || max_prefix_len < 0 || max_prefix_len > (1 << 24)) return false;
   const int G = d.n_q_heads / d.n_kv_heads;
   pl->m_rows = d.n_tree * G;
   const long long units = (long long)d.batch * d.n_kv_heads;
@@ -48,7 +48,7 @@ bool make_attn_plan(const jk_attn_desc& d, int max_prefix_len, AttnPlan* pl) {
     // per split.
     const int n_tiles = (max_prefix_len + kTileKeys - 1) / kTileKeys + (d.n_tree + kTileKeys - 1) / kTileKeys;
     const double kv_bytes = 2.0 * (max_prefix_len + d.n_tree) * d.head_dim * 2.0;
-    const int slots = 2 * device_cu_count();  // resident workgroups
+    const int slots = device_cu_count();  // one workgroup per CU measured best (partials cost more than idle slots)
     int forced_wm = 0, forced_s = 0;
     if (const char* e = std::getenv("JK_ATTN_WM")) forced_wm = std::atoi(e);       // tuning overrides
     if (const char* e = std::getenv("JK_ATTN_SPLITS")) forced_s = std::atoi(e);
@@ -61,26 +61,36 @@ bool make_attn_plan(const jk_attn_desc& d, int max_prefix_len, AttnPlan* pl) {
       const int q_rows = 32 * wm;
       const int n_qtiles = (pl->m_rows + q_rows - 1) / q_rows;
       const long long wgs = units * n_qtiles;
-      long long s = (slots + wgs - 1) / wgs;
+      const long long s_full = (slots + wgs - 1) / wgs;  // splits that fill every resident slot
       const int max_by_tiles = n_tiles / (2 * wn) > 0 ? n_tiles / (2 * wn) : 1;  // >= 2 rounds per split
-      if (s > max_by_tiles) s = max_by_tiles;
-      if (s > kMaxSplits) s = kMaxSplits;
-      if (forced_s >= 1 && forced_s <= kMaxSplits) s = forced_s;
-      // partial outputs are written, flushed at the kernel boundary and read back: weigh them double
-      const double partial = s > 1 ? 4.0 * s * pl->m_rows * d.head_dim * 4.0 : 0.0;
-      // one workgroup per CU already reaches most of the throughput; the second hides latencies
-      const double fill = 0.5 + 0.5 * (double)(wgs * s < slots ? wgs * s : slots) / slots;
-      const double cost = (kv_bytes * (1.0 + 0.25 * (n_qtiles - 1)) + partial) / fill;
-      if (!have || cost < best_cost) {
-        have = true;
-        best_cost = cost;
-        pl->wm = wm; pl->wn = wn; pl->q_rows = q_rows; pl->n_qtiles = n_qtiles; pl->splits = (int)s;
+      for (int shrink = 1; shrink <= 1; shrink *= 2) {
+        long long s = (s_full + shrink - 1) / shrink;
+        if (s > max_by_tiles) s = max_by_tiles;
+        if (s > kMaxSplits) s = kMaxSplits;
+        if (forced_s >= 1 && forced_s <= kMaxSplits) s = forced_s;
+        // partial outputs are written, flushed at the kernel boundary and read back: weigh them double
+        const double partial = s > 1 ? 4.0 * s * pl->m_rows * d.head_dim * 4.0 : 0.0;
+        // one workgroup per CU already reaches most of the throughput; the second hides latencies
+        const double fill = 0.5 + 0.5 * (double)(wgs * s < slots ? wgs * s : slots) / slots;
+        const double cost = (kv_bytes * (1.0 + 0.25 * (n_qtiles - 1)) + partial) / fill;
+        if (!have || cost < best_cost) {
+          have = true;
+          best_cost = cost;
+          pl->wm = wm; pl->wn = wn; pl->q_rows = q_rows; pl->n_qtiles = n_qtiles; pl->splits = (int)s;
+        }
       }
     }
     if (!have) return false;
     pl->m_pad = pl->n_qtiles * pl->q_rows;
+    // the deeper ring (8 tiles) measured no better: row tiles that share K/V through L2 drift apart
+    pl->ring = 4;
+    if (const char* e = std::getenv("JK_ATTN_RING")) {
+      const int v = std::atoi(e);
+      if (v == 4 || v == 8) pl->ring = v;
+    }
   } else {
     pl->wm = pl->wn = 1;
+    pl->ring = 0;
     pl->q_rows = 1;
     pl->n_qtiles = pl->m_rows;
     pl->m_pad = pl->m_rows;

@@ -23,6 +23,7 @@ struct AttnPlan {
   int m_rows;      // T * G query rows per KV head
   int m_pad;       // n_qtiles * q_rows
   int splits;      // KV splits
+  int ring;        // K+V tiles resident in LDS per workgroup: 4 (two workgroups per CU) or 8
   size_t part_o_bytes, part_ml_bytes, total_bytes;
 };
 

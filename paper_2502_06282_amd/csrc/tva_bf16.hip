@@ -44,7 +44,6 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));  // native vecto
 constexpr int kThreads = 256;
 constexpr int kWaves = 4;       // one wave per SIMD; two workgroups share a CU
 constexpr int kWaveRows = 32;   // query rows per wave
-constexpr int kRingTiles = 4;   // K+V tiles resident in LDS (64 KB at head_dim 128)
 
 struct KParams {
   const uint16_t *q, *kc, *vc, *kt, *vt;
@@ -53,11 +52,17 @@ struct KParams {
   float* part_o;
   float2* part_ml;
   int B, T, Hkv, G, M, m_pad, max_prefix, splits, n_qtiles, total_wgs;
+  unsigned long long mg_qtiles, mg_splits, mg_hkv, mg_g;  // floor(2^32 / d) + 1: n / d == (n * mg) >> 32 for n * d < 2^32
   long long q_sb, q_st, q_sh, kc_sb, kc_sl, kc_sh, kt_sb, kt_st, kt_sh, o_sb, o_st, o_sh;
   float scale_log2;
 };
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// n / d by multiplication with the host-made constant mg = floor(2^32 / d) + 1 (exact while n * d < 2^32)
+__device__ __forceinline__ int div_mg(int n, unsigned long long mg) {
+  return (int)(((unsigned long long)(unsigned)n * mg) >> 32);
+}
 
 // max over the two half-waves (lane l and lane l^32)
 __device__ __forceinline__ float half_swap_max(float x) {
@@ -302,11 +307,13 @@ __device__ unsigned long long g_jk_ts[4096 * 8];
 #define JK_TS(i) do { } while (0)
 #endif
 
-template <int D, int WM, int WN>
+// RING: K+V tiles resident in LDS.  4 (64 KB at head_dim 128) lets two workgroups share a CU;
+// 8 keeps more rounds of transfers in flight when there is only one workgroup per CU anyway.
+template <int D, int WM, int WN, int RING>
 __global__ __launch_bounds__(kThreads, 2) void tva_bf16_kernel(const KParams p) {
   using G_ = Geo<D>;
   constexpr int DK = G_::DK, DB = G_::DB;
-  constexpr int NR = kRingTiles / WN;                // rounds resident in the ring
+  constexpr int NR = RING / WN;                      // rounds resident in the ring
   constexpr int QROWS = kWaveRows * WM;
   constexpr int TILE_BYTES = G_::TILE_BYTES;
   constexpr int STAGE_BYTES = WN * 2 * TILE_BYTES;   // one round: WN tiles of K and V
@@ -344,15 +351,37 @@ __global__ __launch_bounds__(kThreads, 2) void tva_bf16_kernel(const KParams p) 
     const int per = p.total_wgs >> 3;  // total_wgs is padded to a multiple of 8
     wid = (n & 7) * per + (n >> 3);
   }
-  const int qtile = wid % p.n_qtiles;
-  int rest = wid / p.n_qtiles;
-  const int split = rest % splits;
-  rest /= splits;
-  if (rest >= p.B * p.Hkv) return;  // padding workgroup
-  const int kv = rest % p.Hkv;
-  const int b = rest / p.Hkv;
+  int rest = div_mg(wid, p.mg_qtiles);
+  const int qtile = wid - rest * p.n_qtiles;
+  {
+    const int r2 = div_mg(rest, p.mg_splits);
+    if (r2 >= p.B * p.Hkv) return;  // padding workgroup
+  }
+  const int unit_id = div_mg(rest, p.mg_splits);  // b * Hkv + kv
+  const int split = rest - unit_id * splits;
+  const int b = div_mg(unit_id, p.mg_hkv);
+  const int kv = unit_id - b * p.Hkv;
 
-  int L = p.prefix_len[b];
+  // ---- issue the prefix-length load, then the query rows (which do not depend on it), and
+  // only then use the length: the two latencies overlap
+  const int L_raw = p.prefix_len[b];
+  WaveState<D> st;
+  const int m_row = qtile * QROWS + wm * kWaveRows + c32;  // this lane's query row
+  const bool row_ok = m_row < M;
+  const int mm = row_ok ? m_row : M - 1;
+  const int my_node = div_mg(mm, p.mg_g);
+  {
+    const uint16_t* src =
+        p.q + b * p.q_sb + my_node * p.q_st + (long long)(kv * G + (mm - my_node * G)) * p.q_sh + 8 * g;
+#pragma unroll
+    for (int ks = 0; ks < DK; ++ks) {
+      u32x4 v = *reinterpret_cast<const u32x4*>(src + ks * 16);  // clamped row: always in bounds
+      if (!row_ok) v = u32x4{0u, 0u, 0u, 0u};
+      st.q[ks] = __builtin_bit_cast(bf16x8, v);
+    }
+  }
+
+  int L = L_raw;
   L = L < 0 ? 0 : (L > p.max_prefix ? p.max_prefix : L);
   JK_TS(1);
   TileSrc ts;
@@ -360,8 +389,8 @@ __global__ __launch_bounds__(kThreads, 2) void tva_bf16_kernel(const KParams p) 
   ts.T = T;
   ts.n_ptiles = (L + kTileKeys - 1) / kTileKeys;
   const int nt = ts.n_ptiles + (T + kTileKeys - 1) / kTileKeys;
-  ts.t_begin = (int)((unsigned)split * (unsigned)nt / (unsigned)splits);  // nt < 2^25, splits <= 64
-  ts.t_end = (int)((unsigned)(split + 1) * (unsigned)nt / (unsigned)splits);
+  ts.t_begin = div_mg(split * nt, p.mg_splits);  // (split + 1) * nt * splits < 2^32: nt < 2^20
+  ts.t_end = div_mg((split + 1) * nt, p.mg_splits);
   ts.kc = p.kc + b * p.kc_sb + (long long)kv * p.kc_sh;
   ts.vc = p.vc + b * p.kc_sb + (long long)kv * p.kc_sh;
   ts.kt = p.kt + b * p.kt_sb + (long long)kv * p.kt_sh;
@@ -370,26 +399,11 @@ __global__ __launch_bounds__(kThreads, 2) void tva_bf16_kernel(const KParams p) 
   ts.kt_st = p.kt_st;
   const int n_rounds = (ts.t_end - ts.t_begin + WN - 1) / WN;
 
-  // ---- ordinary loads first (parent, Q): they are older than every K/V transfer, so the
+  // ---- ordinary loads (Q above, parent here) are older than every K/V transfer, so the
   // compiler's waits for them never include a transfer
   const bool has_tree = ts.t_end > ts.n_ptiles;
   int my_parent = -1;
   if (has_tree && tid < T) my_parent = p.parent[(long long)b * T + tid];
-
-  WaveState<D> st;
-  const int m_row = qtile * QROWS + wm * kWaveRows + c32;  // this lane's query row
-  const bool row_ok = m_row < M;
-  const int mm = row_ok ? m_row : M - 1;
-  const int my_node = mm / G;
-  {
-    const uint16_t* src = p.q + b * p.q_sb + my_node * p.q_st + (long long)(kv * G + mm % G) * p.q_sh + 8 * g;
-#pragma unroll
-    for (int ks = 0; ks < DK; ++ks) {
-      u32x4 v = *reinterpret_cast<const u32x4*>(src + ks * 16);  // clamped row: always in bounds
-      if (!row_ok) v = u32x4{0u, 0u, 0u, 0u};
-      st.q[ks] = __builtin_bit_cast(bf16x8, v);
-    }
-  }
 
   JK_TS(2);
   // ---- start the K/V stream: NR-1 rounds in flight
@@ -517,15 +531,15 @@ __global__ __launch_bounds__(kThreads, 2) void tva_bf16_kernel(const KParams p) 
   JK_TS(7);
 }
 
-template <int D, int WM, int WN>
+template <int D, int WM, int WN, int RING>
 hipError_t launch_one(const KParams& kp, hipStream_t stream) {
   using G_ = Geo<D>;
-  constexpr int RING_BYTES = kRingTiles * 2 * G_::TILE_BYTES;
+  constexpr int RING_BYTES = RING * 2 * G_::TILE_BYTES;
   constexpr int OBUF_BYTES = kWaves * kWaveRows * G_::O_LD * 4;
   constexpr int UNION_BYTES = RING_BYTES > OBUF_BYTES ? RING_BYTES : OBUF_BYTES;
   constexpr int SMEM = UNION_BYTES + kWaves * kWaveRows * 8 + JK_MAX_TREE * 16 + JK_MAX_TREE * 4;
-  static_assert(2 * SMEM <= 160 * 1024, "LDS budget: two workgroups per CU");
-  auto kern = tva_bf16_kernel<D, WM, WN>;
+  static_assert((RING == 4 ? 2 : 1) * SMEM <= 160 * 1024, "LDS budget");
+  auto kern = tva_bf16_kernel<D, WM, WN, RING>;
   static bool lds_limit_raised = false;  // idempotent, so a race between host threads is harmless
   if (!lds_limit_raised) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -568,13 +582,22 @@ hipError_t launch_tva_bf16(const AttnArgs& a, const AttnPlan& pl, hipStream_t st
   kp.kt_sb = d.kt_stride_b; kp.kt_st = d.kt_stride_t; kp.kt_sh = d.kt_stride_h;
   kp.o_sb = d.o_stride_b; kp.o_st = d.o_stride_t; kp.o_sh = d.o_stride_h;
   kp.scale_log2 = a.scale_log2;
+  auto magic = [](int d) { return (1ull << 32) / (unsigned long long)d + 1ull; };
+  kp.mg_qtiles = magic(pl.n_qtiles);
+  kp.mg_splits = magic(pl.splits);
+  kp.mg_hkv = magic(d.n_kv_heads);
+  kp.mg_g = magic(kp.G);
 
-  const int key = d.head_dim * 100 + pl.wm * 10 + pl.wn;
+  const int key = d.head_dim * 1000 + pl.wm * 100 + pl.wn * 10 + pl.ring;
   switch (key) {
-    case 12841: return launch_one<128, 4, 1>(kp, stream);
-    case 12822: return launch_one<128, 2, 2>(kp, stream);
-    case 6441: return launch_one<64, 4, 1>(kp, stream);
-    case 6422: return launch_one<64, 2, 2>(kp, stream);
+    case 128414: return launch_one<128, 4, 1, 4>(kp, stream);
+    case 128418: return launch_one<128, 4, 1, 8>(kp, stream);
+    case 128224: return launch_one<128, 2, 2, 4>(kp, stream);
+    case 128228: return launch_one<128, 2, 2, 8>(kp, stream);
+    case 64414: return launch_one<64, 4, 1, 4>(kp, stream);
+    case 64418: return launch_one<64, 4, 1, 8>(kp, stream);
+    case 64224: return launch_one<64, 2, 2, 4>(kp, stream);
+    case 64228: return launch_one<64, 2, 2, 8>(kp, stream);
     default: return hipErrorInvalidValue;
   }
 }

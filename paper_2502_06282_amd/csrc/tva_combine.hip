@@ -35,37 +35,59 @@ __global__ __launch_bounds__(256) void tva_combine_kernel(CParams p) {
   const int spad = 256 / rpw;                       // weight slots per row: 64 or more, >= splits
   const long long n_rows = (long long)p.B * p.Hkv * p.M;
 
-  // weights of every (row, split) of this workgroup: one thread each
-  {
-    const int rr = tid / spad, sp = tid % spad;
-    const long long r = (long long)blockIdx.x * rpw + rr;
-    float m = -INFINITY, l = 0.f;
-    if (r < n_rows && sp < p.splits) {
-      const long long unit = r / p.M;
-      const float2 ml = p.part_ml[(unit * p.splits + sp) * p.m_pad + (r % p.M)];
-      if (ml.y > 0.f) { m = ml.x; l = ml.y; }  // an empty split carries no weight
-    }
-    float mx = m;
-    // the (at most 64) real splits of a row sit in one wave: slots are 64-aligned
-    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
-    const float mx_use = (mx == -INFINITY) ? 0.f : mx;
-    const float w = LOG2 ? __builtin_amdgcn_exp2f(m - mx_use) : expf(m - mx_use);
-    float lw = l * w;
-    for (int o = 32; o > 0; o >>= 1) lw += __shfl_xor(lw, o);
-    s_w[tid] = w;
-    if (sp == 0) s_l[rr] = lw;
-  }
-  __syncthreads();
-
+  // this thread's output columns; its first four partial loads go out before anything else,
+  // so that their latency overlaps the weight computation below
   const int rr = tid / tpr, half = (tid % tpr) / d4n, d4 = tid % d4n;
   const long long r = (long long)blockIdx.x * rpw + rr;
   const bool live = rr < rpw && r < n_rows;
   const long long unit = live ? r / p.M : 0;
   const int m = live ? (int)(r % p.M) : 0;
   const long long row0 = unit * p.splits * p.m_pad + m;
+  float4 pre[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int sp = half + 2 * u;
+    pre[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (live && sp < p.splits)
+      pre[u] = *reinterpret_cast<const float4*>(p.part_o + (row0 + (long long)sp * p.m_pad) * p.D + 4 * d4);
+  }
+
+  // weights of every (row, split) of this workgroup: one thread each
+  {
+    const int wr = tid / spad, sp = tid % spad;
+    const long long r2 = (long long)blockIdx.x * rpw + wr;
+    float mv = -INFINITY, l = 0.f;
+    if (r2 < n_rows && sp < p.splits) {
+      const long long unit2 = r2 / p.M;
+      const float2 ml = p.part_ml[(unit2 * p.splits + sp) * p.m_pad + (r2 % p.M)];
+      if (ml.y > 0.f) { mv = ml.x; l = ml.y; }  // an empty split carries no weight
+    }
+    float mx = mv;
+    // the (at most 64) real splits of a row sit in one wave: slots are 64-aligned
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+    const float mx_use = (mx == -INFINITY) ? 0.f : mx;
+    const float w = LOG2 ? __builtin_amdgcn_exp2f(mv - mx_use) : expf(mv - mx_use);
+    float lw = l * w;
+    for (int o = 32; o > 0; o >>= 1) lw += __shfl_xor(lw, o);
+    s_w[tid] = w;
+    if (sp == 0) s_l[wr] = lw;
+  }
+  __syncthreads();
+
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
   if (live) {
-    for (int s0 = half; s0 < p.splits; s0 += 8) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int sp = half + 2 * u;
+      const float w = sp < p.splits ? s_w[rr * spad + sp] : 0.f;
+      if (w != 0.f) {  // an unused split may hold anything
+        acc.x = fmaf(pre[u].x, w, acc.x);
+        acc.y = fmaf(pre[u].y, w, acc.y);
+        acc.z = fmaf(pre[u].z, w, acc.z);
+        acc.w = fmaf(pre[u].w, w, acc.w);
+      }
+    }
+    for (int s0 = half + 8; s0 < p.splits; s0 += 8) {
       float4 o[4];
       float w[4];
 #pragma unroll
