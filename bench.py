@@ -28,9 +28,10 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0
 
-# HBM bytes per attention launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by the
-# same counters' reading for a device copy of known size (see profiles/): {workload: bytes} or None.
-MEASURED_TRAFFIC = {"c3_llama3_8b": None}
+# HBM bytes per tva_bf16_kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (KiB per
+# dispatch), each scaled by the same counter's reading for a 256 MiB device copy (factors 2.00 and
+# 1.00); source: profiles/tva_bf16_c3_hbm_traffic.md.  {workload: bytes} or None if not measured.
+MEASURED_TRAFFIC = {"c3_llama3_8b": 25639595}
 
 
 def attn_bytes(cfg) -> int:
@@ -39,44 +40,46 @@ def attn_bytes(cfg) -> int:
     return cfg.batch * (2 * L * Hkv * D * es + 2 * T * Hkv * D * es + 2 * T * Hq * D * es)
 
 
-def cpu_baseline(cfg, par, x, acc):
-    """Oracle (as is, one thread) on a bounded sample: the attention of 2 of the 8 KV
-    heads of one layer, and one acceptance walk.  Reported in the metric's unit."""
-    import numpy as np
+def cpu_baseline(cfg, par, x0, acc, budget_s=10.0):
+    """The oracle as it stands, one thread, on a bounded sample of the same workload: the
+    attention of whole layers (all heads) until about `budget_s` seconds are spent, and one
+    acceptance walk.  Reported in the metric's unit (algorithmic attention bytes per second)."""
     from oracle import accept_path as o_accept, tree_verify_attention as o_attn
+    from workloads import attention_inputs
     try:
         from threadpoolctl import threadpool_limits
     except Exception:  # pragma: no cover
         threadpool_limits = None
-    G = cfg.group
-    nkv = 2
-    sub = {"q": x["q"][:, :, : nkv * G], "k_cache": x["k_cache"][:, :, :nkv], "v_cache": x["v_cache"][:, :, :nkv],
-           "k_tree": x["k_tree"][:, :, :nkv], "v_tree": x["v_tree"][:, :, :nkv]}
 
     def run():
+        t_attn, n_layers = 0.0, 0
+        while t_attn < budget_s and n_layers < 32:
+            x = x0 if n_layers == 0 else attention_inputs(cfg, layer=n_layers)   # generation is not timed
+            t0 = time.perf_counter()
+            o_attn(**x, parent=par, prefix_len=[cfg.prefix_len] * cfg.batch)
+            t_attn += time.perf_counter() - t0
+            n_layers += 1
         t0 = time.perf_counter()
-        o_attn(**sub, parent=par, prefix_len=[cfg.prefix_len] * cfg.batch)
-        t1 = time.perf_counter()
-        o_accept(acc["tokens"][0], par[0], acc["logits"][0], cfg.mode,
-                 None if acc["draft_probs"] is None else acc["draft_probs"][0],
-                 None if acc["uniforms"] is None else acc["uniforms"][0])
-        t2 = time.perf_counter()
-        return t1 - t0, t2 - t1
+        for b in range(cfg.batch):
+            o_accept(acc["tokens"][b], par[b], acc["logits"][b], cfg.mode,
+                     None if acc["draft_probs"] is None else acc["draft_probs"][b],
+                     None if acc["uniforms"] is None else acc["uniforms"][b])
+        return t_attn, n_layers, time.perf_counter() - t0
 
     if threadpool_limits is not None:
         with threadpool_limits(limits=1):
-            t_attn, t_acc = run()
+            t_attn, n_layers, t_acc = run()
     else:
-        t_attn, t_acc = run()
-    frac = nkv / cfg.n_kv_heads
+        t_attn, n_layers, t_acc = run()
     return {
-        "value": attn_bytes(cfg) * frac / t_attn / 1e9,
+        "value": round(attn_bytes(cfg) * n_layers / t_attn / 1e9, 4),
         "unit": "GB/s",
         "cores": 1,
         "kind": "oracle",
-        "sample": f"attention oracle on {nkv} of {cfg.n_kv_heads} KV heads of one layer ({t_attn:.2f} s) "
-                  f"+ one acceptance walk ({t_acc:.2f} s)",
-        "accept_nodes_per_s": cfg.n_tree / t_acc,
+        "sample": f"fp64 NumPy oracle, attention of {n_layers} full layers ({t_attn:.1f} s) "
+                  f"+ one acceptance walk ({t_acc * 1e3:.1f} ms)",
+        "attention_us_per_call": round(t_attn / n_layers * 1e6, 1),
+        "accept_nodes_per_s": round(cfg.batch * cfg.n_tree / t_acc, 1),
     }
 
 
@@ -183,6 +186,28 @@ def main():
     bytes_call = attn_bytes(cfg)
     gbps = bytes_call / (per_call_us * 1e-6) / 1e9
 
+    # ceiling for one layer's K/V on this machine: a kernel that only streams as many bytes as one
+    # layer's K and V prefix (16.8 MB), from its own ring of buffers larger than the Infinity Cache
+    sink = torch.zeros(4, dtype=torch.int32, device=dev)
+    probe_bytes = 2 * layers[0]["k_cache"].numel() * layers[0]["k_cache"].element_size()
+    probe_ring = [torch.full((probe_bytes,), 1, dtype=torch.uint8, device=dev) for _ in range(args.layers)]
+    def stream_pass():
+        for buf in probe_ring:
+            jk.stream_read_probe(buf, sink)
+    stream_pass()
+    torch.cuda.synchronize()
+    g_probe = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g_probe, stream=torch.cuda.Stream()):
+        stream_pass()
+    g_probe.replay()
+    torch.cuda.synchronize()
+    es0, es1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    es0.record()
+    for _ in range(5):
+        g_probe.replay()
+    es1.record()
+    torch.cuda.synchronize()
+    probe_us = es0.elapsed_time(es1) * 1e3 / (5 * args.layers)
     for _ in range(args.copy_calibration):
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)
@@ -212,6 +237,9 @@ def main():
         "accept_us_per_call": round(t_acc_ms * 1e3, 2),
         "accept_nodes_per_s": round(cfg.batch * cfg.n_tree / (t_acc_ms * 1e-3), 1),
         "accept_len": [int(v) for v in res[1].cpu().tolist()],
+        "stream_read_probe": {"bytes_per_launch": probe_bytes, "us_per_launch": round(probe_us, 3),
+                              "GBps": round(probe_bytes / (probe_us * 1e-6) / 1e9, 1),
+                              "note": "pure 128-bit read kernel, one launch per 16.8 MB buffer of a 32-buffer ring, HIP-graph replay"},
         "roofline": {"bound": "hbm", "achieved": round(gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(gbps / HBM_PEAK_GBPS, 4), "traffic": MEASURED_TRAFFIC.get(cfg.name),
                      "kernel": "tva_bf16_kernel (+ tva_combine_kernel): time per jk_tree_verify_attention call",

@@ -169,6 +169,13 @@ jk_status jk_accept_path(int32_t batch, int32_t n_tree, int32_t vocab, int32_t m
  * a null or misaligned pointer. */
 jk_status jk_workspace_init(void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Measurement aid, not part of the method: enqueues a kernel that only streams `bytes`
+ * bytes (device, 16-byte aligned) with 128-bit loads.  Timing it gives the ceiling that an
+ * HBM-bound call of the same size (for instance one attention layer's K/V) can be compared
+ * with on the machine at hand.  `sink` is a device word that is written only if the data
+ * hash to one particular value. */
+jk_status jk_stream_read_probe(const void* src, size_t bytes, void* sink, void* hip_stream);
+
 /* Host-side check of a tree held in host memory: JK_OK, JK_ERR_BAD_TREE
  * (some parent[i] outside [-1, i-1]) or JK_ERR_INVALID_ARG (null, n outside
  * [1, JK_MAX_TREE]). */

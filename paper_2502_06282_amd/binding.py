@@ -39,7 +39,7 @@ class AttnDesc(ctypes.Structure):
 _lib = None
 
 EXPORTS = ("jk_tree_verify_attention_workspace", "jk_tree_verify_attention", "jk_accept_path_workspace",
-           "jk_accept_path", "jk_workspace_init", "jk_validate_tree", "jk_status_string", "jk_version")
+           "jk_accept_path", "jk_workspace_init", "jk_stream_read_probe", "jk_validate_tree", "jk_status_string", "jk_version")
 
 
 def library_path() -> str:
@@ -67,6 +67,8 @@ def lib() -> ctypes.CDLL:
                                      vp, vp, sz, vp]
         l.jk_workspace_init.restype = i32
         l.jk_workspace_init.argtypes = [vp, sz, vp]
+        l.jk_stream_read_probe.restype = i32
+        l.jk_stream_read_probe.argtypes = [vp, sz, vp, vp]
         l.jk_validate_tree.restype = i32
         l.jk_validate_tree.argtypes = [ctypes.POINTER(ctypes.c_int32), i32]
         l.jk_status_string.restype = ctypes.c_char_p
@@ -160,6 +162,13 @@ def tree_verify_attention(q, k_cache, v_cache, k_tree, v_tree, parent, prefix_le
 
 def accept_path_workspace(batch: int, n_tree: int, vocab: int, mode: int) -> int:
     return int(lib().jk_accept_path_workspace(batch, n_tree, vocab, mode))
+
+
+def stream_read_probe(src, sink, stream=None) -> None:
+    """jk_stream_read_probe over the whole tensor `src` (measurement aid)."""
+    st = lib().jk_stream_read_probe(_ptr(src), src.numel() * src.element_size(), _ptr(sink), _stream_handle(stream))
+    if st != 0:
+        raise JakiroError(st, "jk_stream_read_probe")
 
 
 def workspace_init(workspace, stream=None) -> None:

@@ -333,6 +333,27 @@ hipError_t launch_accept_coop(const AcceptArgs& a, void* coop_ws, int W, int sli
   return hipGetLastError();
 }
 
+// Calibration: a pure 128-bit streaming read of `bytes` bytes (nothing is computed or written
+// unless the data happen to hash to a magic value), the ceiling any HBM-bound kernel of the same
+// size can be compared with.
+typedef unsigned int probe_u32x4 __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(256) void stream_read_kernel(const probe_u32x4* __restrict__ src, size_t n_chunks,
+                                                          unsigned* sink) {
+  probe_u32x4 acc = {0u, 0u, 0u, 0u};
+  const size_t stride = (size_t)gridDim.x * 256;
+#pragma unroll 4
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n_chunks; i += stride) acc += src[i];
+  if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9E3779B9u) sink[0] = acc.x;
+}
+hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, hipStream_t stream) {
+  const size_t n = bytes / 16;
+  if (n == 0) return hipSuccess;
+  const unsigned grid = (unsigned)((n + 1023) / 1024 < 16384 ? (n + 1023) / 1024 : 16384);  // ~4 chunks per thread
+  hipLaunchKernelGGL(stream_read_kernel, dim3(grid), dim3(256), 0, stream, static_cast<const probe_u32x4*>(src), n,
+                     static_cast<unsigned*>(sink));
+  return hipGetLastError();
+}
+
 // zero fill as a kernel (safe inside HIP-graph capture, unlike a memset node)
 __global__ void zero_fill_kernel(unsigned long long* p, size_t n) {
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0ull;

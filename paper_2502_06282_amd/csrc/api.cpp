@@ -213,6 +213,12 @@ jk_status jk_workspace_init(void* workspace, size_t workspace_bytes, void* hip_s
              : JK_ERR_HIP;
 }
 
+jk_status jk_stream_read_probe(const void* src, size_t bytes, void* sink, void* hip_stream) {
+  if (!src || !sink || reinterpret_cast<uintptr_t>(src) % 16) return JK_ERR_INVALID_ARG;
+  return launch_stream_read(src, bytes, sink, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? JK_OK
+                                                                                                  : JK_ERR_HIP;
+}
+
 jk_status jk_validate_tree(const int32_t* parent_host, int32_t n_tree) {
   if (!parent_host || n_tree < 1 || n_tree > JK_MAX_TREE) return JK_ERR_INVALID_ARG;
   for (int32_t i = 0; i < n_tree; ++i)

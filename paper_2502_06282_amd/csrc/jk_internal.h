@@ -62,5 +62,6 @@ size_t accept_coop_bytes(int batch);
 bool accept_coop_plan(int batch, int vocab, int cus, int* W, int* slice);
 hipError_t launch_accept_coop(const AcceptArgs& a, void* coop_ws, int W, int slice, hipStream_t stream);
 hipError_t launch_zero_fill(void* p, size_t bytes, hipStream_t stream);
+hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, hipStream_t stream);
 
 }  // namespace jk
