@@ -88,7 +88,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--layers", type=int, default=32)
+    ap.add_argument("--layers", type=int, default=0, help="attention calls (distinct KV buffers) per step; "
+                    "default: the model's depth (32; 40 for c4; 2 x 537 MB for c5)")
     ap.add_argument("--workload", default="c3_llama3_8b")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="issue every library call from Python instead of "
@@ -107,6 +108,8 @@ def main():
 
     jk.lib()  # fail loudly if the HIP library is missing
     cfg = CONFIGS[args.workload]
+    if args.layers <= 0:
+        args.layers = {"c4_llama2_13b": 40, "c5_llama2_70b": 2, "c1_tiny": 32}.get(cfg.name, 32)
     dev = torch.device("cuda:0")
     tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
     par = tree_for_config(cfg)
@@ -234,6 +237,8 @@ def main():
         "percent_of_hbm_peak": round(100.0 * gbps / HBM_PEAK_GBPS, 2),
         "verify_steps_per_s": round(1e3 / ms_per_step, 1),
         "attention_us_per_call": round(per_call_us, 3),
+        "attention_TFLOPs": round(4.0 * cfg.batch * cfg.n_tree * cfg.n_q_heads * (cfg.prefix_len + cfg.n_tree)
+                                  * cfg.head_dim / (per_call_us * 1e-6) / 1e12, 1),
         "accept_us_per_call": round(t_acc_ms * 1e3, 2),
         "accept_nodes_per_s": round(cfg.batch * cfg.n_tree / (t_acc_ms * 1e-3), 1),
         "accept_len": [int(v) for v in res[1].cpu().tolist()],

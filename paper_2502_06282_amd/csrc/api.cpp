@@ -63,13 +63,13 @@ bool make_attn_plan(const jk_attn_desc& d, int max_prefix_len, AttnPlan* pl) {
       const long long wgs = units * n_qtiles;
       const long long s_full = (slots + wgs - 1) / wgs;  // splits that fill every resident slot
       const int max_by_tiles = n_tiles / (2 * wn) > 0 ? n_tiles / (2 * wn) : 1;  // >= 2 rounds per split
-      for (int shrink = 1; shrink <= 1; shrink *= 2) {
-        long long s = (s_full + shrink - 1) / shrink;
+      {
+        long long s = s_full;
         if (s > max_by_tiles) s = max_by_tiles;
         if (s > kMaxSplits) s = kMaxSplits;
         if (forced_s >= 1 && forced_s <= kMaxSplits) s = forced_s;
         // partial outputs are written, flushed at the kernel boundary and read back: weigh them double
-        const double partial = s > 1 ? 4.0 * s * pl->m_rows * d.head_dim * 4.0 : 0.0;
+        const double partial = s > 1 ? 4.0 * s * pl->m_rows * d.head_dim * 2.0 : 0.0;
         // one workgroup per CU already reaches most of the throughput; the second hides latencies
         const double fill = 0.5 + 0.5 * (double)(wgs * s < slots ? wgs * s : slots) / slots;
         const double cost = (kv_bytes * (1.0 + 0.25 * (n_qtiles - 1)) + partial) / fill;
@@ -82,15 +82,8 @@ bool make_attn_plan(const jk_attn_desc& d, int max_prefix_len, AttnPlan* pl) {
     }
     if (!have) return false;
     pl->m_pad = pl->n_qtiles * pl->q_rows;
-    // the deeper ring (8 tiles) measured no better: row tiles that share K/V through L2 drift apart
-    pl->ring = 4;
-    if (const char* e = std::getenv("JK_ATTN_RING")) {
-      const int v = std::atoi(e);
-      if (v == 4 || v == 8) pl->ring = v;
-    }
   } else {
     pl->wm = pl->wn = 1;
-    pl->ring = 0;
     pl->q_rows = 1;
     pl->n_qtiles = pl->m_rows;
     pl->m_pad = pl->m_rows;
@@ -102,7 +95,7 @@ bool make_attn_plan(const jk_attn_desc& d, int max_prefix_len, AttnPlan* pl) {
   auto up = [](size_t x) { return (x + 255) / 256 * 256; };
   const size_t rows = (size_t)units * pl->splits * pl->m_pad;
   const bool need_parts = (d.dtype == JK_F32) || pl->splits > 1;
-  pl->part_o_bytes = need_parts ? up(rows * d.head_dim * sizeof(float)) : 0;
+  pl->part_o_bytes = need_parts ? up(rows * d.head_dim * (d.dtype == JK_BF16 ? 2 : sizeof(float))) : 0;
   pl->part_ml_bytes = need_parts ? up(rows * sizeof(float2)) : 0;
   pl->total_bytes = pl->part_o_bytes + pl->part_ml_bytes;
   if (pl->total_bytes == 0) pl->total_bytes = 256;  // never ask the caller for a zero-byte buffer

@@ -23,7 +23,6 @@ struct AttnPlan {
   int m_rows;      // T * G query rows per KV head
   int m_pad;       // n_qtiles * q_rows
   int splits;      // KV splits
-  int ring;        // K+V tiles resident in LDS per workgroup: 4 (two workgroups per CU) or 8
   size_t part_o_bytes, part_ml_bytes, total_bytes;
 };
 
@@ -34,7 +33,7 @@ struct AttnArgs {
   const int32_t* parent;
   const int32_t* prefix_len;
   void* out;
-  float* part_o;    // [B*Hkv][splits][m_pad][D]
+  float* part_o;    // [B*Hkv][splits][m_pad][D], fp32 (fp32 path) or bf16 (bf16 path)
   float2* part_ml;  // [B*Hkv][splits][m_pad]  (running max in log2 units, sum)
   jk_attn_desc d;
   int max_prefix_len;

@@ -44,6 +44,7 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));  // native vecto
 constexpr int kThreads = 256;
 constexpr int kWaves = 4;       // one wave per SIMD; two workgroups share a CU
 constexpr int kWaveRows = 32;   // query rows per wave
+constexpr int kRingTiles = 4;   // K+V tiles resident in LDS (64 KB at head_dim 128): two workgroups fit a CU
 
 struct KParams {
   const uint16_t *q, *kc, *vc, *kt, *vt;
@@ -207,28 +208,34 @@ struct WaveState {
   float m, l;
 };
 
-// One 32-key tile against the wave's 32 query rows.  mask_mode: 0 none, 1 ragged prefix
-// tail (keys >= nvalid hidden), 2 tree tile (bits = visibility of the tile's 32 keys).
+// S^T = K . Q^T of one 32-key tile against the wave's 32 query rows.
 template <int D>
-__device__ __forceinline__ void compute_tile(WaveState<D>& st, const unsigned char* kt_s,
-                                             const unsigned char* vt_s, int mask_mode, int nvalid,
-                                             unsigned int bits, float scale_log2, int lane) {
+__device__ __forceinline__ floatx16 qk_tile(const WaveState<D>& st, const unsigned char* kt_s, int lane) {
   using G_ = Geo<D>;
-  constexpr int DK = G_::DK, DB = G_::DB;
   const int c32 = lane & 31, g = lane >> 5;
-  // ---- S^T = K . Q^T
   floatx16 sacc;
 #pragma unroll
   for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
-  {
-    const unsigned char* krow = kt_s + c32 * G_::ROW_BYTES;
-    const int x = G_::kswz(c32);
+  const unsigned char* krow = kt_s + c32 * G_::ROW_BYTES;
+  const int x = G_::kswz(c32);
 #pragma unroll
-    for (int ks = 0; ks < DK; ++ks) {
-      const bf16x8 a = *reinterpret_cast<const bf16x8*>(krow + (((2 * ks + g) ^ x) << 4));
-      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, st.q[ks], sacc, 0, 0, 0);
-    }
+  for (int ks = 0; ks < G_::DK; ++ks) {
+    const bf16x8 a = *reinterpret_cast<const bf16x8*>(krow + (((2 * ks + g) ^ x) << 4));
+    sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, st.q[ks], sacc, 0, 0, 0);
   }
+  return sacc;
+}
+
+// Masking, online softmax and O^T += V^T . P^T for one tile whose scores are in sacc.
+// mask_mode: 0 none, 1 ragged prefix tail (keys >= nvalid hidden), 2 tree tile (bits =
+// visibility of the tile's 32 keys).
+template <int D>
+__device__ __forceinline__ void softmax_pv_tile(WaveState<D>& st, floatx16 sacc, const unsigned char* vt_s,
+                                                int mask_mode, int nvalid, unsigned int bits, float scale_log2,
+                                                int lane) {
+  using G_ = Geo<D>;
+  constexpr int DB = G_::DB;
+  const int g = lane >> 5;
   // ---- masks: register i of a lane is key 8*(i/4) + 4*g + i%4 of the tile
   if (mask_mode == 2) {
 #pragma unroll
@@ -307,13 +314,11 @@ __device__ unsigned long long g_jk_ts[4096 * 8];
 #define JK_TS(i) do { } while (0)
 #endif
 
-// RING: K+V tiles resident in LDS.  4 (64 KB at head_dim 128) lets two workgroups share a CU;
-// 8 keeps more rounds of transfers in flight when there is only one workgroup per CU anyway.
-template <int D, int WM, int WN, int RING>
+template <int D, int WM, int WN>
 __global__ __launch_bounds__(kThreads, 2) void tva_bf16_kernel(const KParams p) {
   using G_ = Geo<D>;
   constexpr int DK = G_::DK, DB = G_::DB;
-  constexpr int NR = RING / WN;                      // rounds resident in the ring
+  constexpr int NR = kRingTiles / WN;                // rounds resident in the ring
   constexpr int QROWS = kWaveRows * WM;
   constexpr int TILE_BYTES = G_::TILE_BYTES;
   constexpr int STAGE_BYTES = WN * 2 * TILE_BYTES;   // one round: WN tiles of K and V
@@ -381,38 +386,62 @@ __global__ __launch_bounds__(kThreads, 2) void tva_bf16_kernel(const KParams p) 
     }
   }
 
-  int L = L_raw;
-  L = L < 0 ? 0 : (L > p.max_prefix ? p.max_prefix : L);
-  JK_TS(1);
+  // ---- the parent array as well (4 bytes per thread, needed only by workgroups that reach tree
+  // tiles, but loading it now keeps every ordinary load older than the K/V transfers: the
+  // compiler's waits for ordinary loads then never include a transfer)
+  int my_parent = -1;
+  if (tid < T) my_parent = p.parent[(long long)b * T + tid];
+
+  // ---- tile range of this split.  The prefix length is still on its way: start the K/V
+  // stream on the assumption that it equals the host's upper bound (the usual case); if it
+  // turns out shorter, the speculative transfers are waited for and everything is redone.
   TileSrc ts;
-  ts.L = L;
   ts.T = T;
-  ts.n_ptiles = (L + kTileKeys - 1) / kTileKeys;
-  const int nt = ts.n_ptiles + (T + kTileKeys - 1) / kTileKeys;
-  ts.t_begin = div_mg(split * nt, p.mg_splits);  // (split + 1) * nt * splits < 2^32: nt < 2^20
-  ts.t_end = div_mg((split + 1) * nt, p.mg_splits);
   ts.kc = p.kc + b * p.kc_sb + (long long)kv * p.kc_sh;
   ts.vc = p.vc + b * p.kc_sb + (long long)kv * p.kc_sh;
   ts.kt = p.kt + b * p.kt_sb + (long long)kv * p.kt_sh;
   ts.vt = p.vt + b * p.kt_sb + (long long)kv * p.kt_sh;
   ts.kc_sl = p.kc_sl;
   ts.kt_st = p.kt_st;
-  const int n_rounds = (ts.t_end - ts.t_begin + WN - 1) / WN;
-
-  // ---- ordinary loads (Q above, parent here) are older than every K/V transfer, so the
-  // compiler's waits for them never include a transfer
-  const bool has_tree = ts.t_end > ts.n_ptiles;
-  int my_parent = -1;
-  if (has_tree && tid < T) my_parent = p.parent[(long long)b * T + tid];
-
-  JK_TS(2);
-  // ---- start the K/V stream: NR-1 rounds in flight
+  const int n_ttiles = (T + kTileKeys - 1) / kTileKeys;
+  auto set_range = [&](int len) {
+    ts.L = len;
+    ts.n_ptiles = (len + kTileKeys - 1) / kTileKeys;
+    const int nt = ts.n_ptiles + n_ttiles;
+    ts.t_begin = div_mg(split * nt, p.mg_splits);  // (split + 1) * nt * splits < 2^32: nt < 2^20
+    ts.t_end = div_mg((split + 1) * nt, p.mg_splits);
+  };
   const unsigned ring_addr = (unsigned)(size_t)LDS_PTR(unsigned char, ring);
   LaneChunks<D> lc;
   lane_chunks<D>(lc, wave, lane, ts);
+
+  set_range(p.max_prefix);
+  int n_rounds = (ts.t_end - ts.t_begin + WN - 1) / WN;
+  int n_spec = 0;  // rounds already issued, all of them full prefix tiles under the assumption
 #pragma unroll
   for (int r = 0; r < NR - 1; ++r)
-    if (r < n_rounds) dma_round<D, WN>(r, ts, lc, ring_addr + r * STAGE_BYTES);
+    if (n_spec == r && r < n_rounds && (ts.t_begin + (r + 1) * WN) * kTileKeys <= p.max_prefix) {
+      dma_round<D, WN>(r, ts, lc, ring_addr + r * STAGE_BYTES);
+      n_spec = r + 1;
+    }
+  JK_TS(2);
+
+  int L = L_raw;
+  L = L < 0 ? 0 : (L > p.max_prefix ? p.max_prefix : L);
+  JK_TS(1);
+  if (L != p.max_prefix) {  // uniform over the workgroup
+    if (n_spec > 0) {
+      wait_dma<DMA_PER_ROUND>(0);  // the ring must be quiet before the same slots are filled again
+      __syncthreads();
+      n_spec = 0;
+    }
+    set_range(L);
+    n_rounds = (ts.t_end - ts.t_begin + WN - 1) / WN;
+  }
+  const bool has_tree = ts.t_end > ts.n_ptiles;
+#pragma unroll
+  for (int r = 0; r < NR - 1; ++r)
+    if (r >= n_spec && r < n_rounds) dma_round<D, WN>(r, ts, lc, ring_addr + r * STAGE_BYTES);
 
   JK_TS(3);
   // ---- ancestor sets (only workgroups that reach tree tiles need them)
@@ -439,6 +468,23 @@ __global__ __launch_bounds__(kThreads, 2) void tva_bf16_kernel(const KParams p) 
   st.m = -INFINITY;
   st.l = 0.f;
 
+  // tile of this wave in round r: mask mode and LDS addresses
+  auto tile_of = [&](int r, int& t, int& mode, int& nvalid, unsigned int& bits, const unsigned char*& kt_s) {
+    t = ts.t_begin + r * WN + wn;
+    mode = 0;
+    nvalid = kTileKeys;
+    bits = 0;
+    if (t >= ts.n_ptiles) {
+      const int tt = t - ts.n_ptiles;
+      mode = 2;
+      if (t < ts.t_end) bits = (unsigned int)(anc[2 * my_node + (tt >> 1)] >> ((tt & 1) * 32));
+    } else {
+      nvalid = L - t * kTileKeys;
+      mode = nvalid < kTileKeys ? 1 : 0;
+    }
+    kt_s = ring + (r % NR) * STAGE_BYTES + wn * 2 * TILE_BYTES;
+  };
+
   // ---- main loop.  Round r lives in ring slot r % NR.  Before the barrier a wave waits for
   // its own transfers of round r; after the barrier every wave's have landed, and every wave
   // has finished round r-1, whose slot is therefore free for round r+NR-1.
@@ -449,20 +495,13 @@ __global__ __launch_bounds__(kThreads, 2) void tva_bf16_kernel(const KParams p) 
     if (r == 0) JK_TS(4);
     if (r + NR - 1 < n_rounds)
       dma_round<D, WN>(r + NR - 1, ts, lc, ring_addr + ((r + NR - 1) % NR) * STAGE_BYTES);
-    const int t = ts.t_begin + r * WN + wn;
+    int t, mode, nvalid;
+    unsigned int bits;
+    const unsigned char* kt_s;
+    tile_of(r, t, mode, nvalid, bits, kt_s);
     if (t < ts.t_end) {
-      int mode = 0, nvalid = kTileKeys;
-      unsigned int bits = 0;
-      if (t >= ts.n_ptiles) {
-        const int tt = t - ts.n_ptiles;
-        mode = 2;
-        bits = (unsigned int)(anc[2 * my_node + (tt >> 1)] >> ((tt & 1) * 32));
-      } else {
-        nvalid = L - t * kTileKeys;
-        mode = nvalid < kTileKeys ? 1 : 0;
-      }
-      const unsigned char* kt_s = ring + (r % NR) * STAGE_BYTES + wn * 2 * TILE_BYTES;
-      compute_tile<D>(st, kt_s, kt_s + TILE_BYTES, mode, nvalid, bits, scale_log2, lane);
+      const floatx16 sacc = qk_tile<D>(st, kt_s, lane);
+      softmax_pv_tile<D>(st, sacc, kt_s + TILE_BYTES, mode, nvalid, bits, scale_log2, lane);
     }
   }
   JK_TS(5);
@@ -523,23 +562,33 @@ __global__ __launch_bounds__(kThreads, 2) void tva_bf16_kernel(const KParams p) 
       pk.y = __builtin_bit_cast(unsigned int, hi);
       *reinterpret_cast<uint2*>(dst) = pk;
     } else {
+      // partial output in bf16 (the running max and sum stay fp32): the partials are written,
+      // flushed and read back once per split, and are the largest avoidable traffic of a call
       const long long prow = (unit * splits + split) * p.m_pad + m;
-      *reinterpret_cast<float4*>(p.part_o + prow * D + 4 * d4) = acc;
+      bf16x2 lo, hi;
+      lo[0] = (__bf16)acc.x;
+      lo[1] = (__bf16)acc.y;
+      hi[0] = (__bf16)acc.z;
+      hi[1] = (__bf16)acc.w;
+      uint2 pk;
+      pk.x = __builtin_bit_cast(unsigned int, lo);
+      pk.y = __builtin_bit_cast(unsigned int, hi);
+      *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(p.part_o) + prow * D + 4 * d4) = pk;
       if (d4 == 0) p.part_ml[prow] = make_float2(mx, lsum);
     }
   }
   JK_TS(7);
 }
 
-template <int D, int WM, int WN, int RING>
+template <int D, int WM, int WN>
 hipError_t launch_one(const KParams& kp, hipStream_t stream) {
   using G_ = Geo<D>;
-  constexpr int RING_BYTES = RING * 2 * G_::TILE_BYTES;
+  constexpr int RING_BYTES = kRingTiles * 2 * G_::TILE_BYTES;
   constexpr int OBUF_BYTES = kWaves * kWaveRows * G_::O_LD * 4;
   constexpr int UNION_BYTES = RING_BYTES > OBUF_BYTES ? RING_BYTES : OBUF_BYTES;
   constexpr int SMEM = UNION_BYTES + kWaves * kWaveRows * 8 + JK_MAX_TREE * 16 + JK_MAX_TREE * 4;
-  static_assert((RING == 4 ? 2 : 1) * SMEM <= 160 * 1024, "LDS budget");
-  auto kern = tva_bf16_kernel<D, WM, WN, RING>;
+  static_assert(2 * SMEM <= 160 * 1024, "LDS budget: two workgroups per CU");
+  auto kern = tva_bf16_kernel<D, WM, WN>;
   static bool lds_limit_raised = false;  // idempotent, so a race between host threads is harmless
   if (!lds_limit_raised) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -588,16 +637,12 @@ hipError_t launch_tva_bf16(const AttnArgs& a, const AttnPlan& pl, hipStream_t st
   kp.mg_hkv = magic(d.n_kv_heads);
   kp.mg_g = magic(kp.G);
 
-  const int key = d.head_dim * 1000 + pl.wm * 100 + pl.wn * 10 + pl.ring;
+  const int key = d.head_dim * 100 + pl.wm * 10 + pl.wn;
   switch (key) {
-    case 128414: return launch_one<128, 4, 1, 4>(kp, stream);
-    case 128418: return launch_one<128, 4, 1, 8>(kp, stream);
-    case 128224: return launch_one<128, 2, 2, 4>(kp, stream);
-    case 128228: return launch_one<128, 2, 2, 8>(kp, stream);
-    case 64414: return launch_one<64, 4, 1, 4>(kp, stream);
-    case 64418: return launch_one<64, 4, 1, 8>(kp, stream);
-    case 64224: return launch_one<64, 2, 2, 4>(kp, stream);
-    case 64228: return launch_one<64, 2, 2, 8>(kp, stream);
+    case 12841: return launch_one<128, 4, 1>(kp, stream);
+    case 12822: return launch_one<128, 2, 2>(kp, stream);
+    case 6441: return launch_one<64, 4, 1>(kp, stream);
+    case 6422: return launch_one<64, 2, 2>(kp, stream);
     default: return hipErrorInvalidValue;
   }
 }

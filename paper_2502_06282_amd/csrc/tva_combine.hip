@@ -19,6 +19,17 @@ struct CParams {
   long long o_sb, o_st, o_sh;
 };
 
+// Four consecutive columns of a partial output row: fp32 partials (fp32 path) or bf16 (bf16 path).
+template <bool BF16>
+__device__ __forceinline__ float4 load_part4(const float* part_o, long long row, int D, int d4) {
+  if (BF16) {
+    const uint2 v = *reinterpret_cast<const uint2*>(reinterpret_cast<const uint16_t*>(part_o) + row * D + 4 * d4);
+    return make_float4(__uint_as_float(v.x << 16), __uint_as_float(v.x & 0xffff0000u), __uint_as_float(v.y << 16),
+                       __uint_as_float(v.y & 0xffff0000u));
+  }
+  return *reinterpret_cast<const float4*>(part_o + row * D + 4 * d4);
+}
+
 // A workgroup merges up to 4 consecutive query rows.  A row is
 // covered by two groups of D/4 threads; each thread sums every other split for four output
 // columns with up to four loads in flight, and the two halves meet in LDS.  LOG2: running
@@ -49,7 +60,7 @@ __global__ __launch_bounds__(256) void tva_combine_kernel(CParams p) {
     const int sp = half + 2 * u;
     pre[u] = make_float4(0.f, 0.f, 0.f, 0.f);
     if (live && sp < p.splits)
-      pre[u] = *reinterpret_cast<const float4*>(p.part_o + (row0 + (long long)sp * p.m_pad) * p.D + 4 * d4);
+      pre[u] = load_part4<OUT_BF16>(p.part_o, row0 + (long long)sp * p.m_pad, p.D, d4);
   }
 
   // weights of every (row, split) of this workgroup: one thread each
@@ -96,7 +107,7 @@ __global__ __launch_bounds__(256) void tva_combine_kernel(CParams p) {
         w[u] = sp < p.splits ? s_w[rr * spad + sp] : 0.f;
         o[u] = make_float4(0.f, 0.f, 0.f, 0.f);
         if (w[u] != 0.f)
-          o[u] = *reinterpret_cast<const float4*>(p.part_o + (row0 + (long long)sp * p.m_pad) * p.D + 4 * d4);
+          o[u] = load_part4<OUT_BF16>(p.part_o, row0 + (long long)sp * p.m_pad, p.D, d4);
       }
 #pragma unroll
       for (int u = 0; u < 4; ++u) {

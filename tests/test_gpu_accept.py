@@ -153,6 +153,13 @@ def test_c3_sample_full_vocab():
     assert _compare(a, par, "sample") == 0, "default seed must be admissible (margin > 1e-9)"
 
 
+def test_c5_sample_batched_full_vocab():
+    cfg = CONFIGS["c5_llama2_70b"]
+    par = tree_for_config(cfg)
+    a = accept_inputs(cfg, par)
+    assert _compare(a, par, "sample") == 0
+
+
 def test_argument_errors():
     dev = torch.device("cuda")
     tok = torch.zeros(1, 4, dtype=torch.int32, device=dev)

@@ -193,6 +193,41 @@ def test_c3_full_size_sampled_rows():
         assert err <= BF16_TOL and err <= 1.5e-2 * np.abs(ref).max()
 
 
+def _sampled_unit_check(cfg, x, par, got, n_samples, seed):
+    """Oracle on sampled (sequence, KV head) units of a full-size result."""
+    from oracle import tree_verify_attention as oracle_attention
+    rng = np.random.default_rng(seed)
+    G = cfg.group
+    for _ in range(n_samples):
+        b = int(rng.integers(cfg.batch)); kv = int(rng.integers(cfg.n_kv_heads))
+        hs = slice(kv * G, kv * G + G)
+        sub = {"q": x["q"][b:b + 1, :, hs], "k_cache": x["k_cache"][b:b + 1, :, kv:kv + 1],
+               "v_cache": x["v_cache"][b:b + 1, :, kv:kv + 1], "k_tree": x["k_tree"][b:b + 1, :, kv:kv + 1],
+               "v_tree": x["v_tree"][b:b + 1, :, kv:kv + 1]}
+        ref = oracle_attention(**sub, parent=par[b:b + 1], prefix_len=[cfg.prefix_len])
+        err = np.abs(got[b, :, hs] - ref[0]).max()
+        assert err <= BF16_TOL and err <= 1.5e-2 * np.abs(ref).max(), (b, kv, err)
+
+
+def test_c4_full_size_sampled_units():
+    """Config 4 (LLaMA2-13B shape, batch 4 with a tree per sequence), one layer at full size."""
+    cfg = CONFIGS["c4_llama2_13b"]
+    par = tree_for_config(cfg)
+    x = attention_inputs(cfg, scale_mult=np.sqrt(128.0))
+    got = gpu_attention(x, par, [cfg.prefix_len] * cfg.batch, "bf16")
+    _sampled_unit_check(cfg, x, par, got, 8, 4)
+
+
+def test_c5_full_size_sampled_units():
+    """Config 5 (LLaMA2-70B shape: batch 8, 16384-token prefix, 100-node trees, group 8) at full size."""
+    cfg = CONFIGS["c5_llama2_70b"]
+    par = tree_for_config(cfg)
+    x = attention_inputs(cfg, scale_mult=np.sqrt(128.0))
+    got = gpu_attention(x, par, [cfg.prefix_len] * cfg.batch, "bf16")
+    assert np.isfinite(got).all()
+    _sampled_unit_check(cfg, x, par, got, 2, 5)
+
+
 def test_argument_errors():
     import paper_2502_06282_amd as jk
     dev = torch.device("cuda")
