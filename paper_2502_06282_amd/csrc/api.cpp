@@ -41,43 +41,48 @@ bool make_attn_plan(const jk_attn_desc& d, int max_prefix_len, AttnPlan* pl) {
   pl->m_rows = d.n_tree * G;
   const long long units = (long long)d.batch * d.n_kv_heads;
   if (d.dtype == JK_BF16) {
-    // Candidates: 4x1 or 2x2 waves (32-row blocks x key interleave) per workgroup; two
-    // workgroups fit a CU.  Fewer rows per workgroup means more workgroups per KV head without
-    // more KV splits: the K/V stream is then re-read by the row tiles (from L2, they run side
-    // by side on one XCD) instead of fp32 partial outputs being written and read back once
-    // per split.
+    // Candidates: 4x1, 2x2 or 2x4 waves (32-row blocks x key interleave) per workgroup.  Fewer
+    // rows per workgroup means more workgroups per KV head without more KV splits: the K/V
+    // stream is then re-read by the row tiles (from L2, they run side by side on one XCD)
+    // instead of partial outputs being written and read back once per split.
     const int n_tiles = (max_prefix_len + kTileKeys - 1) / kTileKeys + (d.n_tree + kTileKeys - 1) / kTileKeys;
     const double kv_bytes = 2.0 * (max_prefix_len + d.n_tree) * d.head_dim * 2.0;
     const int slots = device_cu_count();  // one workgroup per CU measured best (partials cost more than idle slots)
-    int forced_wm = 0, forced_s = 0;
+    int forced_wm = 0, forced_wn = 0, forced_s = 0;
     if (const char* e = std::getenv("JK_ATTN_WM")) forced_wm = std::atoi(e);       // tuning overrides
+    if (const char* e = std::getenv("JK_ATTN_WN")) forced_wn = std::atoi(e);
     if (const char* e = std::getenv("JK_ATTN_SPLITS")) forced_s = std::atoi(e);
-    if (forced_wm != 4 && forced_wm != 2) forced_wm = 0;
+    static const int kArr[][2] = {{2, 4}, {2, 2}, {4, 1}};  // waves along rows x along keys
+    bool forced_ok = false;
+    for (const auto& a : kArr) forced_ok |= (a[0] == forced_wm && a[1] == forced_wn);
     double best_cost = 0.0;
     bool have = false;
-    for (int wm = 4; wm >= 2; wm >>= 1) {
-      if (forced_wm ? wm != forced_wm : (wm > 2 && pl->m_rows <= 16 * wm)) continue;  // mostly padding rows
-      const int wn = 4 / wm;
+    for (const auto& a : kArr) {
+      const int wm = a[0], wn = a[1];
+      if (forced_ok ? (wm != forced_wm || wn != forced_wn) : (wm > 2 && pl->m_rows <= 16 * wm)) continue;  // mostly padding rows
       const int q_rows = 32 * wm;
       const int n_qtiles = (pl->m_rows + q_rows - 1) / q_rows;
       const long long wgs = units * n_qtiles;
       const long long s_full = (slots + wgs - 1) / wgs;  // splits that fill every resident slot
       const int max_by_tiles = n_tiles / (2 * wn) > 0 ? n_tiles / (2 * wn) : 1;  // >= 2 rounds per split
-      {
-        long long s = s_full;
-        if (s > max_by_tiles) s = max_by_tiles;
-        if (s > kMaxSplits) s = kMaxSplits;
-        if (forced_s >= 1 && forced_s <= kMaxSplits) s = forced_s;
-        // partial outputs are written, flushed at the kernel boundary and read back: weigh them double
-        const double partial = s > 1 ? 4.0 * s * pl->m_rows * d.head_dim * 2.0 : 0.0;
-        // one workgroup per CU already reaches most of the throughput; the second hides latencies
-        const double fill = 0.5 + 0.5 * (double)(wgs * s < slots ? wgs * s : slots) / slots;
-        const double cost = (kv_bytes * (1.0 + 0.25 * (n_qtiles - 1)) + partial) / fill;
-        if (!have || cost < best_cost) {
-          have = true;
-          best_cost = cost;
-          pl->wm = wm; pl->wn = wn; pl->q_rows = q_rows; pl->n_qtiles = n_qtiles; pl->splits = (int)s;
-        }
+      long long s = s_full;
+      if (s > max_by_tiles) s = max_by_tiles;
+      if (s > kMaxSplits) s = kMaxSplits;
+      if (forced_s >= 1 && forced_s <= kMaxSplits) s = forced_s;
+      // partial outputs are written, flushed at the kernel boundary and read back: weigh them double
+      const double partial = s > 1 ? 4.0 * s * pl->m_rows * d.head_dim * 2.0 : 0.0;
+      // one workgroup per CU already reaches most of the throughput; the second hides latencies
+      const double fill = 0.5 + 0.5 * (double)(wgs * s < slots ? wgs * s : slots) / slots;
+      // 8-wave workgroups (two waves per SIMD overlap each other's issue stalls) pay off only
+      // where a CU holds a single workgroup anyway and that workgroup has several rounds to
+      // run; they start later (more waves to place, twice the LDS) and measured slower elsewhere
+      const int rounds8 = (n_tiles + wn - 1) / wn / (int)s;
+      const double issue = wm * wn == 8 ? ((wgs * s <= slots && rounds8 >= 4) ? 0.97 : 1.25) : 1.0;
+      const double cost = issue * (kv_bytes * (1.0 + 0.25 * (n_qtiles - 1)) + partial) / fill;
+      if (!have || cost < best_cost) {
+        have = true;
+        best_cost = cost;
+        pl->wm = wm; pl->wn = wn; pl->q_rows = q_rows; pl->n_qtiles = n_qtiles; pl->splits = (int)s;
       }
     }
     if (!have) return false;

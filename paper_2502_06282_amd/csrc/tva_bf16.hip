@@ -7,12 +7,14 @@
 //
 // Mapping.  The G query heads that share one KV head and the T tree nodes are
 // packed into one matrix of M = T*G query rows (row m = node m/G, head m%G), so
-// a KV head's K/V stream is read once for all of them.  One workgroup (4
-// waves; two workgroups share a CU, so that one's loads, prologue and epilogue
-// overlap the other's arithmetic) owns 32*WM query rows of one (sequence, KV head) and one split of
-// the key range; the key range (prefix tiles, then tree tiles, 32 keys each) is
-// cut into `splits` contiguous pieces.  Waves are arranged WM x WN: wave
-// (wm, wn) holds query rows [32*wm, 32*wm+32) and processes every WN-th tile.
+// a KV head's K/V stream is read once for all of them.  One workgroup of
+// WM x WN waves owns 32*WM query rows of one (sequence, KV head) and one split
+// of the key range; the key range (prefix tiles, then tree tiles, 32 keys each)
+// is cut into `splits` contiguous pieces.  Wave (wm, wn) holds query rows
+// [32*wm, 32*wm+32) and processes every WN-th tile.  A single wave per SIMD is
+// bound by its own in-order instruction issue (MFMA chain, exponentials, the
+// transfer bookkeeping), so the arrangements aim at two waves per SIMD: either
+// 8-wave workgroups or two 4-wave workgroups per CU.
 //
 // Per tile and wave, with everything transposed so that a lane owns one query
 // row:   S^T = K . Q^T   (v_mfma_f32_32x32x16_bf16, A = K rows from LDS,
@@ -23,7 +25,7 @@
 // ancestor set per node, built in LDS by the workgroups that own tree tiles.
 //
 // K/V travel HBM -> LDS directly (global_load_lds_dwordx4: 16 bytes per lane,
-// 16 lanes per 256-byte row) into a ring of 4 tiles, rounds ahead in flight;
+// 16 lanes per 256-byte row) into a ring of tiles, rounds ahead in flight;
 // each lane fetches the 16-byte chunk that the XOR swizzle maps to its LDS
 // slot, so that both the 128-bit K reads and the transpose V reads are free of
 // bank conflicts.
@@ -41,10 +43,7 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));  // native vecto
 
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
 
-constexpr int kThreads = 256;
-constexpr int kWaves = 4;       // one wave per SIMD; two workgroups share a CU
 constexpr int kWaveRows = 32;   // query rows per wave
-constexpr int kRingTiles = 4;   // K+V tiles resident in LDS (64 KB at head_dim 128): two workgroups fit a CU
 
 struct KParams {
   const uint16_t *q, *kc, *vc, *kt, *vt;
@@ -84,20 +83,29 @@ struct Geo {
   static constexpr int DB = D / 32;               // 32-wide d blocks of the output
   static constexpr int O_LD = D + 4;              // padded row of the epilogue buffer (floats)
   static constexpr int NB = TILE_BYTES / 1024;    // 1 KB transfers per tile and tensor
-  static constexpr int DMA_PER_TILE = 2 * NB / kWaves;  // transfers each wave issues per tile
   __device__ static __forceinline__ int kswz(int row) { return (row / (16 / CPR)) % CPR; }
   __device__ static __forceinline__ int vswz(int row) { return (row / (4 / DB)) % DB; }
 };
 
 // 16 bytes per lane straight from global memory into LDS (global_load_lds_dwordx4): lane l
-// of the wave lands at lds_base + 16*l.  Written as inline assembly so that the compiler
-// does not know about the transfer: its own bookkeeping would make every later LDS read
-// wait for ALL outstanding transfers, which would serialise the multi-stage ring.  The
-// kernel orders transfers and reads itself (wait_dma + __syncthreads).
-__device__ __forceinline__ void dma16(const void* gptr, unsigned lds_base) {
-  const unsigned base = __builtin_amdgcn_readfirstlane(lds_base);  // wave-uniform by construction
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(base), "v"(gptr)
+// of the wave lands at lds_base + 16*l and fetches base + voff (a wave-uniform 64-bit base
+// in scalar registers plus the lane's unsigned 32-bit byte offset).  Written as inline
+// assembly so that the compiler does not know about the transfer: its own bookkeeping
+// would make every later LDS read wait for ALL outstanding transfers, which would
+// serialise the multi-stage ring.  The kernel orders transfers and reads itself
+// (wait_dma + __syncthreads).
+__device__ __forceinline__ void dma16(const uint16_t* base, unsigned voff, unsigned lds_base) {
+  const unsigned m = __builtin_amdgcn_readfirstlane(lds_base);  // wave-uniform by construction
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(m), "v"(voff), "s"(base)
                : "memory", "m0");
+}
+
+// A wave-uniform pointer, made so for the compiler (scalar registers)
+__device__ __forceinline__ const uint16_t* uniform_ptr(const uint16_t* p) {
+  const unsigned long long v = reinterpret_cast<unsigned long long>(p);
+  const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v);
+  const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
+  return reinterpret_cast<const uint16_t*>(((unsigned long long)hi << 32) | lo);
 }
 
 // Wait until at most `rounds_behind` rounds of this wave's transfers are still in flight
@@ -118,66 +126,69 @@ __device__ __forceinline__ void wait_dma(int rounds_behind) {
 #undef JK_VM
 }
 
-// Everything a wave needs to fetch its chunks of a tile.
+// The K/V streams of this (sequence, KV head) and the tile range of this split.
 struct TileSrc {
-  const uint16_t *kc, *vc, *kt, *vt;  // bases of this (sequence, KV head)
-  long long kc_sl, kt_st;             // row strides (elements)
+  long long kc_sl, kt_st;  // row strides (elements)
   int L, T, n_ptiles, t_begin, t_end;
 };
 
 // Where a lane's 16-byte chunks sit inside a tile.  A wave-level transfer fills 1 KB =
 // 64/CPR consecutive tile rows; lane l writes physical chunk l%CPR of row blk*(64/CPR) +
 // l/CPR and fetches the logical chunk that the swizzle maps there, so the tile arrives
-// already swizzled.  The 2*NB transfers of a tile (NB for K, then NB for V) are dealt
-// to the 8 waves in order.
-template <int D>
+// already swizzled.  The 2*NB transfers of a tile (NB for K, then NB for V) are dealt to
+// the NW waves in order, N to each: a wave therefore fetches only K or only V chunks.
+template <int D, int NW>
 struct LaneChunks {
-  static constexpr int N = Geo<D>::DMA_PER_TILE;
-  int row[N];              // tile row
-  int col[N];              // element offset of the chunk inside the row
-  const uint16_t* full[N]; // address of the chunk inside prefix tile 0 (K or V cache)
-  const uint16_t* cache[N];  // K or V cache base of this (sequence, KV head)
-  const uint16_t* tree[N];   // K or V tree base
-  unsigned lds[N];         // byte offset inside the K+V tile pair
+  static constexpr int N = 2 * Geo<D>::NB / NW;
+  static_assert(N >= 1 && Geo<D>::NB % N == 0, "a wave's transfers stay within K or within V");
+  int row[N];             // tile row
+  unsigned col_b[N];      // byte offset of the chunk inside the row
+  unsigned off[N];        // byte offset of the chunk from the first row of a full cache tile
+  unsigned lds[N];        // byte offset inside the K+V tile pair
+  const uint16_t* cache;  // K or V cache of this (sequence, KV head), wave-uniform
+  const uint16_t* tree;   // K or V of the tree
 };
 
-template <int D>
-__device__ __forceinline__ void lane_chunks(LaneChunks<D>& lc, int wave, int lane, const TileSrc& ts) {
+template <int D, int NW>
+__device__ __forceinline__ void lane_chunks(LaneChunks<D, NW>& lc, int wave, int lane, const TileSrc& ts,
+                                            const uint16_t* kc, const uint16_t* vc, const uint16_t* kt,
+                                            const uint16_t* vt) {
   using G_ = Geo<D>;
   constexpr int RPB = 64 / G_::CPR;
+  constexpr int N = LaneChunks<D, NW>::N;
+  const int is_v = (wave * N) / G_::NB;
+  lc.cache = uniform_ptr(is_v ? vc : kc);
+  lc.tree = uniform_ptr(is_v ? vt : kt);
 #pragma unroll
-  for (int i = 0; i < LaneChunks<D>::N; ++i) {
-    const int id = wave * LaneChunks<D>::N + i;  // 0 .. 2*NB-1
-    const int is_v = id / G_::NB, blk = id % G_::NB;
+  for (int i = 0; i < N; ++i) {
+    const int blk = (wave * N + i) % G_::NB;
     const int row = blk * RPB + lane / G_::CPR;
     const int pc = lane % G_::CPR;
-    const int kc = pc ^ G_::kswz(row);                                  // K: 16-byte chunks swizzled
-    const int vc = (((pc >> 2) ^ G_::vswz(row)) << 2) | (pc & 3);       // V: 64-byte blocks swizzled
+    const int kcol = pc ^ G_::kswz(row);                                  // K: 16-byte chunks swizzled
+    const int vcol = (((pc >> 2) ^ G_::vswz(row)) << 2) | (pc & 3);       // V: 64-byte blocks swizzled
     lc.row[i] = row;
-    lc.col[i] = (is_v ? vc : kc) * 8;
-    lc.cache[i] = is_v ? ts.vc : ts.kc;
-    lc.tree[i] = is_v ? ts.vt : ts.kt;
-    lc.full[i] = lc.cache[i] + (long long)row * ts.kc_sl + lc.col[i];
+    lc.col_b[i] = (unsigned)(is_v ? vcol : kcol) * 16u;
+    lc.off[i] = (unsigned)row * (unsigned)ts.kc_sl * 2u + lc.col_b[i];  // < 2^31: strides are bounded by the host
     lc.lds[i] = is_v * G_::TILE_BYTES + blk * 1024;
   }
 }
 
 // Issue the transfers of round r (WN tiles, K and V) into ring slot `slot` (byte address).
-template <int D, int WN>
-__device__ __forceinline__ void dma_round(int r, const TileSrc& ts, const LaneChunks<D>& lc, unsigned slot) {
+template <int D, int NW, int WN>
+__device__ __forceinline__ void dma_round(int r, const TileSrc& ts, const LaneChunks<D, NW>& lc, unsigned slot) {
   using G_ = Geo<D>;
-  constexpr int N = LaneChunks<D>::N;
+  constexpr int N = LaneChunks<D, NW>::N;
   const int t0 = ts.t_begin + r * WN;
   if ((t0 + WN) * kTileKeys <= ts.L) {
-    // every tile of the round is a full prefix tile: one scalar offset per tile plus the
-    // lane's precomputed address
+    // every tile of the round is a full prefix tile: a scalar base per tile plus the lane's
+    // precomputed offsets
     const long long tile_elems = (long long)kTileKeys * ts.kc_sl;
-    long long off = (long long)t0 * tile_elems;
+    const uint16_t* base = lc.cache + (long long)t0 * tile_elems;
 #pragma unroll
     for (int w = 0; w < WN; ++w) {
 #pragma unroll
-      for (int i = 0; i < N; ++i) dma16(lc.full[i] + off, slot + w * 2 * G_::TILE_BYTES + lc.lds[i]);
-      off += tile_elems;
+      for (int i = 0; i < N; ++i) dma16(base, lc.off[i], slot + w * 2 * G_::TILE_BYTES + lc.lds[i]);
+      base += tile_elems;
     }
     return;
   }
@@ -191,11 +202,11 @@ __device__ __forceinline__ void dma_round(int r, const TileSrc& ts, const LaneCh
     const int key0 = (tree ? t - ts.n_ptiles : t) * kTileKeys;
     const int last = (tree ? ts.T : ts.L) - 1 - key0;  // >= 0 (and >= 31 for a full prefix tile)
     const long long rs = tree ? ts.kt_st : ts.kc_sl;
+    const uint16_t* base = (tree ? lc.tree : lc.cache) + (long long)key0 * rs;
 #pragma unroll
     for (int i = 0; i < N; ++i) {
-      const uint16_t* base = tree ? lc.tree[i] : lc.cache[i];
       const int rr = lc.row[i] < last ? lc.row[i] : last;
-      dma16(base + (long long)(key0 + rr) * rs + lc.col[i], dst + lc.lds[i]);
+      dma16(base, (unsigned)rr * (unsigned)rs * 2u + lc.col_b[i], dst + lc.lds[i]);
     }
   }
 }
@@ -314,29 +325,55 @@ __device__ unsigned long long g_jk_ts[4096 * 8];
 #define JK_TS(i) do { } while (0)
 #endif
 
+// LDS plan of one workgroup, shared by the kernel and its launcher.
 template <int D, int WM, int WN>
-__global__ __launch_bounds__(kThreads, 2) void tva_bf16_kernel(const KParams p) {
+struct Plan {
   using G_ = Geo<D>;
+  static constexpr int NW = WM * WN;                    // waves
+  static constexpr int THREADS = 64 * NW;
+  static constexpr int RING_TILES = WN >= 4 ? 2 * WN : 4;  // K+V tile pairs resident in LDS
+  static constexpr int NR = RING_TILES / WN;            // rounds resident in the ring
+  static constexpr int QROWS = kWaveRows * WM;
+  static constexpr int STAGE_BYTES = WN * 2 * G_::TILE_BYTES;  // one round: WN tiles of K and V
+  static constexpr int RING_BYTES = NR * STAGE_BYTES;
+  static constexpr int OBUF_BYTES = NW * kWaveRows * G_::O_LD * 4;
+  static constexpr int UNION_BYTES = RING_BYTES > OBUF_BYTES ? RING_BYTES : OBUF_BYTES;
+  static constexpr int ML_BYTES = NW * kWaveRows * 8;
+  static constexpr int SMEM = UNION_BYTES + ML_BYTES + JK_MAX_TREE * 16 + JK_MAX_TREE * 4;
+  static constexpr int WGS_PER_CU = 2 * SMEM <= 160 * 1024 && NW <= 4 ? 2 : 1;
+  static_assert(SMEM <= 160 * 1024, "LDS budget");
+  static_assert(THREADS >= JK_MAX_TREE, "one thread per tree node in the prologue");
+};
+
+template <int D, int WM, int WN>
+__global__ __launch_bounds__((Plan<D, WM, WN>::THREADS), (Plan<D, WM, WN>::WGS_PER_CU)) void tva_bf16_kernel(
+    const KParams p) {
+  using G_ = Geo<D>;
+  using P_ = Plan<D, WM, WN>;
   constexpr int DK = G_::DK, DB = G_::DB;
-  constexpr int NR = kRingTiles / WN;                // rounds resident in the ring
-  constexpr int QROWS = kWaveRows * WM;
+  constexpr int NW = P_::NW, THREADS = P_::THREADS, NR = P_::NR, QROWS = P_::QROWS;
   constexpr int TILE_BYTES = G_::TILE_BYTES;
-  constexpr int STAGE_BYTES = WN * 2 * TILE_BYTES;   // one round: WN tiles of K and V
-  constexpr int RING_BYTES = NR * STAGE_BYTES;
-  constexpr int DMA_PER_ROUND = WN * G_::DMA_PER_TILE;  // transfers a wave issues per round
-  constexpr int OBUF_BYTES = kWaves * kWaveRows * G_::O_LD * 4;
-  constexpr int UNION_BYTES = RING_BYTES > OBUF_BYTES ? RING_BYTES : OBUF_BYTES;
-  static_assert(WM * WN == kWaves && NR >= 2 && (NR - 2) * DMA_PER_ROUND <= 63, "wave arrangement");
+  constexpr int STAGE_BYTES = P_::STAGE_BYTES;
+  constexpr int DMA_PER_ROUND = WN * LaneChunks<D, NW>::N;  // transfers a wave issues per round
+  static_assert(NR >= 2 && (NR - 2) * DMA_PER_ROUND <= 63, "wave arrangement");
 
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   unsigned char* ring = smem;
-  float* obuf = reinterpret_cast<float*>(smem);                                  // [WN][QROWS][O_LD], after the loop
-  float2* mlbuf = reinterpret_cast<float2*>(smem + UNION_BYTES);                 // [WN][QROWS]
-  unsigned long long* anc =
-      reinterpret_cast<unsigned long long*>(smem + UNION_BYTES + kWaves * kWaveRows * 8);  // [128][2]
-  int* par_s = reinterpret_cast<int*>(smem + UNION_BYTES + kWaves * kWaveRows * 8 + JK_MAX_TREE * 16);  // [128]
+  float* obuf = reinterpret_cast<float*>(smem);                                   // [WN][QROWS][O_LD], after the loop
+  float2* mlbuf = reinterpret_cast<float2*>(smem + P_::UNION_BYTES);              // [WN][QROWS]
+  unsigned long long* anc = reinterpret_cast<unsigned long long*>(smem + P_::UNION_BYTES + P_::ML_BYTES);  // [128][2]
+  int* par_s = reinterpret_cast<int*>(smem + P_::UNION_BYTES + P_::ML_BYTES + JK_MAX_TREE * 16);           // [128]
 
   JK_TS(0);
+  // ---- touch every 64-byte line of the kernel arguments at once: the compiler fetches them
+  // in several dependent batches, and this way only the first batch pays a trip to memory
+  {
+    typedef __attribute__((address_space(4))) const unsigned kernarg_word;
+    kernarg_word* ka = (kernarg_word*)__builtin_amdgcn_kernarg_segment_ptr();
+    static_assert(sizeof(KParams) > 192 && sizeof(KParams) <= 256, "four lines of kernel arguments");
+    const unsigned a0 = ka[0], a1 = ka[16], a2 = ka[32], a3 = ka[48];
+    asm volatile("" ::"s"(a0), "s"(a1), "s"(a2), "s"(a3));
+  }
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -358,37 +395,34 @@ __global__ __launch_bounds__(kThreads, 2) void tva_bf16_kernel(const KParams p) 
   }
   int rest = div_mg(wid, p.mg_qtiles);
   const int qtile = wid - rest * p.n_qtiles;
-  {
-    const int r2 = div_mg(rest, p.mg_splits);
-    if (r2 >= p.B * p.Hkv) return;  // padding workgroup
-  }
   const int unit_id = div_mg(rest, p.mg_splits);  // b * Hkv + kv
+  if (unit_id >= p.B * p.Hkv) return;             // padding workgroup
   const int split = rest - unit_id * splits;
   const int b = div_mg(unit_id, p.mg_hkv);
   const int kv = unit_id - b * p.Hkv;
 
-  // ---- issue the prefix-length load, then the query rows (which do not depend on it), and
-  // only then use the length: the two latencies overlap
-  const int L_raw = p.prefix_len[b];
+  // ---- the prefix length first, as a per-lane vector load (an atomic load is never turned
+  // into a scalar one, and the compiler must not see that the address is uniform, or it
+  // moves the value to a scalar register at once and waits for it): scalar loads share one
+  // counter with the kernel-argument loads, so waiting for an argument would wait for this
+  // trip to memory as well.  Then the query rows and the
+  // parent array, none of which depends on it.  All ordinary loads are older than the K/V
+  // transfers: the compiler's waits for them then never include a transfer.
+  int lane_zero = 0;
+  asm volatile("" : "+v"(lane_zero));  // hides from the compiler that the address is uniform
+  const int L_raw = __hip_atomic_load(p.prefix_len + b + lane_zero, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   WaveState<D> st;
   const int m_row = qtile * QROWS + wm * kWaveRows + c32;  // this lane's query row
   const bool row_ok = m_row < M;
   const int mm = row_ok ? m_row : M - 1;
   const int my_node = div_mg(mm, p.mg_g);
+  u32x4 q_raw[DK];
   {
     const uint16_t* src =
         p.q + b * p.q_sb + my_node * p.q_st + (long long)(kv * G + (mm - my_node * G)) * p.q_sh + 8 * g;
 #pragma unroll
-    for (int ks = 0; ks < DK; ++ks) {
-      u32x4 v = *reinterpret_cast<const u32x4*>(src + ks * 16);  // clamped row: always in bounds
-      if (!row_ok) v = u32x4{0u, 0u, 0u, 0u};
-      st.q[ks] = __builtin_bit_cast(bf16x8, v);
-    }
+    for (int ks = 0; ks < DK; ++ks) q_raw[ks] = *reinterpret_cast<const u32x4*>(src + ks * 16);  // clamped row: in bounds
   }
-
-  // ---- the parent array as well (4 bytes per thread, needed only by workgroups that reach tree
-  // tiles, but loading it now keeps every ordinary load older than the K/V transfers: the
-  // compiler's waits for ordinary loads then never include a transfer)
   int my_parent = -1;
   if (tid < T) my_parent = p.parent[(long long)b * T + tid];
 
@@ -397,51 +431,59 @@ __global__ __launch_bounds__(kThreads, 2) void tva_bf16_kernel(const KParams p) 
   // turns out shorter, the speculative transfers are waited for and everything is redone.
   TileSrc ts;
   ts.T = T;
-  ts.kc = p.kc + b * p.kc_sb + (long long)kv * p.kc_sh;
-  ts.vc = p.vc + b * p.kc_sb + (long long)kv * p.kc_sh;
-  ts.kt = p.kt + b * p.kt_sb + (long long)kv * p.kt_sh;
-  ts.vt = p.vt + b * p.kt_sb + (long long)kv * p.kt_sh;
   ts.kc_sl = p.kc_sl;
   ts.kt_st = p.kt_st;
   const int n_ttiles = (T + kTileKeys - 1) / kTileKeys;
+  // Splits are dealt whole rounds (WN tiles): the first R % splits of them one round more than
+  // the rest, and the last one whatever remains, so that the split that ends with the ragged
+  // prefix tile and the masked tree tiles (slower transfers, mask arithmetic, ancestor sets)
+  // never also carries the extra round.
   auto set_range = [&](int len) {
     ts.L = len;
     ts.n_ptiles = (len + kTileKeys - 1) / kTileKeys;
     const int nt = ts.n_ptiles + n_ttiles;
-    ts.t_begin = div_mg(split * nt, p.mg_splits);  // (split + 1) * nt * splits < 2^32: nt < 2^20
-    ts.t_end = div_mg((split + 1) * nt, p.mg_splits);
+    const int R = (nt + WN - 1) / WN;
+    const int base = div_mg(R, p.mg_splits);
+    const int rem = R - base * splits;
+    const int rb = split * base + (split < rem ? split : rem);
+    const int re = rb + base + (split < rem ? 1 : 0);
+    ts.t_begin = rb * WN < nt ? rb * WN : nt;
+    ts.t_end = re * WN < nt ? re * WN : nt;
   };
   const unsigned ring_addr = (unsigned)(size_t)LDS_PTR(unsigned char, ring);
-  LaneChunks<D> lc;
-  lane_chunks<D>(lc, wave, lane, ts);
+  LaneChunks<D, NW> lc;
+  lane_chunks<D, NW>(lc, wave, lane, ts, p.kc + b * p.kc_sb + (long long)kv * p.kc_sh,
+                     p.vc + b * p.kc_sb + (long long)kv * p.kc_sh, p.kt + b * p.kt_sb + (long long)kv * p.kt_sh,
+                     p.vt + b * p.kt_sb + (long long)kv * p.kt_sh);
 
   set_range(p.max_prefix);
   int n_rounds = (ts.t_end - ts.t_begin + WN - 1) / WN;
+  const bool spec_any = n_rounds > 0 && (ts.t_begin + WN) * kTileKeys <= p.max_prefix;  // same for every wave
   int n_spec = 0;  // rounds already issued, all of them full prefix tiles under the assumption
 #pragma unroll
   for (int r = 0; r < NR - 1; ++r)
     if (n_spec == r && r < n_rounds && (ts.t_begin + (r + 1) * WN) * kTileKeys <= p.max_prefix) {
-      dma_round<D, WN>(r, ts, lc, ring_addr + r * STAGE_BYTES);
+      dma_round<D, NW, WN>(r, ts, lc, ring_addr + r * STAGE_BYTES);
       n_spec = r + 1;
     }
-  JK_TS(2);
-
-  int L = L_raw;
-  L = L < 0 ? 0 : (L > p.max_prefix ? p.max_prefix : L);
   JK_TS(1);
+
+  int L = __builtin_amdgcn_readfirstlane(L_raw);
+  L = L < 0 ? 0 : (L > p.max_prefix ? p.max_prefix : L);
+  JK_TS(2);
   if (L != p.max_prefix) {  // uniform over the workgroup
-    if (n_spec > 0) {
+    if (spec_any) {
       wait_dma<DMA_PER_ROUND>(0);  // the ring must be quiet before the same slots are filled again
       __syncthreads();
-      n_spec = 0;
     }
+    n_spec = 0;
     set_range(L);
     n_rounds = (ts.t_end - ts.t_begin + WN - 1) / WN;
   }
   const bool has_tree = ts.t_end > ts.n_ptiles;
 #pragma unroll
   for (int r = 0; r < NR - 1; ++r)
-    if (r >= n_spec && r < n_rounds) dma_round<D, WN>(r, ts, lc, ring_addr + r * STAGE_BYTES);
+    if (r >= n_spec && r < n_rounds) dma_round<D, NW, WN>(r, ts, lc, ring_addr + r * STAGE_BYTES);
 
   JK_TS(3);
   // ---- ancestor sets (only workgroups that reach tree tiles need them)
@@ -461,6 +503,12 @@ __global__ __launch_bounds__(kThreads, 2) void tva_bf16_kernel(const KParams p) 
     // visibility to the other threads is ordered by the first __syncthreads of the tile loop
   }
 
+#pragma unroll
+  for (int ks = 0; ks < DK; ++ks) {
+    u32x4 v = q_raw[ks];
+    if (!row_ok) v = u32x4{0u, 0u, 0u, 0u};
+    st.q[ks] = __builtin_bit_cast(bf16x8, v);
+  }
 #pragma unroll
   for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -494,7 +542,7 @@ __global__ __launch_bounds__(kThreads, 2) void tva_bf16_kernel(const KParams p) 
     __syncthreads();
     if (r == 0) JK_TS(4);
     if (r + NR - 1 < n_rounds)
-      dma_round<D, WN>(r + NR - 1, ts, lc, ring_addr + ((r + NR - 1) % NR) * STAGE_BYTES);
+      dma_round<D, NW, WN>(r + NR - 1, ts, lc, ring_addr + ((r + NR - 1) % NR) * STAGE_BYTES);
     int t, mode, nvalid;
     unsigned int bits;
     const unsigned char* kt_s;
@@ -524,13 +572,18 @@ __global__ __launch_bounds__(kThreads, 2) void tva_bf16_kernel(const KParams p) 
   __syncthreads();
 
   JK_TS(6);
-  // ---- merge the WN key-interleaved waves, then write the split's partial (or the result)
+  // ---- merge the WN key-interleaved waves, then write the split's partial (or the result).
+  // Item `it` is 4 consecutive output columns of one row; the trip count is a constant so
+  // that the iterations' LDS reads overlap.
   constexpr int D4 = D / 4;
+  constexpr int ITERS = QROWS * D4 / THREADS;
+  static_assert(QROWS * D4 % THREADS == 0, "merge items divide evenly");
   const long long unit = (long long)(b * p.Hkv + kv);
-  for (int it = tid; it < QROWS * D4; it += kThreads) {
+#pragma unroll
+  for (int k = 0; k < ITERS; ++k) {
+    const int it = tid + k * THREADS;
     const int row = it / D4, d4 = it % D4;
     const int m = qtile * QROWS + row;
-    if (m >= M) continue;
     float mx = -INFINITY;
 #pragma unroll
     for (int w = 0; w < WN; ++w) mx = fmaxf(mx, mlbuf[w * QROWS + row].x);
@@ -548,9 +601,10 @@ __global__ __launch_bounds__(kThreads, 2) void tva_bf16_kernel(const KParams p) 
       acc.w = fmaf(o.w, wgt, acc.w);
       lsum = fmaf(ml.y, wgt, lsum);
     }
+    if (m >= M) continue;
     if (splits == 1) {
       const float inv = 1.f / lsum;  // lsum > 0: every row sees at least its own tree key
-      const int node = m / G, hg = m % G;
+      const int node = div_mg(m, p.mg_g), hg = m - node * G;
       uint16_t* dst = p.out + b * p.o_sb + node * p.o_st + (long long)(kv * G + hg) * p.o_sh + 4 * d4;
       bf16x2 lo, hi;
       lo[0] = (__bf16)(acc.x * inv);
@@ -582,21 +636,16 @@ __global__ __launch_bounds__(kThreads, 2) void tva_bf16_kernel(const KParams p) 
 
 template <int D, int WM, int WN>
 hipError_t launch_one(const KParams& kp, hipStream_t stream) {
-  using G_ = Geo<D>;
-  constexpr int RING_BYTES = kRingTiles * 2 * G_::TILE_BYTES;
-  constexpr int OBUF_BYTES = kWaves * kWaveRows * G_::O_LD * 4;
-  constexpr int UNION_BYTES = RING_BYTES > OBUF_BYTES ? RING_BYTES : OBUF_BYTES;
-  constexpr int SMEM = UNION_BYTES + kWaves * kWaveRows * 8 + JK_MAX_TREE * 16 + JK_MAX_TREE * 4;
-  static_assert(2 * SMEM <= 160 * 1024, "LDS budget: two workgroups per CU");
+  using P_ = Plan<D, WM, WN>;
   auto kern = tva_bf16_kernel<D, WM, WN>;
   static bool lds_limit_raised = false;  // idempotent, so a race between host threads is harmless
   if (!lds_limit_raised) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, P_::SMEM);
     if (e != hipSuccess) return e;
     lds_limit_raised = true;
   }
-  hipLaunchKernelGGL(kern, dim3(kp.total_wgs), dim3(kThreads), SMEM, stream, kp);
+  hipLaunchKernelGGL(kern, dim3(kp.total_wgs), dim3(P_::THREADS), P_::SMEM, stream, kp);
   return hipGetLastError();
 }
 
@@ -641,8 +690,10 @@ hipError_t launch_tva_bf16(const AttnArgs& a, const AttnPlan& pl, hipStream_t st
   switch (key) {
     case 12841: return launch_one<128, 4, 1>(kp, stream);
     case 12822: return launch_one<128, 2, 2>(kp, stream);
+    case 12824: return launch_one<128, 2, 4>(kp, stream);
     case 6441: return launch_one<64, 4, 1>(kp, stream);
     case 6422: return launch_one<64, 2, 2>(kp, stream);
+    case 6424: return launch_one<64, 2, 4>(kp, stream);
     default: return hipErrorInvalidValue;
   }
 }
