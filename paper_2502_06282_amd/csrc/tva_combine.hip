@@ -16,8 +16,13 @@ struct CParams {
   const float2* part_ml;
   void* out;
   int B, Hkv, G, M, m_pad, D, splits;
+  unsigned long long mg_hkv, mg_g;  // floor(2^32 / d) + 1: n / d == (n * mg) >> 32 while n * d < 2^32
   long long o_sb, o_st, o_sh;
 };
+
+__device__ __forceinline__ int div_mg(int n, unsigned long long mg) {
+  return (int)(((unsigned long long)(unsigned)n * mg) >> 32);
+}
 
 // Four consecutive columns of a partial output row: fp32 partials (fp32 path) or bf16 (bf16 path).
 template <bool BF16>
@@ -146,6 +151,79 @@ __global__ __launch_bounds__(256) void tva_combine_kernel(CParams p) {
   }
 }
 
+// bf16 path: one wave per query row, a lane per CPL = D/64 output columns, no LDS and no
+// barrier.  The row is wave-uniform, so the (max, sum) pairs of its splits are uniform
+// (scalar) loads and every lane derives the same weights; splits go by in chunks of 8 with
+// all of a chunk's loads in flight together, merged with a running maximum.  Grid: x = unit
+// (sequence, KV head), y = blocks of 4 rows.
+template <int D>
+__global__ __launch_bounds__(256) void tva_combine_bf16_kernel(CParams p) {
+  constexpr int CPL = D / 64;
+  static_assert(CPL == 1 || CPL == 2, "head_dim 64 or 128");
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int unit = blockIdx.x;
+  const int m = blockIdx.y * 4 + wave;
+  if (m >= p.M) return;
+  const int S = p.splits;
+  const long long prow0 = (long long)unit * S * p.m_pad + m;
+  const uint16_t* po = reinterpret_cast<const uint16_t*>(p.part_o) + prow0 * D + CPL * lane;
+  const float2* pml = p.part_ml + prow0;
+  const long long po_step = (long long)p.m_pad * D;  // one split further
+
+  float m_run = -INFINITY, l_run = 0.f, acc0 = 0.f, acc1 = 0.f;
+  for (int s0 = 0; s0 < S; s0 += 8) {
+    float2 ml[8];
+    unsigned raw[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const bool ok = s0 + u < S;
+      ml[u] = ok ? pml[(long long)(s0 + u) * p.m_pad] : make_float2(-INFINITY, 0.f);
+      if (!(ml[u].y > 0.f)) ml[u] = make_float2(-INFINITY, 0.f);  // an empty split carries no weight
+      raw[u] = 0u;
+      if (ok) {
+        const uint16_t* src = po + (long long)(s0 + u) * po_step;
+        raw[u] = CPL == 2 ? *reinterpret_cast<const unsigned*>(src) : (unsigned)*src;
+      }
+    }
+    float cm = ml[0].x;
+#pragma unroll
+    for (int u = 1; u < 8; ++u) cm = fmaxf(cm, ml[u].x);
+    const float m_new = fmaxf(m_run, cm);
+    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+    const float a = __builtin_amdgcn_exp2f(m_run - m_use);  // 0 while nothing has been merged yet
+    acc0 *= a;
+    acc1 *= a;
+    l_run *= a;
+    m_run = m_new;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const float w = __builtin_amdgcn_exp2f(ml[u].x - m_use);  // exp2(-inf) = 0 for empty or absent splits
+      l_run = fmaf(ml[u].y, w, l_run);
+      if (w != 0.f) {  // an unused split may hold anything
+        const float v0 = __uint_as_float(raw[u] << 16);  // the lane's first (or only) column sits in the low half
+        const float v1 = __uint_as_float(raw[u] & 0xffff0000u);
+        acc0 = fmaf(v0, w, acc0);
+        if (CPL == 2) acc1 = fmaf(v1, w, acc1);
+      }
+    }
+  }
+  const float inv = 1.f / l_run;  // > 0: every row sees at least its own tree key
+  const int b = div_mg(unit, p.mg_hkv), kv = unit - b * p.Hkv;
+  const int node = div_mg(m, p.mg_g), hg = m - node * p.G;
+  uint16_t* dst = static_cast<uint16_t*>(p.out) + b * p.o_sb + node * p.o_st + (long long)(kv * p.G + hg) * p.o_sh +
+                  CPL * lane;
+  if (CPL == 2) {
+    bf16x2 o;
+    o[0] = (__bf16)(acc0 * inv);
+    o[1] = (__bf16)(acc1 * inv);
+    *reinterpret_cast<unsigned*>(dst) = __builtin_bit_cast(unsigned, o);
+  } else {
+    const __bf16 o = (__bf16)(acc0 * inv);
+    *dst = __builtin_bit_cast(uint16_t, o);
+  }
+}
+
 }  // namespace
 
 hipError_t launch_tva_combine(const AttnArgs& a, const AttnPlan& pl, hipStream_t stream) {
@@ -157,13 +235,21 @@ hipError_t launch_tva_combine(const AttnArgs& a, const AttnPlan& pl, hipStream_t
   cp.B = d.batch; cp.Hkv = d.n_kv_heads; cp.G = d.n_q_heads / d.n_kv_heads;
   cp.M = pl.m_rows; cp.m_pad = pl.m_pad; cp.D = d.head_dim; cp.splits = pl.splits;
   cp.o_sb = d.o_stride_b; cp.o_st = d.o_stride_t; cp.o_sh = d.o_stride_h;
-  const int tpr = 2 * (d.head_dim / 4);
-  const int rpw = 256 / (tpr > 64 ? tpr : 64);
-  const unsigned grid = (unsigned)(((long long)d.batch * d.n_kv_heads * pl.m_rows + rpw - 1) / rpw);
-  if (d.dtype == JK_BF16)
-    hipLaunchKernelGGL((tva_combine_kernel<true, true>), dim3(grid), dim3(256), 0, stream, cp);
-  else
+  auto magic = [](int v) { return (1ull << 32) / (unsigned long long)v + 1ull; };
+  cp.mg_hkv = magic(cp.Hkv);
+  cp.mg_g = magic(cp.G);
+  if (d.dtype == JK_BF16) {
+    const dim3 grid((unsigned)(d.batch * d.n_kv_heads), (unsigned)((pl.m_rows + 3) / 4));
+    if (d.head_dim == 128)
+      hipLaunchKernelGGL((tva_combine_bf16_kernel<128>), grid, dim3(256), 0, stream, cp);
+    else
+      hipLaunchKernelGGL((tva_combine_bf16_kernel<64>), grid, dim3(256), 0, stream, cp);
+  } else {
+    const int tpr = 2 * (d.head_dim / 4);
+    const int rpw = 256 / (tpr > 64 ? tpr : 64);
+    const unsigned grid = (unsigned)(((long long)d.batch * d.n_kv_heads * pl.m_rows + rpw - 1) / rpw);
     hipLaunchKernelGGL((tva_combine_kernel<false, false>), dim3(grid), dim3(256), 0, stream, cp);
+  }
   return hipGetLastError();
 }
 
