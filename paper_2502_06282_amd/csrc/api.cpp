@@ -41,7 +41,7 @@ bool make_attn_plan(const jk_attn_desc& d, int max_prefix_len, AttnPlan* pl) {
   pl->m_rows = d.n_tree * G;
   const long long units = (long long)d.batch * d.n_kv_heads;
   if (d.dtype == JK_BF16) {
-    // Candidates: 4x1, 2x2 or 2x4 waves (32-row blocks x key interleave) per workgroup.  Fewer
+    // Candidates: 4x1 or 2x2 waves (32-row blocks x key interleave) per workgroup.  Fewer
     // rows per workgroup means more workgroups per KV head without more KV splits: the K/V
     // stream is then re-read by the row tiles (from L2, they run side by side on one XCD)
     // instead of partial outputs being written and read back once per split.
@@ -52,7 +52,7 @@ bool make_attn_plan(const jk_attn_desc& d, int max_prefix_len, AttnPlan* pl) {
     if (const char* e = std::getenv("JK_ATTN_WM")) forced_wm = std::atoi(e);       // tuning overrides
     if (const char* e = std::getenv("JK_ATTN_WN")) forced_wn = std::atoi(e);
     if (const char* e = std::getenv("JK_ATTN_SPLITS")) forced_s = std::atoi(e);
-    static const int kArr[][2] = {{2, 4}, {2, 2}, {4, 1}};  // waves along rows x along keys
+    static const int kArr[][2] = {{2, 2}, {4, 1}};  // waves along rows x along keys
     bool forced_ok = false;
     for (const auto& a : kArr) forced_ok |= (a[0] == forced_wm && a[1] == forced_wn);
     double best_cost = 0.0;
@@ -64,7 +64,8 @@ bool make_attn_plan(const jk_attn_desc& d, int max_prefix_len, AttnPlan* pl) {
       const int n_qtiles = (pl->m_rows + q_rows - 1) / q_rows;
       const long long wgs = units * n_qtiles;
       const long long s_full = (slots + wgs - 1) / wgs;  // splits that fill every resident slot
-      const int max_by_tiles = n_tiles / (2 * wn) > 0 ? n_tiles / (2 * wn) : 1;  // >= 2 rounds per split
+      const int kt = wn == 1 ? 2 : 1;  // a lone key column pairs its tiles (hand-pipelined two-tile path)
+      const int max_by_tiles = n_tiles / (2 * wn * kt) > 0 ? n_tiles / (2 * wn * kt) : 1;  // >= 2 rounds per split
       long long s = s_full;
       if (s > max_by_tiles) s = max_by_tiles;
       if (s > kMaxSplits) s = kMaxSplits;
@@ -73,22 +74,17 @@ bool make_attn_plan(const jk_attn_desc& d, int max_prefix_len, AttnPlan* pl) {
       const double partial = s > 1 ? 4.0 * s * pl->m_rows * d.head_dim * 2.0 : 0.0;
       // one workgroup per CU already reaches most of the throughput; the second hides latencies
       const double fill = 0.5 + 0.5 * (double)(wgs * s < slots ? wgs * s : slots) / slots;
-      // 8-wave workgroups (two waves per SIMD overlap each other's issue stalls) pay off only
-      // where a CU holds a single workgroup anyway and that workgroup has several rounds to
-      // run; they start later (more waves to place, twice the LDS) and measured slower elsewhere
-      const int rounds8 = (n_tiles + wn - 1) / wn / (int)s;
-      const double issue = wm * wn == 8 ? ((wgs * s <= slots && rounds8 >= 4) ? 0.97 : 1.25) : 1.0;
-      const double cost = issue * (kv_bytes * (1.0 + 0.25 * (n_qtiles - 1)) + partial) / fill;
+      const double cost = (kv_bytes * (1.0 + 0.25 * (n_qtiles - 1)) + partial) / fill;
       if (!have || cost < best_cost) {
         have = true;
         best_cost = cost;
-        pl->wm = wm; pl->wn = wn; pl->q_rows = q_rows; pl->n_qtiles = n_qtiles; pl->splits = (int)s;
+        pl->wm = wm; pl->wn = wn; pl->kt = kt; pl->q_rows = q_rows; pl->n_qtiles = n_qtiles; pl->splits = (int)s;
       }
     }
     if (!have) return false;
     pl->m_pad = pl->n_qtiles * pl->q_rows;
   } else {
-    pl->wm = pl->wn = 1;
+    pl->wm = pl->wn = pl->kt = 1;
     pl->q_rows = 1;
     pl->n_qtiles = pl->m_rows;
     pl->m_pad = pl->m_rows;

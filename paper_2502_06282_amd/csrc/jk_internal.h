@@ -17,7 +17,8 @@ constexpr int kMaxSplits = 64;     // upper bound on KV splits per (sequence, KV
 // launch always agree.
 struct AttnPlan {
   int wm;          // waves along the query-row axis (32 rows each)
-  int wn;          // waves along the key axis (each takes every wn-th tile)
+  int wn;          // waves along the key axis (key columns of a round)
+  int kt;          // consecutive 32-key tiles a wave takes per round (1 or 2)
   int q_rows;      // query rows per workgroup = 32 * wm
   int n_qtiles;    // workgroups along the query-row axis
   int m_rows;      // T * G query rows per KV head

@@ -11,10 +11,12 @@
 // WM x WN waves owns 32*WM query rows of one (sequence, KV head) and one split
 // of the key range; the key range (prefix tiles, then tree tiles, 32 keys each)
 // is cut into `splits` contiguous pieces.  Wave (wm, wn) holds query rows
-// [32*wm, 32*wm+32) and processes every WN-th tile.  A single wave per SIMD is
-// bound by its own in-order instruction issue (MFMA chain, exponentials, the
-// transfer bookkeeping), so the arrangements aim at two waves per SIMD: either
-// 8-wave workgroups or two 4-wave workgroups per CU.
+// [32*wm, 32*wm+32) and processes every WN-th tile.  Workgroups have 4 waves
+// (4x1 or 2x2) and two of them fit a CU: a single wave per SIMD is bound by its
+// own in-order instruction issue (MFMA chain, exponentials, transfer
+// bookkeeping), which a second workgroup on the CU overlaps.  (8-wave 2x4
+// workgroups measured no better: they start later and their wider epilogue
+// merge costs what the shorter tile loop gains.)
 //
 // Per tile and wave, with everything transposed so that a lane owns one query
 // row:   S^T = K . Q^T   (v_mfma_f32_32x32x16_bf16, A = K rows from LDS,
@@ -42,6 +44,19 @@ typedef short shortx8 __attribute__((ext_vector_type(8)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));  // native vector: plain loads/stores, no struct copies
 
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
+
+typedef __attribute__((address_space(3))) const bf16x8 lds_bf16x8;
+typedef __attribute__((address_space(3))) shortx4 lds_shortx4;
+
+// LDS reads by byte address.  Tile bases are multiples of 256 bytes, so the XOR swizzles can
+// be applied to the finished address: one address register per operand stream plus an
+// immediate per read, instead of a register per read.
+__device__ __forceinline__ bf16x8 lds_read128(unsigned addr) { return *(lds_bf16x8*)(size_t)addr; }
+__device__ __forceinline__ bf16x8 lds_read_tr2(unsigned addr, unsigned second) {
+  const shortx4 x0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4*)(size_t)addr);
+  const shortx4 x1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4*)(size_t)(addr + second));
+  return __builtin_bit_cast(bf16x8, __builtin_shufflevector(x0, x1, 0, 1, 2, 3, 4, 5, 6, 7));
+}
 
 constexpr int kWaveRows = 32;   // query rows per wave
 
@@ -85,6 +100,21 @@ struct Geo {
   static constexpr int NB = TILE_BYTES / 1024;    // 1 KB transfers per tile and tensor
   __device__ static __forceinline__ int kswz(int row) { return (row / (16 / CPR)) % CPR; }
   __device__ static __forceinline__ int vswz(int row) { return (row / (4 / DB)) % DB; }
+  // K operand of k-step ks (A of S^T = K . Q^T; lane = key row c32, half g): chunk
+  // (2*ks + g) ^ kswz of its row = byte address (tile + k_lane(lane)) ^ (ks << 5)
+  __device__ static __forceinline__ unsigned k_lane(int lane) {
+    const int c32 = lane & 31, g = lane >> 5;
+    return (unsigned)(c32 * ROW_BYTES + ((kswz(c32) ^ g) << 4));
+  }
+  // V^T operand (transpose read: the 16 lanes of a group address 4 keys x 32 bytes, lane i of
+  // the group receives d-column i of those 4 keys; contraction index 4*q'+r of MFMA j is key
+  // 16*j + 8*q' + 4*g + r): 64-byte block db ^ vswz of key row 4*g + (lane%16)/4 = byte
+  // address ((tile + v_lane(lane)) ^ (db << 6)) + 16*j*ROW_BYTES, second half 8 rows further
+  __device__ static __forceinline__ unsigned v_lane(int lane) {
+    const int g = lane >> 5, jj = (lane & 15) >> 2, cc = lane & 3, h16 = (lane & 31) >> 4;
+    const int key_lo = 4 * g + jj;
+    return (unsigned)(key_lo * ROW_BYTES + 32 * h16 + 8 * cc + (vswz(key_lo) << 6));
+  }
 };
 
 // 16 bytes per lane straight from global memory into LDS (global_load_lds_dwordx4): lane l
@@ -173,19 +203,19 @@ __device__ __forceinline__ void lane_chunks(LaneChunks<D, NW>& lc, int wave, int
   }
 }
 
-// Issue the transfers of round r (WN tiles, K and V) into ring slot `slot` (byte address).
-template <int D, int NW, int WN>
+// Issue the transfers of round r (TPR tiles, K and V) into ring slot `slot` (byte address).
+template <int D, int NW, int TPR>
 __device__ __forceinline__ void dma_round(int r, const TileSrc& ts, const LaneChunks<D, NW>& lc, unsigned slot) {
   using G_ = Geo<D>;
   constexpr int N = LaneChunks<D, NW>::N;
-  const int t0 = ts.t_begin + r * WN;
-  if ((t0 + WN) * kTileKeys <= ts.L) {
+  const int t0 = ts.t_begin + r * TPR;
+  if ((t0 + TPR) * kTileKeys <= ts.L) {
     // every tile of the round is a full prefix tile: a scalar base per tile plus the lane's
     // precomputed offsets
     const long long tile_elems = (long long)kTileKeys * ts.kc_sl;
     const uint16_t* base = lc.cache + (long long)t0 * tile_elems;
 #pragma unroll
-    for (int w = 0; w < WN; ++w) {
+    for (int w = 0; w < TPR; ++w) {
 #pragma unroll
       for (int i = 0; i < N; ++i) dma16(base, lc.off[i], slot + w * 2 * G_::TILE_BYTES + lc.lds[i]);
       base += tile_elems;
@@ -193,7 +223,7 @@ __device__ __forceinline__ void dma_round(int r, const TileSrc& ts, const LaneCh
     return;
   }
 #pragma unroll 1
-  for (int w = 0; w < WN; ++w) {
+  for (int w = 0; w < TPR; ++w) {
     int t = t0 + w;
     if (t >= ts.t_end) t = ts.t_end - 1;  // duplicate of a real tile, never consumed
     const unsigned dst = slot + w * 2 * G_::TILE_BYTES;
@@ -219,35 +249,48 @@ struct WaveState {
   float m, l;
 };
 
-// S^T = K . Q^T of one 32-key tile against the wave's 32 query rows.
-template <int D>
-__device__ __forceinline__ floatx16 qk_tile(const WaveState<D>& st, const unsigned char* kt_s, int lane) {
+// S^T = K . Q^T of KT consecutive 32-key tiles (K tiles 2*TILE_BYTES apart in LDS) against
+// the wave's 32 query rows.  A chain of MFMAs into one accumulator issues only every other
+// MFMA slot (each waits for its predecessor's result), so two independent chains are kept in
+// flight: the two tiles' (KT = 2), or the even and odd k-steps of the one tile, summed at
+// the end (KT = 1).
+template <int D, int KT>
+__device__ __forceinline__ void qk_tiles(const WaveState<D>& st, unsigned k_addr, floatx16& s0, floatx16& s1) {
   using G_ = Geo<D>;
-  const int c32 = lane & 31, g = lane >> 5;
-  floatx16 sacc;
+  floatx16 a0, a1;
 #pragma unroll
-  for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
-  const unsigned char* krow = kt_s + c32 * G_::ROW_BYTES;
-  const int x = G_::kswz(c32);
+  for (int i = 0; i < 16; ++i) a0[i] = a1[i] = 0.f;
+  if (KT == 2) {
 #pragma unroll
-  for (int ks = 0; ks < G_::DK; ++ks) {
-    const bf16x8 a = *reinterpret_cast<const bf16x8*>(krow + (((2 * ks + g) ^ x) << 4));
-    sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, st.q[ks], sacc, 0, 0, 0);
+    for (int ks = 0; ks < G_::DK; ++ks) {
+      const bf16x8 k0 = lds_read128(k_addr ^ (ks << 5));
+      const bf16x8 k1 = lds_read128((k_addr ^ (ks << 5)) + 2 * G_::TILE_BYTES);
+      a0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0, st.q[ks], a0, 0, 0, 0);
+      a1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1, st.q[ks], a1, 0, 0, 0);
+    }
+    s0 = a0;
+    s1 = a1;
+  } else {
+#pragma unroll
+    for (int ks = 0; ks < G_::DK; ks += 2) {
+      const bf16x8 k0 = lds_read128(k_addr ^ (ks << 5));
+      const bf16x8 k1 = lds_read128(k_addr ^ ((ks + 1) << 5));
+      a0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0, st.q[ks], a0, 0, 0, 0);
+      a1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1, st.q[ks + 1], a1, 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s0[i] = a0[i] + a1[i];
   }
-  return sacc;
 }
 
-// Masking, online softmax and O^T += V^T . P^T for one tile whose scores are in sacc.
-// mask_mode: 0 none, 1 ragged prefix tail (keys >= nvalid hidden), 2 tree tile (bits =
-// visibility of the tile's 32 keys).
-template <int D>
-__device__ __forceinline__ void softmax_pv_tile(WaveState<D>& st, floatx16 sacc, const unsigned char* vt_s,
-                                                int mask_mode, int nvalid, unsigned int bits, float scale_log2,
-                                                int lane) {
-  using G_ = Geo<D>;
-  constexpr int DB = G_::DB;
-  const int g = lane >> 5;
-  // ---- masks: register i of a lane is key 8*(i/4) + 4*g + i%4 of the tile
+// Hide the masked keys of one tile's scores.  mask_mode: 0 none, 1 ragged prefix tail (keys
+// >= nvalid hidden), 2 tree tile (bits = visibility of the tile's 32 keys; 0 for a tile
+// past the end of the split).  Register i of a lane is key 8*(i/4) + 4*g + i%4 of the tile.
+__device__ __forceinline__ void mask_tile(floatx16& sacc, int mask_mode, int nvalid, unsigned int bits, int g) {
+  if (mask_mode == 0) return;
+  // masked tiles are rare: keep their per-register key indices out of the loop-invariant
+  // registers (the compiler would otherwise hold 32 of them across the whole tile loop)
+  asm volatile("" : "+v"(g));
   if (mask_mode == 2) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
@@ -261,17 +304,28 @@ __device__ __forceinline__ void softmax_pv_tile(WaveState<D>& st, floatx16 sacc,
       if (kk >= nvalid) sacc[i] = -INFINITY;
     }
   }
-  // ---- online softmax; probabilities become bf16 B operands of the value product.
-  // The reference maximum m of a row moves only when the tile's maximum exceeds it by more
+}
+
+// Online softmax and O^T += V^T . P^T for the KT tiles of a round whose (masked) scores are
+// in s0 (and s1); v0 / v1 are their V tiles in LDS.  Two tiles share one running-maximum
+// update, and their independent MFMA chains fill each other's latencies.
+template <int D, int KT>
+__device__ __forceinline__ void softmax_pv(WaveState<D>& st, const floatx16& s0, const floatx16& s1,
+                                           unsigned v_addr, float scale_log2) {
+  using G_ = Geo<D>;
+  constexpr int DB = G_::DB;
+  // The reference maximum m of a row moves only when the round's maximum exceeds it by more
   // than kLazy (in log2 units): weights then stay below 2^kLazy, harmless in fp32/bf16, and
-  // the rescale of the accumulators (which live in accumulation registers and are costly
-  // to touch from the vector ALU) becomes rare.  The result is unchanged: weights, their
+  // the rescale of the accumulators becomes rare.  The result is unchanged: weights, their
   // sum and the accumulators all carry the same reference.
   constexpr float kLazy = 8.f;
-  bf16x8 pb[2];
-  float tmax = fmaxf(sacc[0], sacc[1]);
+  float tmax = fmaxf(s0[0], s0[1]);
 #pragma unroll
-  for (int i = 2; i < 16; ++i) tmax = fmaxf(tmax, sacc[i]);
+  for (int i = 2; i < 16; ++i) tmax = fmaxf(tmax, s0[i]);
+  if (KT == 2) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) tmax = fmaxf(tmax, s1[i]);
+  }
   tmax = half_swap_max(tmax) * scale_log2;
   const float m_old = st.m;
   const bool up = tmax > m_old + kLazy;  // false for tmax = -inf; true for the first visible key
@@ -280,15 +334,20 @@ __device__ __forceinline__ void softmax_pv_tile(WaveState<D>& st, floatx16 sacc,
   const float alpha = up ? fast_exp2(m_old - m_use) : 1.f;
   const bool moved = up && (m_old != -INFINITY);  // accumulators are still zero before the first key
   st.m = m_ref;
+  // probabilities become bf16 B operands of the value product
+  bf16x8 pb[2 * KT];
   float lsum = 0.f;
 #pragma unroll
-  for (int j = 0; j < 2; ++j)
+  for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const float pr = fast_exp2(fmaf(sacc[8 * j + e], scale_log2, -m_use));
-      lsum += pr;
-      pb[j][e] = (__bf16)pr;
-    }
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float sc = kt == 0 ? s0[8 * j + e] : s1[8 * j + e];
+        const float pr = fast_exp2(fmaf(sc, scale_log2, -m_use));
+        lsum += pr;
+        pb[2 * kt + j][e] = (__bf16)pr;
+      }
   st.l = fmaf(st.l, alpha, lsum);
   if (__any(moved)) {
 #pragma unroll
@@ -296,27 +355,144 @@ __device__ __forceinline__ void softmax_pv_tile(WaveState<D>& st, floatx16 sacc,
 #pragma unroll
       for (int i = 0; i < 16; ++i) st.o[db][i] *= alpha;
   }
-  // ---- O^T += V^T . P^T ; contraction index 4*q'+r of MFMA j is key 16*j + 8*q' + 4*g + r.
-  // Transpose read: the 16 lanes of a group address 4 keys x 32 bytes; lane i of the group
-  // receives d-column i of those 4 keys.
-  {
-    const int jj = (lane & 15) >> 2, cc = lane & 3, h16 = (lane & 31) >> 4;
-    const int key_lo = 4 * g + jj;  // + 16*j + 8*q'
-    const unsigned char* vrow = vt_s + key_lo * G_::ROW_BYTES + 32 * h16 + 8 * cc;
-    const int sw = G_::vswz(key_lo);  // keys 8 and 16 apart share it
+  // ---- O^T += V^T . P^T
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
+  for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int db = 0; db < DB; ++db) {
-        const unsigned char* ad = vrow + ((db ^ sw) << 6) + (16 * j) * G_::ROW_BYTES;
-        const shortx4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(shortx4, ad));
-        const shortx4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(shortx4, ad + 8 * G_::ROW_BYTES));
-        const shortx8 v01 = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
-        st.o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, v01), pb[j], st.o[db], 0, 0, 0);
+        const bf16x8 vf = lds_read_tr2((v_addr ^ (db << 6)) + kt * 2 * G_::TILE_BYTES + 16 * j * G_::ROW_BYTES,
+                                       8 * G_::ROW_BYTES);
+        st.o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pb[2 * kt + j], st.o[db], 0, 0, 0);
       }
+}
+
+// Two unmasked tiles A, B of a round, software-pipelined by hand.  Within one tile the score
+// product (MFMA), the softmax (vector ALU, a quarter-rate exponential per score) and the
+// value product (MFMA) depend on each other, and a lone wave on its SIMD issues in order: it
+// would use the two units one after the other.  Here the vector work of one tile is written
+// between the MFMAs of the other:
+//   S(A) | softmax(A) with S(B) | softmax(B) with O += P(A) V(A) | O += P(B) V(B)
+// Each tile updates the running maximum on its own (same lazy rule as softmax_pv).
+template <int D>
+struct PairPipe {
+  using G_ = Geo<D>;
+  static constexpr int DK = G_::DK, DB = G_::DB;
+  static constexpr float kLazy = 8.f;
+
+  // running-maximum update for one tile's scores: returns the reference to subtract; the sum
+  // is rescaled here, the accumulators by rescale() once nothing at the old reference is
+  // still to be added to them
+  static __device__ __forceinline__ float new_reference(WaveState<D>& st, const floatx16& s, float scale_log2,
+                                                        float& alpha, bool& moved) {
+    float tmax = fmaxf(s[0], s[1]);
+#pragma unroll
+    for (int i = 2; i < 16; ++i) tmax = fmaxf(tmax, s[i]);
+    tmax = half_swap_max(tmax) * scale_log2;
+    const float m_old = st.m;
+    const bool up = tmax > m_old + kLazy;
+    const float m_ref = up ? tmax : m_old;
+    const float m_use = (m_ref == -INFINITY) ? 0.f : m_ref;
+    alpha = up ? fast_exp2(m_old - m_use) : 1.f;
+    moved = up && (m_old != -INFINITY);
+    st.m = m_ref;
+    st.l *= alpha;
+    return m_use;
+  }
+  static __device__ __forceinline__ void rescale(WaveState<D>& st, float alpha, bool moved) {
+    if (__any(moved)) {
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) st.o[db][i] *= alpha;
     }
   }
-}
+
+  // two scores -> probabilities (elements 2*i, 2*i+1 of the tile) into their bf16 operand slot
+  static __device__ __forceinline__ void two_probs(const floatx16& s, int i, float scale_log2, float m_use,
+                                                   float& lsum, bf16x8 (&pb)[2]) {
+    const float p0 = fast_exp2(fmaf(s[2 * i], scale_log2, -m_use));
+    const float p1 = fast_exp2(fmaf(s[2 * i + 1], scale_log2, -m_use));
+    lsum += p0 + p1;
+    pb[(2 * i) / 8][(2 * i) % 8] = (__bf16)p0;
+    pb[(2 * i) / 8][(2 * i) % 8 + 1] = (__bf16)p1;
+  }
+
+  // k_addr / v_addr: LDS byte address of tile A's K / V tile plus the lane's Geo::k_lane / v_lane
+  static __device__ __forceinline__ void run(WaveState<D>& st, unsigned k_addr, unsigned v_addr, float scale_log2) {
+    static_assert(DK == 8 || DK == 4, "head_dim 128 or 64");
+    constexpr unsigned kNextTile = 2 * G_::TILE_BYTES;  // tile B's K (V) tile follows tile A's K and V
+    auto v_frag = [&](unsigned tile_off, int j, int db) {
+      return lds_read_tr2((v_addr ^ (db << 6)) + tile_off + 16 * j * G_::ROW_BYTES, 8 * G_::ROW_BYTES);
+    };
+    // LDS operands are fetched a whole phase ahead of the MFMAs that use them: a read issued
+    // just before its MFMA would expose the LDS latency eight times per phase
+    bf16x8 kf[DK], vf[2 * DB];
+
+    // ---- S(A)
+    floatx16 sA, sB;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) sA[i] = sB[i] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < DK; ++ks) kf[ks] = lds_read128(k_addr ^ (ks << 5));
+#pragma unroll
+    for (int ks = 0; ks < DK; ++ks) sA = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], st.q[ks], sA, 0, 0, 0);
+    // (scheduling fences between the phases: left alone, the compiler hoists the next phase's
+    // LDS reads above this phase and runs out of registers)
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int ks = 0; ks < DK; ++ks) kf[ks] = lds_read128((k_addr ^ (ks << 5)) + kNextTile);  // lands while the chain drains
+
+    // ---- softmax(A) between the MFMAs of S(B)
+    bf16x8 pA[2], pB[2];
+    float lsum = 0.f;
+    float alpha;
+    bool moved;
+    const float mA = new_reference(st, sA, scale_log2, alpha, moved);
+    rescale(st, alpha, moved);
+#pragma unroll
+    for (int ks = 0; ks < DK; ++ks) {
+      sB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], st.q[ks], sB, 0, 0, 0);
+#pragma unroll
+      for (int i = ks * (8 / DK); i < (ks + 1) * (8 / DK); ++i) two_probs(sA, i, scale_log2, mA, lsum, pA);
+    }
+    st.l += lsum;
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---- softmax(B) between the MFMAs of O += V(A)^T . P(A)^T
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int db = 0; db < DB; ++db) vf[j * DB + db] = v_frag(0, j, db);
+    lsum = 0.f;
+    const float mB = new_reference(st, sB, scale_log2, alpha, moved);  // accumulators: after P(A) V(A) below
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        st.o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[j * DB + db], pA[j], st.o[db], 0, 0, 0);
+        constexpr int PER = 8 / (2 * DB);  // pairs of scores per MFMA
+#pragma unroll
+        for (int i = (j * DB + db) * PER; i < (j * DB + db + 1) * PER; ++i)
+          two_probs(sB, i, scale_log2, mB, lsum, pB);
+      }
+    st.l += lsum;
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int db = 0; db < DB; ++db) vf[j * DB + db] = v_frag(kNextTile, j, db);
+    rescale(st, alpha, moved);
+
+    // ---- O += V(B)^T . P(B)^T
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+        st.o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[j * DB + db], pB[j], st.o[db], 0, 0, 0);
+  }
+};
 
 #ifdef JK_TIMING
 __device__ unsigned long long g_jk_ts[4096 * 8];
@@ -326,41 +502,44 @@ __device__ unsigned long long g_jk_ts[4096 * 8];
 #endif
 
 // LDS plan of one workgroup, shared by the kernel and its launcher.
-template <int D, int WM, int WN>
+template <int D, int WM, int WN, int KT>
 struct Plan {
   using G_ = Geo<D>;
   static constexpr int NW = WM * WN;                    // waves
   static constexpr int THREADS = 64 * NW;
-  static constexpr int RING_TILES = WN >= 4 ? 2 * WN : 4;  // K+V tile pairs resident in LDS
-  static constexpr int NR = RING_TILES / WN;            // rounds resident in the ring
+  static constexpr int TPR = WN * KT;                   // tiles per round: KT consecutive ones per key column
+  static constexpr int RING_TILES = TPR >= 4 ? 2 * TPR : 4;  // K+V tile pairs resident in LDS
+  static constexpr int NR = RING_TILES / TPR;           // rounds resident in the ring
   static constexpr int QROWS = kWaveRows * WM;
-  static constexpr int STAGE_BYTES = WN * 2 * G_::TILE_BYTES;  // one round: WN tiles of K and V
+  static constexpr int STAGE_BYTES = TPR * 2 * G_::TILE_BYTES;  // one round: TPR tiles of K and V
   static constexpr int RING_BYTES = NR * STAGE_BYTES;
-  static constexpr int OBUF_BYTES = NW * kWaveRows * G_::O_LD * 4;
+  static constexpr int OBUF_BYTES = (WN - 1) * QROWS * G_::O_LD * 4;  // epilogue: O^T of key columns 1..WN-1
   static constexpr int UNION_BYTES = RING_BYTES > OBUF_BYTES ? RING_BYTES : OBUF_BYTES;
   static constexpr int ML_BYTES = NW * kWaveRows * 8;
   static constexpr int SMEM = UNION_BYTES + ML_BYTES + JK_MAX_TREE * 16 + JK_MAX_TREE * 4;
   static constexpr int WGS_PER_CU = 2 * SMEM <= 160 * 1024 && NW <= 4 ? 2 : 1;
+  static constexpr int REG_WGS = NW <= 4 ? 2 : 1;  // register budget: at most 256 VGPRs, no detour through AGPRs
   static_assert(SMEM <= 160 * 1024, "LDS budget");
   static_assert(THREADS >= JK_MAX_TREE, "one thread per tree node in the prologue");
 };
 
-template <int D, int WM, int WN>
-__global__ __launch_bounds__((Plan<D, WM, WN>::THREADS), (Plan<D, WM, WN>::WGS_PER_CU)) void tva_bf16_kernel(
+template <int D, int WM, int WN, int KT>
+__global__ __launch_bounds__((Plan<D, WM, WN, KT>::THREADS), (Plan<D, WM, WN, KT>::REG_WGS)) void tva_bf16_kernel(
     const KParams p) {
   using G_ = Geo<D>;
-  using P_ = Plan<D, WM, WN>;
+  using P_ = Plan<D, WM, WN, KT>;
+  constexpr int TPR = P_::TPR;
   constexpr int DK = G_::DK, DB = G_::DB;
   constexpr int NW = P_::NW, THREADS = P_::THREADS, NR = P_::NR, QROWS = P_::QROWS;
   constexpr int TILE_BYTES = G_::TILE_BYTES;
   constexpr int STAGE_BYTES = P_::STAGE_BYTES;
-  constexpr int DMA_PER_ROUND = WN * LaneChunks<D, NW>::N;  // transfers a wave issues per round
+  constexpr int DMA_PER_ROUND = TPR * LaneChunks<D, NW>::N;  // transfers a wave issues per round
   static_assert(NR >= 2 && (NR - 2) * DMA_PER_ROUND <= 63, "wave arrangement");
 
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];  // the kernel has no other LDS: offset 0
   unsigned char* ring = smem;
-  float* obuf = reinterpret_cast<float*>(smem);                                   // [WN][QROWS][O_LD], after the loop
-  float2* mlbuf = reinterpret_cast<float2*>(smem + P_::UNION_BYTES);              // [WN][QROWS]
+  float* obuf = reinterpret_cast<float*>(smem);                                   // [WN-1][QROWS][O_LD], after the loop
+  float2* mlbuf = reinterpret_cast<float2*>(smem + P_::UNION_BYTES);              // [WN-1][QROWS]
   unsigned long long* anc = reinterpret_cast<unsigned long long*>(smem + P_::UNION_BYTES + P_::ML_BYTES);  // [128][2]
   int* par_s = reinterpret_cast<int*>(smem + P_::UNION_BYTES + P_::ML_BYTES + JK_MAX_TREE * 16);           // [128]
 
@@ -434,36 +613,44 @@ __global__ __launch_bounds__((Plan<D, WM, WN>::THREADS), (Plan<D, WM, WN>::WGS_P
   ts.kc_sl = p.kc_sl;
   ts.kt_st = p.kt_st;
   const int n_ttiles = (T + kTileKeys - 1) / kTileKeys;
-  // Splits are dealt whole rounds (WN tiles): the first R % splits of them one round more than
-  // the rest, and the last one whatever remains, so that the split that ends with the ragged
-  // prefix tile and the masked tree tiles (slower transfers, mask arithmetic, ancestor sets)
-  // never also carries the extra round.
+  // Splits are dealt whole rounds (TPR tiles).  The rounds at the end of the key range that
+  // hold the ragged prefix tile or masked tree tiles are slower (per-lane clamped transfers,
+  // mask arithmetic, ancestor sets first), so each of them counts double when the rounds are
+  // shared out (up to half of a split's share), the surplus going to the first splits: the
+  // split that ends the range then finishes with the others instead of after them.
   auto set_range = [&](int len) {
     ts.L = len;
     ts.n_ptiles = (len + kTileKeys - 1) / kTileKeys;
     const int nt = ts.n_ptiles + n_ttiles;
-    const int R = (nt + WN - 1) / WN;
-    const int base = div_mg(R, p.mg_splits);
-    const int rem = R - base * splits;
-    const int rb = split * base + (split < rem ? split : rem);
-    const int re = rb + base + (split < rem ? 1 : 0);
-    ts.t_begin = rb * WN < nt ? rb * WN : nt;
-    ts.t_end = re * WN < nt ? re * WN : nt;
+    const int R = (nt + TPR - 1) / TPR;
+    const int slow = R - (len / kTileKeys) / TPR;  // rounds that are not all full prefix tiles
+    const int share = div_mg(R, p.mg_splits);
+    const int extra = slow < share / 2 ? slow : share / 2;
+    const int Rv = R + extra;
+    const int base = div_mg(Rv, p.mg_splits);
+    const int rem = Rv - base * splits;
+    int rb = split * base + (split < rem ? split : rem);
+    int re = rb + base + (split < rem ? 1 : 0);
+    rb = rb < R ? rb : R;
+    re = re < R ? re : R;
+    ts.t_begin = rb * TPR < nt ? rb * TPR : nt;
+    ts.t_end = re * TPR < nt ? re * TPR : nt;
   };
-  const unsigned ring_addr = (unsigned)(size_t)LDS_PTR(unsigned char, ring);
+  const unsigned ring_addr = (unsigned)(size_t)LDS_PTR(unsigned char, ring);  // a multiple of 1024
+  const unsigned k_lane = G_::k_lane(lane), v_lane = G_::v_lane(lane);
   LaneChunks<D, NW> lc;
   lane_chunks<D, NW>(lc, wave, lane, ts, p.kc + b * p.kc_sb + (long long)kv * p.kc_sh,
                      p.vc + b * p.kc_sb + (long long)kv * p.kc_sh, p.kt + b * p.kt_sb + (long long)kv * p.kt_sh,
                      p.vt + b * p.kt_sb + (long long)kv * p.kt_sh);
 
   set_range(p.max_prefix);
-  int n_rounds = (ts.t_end - ts.t_begin + WN - 1) / WN;
-  const bool spec_any = n_rounds > 0 && (ts.t_begin + WN) * kTileKeys <= p.max_prefix;  // same for every wave
+  int n_rounds = (ts.t_end - ts.t_begin + TPR - 1) / TPR;
+  const bool spec_any = n_rounds > 0 && (ts.t_begin + TPR) * kTileKeys <= p.max_prefix;  // same for every wave
   int n_spec = 0;  // rounds already issued, all of them full prefix tiles under the assumption
 #pragma unroll
   for (int r = 0; r < NR - 1; ++r)
-    if (n_spec == r && r < n_rounds && (ts.t_begin + (r + 1) * WN) * kTileKeys <= p.max_prefix) {
-      dma_round<D, NW, WN>(r, ts, lc, ring_addr + r * STAGE_BYTES);
+    if (n_spec == r && r < n_rounds && (ts.t_begin + (r + 1) * TPR) * kTileKeys <= p.max_prefix) {
+      dma_round<D, NW, TPR>(r, ts, lc, ring_addr + r * STAGE_BYTES);
       n_spec = r + 1;
     }
   JK_TS(1);
@@ -478,29 +665,39 @@ __global__ __launch_bounds__((Plan<D, WM, WN>::THREADS), (Plan<D, WM, WN>::WGS_P
     }
     n_spec = 0;
     set_range(L);
-    n_rounds = (ts.t_end - ts.t_begin + WN - 1) / WN;
+    n_rounds = (ts.t_end - ts.t_begin + TPR - 1) / TPR;
   }
   const bool has_tree = ts.t_end > ts.n_ptiles;
 #pragma unroll
   for (int r = 0; r < NR - 1; ++r)
-    if (r >= n_spec && r < n_rounds) dma_round<D, NW, WN>(r, ts, lc, ring_addr + r * STAGE_BYTES);
+    if (r >= n_spec && r < n_rounds) dma_round<D, NW, TPR>(r, ts, lc, ring_addr + r * STAGE_BYTES);
 
   JK_TS(3);
-  // ---- ancestor sets (only workgroups that reach tree tiles need them)
+  // ---- ancestor sets (only workgroups that reach tree tiles need them), by pointer
+  // doubling: after k steps a node knows its nearest 2^k ancestors-or-self and its 2^k-th
+  // ancestor, so the number of steps is logarithmic in the depth of the tree rather than
+  // the depth itself (every step is a round trip through LDS)
   if (has_tree) {
-    if (tid < T) par_s[tid] = (my_parent >= -1 && my_parent < tid) ? my_parent : -1;
-    __syncthreads();
+    int up = -1;
+    unsigned long long lo = 0, hi = 0;
     if (tid < T) {
-      unsigned long long lo = 0, hi = 0;
-      int a = tid;
-      while (a >= 0) {  // parent indices strictly decrease, so at most tid+1 steps
-        if (a < 64) lo |= 1ull << a; else hi |= 1ull << (a - 64);
-        a = par_s[a];
-      }
-      anc[2 * tid] = lo;
-      anc[2 * tid + 1] = hi;
+      up = (my_parent >= -1 && my_parent < tid) ? my_parent : -1;  // indices strictly decrease towards the root
+      if (tid < 64) lo = 1ull << tid; else hi = 1ull << (tid - 64);
     }
-    // visibility to the other threads is ordered by the first __syncthreads of the tile loop
+    for (;;) {
+      if (tid < T) {
+        par_s[tid] = up;
+        anc[2 * tid] = lo;
+        anc[2 * tid + 1] = hi;
+      }
+      if (!__syncthreads_or(up >= 0)) break;  // nobody has an ancestor left to fold in: LDS holds the sets
+      if (up >= 0) {
+        lo |= anc[2 * up];
+        hi |= anc[2 * up + 1];
+        up = par_s[up];
+      }
+      __syncthreads();  // every read of this step precedes the next step's writes
+    }
   }
 
 #pragma unroll
@@ -516,50 +713,64 @@ __global__ __launch_bounds__((Plan<D, WM, WN>::THREADS), (Plan<D, WM, WN>::WGS_P
   st.m = -INFINITY;
   st.l = 0.f;
 
-  // tile of this wave in round r: mask mode and LDS addresses
-  auto tile_of = [&](int r, int& t, int& mode, int& nvalid, unsigned int& bits, const unsigned char*& kt_s) {
-    t = ts.t_begin + r * WN + wn;
+  // mask of tile t: mode (see mask_tile), valid keys of a ragged prefix tile, visibility bits
+  auto mask_of = [&](int t, int& mode, int& nvalid, unsigned int& bits) {
     mode = 0;
     nvalid = kTileKeys;
     bits = 0;
-    if (t >= ts.n_ptiles) {
+    if (t >= ts.t_end) {
+      mode = 2;  // past the split: every key hidden (its LDS tile holds a copy of real data)
+    } else if (t >= ts.n_ptiles) {
       const int tt = t - ts.n_ptiles;
       mode = 2;
-      if (t < ts.t_end) bits = (unsigned int)(anc[2 * my_node + (tt >> 1)] >> ((tt & 1) * 32));
+      bits = (unsigned int)(anc[2 * my_node + (tt >> 1)] >> ((tt & 1) * 32));
     } else {
       nvalid = L - t * kTileKeys;
       mode = nvalid < kTileKeys ? 1 : 0;
     }
-    kt_s = ring + (r % NR) * STAGE_BYTES + wn * 2 * TILE_BYTES;
   };
 
-  // ---- main loop.  Round r lives in ring slot r % NR.  Before the barrier a wave waits for
-  // its own transfers of round r; after the barrier every wave's have landed, and every wave
-  // has finished round r-1, whose slot is therefore free for round r+NR-1.
+  // ---- main loop.  Round r lives in ring slot r % NR; wave column wn takes tiles
+  // (r*WN + wn)*KT .. +KT-1 of the split.  Before the barrier a wave waits for its own
+  // transfers of round r; after the barrier every wave's have landed, and every wave has
+  // finished round r-1, whose slot is therefore free for round r+NR-1.
   for (int r = 0; r < n_rounds; ++r) {
     const int ahead = n_rounds - 1 - r;  // rounds issued after r: min(NR-2, ahead)
     wait_dma<DMA_PER_ROUND>(ahead < NR - 2 ? ahead : NR - 2);
     __syncthreads();
     if (r == 0) JK_TS(4);
     if (r + NR - 1 < n_rounds)
-      dma_round<D, NW, WN>(r + NR - 1, ts, lc, ring_addr + ((r + NR - 1) % NR) * STAGE_BYTES);
-    int t, mode, nvalid;
-    unsigned int bits;
-    const unsigned char* kt_s;
-    tile_of(r, t, mode, nvalid, bits, kt_s);
-    if (t < ts.t_end) {
-      const floatx16 sacc = qk_tile<D>(st, kt_s, lane);
-      softmax_pv_tile<D>(st, sacc, kt_s + TILE_BYTES, mode, nvalid, bits, scale_log2, lane);
+      dma_round<D, NW, TPR>(r + NR - 1, ts, lc, ring_addr + ((r + NR - 1) % NR) * STAGE_BYTES);
+    const int tb = ts.t_begin + (r * WN + wn) * KT;
+    const unsigned tile_a = ring_addr + (r % NR) * STAGE_BYTES + wn * KT * 2 * TILE_BYTES;  // K of the first tile
+    if (KT == 2 && (tb + 2) * kTileKeys <= L && tb + 2 <= ts.t_end) {
+      PairPipe<D>::run(st, tile_a + k_lane, tile_a + TILE_BYTES + v_lane, scale_log2);  // two full prefix tiles
+    } else if (tb < ts.t_end) {
+      int mode, nvalid;
+      unsigned int bits;
+      floatx16 s0, s1;
+      qk_tiles<D, KT>(st, tile_a + k_lane, s0, s1);
+      mask_of(tb, mode, nvalid, bits);
+      mask_tile(s0, mode, nvalid, bits, g);
+      if (KT == 2) {
+        mask_of(tb + 1, mode, nvalid, bits);
+        mask_tile(s1, mode, nvalid, bits, g);
+      }
+      softmax_pv<D, KT>(st, s0, s1, tile_a + TILE_BYTES + v_lane, scale_log2);
     }
   }
   JK_TS(5);
   __syncthreads();  // every wave is done with the ring before it becomes the epilogue buffer
 
-  // ---- epilogue: O^T and (max, sum) of each wave into LDS
-  {
-    const float l_tot = half_swap_sum(st.l);
-    const int row = wm * kWaveRows + c32;
-    float* orow = obuf + ((size_t)wn * QROWS + row) * G_::O_LD;
+  // ---- epilogue: the waves of key column 0 own the result of their 32 rows.  The other
+  // columns park their O^T and (max, sum) in LDS (the ring is dead by now); the owners fold
+  // them into their own accumulators, register for register (all waves share one layout),
+  // and store straight from that layout: lane (row, g) holds, per 32-wide block db and
+  // quarter q4, the 4 columns 32*db + 8*q4 + 4*g .. +3 of its row.
+  const float l_own = half_swap_sum(st.l);
+  const int row = wm * kWaveRows + c32;
+  if (wn != 0) {
+    float* orow = obuf + ((size_t)(wn - 1) * QROWS + row) * G_::O_LD;
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -567,77 +778,78 @@ __global__ __launch_bounds__((Plan<D, WM, WN>::THREADS), (Plan<D, WM, WN>::WGS_P
         float4 v = make_float4(st.o[db][4 * q4], st.o[db][4 * q4 + 1], st.o[db][4 * q4 + 2], st.o[db][4 * q4 + 3]);
         *reinterpret_cast<float4*>(orow + 32 * db + 8 * q4 + 4 * g) = v;
       }
-    if (g == 0) mlbuf[wn * QROWS + row] = make_float2(st.m, l_tot);
+    if (g == 0) mlbuf[(wn - 1) * QROWS + row] = make_float2(st.m, l_own);
   }
-  __syncthreads();
-
+  if (WN > 1) __syncthreads();
   JK_TS(6);
-  // ---- merge the WN key-interleaved waves, then write the split's partial (or the result).
-  // Item `it` is 4 consecutive output columns of one row; the trip count is a constant so
-  // that the iterations' LDS reads overlap.
-  constexpr int D4 = D / 4;
-  constexpr int ITERS = QROWS * D4 / THREADS;
-  static_assert(QROWS * D4 % THREADS == 0, "merge items divide evenly");
-  const long long unit = (long long)(b * p.Hkv + kv);
+  if (wn == 0) {
+    float mx = st.m;
 #pragma unroll
-  for (int k = 0; k < ITERS; ++k) {
-    const int it = tid + k * THREADS;
-    const int row = it / D4, d4 = it % D4;
-    const int m = qtile * QROWS + row;
-    float mx = -INFINITY;
-#pragma unroll
-    for (int w = 0; w < WN; ++w) mx = fmaxf(mx, mlbuf[w * QROWS + row].x);
+    for (int w = 1; w < WN; ++w) mx = fmaxf(mx, mlbuf[(w - 1) * QROWS + row].x);
     const float mx_use = (mx == -INFINITY) ? 0.f : mx;
-    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    float lsum = 0.f;
+    float lsum = l_own;
+    if (WN > 1) {
+      const float w0 = fast_exp2(st.m - mx_use);
+      lsum *= w0;
 #pragma unroll
-    for (int w = 0; w < WN; ++w) {
-      const float2 ml = mlbuf[w * QROWS + row];
-      const float wgt = fast_exp2(ml.x - mx_use);
-      const float4 o = *reinterpret_cast<const float4*>(obuf + ((size_t)w * QROWS + row) * G_::O_LD + 4 * d4);
-      acc.x = fmaf(o.x, wgt, acc.x);
-      acc.y = fmaf(o.y, wgt, acc.y);
-      acc.z = fmaf(o.z, wgt, acc.z);
-      acc.w = fmaf(o.w, wgt, acc.w);
-      lsum = fmaf(ml.y, wgt, lsum);
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) st.o[db][i] *= w0;
+#pragma unroll
+      for (int w = 1; w < WN; ++w) {
+        const float2 ml = mlbuf[(w - 1) * QROWS + row];
+        const float wgt = fast_exp2(ml.x - mx_use);
+        lsum = fmaf(ml.y, wgt, lsum);
+        const float* orow = obuf + ((size_t)(w - 1) * QROWS + row) * G_::O_LD;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int q4 = 0; q4 < 4; ++q4) {
+            const float4 v = *reinterpret_cast<const float4*>(orow + 32 * db + 8 * q4 + 4 * g);
+            st.o[db][4 * q4] = fmaf(v.x, wgt, st.o[db][4 * q4]);
+            st.o[db][4 * q4 + 1] = fmaf(v.y, wgt, st.o[db][4 * q4 + 1]);
+            st.o[db][4 * q4 + 2] = fmaf(v.z, wgt, st.o[db][4 * q4 + 2]);
+            st.o[db][4 * q4 + 3] = fmaf(v.w, wgt, st.o[db][4 * q4 + 3]);
+          }
+      }
     }
-    if (m >= M) continue;
-    if (splits == 1) {
-      const float inv = 1.f / lsum;  // lsum > 0: every row sees at least its own tree key
-      const int node = div_mg(m, p.mg_g), hg = m - node * G;
-      uint16_t* dst = p.out + b * p.o_sb + node * p.o_st + (long long)(kv * G + hg) * p.o_sh + 4 * d4;
-      bf16x2 lo, hi;
-      lo[0] = (__bf16)(acc.x * inv);
-      lo[1] = (__bf16)(acc.y * inv);
-      hi[0] = (__bf16)(acc.z * inv);
-      hi[1] = (__bf16)(acc.w * inv);
-      uint2 pk;
-      pk.x = __builtin_bit_cast(unsigned int, lo);
-      pk.y = __builtin_bit_cast(unsigned int, hi);
-      *reinterpret_cast<uint2*>(dst) = pk;
-    } else {
-      // partial output in bf16 (the running max and sum stay fp32): the partials are written,
-      // flushed and read back once per split, and are the largest avoidable traffic of a call
-      const long long prow = (unit * splits + split) * p.m_pad + m;
-      bf16x2 lo, hi;
-      lo[0] = (__bf16)acc.x;
-      lo[1] = (__bf16)acc.y;
-      hi[0] = (__bf16)acc.z;
-      hi[1] = (__bf16)acc.w;
-      uint2 pk;
-      pk.x = __builtin_bit_cast(unsigned int, lo);
-      pk.y = __builtin_bit_cast(unsigned int, hi);
-      *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(p.part_o) + prow * D + 4 * d4) = pk;
-      if (d4 == 0) p.part_ml[prow] = make_float2(mx, lsum);
+    if (row_ok) {
+      // the final result (no splits), or the split's partial in bf16 (the running max and sum
+      // stay fp32): the partials are written, flushed and read back once per split, and are
+      // the largest avoidable traffic of a call
+      uint16_t* dst;
+      float mul = 1.f;
+      if (splits == 1) {
+        mul = 1.f / lsum;  // lsum > 0: every row sees at least its own tree key
+        dst = p.out + b * p.o_sb + my_node * p.o_st + (long long)(kv * G + (m_row - my_node * G)) * p.o_sh;
+      } else {
+        const long long prow = ((long long)unit_id * splits + split) * p.m_pad + m_row;
+        dst = reinterpret_cast<uint16_t*>(p.part_o) + prow * D;
+        if (g == 0) p.part_ml[prow] = make_float2(mx, lsum);
+      }
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          bf16x2 lo, hi;
+          lo[0] = (__bf16)(st.o[db][4 * q4] * mul);
+          lo[1] = (__bf16)(st.o[db][4 * q4 + 1] * mul);
+          hi[0] = (__bf16)(st.o[db][4 * q4 + 2] * mul);
+          hi[1] = (__bf16)(st.o[db][4 * q4 + 3] * mul);
+          uint2 pk;
+          pk.x = __builtin_bit_cast(unsigned int, lo);
+          pk.y = __builtin_bit_cast(unsigned int, hi);
+          *reinterpret_cast<uint2*>(dst + 32 * db + 8 * q4 + 4 * g) = pk;
+        }
     }
   }
   JK_TS(7);
 }
 
-template <int D, int WM, int WN>
+template <int D, int WM, int WN, int KT>
 hipError_t launch_one(const KParams& kp, hipStream_t stream) {
-  using P_ = Plan<D, WM, WN>;
-  auto kern = tva_bf16_kernel<D, WM, WN>;
+  using P_ = Plan<D, WM, WN, KT>;
+  auto kern = tva_bf16_kernel<D, WM, WN, KT>;
   static bool lds_limit_raised = false;  // idempotent, so a race between host threads is harmless
   if (!lds_limit_raised) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -686,14 +898,12 @@ hipError_t launch_tva_bf16(const AttnArgs& a, const AttnPlan& pl, hipStream_t st
   kp.mg_hkv = magic(d.n_kv_heads);
   kp.mg_g = magic(kp.G);
 
-  const int key = d.head_dim * 100 + pl.wm * 10 + pl.wn;
+  const int key = d.head_dim * 1000 + pl.wm * 100 + pl.wn * 10 + pl.kt;
   switch (key) {
-    case 12841: return launch_one<128, 4, 1>(kp, stream);
-    case 12822: return launch_one<128, 2, 2>(kp, stream);
-    case 12824: return launch_one<128, 2, 4>(kp, stream);
-    case 6441: return launch_one<64, 4, 1>(kp, stream);
-    case 6422: return launch_one<64, 2, 2>(kp, stream);
-    case 6424: return launch_one<64, 2, 4>(kp, stream);
+    case 128412: return launch_one<128, 4, 1, 2>(kp, stream);
+    case 128221: return launch_one<128, 2, 2, 1>(kp, stream);
+    case 64412: return launch_one<64, 4, 1, 2>(kp, stream);
+    case 64221: return launch_one<64, 2, 2, 1>(kp, stream);
     default: return hipErrorInvalidValue;
   }
 }
