@@ -1,6 +1,7 @@
 // C-ABI entry points of libjakiro_verify: argument checks, launch planning,
 // kernel launches.  No device memory is allocated here and nothing synchronises.
 #include <cmath>
+#include <cstdio>
 #include <cstdlib>
 #include <cstring>
 
@@ -70,11 +71,19 @@ bool make_attn_plan(const jk_attn_desc& d, int max_prefix_len, AttnPlan* pl) {
       if (s > max_by_tiles) s = max_by_tiles;
       if (s > kMaxSplits) s = kMaxSplits;
       if (forced_s >= 1 && forced_s <= kMaxSplits) s = forced_s;
-      // partial outputs are written, flushed at the kernel boundary and read back: weigh them double
-      const double partial = s > 1 ? 4.0 * s * pl->m_rows * d.head_dim * 2.0 : 0.0;
-      // one workgroup per CU already reaches most of the throughput; the second hides latencies
-      const double fill = 0.5 + 0.5 * (double)(wgs * s < slots ? wgs * s : slots) / slots;
-      const double cost = (kv_bytes * (1.0 + 0.25 * (n_qtiles - 1)) + partial) / fill;
+      // Estimated time of a call, in microseconds, from what was measured on an MI355X at
+      // head_dim 128: a workgroup runs a round (2 tiles per key column) in about 0.95 us as
+      // 2x2 waves and 1.4 us as 4x1 waves (which cover twice the rows, hand-pipelined);
+      // workgroups beyond one per CU share its throughput; the K/V stream (re-read from L2
+      // by the row tiles at a quarter of the price) moves at about 4 TB/s; partial outputs
+      // (bf16, written, flushed at the kernel boundary and read back) cost about 0.28 us per MB.
+      const double t_round = (wn == 1 ? 1.4 : 0.95) * d.head_dim / 128.0;
+      const double rounds = (double)((n_tiles + wn * kt - 1) / (wn * kt)) / (double)s;
+      const double share = (double)(wgs * s) / slots > 1.0 ? (double)(wgs * s) / slots : 1.0;
+      const double loop_us = rounds * t_round * share;
+      const double stream_us = (double)units * kv_bytes * (1.0 + 0.25 * (n_qtiles - 1)) / 4.0e6;
+      const double partial_us = s > 1 ? 0.28e-6 * (double)units * s * pl->m_rows * d.head_dim * 2.0 : 0.0;
+      const double cost = (loop_us > stream_us ? loop_us : stream_us) + partial_us;
       if (!have || cost < best_cost) {
         have = true;
         best_cost = cost;
@@ -100,6 +109,9 @@ bool make_attn_plan(const jk_attn_desc& d, int max_prefix_len, AttnPlan* pl) {
   pl->part_ml_bytes = need_parts ? up(rows * sizeof(float2)) : 0;
   pl->total_bytes = pl->part_o_bytes + pl->part_ml_bytes;
   if (pl->total_bytes == 0) pl->total_bytes = 256;  // never ask the caller for a zero-byte buffer
+  if (std::getenv("JK_ATTN_VERBOSE"))
+    std::fprintf(stderr, "jk attention plan: waves %dx%d, %d tile(s) per wave and round, %d row tile(s), %d split(s)\n",
+                 pl->wm, pl->wn, pl->kt, pl->n_qtiles, pl->splits);
   return true;
 }
 
