@@ -514,7 +514,10 @@ struct Plan {
   static constexpr int STAGE_BYTES = TPR * 2 * G_::TILE_BYTES;  // one round: TPR tiles of K and V
   static constexpr int RING_BYTES = NR * STAGE_BYTES;
   static constexpr int OBUF_BYTES = (WN - 1) * QROWS * G_::O_LD * 4;  // epilogue: O^T of key columns 1..WN-1
-  static constexpr int UNION_BYTES = RING_BYTES > OBUF_BYTES ? RING_BYTES : OBUF_BYTES;
+  static constexpr int PATCH_LD = D * 2 + 16;                         // padded bf16 row of the store patches
+  static constexpr int PATCH_BYTES = kWaveRows * PATCH_LD;            // one owner wave's 32 finished rows
+  static constexpr int EPI_BYTES = OBUF_BYTES + WM * PATCH_BYTES;
+  static constexpr int UNION_BYTES = RING_BYTES > EPI_BYTES ? RING_BYTES : EPI_BYTES;
   static constexpr int ML_BYTES = NW * kWaveRows * 8;
   static constexpr int SMEM = UNION_BYTES + ML_BYTES + JK_MAX_TREE * 16 + JK_MAX_TREE * 4;
   static constexpr int WGS_PER_CU = 2 * SMEM <= 160 * 1024 && NW <= 4 ? 2 : 1;
@@ -813,20 +816,19 @@ __global__ __launch_bounds__((Plan<D, WM, WN, KT>::THREADS), (Plan<D, WM, WN, KT
           }
       }
     }
-    if (row_ok) {
-      // the final result (no splits), or the split's partial in bf16 (the running max and sum
-      // stay fp32): the partials are written, flushed and read back once per split, and are
-      // the largest avoidable traffic of a call
-      uint16_t* dst;
-      float mul = 1.f;
-      if (splits == 1) {
-        mul = 1.f / lsum;  // lsum > 0: every row sees at least its own tree key
-        dst = p.out + b * p.o_sb + my_node * p.o_st + (long long)(kv * G + (m_row - my_node * G)) * p.o_sh;
-      } else {
-        const long long prow = ((long long)unit_id * splits + split) * p.m_pad + m_row;
-        dst = reinterpret_cast<uint16_t*>(p.part_o) + prow * D;
-        if (g == 0) p.part_ml[prow] = make_float2(mx, lsum);
-      }
+    // ---- store.  The accumulator layout gives a lane 4 columns here and 4 there of one row:
+    // stored as it is, every instruction would touch 32 rows with 16 bytes each.  So the wave
+    // first lays its 32 finished rows out in LDS as bf16 (a private patch behind the parked
+    // columns) and reads them back row-wise: 16 lanes x 16 bytes per row, whole 128-byte lines
+    // per store.  Holds the final result (no splits) or the split's partial in bf16 (the
+    // running max and sum stay fp32): partials are written, flushed and read back once per
+    // split, and are the largest avoidable traffic of a call.
+    const float mul = splits == 1 ? 1.f / lsum : 1.f;  // lsum > 0: every row sees at least its own tree key
+    const long long prow0 = ((long long)unit_id * splits + split) * p.m_pad + qtile * QROWS + wm * kWaveRows;
+    if (splits > 1 && row_ok && g == 0) p.part_ml[prow0 + c32] = make_float2(mx, lsum);
+    unsigned char* patch = smem + P_::OBUF_BYTES + wm * P_::PATCH_BYTES;
+    {
+      unsigned char* prow = patch + c32 * P_::PATCH_LD;
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -839,8 +841,28 @@ __global__ __launch_bounds__((Plan<D, WM, WN, KT>::THREADS), (Plan<D, WM, WN, KT
           uint2 pk;
           pk.x = __builtin_bit_cast(unsigned int, lo);
           pk.y = __builtin_bit_cast(unsigned int, hi);
-          *reinterpret_cast<uint2*>(dst + 32 * db + 8 * q4 + 4 * g) = pk;
+          *reinterpret_cast<uint2*>(prow + (32 * db + 8 * q4 + 4 * g) * 2) = pk;
         }
+    }
+    // (same wave wrote and reads: LDS operations of a wave complete in order)
+    constexpr int CPR = G_::CPR;             // 16-byte chunks per row
+    constexpr int RPI = 64 / CPR;            // rows per store instruction
+    const int chunk = lane % CPR, rsub = lane / CPR;
+#pragma unroll
+    for (int k = 0; k < kWaveRows / RPI; ++k) {
+      const int rr = k * RPI + rsub;                               // row of the wave
+      const int m = qtile * QROWS + wm * kWaveRows + rr;           // query row
+      const u32x4 v = *reinterpret_cast<const u32x4*>(patch + rr * P_::PATCH_LD + chunk * 16);
+      if (m < M) {
+        uint16_t* dst;
+        if (splits == 1) {
+          const int node = div_mg(m, p.mg_g);
+          dst = p.out + b * p.o_sb + node * p.o_st + (long long)(kv * G + (m - node * G)) * p.o_sh;
+        } else {
+          dst = reinterpret_cast<uint16_t*>(p.part_o) + (prow0 + rr) * D;
+        }
+        *reinterpret_cast<u32x4*>(dst + chunk * 8) = v;
+      }
     }
   }
   JK_TS(7);
