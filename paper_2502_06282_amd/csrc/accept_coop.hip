@@ -36,13 +36,39 @@ struct Slot {  // 32 bytes
 
 struct CoopParams {
   int n_tree, vocab, max_depth, W, slice;
-  double temp;
+  double inv_temp;  // 1 / temperature
   const int *tokens, *parent;
   const float *logits, *draft, *uniforms;
   unsigned long long* epoch;  // [batch] workspace words, each bumped once per call by its tree
   Slot* slots;                // [batch][2][W]
   int *out_path, *out_len, *out_bonus;
 };
+
+// e^x for x <= 0 in fp64 (every exponent of the walk is a difference to a maximum): argument
+// reduction by ln 2 in two pieces, Taylor polynomial of degree 13 on |r| <= ln(2)/2
+// (truncation below 5e-18 relative), scaling by v_ldexp_f64.  A fraction of the instructions
+// of the general library routine, which the walk would otherwise run thousands of times.
+__device__ __forceinline__ double exp_nonpos(double x) {
+  if (!(x > -745.2)) return 0.0;  // underflow, -inf
+  const double k = rint(x * 1.4426950408889634074);
+  double r = fma(k, -6.93147180369123816490e-01, x);
+  r = fma(k, -1.90821492927058770002e-10, r);
+  double q = 1.0 / 6227020800.0;
+  q = fma(q, r, 1.0 / 479001600.0);
+  q = fma(q, r, 1.0 / 39916800.0);
+  q = fma(q, r, 1.0 / 3628800.0);
+  q = fma(q, r, 1.0 / 362880.0);
+  q = fma(q, r, 1.0 / 40320.0);
+  q = fma(q, r, 1.0 / 5040.0);
+  q = fma(q, r, 1.0 / 720.0);
+  q = fma(q, r, 1.0 / 120.0);
+  q = fma(q, r, 1.0 / 24.0);
+  q = fma(q, r, 1.0 / 6.0);
+  q = fma(q, r, 0.5);
+  q = fma(q, r, 1.0);
+  q = fma(q, r, 1.0);
+  return ldexp(q, (int)k);
+}
 
 __device__ __forceinline__ double block_sum(double v, double* red) {
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
@@ -62,14 +88,17 @@ __device__ __forceinline__ double block_max(double v, double* red) {
 __global__ __launch_bounds__(kCoopThreads) void walk_sample_coop_kernel(CoopParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   double* cur = reinterpret_cast<double*>(smem);   // [slice] current distribution of my slice
-  double* nxt = cur + p.slice;                     // [slice] candidate residual
   __shared__ double red[4];
   __shared__ double xa[64], xb[64];                // the W partials of an exchange
   __shared__ unsigned xh[256];                     // their 32-bit halves as they arrive
   __shared__ int par_s[JK_MAX_TREE];
+  __shared__ int tok_s[JK_MAX_TREE];
   __shared__ int s_fail, s_found;
-  __shared__ double rej_s[JK_MAX_TREE];            // residual masses of the rejected siblings at this node
+  __shared__ double xw[64];                        // weights of the W partial softmax sums
+  __shared__ double rej_inv[JK_MAX_TREE];          // 1 / residual mass of the rejected siblings at this node
   __shared__ int rej_k[JK_MAX_TREE];
+  __shared__ float pf_q[JK_MAX_TREE + 2];          // prefetched scalars of the next candidate (see below)
+  __shared__ float uni_s[JK_MAX_TREE + 1];
 
   const int tid = threadIdx.x;
   const int W = p.W;
@@ -77,17 +106,32 @@ __global__ __launch_bounds__(kCoopThreads) void walk_sample_coop_kernel(CoopPara
   const int N = p.n_tree, V = p.vocab, rows = N + 1;
   const int v_lo = min(V, w * p.slice), v_hi = min(V, v_lo + p.slice);
   const int n_mine = v_hi - v_lo;
+  constexpr int kPer = 4096 / kCoopThreads;        // slice elements per thread at most
 
+  // the tree's small arrays: loads go out now, the values are parked in LDS after the first
+  // logits row has been processed (nothing needs them before), so their latency is hidden
+  int pa_reg = -1, tok_reg = 0;
+  float uni_reg = 0.f;
   if (tid < N) {
-    const int pa = p.parent[(long long)b * N + tid];
-    par_s[tid] = (pa >= -1 && pa < tid) ? pa : -1;
+    pa_reg = p.parent[(long long)b * N + tid];
+    tok_reg = p.tokens[(long long)b * N + tid];
   }
+  if (tid <= N) uni_reg = p.uniforms[(long long)b * rows + tid];
   if (tid == 0) s_fail = 0;
   const unsigned long long epoch = __hip_atomic_load(p.epoch + b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   __syncthreads();
 
-  const int* tok = p.tokens + (long long)b * N;
-  const float* uni = p.uniforms + (long long)b * rows;
+  // smallest j >= from with parent c, or -1: every wave looks at all (at most 128) nodes, two
+  // per lane, so no barrier is needed and all waves get the same answer
+  auto find_child = [&](int c, int from) -> int {
+    const int lane = tid & 63;
+    const bool h0 = lane < N && lane >= from && par_s[lane] == c;
+    const bool h1 = lane + 64 < N && lane + 64 >= from && par_s[lane + 64] == c;
+    const unsigned long long m0 = __ballot(h0), m1 = __ballot(h1);
+    return m0 ? __ffsll((long long)m0) - 1 : (m1 ? 63 + __ffsll((long long)m1) : -1);
+  };
+
+  const int n_per = (p.slice + kCoopThreads - 1) / kCoopThreads;  // slice elements per thread (uniform)
   Slot* slots = p.slots + (long long)b * 2 * 64;
   unsigned n_exch = 0;
 
@@ -95,7 +139,7 @@ __global__ __launch_bounds__(kCoopThreads) void walk_sample_coop_kernel(CoopPara
   // Tags: 22 bits of call epoch, 10 bits of exchange number (at most N + depth + 2 < 1024 per
   // call).  Both tables are rewritten by every call (a call has at least two exchanges), so
   // a stale word is at most one epoch old and can never carry the current tag.
-  auto exchange = [&](double a, double bb) {
+  auto exchange = [&](double a, double bb, double pad_a) {
     ++n_exch;
     const unsigned tag = (unsigned)(((epoch + 1) & 0x3FFFFFull) << 10) | (n_exch & 0x3FFu);
     Slot* tab = slots + (n_exch & 1) * W;
@@ -119,91 +163,182 @@ __global__ __launch_bounds__(kCoopThreads) void walk_sample_coop_kernel(CoopPara
     if (tid < W) {
       xa[tid] = __longlong_as_double((long long)(((unsigned long long)xh[4 * tid + 1] << 32) | xh[4 * tid]));
       xb[tid] = __longlong_as_double((long long)(((unsigned long long)xh[4 * tid + 3] << 32) | xh[4 * tid + 2]));
+    } else if (tid < 64) {
+      xa[tid] = pad_a;  // the reductions below always run over 64 entries
+      xb[tid] = 0.0;
     }
     __syncthreads();
   };
+  // sum of 64 LDS doubles in a fixed order (four interleaved chains): identical in every workgroup
+  auto sum64 = [&](const double* v) {
+    double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
+#pragma unroll
+    for (int i = 0; i < 64; i += 4) {
+      a0 += v[i];
+      a1 += v[i + 1];
+      a2 += v[i + 2];
+      a3 += v[i + 3];
+    }
+    return (a0 + a1) + (a2 + a3);
+  };
 
-  double row_m = 0.0, row_z = 1.0;  // max of row/T and sum of exp(row/T - max) of the current row
+  double row_m = 0.0, row_inv_z = 1.0;  // max of row/T, and 1 / sum of exp(row/T - max), of the current row
   const float* row = nullptr;
 
-  // softmax of logits row r over my slice into cur[]; (row_m, row_z) for everybody
+  // softmax of logits row r over my slice into cur[]; (row_m, row_inv_z) for everybody
   auto load_row = [&](int r) {
     row = p.logits + ((long long)b * rows + r) * V;
+    double z[kPer];
     double lm = -INFINITY;
-    for (int i = tid; i < n_mine; i += kCoopThreads) {
-      const double z = (double)row[v_lo + i] / p.temp;
-      cur[i] = z;
-      lm = fmax(lm, z);
+#pragma unroll
+    for (int u = 0; u < kPer; ++u) {
+      if (u >= n_per) break;
+      const int i = tid + u * kCoopThreads;
+      z[u] = i < n_mine ? (double)row[v_lo + i] * p.inv_temp : -INFINITY;
+      lm = fmax(lm, z[u]);
     }
     const double m_w = block_max(lm, red);
     const double m_use = (m_w == -INFINITY) ? 0.0 : m_w;
     double ls = 0.0;
-    for (int i = tid; i < n_mine; i += kCoopThreads) {
-      const double e = exp(cur[i] - m_use);
-      cur[i] = e;
-      ls += e;
+#pragma unroll
+    for (int u = 0; u < kPer; ++u) {
+      if (u >= n_per) break;
+      z[u] = exp_nonpos(z[u] - m_use);
+      ls += z[u];
     }
     const double z_w = block_sum(ls, red);
-    exchange(m_w, z_w);
-    double M = -INFINITY;
-    for (int i = 0; i < W; ++i) M = fmax(M, xa[i]);
+    exchange(m_w, z_w, -INFINITY);
+    double M0 = -INFINITY, M1 = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < 64; i += 2) {
+      M0 = fmax(M0, xa[i]);
+      M1 = fmax(M1, xa[i + 1]);
+    }
+    const double M = fmax(M0, M1);
     const double M_use = (M == -INFINITY) ? 0.0 : M;
-    double Z = 0.0;
-    for (int i = 0; i < W; ++i)
-      if (xa[i] != -INFINITY) Z += xb[i] * exp(xa[i] - M_use);
+    if (tid < 64) xw[tid] = xb[tid] * exp_nonpos(xa[tid] - M_use);  // 0 for an empty slice (-inf) and for the padding
+    __syncthreads();
+    const double Z = sum64(xw);  // same numbers, same order in every workgroup
     row_m = M_use;
-    row_z = Z;
-    const double sc = exp(m_use - M_use) / Z;
-    for (int i = tid; i < n_mine; i += kCoopThreads) cur[i] *= sc;
+    row_inv_z = 1.0 / Z;
+    const double sc = exp_nonpos(m_use - M_use) * row_inv_z;
+#pragma unroll
+    for (int u = 0; u < kPer; ++u) {
+      if (u >= n_per) break;
+      const int i = tid + u * kCoopThreads;
+      if (i < n_mine) cur[i] = z[u] * sc;
+    }
     __syncthreads();
   };
 
-  int c = -1, len = 0, k = 0, n_rej = 0;
+  // Scalars a candidate's test needs, gathered by one thread each and parked in LDS:
+  // pf_q[i] = q_{rej_k[i]}[x] for the n_rej siblings rejected so far, then q_child[x], then
+  // logits_row[x], with x the candidate's token.  `extra` >= 0 adds one more (pending)
+  // rejected sibling to the list: the gather for the next sibling is issued before the
+  // current one's fate is known, so that its latency hides behind the exchange.
+  auto gather_issue = [&](int child, int n_rej, int extra) -> float {
+    const int x = tok_s[child];
+    const int n_list = n_rej + (extra >= 0 ? 1 : 0);
+    float v = 0.f;
+    if (tid < n_list) {
+      const int kq = tid < n_rej ? rej_k[tid] : extra;
+      v = p.draft[((long long)b * N + kq) * V + x];
+    } else if (tid == n_list) {
+      v = p.draft[((long long)b * N + child) * V + x];
+    } else if (tid == n_list + 1) {
+      v = row[x];
+    }
+    return v;
+  };
+  auto gather_park = [&](float v, int n_list) {
+    if (tid < n_list + 2) pf_q[tid] = v;
+  };
+
+  int c = -1, len = 0, n_rej = 0;
   load_row(0);
-  while (!s_fail) {
-    int child = -1;
-    for (int j = k; j < N; ++j)
-      if (par_s[j] == c) { child = j; break; }
-    if (child < 0) break;
-    const int x = min(max(tok[child], 0), V - 1);  // a token id outside the vocabulary must not fault
+  if (tid < N) {
+    par_s[tid] = (pa_reg >= -1 && pa_reg < tid) ? pa_reg : -1;
+    tok_s[tid] = min(max(tok_reg, 0), V - 1);  // a token id outside the vocabulary must not fault
+  }
+  if (tid <= N) uni_s[tid] = uni_reg;
+  __syncthreads();
+  int child = find_child(-1, 0);
+  bool have_pf = false;     // pf_q[] and qreg[] already hold `child`'s data
+  float qreg[kPer];         // q_child over my slice
+  while (!s_fail && child >= 0) {
     const float* qk = p.draft + ((long long)b * N + child) * V;
+    if (!have_pf) {
+      const float v = gather_issue(child, n_rej, -1);
+#pragma unroll
+      for (int u = 0; u < kPer; ++u) {
+        const int i = tid + u * kCoopThreads;
+        qreg[u] = i < n_mine ? qk[v_lo + i] : 0.f;
+      }
+      gather_park(v, n_rej);
+      __syncthreads();
+    }
     // probability of token x under the current distribution: the same chain of operations in
     // every workgroup (global data only), so that all take the same decision
-    double px = exp((double)row[x] / p.temp - row_m) / row_z;
-    for (int i = 0; i < n_rej; ++i) {
-      const float* qi = p.draft + ((long long)b * N + rej_k[i]) * V;
-      px = fmax(0.0, px - (double)qi[x]) / rej_s[i];
-    }
-    const double lhs = (double)uni[child] * (double)qk[x];
+    double px = exp_nonpos((double)pf_q[n_rej + 1] * p.inv_temp - row_m) * row_inv_z;
+    for (int i = 0; i < n_rej; ++i) px = fmax(0.0, px - (double)pf_q[i]) * rej_inv[i];
+    const double lhs = (double)uni_s[child] * (double)pf_q[n_rej];
     if (lhs < px) {
       if (len < p.max_depth && tid == 0 && w == 0) p.out_path[(long long)b * p.max_depth + len] = child;
       ++len;
       c = child;
-      k = child + 1;
       n_rej = 0;
+      have_pf = false;
+      __syncthreads();  // pf_q is rewritten for the first child
       load_row(c + 1);
+      child = find_child(c, c + 1);
       continue;
     }
     // rejected: candidate residual of my slice and its mass
     double part = 0.0;
-    for (int i = tid; i < n_mine; i += kCoopThreads) {
-      const double r = fmax(0.0, cur[i] - (double)qk[v_lo + i]);
-      nxt[i] = r;
-      part += r;
+    double res[kPer];
+#pragma unroll
+    for (int u = 0; u < kPer; ++u) {
+      if (u >= n_per) break;
+      const int i = tid + u * kCoopThreads;
+      res[u] = i < n_mine ? fmax(0.0, cur[i] - (double)qreg[u]) : 0.0;
+      part += res[u];
+    }
+    // the next sibling's data go out now; they arrive while the exchange is under way
+    const int nxt_child = find_child(c, child + 1);
+    float pv = 0.f;
+    float qnext[kPer];
+    if (nxt_child >= 0) {
+      pv = gather_issue(nxt_child, n_rej, child);
+      const float* qn = p.draft + ((long long)b * N + nxt_child) * V;
+#pragma unroll
+      for (int u = 0; u < kPer; ++u) {
+        const int i = tid + u * kCoopThreads;
+        qnext[u] = i < n_mine ? qn[v_lo + i] : 0.f;
+      }
     }
     const double s_w = block_sum(part, red);
-    exchange(s_w, 0.0);
-    double s = 0.0;
-    for (int i = 0; i < W; ++i) s += xa[i];
+    exchange(s_w, 0.0, 0.0);
+    const double s = sum64(xa);
+    have_pf = false;
     if (s > 0.0) {
-      for (int i = tid; i < n_mine; i += kCoopThreads) cur[i] = nxt[i] / s;
-      if (tid == 0) { rej_k[n_rej] = child; rej_s[n_rej] = s; }
+      const double inv_s = 1.0 / s;
+#pragma unroll
+      for (int u = 0; u < kPer; ++u) {
+        const int i = tid + u * kCoopThreads;
+        if (i < n_mine) cur[i] = res[u] * inv_s;
+      }
+      if (tid == 0) { rej_k[n_rej] = child; rej_inv[n_rej] = inv_s; }
+      if (nxt_child >= 0) {  // the prefetched list assumed exactly this rejection
+        gather_park(pv, n_rej + 1);
+#pragma unroll
+        for (int u = 0; u < kPer; ++u) qreg[u] = qnext[u];  // (registers: nothing to skip)
+        have_pf = true;
+      }
       ++n_rej;
-      __syncthreads();
     }
-    k = child + 1;
+    __syncthreads();
+    child = nxt_child;
   }
-
   // ---- final draw: smallest v whose cumulative probability exceeds u * total
   if (!s_fail) {
     double part = 0.0;
@@ -236,7 +371,7 @@ __global__ __launch_bounds__(kCoopThreads) void walk_sample_coop_kernel(CoopPara
     for (int i = 0; i < (tid >> 6); ++i) woff += red[i];
     const double t_w = ((red[0] + red[1]) + red[2]) + red[3];
     const int lp_w = max(max(s_lp[0], s_lp[1]), max(s_lp[2], s_lp[3]));
-    exchange(t_w, (double)lp_w);
+    exchange(t_w, (double)lp_w, 0.0);
     if (!s_fail) {
       double before = 0.0, total = 0.0;
       int last_any = -1;
@@ -245,7 +380,7 @@ __global__ __launch_bounds__(kCoopThreads) void walk_sample_coop_kernel(CoopPara
         total += xa[i];
         last_any = max(last_any, (int)xb[i]);
       }
-      const double target = (double)uni[N] * total;
+      const double target = (double)uni_s[N] * total;
       if (tid == 0) s_found = -1;
       __syncthreads();
       // is the crossing inside my segment?
@@ -306,7 +441,7 @@ bool accept_coop_plan(int batch, int vocab, int cus, int* W, int* slice) {
   if (w > 64) w = 64;
   if (w < 1) return false;
   const int sl = (vocab + w - 1) / w;
-  if (sl > 4096) return false;  // 2 x 4096 doubles of LDS per workgroup
+  if (sl > 4096) return false;  // 4096 doubles of LDS and 16 slice elements per thread
   *W = w;
   *slice = sl;
   return true;
@@ -315,17 +450,17 @@ bool accept_coop_plan(int batch, int vocab, int cus, int* W, int* slice) {
 hipError_t launch_accept_coop(const AcceptArgs& a, void* coop_ws, int W, int slice, hipStream_t stream) {
   CoopParams cp;
   cp.n_tree = a.n_tree; cp.vocab = a.vocab; cp.max_depth = a.max_depth; cp.W = W; cp.slice = slice;
-  cp.temp = (double)a.temperature;
+  cp.inv_temp = 1.0 / (double)a.temperature;
   cp.tokens = a.tokens; cp.parent = a.parent;
   cp.logits = a.logits; cp.draft = a.draft_probs; cp.uniforms = a.uniforms;
   cp.epoch = static_cast<unsigned long long*>(coop_ws);
   cp.slots = reinterpret_cast<Slot*>(static_cast<char*>(coop_ws) + coop_header_bytes(a.batch));
   cp.out_path = a.out_path; cp.out_len = a.out_len; cp.out_bonus = a.out_bonus;
-  const size_t lds = (size_t)2 * slice * sizeof(double);
+  const size_t lds = (size_t)slice * sizeof(double);
   static bool lds_limit_raised = false;
   if (!lds_limit_raised) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(walk_sample_coop_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 2 * 4096 * 8);
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 4096 * 8);
     if (e != hipSuccess) return e;
     lds_limit_raised = true;
   }
