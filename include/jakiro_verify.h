@@ -107,11 +107,14 @@ size_t jk_tree_verify_attention_workspace(const jk_attn_desc* desc, int32_t max_
  * Supported: JK_BF16 with head_dim 64 or 128 (MFMA path), JK_F32 with
  * head_dim <= 256 and a multiple of 4 and max_prefix_len + n_tree <= 65536
  * (plain-ALU path); 1 <= n_tree <= JK_MAX_TREE;
- * n_q_heads a multiple of n_kv_heads.  Value rows of tree nodes that a query
+ * n_q_heads a multiple of n_kv_heads; JK_BF16: kc_stride_l and kt_stride_t at
+ * most 2^24 elements (JK_ERR_UNSUPPORTED beyond).  Value rows of tree nodes that a query
  * cannot see must be finite (they are multiplied by an exact zero); their key
  * rows, and anything in the cache beyond prefix_len, are never used.
  * Accumulation is fp32; JK_BF16 rounds the softmax weights to bf16 before the
- * value product. */
+ * value product and, when the key range is split over several workgroups, the
+ * partial outputs to bf16 before they are merged (running maxima and sums stay
+ * fp32). */
 jk_status jk_tree_verify_attention(const jk_attn_desc* desc, const void* q, const void* k_cache,
                                    const void* v_cache, const void* k_tree, const void* v_tree,
                                    const int32_t* parent, const int32_t* prefix_len,

@@ -145,6 +145,8 @@ jk_status jk_tree_verify_attention(const jk_attn_desc* desc, const void* q, cons
   for (int64_t s : strides)
     if (s < 0 || s % align) return JK_ERR_INVALID_ARG;
   if (d.q_stride_t < d.head_dim && d.n_tree > 1) return JK_ERR_INVALID_ARG;
+  // the bf16 kernel addresses a tile's rows with 32-bit byte offsets from the tile's first row
+  if (d.dtype == JK_BF16 && (d.kc_stride_l > (1 << 24) || d.kt_stride_t > (1 << 24))) return JK_ERR_UNSUPPORTED;
   const void* ptrs[] = {q, k_cache, v_cache, k_tree, v_tree, out};
   for (const void* p : ptrs)
     if (reinterpret_cast<uintptr_t>(p) % (align * es)) return JK_ERR_INVALID_ARG;
