@@ -10,7 +10,7 @@ from workloads import CONFIGS, attention_inputs, coin_tree, round_to_bf16, tree_
 
 pytestmark = pytest.mark.gpu
 
-from gpu_util import check_attention, gpu_attention  # noqa: E402
+from gpu_util import check_attention, gpu_attention, oracle_attention  # noqa: E402
 
 BF16_TOL, F32_TOL = 2e-2, 1e-5
 
@@ -155,6 +155,36 @@ def test_bf16_split_invariance(monkeypatch):
         outs.append(gpu_attention(x, par, [2000], "bf16"))
     for o in outs[1:]:
         assert np.abs(o - outs[0]).max() <= 2.0 ** -7 * np.abs(outs[0]).max()
+
+
+@pytest.mark.parametrize("wm,wn", [(2, 2), (4, 1)], ids=["2x2", "4x1"])
+@pytest.mark.parametrize("L", [0, 31, 64, 97, 130, 257, 1000])
+def test_bf16_wave_arrangements(monkeypatch, wm, wn, L):
+    """Both workgroup arrangements (the 4x1 one takes its tiles in hand-pipelined pairs) over prefix
+    lengths that leave full pairs, a lone tile, a ragged tile and tree tiles in every position of a
+    round, unsplit and with three splits."""
+    monkeypatch.setenv("JK_ATTN_WM", str(wm))
+    monkeypatch.setenv("JK_ATTN_WN", str(wn))
+    cfg = _cfg("c3_llama3_8b", batch=2, prefix_len=L, n_q_heads=8, n_kv_heads=2)
+    par = tree_for_config(cfg, seed=L)
+    x = attention_inputs(cfg, seed=L, scale_mult=np.sqrt(128.0))
+    for s in ("1", "3"):
+        monkeypatch.setenv("JK_ATTN_SPLITS", s)
+        check_attention(x, par, [L, L // 2], "bf16", BF16_TOL, rel_tol=2e-2)
+
+
+@pytest.mark.parametrize("wm,wn", [(2, 2), (4, 1)], ids=["2x2", "4x1"])
+def test_bf16_prefix_shorter_than_bound(monkeypatch, wm, wn):
+    """The first K/V transfers go out on the assumption prefix_len == max_prefix_len; here it is
+    not, for one sequence by a lot and for the other by one key."""
+    monkeypatch.setenv("JK_ATTN_WM", str(wm))
+    monkeypatch.setenv("JK_ATTN_WN", str(wn))
+    cfg = _cfg("c3_llama3_8b", batch=2, prefix_len=1500, n_q_heads=8, n_kv_heads=2)
+    par = tree_for_config(cfg)
+    x = attention_inputs(cfg, scale_mult=np.sqrt(128.0))
+    ref = oracle_attention(**x, parent=par, prefix_len=[200, 1499])
+    got = gpu_attention(x, par, [200, 1499], "bf16", max_prefix_len=1500)
+    assert np.abs(got - ref).max() <= BF16_TOL
 
 
 def test_c2_full_size_sampled_rows():
