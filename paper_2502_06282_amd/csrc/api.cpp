@@ -64,30 +64,36 @@ bool make_attn_plan(const jk_attn_desc& d, int max_prefix_len, AttnPlan* pl) {
       const int q_rows = 32 * wm;
       const int n_qtiles = (pl->m_rows + q_rows - 1) / q_rows;
       const long long wgs = units * n_qtiles;
-      const long long s_full = (slots + wgs - 1) / wgs;  // splits that fill every resident slot
       const int kt = wn == 1 ? 2 : 1;  // a lone key column pairs its tiles (hand-pipelined two-tile path)
       const int max_by_tiles = n_tiles / (2 * wn * kt) > 0 ? n_tiles / (2 * wn * kt) : 1;  // >= 2 rounds per split
-      long long s = s_full;
-      if (s > max_by_tiles) s = max_by_tiles;
-      if (s > kMaxSplits) s = kMaxSplits;
-      if (forced_s >= 1 && forced_s <= kMaxSplits) s = forced_s;
-      // Estimated time of a call, in microseconds, from what was measured on an MI355X at
-      // head_dim 128: a workgroup runs a round (2 tiles per key column) in about 0.95 us as
-      // 2x2 waves and 1.4 us as 4x1 waves (which cover twice the rows, hand-pipelined);
-      // workgroups beyond one per CU share its throughput; the K/V stream (re-read from L2
-      // by the row tiles at a quarter of the price) moves at about 4 TB/s; partial outputs
-      // (bf16, written, flushed at the kernel boundary and read back) cost about 0.28 us per MB.
-      const double t_round = (wn == 1 ? 1.4 : 0.95) * d.head_dim / 128.0;
-      const double rounds = (double)((n_tiles + wn * kt - 1) / (wn * kt)) / (double)s;
-      const double share = (double)(wgs * s) / slots > 1.0 ? (double)(wgs * s) / slots : 1.0;
-      const double loop_us = rounds * t_round * share;
-      const double stream_us = (double)units * kv_bytes * (1.0 + 0.25 * (n_qtiles - 1)) / 4.0e6;
-      const double partial_us = s > 1 ? 0.28e-6 * (double)units * s * pl->m_rows * d.head_dim * 2.0 : 0.0;
-      const double cost = (loop_us > stream_us ? loop_us : stream_us) + partial_us;
-      if (!have || cost < best_cost) {
-        have = true;
-        best_cost = cost;
-        pl->wm = wm; pl->wn = wn; pl->kt = kt; pl->q_rows = q_rows; pl->n_qtiles = n_qtiles; pl->splits = (int)s;
+      // split counts worth a look: one workgroup per CU, or (nearly) two
+      const long long cand[3] = {(slots + wgs - 1) / wgs, 2 * slots / wgs, (2 * slots + wgs - 1) / wgs};
+      for (int ci = 0; ci < 3; ++ci) {
+        long long s = cand[ci] < 1 ? 1 : cand[ci];
+        if (s > max_by_tiles) s = max_by_tiles;
+        if (s > kMaxSplits) s = kMaxSplits;
+        if (forced_s >= 1 && forced_s <= kMaxSplits) s = forced_s;
+        // Estimated time of a call, in microseconds, from what was measured on an MI355X at
+        // head_dim 128: a workgroup runs a round (2 tiles per key column) in about 0.95 us as
+        // 2x2 waves and 1.4 us as 4x1 waves (which cover twice the rows, hand-pipelined);
+        // workgroups beyond one per CU share its throughput; the K/V stream (re-read from L2
+        // by the row tiles at a quarter of the price) moves at about 4 TB/s while every CU
+        // pulls, so CUs with one workgroup more than the average stretch it; partial outputs
+        // (bf16, written, flushed at the kernel boundary and read back) cost about 0.28 us per MB.
+        const double t_round = (wn == 1 ? 1.4 : 0.95) * d.head_dim / 128.0;
+        const double rounds = (double)((n_tiles + wn * kt - 1) / (wn * kt)) / (double)s;
+        const double per_cu = (double)(wgs * s) / slots;
+        const double share = per_cu > 1.0 ? per_cu : 1.0;
+        const double imbalance = per_cu > 1.0 ? std::ceil(per_cu) / per_cu : 1.0;
+        const double loop_us = rounds * t_round * share;
+        const double stream_us = imbalance * (double)units * kv_bytes * (1.0 + 0.25 * (n_qtiles - 1)) / 4.0e6;
+        const double partial_us = s > 1 ? 0.28e-6 * (double)units * s * pl->m_rows * d.head_dim * 2.0 : 0.0;
+        const double cost = (loop_us > stream_us ? loop_us : stream_us) + partial_us;
+        if (!have || cost < best_cost) {
+          have = true;
+          best_cost = cost;
+          pl->wm = wm; pl->wn = wn; pl->kt = kt; pl->q_rows = q_rows; pl->n_qtiles = n_qtiles; pl->splits = (int)s;
+        }
       }
     }
     if (!have) return false;
