@@ -66,9 +66,11 @@ bool make_attn_plan(const jk_attn_desc& d, int max_prefix_len, AttnPlan* pl) {
       const long long wgs = units * n_qtiles;
       const int kt = wn == 1 ? 2 : 1;  // a lone key column pairs its tiles (hand-pipelined two-tile path)
       const int max_by_tiles = n_tiles / (2 * wn * kt) > 0 ? n_tiles / (2 * wn * kt) : 1;  // >= 2 rounds per split
-      // split counts worth a look: one workgroup per CU, or (nearly) two
-      const long long cand[3] = {(slots + wgs - 1) / wgs, 2 * slots / wgs, (2 * slots + wgs - 1) / wgs};
-      for (int ci = 0; ci < 3; ++ci) {
+      // split counts worth a look: one workgroup per CU, (nearly) two, and a few multiples
+      // (smaller workgroups even out the load when there are more of them than CUs)
+      const long long s1 = (slots + wgs - 1) / wgs;
+      const long long cand[6] = {s1, 2 * slots / wgs, (2 * slots + wgs - 1) / wgs, 2 * s1, 4 * s1, 8 * s1};
+      for (int ci = 0; ci < 6; ++ci) {
         long long s = cand[ci] < 1 ? 1 : cand[ci];
         if (s > max_by_tiles) s = max_by_tiles;
         if (s > kMaxSplits) s = kMaxSplits;
@@ -83,7 +85,7 @@ bool make_attn_plan(const jk_attn_desc& d, int max_prefix_len, AttnPlan* pl) {
         const double t_round = (wn == 1 ? 1.4 : 0.95) * d.head_dim / 128.0;
         const double rounds = (double)((n_tiles + wn * kt - 1) / (wn * kt)) / (double)s;
         const double per_cu = (double)(wgs * s) / slots;
-        const double share = per_cu > 1.0 ? per_cu : 1.0;
+        const double share = per_cu > 1.0 ? per_cu + 0.5 : 1.0;  // + half a workgroup of tail
         const double imbalance = per_cu > 1.0 ? std::ceil(per_cu) / per_cu : 1.0;
         const double loop_us = rounds * t_round * share;
         const double stream_us = imbalance * (double)units * kv_bytes * (1.0 + 0.25 * (n_qtiles - 1)) / 4.0e6;
