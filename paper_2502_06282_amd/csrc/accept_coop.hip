@@ -44,32 +44,6 @@ struct CoopParams {
   int *out_path, *out_len, *out_bonus;
 };
 
-// e^x for x <= 0 in fp64 (every exponent of the walk is a difference to a maximum): argument
-// reduction by ln 2 in two pieces, Taylor polynomial of degree 13 on |r| <= ln(2)/2
-// (truncation below 5e-18 relative), scaling by v_ldexp_f64.  A fraction of the instructions
-// of the general library routine, which the walk would otherwise run thousands of times.
-__device__ __forceinline__ double exp_nonpos(double x) {
-  if (!(x > -745.2)) return 0.0;  // underflow, -inf
-  const double k = rint(x * 1.4426950408889634074);
-  double r = fma(k, -6.93147180369123816490e-01, x);
-  r = fma(k, -1.90821492927058770002e-10, r);
-  double q = 1.0 / 6227020800.0;
-  q = fma(q, r, 1.0 / 479001600.0);
-  q = fma(q, r, 1.0 / 39916800.0);
-  q = fma(q, r, 1.0 / 3628800.0);
-  q = fma(q, r, 1.0 / 362880.0);
-  q = fma(q, r, 1.0 / 40320.0);
-  q = fma(q, r, 1.0 / 5040.0);
-  q = fma(q, r, 1.0 / 720.0);
-  q = fma(q, r, 1.0 / 120.0);
-  q = fma(q, r, 1.0 / 24.0);
-  q = fma(q, r, 1.0 / 6.0);
-  q = fma(q, r, 0.5);
-  q = fma(q, r, 1.0);
-  q = fma(q, r, 1.0);
-  return ldexp(q, (int)k);
-}
-
 __device__ __forceinline__ double block_sum(double v, double* red) {
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
   __syncthreads();
@@ -203,7 +177,7 @@ __global__ __launch_bounds__(kCoopThreads) void walk_sample_coop_kernel(CoopPara
 #pragma unroll
     for (int u = 0; u < kPer; ++u) {
       if (u >= n_per) break;
-      z[u] = exp_nonpos(z[u] - m_use);
+      z[u] = exp(z[u] - m_use);
       ls += z[u];
     }
     const double z_w = block_sum(ls, red);
@@ -216,12 +190,12 @@ __global__ __launch_bounds__(kCoopThreads) void walk_sample_coop_kernel(CoopPara
     }
     const double M = fmax(M0, M1);
     const double M_use = (M == -INFINITY) ? 0.0 : M;
-    if (tid < 64) xw[tid] = xb[tid] * exp_nonpos(xa[tid] - M_use);  // 0 for an empty slice (-inf) and for the padding
+    if (tid < 64) xw[tid] = xb[tid] * exp(xa[tid] - M_use);  // 0 for an empty slice (-inf) and for the padding
     __syncthreads();
     const double Z = sum64(xw);  // same numbers, same order in every workgroup
     row_m = M_use;
     row_inv_z = 1.0 / Z;
-    const double sc = exp_nonpos(m_use - M_use) * row_inv_z;
+    const double sc = exp(m_use - M_use) * row_inv_z;
 #pragma unroll
     for (int u = 0; u < kPer; ++u) {
       if (u >= n_per) break;
@@ -279,7 +253,7 @@ __global__ __launch_bounds__(kCoopThreads) void walk_sample_coop_kernel(CoopPara
     }
     // probability of token x under the current distribution: the same chain of operations in
     // every workgroup (global data only), so that all take the same decision
-    double px = exp_nonpos((double)pf_q[n_rej + 1] * p.inv_temp - row_m) * row_inv_z;
+    double px = exp((double)pf_q[n_rej + 1] * p.inv_temp - row_m) * row_inv_z;
     for (int i = 0; i < n_rej; ++i) px = fmax(0.0, px - (double)pf_q[i]) * rej_inv[i];
     const double lhs = (double)uni_s[child] * (double)pf_q[n_rej];
     if (lhs < px) {
