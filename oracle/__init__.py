@@ -2,9 +2,11 @@
 
 Plain, slow, fp64 NumPy restatements of what the verification step of the
 paper computes (Section 2.1 steps 2-3; the tree attention mask of Section
-3.1.2 / Fig. "tree attention mask").  Only tests, the smoke check and the
+3.1.2 / Fig. "tree attention mask"), and of the commit of the accepted path to
+the KV cache that follows it.  Only tests, the smoke check and the
 benchmark's CPU-baseline leg may import this package; it shares no code with
 the HIP library and never calls it.
 """
 from .tree_attention import ancestor_sets, tree_verify_attention  # noqa: F401
 from .accept_path import accept_path, AcceptResult  # noqa: F401
+from .commit_path import commit_path, committed_rows  # noqa: F401
