@@ -211,6 +211,43 @@ def main():
     es1.record()
     torch.cuda.synchronize()
     probe_us = es0.elapsed_time(es1) * 1e3 / (5 * args.layers)
+    # the step after the path (not part of the timed step): commit of a full-depth accepted path to
+    # every layer's cache in one call, rows landing in the last `depth` rows of the caches, length not advanced
+    chain = []
+    for i in range(cfg.n_tree):
+        c, a = [], i
+        while a >= 0:
+            c.append(a)
+            a = int(par[0, a])
+        if len(c) > len(chain):
+            chain = c[::-1]
+    chain = (chain + [-1] * cfg.depth)[:cfg.depth]
+    n_commit = sum(1 for v in chain if v >= 0)
+    c_path = torch.tensor([chain] * cfg.batch, dtype=torch.int32, device=dev)
+    c_len = torch.full((cfg.batch,), n_commit, dtype=torch.int32, device=dev)
+    c_plen = torch.full((cfg.batch,), cfg.prefix_len - n_commit, dtype=torch.int32, device=dev)
+    commit_call = jk.prepare_commit_path_layers([lyr["k_tree"] for lyr in layers], [lyr["v_tree"] for lyr in layers],
+                                                [lyr["k_cache"] for lyr in layers], [lyr["v_cache"] for lyr in layers],
+                                                c_path, c_len, c_plen, advance=False)
+    def commit_pass():  # 16 calls per graph replay, so that the replay's own cost does not hide the call's
+        for _ in range(16):
+            commit_call.launch()
+    commit_pass()
+    torch.cuda.synchronize()
+    g_commit = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g_commit, stream=torch.cuda.Stream()):
+        commit_pass()
+    g_commit.replay()
+    torch.cuda.synchronize()
+    ec0, ec1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ec0.record()
+    for _ in range(5):
+        g_commit.replay()
+    ec1.record()
+    torch.cuda.synchronize()
+    commit_us = ec0.elapsed_time(ec1) * 1e3 / (5 * 16)
+    commit_bytes = args.layers * 4 * cfg.batch * n_commit * cfg.n_kv_heads * cfg.head_dim * layers[0]["k_cache"].element_size()
+
     for _ in range(args.copy_calibration):
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)
@@ -245,6 +282,10 @@ def main():
         "stream_read_probe": {"bytes_per_launch": probe_bytes, "us_per_launch": round(probe_us, 3),
                               "GBps": round(probe_bytes / (probe_us * 1e-6) / 1e9, 1),
                               "note": "pure 128-bit read kernel, one launch per 16.8 MB buffer of a 32-buffer ring, HIP-graph replay"},
+        "commit_path": {"us_per_call": round(commit_us, 3), "rows_per_sequence": n_commit,
+                        "bytes_per_call": commit_bytes,
+                        "layers": args.layers,
+                        "note": "one jk_commit_path_layers call for all layers after the step (not in ms_per_step)"},
         "roofline": {"bound": "hbm", "achieved": round(gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(gbps / HBM_PEAK_GBPS, 4), "traffic": MEASURED_TRAFFIC.get(cfg.name),
                      "kernel": "tva_bf16_kernel (+ tva_combine_kernel): time per jk_tree_verify_attention call",

@@ -165,6 +165,43 @@ jk_status jk_accept_path(int32_t batch, int32_t n_tree, int32_t vocab, int32_t m
                          int32_t* out_accept_len, int32_t* out_bonus_token, void* workspace,
                          size_t workspace_bytes, void* hip_stream);
 
+/* Commit of the accepted path to one layer's KV cache (Section 2.1 step 3:
+ * accepted tokens are appended to the sequence, the rest of the draft is
+ * dropped).  For every sequence b and i < n_b the K and V rows (all KV heads) of
+ * tree node path[b][i] are copied to cache position prefix_len[b] + i; with
+ * `advance` != 0 prefix_len[b] then grows by n_b (the caches of all layers share
+ * one length: set it on the last layer's call only).  n_b is accept_len[b] cut
+ * to [0, max_depth], ended in front of the first path entry outside [0, n_tree)
+ * and limited to the room left (cache_capacity - prefix_len[b]): a walk that
+ * gave up (accept_len -1) commits nothing.  The token the target adds after
+ * the last accepted node has no key/value yet and is not part of this call.
+ *
+ *   desc         as for jk_tree_verify_attention; only batch, n_tree, n_kv_heads,
+ *                head_dim, dtype and the kc_ / kt_ strides are used
+ *   k_tree, v_tree    device, read      [batch, n_tree, n_kv_heads, head_dim]
+ *   k_cache, v_cache  device, written   [batch, cache_capacity, n_kv_heads, head_dim]
+ *   path         device int32 [batch, max_depth] as written by jk_accept_path
+ *   accept_len   device int32 [batch]
+ *   prefix_len   device int32 [batch], read; written iff advance != 0
+ *
+ * Pointers and strides obey the alignment rules of the attention call (whole
+ * 16-byte chunks).  Nothing is allocated; no workspace is needed. */
+jk_status jk_commit_path(const jk_attn_desc* desc, const void* k_tree, const void* v_tree, void* k_cache,
+                         void* v_cache, const int32_t* path, const int32_t* accept_len, int32_t max_depth,
+                         int32_t cache_capacity, int32_t* prefix_len, int32_t advance, void* hip_stream);
+
+/* The same commit for all layers of a model in one launch (a layer's copy is a
+ * few tens of KB: a launch per layer costs more than the copies).  k_tree,
+ * v_tree, k_cache and v_cache are DEVICE arrays of n_layers device pointers, one
+ * tensor per layer, all of the shape, strides and dtype that `desc` gives and
+ * 16-byte aligned (they live on the device, so the library cannot check them).
+ * path, accept_len and prefix_len are shared by the layers; `advance` applies
+ * once.  1 <= n_layers <= 65535. */
+jk_status jk_commit_path_layers(const jk_attn_desc* desc, int32_t n_layers, const void* const* k_tree,
+                                const void* const* v_tree, void* const* k_cache, void* const* v_cache,
+                                const int32_t* path, const int32_t* accept_len, int32_t max_depth,
+                                int32_t cache_capacity, int32_t* prefix_len, int32_t advance, void* hip_stream);
+
 /* Zero-fills a workspace with a small kernel on `hip_stream` (safe under HIP-graph
  * capture).  Needed once per workspace before its first jk_accept_path call: the
  * cooperative sampling walk synchronises its workgroups through tagged words in

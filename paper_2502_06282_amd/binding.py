@@ -39,7 +39,7 @@ class AttnDesc(ctypes.Structure):
 _lib = None
 
 EXPORTS = ("jk_tree_verify_attention_workspace", "jk_tree_verify_attention", "jk_accept_path_workspace",
-           "jk_accept_path", "jk_workspace_init", "jk_stream_read_probe", "jk_validate_tree", "jk_status_string", "jk_version")
+           "jk_accept_path", "jk_commit_path", "jk_commit_path_layers", "jk_workspace_init", "jk_stream_read_probe", "jk_validate_tree", "jk_status_string", "jk_version")
 
 
 def library_path() -> str:
@@ -65,6 +65,10 @@ def lib() -> ctypes.CDLL:
         l.jk_accept_path.restype = i32
         l.jk_accept_path.argtypes = [i32, i32, i32, i32, vp, vp, vp, i32, ctypes.c_float, vp, vp, vp, vp,
                                      vp, vp, sz, vp]
+        l.jk_commit_path.restype = i32
+        l.jk_commit_path.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp, i32, i32, vp, i32, vp]
+        l.jk_commit_path_layers.restype = i32
+        l.jk_commit_path_layers.argtypes = [ctypes.POINTER(AttnDesc), i32, vp, vp, vp, vp, vp, vp, i32, i32, vp, i32, vp]
         l.jk_workspace_init.restype = i32
         l.jk_workspace_init.argtypes = [vp, sz, vp]
         l.jk_stream_read_probe.restype = i32
@@ -244,6 +248,62 @@ def prepare_tree_verify_attention(q, k_cache, v_cache, k_tree, v_tree, parent, p
             workspace.numel() * workspace.element_size(), None]
     return PreparedCall(lib().jk_tree_verify_attention, "jk_tree_verify_attention", args, 12,
                         (d, q, k_cache, v_cache, k_tree, v_tree, parent, prefix_len, out, workspace))
+
+
+def _commit_args(k_tree, v_tree, k_cache, v_cache, path, accept_len, prefix_len, advance):
+    import torch
+    B, T, Hkv, D = k_tree.shape
+    if k_tree.dtype == torch.bfloat16:
+        dt = JK_BF16
+    elif k_tree.dtype == torch.float32:
+        dt = JK_F32
+    else:
+        raise TypeError("k_tree must be bfloat16 or float32")
+    if v_tree.stride() != k_tree.stride() or v_cache.stride() != k_cache.stride():
+        raise ValueError("K and V must share strides")
+    for t in (k_tree, k_cache):
+        if t.stride(-1) != 1 and t.shape[-1] > 1:
+            raise ValueError("head_dim must be the contiguous innermost axis")
+    d = AttnDesc(B, T, Hkv, Hkv, D, 0, 0, 0, k_cache.stride(0), k_cache.stride(1), k_cache.stride(2),
+                 k_tree.stride(0), k_tree.stride(1), k_tree.stride(2), 0, 0, 0, 0.0, dt)
+    return d, [_ptr(k_tree), _ptr(v_tree), _ptr(k_cache), _ptr(v_cache), _ptr(path), _ptr(accept_len),
+               int(path.shape[1]), int(k_cache.shape[1]), _ptr(prefix_len), 1 if advance else 0]
+
+
+def commit_path(k_tree, v_tree, k_cache, v_cache, path, accept_len, prefix_len, advance: bool = True,
+                stream=None) -> None:
+    """jk_commit_path: copies the K/V rows of the accepted nodes path[b][:accept_len[b]] to the cache
+    positions prefix_len[b]..., in place; advances prefix_len (device int32 [B]) when `advance`."""
+    d, args = _commit_args(k_tree, v_tree, k_cache, v_cache, path, accept_len, prefix_len, advance)
+    st = lib().jk_commit_path(ctypes.byref(d), *args, _stream_handle(stream))
+    if st != 0:
+        raise JakiroError(st, "jk_commit_path")
+
+
+def prepare_commit_path(k_tree, v_tree, k_cache, v_cache, path, accept_len, prefix_len,
+                        advance: bool = True) -> "PreparedCall":
+    """Same arguments as commit_path; nothing is launched."""
+    d, args = _commit_args(k_tree, v_tree, k_cache, v_cache, path, accept_len, prefix_len, advance)
+    return PreparedCall(lib().jk_commit_path, "jk_commit_path", [ctypes.byref(d)] + args + [None], 11,
+                        (d, k_tree, v_tree, k_cache, v_cache, path, accept_len, prefix_len))
+
+
+def prepare_commit_path_layers(k_trees, v_trees, k_caches, v_caches, path, accept_len, prefix_len,
+                               advance: bool = True) -> "PreparedCall":
+    """jk_commit_path_layers for lists of per-layer tensors (all of one shape, dtype and stride set): builds the
+    device pointer tables once; `launch()` commits every layer with one call."""
+    import torch
+    n = len(k_trees)
+    for ts in (k_trees, v_trees, k_caches, v_caches):
+        if len(ts) != n or any(t.stride() != ts[0].stride() or t.shape != ts[0].shape for t in ts):
+            raise ValueError("per-layer tensors must share shape and strides")
+    d, args = _commit_args(k_trees[0], v_trees[0], k_caches[0], v_caches[0], path, accept_len, prefix_len, advance)
+    tables = [torch.tensor([t.data_ptr() for t in ts], dtype=torch.int64, device=path.device)
+              for ts in (k_trees, v_trees, k_caches, v_caches)]
+    call_args = [ctypes.byref(d), n] + [_ptr(t) for t in tables] + args[4:] + [None]
+    return PreparedCall(lib().jk_commit_path_layers, "jk_commit_path_layers", call_args, 12,
+                        (d, tables, list(k_trees), list(v_trees), list(k_caches), list(v_caches), path, accept_len,
+                         prefix_len))
 
 
 def prepare_accept_path(tree_tokens, parent, target_logits, mode, temperature, draft_probs, uniforms, out_path,

@@ -222,6 +222,55 @@ jk_status jk_accept_path(int32_t batch, int32_t n_tree, int32_t vocab, int32_t m
   return launch_accept(a, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? JK_OK : JK_ERR_HIP;
 }
 
+static jk_status commit_common(const jk_attn_desc* desc, int n_layers, const void* k_tree, const void* v_tree,
+                               void* k_cache, void* v_cache, const int32_t* path, const int32_t* accept_len,
+                               int32_t max_depth, int32_t cache_capacity, int32_t* prefix_len, int32_t advance,
+                               void* hip_stream) {
+  if (!desc || !k_tree || !v_tree || !k_cache || !v_cache || !path || !accept_len || !prefix_len)
+    return JK_ERR_INVALID_ARG;
+  const jk_attn_desc& d = *desc;
+  if (d.batch < 1 || d.n_tree < 1 || d.n_tree > JK_MAX_TREE || d.n_kv_heads < 1 || d.head_dim < 1)
+    return JK_ERR_INVALID_ARG;
+  if (d.dtype != JK_BF16 && d.dtype != JK_F32) return JK_ERR_INVALID_ARG;
+  if (max_depth < 1 || cache_capacity < 1) return JK_ERR_INVALID_ARG;
+  if ((long long)d.batch * max_depth > 0x7fffffffLL || n_layers > 65535) return JK_ERR_UNSUPPORTED;
+  const int64_t es = d.dtype == JK_BF16 ? 2 : 4;
+  const int64_t align = 16 / es;  // elements per 16-byte chunk
+  if (d.head_dim % align) return JK_ERR_UNSUPPORTED;
+  const int64_t strides[] = {d.kc_stride_b, d.kc_stride_l, d.kc_stride_h, d.kt_stride_b, d.kt_stride_t, d.kt_stride_h};
+  for (int64_t s : strides)
+    if (s < 0 || s % align) return JK_ERR_INVALID_ARG;
+  if (n_layers == 0) {  // (with several layers the tensor pointers live on the device and cannot be checked here)
+    const void* ptrs[] = {k_tree, v_tree, k_cache, v_cache};
+    for (const void* p : ptrs)
+      if (reinterpret_cast<uintptr_t>(p) % 16) return JK_ERR_INVALID_ARG;
+  }
+  CommitArgs a;
+  a.d = d;
+  a.k_tree = k_tree; a.v_tree = v_tree; a.k_cache = k_cache; a.v_cache = v_cache;
+  a.path = path; a.accept_len = accept_len; a.prefix_len = prefix_len;
+  a.max_depth = max_depth; a.capacity = cache_capacity; a.advance = advance != 0;
+  a.n_layers = n_layers;
+  return launch_commit(a, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? JK_OK : JK_ERR_HIP;
+}
+
+jk_status jk_commit_path(const jk_attn_desc* desc, const void* k_tree, const void* v_tree, void* k_cache,
+                         void* v_cache, const int32_t* path, const int32_t* accept_len, int32_t max_depth,
+                         int32_t cache_capacity, int32_t* prefix_len, int32_t advance, void* hip_stream) {
+  return commit_common(desc, 0, k_tree, v_tree, k_cache, v_cache, path, accept_len, max_depth, cache_capacity,
+                       prefix_len, advance, hip_stream);
+}
+
+jk_status jk_commit_path_layers(const jk_attn_desc* desc, int32_t n_layers, const void* const* k_tree,
+                                const void* const* v_tree, void* const* k_cache, void* const* v_cache,
+                                const int32_t* path, const int32_t* accept_len, int32_t max_depth,
+                                int32_t cache_capacity, int32_t* prefix_len, int32_t advance, void* hip_stream) {
+  if (n_layers < 1) return JK_ERR_INVALID_ARG;
+  return commit_common(desc, n_layers, k_tree, v_tree, const_cast<void**>(reinterpret_cast<void* const*>(k_cache)),
+                       const_cast<void**>(reinterpret_cast<void* const*>(v_cache)), path, accept_len, max_depth,
+                       cache_capacity, prefix_len, advance, hip_stream);
+}
+
 jk_status jk_workspace_init(void* workspace, size_t workspace_bytes, void* hip_stream) {
   if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256) return JK_ERR_WORKSPACE;
   return launch_zero_fill(workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream)) == hipSuccess

@@ -57,6 +57,17 @@ size_t accept_workspace_bytes(int batch, int n_tree, int vocab, int mode);
 hipError_t launch_accept(const AcceptArgs& a, hipStream_t stream);
 int device_cu_count();
 
+struct CommitArgs {
+  jk_attn_desc d;
+  const void *k_tree, *v_tree;
+  void *k_cache, *v_cache;
+  const int32_t *path, *accept_len;
+  int32_t* prefix_len;
+  int max_depth, capacity, advance;
+  int n_layers;  // 0: the four pointers are the tensors; > 0: device arrays of that many tensor pointers
+};
+hipError_t launch_commit(const CommitArgs& a, hipStream_t stream);
+
 // cooperative sampling walk (several workgroups per tree)
 size_t accept_coop_bytes(int batch);
 bool accept_coop_plan(int batch, int vocab, int cus, int* W, int* slice);
