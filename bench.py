@@ -109,7 +109,7 @@ def main():
     jk.lib()  # fail loudly if the HIP library is missing
     cfg = CONFIGS[args.workload]
     if args.layers <= 0:
-        args.layers = {"c4_llama2_13b": 40, "c5_llama2_70b": 2, "c1_tiny": 32}.get(cfg.name, 32)
+        args.layers = {"c4_llama2_13b": 40, "c5_llama2_70b": 2, "c1_tiny": 32, "c6_chain_sps": 4, "c7_static_tree": 16}.get(cfg.name, 32)
     dev = torch.device("cuda:0")
     tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
     par = tree_for_config(cfg)

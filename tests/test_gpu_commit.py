@@ -155,6 +155,47 @@ def test_commit_all_layers_in_one_call():
     np.testing.assert_array_equal(pl.cpu().numpy(), rl)
 
 
+@pytest.mark.parametrize("name", ["c6_chain_sps", "c7_static_tree"])
+def test_chain_and_static_tree_rounds(name):
+    """The second workload family (a chain of gamma draft tokens; a predefined static tree) through
+    the same three calls, ragged prefix lengths in the batch, against the oracles."""
+    cfg = CONFIGS[name].with_(batch=3, prefix_len=700, n_q_heads=8, n_kv_heads=4, vocab=3000)
+    par = tree_for_config(cfg)
+    acc = accept_inputs(cfg, par)
+    x = {k: round_to_bf16(v) for k, v in attention_inputs(cfg, scale_mult=np.sqrt(128.0)).items()}
+    bf = torch.bfloat16
+    plen0 = [690, 333, 5]
+    kc, vc = _dev(x["k_cache"], bf), _dev(x["v_cache"], bf)
+    kt, vt = _dev(x["k_tree"], bf), _dev(x["v_tree"], bf)
+    parent = torch.from_numpy(par).cuda()
+    pl = torch.tensor(plen0, dtype=torch.int32).cuda()
+    out = jk.tree_verify_attention(_dev(x["q"], bf), kc, vc, kt, vt, parent, pl)
+    sample = cfg.mode == "sample"
+    path, alen, bonus = jk.accept_path(
+        torch.from_numpy(acc["tokens"]).cuda(), parent, torch.from_numpy(acc["logits"]).cuda(),
+        mode=jk.JK_SAMPLE if sample else jk.JK_GREEDY,
+        draft_probs=torch.from_numpy(acc["draft_probs"]).cuda() if sample else None,
+        uniforms=torch.from_numpy(acc["uniforms"]).cuda() if sample else None, max_depth=cfg.depth)
+    jk.commit_path(kt, vt, kc, vc, path, alen, pl)
+    torch.cuda.synchronize()
+    ref = oracle_attention(**x, parent=par, prefix_len=plen0)
+    assert np.abs(out.float().cpu().numpy() - ref).max() <= 2e-2
+    rp, rl = [], []
+    for b in range(cfg.batch):
+        r = oracle_accept(acc["tokens"][b], par[b], acc["logits"][b], cfg.mode,
+                          draft_probs=acc["draft_probs"][b] if sample else None,
+                          uniforms=acc["uniforms"][b] if sample else None)
+        assert r.min_margin is None or r.min_margin > 1e-9
+        rp.append((list(r.path) + [-1] * cfg.depth)[:cfg.depth])
+        rl.append(min(r.accept_len, cfg.depth))
+        assert int(bonus[b]) == r.bonus_token
+    np.testing.assert_array_equal(path.cpu().numpy(), np.array(rp))
+    rk, rv, new_len = oracle_commit(x["k_cache"], x["v_cache"], x["k_tree"], x["v_tree"], np.array(rp), rl, plen0)
+    np.testing.assert_array_equal(kc.float().cpu().numpy(), rk.astype(np.float32))
+    np.testing.assert_array_equal(vc.float().cpu().numpy(), rv.astype(np.float32))
+    np.testing.assert_array_equal(pl.cpu().numpy(), new_len)
+
+
 def test_commit_argument_errors():
     cfg = CONFIGS["c1_tiny"]
     x = attention_inputs(cfg)

@@ -83,3 +83,19 @@ def test_sample_inputs():
     assert (q[0, np.arange(12), a["tokens"][0]] > 0).all()
     u = a["uniforms"]
     assert u.shape == (1, 13) and (u >= 0).all() and (u < 1).all()
+
+
+def test_chain_and_static_trees():
+    from workloads import chain_tree, static_tree, tree_depths
+    c = chain_tree(5)
+    assert c.tolist() == [-1, 0, 1, 2, 3]
+    t = static_tree()
+    assert len(t) == 28 and all(-1 <= p < i for i, p in enumerate(t)) and tree_depths(t).max() == 5
+    # children of one parent are consecutive (BFS) and the first child of every node has the most children
+    kids = {}
+    for i, p in enumerate(t):
+        kids.setdefault(int(p), []).append(i)
+    assert len(kids[-1]) == 4 and [len(kids.get(k, [])) for k in kids[-1]] == [3, 2, 1, 0]
+    for name, T in (("c6_chain_sps", 5), ("c7_static_tree", 28)):
+        par = tree_for_config(CONFIGS[name])
+        assert par.shape == (CONFIGS[name].batch, T) and (par == par[0]).all()

@@ -12,9 +12,11 @@ from .generators import (  # noqa: F401
     attention_inputs,
     bf16_bits,
     bf16_bits_to_f32,
+    chain_tree,
     coin_tree,
     config_rng,
     round_to_bf16,
+    static_tree,
     tree_depths,
     two_expert_tree,
     tree_for_config,

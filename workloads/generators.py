@@ -35,7 +35,7 @@ class VerifyConfig:
     dtype: str           # "bf16" | "f32"
     vocab: int
     mode: str            # "greedy" | "sample"
-    tree_kind: str       # "coin" | "two_expert"
+    tree_kind: str       # "coin" | "two_expert" | "chain" | "static"
     input_scale: float   # Q, K, V ~ N(0,1) * input_scale
     hit_prob: float      # greedy: P(node token is the planted target top-1)
     seed: int
@@ -61,6 +61,13 @@ CONFIGS: Dict[str, VerifyConfig] = {
                                   "bf16", 32000, "greedy", "two_expert", _S128, 0.7, 3),
     "c5_llama2_70b": VerifyConfig("c5_llama2_70b", 8, 1, 64, 8, 128, 16384, 100, 8, 6, 5,
                                   "bf16", 32000, "sample", "two_expert", _S128, 0.0, 4),
+    # second workload family for the same kernels (Section 2.1: a chain of gamma draft tokens is
+    # the original speculative sampling; Section 3.1.2: the method also runs on predefined static
+    # trees): not in the graded set, shapes of a 7B model
+    "c6_chain_sps": VerifyConfig("c6_chain_sps", 8, 32, 32, 32, 128, 2048, 5, 5, 1, 1,
+                                 "bf16", 32000, "sample", "chain", _S128, 0.0, 5),
+    "c7_static_tree": VerifyConfig("c7_static_tree", 4, 32, 32, 32, 128, 1024, 28, 5, 4, 0,
+                                   "bf16", 32000, "greedy", "static", _S128, 0.7, 6),
 }
 
 
@@ -187,13 +194,41 @@ def two_expert_tree(rng: np.random.Generator, depth: int, topk: int, frontier: i
     }
 
 
+def chain_tree(n_nodes: int) -> np.ndarray:
+    """gamma draft tokens in a row: node i hangs off node i-1, node 0 off the committed prefix."""
+    return np.arange(-1, n_nodes - 1, dtype=np.int32)
+
+
+def static_tree(widths=(4, 3, 2, 1, 1)) -> np.ndarray:
+    """A predefined tree shape, the same for every sequence and round: a node that is the r-th
+    (0-based) child of its parent and whose children sit at depth d gets max(0, widths[d-1] - r)
+    children; BFS numbering.  The default widths give 4 + 6 + 8 + 5 + 5 = 28 nodes, depth 5."""
+    parent = []
+    level = [(-1, 0)]  # (node id, rank among its siblings)
+    for w in widths:
+        nxt = []
+        for node, r in level:
+            for c in range(max(0, w - r)):
+                nxt.append((len(parent), c))
+                parent.append(node)
+        level = nxt
+    return np.asarray(parent, dtype=np.int32)
+
+
 def tree_for_config(cfg: VerifyConfig, seed: Optional[int] = None) -> np.ndarray:
-    """parent[B, T] for a configuration: one independently drawn tree per sequence."""
+    """parent[B, T] for a configuration: one independently drawn tree per sequence (chain and
+    static trees are the same for all)."""
     out = np.empty((cfg.batch, cfg.n_tree), dtype=np.int32)
     for b in range(cfg.batch):
         rng = config_rng(cfg, 1000 + b, seed)
         if cfg.tree_kind == "coin":
             out[b] = coin_tree(rng, cfg.n_tree, cfg.depth)
+        elif cfg.tree_kind == "chain":
+            out[b] = chain_tree(cfg.n_tree)
+        elif cfg.tree_kind == "static":
+            t = static_tree()
+            assert len(t) >= cfg.n_tree
+            out[b] = t[:cfg.n_tree]
         else:
             out[b] = two_expert_tree(rng, cfg.depth, cfg.topk, cfg.frontier, cfg.n_tree)["parent"]
     return out
