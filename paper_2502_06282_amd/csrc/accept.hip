@@ -113,11 +113,20 @@ __global__ __launch_bounds__(128) void walk_greedy_kernel(int n_tree, int nch, i
   const int rows = n_tree + 1;
   for (int r = tid; r < rows; r += blockDim.x) {
     const long long base = ((long long)b * rows + r) * nch;
-    float best = pmax[base];
-    int bi = pidx[base];
-    for (int c = 1; c < nch; ++c) {  // chunks ascend in token id: strict > keeps the lowest id
-      const float v = pmax[base + c];
-      if (v > best) { best = v; bi = pidx[base + c]; }
+    float best = -INFINITY;
+    int bi = 0x7fffffff;
+    for (int c0 = 0; c0 < nch; c0 += 8) {  // eight partials in flight at a time
+      float v[8];
+      int id[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const bool in = c0 + u < nch;
+        v[u] = in ? pmax[base + c0 + u] : -INFINITY;
+        id[u] = in ? pidx[base + c0 + u] : 0x7fffffff;
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u)  // chunks ascend in token id: strict > keeps the lowest id
+        if (v[u] > best) { best = v[u]; bi = id[u]; }
     }
     amax[r] = (bi == 0x7fffffff) ? 0 : bi;  // a row of -inf only: id 0, the first maximum
   }
@@ -125,19 +134,21 @@ __global__ __launch_bounds__(128) void walk_greedy_kernel(int n_tree, int nch, i
   __syncthreads();
   if (tid < n_tree) ok[tid] = (tokens[(long long)b * n_tree + tid] == amax[par_s[tid] + 1]);
   __syncthreads();
-  if (tid == 0) {
+  if (tid < 64) {  // wave 0 descends: the first accepted child of c, found with two ballots per level
+    const int lane = tid;
+    const bool in0 = lane < n_tree, in1 = lane + 64 < n_tree;
+    const int p0 = in0 ? par_s[lane] : -2, p1 = in1 ? par_s[lane + 64] : -2;
+    const bool ok0 = in0 && ok[lane], ok1 = in1 && ok[lane + 64];
     int c = -1, len = 0;
-    int k = 0;
-    // nodes are numbered topologically, so children of c have larger indices than c:
-    // one forward sweep finds the whole chain, taking the first accepted child each time
-    while (k < n_tree) {
-      if (par_s[k] == c && ok[k]) {
-        if (len < max_depth) out_path[(long long)b * max_depth + len] = k;
-        ++len;
-        c = k;
-      }
-      ++k;
+    for (;;) {  // nodes are numbered topologically: a child has a larger index than its parent
+      const unsigned long long m0 = __ballot(ok0 && p0 == c), m1 = __ballot(ok1 && p1 == c);
+      const int k = m0 ? __ffsll((long long)m0) - 1 : (m1 ? 63 + __ffsll((long long)m1) : -1);
+      if (k < 0) break;
+      if (len < max_depth && lane == 0) out_path[(long long)b * max_depth + len] = k;
+      ++len;
+      c = k;
     }
+    if (lane != 0) return;
     const int capped = len < max_depth ? len : max_depth;
     for (int i = capped; i < max_depth; ++i) out_path[(long long)b * max_depth + i] = -1;
     out_len[b] = capped;

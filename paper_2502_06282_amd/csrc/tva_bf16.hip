@@ -494,6 +494,11 @@ struct PairPipe {
   }
 };
 
+// Profiling build only (-DJK_TIMING, not part of the shipped library): thread 0 of every
+// workgroup records the 100 MHz wall clock at eight points of the kernel (entry, speculative
+// transfers issued, prefix length known, transfers issued, first round landed, loop done,
+// columns parked, end); jk_debug_read_timing copies the table of the last launch to the host
+// (grids of at most 4096 workgroups).  The phase times quoted in the design notes come from it.
 #ifdef JK_TIMING
 __device__ unsigned long long g_jk_ts[4096 * 8];
 #define JK_TS(i) do { if (threadIdx.x == 0) g_jk_ts[blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
