@@ -239,6 +239,48 @@ def _sampled_unit_check(cfg, x, par, got, n_samples, seed):
         assert err <= BF16_TOL and err <= 1.5e-2 * np.abs(ref).max(), (b, kv, err)
 
 
+def test_c3_full_size_graph_replay_as_benchmarked():
+    """The launch configuration bench.py times: prepared calls of several full-size c3 layers sharing
+    one workspace, captured in a HIP graph and replayed, with eager work between the replays; every
+    replay must reproduce the eager result bit for bit, and the result is checked against the oracle
+    on sampled KV heads."""
+    import paper_2502_06282_amd as jk
+    cfg = CONFIGS["c3_llama3_8b"]
+    par = tree_for_config(cfg)
+    dev = torch.device("cuda")
+    n_layers = 3
+    xs = [attention_inputs(cfg, layer=l, scale_mult=np.sqrt(128.0)) for l in range(n_layers)]
+    lys = [{k: torch.from_numpy(v).to(dev).to(torch.bfloat16) for k, v in x.items()} for x in xs]
+    parent = torch.from_numpy(par).to(dev)
+    plen = torch.full((cfg.batch,), cfg.prefix_len, dtype=torch.int32, device=dev)
+    outs = [torch.empty_like(l["q"]) for l in lys]
+    ws = torch.empty(jk.tree_verify_attention_workspace(lys[0]["q"], lys[0]["k_cache"], lys[0]["k_tree"], cfg.prefix_len),
+                     dtype=torch.uint8, device=dev)
+    calls = [jk.prepare_tree_verify_attention(l["q"], l["k_cache"], l["v_cache"], l["k_tree"], l["v_tree"], parent, plen,
+                                              o, ws, max_prefix_len=cfg.prefix_len) for l, o in zip(lys, outs)]
+    for c in calls:
+        c.launch()
+    torch.cuda.synchronize()
+    eager = [o.clone() for o in outs]
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=torch.cuda.Stream()):
+        for c in calls:
+            c.launch()
+    for rep in range(3):
+        for o in outs:
+            o.fill_(float("nan"))
+        ws.random_(0, 255)                     # stale partials must not matter
+        junk = torch.randn(1 << 20, device=dev).sum()   # the program's own eager work between replays
+        g.replay()
+        torch.cuda.synchronize()
+        for o, e in zip(outs, eager):
+            assert torch.equal(o, e), f"replay {rep} differs from the eager result"
+        assert torch.isfinite(junk)
+    for l in (0, n_layers - 1):
+        got = outs[l].float().cpu().numpy().astype(np.float64)
+        _sampled_unit_check(cfg, xs[l], par, got, 3, 10 + l)
+
+
 def test_c4_full_size_sampled_units():
     """Config 4 (LLaMA2-13B shape, batch 4 with a tree per sequence), one layer at full size."""
     cfg = CONFIGS["c4_llama2_13b"]
