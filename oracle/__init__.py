@@ -10,3 +10,4 @@ the HIP library and never calls it.
 from .tree_attention import ancestor_sets, tree_verify_attention  # noqa: F401
 from .accept_path import accept_path, AcceptResult  # noqa: F401
 from .commit_path import commit_path, committed_rows  # noqa: F401
+from .paged_kv import gather_pages, scatter_rows  # noqa: F401

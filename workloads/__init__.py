@@ -15,6 +15,7 @@ from .generators import (  # noqa: F401
     chain_tree,
     coin_tree,
     config_rng,
+    paged_layout,
     round_to_bf16,
     static_tree,
     tree_depths,

@@ -262,6 +262,26 @@ def attention_inputs(cfg: VerifyConfig, layer: int = 0, seed: Optional[int] = No
     }
 
 
+def paged_layout(k_cache: np.ndarray, v_cache: np.ndarray, page_size: int, seed: int = 0, spare_pages: int = 3):
+    """Scatter contiguous caches [B, L, Hkv, D] into page pools [n_pages, page_size, Hkv, D] with a random
+    assignment of physical pages (a few spare pages, filled with NaN, are never referenced) and return
+    ((k_pool, v_pool), block_table[B, blocks_per_sequence]).  Slots past L in a sequence's last page hold NaN."""
+    B, L = k_cache.shape[0], k_cache.shape[1]
+    nb = (L + page_size - 1) // page_size
+    n_pages = B * nb + spare_pages
+    rng = np.random.Generator(np.random.PCG64([int(seed), 3000]))
+    ids = rng.permutation(n_pages)[: B * nb].astype(np.int32).reshape(B, nb)
+    pools = []
+    for c in (k_cache, v_cache):
+        pool = np.full((n_pages, page_size) + c.shape[2:], np.nan, dtype=c.dtype)
+        for b in range(B):
+            for j in range(nb):
+                n = min(page_size, L - j * page_size)
+                pool[ids[b, j], :n] = c[b, j * page_size: j * page_size + n]
+        pools.append(pool)
+    return (pools[0], pools[1]), ids
+
+
 # --------------------------------------------------------------------------
 # acceptance inputs
 # --------------------------------------------------------------------------
