@@ -91,6 +91,9 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="attention calls (distinct KV buffers) per step; "
                     "default: the model's depth (32; 40 for c4; 2 x 537 MB for c5)")
     ap.add_argument("--workload", default="c3_llama3_8b")
+    ap.add_argument("--paged", type=int, default=0, metavar="PAGE_SIZE",
+                    help="keep the KV caches in page pools of this page size (a multiple of 32) with a shuffled "
+                         "block table and time jk_tree_verify_attention_paged instead")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="issue every library call from Python instead of "
                     "replaying the step's two HIP graphs")
@@ -142,9 +145,29 @@ def main():
     o_path = torch.empty((cfg.batch, cfg.depth), dtype=torch.int32, device=dev)
     o_len = torch.empty((cfg.batch,), dtype=torch.int32, device=dev)
     o_bonus = torch.empty((cfg.batch,), dtype=torch.int32, device=dev)
-    attn_calls = [jk.prepare_tree_verify_attention(lyr["q"], lyr["k_cache"], lyr["v_cache"], lyr["k_tree"],
-                                                   lyr["v_tree"], parent, plen, out, ws_attn,
-                                                   max_prefix_len=cfg.prefix_len) for lyr in layers]
+    if args.paged:
+        # the same cache contents, page by page at shuffled places of a pool (one table for all layers)
+        ps = args.paged
+        nb = (cfg.prefix_len + ps - 1) // ps
+        n_pages = cfg.batch * nb + 3
+        perm = torch.randperm(n_pages, generator=torch.Generator().manual_seed(0))[: cfg.batch * nb]
+        table = perm.to(torch.int32).reshape(cfg.batch, nb).to(dev)
+        for lyr in layers:
+            for name in ("k_cache", "v_cache"):
+                c = lyr[name]
+                pad = nb * ps - cfg.prefix_len
+                if pad:
+                    c = torch.cat([c, torch.zeros((cfg.batch, pad) + tuple(c.shape[2:]), dtype=c.dtype, device=dev)], 1)
+                pool = torch.zeros((n_pages, ps) + tuple(c.shape[2:]), dtype=c.dtype, device=dev)
+                pool[table.reshape(-1).long()] = c.reshape(cfg.batch * nb, ps, *c.shape[2:])
+                lyr[name + "_pool"] = pool
+        attn_calls = [jk.prepare_tree_verify_attention_paged(lyr["q"], lyr["k_cache_pool"], lyr["v_cache_pool"], table,
+                                                             lyr["k_tree"], lyr["v_tree"], parent, plen, out, ws_attn,
+                                                             max_prefix_len=cfg.prefix_len) for lyr in layers]
+    else:
+        attn_calls = [jk.prepare_tree_verify_attention(lyr["q"], lyr["k_cache"], lyr["v_cache"], lyr["k_tree"],
+                                                       lyr["v_tree"], parent, plen, out, ws_attn,
+                                                       max_prefix_len=cfg.prefix_len) for lyr in layers]
     acc_call = jk.prepare_accept_path(tokens, parent, logits, mode, 1.0, draft, unif, o_path, o_len, o_bonus, ws_acc)
     res = (o_path, o_len, o_bonus)
 
@@ -270,7 +293,8 @@ def main():
         "config": {"workload": f"{cfg.name}: B{cfg.batch} Hq{cfg.n_q_heads} Hkv{cfg.n_kv_heads} D{cfg.head_dim} "
                                f"prefix{cfg.prefix_len} tree{cfg.n_tree} vocab{cfg.vocab} {cfg.mode}",
                    "layers": args.layers, "attention_calls_per_step": args.layers, "accept_calls_per_step": 1,
-                   "launch": "eager" if args.no_graph else "hip_graph"},
+                   "launch": "eager" if args.no_graph else "hip_graph",
+                   "kv_cache": f"paged, {args.paged} tokens per page" if args.paged else "contiguous"},
         "percent_of_hbm_peak": round(100.0 * gbps / HBM_PEAK_GBPS, 2),
         "verify_steps_per_s": round(1e3 / ms_per_step, 1),
         "attention_us_per_call": round(per_call_us, 3),

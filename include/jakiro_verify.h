@@ -121,6 +121,31 @@ jk_status jk_tree_verify_attention(const jk_attn_desc* desc, const void* q, cons
                                    int32_t max_prefix_len, void* out, void* workspace,
                                    size_t workspace_bytes, void* hip_stream);
 
+/* Paged KV cache: one pool of fixed-size pages per tensor, [n_pages, page_size,
+ * n_kv_heads, head_dim] with desc->kc_stride_l / kc_stride_h as the token and head
+ * strides inside a page (kc_stride_b is ignored) and page_stride elements between
+ * pages; token t of sequence b lives in page block_table[b * max_blocks + t /
+ * page_size] at slot t % page_size.  Entries for tokens below prefix_len[b] must
+ * be valid page ids; others are never read (ids outside [0, n_pages) are clamped
+ * into the pool rather than followed).  The paper does not discuss cache layout:
+ * this is a library convention for serving stacks. */
+typedef struct {
+  const int32_t* block_table; /* device int32 [batch, max_blocks] */
+  int32_t max_blocks;         /* max_blocks * page_size >= max_prefix_len */
+  int32_t page_size;          /* tokens per page, a multiple of 32 */
+  int32_t n_pages;            /* pages in the pool */
+  int64_t page_stride;        /* elements, a multiple of 8 */
+} jk_paged_kv;
+
+/* jk_tree_verify_attention over a paged cache (JK_BF16 only).  k_pool / v_pool
+ * take the place of k_cache / v_cache; everything else, including the workspace
+ * size (jk_tree_verify_attention_workspace), is as for the contiguous call. */
+jk_status jk_tree_verify_attention_paged(const jk_attn_desc* desc, const jk_paged_kv* pages, const void* q,
+                                         const void* k_pool, const void* v_pool, const void* k_tree,
+                                         const void* v_tree, const int32_t* parent, const int32_t* prefix_len,
+                                         int32_t max_prefix_len, void* out, void* workspace,
+                                         size_t workspace_bytes, void* hip_stream);
+
 /* Bytes of workspace jk_accept_path needs.  Returns 0 for invalid sizes. */
 size_t jk_accept_path_workspace(int32_t batch, int32_t n_tree, int32_t vocab, int32_t mode);
 
@@ -201,6 +226,16 @@ jk_status jk_commit_path_layers(const jk_attn_desc* desc, int32_t n_layers, cons
                                 const void* const* v_tree, void* const* k_cache, void* const* v_cache,
                                 const int32_t* path, const int32_t* accept_len, int32_t max_depth,
                                 int32_t cache_capacity, int32_t* prefix_len, int32_t advance, void* hip_stream);
+
+/* jk_commit_path_layers into paged caches: k_pool / v_pool are device arrays of
+ * n_layers pool pointers, all described by `pages` (one block table for all
+ * layers); the capacity is max_blocks * page_size.  The pages the new rows land
+ * in must already be in the table. */
+jk_status jk_commit_path_layers_paged(const jk_attn_desc* desc, const jk_paged_kv* pages, int32_t n_layers,
+                                      const void* const* k_tree, const void* const* v_tree,
+                                      void* const* k_pool, void* const* v_pool, const int32_t* path,
+                                      const int32_t* accept_len, int32_t max_depth, int32_t* prefix_len,
+                                      int32_t advance, void* hip_stream);
 
 /* Zero-fills a workspace with a small kernel on `hip_stream` (safe under HIP-graph
  * capture).  Needed once per workspace before its first jk_accept_path call: the

@@ -38,7 +38,14 @@ class AttnDesc(ctypes.Structure):
 
 _lib = None
 
-EXPORTS = ("jk_tree_verify_attention_workspace", "jk_tree_verify_attention", "jk_accept_path_workspace",
+class PagedKV(ctypes.Structure):
+    """jk_paged_kv"""
+    _fields_ = [("block_table", ctypes.c_void_p), ("max_blocks", ctypes.c_int32), ("page_size", ctypes.c_int32),
+                ("n_pages", ctypes.c_int32), ("page_stride", ctypes.c_int64)]
+
+
+EXPORTS = ("jk_tree_verify_attention_workspace", "jk_tree_verify_attention", "jk_tree_verify_attention_paged",
+           "jk_commit_path_layers_paged", "jk_accept_path_workspace",
            "jk_accept_path", "jk_commit_path", "jk_commit_path_layers", "jk_workspace_init", "jk_stream_read_probe", "jk_validate_tree", "jk_status_string", "jk_version")
 
 
@@ -60,6 +67,12 @@ def lib() -> ctypes.CDLL:
         l.jk_tree_verify_attention.restype = i32
         l.jk_tree_verify_attention.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp, vp, i32,
                                                vp, vp, sz, vp]
+        l.jk_tree_verify_attention_paged.restype = i32
+        l.jk_tree_verify_attention_paged.argtypes = [ctypes.POINTER(AttnDesc), ctypes.POINTER(PagedKV), vp, vp, vp, vp, vp,
+                                                     vp, vp, i32, vp, vp, sz, vp]
+        l.jk_commit_path_layers_paged.restype = i32
+        l.jk_commit_path_layers_paged.argtypes = [ctypes.POINTER(AttnDesc), ctypes.POINTER(PagedKV), i32, vp, vp, vp, vp,
+                                                  vp, vp, i32, vp, i32, vp]
         l.jk_accept_path_workspace.restype = sz
         l.jk_accept_path_workspace.argtypes = [i32, i32, i32, i32]
         l.jk_accept_path.restype = i32
@@ -304,6 +317,73 @@ def prepare_commit_path_layers(k_trees, v_trees, k_caches, v_caches, path, accep
     return PreparedCall(lib().jk_commit_path_layers, "jk_commit_path_layers", call_args, 12,
                         (d, tables, list(k_trees), list(v_trees), list(k_caches), list(v_caches), path, accept_len,
                          prefix_len))
+
+
+def _paged(k_pool, block_table) -> PagedKV:
+    """k_pool [n_pages, page_size, Hkv, D]; block_table int32 [B, max_blocks] on the device."""
+    return PagedKV(block_table.data_ptr(), int(block_table.shape[1]), int(k_pool.shape[1]), int(k_pool.shape[0]),
+                   int(k_pool.stride(0)))
+
+
+def _paged_desc(q, k_pool, k_tree, out, scale):
+    d = _make_desc(q, None, k_tree, out, scale)
+    d.kc_stride_b, d.kc_stride_l, d.kc_stride_h = 0, k_pool.stride(1), k_pool.stride(2)
+    return d
+
+
+def prepare_tree_verify_attention_paged(q, k_pool, v_pool, block_table, k_tree, v_tree, parent, prefix_len, out,
+                                        workspace, max_prefix_len: int, scale: float = 0.0) -> "PreparedCall":
+    """jk_tree_verify_attention_paged with out and workspace given; nothing is launched.  k_pool, v_pool
+    [n_pages, page_size, Hkv, D] (same strides), block_table int32 [B, max_blocks]."""
+    if v_pool.stride() != k_pool.stride():
+        raise ValueError("K and V pools must share strides")
+    d = _paged_desc(q, k_pool, k_tree, out, scale)
+    pg = _paged(k_pool, block_table)
+    args = [ctypes.byref(d), ctypes.byref(pg), _ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(k_tree), _ptr(v_tree),
+            _ptr(parent), _ptr(prefix_len), int(max_prefix_len), _ptr(out), _ptr(workspace),
+            workspace.numel() * workspace.element_size(), None]
+    return PreparedCall(lib().jk_tree_verify_attention_paged, "jk_tree_verify_attention_paged", args, 13,
+                        (d, pg, q, k_pool, v_pool, block_table, k_tree, v_tree, parent, prefix_len, out, workspace))
+
+
+def tree_verify_attention_paged(q, k_pool, v_pool, block_table, k_tree, v_tree, parent, prefix_len,
+                                max_prefix_len: int, scale: float = 0.0, out=None, workspace=None, stream=None):
+    """jk_tree_verify_attention_paged; returns out [B,T,Hq,D] (allocated unless given)."""
+    import torch
+    if out is None:
+        out = torch.empty_like(q)
+    if workspace is None:
+        d = _paged_desc(q, k_pool, k_tree, out, scale)
+        need = int(lib().jk_tree_verify_attention_workspace(ctypes.byref(d), int(max_prefix_len)))
+        if need == 0:
+            raise JakiroError(3, "jk_tree_verify_attention_workspace")
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    prepare_tree_verify_attention_paged(q, k_pool, v_pool, block_table, k_tree, v_tree, parent, prefix_len, out,
+                                        workspace, max_prefix_len, scale).launch(stream)
+    return out
+
+
+def prepare_commit_path_layers_paged(k_trees, v_trees, k_pools, v_pools, block_table, path, accept_len, prefix_len,
+                                     advance: bool = True) -> "PreparedCall":
+    """jk_commit_path_layers_paged for lists of per-layer tree tensors and page pools (one block table)."""
+    import torch
+    n = len(k_trees)
+    for ts in (k_trees, v_trees, k_pools, v_pools):
+        if len(ts) != n or any(t.stride() != ts[0].stride() or t.shape != ts[0].shape for t in ts):
+            raise ValueError("per-layer tensors must share shape and strides")
+    kt, kp = k_trees[0], k_pools[0]
+    B, T, Hkv, D = kt.shape
+    dt = JK_BF16 if kt.dtype == torch.bfloat16 else JK_F32
+    d = AttnDesc(B, T, Hkv, Hkv, D, 0, 0, 0, 0, kp.stride(1), kp.stride(2), kt.stride(0), kt.stride(1), kt.stride(2),
+                 0, 0, 0, 0.0, dt)
+    pg = _paged(kp, block_table)
+    tables = [torch.tensor([t.data_ptr() for t in ts], dtype=torch.int64, device=path.device)
+              for ts in (k_trees, v_trees, k_pools, v_pools)]
+    args = [ctypes.byref(d), ctypes.byref(pg), n] + [_ptr(t) for t in tables] + \
+           [_ptr(path), _ptr(accept_len), int(path.shape[1]), _ptr(prefix_len), 1 if advance else 0, None]
+    return PreparedCall(lib().jk_commit_path_layers_paged, "jk_commit_path_layers_paged", args, 12,
+                        (d, pg, tables, list(k_trees), list(v_trees), list(k_pools), list(v_pools), block_table, path,
+                         accept_len, prefix_len))
 
 
 def prepare_accept_path(tree_tokens, parent, target_logits, mode, temperature, draft_probs, uniforms, out_path,

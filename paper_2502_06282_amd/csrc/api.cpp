@@ -75,6 +75,10 @@ bool make_attn_plan(const jk_attn_desc& d, int max_prefix_len, AttnPlan* pl) {
         if (s > max_by_tiles) s = max_by_tiles;
         if (s > kMaxSplits) s = kMaxSplits;
         if (forced_s >= 1 && forced_s <= kMaxSplits) s = forced_s;
+        // a split's tiles stay within what a workgroup can keep page ids for (paged caches)
+        const long long s_min = (n_tiles + kMaxTilesPerSplit - 1) / kMaxTilesPerSplit;
+        if (s < s_min) s = s_min;
+        if (s > kMaxSplits) continue;
         // Estimated time of a call, in microseconds, from what was measured on an MI355X at
         // head_dim 128: a workgroup runs a round (2 tiles per key column) in about 0.95 us as
         // 2x2 waves and 1.4 us as 4x1 waves (which cover twice the rows, hand-pipelined);
@@ -135,10 +139,10 @@ size_t jk_tree_verify_attention_workspace(const jk_attn_desc* desc, int32_t max_
   return pl.total_bytes;
 }
 
-jk_status jk_tree_verify_attention(const jk_attn_desc* desc, const void* q, const void* k_cache,
-                                   const void* v_cache, const void* k_tree, const void* v_tree,
-                                   const int32_t* parent, const int32_t* prefix_len, int32_t max_prefix_len,
-                                   void* out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+static jk_status attention_common(const jk_attn_desc* desc, const jk_paged_kv* pages, const void* q,
+                                  const void* k_cache, const void* v_cache, const void* k_tree, const void* v_tree,
+                                  const int32_t* parent, const int32_t* prefix_len, int32_t max_prefix_len, void* out,
+                                  void* workspace, size_t workspace_bytes, void* hip_stream) {
   if (!desc || !q || !k_tree || !v_tree || !parent || !prefix_len || !out) return JK_ERR_INVALID_ARG;
   if (max_prefix_len < 0) return JK_ERR_INVALID_ARG;
   if (max_prefix_len > 0 && (!k_cache || !v_cache)) return JK_ERR_INVALID_ARG;
@@ -158,6 +162,14 @@ jk_status jk_tree_verify_attention(const jk_attn_desc* desc, const void* q, cons
   const void* ptrs[] = {q, k_cache, v_cache, k_tree, v_tree, out};
   for (const void* p : ptrs)
     if (reinterpret_cast<uintptr_t>(p) % (align * es)) return JK_ERR_INVALID_ARG;
+  if (pages) {
+    if (d.dtype != JK_BF16) return JK_ERR_UNSUPPORTED;
+    if (!pages->block_table || pages->page_size < 1 || pages->max_blocks < 1 || pages->n_pages < 1)
+      return JK_ERR_INVALID_ARG;
+    if (pages->page_size % kTileKeys) return JK_ERR_UNSUPPORTED;  // a page holds whole 32-key tiles
+    if (pages->page_stride < 0 || pages->page_stride % align) return JK_ERR_INVALID_ARG;
+    if ((long long)pages->max_blocks * pages->page_size < max_prefix_len) return JK_ERR_INVALID_ARG;
+  }
 
   AttnPlan pl;
   if (!make_attn_plan(d, max_prefix_len, &pl)) return JK_ERR_UNSUPPORTED;
@@ -171,6 +183,11 @@ jk_status jk_tree_verify_attention(const jk_attn_desc* desc, const void* q, cons
   a.part_ml = reinterpret_cast<float2*>(static_cast<char*>(workspace) + pl.part_o_bytes);
   a.d = d;
   a.max_prefix_len = max_prefix_len;
+  a.block_table = pages ? pages->block_table : nullptr;
+  a.max_blocks = pages ? pages->max_blocks : 0;
+  a.page_size = pages ? pages->page_size : 0;
+  a.n_pages = pages ? pages->n_pages : 0;
+  a.page_stride = pages ? pages->page_stride : 0;
   const float scale = d.scale > 0.f ? d.scale : 1.0f / std::sqrt((float)d.head_dim);
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   hipError_t e;
@@ -184,6 +201,24 @@ jk_status jk_tree_verify_attention(const jk_attn_desc* desc, const void* q, cons
     if (e == hipSuccess) e = launch_tva_combine(a, pl, stream);
   }
   return e == hipSuccess ? JK_OK : JK_ERR_HIP;
+}
+
+jk_status jk_tree_verify_attention(const jk_attn_desc* desc, const void* q, const void* k_cache,
+                                   const void* v_cache, const void* k_tree, const void* v_tree,
+                                   const int32_t* parent, const int32_t* prefix_len, int32_t max_prefix_len,
+                                   void* out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return attention_common(desc, nullptr, q, k_cache, v_cache, k_tree, v_tree, parent, prefix_len, max_prefix_len, out,
+                          workspace, workspace_bytes, hip_stream);
+}
+
+jk_status jk_tree_verify_attention_paged(const jk_attn_desc* desc, const jk_paged_kv* pages, const void* q,
+                                         const void* k_pool, const void* v_pool, const void* k_tree,
+                                         const void* v_tree, const int32_t* parent, const int32_t* prefix_len,
+                                         int32_t max_prefix_len, void* out, void* workspace, size_t workspace_bytes,
+                                         void* hip_stream) {
+  if (!pages) return JK_ERR_INVALID_ARG;
+  return attention_common(desc, pages, q, k_pool, v_pool, k_tree, v_tree, parent, prefix_len, max_prefix_len, out,
+                          workspace, workspace_bytes, hip_stream);
 }
 
 size_t jk_accept_path_workspace(int32_t batch, int32_t n_tree, int32_t vocab, int32_t mode) {
@@ -222,7 +257,7 @@ jk_status jk_accept_path(int32_t batch, int32_t n_tree, int32_t vocab, int32_t m
   return launch_accept(a, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? JK_OK : JK_ERR_HIP;
 }
 
-static jk_status commit_common(const jk_attn_desc* desc, int n_layers, const void* k_tree, const void* v_tree,
+static jk_status commit_common(const jk_attn_desc* desc, const jk_paged_kv* pages, int n_layers, const void* k_tree, const void* v_tree,
                                void* k_cache, void* v_cache, const int32_t* path, const int32_t* accept_len,
                                int32_t max_depth, int32_t cache_capacity, int32_t* prefix_len, int32_t advance,
                                void* hip_stream) {
@@ -245,20 +280,31 @@ static jk_status commit_common(const jk_attn_desc* desc, int n_layers, const voi
     for (const void* p : ptrs)
       if (reinterpret_cast<uintptr_t>(p) % 16) return JK_ERR_INVALID_ARG;
   }
+  if (pages) {
+    if (!pages->block_table || pages->page_size < 1 || pages->max_blocks < 1 || pages->n_pages < 1)
+      return JK_ERR_INVALID_ARG;
+    if (pages->page_stride < 0 || pages->page_stride % align) return JK_ERR_INVALID_ARG;
+    if ((long long)pages->max_blocks * pages->page_size < cache_capacity) return JK_ERR_INVALID_ARG;
+  }
   CommitArgs a;
   a.d = d;
   a.k_tree = k_tree; a.v_tree = v_tree; a.k_cache = k_cache; a.v_cache = v_cache;
   a.path = path; a.accept_len = accept_len; a.prefix_len = prefix_len;
   a.max_depth = max_depth; a.capacity = cache_capacity; a.advance = advance != 0;
   a.n_layers = n_layers;
+  a.block_table = pages ? pages->block_table : nullptr;
+  a.max_blocks = pages ? pages->max_blocks : 0;
+  a.page_size = pages ? pages->page_size : 0;
+  a.n_pages = pages ? pages->n_pages : 0;
+  a.page_stride = pages ? pages->page_stride : 0;
   return launch_commit(a, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? JK_OK : JK_ERR_HIP;
 }
 
 jk_status jk_commit_path(const jk_attn_desc* desc, const void* k_tree, const void* v_tree, void* k_cache,
                          void* v_cache, const int32_t* path, const int32_t* accept_len, int32_t max_depth,
                          int32_t cache_capacity, int32_t* prefix_len, int32_t advance, void* hip_stream) {
-  return commit_common(desc, 0, k_tree, v_tree, k_cache, v_cache, path, accept_len, max_depth, cache_capacity,
-                       prefix_len, advance, hip_stream);
+  return commit_common(desc, nullptr, 0, k_tree, v_tree, k_cache, v_cache, path, accept_len, max_depth,
+                       cache_capacity, prefix_len, advance, hip_stream);
 }
 
 jk_status jk_commit_path_layers(const jk_attn_desc* desc, int32_t n_layers, const void* const* k_tree,
@@ -266,9 +312,22 @@ jk_status jk_commit_path_layers(const jk_attn_desc* desc, int32_t n_layers, cons
                                 const int32_t* path, const int32_t* accept_len, int32_t max_depth,
                                 int32_t cache_capacity, int32_t* prefix_len, int32_t advance, void* hip_stream) {
   if (n_layers < 1) return JK_ERR_INVALID_ARG;
-  return commit_common(desc, n_layers, k_tree, v_tree, const_cast<void**>(reinterpret_cast<void* const*>(k_cache)),
+  return commit_common(desc, nullptr, n_layers, k_tree, v_tree,
+                       const_cast<void**>(reinterpret_cast<void* const*>(k_cache)),
                        const_cast<void**>(reinterpret_cast<void* const*>(v_cache)), path, accept_len, max_depth,
                        cache_capacity, prefix_len, advance, hip_stream);
+}
+
+jk_status jk_commit_path_layers_paged(const jk_attn_desc* desc, const jk_paged_kv* pages, int32_t n_layers,
+                                      const void* const* k_tree, const void* const* v_tree, void* const* k_pool,
+                                      void* const* v_pool, const int32_t* path, const int32_t* accept_len,
+                                      int32_t max_depth, int32_t* prefix_len, int32_t advance, void* hip_stream) {
+  if (n_layers < 1 || !pages) return JK_ERR_INVALID_ARG;
+  const long long cap = (long long)pages->max_blocks * pages->page_size;
+  return commit_common(desc, pages, n_layers, k_tree, v_tree,
+                       const_cast<void**>(reinterpret_cast<void* const*>(k_pool)),
+                       const_cast<void**>(reinterpret_cast<void* const*>(v_pool)), path, accept_len, max_depth,
+                       (int32_t)(cap > 0x7fffffffLL ? 0x7fffffffLL : cap), prefix_len, advance, hip_stream);
 }
 
 jk_status jk_workspace_init(void* workspace, size_t workspace_bytes, void* hip_stream) {

@@ -24,6 +24,11 @@ struct CommitParams {
   int T, Hkv, max_depth, capacity;
   int row_chunks;                  // 16-byte chunks per (node, KV head) row
   long long kc_sb, kc_sl, kc_sh, kt_sb, kt_st, kt_sh;  // strides in bytes
+  // paged caches: kc / vc are page pools and position t of sequence b lives in page
+  // block_table[b * max_blocks + t / page_size], slot t % page_size
+  const int32_t* block_table;
+  int max_blocks, page_size, n_pages;
+  long long page_sb;  // page stride in bytes
 };
 
 // rows of sequence b that are committed: accept_len cut to [0, max_depth], ended in front of
@@ -57,8 +62,15 @@ __global__ __launch_bounds__(256) void commit_rows_kernel(CommitParams p) {
   }
   const unsigned char* ks = kt + b * p.kt_sb + node * p.kt_st;
   const unsigned char* vs = vt + b * p.kt_sb + node * p.kt_st;
-  unsigned char* kd = kc + b * p.kc_sb + (long long)(L + i) * p.kc_sl;
-  unsigned char* vd = vc + b * p.kc_sb + (long long)(L + i) * p.kc_sl;
+  long long dst = b * p.kc_sb + (long long)(L + i) * p.kc_sl;
+  if (p.block_table) {
+    const int pos = L + i, pi = pos / p.page_size;  // pi < max_blocks: pos < capacity <= max_blocks * page_size
+    int page = p.block_table[(long long)b * p.max_blocks + pi];
+    page = page < 0 ? 0 : (page >= p.n_pages ? p.n_pages - 1 : page);
+    dst = page * p.page_sb + (long long)(pos - pi * p.page_size) * p.kc_sl;
+  }
+  unsigned char* kd = kc + dst;
+  unsigned char* vd = vc + dst;
   const int total = p.Hkv * p.row_chunks;
   for (int c = threadIdx.x; c < total; c += 256) {
     const int h = c / p.row_chunks, o = (c % p.row_chunks) * 16;
@@ -92,6 +104,8 @@ hipError_t launch_commit(const CommitArgs& a, hipStream_t stream) {
   p.row_chunks = (int)(d.head_dim * es / 16);
   p.kc_sb = d.kc_stride_b * es; p.kc_sl = d.kc_stride_l * es; p.kc_sh = d.kc_stride_h * es;
   p.kt_sb = d.kt_stride_b * es; p.kt_st = d.kt_stride_t * es; p.kt_sh = d.kt_stride_h * es;
+  p.block_table = a.block_table; p.max_blocks = a.max_blocks; p.page_size = a.page_size; p.n_pages = a.n_pages;
+  p.page_sb = a.page_stride * es;
   const dim3 grid((unsigned)(d.batch * a.max_depth), (unsigned)(a.n_layers > 0 ? a.n_layers : 1));
   if (a.n_layers > 0)
     hipLaunchKernelGGL(commit_rows_kernel<true>, grid, dim3(256), 0, stream, p);

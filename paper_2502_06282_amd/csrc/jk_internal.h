@@ -11,6 +11,7 @@ namespace jk {
 constexpr int kWaveSize = 64;
 constexpr int kTileKeys = 32;      // keys per attention tile (one MFMA M-block)
 constexpr int kMaxSplits = 64;     // upper bound on KV splits per (sequence, KV head)
+constexpr int kMaxTilesPerSplit = 1024;  // so that a split's page ids (paged caches) fit a workgroup's LDS table
 
 // How one attention call is cut into workgroups.  Derived on the host from the
 // descriptor and the prefix bound only, so that the workspace query and the
@@ -39,6 +40,10 @@ struct AttnArgs {
   jk_attn_desc d;
   int max_prefix_len;
   float scale_log2;  // softmax scale * log2(e)
+  // paged cache (bf16 path only): nullptr / 0 for a contiguous cache
+  const int32_t* block_table;
+  int max_blocks, page_size, n_pages;
+  long long page_stride;
 };
 
 hipError_t launch_tva_bf16(const AttnArgs& a, const AttnPlan& p, hipStream_t stream);
@@ -65,6 +70,10 @@ struct CommitArgs {
   int32_t* prefix_len;
   int max_depth, capacity, advance;
   int n_layers;  // 0: the four pointers are the tensors; > 0: device arrays of that many tensor pointers
+  // paged caches: nullptr / 0 for contiguous ones
+  const int32_t* block_table;
+  int max_blocks, page_size, n_pages;
+  long long page_stride;
 };
 hipError_t launch_commit(const CommitArgs& a, hipStream_t stream);
 

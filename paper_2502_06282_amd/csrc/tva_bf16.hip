@@ -70,6 +70,12 @@ struct KParams {
   unsigned long long mg_qtiles, mg_splits, mg_hkv, mg_g;  // floor(2^32 / d) + 1: n / d == (n * mg) >> 32 for n * d < 2^32
   long long q_sb, q_st, q_sh, kc_sb, kc_sl, kc_sh, kt_sb, kt_st, kt_sh, o_sb, o_st, o_sh;
   float scale_log2;
+  // paged cache (block_table != nullptr): kc / vc are page pools, token t of sequence b lives in page
+  // block_table[b * max_blocks + t / page_size], slot t % page_size; tpp = 32-key tiles per page
+  const int32_t* block_table;
+  int max_blocks, tpp, n_pages;
+  long long page_stride;
+  unsigned long long mg_tpp;
 };
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -160,7 +166,14 @@ __device__ __forceinline__ void wait_dma(int rounds_behind) {
 struct TileSrc {
   long long kc_sl, kt_st;  // row strides (elements)
   int L, T, n_ptiles, t_begin, t_end;
+  // paged cache: page ids of the split's prefix tiles (LDS), index of the first one, tiles per page
+  const int* pg_s;
+  int pg_first, tpp;
+  unsigned long long mg_tpp;
+  long long page_stride;
 };
+
+constexpr int kMaxPagesPerSplit = 1024;  // page ids a workgroup keeps in LDS (the host keeps splits within it)
 
 // Where a lane's 16-byte chunks sit inside a tile.  A wave-level transfer fills 1 KB =
 // 64/CPR consecutive tile rows; lane l writes physical chunk l%CPR of row blk*(64/CPR) +
@@ -203,8 +216,18 @@ __device__ __forceinline__ void lane_chunks(LaneChunks<D, NW>& lc, int wave, int
   }
 }
 
+// First row of prefix tile t of this (sequence, KV head): contiguous cache, or looked up in the
+// split's page list (the tile never straddles pages: a page holds whole tiles).
+template <bool PAGED>
+__device__ __forceinline__ const uint16_t* prefix_tile_base(const TileSrc& ts, const uint16_t* cache, int t) {
+  if (!PAGED) return cache + (long long)t * kTileKeys * ts.kc_sl;
+  const int pi = div_mg(t, ts.mg_tpp);
+  const int page = __builtin_amdgcn_readfirstlane(ts.pg_s[pi - ts.pg_first]);
+  return cache + (long long)page * ts.page_stride + (long long)(t - pi * ts.tpp) * kTileKeys * ts.kc_sl;
+}
+
 // Issue the transfers of round r (TPR tiles, K and V) into ring slot `slot` (byte address).
-template <int D, int NW, int TPR>
+template <int D, int NW, int TPR, bool PAGED>
 __device__ __forceinline__ void dma_round(int r, const TileSrc& ts, const LaneChunks<D, NW>& lc, unsigned slot) {
   using G_ = Geo<D>;
   constexpr int N = LaneChunks<D, NW>::N;
@@ -212,13 +235,22 @@ __device__ __forceinline__ void dma_round(int r, const TileSrc& ts, const LaneCh
   if ((t0 + TPR) * kTileKeys <= ts.L) {
     // every tile of the round is a full prefix tile: a scalar base per tile plus the lane's
     // precomputed offsets
-    const long long tile_elems = (long long)kTileKeys * ts.kc_sl;
-    const uint16_t* base = lc.cache + (long long)t0 * tile_elems;
+    if (!PAGED) {
+      const long long tile_elems = (long long)kTileKeys * ts.kc_sl;
+      const uint16_t* base = lc.cache + (long long)t0 * tile_elems;
 #pragma unroll
-    for (int w = 0; w < TPR; ++w) {
+      for (int w = 0; w < TPR; ++w) {
 #pragma unroll
-      for (int i = 0; i < N; ++i) dma16(base, lc.off[i], slot + w * 2 * G_::TILE_BYTES + lc.lds[i]);
-      base += tile_elems;
+        for (int i = 0; i < N; ++i) dma16(base, lc.off[i], slot + w * 2 * G_::TILE_BYTES + lc.lds[i]);
+        base += tile_elems;
+      }
+    } else {
+#pragma unroll
+      for (int w = 0; w < TPR; ++w) {
+        const uint16_t* base = prefix_tile_base<true>(ts, lc.cache, t0 + w);
+#pragma unroll
+        for (int i = 0; i < N; ++i) dma16(base, lc.off[i], slot + w * 2 * G_::TILE_BYTES + lc.lds[i]);
+      }
     }
     return;
   }
@@ -232,7 +264,7 @@ __device__ __forceinline__ void dma_round(int r, const TileSrc& ts, const LaneCh
     const int key0 = (tree ? t - ts.n_ptiles : t) * kTileKeys;
     const int last = (tree ? ts.T : ts.L) - 1 - key0;  // >= 0 (and >= 31 for a full prefix tile)
     const long long rs = tree ? ts.kt_st : ts.kc_sl;
-    const uint16_t* base = (tree ? lc.tree : lc.cache) + (long long)key0 * rs;
+    const uint16_t* base = tree ? lc.tree + (long long)key0 * rs : prefix_tile_base<PAGED>(ts, lc.cache, t);
 #pragma unroll
     for (int i = 0; i < N; ++i) {
       const int rr = lc.row[i] < last ? lc.row[i] : last;
@@ -507,7 +539,7 @@ __device__ unsigned long long g_jk_ts[4096 * 8];
 #endif
 
 // LDS plan of one workgroup, shared by the kernel and its launcher.
-template <int D, int WM, int WN, int KT>
+template <int D, int WM, int WN, int KT, bool PAGED = false>
 struct Plan {
   using G_ = Geo<D>;
   static constexpr int NW = WM * WN;                    // waves
@@ -524,18 +556,19 @@ struct Plan {
   static constexpr int EPI_BYTES = OBUF_BYTES + WM * PATCH_BYTES;
   static constexpr int UNION_BYTES = RING_BYTES > EPI_BYTES ? RING_BYTES : EPI_BYTES;
   static constexpr int ML_BYTES = NW * kWaveRows * 8;
-  static constexpr int SMEM = UNION_BYTES + ML_BYTES + JK_MAX_TREE * 16 + JK_MAX_TREE * 4;
+  static constexpr int PAGES_BYTES = PAGED ? kMaxPagesPerSplit * 4 : 0;
+  static constexpr int SMEM = UNION_BYTES + ML_BYTES + JK_MAX_TREE * 16 + JK_MAX_TREE * 4 + PAGES_BYTES;
   static constexpr int WGS_PER_CU = 2 * SMEM <= 160 * 1024 && NW <= 4 ? 2 : 1;
   static constexpr int REG_WGS = NW <= 4 ? 2 : 1;  // register budget: at most 256 VGPRs, no detour through AGPRs
   static_assert(SMEM <= 160 * 1024, "LDS budget");
   static_assert(THREADS >= JK_MAX_TREE, "one thread per tree node in the prologue");
 };
 
-template <int D, int WM, int WN, int KT>
-__global__ __launch_bounds__((Plan<D, WM, WN, KT>::THREADS), (Plan<D, WM, WN, KT>::REG_WGS)) void tva_bf16_kernel(
+template <int D, int WM, int WN, int KT, bool PAGED>
+__global__ __launch_bounds__((Plan<D, WM, WN, KT, PAGED>::THREADS), (Plan<D, WM, WN, KT, PAGED>::REG_WGS)) void tva_bf16_kernel(
     const KParams p) {
   using G_ = Geo<D>;
-  using P_ = Plan<D, WM, WN, KT>;
+  using P_ = Plan<D, WM, WN, KT, PAGED>;
   constexpr int TPR = P_::TPR;
   constexpr int DK = G_::DK, DB = G_::DB;
   constexpr int NW = P_::NW, THREADS = P_::THREADS, NR = P_::NR, QROWS = P_::QROWS;
@@ -550,6 +583,7 @@ __global__ __launch_bounds__((Plan<D, WM, WN, KT>::THREADS), (Plan<D, WM, WN, KT
   float2* mlbuf = reinterpret_cast<float2*>(smem + P_::UNION_BYTES);              // [WN-1][QROWS]
   unsigned long long* anc = reinterpret_cast<unsigned long long*>(smem + P_::UNION_BYTES + P_::ML_BYTES);  // [128][2]
   int* par_s = reinterpret_cast<int*>(smem + P_::UNION_BYTES + P_::ML_BYTES + JK_MAX_TREE * 16);           // [128]
+  int* pg_s = par_s + JK_MAX_TREE;                                                                         // [1024], paged caches only
 
   JK_TS(0);
   // ---- touch every 64-byte line of the kernel arguments at once: the compiler fetches them
@@ -557,9 +591,9 @@ __global__ __launch_bounds__((Plan<D, WM, WN, KT>::THREADS), (Plan<D, WM, WN, KT
   {
     typedef __attribute__((address_space(4))) const unsigned kernarg_word;
     kernarg_word* ka = (kernarg_word*)__builtin_amdgcn_kernarg_segment_ptr();
-    static_assert(sizeof(KParams) > 192 && sizeof(KParams) <= 256, "four lines of kernel arguments");
-    const unsigned a0 = ka[0], a1 = ka[16], a2 = ka[32], a3 = ka[48];
-    asm volatile("" ::"s"(a0), "s"(a1), "s"(a2), "s"(a3));
+    static_assert(sizeof(KParams) > 256 && sizeof(KParams) <= 320, "five lines of kernel arguments");
+    const unsigned a0 = ka[0], a1 = ka[16], a2 = ka[32], a3 = ka[48], a4 = ka[64];
+    asm volatile("" ::"s"(a0), "s"(a1), "s"(a2), "s"(a3), "s"(a4));
   }
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -620,6 +654,11 @@ __global__ __launch_bounds__((Plan<D, WM, WN, KT>::THREADS), (Plan<D, WM, WN, KT
   ts.T = T;
   ts.kc_sl = p.kc_sl;
   ts.kt_st = p.kt_st;
+  ts.pg_s = pg_s;
+  ts.pg_first = 0;
+  ts.tpp = p.tpp;
+  ts.mg_tpp = p.mg_tpp;
+  ts.page_stride = p.page_stride;
   const int n_ttiles = (T + kTileKeys - 1) / kTileKeys;
   // Splits are dealt whole rounds (TPR tiles).  The rounds at the end of the key range that
   // hold the ragged prefix tile or masked tree tiles are slower (per-lane clamped transfers,
@@ -647,18 +686,19 @@ __global__ __launch_bounds__((Plan<D, WM, WN, KT>::THREADS), (Plan<D, WM, WN, KT
   const unsigned ring_addr = (unsigned)(size_t)LDS_PTR(unsigned char, ring);  // a multiple of 1024
   const unsigned k_lane = G_::k_lane(lane), v_lane = G_::v_lane(lane);
   LaneChunks<D, NW> lc;
-  lane_chunks<D, NW>(lc, wave, lane, ts, p.kc + b * p.kc_sb + (long long)kv * p.kc_sh,
-                     p.vc + b * p.kc_sb + (long long)kv * p.kc_sh, p.kt + b * p.kt_sb + (long long)kv * p.kt_sh,
+  lane_chunks<D, NW>(lc, wave, lane, ts, p.kc + (PAGED ? 0 : b * p.kc_sb) + (long long)kv * p.kc_sh,
+                     p.vc + (PAGED ? 0 : b * p.kc_sb) + (long long)kv * p.kc_sh, p.kt + b * p.kt_sb + (long long)kv * p.kt_sh,
                      p.vt + b * p.kt_sb + (long long)kv * p.kt_sh);
 
   set_range(p.max_prefix);
   int n_rounds = (ts.t_end - ts.t_begin + TPR - 1) / TPR;
-  const bool spec_any = n_rounds > 0 && (ts.t_begin + TPR) * kTileKeys <= p.max_prefix;  // same for every wave
+  // (a paged cache cannot be read ahead of the length: table entries past the sequence's pages may hold anything)
+  const bool spec_any = !PAGED && n_rounds > 0 && (ts.t_begin + TPR) * kTileKeys <= p.max_prefix;  // same for every wave
   int n_spec = 0;  // rounds already issued, all of them full prefix tiles under the assumption
 #pragma unroll
   for (int r = 0; r < NR - 1; ++r)
-    if (n_spec == r && r < n_rounds && (ts.t_begin + (r + 1) * TPR) * kTileKeys <= p.max_prefix) {
-      dma_round<D, NW, TPR>(r, ts, lc, ring_addr + r * STAGE_BYTES);
+    if (!PAGED && n_spec == r && r < n_rounds && (ts.t_begin + (r + 1) * TPR) * kTileKeys <= p.max_prefix) {
+      dma_round<D, NW, TPR, PAGED>(r, ts, lc, ring_addr + r * STAGE_BYTES);
       n_spec = r + 1;
     }
   JK_TS(1);
@@ -676,9 +716,23 @@ __global__ __launch_bounds__((Plan<D, WM, WN, KT>::THREADS), (Plan<D, WM, WN, KT
     n_rounds = (ts.t_end - ts.t_begin + TPR - 1) / TPR;
   }
   const bool has_tree = ts.t_end > ts.n_ptiles;
+  if (PAGED) {
+    // page ids of the prefix tiles this split will fetch (whole rounds), clamped into the pool
+    const int te = min(ts.n_ptiles, ts.t_begin + n_rounds * TPR);
+    if (te > ts.t_begin) {
+      ts.pg_first = div_mg(ts.t_begin, p.mg_tpp);
+      const int n_pg = div_mg(te - 1, p.mg_tpp) - ts.pg_first + 1;  // <= kMaxPagesPerSplit by the host's plan
+      for (int i = tid; i < n_pg && i < kMaxPagesPerSplit; i += THREADS) {
+        const int pi = ts.pg_first + i;
+        int id = pi < p.max_blocks ? p.block_table[(long long)b * p.max_blocks + pi] : 0;
+        pg_s[i] = id < 0 ? 0 : (id >= p.n_pages ? p.n_pages - 1 : id);
+      }
+    }
+    __syncthreads();
+  }
 #pragma unroll
   for (int r = 0; r < NR - 1; ++r)
-    if (r >= n_spec && r < n_rounds) dma_round<D, NW, TPR>(r, ts, lc, ring_addr + r * STAGE_BYTES);
+    if (r >= n_spec && r < n_rounds) dma_round<D, NW, TPR, PAGED>(r, ts, lc, ring_addr + r * STAGE_BYTES);
 
   JK_TS(3);
   // ---- ancestor sets (only workgroups that reach tree tiles need them), by pointer
@@ -748,7 +802,7 @@ __global__ __launch_bounds__((Plan<D, WM, WN, KT>::THREADS), (Plan<D, WM, WN, KT
     __syncthreads();
     if (r == 0) JK_TS(4);
     if (r + NR - 1 < n_rounds)
-      dma_round<D, NW, TPR>(r + NR - 1, ts, lc, ring_addr + ((r + NR - 1) % NR) * STAGE_BYTES);
+      dma_round<D, NW, TPR, PAGED>(r + NR - 1, ts, lc, ring_addr + ((r + NR - 1) % NR) * STAGE_BYTES);
     const int tb = ts.t_begin + (r * WN + wn) * KT;
     const unsigned tile_a = ring_addr + (r % NR) * STAGE_BYTES + wn * KT * 2 * TILE_BYTES;  // K of the first tile
     if (KT == 2 && (tb + 2) * kTileKeys <= L && tb + 2 <= ts.t_end) {
@@ -873,10 +927,10 @@ __global__ __launch_bounds__((Plan<D, WM, WN, KT>::THREADS), (Plan<D, WM, WN, KT
   JK_TS(7);
 }
 
-template <int D, int WM, int WN, int KT>
+template <int D, int WM, int WN, int KT, bool PAGED>
 hipError_t launch_one(const KParams& kp, hipStream_t stream) {
-  using P_ = Plan<D, WM, WN, KT>;
-  auto kern = tva_bf16_kernel<D, WM, WN, KT>;
+  using P_ = Plan<D, WM, WN, KT, PAGED>;
+  auto kern = tva_bf16_kernel<D, WM, WN, KT, PAGED>;
   static bool lds_limit_raised = false;  // idempotent, so a race between host threads is harmless
   if (!lds_limit_raised) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -925,14 +979,24 @@ hipError_t launch_tva_bf16(const AttnArgs& a, const AttnPlan& pl, hipStream_t st
   kp.mg_hkv = magic(d.n_kv_heads);
   kp.mg_g = magic(kp.G);
 
-  const int key = d.head_dim * 1000 + pl.wm * 100 + pl.wn * 10 + pl.kt;
+  kp.block_table = a.block_table;
+  kp.max_blocks = a.max_blocks;
+  kp.n_pages = a.n_pages;
+  kp.tpp = a.block_table ? a.page_size / kTileKeys : 1;
+  kp.page_stride = a.page_stride;
+  kp.mg_tpp = magic(kp.tpp);
+  const int key = (d.head_dim * 1000 + pl.wm * 100 + pl.wn * 10 + pl.kt) * 2 + (a.block_table ? 1 : 0);
+#define JK_CASE(D_, WM_, WN_, KT_)                                                                  \
+  case ((D_) * 1000 + (WM_) * 100 + (WN_) * 10 + (KT_)) * 2: return launch_one<D_, WM_, WN_, KT_, false>(kp, stream); \
+  case ((D_) * 1000 + (WM_) * 100 + (WN_) * 10 + (KT_)) * 2 + 1: return launch_one<D_, WM_, WN_, KT_, true>(kp, stream);
   switch (key) {
-    case 128412: return launch_one<128, 4, 1, 2>(kp, stream);
-    case 128221: return launch_one<128, 2, 2, 1>(kp, stream);
-    case 64412: return launch_one<64, 4, 1, 2>(kp, stream);
-    case 64221: return launch_one<64, 2, 2, 1>(kp, stream);
+    JK_CASE(128, 4, 1, 2)
+    JK_CASE(128, 2, 2, 1)
+    JK_CASE(64, 4, 1, 2)
+    JK_CASE(64, 2, 2, 1)
     default: return hipErrorInvalidValue;
   }
+#undef JK_CASE
 }
 
 }  // namespace jk

@@ -1,0 +1,114 @@
+"""GPU parity for the paged KV cache: jk_tree_verify_attention_paged against the attention oracle on
+the cache read back in table order, bitwise against the contiguous call on the same data, and
+jk_commit_path_layers_paged against the commit oracle at the paged addresses."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2502_06282_amd as jk
+from oracle import commit_path as oracle_commit, gather_pages, tree_verify_attention as oracle_attention
+from workloads import CONFIGS, attention_inputs, paged_layout, round_to_bf16, tree_for_config
+
+pytestmark = pytest.mark.gpu
+BF = torch.bfloat16
+
+
+def _dev(a, dtype=BF):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda().to(dtype)
+
+
+def _paged_case(cfg, page_size, L, seed=0):
+    par = tree_for_config(cfg, seed=seed)
+    x = {k: round_to_bf16(v) for k, v in attention_inputs(cfg, seed=seed, prefix_len=L, scale_mult=np.sqrt(128.0)).items()}
+    (kp, vp), table = paged_layout(x["k_cache"], x["v_cache"], page_size, seed=seed)
+    return par, x, kp, vp, table
+
+
+@pytest.mark.parametrize("wm,wn", [(2, 2), (4, 1)], ids=["2x2", "4x1"])
+@pytest.mark.parametrize("page_size,L", [(32, 97), (64, 300), (128, 1000), (32, 0), (256, 515)])
+def test_paged_attention_matches_oracle_and_contiguous(monkeypatch, wm, wn, page_size, L):
+    monkeypatch.setenv("JK_ATTN_WM", str(wm))
+    monkeypatch.setenv("JK_ATTN_WN", str(wn))
+    cfg = CONFIGS["c3_llama3_8b"].with_(batch=2, prefix_len=L, n_q_heads=8, n_kv_heads=2)
+    par, x, kp, vp, table = _paged_case(cfg, page_size, max(L, 1), seed=L + page_size)
+    plen = [L, L // 3]
+    ref = oracle_attention(**x, parent=par, prefix_len=plen)
+    parent = torch.from_numpy(par).cuda()
+    pl = torch.tensor(plen, dtype=torch.int32).cuda()
+    for s in ("1", "3"):
+        monkeypatch.setenv("JK_ATTN_SPLITS", s)
+        got = jk.tree_verify_attention_paged(_dev(x["q"]), _dev(kp), _dev(vp), torch.from_numpy(table).cuda(),
+                                             _dev(x["k_tree"]), _dev(x["v_tree"]), parent, pl, max_prefix_len=max(L, 1))
+        cont = jk.tree_verify_attention(_dev(x["q"]), _dev(x["k_cache"]), _dev(x["v_cache"]), _dev(x["k_tree"]),
+                                        _dev(x["v_tree"]), parent, pl, max_prefix_len=max(L, 1))
+        torch.cuda.synchronize()
+        g = got.float().cpu().numpy()
+        assert np.isfinite(g).all()            # the NaN-filled spare pages and page tails were never read
+        assert np.abs(g - ref).max() <= 2e-2
+        assert torch.equal(got, cont)          # same arithmetic in the same order, only the addresses differ
+
+
+def test_paged_attention_full_size_c3():
+    cfg = CONFIGS["c3_llama3_8b"]
+    par, x, kp, vp, table = _paged_case(cfg, 128, cfg.prefix_len)
+    parent = torch.from_numpy(par).cuda()
+    pl = torch.tensor([cfg.prefix_len], dtype=torch.int32).cuda()
+    got = jk.tree_verify_attention_paged(_dev(x["q"]), _dev(kp), _dev(vp), torch.from_numpy(table).cuda(),
+                                         _dev(x["k_tree"]), _dev(x["v_tree"]), parent, pl, max_prefix_len=cfg.prefix_len)
+    cont = jk.tree_verify_attention(_dev(x["q"]), _dev(x["k_cache"]), _dev(x["v_cache"]), _dev(x["k_tree"]),
+                                    _dev(x["v_tree"]), parent, pl)
+    torch.cuda.synchronize()
+    assert torch.equal(got, cont)
+    kv = 5
+    G = cfg.group
+    sub = {"q": x["q"][:, :, kv * G:(kv + 1) * G], "k_cache": x["k_cache"][:, :, kv:kv + 1], "v_cache": x["v_cache"][:, :, kv:kv + 1],
+           "k_tree": x["k_tree"][:, :, kv:kv + 1], "v_tree": x["v_tree"][:, :, kv:kv + 1]}
+    ref = oracle_attention(**sub, parent=par, prefix_len=[cfg.prefix_len])
+    assert np.abs(got.float().cpu().numpy()[0, :, kv * G:(kv + 1) * G] - ref[0]).max() <= 2e-2
+
+
+def test_paged_commit_all_layers():
+    cfg = CONFIGS["c2_vicuna7b"].with_(batch=2, prefix_len=160, n_q_heads=4, n_kv_heads=4)
+    page = 32
+    rng = np.random.default_rng(9)
+    n_layers = 3
+    xs = [{k: round_to_bf16(v) for k, v in attention_inputs(cfg, layer=l).items()} for l in range(n_layers)]
+    layouts = [paged_layout(x["k_cache"], x["v_cache"], page, seed=1) for x in xs]   # same table for all layers
+    table = layouts[0][1]
+    path = np.full((2, cfg.depth), -1, dtype=np.int32)
+    path[0, :4] = [3, 9, 20, 41]
+    path[1, :2] = [0, 7]
+    alen, plen = [4, 2], [94, 158]          # sequence 0 crosses a page boundary (96); sequence 1 ends the cache
+    kps = [_dev(l[0][0]) for l in layouts]
+    vps = [_dev(l[0][1]) for l in layouts]
+    kts, vts = [_dev(x["k_tree"]) for x in xs], [_dev(x["v_tree"]) for x in xs]
+    p = torch.from_numpy(path).cuda()
+    al = torch.tensor(alen, dtype=torch.int32).cuda()
+    pl = torch.tensor(plen, dtype=torch.int32).cuda()
+    jk.prepare_commit_path_layers_paged(kts, vts, kps, vps, torch.from_numpy(table).cuda(), p, al, pl).launch()
+    torch.cuda.synchronize()
+    for l, x in enumerate(xs):
+        rk, rv, rl = oracle_commit(x["k_cache"], x["v_cache"], x["k_tree"], x["v_tree"], path, alen, plen)
+        gk = gather_pages(kps[l].float().cpu().numpy(), table, page, 160)
+        gv = gather_pages(vps[l].float().cpu().numpy(), table, page, 160)
+        np.testing.assert_array_equal(gk, rk.astype(np.float32))
+        np.testing.assert_array_equal(gv, rv.astype(np.float32))
+        # spare pages stay NaN: nothing was written outside the sequences' own pages
+        used = set(table.ravel().tolist())
+        spare = [i for i in range(kps[l].shape[0]) if i not in used]
+        assert torch.isnan(kps[l][spare].float()).all()
+    np.testing.assert_array_equal(pl.cpu().numpy(), rl)
+
+
+def test_paged_argument_errors():
+    cfg = CONFIGS["c2_vicuna7b"].with_(batch=1, prefix_len=64, n_q_heads=4, n_kv_heads=4)
+    par, x, kp, vp, table = _paged_case(cfg, 48, 64)      # 48 is not a multiple of 32
+    parent = torch.from_numpy(par).cuda()
+    pl = torch.tensor([64], dtype=torch.int32).cuda()
+    with pytest.raises(jk.JakiroError):
+        jk.tree_verify_attention_paged(_dev(x["q"]), _dev(kp), _dev(vp), torch.from_numpy(table).cuda(), _dev(x["k_tree"]),
+                                       _dev(x["v_tree"]), parent, pl, max_prefix_len=64)
+    par, x, kp, vp, table = _paged_case(cfg, 32, 64)
+    with pytest.raises(jk.JakiroError):                    # the table cannot hold max_prefix_len tokens
+        jk.tree_verify_attention_paged(_dev(x["q"]), _dev(kp), _dev(vp), torch.from_numpy(table).cuda(), _dev(x["k_tree"]),
+                                       _dev(x["v_tree"]), parent, pl, max_prefix_len=200)
