@@ -15,6 +15,8 @@ from .generators import (  # noqa: F401
     chain_tree,
     coin_tree,
     config_rng,
+    draft_head_inputs,
+    moe_inputs,
     paged_layout,
     round_to_bf16,
     static_tree,

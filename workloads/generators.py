@@ -350,3 +350,36 @@ def accept_inputs(cfg: VerifyConfig, parent: np.ndarray, seed: Optional[int] = N
         out["uniforms"] = rng.random((B, N + 1), dtype=np.float32)
     out["tokens"] = tokens
     return out
+
+
+# --------------------------------------------------------------------------
+# draft-head step (Section 3.1.2 / 3.2): random weights of the model's shapes
+# --------------------------------------------------------------------------
+def draft_head_inputs(rows: int, d_model: int, vocab: int, seed: int = 0, logit_std: float = 2.5):
+    """Inputs of the dual-head step: per-expert features of `rows` hidden states, the two router
+    scores of each (larger first, sum below 1) and an output-embedding matrix scaled so that the
+    logits of a unit-score feature have about `logit_std` standard deviation.  Features and weights
+    are bf16-representable float32 arrays."""
+    rng = np.random.Generator(np.random.PCG64([int(seed), 77]))
+    f_top = round_to_bf16(rng.standard_normal((rows, 2, d_model), dtype=np.float32))
+    hi = rng.uniform(0.3, 0.7, size=rows)
+    lo = rng.uniform(0.05, 1.0, size=rows) * np.minimum(hi, 1.0 - hi)
+    s_top = np.stack([hi, lo], axis=1).astype(np.float32)
+    w_head = round_to_bf16(rng.standard_normal((vocab, d_model), dtype=np.float32)
+                           * np.float32(logit_std / np.sqrt(d_model) / 0.5))
+    return {"f_top": f_top, "s_top": s_top, "w_head": w_head}
+
+
+def moe_inputs(rows: int, d_model: int, d_ff: int, n_experts: int, seed: int = 0):
+    """Inputs of the router and the expert MLPs: hidden states, expert centroids and the three
+    weight matrices of each expert, all bf16-representable float32 arrays."""
+    rng = np.random.Generator(np.random.PCG64([int(seed), 78]))
+    sd = np.float32(1.0 / np.sqrt(d_model))
+    return {
+        "u": round_to_bf16(rng.standard_normal((rows, d_model), dtype=np.float32)),
+        "centroids": round_to_bf16(rng.standard_normal((n_experts, d_model), dtype=np.float32) * sd * np.float32(1.5)),
+        "w_gate": round_to_bf16(rng.standard_normal((n_experts, d_ff, d_model), dtype=np.float32) * sd),
+        "w_up": round_to_bf16(rng.standard_normal((n_experts, d_ff, d_model), dtype=np.float32) * sd),
+        "w_down": round_to_bf16(rng.standard_normal((n_experts, d_model, d_ff), dtype=np.float32)
+                                * np.float32(1.0 / np.sqrt(d_ff))),
+    }
