@@ -237,6 +237,54 @@ jk_status jk_commit_path_layers_paged(const jk_attn_desc* desc, const jk_paged_k
                                       const int32_t* accept_len, int32_t max_depth, int32_t* prefix_len,
                                       int32_t advance, void* hip_stream);
 
+/* ---- the step in front of verification: the draft model's two output heads ----
+ *
+ * Jakiro's draft layer routes a hidden state to its two best experts and gives
+ * both experts' features to the output embedding it shares with the target
+ * model (Section 3.1.2 Eq. 4, Section 3.2 Eq. 6-8).  With f1, f2 the features of
+ * the expert with the larger / smaller router score and s1 >= s2 those scores:
+ *
+ *   JK_HEADS_DECOUPLED    x_left = s1 f1,           x_right = s2 f2           (Eq. 4)
+ *   JK_HEADS_CONTRASTIVE  x_moe  = s1 f1 + s2 f2,   x_const = beta f1 - alpha f2   (Eq. 6, 7)
+ *   logits[r][h] = w_head . x_h            (both heads, one pass over w_head)
+ *   draft_probs[r][h] = softmax(logits[r][h] / temperature)      (the q of the acceptance test)
+ *   topk_tokens[r][h] = the top_k largest logits' token ids, best first, equal
+ *                       logits by increasing id; topk_probs their draft_probs
+ *
+ * (Eq. 4 as printed puts the mixed feature into both heads; the per-expert
+ * features of Eq. 6 are what is computed here, so that left + right = moe.)
+ * The heads' inputs are rounded to bf16 once, products accumulate in fp32.
+ *
+ *   rows         hidden states in this call (tree nodes being expanded, all
+ *                sequences together), 1..128
+ *   d_model      feature width, a multiple of 128, at most 16384
+ *   vocab        rows of w_head, >= top_k
+ *   top_k        1..16
+ *   f_top        device bf16 [rows][2][d_model], 16-byte aligned
+ *   s_top        device fp32 [rows][2]
+ *   w_head       device bf16 [vocab][d_model], 16-byte aligned
+ *   logits       device fp32 [rows][2][vocab], written
+ *   draft_probs  device fp32 [rows][2][vocab], written; may be NULL
+ *   topk_tokens  device int32 [rows][2][top_k], written
+ *   topk_probs   device fp32 [rows][2][top_k], written
+ *   workspace    device, jk_draft_heads_workspace(rows, d_model) bytes, 256-byte aligned
+ * A logits row containing NaN gives unspecified candidates for that row.
+ * JK_ERR_UNSUPPORTED for rows, d_model or top_k outside the ranges above. */
+typedef enum { JK_HEADS_DECOUPLED = 0, JK_HEADS_CONTRASTIVE = 1 } jk_heads_mode;
+
+typedef struct {
+  int32_t rows, d_model, vocab, top_k;
+  int32_t mode;      /* jk_heads_mode */
+  float temperature; /* > 0 */
+  float alpha, beta; /* Eq. 7; ignored for JK_HEADS_DECOUPLED */
+} jk_draft_heads_desc;
+
+size_t jk_draft_heads_workspace(int32_t rows, int32_t d_model);
+
+jk_status jk_draft_heads(const jk_draft_heads_desc* desc, const void* f_top, const float* s_top,
+                         const void* w_head, float* logits, float* draft_probs, int32_t* topk_tokens,
+                         float* topk_probs, void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Zero-fills a workspace with a small kernel on `hip_stream` (safe under HIP-graph
  * capture).  Needed once per workspace before its first jk_accept_path call: the
  * cooperative sampling walk synchronises its workgroups through tagged words in

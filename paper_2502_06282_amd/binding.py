@@ -15,6 +15,7 @@ _LIB_PATH = os.path.join(_HERE, "libjakiro_verify.so")
 
 JK_BF16, JK_F32 = 0, 1
 JK_GREEDY, JK_SAMPLE = 0, 1
+JK_HEADS_DECOUPLED, JK_HEADS_CONTRASTIVE = 0, 1
 MAX_TREE = 128
 
 
@@ -38,6 +39,13 @@ class AttnDesc(ctypes.Structure):
 
 _lib = None
 
+class DraftHeadsDesc(ctypes.Structure):
+    """jk_draft_heads_desc"""
+    _fields_ = [("rows", ctypes.c_int32), ("d_model", ctypes.c_int32), ("vocab", ctypes.c_int32),
+                ("top_k", ctypes.c_int32), ("mode", ctypes.c_int32), ("temperature", ctypes.c_float),
+                ("alpha", ctypes.c_float), ("beta", ctypes.c_float)]
+
+
 class PagedKV(ctypes.Structure):
     """jk_paged_kv"""
     _fields_ = [("block_table", ctypes.c_void_p), ("max_blocks", ctypes.c_int32), ("page_size", ctypes.c_int32),
@@ -46,7 +54,7 @@ class PagedKV(ctypes.Structure):
 
 EXPORTS = ("jk_tree_verify_attention_workspace", "jk_tree_verify_attention", "jk_tree_verify_attention_paged",
            "jk_commit_path_layers_paged", "jk_accept_path_workspace",
-           "jk_accept_path", "jk_commit_path", "jk_commit_path_layers", "jk_workspace_init", "jk_stream_read_probe", "jk_validate_tree", "jk_status_string", "jk_version")
+           "jk_accept_path", "jk_draft_heads_workspace", "jk_draft_heads", "jk_commit_path", "jk_commit_path_layers", "jk_workspace_init", "jk_stream_read_probe", "jk_validate_tree", "jk_status_string", "jk_version")
 
 
 def library_path() -> str:
@@ -82,6 +90,10 @@ def lib() -> ctypes.CDLL:
         l.jk_commit_path.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp, i32, i32, vp, i32, vp]
         l.jk_commit_path_layers.restype = i32
         l.jk_commit_path_layers.argtypes = [ctypes.POINTER(AttnDesc), i32, vp, vp, vp, vp, vp, vp, i32, i32, vp, i32, vp]
+        l.jk_draft_heads_workspace.restype = sz
+        l.jk_draft_heads_workspace.argtypes = [i32, i32]
+        l.jk_draft_heads.restype = i32
+        l.jk_draft_heads.argtypes = [ctypes.POINTER(DraftHeadsDesc), vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         l.jk_workspace_init.restype = i32
         l.jk_workspace_init.argtypes = [vp, sz, vp]
         l.jk_stream_read_probe.restype = i32
@@ -397,3 +409,62 @@ def prepare_accept_path(tree_tokens, parent, target_logits, mode, temperature, d
     return PreparedCall(lib().jk_accept_path, "jk_accept_path", args, 16,
                         (tree_tokens, parent, target_logits, draft_probs, uniforms, out_path, out_accept_len,
                          out_bonus_token, workspace))
+
+
+def _draft_heads_args(f_top, s_top, w_head, mode, temperature, top_k, alpha, beta, logits, draft_probs,
+                      topk_tokens, topk_probs, workspace):
+    import torch
+    R, two, d = f_top.shape
+    V = w_head.shape[0]
+    if two != 2 or tuple(s_top.shape) != (R, 2) or w_head.shape[1] != d:
+        raise ValueError("f_top [R,2,d], s_top [R,2], w_head [V,d]")
+    for t in (f_top, w_head):
+        if t.dtype != torch.bfloat16 or not t.is_contiguous():
+            raise TypeError("f_top and w_head must be contiguous bfloat16")
+    for t in (s_top, logits, draft_probs, topk_probs):
+        if t is not None and (t.dtype != torch.float32 or not t.is_contiguous()):
+            raise TypeError("s_top, logits, draft_probs and topk_probs must be contiguous float32")
+    if topk_tokens.dtype != torch.int32 or not topk_tokens.is_contiguous():
+        raise TypeError("topk_tokens must be contiguous int32")
+    desc = DraftHeadsDesc(R, d, V, int(top_k), int(mode), float(temperature), float(alpha), float(beta))
+    args = [ctypes.byref(desc), _ptr(f_top), _ptr(s_top), _ptr(w_head), _ptr(logits), _ptr(draft_probs),
+            _ptr(topk_tokens), _ptr(topk_probs), _ptr(workspace), workspace.numel() * workspace.element_size(), None]
+    return desc, args
+
+
+def draft_heads_workspace(rows: int, d_model: int) -> int:
+    return int(lib().jk_draft_heads_workspace(int(rows), int(d_model)))
+
+
+def draft_heads(f_top, s_top, w_head, mode: int = JK_HEADS_DECOUPLED, temperature: float = 1.0, top_k: int = 10,
+                alpha: float = 0.0, beta: float = 0.0, want_probs: bool = True, stream=None):
+    """jk_draft_heads.  f_top bf16 [R,2,d], s_top fp32 [R,2], w_head bf16 [V,d].
+    Returns (logits [R,2,V], draft_probs [R,2,V] or None, topk_tokens [R,2,k] int32, topk_probs [R,2,k])."""
+    import torch
+    R, _, d = f_top.shape
+    V = w_head.shape[0]
+    dev = f_top.device
+    logits = torch.empty((R, 2, V), dtype=torch.float32, device=dev)
+    probs = torch.empty((R, 2, V), dtype=torch.float32, device=dev) if want_probs else None
+    tk = torch.empty((R, 2, int(top_k)), dtype=torch.int32, device=dev)
+    tp = torch.empty((R, 2, int(top_k)), dtype=torch.float32, device=dev)
+    need = draft_heads_workspace(R, d)
+    if need == 0:
+        raise JakiroError(3, "jk_draft_heads_workspace")
+    ws = torch.empty(need, dtype=torch.uint8, device=dev)
+    desc, args = _draft_heads_args(f_top, s_top, w_head, mode, temperature, top_k, alpha, beta, logits, probs,
+                                   tk, tp, ws)
+    args[-1] = _stream_handle(stream)
+    st = lib().jk_draft_heads(*args)
+    if st != 0:
+        raise JakiroError(st, "jk_draft_heads")
+    return logits, probs, tk, tp
+
+
+def prepare_draft_heads(f_top, s_top, w_head, mode, temperature, top_k, alpha, beta, logits, draft_probs,
+                        topk_tokens, topk_probs, workspace) -> PreparedCall:
+    """jk_draft_heads with outputs and workspace given; nothing is launched."""
+    desc, args = _draft_heads_args(f_top, s_top, w_head, mode, temperature, top_k, alpha, beta, logits, draft_probs,
+                                   topk_tokens, topk_probs, workspace)
+    return PreparedCall(lib().jk_draft_heads, "jk_draft_heads", args, 10,
+                        (desc, f_top, s_top, w_head, logits, draft_probs, topk_tokens, topk_probs, workspace))

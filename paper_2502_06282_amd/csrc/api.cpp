@@ -330,6 +330,34 @@ jk_status jk_commit_path_layers_paged(const jk_attn_desc* desc, const jk_paged_k
                        (int32_t)(cap > 0x7fffffffLL ? 0x7fffffffLL : cap), prefix_len, advance, hip_stream);
 }
 
+size_t jk_draft_heads_workspace(int32_t rows, int32_t d_model) {
+  if (rows < 1 || rows > 128 || d_model < 128 || d_model > 16384 || d_model % 128) return 0;
+  return draft_heads_workspace_bytes(rows, d_model);
+}
+
+jk_status jk_draft_heads(const jk_draft_heads_desc* desc, const void* f_top, const float* s_top,
+                         const void* w_head, float* logits, float* draft_probs, int32_t* topk_tokens,
+                         float* topk_probs, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!desc || !f_top || !s_top || !w_head || !logits || !topk_tokens || !topk_probs) return JK_ERR_INVALID_ARG;
+  const jk_draft_heads_desc& d = *desc;
+  if (d.rows < 1 || d.d_model < 1 || d.vocab < 1 || d.top_k < 1 || d.top_k > d.vocab) return JK_ERR_INVALID_ARG;
+  if (d.mode != JK_HEADS_DECOUPLED && d.mode != JK_HEADS_CONTRASTIVE) return JK_ERR_INVALID_ARG;
+  if (!(d.temperature > 0.f) || !std::isfinite(d.temperature)) return JK_ERR_INVALID_ARG;
+  if (d.mode == JK_HEADS_CONTRASTIVE && (!std::isfinite(d.alpha) || !std::isfinite(d.beta))) return JK_ERR_INVALID_ARG;
+  if (reinterpret_cast<uintptr_t>(f_top) % 16 || reinterpret_cast<uintptr_t>(w_head) % 16) return JK_ERR_INVALID_ARG;
+  if (d.rows > 128 || d.d_model < 128 || d.d_model > 16384 || d.d_model % 128 || d.top_k > 16) return JK_ERR_UNSUPPORTED;
+  if ((long long)2 * d.rows * d.vocab > 0x7fffffffLL * 4) return JK_ERR_UNSUPPORTED;
+  const size_t need = draft_heads_workspace_bytes(d.rows, d.d_model);
+  if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256 || workspace_bytes < need) return JK_ERR_WORKSPACE;
+  DraftHeadsArgs a;
+  a.rows = d.rows; a.d_model = d.d_model; a.vocab = d.vocab; a.top_k = d.top_k; a.mode = d.mode;
+  a.temperature = d.temperature; a.alpha = d.alpha; a.beta = d.beta;
+  a.f_top = f_top; a.w_head = w_head; a.s_top = s_top;
+  a.logits = logits; a.draft_probs = draft_probs; a.topk_probs = topk_probs; a.topk_tokens = topk_tokens;
+  a.workspace = workspace;
+  return launch_draft_heads(a, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? JK_OK : JK_ERR_HIP;
+}
+
 jk_status jk_workspace_init(void* workspace, size_t workspace_bytes, void* hip_stream) {
   if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256) return JK_ERR_WORKSPACE;
   return launch_zero_fill(workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream)) == hipSuccess

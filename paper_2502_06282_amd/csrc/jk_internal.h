@@ -84,4 +84,17 @@ hipError_t launch_accept_coop(const AcceptArgs& a, void* coop_ws, int W, int sli
 hipError_t launch_zero_fill(void* p, size_t bytes, hipStream_t stream);
 hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, hipStream_t stream);
 
+// draft head step (two heads over the shared output embedding)
+struct DraftHeadsArgs {
+  int rows, d_model, vocab, top_k, mode;
+  float temperature, alpha, beta;
+  const void *f_top, *w_head;
+  const float* s_top;
+  float *logits, *draft_probs, *topk_probs;
+  int32_t* topk_tokens;
+  void* workspace;
+};
+size_t draft_heads_workspace_bytes(int rows, int d_model);
+hipError_t launch_draft_heads(const DraftHeadsArgs& a, hipStream_t stream);
+
 }  // namespace jk
