@@ -258,7 +258,7 @@ jk_status jk_commit_path_layers_paged(const jk_attn_desc* desc, const jk_paged_k
  *   rows         hidden states in this call (tree nodes being expanded, all
  *                sequences together), 1..128
  *   d_model      feature width, a multiple of 128, at most 16384
- *   vocab        rows of w_head, >= top_k
+ *   vocab        rows of w_head, top_k..2^24
  *   top_k        1..16
  *   f_top        device bf16 [rows][2][d_model], 16-byte aligned
  *   s_top        device fp32 [rows][2]
@@ -267,8 +267,10 @@ jk_status jk_commit_path_layers_paged(const jk_attn_desc* desc, const jk_paged_k
  *   draft_probs  device fp32 [rows][2][vocab], written; may be NULL
  *   topk_tokens  device int32 [rows][2][top_k], written
  *   topk_probs   device fp32 [rows][2][top_k], written
- *   workspace    device, jk_draft_heads_workspace(rows, d_model) bytes, 256-byte aligned
- * A logits row containing NaN gives unspecified candidates for that row.
+ *   workspace    device, jk_draft_heads_workspace(rows, d_model, vocab) bytes, 256-byte aligned
+ * A logits row containing NaN gives unspecified candidates for that row; a row
+ * with fewer than top_k logits above -inf reports token 0 with probability 0 in
+ * the remaining places.
  * JK_ERR_UNSUPPORTED for rows, d_model or top_k outside the ranges above. */
 typedef enum { JK_HEADS_DECOUPLED = 0, JK_HEADS_CONTRASTIVE = 1 } jk_heads_mode;
 
@@ -279,7 +281,7 @@ typedef struct {
   float alpha, beta; /* Eq. 7; ignored for JK_HEADS_DECOUPLED */
 } jk_draft_heads_desc;
 
-size_t jk_draft_heads_workspace(int32_t rows, int32_t d_model);
+size_t jk_draft_heads_workspace(int32_t rows, int32_t d_model, int32_t vocab);
 
 jk_status jk_draft_heads(const jk_draft_heads_desc* desc, const void* f_top, const float* s_top,
                          const void* w_head, float* logits, float* draft_probs, int32_t* topk_tokens,

@@ -91,7 +91,7 @@ def lib() -> ctypes.CDLL:
         l.jk_commit_path_layers.restype = i32
         l.jk_commit_path_layers.argtypes = [ctypes.POINTER(AttnDesc), i32, vp, vp, vp, vp, vp, vp, i32, i32, vp, i32, vp]
         l.jk_draft_heads_workspace.restype = sz
-        l.jk_draft_heads_workspace.argtypes = [i32, i32]
+        l.jk_draft_heads_workspace.argtypes = [i32, i32, i32]
         l.jk_draft_heads.restype = i32
         l.jk_draft_heads.argtypes = [ctypes.POINTER(DraftHeadsDesc), vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         l.jk_workspace_init.restype = i32
@@ -432,8 +432,8 @@ def _draft_heads_args(f_top, s_top, w_head, mode, temperature, top_k, alpha, bet
     return desc, args
 
 
-def draft_heads_workspace(rows: int, d_model: int) -> int:
-    return int(lib().jk_draft_heads_workspace(int(rows), int(d_model)))
+def draft_heads_workspace(rows: int, d_model: int, vocab: int) -> int:
+    return int(lib().jk_draft_heads_workspace(int(rows), int(d_model), int(vocab)))
 
 
 def draft_heads(f_top, s_top, w_head, mode: int = JK_HEADS_DECOUPLED, temperature: float = 1.0, top_k: int = 10,
@@ -448,7 +448,7 @@ def draft_heads(f_top, s_top, w_head, mode: int = JK_HEADS_DECOUPLED, temperatur
     probs = torch.empty((R, 2, V), dtype=torch.float32, device=dev) if want_probs else None
     tk = torch.empty((R, 2, int(top_k)), dtype=torch.int32, device=dev)
     tp = torch.empty((R, 2, int(top_k)), dtype=torch.float32, device=dev)
-    need = draft_heads_workspace(R, d)
+    need = draft_heads_workspace(R, d, V)
     if need == 0:
         raise JakiroError(3, "jk_draft_heads_workspace")
     ws = torch.empty(need, dtype=torch.uint8, device=dev)

@@ -330,9 +330,11 @@ jk_status jk_commit_path_layers_paged(const jk_attn_desc* desc, const jk_paged_k
                        (int32_t)(cap > 0x7fffffffLL ? 0x7fffffffLL : cap), prefix_len, advance, hip_stream);
 }
 
-size_t jk_draft_heads_workspace(int32_t rows, int32_t d_model) {
-  if (rows < 1 || rows > 128 || d_model < 128 || d_model > 16384 || d_model % 128) return 0;
-  return draft_heads_workspace_bytes(rows, d_model);
+size_t jk_draft_heads_workspace(int32_t rows, int32_t d_model, int32_t vocab) {
+  if (rows < 1 || rows > 128 || d_model < 128 || d_model > 16384 || d_model % 128 || vocab < 1 ||
+      vocab > (1 << 24))
+    return 0;
+  return draft_heads_workspace_bytes(rows, d_model, vocab);
 }
 
 jk_status jk_draft_heads(const jk_draft_heads_desc* desc, const void* f_top, const float* s_top,
@@ -347,7 +349,8 @@ jk_status jk_draft_heads(const jk_draft_heads_desc* desc, const void* f_top, con
   if (reinterpret_cast<uintptr_t>(f_top) % 16 || reinterpret_cast<uintptr_t>(w_head) % 16) return JK_ERR_INVALID_ARG;
   if (d.rows > 128 || d.d_model < 128 || d.d_model > 16384 || d.d_model % 128 || d.top_k > 16) return JK_ERR_UNSUPPORTED;
   if ((long long)2 * d.rows * d.vocab > 0x7fffffffLL * 4) return JK_ERR_UNSUPPORTED;
-  const size_t need = draft_heads_workspace_bytes(d.rows, d.d_model);
+  if (d.vocab > (1 << 24)) return JK_ERR_UNSUPPORTED;
+  const size_t need = draft_heads_workspace_bytes(d.rows, d.d_model, d.vocab);
   if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256 || workspace_bytes < need) return JK_ERR_WORKSPACE;
   DraftHeadsArgs a;
   a.rows = d.rows; a.d_model = d.d_model; a.vocab = d.vocab; a.top_k = d.top_k; a.mode = d.mode;

@@ -4,14 +4,14 @@
 // both heads, the draft distributions q = softmax(logits / temperature) that the acceptance test
 // divides by, and each head's top-k candidates.
 //
-// Three kernels:
+// Kernels:
 //   head_inputs_kernel     X[2R (padded to 32), d] bf16 from f_top, s_top (elementwise, tiny)
 //   skinny_gemm_kernel     Y[M, N] fp32 = X[M, K] . W[N, K]^T with M <= 256: the weight matrix
 //                          (gigabytes for an output embedding) is streamed from HBM exactly once,
 //                          straight into MFMA operand registers; X is small, is shared by all
 //                          workgroups through L2 and staged per 64-wide k block in LDS.
-//   draft_softmax_topk_kernel  per logits row: maximum, normaliser, top-k by value (ties to the
-//                          lower token id), probabilities.
+//   row_parts_kernel, row_merge_kernel, row_probs_kernel   per logits row: maximum, normaliser,
+//                          top-k by value (ties to the lower token id), probabilities.
 #include <climits>
 
 #include "jk_internal.h"
@@ -76,92 +76,182 @@ __global__ __launch_bounds__(256) void head_inputs_kernel(MixParams p) {
 }
 
 // ------------------------------------------------------------------ skinny GEMM
-constexpr int kGemmThreads = 256;
-constexpr int kStripRows = 128;  // weight rows (output columns) per workgroup: 32 per wave
-constexpr int kKB = 64;          // k extent of one main-loop step (four MFMA k steps)
-constexpr int kSlabLd = 144;     // bytes per X row in the LDS slab: 128 of data + 16 of padding
+constexpr int kGemmThreads = 512;  // 8 waves
+constexpr int kKB = 32;            // k extent of one main-loop step (two MFMA k steps): 64 bytes per row
 
 struct GemmParams {
-  const unsigned short* x;  // [MB*32][k] bf16, rows >= m are readable (zero or anything: not stored)
-  const unsigned short* w;  // [n][ldw] bf16
-  float* y;                 // [m][ldy]
+  const uint16_t* x;  // [MB*32][k] bf16, rows >= m are readable (zero or anything: not stored)
+  const uint16_t* w;  // [n][ldw] bf16
+  float* y;           // [m][ldy]
   int m, n, k;
   long long ldw, ldy;
+};
+
+typedef __attribute__((address_space(3))) const bf16x8 lds_bf16x8_t;
+__device__ __forceinline__ bf16x8 lds_read16(unsigned addr) { return *(lds_bf16x8_t*)(size_t)addr; }
+
+// 16 bytes per lane from global memory straight into LDS (global_load_lds_dwordx4): lane l lands
+// at lds_base + 16 l and fetches base + voff (wave-uniform base in scalar registers, the lane's
+// 32-bit byte offset).  Inline assembly, so that the compiler's own bookkeeping does not make
+// every LDS read wait for all transfers in flight; the kernel counts them itself (wait_vm).
+__device__ __forceinline__ void dma16(const uint16_t* base, unsigned voff, unsigned lds_base) {
+  const unsigned m = __builtin_amdgcn_readfirstlane(lds_base);
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(m), "v"(voff), "s"(base)
+               : "memory", "m0");
+}
+__device__ __forceinline__ const uint16_t* uniform_ptr(const uint16_t* p) {
+  const unsigned long long v = reinterpret_cast<unsigned long long>(p);
+  const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v);
+  const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
+  return reinterpret_cast<const uint16_t*>(((unsigned long long)hi << 32) | lo);
+}
+// wait until at most N of this wave's transfers are outstanding (they complete in issue order)
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit field");
+  __builtin_amdgcn_s_waitcnt(((N & 0xF) | ((N >> 4) << 14)) | 0x0F70);
+  asm volatile("" ::: "memory");
+}
+
+// Plan of one workgroup (one per CU, 8 waves).  Every wave owns NBW 32-row blocks of the weight
+// strip and all MB 32-row blocks of X: NBW * MB accumulator tiles of 16 registers.  LDS holds a
+// ring of DW steps of weight fragments per wave (private to the wave that loads and reads them)
+// and a ring of DX steps of X slabs (shared by the workgroup).
+template <int MB>
+struct GemmCfg {
+  static constexpr int NBW = MB <= 6 ? 2 : 1;
+  static constexpr int STRIP = 8 * 32 * NBW;       // weight rows (output columns) per workgroup
+  static constexpr int DW = NBW == 1 ? 6 : 4;
+  static constexpr int DX = MB <= 3 ? 4 : (MB <= 5 ? 3 : (MB == 6 ? 2 : 3));
+  static constexpr int W_STEP = NBW * 2048;        // bytes per wave and step: NBW*32 rows of 64 bytes
+  static constexpr int W_WAVE = DW * W_STEP;
+  static constexpr int X_STEP = MB * 2048;         // MB*32 rows of 64 bytes
+  static constexpr int X_BASE = 8 * W_WAVE;
+  static constexpr int SMEM = X_BASE + DX * X_STEP;
+  static constexpr int NXI = 2 * MB;               // X transfers per step (1 KB = 16 rows each), dealt out to the waves
+  static constexpr int NWI = 2 * NBW;              // weight transfers per wave and step
+  static_assert(SMEM <= 160 * 1024, "LDS plan");
+  // Transfers complete in issue order; a wave issues, per step, its cx X transfers, then NWI of
+  // weights.  At the top of step kb the data of step kb must have landed: X(kb) was asked for
+  // DX - 1 steps ago, W(kb) DW - 1 steps ago.
+  static constexpr int wait_count(int cx) {
+    const int per = cx + NWI;
+    const int wx = NWI + (DX - 2) * per, ww = (DW - 2) * per;
+    return cx == 0 ? ww : (wx < ww ? wx : ww);
+  }
 };
 
 // v_mfma_f32_32x32x16_bf16 computes D[i][j] += sum_k A[i][k] B[k][j] with lane l holding
 // A[l % 32][8 (l / 32) .. + 8], B[.. same k ..][l % 32], and D[8 (v / 4) + 4 (l / 32) + v % 4][l % 32]
 // in accumulator register v.  Here i runs over weight rows (output columns n) and j over X rows
 // (output rows m): a lane's four consecutive accumulator registers are four consecutive n of
-// one output row, i.e. one 16-byte store.  Which sixteen k of the 64-wide block a given MFMA
-// sums over is free as long as A and B agree: lane half h takes k = 32 h + 8 step .. + 8, so
-// that each lane's four weight loads of a block are 64 contiguous bytes.
+// one output row, i.e. one 16-byte store.
+//
+// Both operands go HBM/L2 -> LDS in 64-byte row segments, four lanes per row (an MFMA operand
+// read straight from global memory would touch 32 cache lines per instruction and use 32 bytes
+// of each).  The strip is wide (up to 512 weight rows) because every workgroup has to pull all
+// of X through the same path as its weights: X traffic is (m / strip) of the weight traffic.
+// A row's four 16-byte pieces are stored XOR-swizzled with bits 1-2 of the row number (the
+// transfer fetches piece s ^ key into slot s), so that an operand read (32 rows, one piece of
+// each) spreads over all banks.
 template <int MB>
-__global__ __launch_bounds__(kGemmThreads, 2) void skinny_gemm_kernel(GemmParams p) {
-  __shared__ __attribute__((aligned(16))) unsigned char slab[2][MB * 32 * kSlabLd];
+__global__ __launch_bounds__(kGemmThreads, 1) void skinny_gemm_kernel(GemmParams p) {
+  using C = GemmCfg<MB>;
+  constexpr int NBW = C::NBW;
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];  // the kernel's only LDS: offset 0
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 31, h = lane >> 5;
-  const int n_base = blockIdx.x * kStripRows + wave * 32;
-  // weight rows past the end re-read the last row; their results are never stored
-  const int n_row = min(n_base + r, p.n - 1);
-  const u32x4* wp = reinterpret_cast<const u32x4*>(p.w + (long long)n_row * p.ldw + h * 32);
+  const long long strip0 = (long long)blockIdx.x * C::STRIP;
+  const int n_base = (int)strip0 + wave * 32 * NBW;
   const int nkb = p.k / kKB;
+  // Workgroups start at different k blocks and wrap around, so that at any moment they ask for
+  // different columns of the weight matrix and of X.
+  const int kb0 = (int)((blockIdx.x * 5u) % (unsigned)nkb);
+  auto rot = [&](int kb) {
+    const int t = (kb < nkb ? kb : nkb - 1) + kb0;  // past the end: the last block again (unused, keeps the counts exact)
+    return t >= nkb ? t - nkb : t;
+  };
 
-  floatx16 acc[MB];
+  // transfer geometry: one instruction covers 16 rows, lane l -> row l / 4 of them, slot l % 4
+  const int sub = lane >> 2, slot = lane & 3;
+  const unsigned piece = (unsigned)((slot ^ ((sub >> 1) & 3)) << 4);
+  unsigned voff_w[C::NWI], voff_x[2];
 #pragma unroll
-  for (int mb = 0; mb < MB; ++mb)
+  for (int i = 0; i < C::NWI; ++i) {
+    const int row = min(n_base + 16 * i + sub, p.n - 1);  // rows past the end repeat the last one; never stored
+    voff_w[i] = (unsigned)((row - strip0) * p.ldw * 2) + piece;
+  }
+  // X transfer q (16 rows) belongs to wave q % 8: at most two per wave (MB <= 8)
+  const int cx = (wave < C::NXI ? 1 : 0) + (wave + 8 < C::NXI ? 1 : 0);
 #pragma unroll
-    for (int v = 0; v < 16; ++v) acc[mb][v] = 0.f;
+  for (int t = 0; t < 2; ++t) voff_x[t] = (unsigned)((16 * (wave + 8 * t) + sub) * p.k * 2) + piece;
+  const uint16_t* w_strip = uniform_ptr(p.w + strip0 * p.ldw);
+  const unsigned w_ring = (unsigned)(wave * C::W_WAVE);
 
-  u32x4 wa[4], wb[4], xs[MB];
-  auto load_w = [&](u32x4(&dst)[4], int kb) {
-#pragma unroll
-    for (int j = 0; j < 4; ++j) dst[j] = __builtin_nontemporal_load(wp + kb * 8 + j);
+  auto issue_x = [&](int kb) {
+    const uint16_t* xb = uniform_ptr(p.x + rot(kb) * kKB);
+    const unsigned xs = (unsigned)(C::X_BASE + (kb % C::DX) * C::X_STEP);
+    if (cx > 0) dma16(xb, voff_x[0], xs + (unsigned)(wave * 1024));
+    if (cx > 1) dma16(xb, voff_x[1], xs + (unsigned)((wave + 8) * 1024));
   };
-  // X slab: MB*32 rows of 128 bytes, 16 bytes per thread and pass
-  auto load_x = [&](int kb) {
+  auto issue_w = [&](int kb) {
+    const uint16_t* wb = uniform_ptr(w_strip + rot(kb) * kKB);
+    const unsigned ws = w_ring + (unsigned)((kb % C::DW) * C::W_STEP);
 #pragma unroll
-    for (int i = 0; i < MB; ++i) {
-      const int q = tid + kGemmThreads * i;
-      xs[i] = *reinterpret_cast<const u32x4*>(p.x + (long long)(q >> 3) * p.k + kb * kKB + (q & 7) * 8);
-    }
+    for (int i = 0; i < C::NWI; ++i) dma16(wb, voff_w[i], ws + (unsigned)(i * 1024));
   };
-  auto park_x = [&](int buf) {
+
+  floatx16 acc[NBW][MB];
 #pragma unroll
-    for (int i = 0; i < MB; ++i) {
-      const int q = tid + kGemmThreads * i;
-      *reinterpret_cast<u32x4*>(&slab[buf][(q >> 3) * kSlabLd + (q & 7) * 16]) = xs[i];
-    }
-  };
-  auto step = [&](const u32x4(&cur)[4], u32x4(&nxt)[4], int kb, int buf) {
-    const bool more = kb + 1 < nkb;
-    if (more) {
-      load_w(nxt, kb + 1);
-      load_x(kb + 1);
-    }
+  for (int nb = 0; nb < NBW; ++nb)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const bf16x8 a = __builtin_bit_cast(bf16x8, cur[j]);
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[nb][mb][v] = 0.f;
+
+  // operand read addresses within a slab: row r of a 32-row block (64 bytes per row), piece
+  // 2 j + h of MFMA k step j, swizzled
+  const unsigned rd = (unsigned)(r * 64);
+  const unsigned key = (unsigned)((r >> 1) & 3);
+
+#pragma unroll
+  for (int s = 0; s < C::DX - 1; ++s) issue_x(s);
+#pragma unroll
+  for (int s = 0; s < C::DW - 1; ++s) issue_w(s);
+
+  for (int kb = 0; kb < nkb; ++kb) {
+    if (kb < (C::DW > C::DX ? C::DW : C::DX)) {
+      wait_vm<0>();  // (the prologue's order differs from the steady state's)
+    } else if (cx == 2) {
+      wait_vm<C::wait_count(2)>();
+    } else if (cx == 1) {
+      wait_vm<C::wait_count(1)>();
+    } else {
+      wait_vm<C::wait_count(0)>();
+    }
+    __syncthreads();  // every wave's part of X(kb) has landed; everybody is done with step kb - 1
+    issue_x(kb + C::DX - 1);
+    issue_w(kb + C::DW - 1);
+    const unsigned xa = (unsigned)(C::X_BASE + (kb % C::DX) * C::X_STEP) + rd;
+    const unsigned wa = w_ring + (unsigned)((kb % C::DW) * C::W_STEP) + rd;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const unsigned pc = ((unsigned)(2 * j + h) ^ key) << 4;
+      bf16x8 a[NBW];
+#pragma unroll
+      for (int nb = 0; nb < NBW; ++nb) a[nb] = lds_read16(wa + (unsigned)(nb * 2048) + pc);
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb) {
-        const bf16x8 b = *reinterpret_cast<const bf16x8*>(&slab[buf][(mb * 32 + r) * kSlabLd + h * 64 + j * 16]);
-        acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[mb], 0, 0, 0);
+        const bf16x8 b = lds_read16(xa + (unsigned)(mb * 2048) + pc);
+#pragma unroll
+        for (int nb = 0; nb < NBW; ++nb)
+          acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[nb], b, acc[nb][mb], 0, 0, 0);
       }
     }
-    if (more) park_x(buf ^ 1);
-    __syncthreads();
-  };
-
-  load_w(wa, 0);
-  load_x(0);
-  park_x(0);
-  __syncthreads();
-  for (int kb = 0; kb < nkb; kb += 2) {  // k is a multiple of 128: an even number of steps
-    step(wa, wb, kb, 0);
-    step(wb, wa, kb + 1, 1);
   }
+  wait_vm<0>();  // the redundant transfers of the last steps must not outlive the workgroup's LDS
 
-  // epilogue: lane (r, h) holds, for output row mb*32 + r, columns n_base + 8 q + 4 h + (0..3)
+  // epilogue: lane (r, h) holds, for output row mb*32 + r, columns block + 8 q + 4 h + (0..3)
   const bool vec_ok = (p.ldy & 3) == 0 && (reinterpret_cast<size_t>(p.y) & 15) == 0;
 #pragma unroll
   for (int mb = 0; mb < MB; ++mb) {
@@ -169,24 +259,33 @@ __global__ __launch_bounds__(kGemmThreads, 2) void skinny_gemm_kernel(GemmParams
     if (m >= p.m) continue;
     float* yrow = p.y + (long long)m * p.ldy;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int n = n_base + 8 * q + 4 * h;
-      if (vec_ok && n + 3 < p.n) {
-        *reinterpret_cast<floatx4*>(yrow + n) =
-            floatx4{acc[mb][4 * q], acc[mb][4 * q + 1], acc[mb][4 * q + 2], acc[mb][4 * q + 3]};
-      } else {
+    for (int nb = 0; nb < NBW; ++nb)
 #pragma unroll
-        for (int t = 0; t < 4; ++t)
-          if (n + t < p.n) yrow[n + t] = acc[mb][4 * q + t];
+      for (int q = 0; q < 4; ++q) {
+        const int n = n_base + 32 * nb + 8 * q + 4 * h;
+        if (vec_ok && n + 3 < p.n) {
+          *reinterpret_cast<floatx4*>(yrow + n) = floatx4{acc[nb][mb][4 * q], acc[nb][mb][4 * q + 1],
+                                                          acc[nb][mb][4 * q + 2], acc[nb][mb][4 * q + 3]};
+        } else {
+#pragma unroll
+          for (int t = 0; t < 4; ++t)
+            if (n + t < p.n) yrow[n + t] = acc[nb][mb][4 * q + t];
+        }
       }
-    }
   }
 }
 
 template <int MB>
 hipError_t launch_gemm_mb(const GemmParams& p, hipStream_t stream) {
-  const unsigned grid = (unsigned)((p.n + kStripRows - 1) / kStripRows);
-  hipLaunchKernelGGL(skinny_gemm_kernel<MB>, dim3(grid), dim3(kGemmThreads), 0, stream, p);
+  static bool lds_limit_raised = false;  // (same value whoever sets it first)
+  if (!lds_limit_raised) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_gemm_kernel<MB>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, GemmCfg<MB>::SMEM);
+    if (e != hipSuccess) return e;
+    lds_limit_raised = true;
+  }
+  const unsigned grid = (unsigned)((p.n + GemmCfg<MB>::STRIP - 1) / GemmCfg<MB>::STRIP);
+  hipLaunchKernelGGL(skinny_gemm_kernel<MB>, dim3(grid), dim3(kGemmThreads), GemmCfg<MB>::SMEM, stream, p);
   return hipGetLastError();
 }
 
@@ -205,16 +304,27 @@ hipError_t launch_gemm(const GemmParams& p, hipStream_t stream) {
 }
 
 // ------------------------------------------------------------------ softmax + top-k per logits row
-constexpr int kSoftThreads = 1024;
-constexpr int kSoftWaves = kSoftThreads / 64;
-constexpr int kCandCap = 4096;
+// A row (a vocabulary of 10^5 entries) is cut into parts of at most 16 384 entries so that the
+// work spreads over all CUs:
+//   row_parts_kernel   per (row, part): maximum, sum of exp((x - max) / T), the part's k best
+//   row_merge_kernel   per row: the row's maximum and normaliser from the parts' pairs, the k
+//                      best of the parts' candidates, their probabilities
+//   row_probs_kernel   per (row, part): q = exp((x - max) / T) / Z      (skipped if not asked for)
+constexpr int kPartThreads = 256;
+constexpr int kPartPerThread = 64;                             // entries a thread holds in registers
+constexpr int kPartMax = kPartThreads * kPartPerThread;        // 16 384
+constexpr int kMaxTopK = 16;
 
 struct SoftParams {
   const float* logits;  // [n_rows][vocab]
   float* probs;         // [n_rows][vocab] or nullptr
   int* tk_ids;          // [n_rows][k]
   float* tk_probs;      // [n_rows][k]
-  int n_rows, vocab, k;
+  float* part_ms;       // [n_rows][parts][2]   max, sum
+  float* part_cv;       // [n_rows][parts][k]   candidate values
+  int* part_ci;         // [n_rows][parts][k]   candidate ids (INT_MAX: none)
+  float* row_mz;        // [n_rows][2]          max, 1 / normaliser
+  int n_rows, vocab, k, parts, part_len;  // part_len: entries per part, a multiple of 4
   float inv_temp;
 };
 
@@ -227,9 +337,13 @@ struct Best {
   float v;
   int id;
 };
+// the same order without short-circuit evaluation: both operands are always read, so that a
+// counting loop over LDS stays free of branches and its reads can be batched
+__device__ __forceinline__ int beats(float av, int ai, float bv, int bi) {
+  return (int)(av > bv) | ((int)(av == bv) & (int)(ai < bi));
+}
 
-// best (value, id) pair of the block, for every thread
-__device__ __forceinline__ Best block_best(float v, int id, float* sv, int* si) {
+__device__ __forceinline__ Best wave_best(float v, int id) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {
     const float ov = __shfl_xor(v, o);
@@ -239,189 +353,319 @@ __device__ __forceinline__ Best block_best(float v, int id, float* sv, int* si) 
       id = oi;
     }
   }
-  __syncthreads();  // the previous round's readers are done with sv, si
+  return Best{v, id};
+}
+
+constexpr int kCandCap = 512;
+
+// best (value, id) pair of a 4-wave workgroup, for every thread.  `buf` alternates between
+// consecutive calls, so that one barrier per call is enough.
+__device__ __forceinline__ Best block_best4(float v, int id, float (*sv)[4], int (*si)[4], int buf) {
+  const Best w = wave_best(v, id);
   if ((threadIdx.x & 63) == 0) {
-    sv[threadIdx.x >> 6] = v;
-    si[threadIdx.x >> 6] = id;
+    sv[buf][threadIdx.x >> 6] = w.v;
+    si[buf][threadIdx.x >> 6] = w.id;
   }
   __syncthreads();
-  Best b{sv[0], si[0]};
+  Best b{sv[buf][0], si[buf][0]};
 #pragma unroll
-  for (int i = 1; i < kSoftWaves; ++i)
-    if (better(sv[i], si[i], b.v, b.id)) b = Best{sv[i], si[i]};
+  for (int i = 1; i < 4; ++i)
+    if (better(sv[buf][i], si[buf][i], b.v, b.id)) b = Best{sv[buf][i], si[buf][i]};
   return b;
 }
 
-// One workgroup per row.  Top-k: the k-th largest of the threads' own maxima is a lower bound of
-// the row's k-th largest value, so only elements at or above it can be among the top k; they
-// are collected in LDS during the normaliser pass (few, unless the row is full of ties) and the
-// k winners are picked from that list.  A row with more such elements than the list holds is
-// handled by k selection passes over the whole row instead.
-__global__ __launch_bounds__(kSoftThreads) void draft_softmax_topk_kernel(SoftParams p) {
-  __shared__ float sv[kSoftWaves];
-  __shared__ int si[kSoftWaves];
-  __shared__ double sd[kSoftWaves];
+// Top-k of a part: the k-th largest of 64 disjoint groups' maxima is a lower bound of the part's
+// k-th largest value, so only entries at or above it can be among the k best; they are put on a
+// short list in LDS (few, unless the part is full of ties) and each listed entry finds its place
+// by counting the entries that beat it.  A part with more such entries than the list holds
+// takes k passes over the registers instead.
+__global__ __launch_bounds__(kPartThreads) void row_parts_kernel(SoftParams p) {
+  __shared__ float sv[2][4];
+  __shared__ int si[2][4];
+  __shared__ float sf[4];
   __shared__ float cand_v[kCandCap];
   __shared__ int cand_i[kCandCap];
   __shared__ int n_cand;
-  __shared__ float win_v[16];
-  __shared__ int win_i[16];
+  __shared__ float lane_max[kPartThreads];
+  __shared__ float s_tau;
   const int tid = threadIdx.x, V = p.vocab, K = p.k;
-  const float* x = p.logits + (long long)blockIdx.x * V;
+  const int row = blockIdx.x / p.parts, part = blockIdx.x % p.parts;
+  const int lo = part * p.part_len, hi = min(V, lo + p.part_len);
+  const float* x = p.logits + (long long)row * V;
   const bool vec = (V & 3) == 0 && (reinterpret_cast<size_t>(p.logits) & 15) == 0;
-  const int n4 = vec ? V / 4 : 0;
-  const floatx4* x4 = reinterpret_cast<const floatx4*>(x);
+  if (tid == 0) {
+    n_cand = 0;
+    s_tau = -INFINITY;
+  }
 
-  // every element once, ids increasing within a thread
-  auto for_each = [&](auto&& fn) {
-    for (int i = tid; i < n4; i += kSoftThreads) {
-      const floatx4 q = x4[i];
-      fn(4 * i, q[0]);
-      fn(4 * i + 1, q[1]);
-      fn(4 * i + 2, q[2]);
-      fn(4 * i + 3, q[3]);
-    }
-    for (int i = 4 * n4 + tid; i < V; i += kSoftThreads) fn(i, x[i]);
-  };
-
-  // pass 1: each thread's maximum
-  float tv = -INFINITY;
-  int ti = INT_MAX;
-  for_each([&](int i, float v) {
-    if (v > tv) {
-      tv = v;
-      ti = i;
-    }
-  });
-  if (tid == 0) n_cand = 0;
-  float row_max = -INFINITY, tau = -INFINITY;
-  for (int i = 0; i < K; ++i) {
-    const Best b = block_best(tv, ti, sv, si);
-    if (i == 0) row_max = b.v;
-    tau = b.id == INT_MAX ? -INFINITY : b.v;
-    if (b.id == ti) {  // (ids are distinct, INT_MAX marks "none")
-      tv = -INFINITY;
-      ti = INT_MAX;
+  // entry (u, c) of this thread is vocabulary id lo + 4 (tid + 256 u) + c: ids increase with (u, c)
+  auto id_of = [&](int i) { return lo + 4 * (tid + kPartThreads * (i >> 2)) + (i & 3); };
+  float val[kPartPerThread];
+#pragma unroll
+  for (int u = 0; u < kPartPerThread / 4; ++u) {
+    const int e = lo + 4 * (tid + kPartThreads * u);
+    if (vec && e + 3 < hi) {
+      const floatx4 q = *reinterpret_cast<const floatx4*>(x + e);
+#pragma unroll
+      for (int c = 0; c < 4; ++c) val[4 * u + c] = q[c];
+    } else {
+#pragma unroll
+      for (int c = 0; c < 4; ++c) val[4 * u + c] = e + c < hi ? x[e + c] : -INFINITY;
     }
   }
-  if (!(row_max > -INFINITY)) row_max = 0.f;  // a row of -inf (or NaN): nothing sensible to subtract
+  // the thread's own maximum (first of equal values: lowest id)
+  float tv = -INFINITY;
+  int ti = INT_MAX;
+#pragma unroll
+  for (int i = 0; i < kPartPerThread; ++i)
+    if (val[i] > tv) {
+      tv = val[i];
+      ti = id_of(i);
+    }
+  float m = tv;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+  if ((tid & 63) == 0) sf[tid >> 6] = m;
   __syncthreads();
+  m = fmaxf(fmaxf(sf[0], sf[1]), fmaxf(sf[2], sf[3]));
+  const float m_use = m > -INFINITY ? m : 0.f;  // a part of -inf only: nothing sensible to subtract
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < kPartPerThread; ++i) s += expf((val[i] - m_use) * p.inv_temp);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+  __syncthreads();
+  if ((tid & 63) == 0) sf[tid >> 6] = s;
+  __syncthreads();
+  const long long slot = (long long)row * p.parts + part;
+  if (tid == 0) {
+    p.part_ms[2 * slot] = m;
+    p.part_ms[2 * slot + 1] = (sf[0] + sf[1]) + (sf[2] + sf[3]);
+  }
 
-  // pass 2: normaliser and candidates
-  float lsum = 0.f;
-  for_each([&](int i, float v) {
-    lsum += expf((v - row_max) * p.inv_temp);
-    if (v >= tau) {
-      const int slot = atomicAdd(&n_cand, 1);
-      if (slot < kCandCap) {
-        cand_v[slot] = v;
-        cand_i[slot] = i;
+  // threshold: the k-th largest of the 64 per-lane maxima (maximum over the four waves of the
+  // threads' own maxima), found by ranking: no rounds, no reductions
+  lane_max[tid] = tv;
+  __syncthreads();
+  if (tid < 64) {
+    const float v = fmaxf(fmaxf(lane_max[tid], lane_max[tid + 64]), fmaxf(lane_max[tid + 128], lane_max[tid + 192]));
+    lane_max[tid] = v;  // (wave 0 only reads and writes its own column here)
+  }
+  __syncthreads();
+  if (tid < 64) {
+    const float mine = lane_max[tid];
+    int rank = 0;
+#pragma unroll 8
+    for (int j = 0; j < 64; ++j) {
+      rank += beats(lane_max[j], j, mine, tid);
+    }
+    if (rank == K - 1) s_tau = mine;
+  }
+  __syncthreads();
+  const float tau = s_tau;
+#pragma unroll
+  for (int i = 0; i < kPartPerThread; ++i)
+    if (val[i] >= tau && id_of(i) < hi) {
+      const int at = atomicAdd(&n_cand, 1);
+      if (at < kCandCap) {
+        cand_v[at] = val[i];
+        cand_i[at] = id_of(i);
       }
     }
-  });
-  double ds = (double)lsum;
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) ds += __shfl_xor(ds, o);
-  if ((tid & 63) == 0) sd[tid >> 6] = ds;
   __syncthreads();
-  double z = 0.0;
-#pragma unroll
-  for (int i = 0; i < kSoftWaves; ++i) z += sd[i];
-  const float inv_z = (float)(1.0 / z);
   const int nc = n_cand;
-
+  int round_no = 0;
   if (nc <= kCandCap) {
-    for (int i = 0; i < K; ++i) {
-      float bv = -INFINITY;
-      int bi = INT_MAX, bj = -1;
-      for (int j = tid; j < nc; j += kSoftThreads)
-        if (better(cand_v[j], cand_i[j], bv, bi)) {
-          bv = cand_v[j];
-          bi = cand_i[j];
-          bj = j;
-        }
-      const Best b = block_best(bv, bi, sv, si);
-      if (bj >= 0 && b.id == bi) {  // mine: take it out of the list
-        cand_v[bj] = -INFINITY;
-        cand_i[bj] = INT_MAX;
+    // rank every listed entry among the list; ranks below k are the winners' places
+    if (tid < K && tid >= nc) {  // (a part with fewer than k entries)
+      p.part_cv[slot * K + tid] = -INFINITY;
+      p.part_ci[slot * K + tid] = INT_MAX;
+    }
+    for (int j = tid; j < nc; j += kPartThreads) {
+      const float v = cand_v[j];
+      const int id = cand_i[j];
+      int rank = 0;
+#pragma unroll 8
+      for (int i = 0; i < nc; ++i) rank += beats(cand_v[i], cand_i[i], v, id);
+      if (rank < K) {
+        p.part_cv[slot * K + rank] = v;
+        p.part_ci[slot * K + rank] = id;
       }
-      if (tid == 0) {
-        win_v[i] = b.v;
-        win_i[i] = b.id;
-      }
-      // (the next round's first barrier inside block_best orders the removal before the scans)
-      __syncthreads();
     }
   } else {
+    // one winner per pass: every thread offers its best entry that comes after the previous
+    // winner in the candidate order
     float pv = INFINITY;
     int pi = -1;
-    for (int i = 0; i < K; ++i) {
+    for (int round = 0; round < K; ++round) {
       float bv = -INFINITY;
       int bi = INT_MAX;
-      for_each([&](int id, float v) {
-        const bool after = pi < 0 || v < pv || (v == pv && id > pi);
-        if (after && better(v, id, bv, bi)) {
+#pragma unroll
+      for (int i = 0; i < kPartPerThread; ++i) {
+        const int id = id_of(i);
+        const float v = val[i];
+        const bool after = v < pv || (v == pv && id > pi);
+        // ids increase with i, so among equal values the first one seen is the one to keep
+        if (after && id < hi && v > bv) {
           bv = v;
           bi = id;
         }
-      });
-      const Best b = block_best(bv, bi, sv, si);
-      pv = b.v;
-      pi = b.id == INT_MAX ? V : b.id;
-      if (tid == 0) {
-        win_v[i] = b.v;
-        win_i[i] = b.id;
       }
+      const Best b = block_best4(bv, bi, sv, si, (round_no++) & 1);
+      if (tid == 0) {
+        p.part_cv[slot * K + round] = b.v;
+        p.part_ci[slot * K + round] = b.id;
+      }
+      pv = b.v;
+      pi = b.id;  // INT_MAX once the part is exhausted: nothing comes after it
+    }
+  }
+}
+
+// one wave per row
+__global__ __launch_bounds__(64) void row_merge_kernel(SoftParams p) {
+  const int lane = threadIdx.x, row = blockIdx.x, K = p.k, P = p.parts;
+  const float* ms = p.part_ms + (long long)row * P * 2;
+  float m = -INFINITY;
+  for (int i = lane; i < P; i += 64) m = fmaxf(m, ms[2 * i]);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+  const float m_use = m > -INFINITY ? m : 0.f;
+  double z = 0.0;
+  for (int i = lane; i < P; i += 64) {
+    const float mp = ms[2 * i];
+    if (mp > -INFINITY) z += (double)ms[2 * i + 1] * (double)expf((mp - m_use) * p.inv_temp);
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) z += __shfl_xor(z, o);
+  const float inv_z = (float)(1.0 / z);
+  if (lane == 0) {
+    p.row_mz[2 * row] = m_use;
+    p.row_mz[2 * row + 1] = inv_z;
+  }
+  const float* cv = p.part_cv + (long long)row * P * K;
+  const int* ci = p.part_ci + (long long)row * P * K;
+  const int n = P * K;
+  auto emit = [&](int round, const Best& b) {
+    if (lane == 0) {
+      const bool ok = b.id >= 0 && b.id < p.vocab;
+      p.tk_ids[(long long)row * K + round] = ok ? b.id : 0;
+      p.tk_probs[(long long)row * K + round] = ok ? expf((b.v - m_use) * p.inv_temp) * inv_z : 0.f;
+    }
+  };
+  if (n <= 256) {  // the usual case: every candidate finds its place by counting those that beat it
+    __shared__ float mv[256];
+    __shared__ int mi[256];
+    for (int i = lane; i < n; i += 64) {
+      mv[i] = cv[i];
+      mi[i] = ci[i];
+    }
+    // places that no candidate claims (fewer than k candidates in the whole row) read "none";
+    // the winners' stores below come later in this wave's program order
+    if (lane < K) {
+      p.tk_ids[(long long)row * K + lane] = 0;
+      p.tk_probs[(long long)row * K + lane] = 0.f;
     }
     __syncthreads();
-  }
-  if (tid < K) {
-    const int id = win_i[tid];
-    const bool ok = id >= 0 && id < V;
-    p.tk_ids[(long long)blockIdx.x * K + tid] = ok ? id : 0;
-    p.tk_probs[(long long)blockIdx.x * K + tid] = ok ? expf((win_v[tid] - row_max) * p.inv_temp) * inv_z : 0.f;
-  }
-
-  // pass 3: the distribution itself
-  if (p.probs) {
-    float* q = p.probs + (long long)blockIdx.x * V;
-    floatx4* q4 = reinterpret_cast<floatx4*>(q);
-    const bool qvec = vec && (reinterpret_cast<size_t>(p.probs) & 15) == 0;
-    if (qvec) {
-      for (int i = tid; i < n4; i += kSoftThreads) {
-        const floatx4 s = x4[i];
-        floatx4 o;
-#pragma unroll
-        for (int t = 0; t < 4; ++t) o[t] = expf((s[t] - row_max) * p.inv_temp) * inv_z;
-        q4[i] = o;
+    for (int j = lane; j < n; j += 64) {
+      const float v = mv[j];
+      const int id = mi[j];
+      if (id < 0 || id >= p.vocab) continue;  // an exhausted part's filler
+      int rank = 0;
+#pragma unroll 8
+      for (int i = 0; i < n; ++i) rank += beats(mv[i], mi[i], v, id);
+      if (rank < K) {
+        p.tk_ids[(long long)row * K + rank] = id;
+        p.tk_probs[(long long)row * K + rank] = expf((v - m_use) * p.inv_temp) * inv_z;
       }
+    }
+    return;
+  }
+  float pv = INFINITY;
+  int pi = -1;
+  for (int round = 0; round < K; ++round) {
+    float bv = -INFINITY;
+    int bi = INT_MAX;
+    for (int i = lane; i < n; i += 64) {
+      const float v = cv[i];
+      const int id = ci[i];
+      const bool after = v < pv || (v == pv && id > pi);
+      if (after && better(v, id, bv, bi)) {
+        bv = v;
+        bi = id;
+      }
+    }
+    const Best b = wave_best(bv, bi);
+    emit(round, b);
+    pv = b.v;
+    pi = b.id;
+  }
+}
+
+__global__ __launch_bounds__(kPartThreads) void row_probs_kernel(SoftParams p) {
+  const int tid = threadIdx.x, V = p.vocab;
+  const int row = blockIdx.x / p.parts, part = blockIdx.x % p.parts;
+  const int lo = part * p.part_len, hi = min(V, lo + p.part_len);
+  const float* x = p.logits + (long long)row * V;
+  float* q = p.probs + (long long)row * V;
+  const float m = p.row_mz[2 * row], inv_z = p.row_mz[2 * row + 1];
+  const bool vec = (V & 3) == 0 && (reinterpret_cast<size_t>(p.logits) & 15) == 0 &&
+                   (reinterpret_cast<size_t>(p.probs) & 15) == 0;
+#pragma unroll 4
+  for (int u = 0; u < kPartPerThread / 4; ++u) {
+    const int e = lo + 4 * (tid + kPartThreads * u);
+    if (vec && e + 3 < hi) {
+      const floatx4 s = *reinterpret_cast<const floatx4*>(x + e);
+      floatx4 o;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) o[c] = expf((s[c] - m) * p.inv_temp) * inv_z;
+      *reinterpret_cast<floatx4*>(q + e) = o;
     } else {
-      for (int i = tid; i < V; i += kSoftThreads) q[i] = expf((x[i] - row_max) * p.inv_temp) * inv_z;
+      for (int c = 0; c < 4; ++c)
+        if (e + c < hi) q[e + c] = expf((x[e + c] - m) * p.inv_temp) * inv_z;
     }
   }
+}
+
+struct RowPlan {
+  int parts, part_len;
+  size_t x_bytes, ms_off, cv_off, ci_off, mz_off, total;
+};
+RowPlan row_plan(int rows, int d_model, int vocab) {
+  RowPlan r;
+  const size_t m = 2 * (size_t)rows, m_pad = (m + 31) / 32 * 32;
+  r.parts = (vocab + kPartMax - 1) / kPartMax;
+  r.part_len = ((vocab + r.parts - 1) / r.parts + 3) / 4 * 4;
+  auto up = [](size_t v) { return (v + 255) / 256 * 256; };
+  r.x_bytes = up(m_pad * (size_t)d_model * 2);
+  r.ms_off = r.x_bytes;
+  r.cv_off = r.ms_off + up(m * r.parts * 2 * 4);
+  r.ci_off = r.cv_off + up(m * r.parts * kMaxTopK * 4);
+  r.mz_off = r.ci_off + up(m * r.parts * kMaxTopK * 4);
+  r.total = r.mz_off + up(m * 2 * 4);
+  return r;
 }
 
 }  // namespace
 
-size_t draft_heads_workspace_bytes(int rows, int d_model) {
-  const size_t m_pad = (size_t)((2 * rows + 31) / 32) * 32;
-  return (m_pad * (size_t)d_model * 2 + 255) / 256 * 256;
-}
+size_t draft_heads_workspace_bytes(int rows, int d_model, int vocab) { return row_plan(rows, d_model, vocab).total; }
 
 hipError_t launch_draft_heads(const DraftHeadsArgs& a, hipStream_t stream) {
   const int m = 2 * a.rows, m_pad = (m + 31) / 32 * 32;
+  const RowPlan rp = row_plan(a.rows, a.d_model, a.vocab);
+  char* ws = static_cast<char*>(a.workspace);
   MixParams mp;
   mp.f_top = static_cast<const unsigned short*>(a.f_top);
   mp.s_top = a.s_top;
-  mp.x = static_cast<unsigned short*>(a.workspace);
+  mp.x = reinterpret_cast<unsigned short*>(ws);
   mp.rows = a.rows; mp.d = a.d_model; mp.mode = a.mode; mp.alpha = a.alpha; mp.beta = a.beta;
   hipLaunchKernelGGL(head_inputs_kernel, dim3(m_pad), dim3(256), 0, stream, mp);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
 
   GemmParams gp;
-  gp.x = mp.x;
-  gp.w = static_cast<const unsigned short*>(a.w_head);
+  gp.x = reinterpret_cast<const uint16_t*>(ws);
+  gp.w = static_cast<const uint16_t*>(a.w_head);
   gp.y = a.logits;
   gp.m = m; gp.n = a.vocab; gp.k = a.d_model;
   gp.ldw = a.d_model; gp.ldy = a.vocab;
@@ -430,9 +674,21 @@ hipError_t launch_draft_heads(const DraftHeadsArgs& a, hipStream_t stream) {
 
   SoftParams sp;
   sp.logits = a.logits; sp.probs = a.draft_probs; sp.tk_ids = a.topk_tokens; sp.tk_probs = a.topk_probs;
-  sp.n_rows = m; sp.vocab = a.vocab; sp.k = a.top_k; sp.inv_temp = 1.0f / a.temperature;
-  hipLaunchKernelGGL(draft_softmax_topk_kernel, dim3(m), dim3(kSoftThreads), 0, stream, sp);
-  return hipGetLastError();
+  sp.part_ms = reinterpret_cast<float*>(ws + rp.ms_off);
+  sp.part_cv = reinterpret_cast<float*>(ws + rp.cv_off);
+  sp.part_ci = reinterpret_cast<int*>(ws + rp.ci_off);
+  sp.row_mz = reinterpret_cast<float*>(ws + rp.mz_off);
+  sp.n_rows = m; sp.vocab = a.vocab; sp.k = a.top_k; sp.parts = rp.parts; sp.part_len = rp.part_len;
+  sp.inv_temp = 1.0f / a.temperature;
+  hipLaunchKernelGGL(row_parts_kernel, dim3(m * rp.parts), dim3(kPartThreads), 0, stream, sp);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  hipLaunchKernelGGL(row_merge_kernel, dim3(m), dim3(64), 0, stream, sp);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  if (a.draft_probs) {
+    hipLaunchKernelGGL(row_probs_kernel, dim3(m * rp.parts), dim3(kPartThreads), 0, stream, sp);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 }  // namespace jk

@@ -94,7 +94,7 @@ struct DraftHeadsArgs {
   int32_t* topk_tokens;
   void* workspace;
 };
-size_t draft_heads_workspace_bytes(int rows, int d_model);
+size_t draft_heads_workspace_bytes(int rows, int d_model, int vocab);
 hipError_t launch_draft_heads(const DraftHeadsArgs& a, hipStream_t stream);
 
 }  // namespace jk
