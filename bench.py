@@ -95,6 +95,9 @@ def main():
                     help="keep the KV caches in page pools of this page size (a multiple of 32) with a shuffled "
                          "block table and time jk_tree_verify_attention_paged instead")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-draft-heads", action="store_true", help="skip the jk_draft_heads timing (extra field)")
+    ap.add_argument("--draft-rows", type=int, default=0, help="hidden states per jk_draft_heads call "
+                    "(default: 10 per sequence of the workload)")
     ap.add_argument("--no-graph", action="store_true", help="issue every library call from Python instead of "
                     "replaying the step's two HIP graphs")
     ap.add_argument("--copy-calibration", type=int, default=0,
@@ -271,6 +274,48 @@ def main():
     commit_us = ec0.elapsed_time(ec1) * 1e3 / (5 * 16)
     commit_bytes = args.layers * 4 * cfg.batch * n_commit * cfg.n_kv_heads * cfg.head_dim * layers[0]["k_cache"].element_size()
 
+    # the step in front of the path (not part of the timed step): both draft heads over the shared
+    # output embedding for the nodes one draft step expands (10 per sequence), random weights
+    draft = None
+    if not args.no_draft_heads:
+        dh_rows = min(128, args.draft_rows if args.draft_rows > 0 else 10 * cfg.batch)
+        d_model = cfg.n_q_heads * cfg.head_dim
+        gen = torch.Generator(device=dev).manual_seed(cfg.seed)
+        dh_f = torch.randn((dh_rows, 2, d_model), device=dev, generator=gen).to(torch.bfloat16)
+        dh_s = torch.rand((dh_rows, 2), device=dev, generator=gen) * 0.5
+        dh_w = (torch.randn((cfg.vocab, d_model), device=dev, generator=gen) * (5.0 / d_model ** 0.5)).to(torch.bfloat16)
+        dh_lg = torch.empty((dh_rows, 2, cfg.vocab), device=dev)
+        dh_q = torch.empty((dh_rows, 2, cfg.vocab), device=dev)
+        dh_tk = torch.empty((dh_rows, 2, 10), dtype=torch.int32, device=dev)
+        dh_tp = torch.empty((dh_rows, 2, 10), device=dev)
+        dh_ws = torch.empty(jk.draft_heads_workspace(dh_rows, d_model, cfg.vocab), dtype=torch.uint8, device=dev)
+        dh_call = jk.prepare_draft_heads(dh_f, dh_s, dh_w, jk.JK_HEADS_DECOUPLED, 1.0, 10, 0.0, 0.0, dh_lg, dh_q,
+                                         dh_tk, dh_tp, dh_ws)
+        def draft_pass():
+            for _ in range(4):
+                dh_call.launch()
+        draft_pass()
+        torch.cuda.synchronize()
+        g_draft = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g_draft, stream=torch.cuda.Stream()):
+            draft_pass()
+        g_draft.replay()
+        torch.cuda.synchronize()
+        ed0, ed1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ed0.record()
+        for _ in range(5):
+            g_draft.replay()
+        ed1.record()
+        torch.cuda.synchronize()
+        dh_us = ed0.elapsed_time(ed1) * 1e3 / 20
+        w_bytes = cfg.vocab * d_model * 2
+        draft = {"us_per_call": round(dh_us, 1), "rows": dh_rows, "d_model": d_model, "vocab": cfg.vocab, "top_k": 10,
+                 "weight_stream_GBps": round(w_bytes / (dh_us * 1e-6) / 1e9, 1),
+                 "TFLOPs": round(4.0 * dh_rows * d_model * cfg.vocab / (dh_us * 1e-6) / 1e12, 1),
+                 "note": "one jk_draft_heads call: head inputs, both heads' logits, draft distributions, top-10 "
+                         "(not in ms_per_step)"}
+        del dh_w, dh_lg, dh_q
+
     for _ in range(args.copy_calibration):
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)
@@ -310,6 +355,7 @@ def main():
                         "bytes_per_call": commit_bytes,
                         "layers": args.layers,
                         "note": "one jk_commit_path_layers call for all layers after the step (not in ms_per_step)"},
+        "draft_heads": draft,
         "roofline": {"bound": "hbm", "achieved": round(gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(gbps / HBM_PEAK_GBPS, 4), "traffic": MEASURED_TRAFFIC.get(cfg.name),
                      "kernel": "tva_bf16_kernel (+ tva_combine_kernel): time per jk_tree_verify_attention call",
