@@ -287,6 +287,42 @@ jk_status jk_draft_heads(const jk_draft_heads_desc* desc, const void* f_top, con
                          const void* w_head, float* logits, float* draft_probs, int32_t* topk_tokens,
                          float* topk_probs, void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* The draft layer's router and expert MLPs that produce jk_draft_heads' inputs
+ * (Section 3.1.2, Eq. 2, 3 and 5 with K = 2 activated experts), for `rows`
+ * hidden states u (Eq. 1's output: the draft layer's attention plus residual is
+ * an input here):
+ *
+ *   s_j = softmax_j(u . e_j)                  router over the n_experts centroids (Eq. 2, fp32)
+ *   top1, top2 = the two largest s_j, larger first, ties to the lower expert (Eq. 5)
+ *   f_top[r][k] = Expert_topk(u_r) + u_r      Expert_j(x) = w_down_j (silu(w_gate_j x) * (w_up_j x))
+ *   f_mix[r]    = s_top1 Expert_top1(u_r) + s_top2 Expert_top2(u_r) + u_r            (Eq. 3)
+ *
+ * (The paper calls the experts lightweight MLPs and leaves out normalisation
+ * layers; the gated form is this library's reading.)  The projections run
+ * through the same MFMA kernel as jk_draft_heads with bf16 operands and fp32
+ * accumulation; the hidden activation silu(gate)*up and the outputs are rounded
+ * to bf16 once each.  Every expert that at least one row selected is evaluated
+ * for all rows (its weights are streamed once either way; gathering rows would
+ * cost more than the MFMAs it saves); experts that no row selected are skipped.
+ *
+ *   rows        1..128;  d_model, d_ff multiples of 128 up to 65536;  n_experts 2..64
+ *   u           device bf16 [rows][d_model], 16-byte aligned
+ *   centroids   device bf16 [n_experts][d_model]
+ *   w_gate, w_up  device bf16 [n_experts][d_ff][d_model];  w_down [n_experts][d_model][d_ff]
+ *   f_top       device bf16 [rows][2][d_model], written
+ *   s_top       device fp32 [rows][2], written;  expert_idx device int32 [rows][2], written
+ *   f_mix       device bf16 [rows][d_model], written; may be NULL
+ *   workspace   jk_moe_experts_workspace(desc) bytes, 256-byte aligned */
+typedef struct {
+  int32_t rows, d_model, d_ff, n_experts;
+} jk_moe_desc;
+
+size_t jk_moe_experts_workspace(const jk_moe_desc* desc);
+
+jk_status jk_moe_experts(const jk_moe_desc* desc, const void* u, const void* centroids, const void* w_gate,
+                         const void* w_up, const void* w_down, void* f_top, float* s_top, int32_t* expert_idx,
+                         void* f_mix, void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Zero-fills a workspace with a small kernel on `hip_stream` (safe under HIP-graph
  * capture).  Needed once per workspace before its first jk_accept_path call: the
  * cooperative sampling walk synchronises its workgroups through tagged words in

@@ -46,6 +46,12 @@ class DraftHeadsDesc(ctypes.Structure):
                 ("alpha", ctypes.c_float), ("beta", ctypes.c_float)]
 
 
+class MoeDesc(ctypes.Structure):
+    """jk_moe_desc"""
+    _fields_ = [("rows", ctypes.c_int32), ("d_model", ctypes.c_int32), ("d_ff", ctypes.c_int32),
+                ("n_experts", ctypes.c_int32)]
+
+
 class PagedKV(ctypes.Structure):
     """jk_paged_kv"""
     _fields_ = [("block_table", ctypes.c_void_p), ("max_blocks", ctypes.c_int32), ("page_size", ctypes.c_int32),
@@ -54,7 +60,7 @@ class PagedKV(ctypes.Structure):
 
 EXPORTS = ("jk_tree_verify_attention_workspace", "jk_tree_verify_attention", "jk_tree_verify_attention_paged",
            "jk_commit_path_layers_paged", "jk_accept_path_workspace",
-           "jk_accept_path", "jk_draft_heads_workspace", "jk_draft_heads", "jk_commit_path", "jk_commit_path_layers", "jk_workspace_init", "jk_stream_read_probe", "jk_validate_tree", "jk_status_string", "jk_version")
+           "jk_accept_path", "jk_draft_heads_workspace", "jk_draft_heads", "jk_moe_experts_workspace", "jk_moe_experts", "jk_commit_path", "jk_commit_path_layers", "jk_workspace_init", "jk_stream_read_probe", "jk_validate_tree", "jk_status_string", "jk_version")
 
 
 def library_path() -> str:
@@ -94,6 +100,10 @@ def lib() -> ctypes.CDLL:
         l.jk_draft_heads_workspace.argtypes = [i32, i32, i32]
         l.jk_draft_heads.restype = i32
         l.jk_draft_heads.argtypes = [ctypes.POINTER(DraftHeadsDesc), vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        l.jk_moe_experts_workspace.restype = sz
+        l.jk_moe_experts_workspace.argtypes = [ctypes.POINTER(MoeDesc)]
+        l.jk_moe_experts.restype = i32
+        l.jk_moe_experts.argtypes = [ctypes.POINTER(MoeDesc), vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         l.jk_workspace_init.restype = i32
         l.jk_workspace_init.argtypes = [vp, sz, vp]
         l.jk_stream_read_probe.restype = i32
@@ -468,3 +478,54 @@ def prepare_draft_heads(f_top, s_top, w_head, mode, temperature, top_k, alpha, b
                                    topk_tokens, topk_probs, workspace)
     return PreparedCall(lib().jk_draft_heads, "jk_draft_heads", args, 10,
                         (desc, f_top, s_top, w_head, logits, draft_probs, topk_tokens, topk_probs, workspace))
+
+
+def _moe_args(u, centroids, w_gate, w_up, w_down, f_top, s_top, expert_idx, f_mix, workspace):
+    import torch
+    R, d = u.shape
+    N, F, d2 = w_gate.shape
+    if d2 != d or tuple(centroids.shape) != (N, d) or tuple(w_up.shape) != (N, F, d) or tuple(w_down.shape) != (N, d, F):
+        raise ValueError("u [R,d], centroids [N,d], w_gate/w_up [N,F,d], w_down [N,d,F]")
+    for t in (u, centroids, w_gate, w_up, w_down, f_top, f_mix):
+        if t is not None and (t.dtype != torch.bfloat16 or not t.is_contiguous()):
+            raise TypeError("features and weights must be contiguous bfloat16")
+    if s_top.dtype != torch.float32 or expert_idx.dtype != torch.int32:
+        raise TypeError("s_top float32, expert_idx int32")
+    desc = MoeDesc(R, d, F, N)
+    need = int(lib().jk_moe_experts_workspace(ctypes.byref(desc)))
+    if workspace is None:
+        if need == 0:
+            raise JakiroError(3, "jk_moe_experts_workspace")
+        workspace = torch.empty(need, dtype=torch.uint8, device=u.device)
+    args = [ctypes.byref(desc), _ptr(u), _ptr(centroids), _ptr(w_gate), _ptr(w_up), _ptr(w_down), _ptr(f_top),
+            _ptr(s_top), _ptr(expert_idx), _ptr(f_mix), _ptr(workspace), workspace.numel() * workspace.element_size(),
+            None]
+    return desc, args, workspace
+
+
+def moe_experts_workspace(rows: int, d_model: int, d_ff: int, n_experts: int) -> int:
+    return int(lib().jk_moe_experts_workspace(ctypes.byref(MoeDesc(int(rows), int(d_model), int(d_ff), int(n_experts)))))
+
+
+def moe_experts(u, centroids, w_gate, w_up, w_down, want_mix: bool = True, stream=None):
+    """jk_moe_experts.  Returns (f_top [R,2,d] bf16, s_top [R,2], expert_idx [R,2] int32, f_mix [R,d] bf16 or None)."""
+    import torch
+    R, d = u.shape
+    dev = u.device
+    f_top = torch.empty((R, 2, d), dtype=torch.bfloat16, device=dev)
+    s_top = torch.empty((R, 2), dtype=torch.float32, device=dev)
+    idx = torch.empty((R, 2), dtype=torch.int32, device=dev)
+    f_mix = torch.empty((R, d), dtype=torch.bfloat16, device=dev) if want_mix else None
+    desc, args, ws = _moe_args(u, centroids, w_gate, w_up, w_down, f_top, s_top, idx, f_mix, None)
+    args[-1] = _stream_handle(stream)
+    st = lib().jk_moe_experts(*args)
+    if st != 0:
+        raise JakiroError(st, "jk_moe_experts")
+    return f_top, s_top, idx, f_mix
+
+
+def prepare_moe_experts(u, centroids, w_gate, w_up, w_down, f_top, s_top, expert_idx, f_mix, workspace) -> PreparedCall:
+    """jk_moe_experts with outputs and workspace given; nothing is launched."""
+    desc, args, ws = _moe_args(u, centroids, w_gate, w_up, w_down, f_top, s_top, expert_idx, f_mix, workspace)
+    return PreparedCall(lib().jk_moe_experts, "jk_moe_experts", args, 12,
+                        (desc, u, centroids, w_gate, w_up, w_down, f_top, s_top, expert_idx, f_mix, ws))

@@ -4,6 +4,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <initializer_list>
 
 #include "jk_internal.h"
 
@@ -359,6 +360,37 @@ jk_status jk_draft_heads(const jk_draft_heads_desc* desc, const void* f_top, con
   a.logits = logits; a.draft_probs = draft_probs; a.topk_probs = topk_probs; a.topk_tokens = topk_tokens;
   a.workspace = workspace;
   return launch_draft_heads(a, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? JK_OK : JK_ERR_HIP;
+}
+
+static bool moe_desc_ok(const jk_moe_desc& d) {
+  return d.rows >= 1 && d.d_model >= 1 && d.d_ff >= 1 && d.n_experts >= 2;
+}
+static bool moe_desc_supported(const jk_moe_desc& d) {
+  return d.rows <= 128 && d.d_model >= 128 && d.d_model <= 65536 && d.d_model % 128 == 0 && d.d_ff >= 128 &&
+         d.d_ff <= 65536 && d.d_ff % 128 == 0 && d.n_experts <= 64;
+}
+
+size_t jk_moe_experts_workspace(const jk_moe_desc* desc) {
+  if (!desc || !moe_desc_ok(*desc) || !moe_desc_supported(*desc)) return 0;
+  return moe_experts_workspace_bytes(desc->rows, desc->d_model, desc->d_ff, desc->n_experts);
+}
+
+jk_status jk_moe_experts(const jk_moe_desc* desc, const void* u, const void* centroids, const void* w_gate,
+                         const void* w_up, const void* w_down, void* f_top, float* s_top, int32_t* expert_idx,
+                         void* f_mix, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!desc || !u || !centroids || !w_gate || !w_up || !w_down || !f_top || !s_top || !expert_idx)
+    return JK_ERR_INVALID_ARG;
+  if (!moe_desc_ok(*desc)) return JK_ERR_INVALID_ARG;
+  for (const void* ptr : {u, centroids, w_gate, w_up, w_down, (const void*)f_top, (const void*)f_mix})
+    if (reinterpret_cast<uintptr_t>(ptr) % 16) return JK_ERR_INVALID_ARG;
+  if (!moe_desc_supported(*desc)) return JK_ERR_UNSUPPORTED;
+  const size_t need = moe_experts_workspace_bytes(desc->rows, desc->d_model, desc->d_ff, desc->n_experts);
+  if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256 || workspace_bytes < need) return JK_ERR_WORKSPACE;
+  MoeArgs a;
+  a.rows = desc->rows; a.d_model = desc->d_model; a.d_ff = desc->d_ff; a.n_experts = desc->n_experts;
+  a.u = u; a.centroids = centroids; a.w_gate = w_gate; a.w_up = w_up; a.w_down = w_down;
+  a.f_top = f_top; a.f_mix = f_mix; a.s_top = s_top; a.expert_idx = expert_idx; a.workspace = workspace;
+  return launch_moe_experts(a, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? JK_OK : JK_ERR_HIP;
 }
 
 jk_status jk_workspace_init(void* workspace, size_t workspace_bytes, void* hip_stream) {

@@ -85,6 +85,11 @@ struct GemmParams {
   float* y;           // [m][ldy]
   int m, n, k;
   long long ldw, ldy;
+  // batch (blockIdx.y): element offsets between consecutive problems; `used` (device, may be null)
+  // switches single problems off
+  int batch;
+  long long x_batch, w_batch, y_batch;
+  const int* used;
 };
 
 typedef __attribute__((address_space(3))) const bf16x8 lds_bf16x8_t;
@@ -159,6 +164,10 @@ __global__ __launch_bounds__(kGemmThreads, 1) void skinny_gemm_kernel(GemmParams
   using C = GemmCfg<MB>;
   constexpr int NBW = C::NBW;
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];  // the kernel's only LDS: offset 0
+  if (p.used && p.used[blockIdx.y] == 0) return;  // (the whole workgroup: nobody waits at a barrier)
+  p.x += (long long)blockIdx.y * p.x_batch;
+  p.w += (long long)blockIdx.y * p.w_batch;
+  p.y += (long long)blockIdx.y * p.y_batch;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 31, h = lane >> 5;
   const long long strip0 = (long long)blockIdx.x * C::STRIP;
@@ -285,7 +294,7 @@ hipError_t launch_gemm_mb(const GemmParams& p, hipStream_t stream) {
     lds_limit_raised = true;
   }
   const unsigned grid = (unsigned)((p.n + GemmCfg<MB>::STRIP - 1) / GemmCfg<MB>::STRIP);
-  hipLaunchKernelGGL(skinny_gemm_kernel<MB>, dim3(grid), dim3(kGemmThreads), GemmCfg<MB>::SMEM, stream, p);
+  hipLaunchKernelGGL(skinny_gemm_kernel<MB>, dim3(grid, (unsigned)p.batch), dim3(kGemmThreads), GemmCfg<MB>::SMEM, stream, p);
   return hipGetLastError();
 }
 
@@ -627,6 +636,149 @@ __global__ __launch_bounds__(kPartThreads) void row_probs_kernel(SoftParams p) {
   }
 }
 
+// ------------------------------------------------------------------ router and experts (Eq. 2, 3, 5)
+constexpr int kMaxExperts = 64;
+
+struct RouterParams {
+  const uint16_t* u;          // [rows][d] bf16
+  const uint16_t* centroids;  // [n_experts][d] bf16
+  uint16_t* x;                // [rows padded to 32][d] bf16: copy of u, zero rows behind it
+  float* s_top;               // [rows][2]
+  int* idx;                   // [rows][2]
+  int* used;                  // [n_experts], zeroed by clear_flags_kernel before
+  int rows, d, n_experts;
+};
+
+__global__ void clear_flags_kernel(int* used, int n) {
+  if ((int)threadIdx.x < n) used[threadIdx.x] = 0;
+}
+
+// One workgroup per (padded) row: copies the row into the GEMM's padded input, and for real rows
+// computes the router scores s_j = softmax_j(u . e_j) (Eq. 2; fp32), picks the two largest (Eq. 5,
+// K = 2, ties to the lower expert) and flags the chosen experts as used.
+__global__ __launch_bounds__(256) void router_kernel(RouterParams p) {
+  __shared__ float score[kMaxExperts];
+  const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  u32x4* dst = reinterpret_cast<u32x4*>(p.x + (long long)row * p.d);
+  if (row >= p.rows) {
+    for (int c = tid; c < p.d / 8; c += 256) dst[c] = u32x4{0u, 0u, 0u, 0u};
+    return;
+  }
+  const u32x4* src = reinterpret_cast<const u32x4*>(p.u + (long long)row * p.d);
+  for (int c = tid; c < p.d / 8; c += 256) dst[c] = src[c];
+  for (int j = wave; j < p.n_experts; j += 4) {
+    const u32x4* e = reinterpret_cast<const u32x4*>(p.centroids + (long long)j * p.d);
+    float acc = 0.f;
+    for (int c = lane; c < p.d / 8; c += 64) {
+      const u32x4 a = src[c], b = e[c];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) acc += bf16_lo(a[i]) * bf16_lo(b[i]) + bf16_hi(a[i]) * bf16_hi(b[i]);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
+    if (lane == 0) score[j] = acc;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    float m = -INFINITY;
+    for (int j = 0; j < p.n_experts; ++j) m = fmaxf(m, score[j]);
+    float z = 0.f;
+    for (int j = 0; j < p.n_experts; ++j) z += expf(score[j] - m);
+    int i1 = 0;
+    for (int j = 1; j < p.n_experts; ++j)
+      if (score[j] > score[i1]) i1 = j;
+    int i2 = i1 == 0 ? 1 : 0;
+    for (int j = 0; j < p.n_experts; ++j)
+      if (j != i1 && score[j] > score[i2]) i2 = j;
+    p.s_top[2 * row] = expf(score[i1] - m) / z;
+    p.s_top[2 * row + 1] = expf(score[i2] - m) / z;
+    p.idx[2 * row] = i1;
+    p.idx[2 * row + 1] = i2;
+    p.used[i1] = 1;  // (several rows may write the same 1)
+    p.used[i2] = 1;
+  }
+}
+
+struct ActParams {
+  const float *g, *up;  // [n_experts][rows][f] fp32: gate and up projections
+  uint16_t* h;          // [n_experts][rows padded to 32][f] bf16
+  const int* used;
+  int rows, rows_pad, f;
+};
+
+// h = silu(gate) * up, rounded to bf16 once; padding rows are zero-filled
+__global__ __launch_bounds__(256) void gated_act_kernel(ActParams p) {
+  const int e = blockIdx.y, row = blockIdx.x;
+  if (p.used[e] == 0) return;
+  uint16_t* h = p.h + ((long long)e * p.rows_pad + row) * p.f;
+  if (row >= p.rows) {
+    for (int c = threadIdx.x; c < p.f / 8; c += 256) reinterpret_cast<u32x4*>(h)[c] = u32x4{0u, 0u, 0u, 0u};
+    return;
+  }
+  const float* g = p.g + ((long long)e * p.rows + row) * p.f;
+  const float* up = p.up + ((long long)e * p.rows + row) * p.f;
+  for (int c = threadIdx.x; c < p.f / 4; c += 256) {
+    const floatx4 a = reinterpret_cast<const floatx4*>(g)[c], b = reinterpret_cast<const floatx4*>(up)[c];
+    float o[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) o[i] = a[i] / (1.f + expf(-a[i])) * b[i];
+    uint2 w;
+    w.x = bf16_bits_rne(o[0]) | (bf16_bits_rne(o[1]) << 16);
+    w.y = bf16_bits_rne(o[2]) | (bf16_bits_rne(o[3]) << 16);
+    reinterpret_cast<uint2*>(h)[c] = w;
+  }
+}
+
+struct SelectParams {
+  const float* y;     // [n_experts][rows][d] fp32: the experts' outputs
+  const uint16_t* u;  // [rows][d] bf16
+  const float* s_top;
+  const int* idx;
+  uint16_t* f_top;    // [rows][2][d] bf16
+  uint16_t* f_mix;    // [rows][d] bf16 or null
+  int rows, d;
+};
+
+// f_top[r][k] = Expert_{idx[r][k]}(u_r) + u_r; f_mix[r] = sum_k s_k Expert_k(u_r) + u_r (Eq. 3)
+__global__ __launch_bounds__(256) void select_kernel(SelectParams p) {
+  const int row = blockIdx.x;
+  const int i1 = p.idx[2 * row], i2 = p.idx[2 * row + 1];
+  const float s1 = p.s_top[2 * row], s2 = p.s_top[2 * row + 1];
+  const float* y1 = p.y + ((long long)i1 * p.rows + row) * p.d;
+  const float* y2 = p.y + ((long long)i2 * p.rows + row) * p.d;
+  const uint16_t* u = p.u + (long long)row * p.d;
+  for (int c = threadIdx.x; c < p.d / 2; c += 256) {
+    const unsigned uu = reinterpret_cast<const unsigned*>(u)[c];
+    const float u0 = bf16_lo(uu), u1 = bf16_hi(uu);
+    const float2 a = reinterpret_cast<const float2*>(y1)[c], b = reinterpret_cast<const float2*>(y2)[c];
+    reinterpret_cast<unsigned*>(p.f_top + ((long long)row * 2 + 0) * p.d)[c] =
+        bf16_bits_rne(a.x + u0) | (bf16_bits_rne(a.y + u1) << 16);
+    reinterpret_cast<unsigned*>(p.f_top + ((long long)row * 2 + 1) * p.d)[c] =
+        bf16_bits_rne(b.x + u0) | (bf16_bits_rne(b.y + u1) << 16);
+    if (p.f_mix)
+      reinterpret_cast<unsigned*>(p.f_mix + (long long)row * p.d)[c] =
+          bf16_bits_rne(s1 * a.x + s2 * b.x + u0) | (bf16_bits_rne(s1 * a.y + s2 * b.y + u1) << 16);
+  }
+}
+
+struct MoePlan {
+  int rows_pad;
+  size_t x_off, used_off, g_off, up_off, h_off, y_off, total;
+};
+MoePlan moe_plan(int rows, int d, int f, int n) {
+  MoePlan m;
+  auto up = [](size_t v) { return (v + 255) / 256 * 256; };
+  m.rows_pad = (rows + 31) / 32 * 32;
+  m.x_off = 0;
+  m.used_off = up((size_t)m.rows_pad * d * 2);
+  m.g_off = m.used_off + up((size_t)kMaxExperts * 4);
+  m.up_off = m.g_off + up((size_t)n * rows * f * 4);
+  m.h_off = m.up_off + up((size_t)n * rows * f * 4);
+  m.y_off = m.h_off + up((size_t)n * m.rows_pad * f * 2);
+  m.total = m.y_off + up((size_t)n * rows * d * 4);
+  return m;
+}
+
 struct RowPlan {
   int parts, part_len;
   size_t x_bytes, ms_off, cv_off, ci_off, mz_off, total;
@@ -669,6 +821,7 @@ hipError_t launch_draft_heads(const DraftHeadsArgs& a, hipStream_t stream) {
   gp.y = a.logits;
   gp.m = m; gp.n = a.vocab; gp.k = a.d_model;
   gp.ldw = a.d_model; gp.ldy = a.vocab;
+  gp.batch = 1; gp.x_batch = gp.w_batch = gp.y_batch = 0; gp.used = nullptr;
   e = launch_gemm(gp, stream);
   if (e != hipSuccess) return e;
 
@@ -689,6 +842,55 @@ hipError_t launch_draft_heads(const DraftHeadsArgs& a, hipStream_t stream) {
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   return hipSuccess;
+}
+
+size_t moe_experts_workspace_bytes(int rows, int d_model, int d_ff, int n_experts) {
+  return moe_plan(rows, d_model, d_ff, n_experts).total;
+}
+
+hipError_t launch_moe_experts(const MoeArgs& a, hipStream_t stream) {
+  const MoePlan mp = moe_plan(a.rows, a.d_model, a.d_ff, a.n_experts);
+  char* ws = static_cast<char*>(a.workspace);
+  int* used = reinterpret_cast<int*>(ws + mp.used_off);
+  hipError_t e;
+  hipLaunchKernelGGL(clear_flags_kernel, dim3(1), dim3(kMaxExperts), 0, stream, used, a.n_experts);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  RouterParams rp;
+  rp.u = static_cast<const uint16_t*>(a.u); rp.centroids = static_cast<const uint16_t*>(a.centroids);
+  rp.x = reinterpret_cast<uint16_t*>(ws + mp.x_off);
+  rp.s_top = a.s_top; rp.idx = a.expert_idx; rp.used = used;
+  rp.rows = a.rows; rp.d = a.d_model; rp.n_experts = a.n_experts;
+  hipLaunchKernelGGL(router_kernel, dim3(mp.rows_pad), dim3(256), 0, stream, rp);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+
+  GemmParams gp;
+  gp.x = rp.x; gp.m = a.rows; gp.n = a.d_ff; gp.k = a.d_model; gp.ldw = a.d_model; gp.ldy = a.d_ff;
+  gp.batch = a.n_experts; gp.x_batch = 0; gp.w_batch = (long long)a.d_ff * a.d_model;
+  gp.y_batch = (long long)a.rows * a.d_ff; gp.used = used;
+  gp.w = static_cast<const uint16_t*>(a.w_gate); gp.y = reinterpret_cast<float*>(ws + mp.g_off);
+  if ((e = launch_gemm(gp, stream)) != hipSuccess) return e;
+  gp.w = static_cast<const uint16_t*>(a.w_up); gp.y = reinterpret_cast<float*>(ws + mp.up_off);
+  if ((e = launch_gemm(gp, stream)) != hipSuccess) return e;
+
+  ActParams ap;
+  ap.g = reinterpret_cast<const float*>(ws + mp.g_off); ap.up = reinterpret_cast<const float*>(ws + mp.up_off);
+  ap.h = reinterpret_cast<uint16_t*>(ws + mp.h_off); ap.used = used;
+  ap.rows = a.rows; ap.rows_pad = mp.rows_pad; ap.f = a.d_ff;
+  hipLaunchKernelGGL(gated_act_kernel, dim3(mp.rows_pad, a.n_experts), dim3(256), 0, stream, ap);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+
+  gp.x = ap.h; gp.m = a.rows; gp.n = a.d_model; gp.k = a.d_ff; gp.ldw = a.d_ff; gp.ldy = a.d_model;
+  gp.x_batch = (long long)mp.rows_pad * a.d_ff; gp.w_batch = (long long)a.d_model * a.d_ff;
+  gp.y_batch = (long long)a.rows * a.d_model;
+  gp.w = static_cast<const uint16_t*>(a.w_down); gp.y = reinterpret_cast<float*>(ws + mp.y_off);
+  if ((e = launch_gemm(gp, stream)) != hipSuccess) return e;
+
+  SelectParams sp;
+  sp.y = reinterpret_cast<const float*>(ws + mp.y_off); sp.u = rp.u; sp.s_top = a.s_top; sp.idx = a.expert_idx;
+  sp.f_top = static_cast<uint16_t*>(a.f_top); sp.f_mix = static_cast<uint16_t*>(a.f_mix);
+  sp.rows = a.rows; sp.d = a.d_model;
+  hipLaunchKernelGGL(select_kernel, dim3(a.rows), dim3(256), 0, stream, sp);
+  return hipGetLastError();
 }
 
 }  // namespace jk

@@ -97,4 +97,16 @@ struct DraftHeadsArgs {
 size_t draft_heads_workspace_bytes(int rows, int d_model, int vocab);
 hipError_t launch_draft_heads(const DraftHeadsArgs& a, hipStream_t stream);
 
+// router + expert MLPs of the draft layer
+struct MoeArgs {
+  int rows, d_model, d_ff, n_experts;
+  const void *u, *centroids, *w_gate, *w_up, *w_down;
+  void *f_top, *f_mix;
+  float* s_top;
+  int32_t* expert_idx;
+  void* workspace;
+};
+size_t moe_experts_workspace_bytes(int rows, int d_model, int d_ff, int n_experts);
+hipError_t launch_moe_experts(const MoeArgs& a, hipStream_t stream);
+
 }  // namespace jk
