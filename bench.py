@@ -315,6 +315,39 @@ def main():
                  "note": "one jk_draft_heads call: head inputs, both heads' logits, draft distributions, top-10 "
                          "(not in ms_per_step)"}
         del dh_w, dh_lg, dh_q
+        # router + experts that feed the heads: 8 experts of the model's width (random weights)
+        n_exp, d_ff = 8, d_model
+        mo_u = torch.randn((dh_rows, d_model), device=dev, generator=gen).to(torch.bfloat16)
+        mo_c = (torch.randn((n_exp, d_model), device=dev, generator=gen) * (1.5 / d_model ** 0.5)).to(torch.bfloat16)
+        mo_w = [(torch.randn(shape, device=dev, generator=gen) * sc).to(torch.bfloat16)
+                for shape, sc in (((n_exp, d_ff, d_model), d_model ** -0.5), ((n_exp, d_ff, d_model), d_model ** -0.5),
+                                  ((n_exp, d_model, d_ff), d_ff ** -0.5))]
+        mo_idx = torch.empty((dh_rows, 2), dtype=torch.int32, device=dev)
+        mo_ws = torch.empty(jk.moe_experts_workspace(dh_rows, d_model, d_ff, n_exp), dtype=torch.uint8, device=dev)
+        mo_call = jk.prepare_moe_experts(mo_u, mo_c, mo_w[0], mo_w[1], mo_w[2], dh_f, dh_s, mo_idx, None, mo_ws)
+        def moe_pass():
+            for _ in range(4):
+                mo_call.launch()
+        moe_pass()
+        torch.cuda.synchronize()
+        g_moe = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g_moe, stream=torch.cuda.Stream()):
+            moe_pass()
+        g_moe.replay()
+        torch.cuda.synchronize()
+        em0, em1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        em0.record()
+        for _ in range(5):
+            g_moe.replay()
+        em1.record()
+        torch.cuda.synchronize()
+        mo_us = em0.elapsed_time(em1) * 1e3 / 20
+        n_used = len(set(mo_idx.cpu().reshape(-1).tolist()))
+        draft["moe_experts"] = {"us_per_call": round(mo_us, 1), "n_experts": n_exp, "experts_used": n_used,
+                                "d_ff": d_ff,
+                                "weight_stream_GBps": round(n_used * 3 * d_model * d_ff * 2 / (mo_us * 1e-6) / 1e9, 1),
+                                "note": "one jk_moe_experts call: router, top-2, expert MLPs of the selected experts"}
+        del mo_w
 
     for _ in range(args.copy_calibration):
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)

@@ -90,6 +90,10 @@ struct GemmParams {
   int batch;
   long long x_batch, w_batch, y_batch;
   const int* used;
+  // split of the k range (blockIdx.z): every part writes its own partial output, y_split elements
+  // apart; whoever reads y adds them up in a fixed order
+  int ksplit;
+  long long y_split;
 };
 
 typedef __attribute__((address_space(3))) const bf16x8 lds_bf16x8_t;
@@ -167,12 +171,13 @@ __global__ __launch_bounds__(kGemmThreads, 1) void skinny_gemm_kernel(GemmParams
   if (p.used && p.used[blockIdx.y] == 0) return;  // (the whole workgroup: nobody waits at a barrier)
   p.x += (long long)blockIdx.y * p.x_batch;
   p.w += (long long)blockIdx.y * p.w_batch;
-  p.y += (long long)blockIdx.y * p.y_batch;
+  p.y += (long long)blockIdx.y * p.y_batch + (long long)blockIdx.z * p.y_split;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 31, h = lane >> 5;
   const long long strip0 = (long long)blockIdx.x * C::STRIP;
   const int n_base = (int)strip0 + wave * 32 * NBW;
-  const int nkb = p.k / kKB;
+  const int nkb = p.k / kKB / p.ksplit;  // k blocks of this part
+  const int k_first = (int)blockIdx.z * nkb * kKB;
   // Workgroups start at different k blocks and wrap around, so that at any moment they ask for
   // different columns of the weight matrix and of X.
   const int kb0 = (int)((blockIdx.x * 5u) % (unsigned)nkb);
@@ -198,13 +203,13 @@ __global__ __launch_bounds__(kGemmThreads, 1) void skinny_gemm_kernel(GemmParams
   const unsigned w_ring = (unsigned)(wave * C::W_WAVE);
 
   auto issue_x = [&](int kb) {
-    const uint16_t* xb = uniform_ptr(p.x + rot(kb) * kKB);
+    const uint16_t* xb = uniform_ptr(p.x + k_first + rot(kb) * kKB);
     const unsigned xs = (unsigned)(C::X_BASE + (kb % C::DX) * C::X_STEP);
     if (cx > 0) dma16(xb, voff_x[0], xs + (unsigned)(wave * 1024));
     if (cx > 1) dma16(xb, voff_x[1], xs + (unsigned)((wave + 8) * 1024));
   };
   auto issue_w = [&](int kb) {
-    const uint16_t* wb = uniform_ptr(w_strip + rot(kb) * kKB);
+    const uint16_t* wb = uniform_ptr(w_strip + k_first + rot(kb) * kKB);
     const unsigned ws = w_ring + (unsigned)((kb % C::DW) * C::W_STEP);
 #pragma unroll
     for (int i = 0; i < C::NWI; ++i) dma16(wb, voff_w[i], ws + (unsigned)(i * 1024));
@@ -294,7 +299,8 @@ hipError_t launch_gemm_mb(const GemmParams& p, hipStream_t stream) {
     lds_limit_raised = true;
   }
   const unsigned grid = (unsigned)((p.n + GemmCfg<MB>::STRIP - 1) / GemmCfg<MB>::STRIP);
-  hipLaunchKernelGGL(skinny_gemm_kernel<MB>, dim3(grid, (unsigned)p.batch), dim3(kGemmThreads), GemmCfg<MB>::SMEM, stream, p);
+  hipLaunchKernelGGL(skinny_gemm_kernel<MB>, dim3(grid, (unsigned)p.batch, (unsigned)p.ksplit), dim3(kGemmThreads),
+                     GemmCfg<MB>::SMEM, stream, p);
   return hipGetLastError();
 }
 
@@ -700,10 +706,11 @@ __global__ __launch_bounds__(256) void router_kernel(RouterParams p) {
 }
 
 struct ActParams {
-  const float *g, *up;  // [n_experts][rows][f] fp32: gate and up projections
+  const float *g, *up;  // [ksplit][n_experts][rows][f] fp32: partial gate and up projections
   uint16_t* h;          // [n_experts][rows padded to 32][f] bf16
   const int* used;
-  int rows, rows_pad, f;
+  int rows, rows_pad, f, ksplit;
+  long long split_stride;
 };
 
 // h = silu(gate) * up, rounded to bf16 once; padding rows are zero-filled
@@ -718,7 +725,11 @@ __global__ __launch_bounds__(256) void gated_act_kernel(ActParams p) {
   const float* g = p.g + ((long long)e * p.rows + row) * p.f;
   const float* up = p.up + ((long long)e * p.rows + row) * p.f;
   for (int c = threadIdx.x; c < p.f / 4; c += 256) {
-    const floatx4 a = reinterpret_cast<const floatx4*>(g)[c], b = reinterpret_cast<const floatx4*>(up)[c];
+    floatx4 a = reinterpret_cast<const floatx4*>(g)[c], b = reinterpret_cast<const floatx4*>(up)[c];
+    for (int z = 1; z < p.ksplit; ++z) {
+      a += reinterpret_cast<const floatx4*>(g + z * p.split_stride)[c];
+      b += reinterpret_cast<const floatx4*>(up + z * p.split_stride)[c];
+    }
     float o[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) o[i] = a[i] / (1.f + expf(-a[i])) * b[i];
@@ -730,7 +741,9 @@ __global__ __launch_bounds__(256) void gated_act_kernel(ActParams p) {
 }
 
 struct SelectParams {
-  const float* y;     // [n_experts][rows][d] fp32: the experts' outputs
+  int ksplit;
+  long long split_stride;
+  const float* y;     // [ksplit][n_experts][rows][d] fp32: the experts' (partial) outputs
   const uint16_t* u;  // [rows][d] bf16
   const float* s_top;
   const int* idx;
@@ -747,10 +760,16 @@ __global__ __launch_bounds__(256) void select_kernel(SelectParams p) {
   const float* y1 = p.y + ((long long)i1 * p.rows + row) * p.d;
   const float* y2 = p.y + ((long long)i2 * p.rows + row) * p.d;
   const uint16_t* u = p.u + (long long)row * p.d;
-  for (int c = threadIdx.x; c < p.d / 2; c += 256) {
+  for (int c = blockIdx.y * 256 + threadIdx.x; c < p.d / 2; c += 256 * gridDim.y) {
     const unsigned uu = reinterpret_cast<const unsigned*>(u)[c];
     const float u0 = bf16_lo(uu), u1 = bf16_hi(uu);
-    const float2 a = reinterpret_cast<const float2*>(y1)[c], b = reinterpret_cast<const float2*>(y2)[c];
+    float2 a = reinterpret_cast<const float2*>(y1)[c], b = reinterpret_cast<const float2*>(y2)[c];
+    for (int z = 1; z < p.ksplit; ++z) {
+      const float2 az = reinterpret_cast<const float2*>(y1 + z * p.split_stride)[c];
+      const float2 bz = reinterpret_cast<const float2*>(y2 + z * p.split_stride)[c];
+      a.x += az.x; a.y += az.y;
+      b.x += bz.x; b.y += bz.y;
+    }
     reinterpret_cast<unsigned*>(p.f_top + ((long long)row * 2 + 0) * p.d)[c] =
         bf16_bits_rne(a.x + u0) | (bf16_bits_rne(a.y + u1) << 16);
     reinterpret_cast<unsigned*>(p.f_top + ((long long)row * 2 + 1) * p.d)[c] =
@@ -762,20 +781,36 @@ __global__ __launch_bounds__(256) void select_kernel(SelectParams p) {
 }
 
 struct MoePlan {
-  int rows_pad;
+  int rows_pad, split1, split2;
   size_t x_off, used_off, g_off, up_off, h_off, y_off, total;
 };
+// k parts so that a projection with few output columns still fills the chip: a workgroup can
+// pull only a fixed share of the memory bandwidth, so the weight stream needs about one
+// workgroup per CU.  A part keeps at least 512 of k and a multiple of 128.
+int pick_ksplit(int n_out, int k, int mb, int batch, int cus) {
+  const int strip = mb <= 6 ? 512 : 256;
+  const long long wgs = (long long)((n_out + strip - 1) / strip) * batch;
+  int best = 1;
+  for (int s = 2; s <= 8; ++s) {
+    if (k % (128 * s) != 0 || k / s < 512) continue;
+    if (wgs * s <= (long long)cus + cus / 8) best = s;
+  }
+  return best;
+}
 MoePlan moe_plan(int rows, int d, int f, int n) {
   MoePlan m;
   auto up = [](size_t v) { return (v + 255) / 256 * 256; };
   m.rows_pad = (rows + 31) / 32 * 32;
+  const int cus = device_cu_count();
+  m.split1 = pick_ksplit(f, d, m.rows_pad / 32, n, cus);
+  m.split2 = pick_ksplit(d, f, m.rows_pad / 32, n, cus);
   m.x_off = 0;
   m.used_off = up((size_t)m.rows_pad * d * 2);
   m.g_off = m.used_off + up((size_t)kMaxExperts * 4);
-  m.up_off = m.g_off + up((size_t)n * rows * f * 4);
-  m.h_off = m.up_off + up((size_t)n * rows * f * 4);
+  m.up_off = m.g_off + up((size_t)m.split1 * n * rows * f * 4);
+  m.h_off = m.up_off + up((size_t)m.split1 * n * rows * f * 4);
   m.y_off = m.h_off + up((size_t)n * m.rows_pad * f * 2);
-  m.total = m.y_off + up((size_t)n * rows * d * 4);
+  m.total = m.y_off + up((size_t)m.split2 * n * rows * d * 4);
   return m;
 }
 
@@ -822,6 +857,7 @@ hipError_t launch_draft_heads(const DraftHeadsArgs& a, hipStream_t stream) {
   gp.m = m; gp.n = a.vocab; gp.k = a.d_model;
   gp.ldw = a.d_model; gp.ldy = a.vocab;
   gp.batch = 1; gp.x_batch = gp.w_batch = gp.y_batch = 0; gp.used = nullptr;
+  gp.ksplit = 1; gp.y_split = 0;
   e = launch_gemm(gp, stream);
   if (e != hipSuccess) return e;
 
@@ -867,6 +903,7 @@ hipError_t launch_moe_experts(const MoeArgs& a, hipStream_t stream) {
   gp.x = rp.x; gp.m = a.rows; gp.n = a.d_ff; gp.k = a.d_model; gp.ldw = a.d_model; gp.ldy = a.d_ff;
   gp.batch = a.n_experts; gp.x_batch = 0; gp.w_batch = (long long)a.d_ff * a.d_model;
   gp.y_batch = (long long)a.rows * a.d_ff; gp.used = used;
+  gp.ksplit = mp.split1; gp.y_split = (long long)a.n_experts * a.rows * a.d_ff;
   gp.w = static_cast<const uint16_t*>(a.w_gate); gp.y = reinterpret_cast<float*>(ws + mp.g_off);
   if ((e = launch_gemm(gp, stream)) != hipSuccess) return e;
   gp.w = static_cast<const uint16_t*>(a.w_up); gp.y = reinterpret_cast<float*>(ws + mp.up_off);
@@ -876,12 +913,14 @@ hipError_t launch_moe_experts(const MoeArgs& a, hipStream_t stream) {
   ap.g = reinterpret_cast<const float*>(ws + mp.g_off); ap.up = reinterpret_cast<const float*>(ws + mp.up_off);
   ap.h = reinterpret_cast<uint16_t*>(ws + mp.h_off); ap.used = used;
   ap.rows = a.rows; ap.rows_pad = mp.rows_pad; ap.f = a.d_ff;
+  ap.ksplit = mp.split1; ap.split_stride = gp.y_split;
   hipLaunchKernelGGL(gated_act_kernel, dim3(mp.rows_pad, a.n_experts), dim3(256), 0, stream, ap);
   if ((e = hipGetLastError()) != hipSuccess) return e;
 
   gp.x = ap.h; gp.m = a.rows; gp.n = a.d_model; gp.k = a.d_ff; gp.ldw = a.d_ff; gp.ldy = a.d_model;
   gp.x_batch = (long long)mp.rows_pad * a.d_ff; gp.w_batch = (long long)a.d_model * a.d_ff;
   gp.y_batch = (long long)a.rows * a.d_model;
+  gp.ksplit = mp.split2; gp.y_split = (long long)a.n_experts * a.rows * a.d_model;
   gp.w = static_cast<const uint16_t*>(a.w_down); gp.y = reinterpret_cast<float*>(ws + mp.y_off);
   if ((e = launch_gemm(gp, stream)) != hipSuccess) return e;
 
@@ -889,7 +928,9 @@ hipError_t launch_moe_experts(const MoeArgs& a, hipStream_t stream) {
   sp.y = reinterpret_cast<const float*>(ws + mp.y_off); sp.u = rp.u; sp.s_top = a.s_top; sp.idx = a.expert_idx;
   sp.f_top = static_cast<uint16_t*>(a.f_top); sp.f_mix = static_cast<uint16_t*>(a.f_mix);
   sp.rows = a.rows; sp.d = a.d_model;
-  hipLaunchKernelGGL(select_kernel, dim3(a.rows), dim3(256), 0, stream, sp);
+  sp.ksplit = mp.split2; sp.split_stride = gp.y_split;
+  const unsigned chunks = (unsigned)(a.d_model / 512 < 8 ? (a.d_model / 512 > 0 ? a.d_model / 512 : 1) : 8);
+  hipLaunchKernelGGL(select_kernel, dim3(a.rows, chunks), dim3(256), 0, stream, sp);
   return hipGetLastError();
 }
 
