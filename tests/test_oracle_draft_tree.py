@@ -1,0 +1,103 @@
+"""Pins for the draft-tree growth oracle (Section 3.1.2: two candidate lists per expanded node, left
+expert first; top-k construction): hand-worked example, chain special case, structural invariants."""
+import numpy as np
+
+from oracle import draft_tree as dt
+
+
+def _grow_random(rng, depth, k, width, max_nodes, vocab=1000):
+    st = dt.TreeState()
+    frontier = [-1]
+    base = 0
+    for d in range(depth):
+        nf = len(frontier)
+        p = np.sort(rng.random((nf, 2, k)).astype(np.float32), axis=2)[:, :, ::-1] * np.float32(0.9)
+        tok = rng.integers(0, vocab, size=(nf, 2, k))
+        frontier = dt.grow(st, frontier, tok, p, width, max_nodes, base)
+        base += 2 * nf
+    return st
+
+
+def test_hand_worked_two_depths():
+    st = dt.TreeState()
+    tok0 = np.array([[[11, 12], [21, 22]]])
+    p0 = np.array([[[0.5, 0.2], [0.25, 0.05]]], dtype=np.float32)
+    fr = dt.grow(st, [-1], tok0, p0, width=2, max_nodes=64, q_row_base=0)
+    assert st.tokens == [11, 12, 21, 22] and st.parent == [-1] * 4 and st.q_row == [0, 0, 1, 1]
+    assert fr == [0, 2]                                   # scores 0.5 and 0.25
+    tok1 = np.array([[[31, 32], [41, 42]], [[51, 52], [61, 62]]])
+    p1 = np.array([[[0.5, 0.25], [0.125, 0.0625]], [[1.0, 0.5], [0.25, 0.125]]], dtype=np.float32)
+    fr = dt.grow(st, fr, tok1, p1, width=2, max_nodes=64, q_row_base=2)
+    assert st.parent[4:] == [0, 0, 0, 0, 2, 2, 2, 2]
+    assert [float(s) for s in st.score[4:]] == [0.25, 0.125, 0.0625, 0.03125, 0.25, 0.125, 0.0625, 0.03125]
+    assert st.q_row[4:] == [2, 2, 3, 3, 4, 4, 5, 5]
+    assert fr == [4, 8]                                   # 0.25 twice: both kept, in index order
+    tokens, parent, q_row, old = dt.finalize(st, 6)
+    # best six: 0 (.5), 2 (.25), 4 (.25), 8 (.25), 1 (.2), then .125 twice: the lower index (5) wins
+    assert old.tolist() == [0, 1, 2, 4, 5, 8]
+    assert parent.tolist() == [-1, -1, -1, 0, 0, 2]
+    assert tokens.tolist() == [11, 12, 21, 31, 32, 51]
+    assert q_row.tolist() == [0, 0, 1, 2, 2, 4]
+
+
+def test_single_candidate_single_slot_is_a_chain():
+    st = dt.TreeState()
+    fr = [-1]
+    for d in range(5):
+        tok = np.array([[[100 + d], [200 + d]]])
+        p = np.array([[[0.9], [0.3]]], dtype=np.float32)
+        fr = dt.grow(st, fr, tok, p, width=1, max_nodes=64, q_row_base=2 * d)
+        assert fr == [2 * d]                              # the left expert's candidate
+    tokens, parent, q_row, old = dt.finalize(st, 5)
+    assert old.tolist() == [0, 2, 4, 6, 8] and parent.tolist() == [-1, 0, 1, 2, 3]
+    assert tokens.tolist() == [100, 101, 102, 103, 104]
+
+
+def test_invariants_on_random_trees():
+    rng = np.random.default_rng(0)
+    for trial in range(20):
+        k, width, depth = int(rng.integers(1, 6)), int(rng.integers(1, 6)), int(rng.integers(1, 7))
+        width = min(width, 2 * k)
+        st = _grow_random(rng, depth, k, width, max_nodes=500)
+        n = len(st.tokens)
+        par = np.array(st.parent)
+        assert (par < np.arange(n)).all() and (par >= -1).all()
+        # score = product of the candidate probabilities along the path: never above the parent's
+        for i in range(n):
+            if par[i] >= 0:
+                assert st.score[i] <= st.score[par[i]]
+        # children of one parent: contiguous, left expert's rows (even q_row) before the right's, each list
+        # by non-increasing score
+        for pnode in set(par.tolist()):
+            ch = np.nonzero(par == pnode)[0]
+            assert (np.diff(ch) == 1).all() and len(ch) == 2 * k
+            assert [st.q_row[c] % 2 for c in ch] == [0] * k + [1] * k
+            for half in (ch[:k], ch[k:]):
+                sc = [float(st.score[c]) for c in half]
+                assert sc == sorted(sc, reverse=True)
+        for n_keep in (1, n // 2, n):
+            if n_keep < 1:
+                continue
+            tokens, parent, q_row, old = dt.finalize(st, n_keep)
+            assert len(old) == n_keep and (np.diff(old) > 0).all()
+            kept = set(old.tolist())
+            assert all(st.parent[o] in kept or st.parent[o] < 0 for o in old)          # closed under ancestors
+            assert (parent < np.arange(n_keep)).all()
+            worst_kept = min(float(st.score[o]) for o in old)
+            assert all(float(st.score[i]) <= worst_kept for i in range(n) if i not in kept)
+            assert [st.tokens[o] for o in old] == tokens.tolist()
+            # the renumbering keeps the tree: parents map to parents
+            back = {o: i for i, o in enumerate(old.tolist())}
+            assert all((parent[i] == -1 and st.parent[o] < 0) or back[st.parent[o]] == parent[i]
+                       for i, o in enumerate(old.tolist()))
+        if n_keep == n:
+            assert old.tolist() == list(range(n))
+
+
+def test_ties_go_to_the_lower_index_and_capacity_drops_the_tail():
+    st = dt.TreeState()
+    tok = np.arange(8).reshape(1, 2, 4)
+    p = np.full((1, 2, 4), 0.5, dtype=np.float32)
+    fr = dt.grow(st, [-1], tok, p, width=3, max_nodes=6, q_row_base=0)
+    assert len(st.tokens) == 6 and fr == [0, 1, 2]
+    assert dt.finalize(st, 4)[3].tolist() == [0, 1, 2, 3]
