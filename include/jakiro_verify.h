@@ -323,6 +323,61 @@ jk_status jk_moe_experts(const jk_moe_desc* desc, const void* u, const void* cen
                          const void* w_up, const void* w_down, void* f_top, float* s_top, int32_t* expert_idx,
                          void* f_mix, void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* ---- growing the draft tree from the heads' candidate lists ----
+ *
+ * Section 3.1.2: at every depth both activated experts propose their own top-k
+ * candidates for each expanded node, the expert with the larger router score on
+ * the left, following the top-k construction of a dynamically built tree.  The
+ * paper fixes no further detail; this library grows the tree like this, per
+ * sequence (all decisions on fp32 scores, ties to the lower node index):
+ *
+ *   jk_tree_grow      one depth.  For every frontier node f (in node order), expert
+ *       e = left, right, rank j: a new node with token cand_tokens[f][e][j], parent f,
+ *       score = score(f) * cand_probs[f][e][j] (the root scores 1), numbered in that
+ *       order behind the existing nodes: children of a node are ordered left to right
+ *       by index, the left expert's list first.  Nodes beyond max_nodes are dropped.
+ *       The `width` best new nodes, in increasing index, are the next frontier (if there
+ *       are fewer new nodes the remaining places repeat the first one).
+ *   jk_tree_finalize  keeps the n_keep best nodes (a node never scores above its parent,
+ *       so ancestors come along), renumbers them in increasing old index and translates
+ *       the parents: tree_tokens / parent as jk_tree_verify_attention and jk_accept_path
+ *       take them.  n_valid[b] = min(nodes grown, n_keep); places beyond it hold token -1.
+ *   jk_gather_draft_probs  draft_probs[b][i][:] = q_all[q_row[b][i]][:], the dense array
+ *       jk_accept_path takes (q_all: all draft distributions of the round, one row per
+ *       (hidden state, head), e.g. the draft_probs outputs of the round's jk_draft_heads
+ *       calls in one buffer; a row number outside [0, n_q_rows) is clamped).
+ *
+ * The state arrays are device memory owned by the caller: tokens, parent, q_row
+ * int32 [batch][max_nodes], score fp32 [batch][max_nodes], n_nodes int32 [batch]
+ * (zero before the first depth of a round).  q_row of a node is
+ * q_row_base + 2 * (b * n_front + f) + e: the row of the distribution its token
+ * was a candidate of, when the rows of the call's hidden states start at q_row_base.
+ *   n_front      frontier nodes per sequence in this call (1 for the root: frontier_in NULL)
+ *   top_k, width n_front * 2 * top_k <= 256, 1 <= width <= 256
+ *   frontier_in  device int32 [batch][n_front] (the previous call's frontier_out) or NULL
+ *   cand_tokens, cand_probs  device [batch * n_front][2][top_k] (jk_draft_heads' topk outputs
+ *                for the hidden states of the frontier nodes, sequence-major)
+ *   frontier_out device int32 [batch][width], written
+ *   max_nodes    1..1024;  1 <= n_keep <= max_nodes;  old_index may be NULL */
+typedef struct {
+  int32_t* tokens;
+  int32_t* parent;
+  float* score;
+  int32_t* q_row;
+  int32_t* n_nodes;
+  int32_t max_nodes;
+} jk_tree_state;
+
+jk_status jk_tree_grow(const jk_tree_state* state, int32_t batch, int32_t n_front, int32_t top_k, int32_t width,
+                       int32_t q_row_base, const int32_t* frontier_in, const int32_t* cand_tokens,
+                       const float* cand_probs, int32_t* frontier_out, void* hip_stream);
+
+jk_status jk_tree_finalize(const jk_tree_state* state, int32_t batch, int32_t n_keep, int32_t* tree_tokens,
+                           int32_t* parent, int32_t* q_row, int32_t* old_index, int32_t* n_valid, void* hip_stream);
+
+jk_status jk_gather_draft_probs(int32_t batch, int32_t n_tree, int32_t vocab, const float* q_all, int64_t n_q_rows,
+                                const int32_t* q_row, float* draft_probs, void* hip_stream);
+
 /* Zero-fills a workspace with a small kernel on `hip_stream` (safe under HIP-graph
  * capture).  Needed once per workspace before its first jk_accept_path call: the
  * cooperative sampling walk synchronises its workgroups through tagged words in

@@ -52,6 +52,12 @@ class MoeDesc(ctypes.Structure):
                 ("n_experts", ctypes.c_int32)]
 
 
+class TreeStateDesc(ctypes.Structure):
+    """jk_tree_state"""
+    _fields_ = [("tokens", ctypes.c_void_p), ("parent", ctypes.c_void_p), ("score", ctypes.c_void_p),
+                ("q_row", ctypes.c_void_p), ("n_nodes", ctypes.c_void_p), ("max_nodes", ctypes.c_int32)]
+
+
 class PagedKV(ctypes.Structure):
     """jk_paged_kv"""
     _fields_ = [("block_table", ctypes.c_void_p), ("max_blocks", ctypes.c_int32), ("page_size", ctypes.c_int32),
@@ -60,7 +66,7 @@ class PagedKV(ctypes.Structure):
 
 EXPORTS = ("jk_tree_verify_attention_workspace", "jk_tree_verify_attention", "jk_tree_verify_attention_paged",
            "jk_commit_path_layers_paged", "jk_accept_path_workspace",
-           "jk_accept_path", "jk_draft_heads_workspace", "jk_draft_heads", "jk_moe_experts_workspace", "jk_moe_experts", "jk_commit_path", "jk_commit_path_layers", "jk_workspace_init", "jk_stream_read_probe", "jk_validate_tree", "jk_status_string", "jk_version")
+           "jk_accept_path", "jk_draft_heads_workspace", "jk_draft_heads", "jk_moe_experts_workspace", "jk_moe_experts", "jk_tree_grow", "jk_tree_finalize", "jk_gather_draft_probs", "jk_commit_path", "jk_commit_path_layers", "jk_workspace_init", "jk_stream_read_probe", "jk_validate_tree", "jk_status_string", "jk_version")
 
 
 def library_path() -> str:
@@ -104,6 +110,12 @@ def lib() -> ctypes.CDLL:
         l.jk_moe_experts_workspace.argtypes = [ctypes.POINTER(MoeDesc)]
         l.jk_moe_experts.restype = i32
         l.jk_moe_experts.argtypes = [ctypes.POINTER(MoeDesc), vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        l.jk_tree_grow.restype = i32
+        l.jk_tree_grow.argtypes = [ctypes.POINTER(TreeStateDesc), i32, i32, i32, i32, i32, vp, vp, vp, vp, vp]
+        l.jk_tree_finalize.restype = i32
+        l.jk_tree_finalize.argtypes = [ctypes.POINTER(TreeStateDesc), i32, i32, vp, vp, vp, vp, vp, vp]
+        l.jk_gather_draft_probs.restype = i32
+        l.jk_gather_draft_probs.argtypes = [i32, i32, i32, vp, ctypes.c_int64, vp, vp, vp]
         l.jk_workspace_init.restype = i32
         l.jk_workspace_init.argtypes = [vp, sz, vp]
         l.jk_stream_read_probe.restype = i32
@@ -529,3 +541,77 @@ def prepare_moe_experts(u, centroids, w_gate, w_up, w_down, f_top, s_top, expert
     desc, args, ws = _moe_args(u, centroids, w_gate, w_up, w_down, f_top, s_top, expert_idx, f_mix, workspace)
     return PreparedCall(lib().jk_moe_experts, "jk_moe_experts", args, 12,
                         (desc, u, centroids, w_gate, w_up, w_down, f_top, s_top, expert_idx, f_mix, ws))
+
+
+class TreeState:
+    """Device arrays of a growing draft tree (jk_tree_state), one set per batch."""
+
+    def __init__(self, batch: int, max_nodes: int, device="cuda"):
+        import torch
+        self.batch, self.max_nodes = int(batch), int(max_nodes)
+        self.tokens = torch.zeros((batch, max_nodes), dtype=torch.int32, device=device)
+        self.parent = torch.full((batch, max_nodes), -1, dtype=torch.int32, device=device)
+        self.score = torch.zeros((batch, max_nodes), dtype=torch.float32, device=device)
+        self.q_row = torch.zeros((batch, max_nodes), dtype=torch.int32, device=device)
+        self.n_nodes = torch.zeros((batch,), dtype=torch.int32, device=device)
+
+    def reset(self) -> None:
+        self.n_nodes.zero_()
+
+    def desc(self) -> TreeStateDesc:
+        return TreeStateDesc(_ptr(self.tokens), _ptr(self.parent), _ptr(self.score), _ptr(self.q_row),
+                             _ptr(self.n_nodes), self.max_nodes)
+
+
+def tree_grow(state: TreeState, frontier_in, cand_tokens, cand_probs, width: int, q_row_base: int, stream=None):
+    """jk_tree_grow.  frontier_in int32 [B,n_front] or None (root); cand_tokens int32 / cand_probs fp32
+    [B*n_front,2,k].  Returns the next frontier, int32 [B,width]."""
+    import torch
+    B = state.batch
+    n_front = 1 if frontier_in is None else int(frontier_in.shape[1])
+    rows, two, k = cand_tokens.shape
+    if rows != B * n_front or two != 2 or tuple(cand_probs.shape) != (rows, 2, k):
+        raise ValueError("cand_tokens / cand_probs must be [B*n_front, 2, k]")
+    if cand_tokens.dtype != torch.int32 or cand_probs.dtype != torch.float32 or \
+            not cand_tokens.is_contiguous() or not cand_probs.is_contiguous():
+        raise TypeError("cand_tokens contiguous int32, cand_probs contiguous float32")
+    if frontier_in is not None and (frontier_in.dtype != torch.int32 or not frontier_in.is_contiguous()):
+        raise TypeError("frontier_in contiguous int32")
+    out = torch.empty((B, int(width)), dtype=torch.int32, device=cand_tokens.device)
+    d = state.desc()
+    st = lib().jk_tree_grow(ctypes.byref(d), B, n_front, int(k), int(width), int(q_row_base), _ptr(frontier_in),
+                            _ptr(cand_tokens), _ptr(cand_probs), _ptr(out), _stream_handle(stream))
+    if st != 0:
+        raise JakiroError(st, "jk_tree_grow")
+    return out
+
+
+def tree_finalize(state: TreeState, n_keep: int, stream=None):
+    """jk_tree_finalize.  Returns (tree_tokens, parent, q_row, old_index) int32 [B,n_keep] and n_valid int32 [B]."""
+    import torch
+    B = state.batch
+    dev = state.tokens.device
+    outs = [torch.empty((B, int(n_keep)), dtype=torch.int32, device=dev) for _ in range(4)]
+    n_valid = torch.empty((B,), dtype=torch.int32, device=dev)
+    d = state.desc()
+    st = lib().jk_tree_finalize(ctypes.byref(d), B, int(n_keep), _ptr(outs[0]), _ptr(outs[1]), _ptr(outs[2]),
+                                _ptr(outs[3]), _ptr(n_valid), _stream_handle(stream))
+    if st != 0:
+        raise JakiroError(st, "jk_tree_finalize")
+    return outs[0], outs[1], outs[2], outs[3], n_valid
+
+
+def gather_draft_probs(q_all, q_row, stream=None):
+    """jk_gather_draft_probs.  q_all fp32 [n_rows, V] (contiguous), q_row int32 [B, N] -> fp32 [B, N, V]."""
+    import torch
+    if q_all.dtype != torch.float32 or not q_all.is_contiguous() or q_row.dtype != torch.int32 or \
+            not q_row.is_contiguous():
+        raise TypeError("q_all contiguous float32, q_row contiguous int32")
+    V = q_all.shape[-1]
+    n_rows = q_all.numel() // V
+    B, N = q_row.shape
+    out = torch.empty((B, N, V), dtype=torch.float32, device=q_all.device)
+    st = lib().jk_gather_draft_probs(B, N, V, _ptr(q_all), n_rows, _ptr(q_row), _ptr(out), _stream_handle(stream))
+    if st != 0:
+        raise JakiroError(st, "jk_gather_draft_probs")
+    return out

@@ -10,7 +10,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libjakiro_verify.so")
 SOURCES = ["api.cpp", "tva_bf16.hip", "tva_f32.hip", "tva_combine.hip", "accept.hip", "accept_coop.hip", "commit.hip",
-           "draft_head.hip"]
+           "draft_head.hip", "draft_tree.hip"]
 # packed-fp32 code generation is switched off for all device code
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -393,6 +393,51 @@ jk_status jk_moe_experts(const jk_moe_desc* desc, const void* u, const void* cen
   return launch_moe_experts(a, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? JK_OK : JK_ERR_HIP;
 }
 
+static bool tree_state_ok(const jk_tree_state* s) {
+  return s && s->tokens && s->parent && s->score && s->q_row && s->n_nodes && s->max_nodes >= 1;
+}
+
+jk_status jk_tree_grow(const jk_tree_state* state, int32_t batch, int32_t n_front, int32_t top_k, int32_t width,
+                       int32_t q_row_base, const int32_t* frontier_in, const int32_t* cand_tokens,
+                       const float* cand_probs, int32_t* frontier_out, void* hip_stream) {
+  if (!tree_state_ok(state) || !cand_tokens || !cand_probs || !frontier_out) return JK_ERR_INVALID_ARG;
+  if (batch < 1 || n_front < 1 || top_k < 1 || width < 1 || q_row_base < 0) return JK_ERR_INVALID_ARG;
+  if (!frontier_in && n_front != 1) return JK_ERR_INVALID_ARG;
+  if (state->max_nodes > tree_max_nodes() || (long long)n_front * 2 * top_k > 256 || width > 256 || batch > 65535)
+    return JK_ERR_UNSUPPORTED;
+  TreeGrowArgs a;
+  a.batch = batch; a.n_front = n_front; a.top_k = top_k; a.width = width; a.max_nodes = state->max_nodes;
+  a.q_row_base = q_row_base;
+  a.tokens = state->tokens; a.parent = state->parent; a.q_row = state->q_row; a.n_nodes = state->n_nodes;
+  a.score = state->score;
+  a.frontier_in = frontier_in; a.cand_tok = cand_tokens; a.cand_p = cand_probs; a.frontier_out = frontier_out;
+  return launch_tree_grow(a, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? JK_OK : JK_ERR_HIP;
+}
+
+jk_status jk_tree_finalize(const jk_tree_state* state, int32_t batch, int32_t n_keep, int32_t* tree_tokens,
+                           int32_t* parent, int32_t* q_row, int32_t* old_index, int32_t* n_valid, void* hip_stream) {
+  if (!tree_state_ok(state) || !tree_tokens || !parent || !q_row || !n_valid) return JK_ERR_INVALID_ARG;
+  if (batch < 1 || n_keep < 1 || n_keep > state->max_nodes) return JK_ERR_INVALID_ARG;
+  if (state->max_nodes > tree_max_nodes() || batch > 65535) return JK_ERR_UNSUPPORTED;
+  TreeFinalArgs a;
+  a.batch = batch; a.n_keep = n_keep; a.max_nodes = state->max_nodes;
+  a.tokens = state->tokens; a.parent = state->parent; a.q_row = state->q_row; a.n_nodes = state->n_nodes;
+  a.score = state->score;
+  a.out_tokens = tree_tokens; a.out_parent = parent; a.out_q_row = q_row; a.out_old = old_index; a.n_valid = n_valid;
+  return launch_tree_finalize(a, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? JK_OK : JK_ERR_HIP;
+}
+
+jk_status jk_gather_draft_probs(int32_t batch, int32_t n_tree, int32_t vocab, const float* q_all, int64_t n_q_rows,
+                                const int32_t* q_row, float* draft_probs, void* hip_stream) {
+  if (!q_all || !q_row || !draft_probs || batch < 1 || n_tree < 1 || vocab < 1 || n_q_rows < 1)
+    return JK_ERR_INVALID_ARG;
+  if ((long long)batch * n_tree > 0x7fffffffLL) return JK_ERR_UNSUPPORTED;
+  return launch_gather_rows(q_all, q_row, draft_probs, (long long)batch * n_tree, vocab, n_q_rows,
+                            static_cast<hipStream_t>(hip_stream)) == hipSuccess
+             ? JK_OK
+             : JK_ERR_HIP;
+}
+
 jk_status jk_workspace_init(void* workspace, size_t workspace_bytes, void* hip_stream) {
   if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256) return JK_ERR_WORKSPACE;
   return launch_zero_fill(workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream)) == hipSuccess

@@ -1,0 +1,162 @@
+// Growing the draft token tree on the device (gfx950), one depth at a time, from the candidate
+// lists that jk_draft_heads returns (Section 3.1.2 of the paper: both activated experts propose
+// their own top-k candidates for every expanded node, the expert with the larger router score
+// on the left; top-k construction as in a dynamically built tree).
+//
+//   grow      per sequence: a new node for every (frontier node, expert, rank) in that order,
+//             score = parent's score * candidate probability; the `width` best new nodes (ties
+//             to the lower index) become the next frontier, listed in increasing index.
+//   finalize  per sequence: the n_keep best nodes (ties to the lower index; a node never scores
+//             above its parent, so ancestors come along), renumbered in increasing old index.
+//   gather    the kept nodes' draft distributions as the dense [batch][n_tree][vocab] array that
+//             jk_accept_path takes.
+// All choices are made by counting how many entries beat a given one (no sorting network, no
+// reduction rounds): at most a few hundred entries per sequence.
+#include <climits>
+
+#include "jk_internal.h"
+
+namespace jk {
+namespace {
+
+constexpr int kTreeThreads = 256;
+constexpr int kMaxGrowNodes = 1024;  // node capacity per sequence the kernels are laid out for
+
+// larger score first, equal scores by increasing index (both operands always evaluated)
+__device__ __forceinline__ int beats(float av, int ai, float bv, int bi) {
+  return (int)(av > bv) | ((int)(av == bv) & (int)(ai < bi));
+}
+
+__global__ __launch_bounds__(kTreeThreads) void grow_kernel(TreeGrowArgs a) {
+  __shared__ float s_sc[kTreeThreads];
+  __shared__ int s_sel[kTreeThreads];
+  __shared__ int s_first;
+  const int b = blockIdx.x, t = threadIdx.x;
+  const int C = a.n_front * 2 * a.top_k;
+  const int n0 = a.n_nodes[b];
+  const int id = n0 + t;
+  const bool valid = t < C && id < a.max_nodes;
+  float sc = -INFINITY;
+  if (valid) {
+    const int f = t / (2 * a.top_k), e = (t / a.top_k) & 1;
+    const long long row = (long long)b * a.n_front + f;
+    const int pid = a.frontier_in ? a.frontier_in[row] : -1;
+    const bool has_parent = pid >= 0 && pid < n0;
+    const float ps = has_parent ? a.score[(long long)b * a.max_nodes + pid] : 1.0f;
+    sc = ps * a.cand_p[row * 2 * a.top_k + (t - f * 2 * a.top_k)];
+    const long long at = (long long)b * a.max_nodes + id;
+    a.tokens[at] = a.cand_tok[row * 2 * a.top_k + (t - f * 2 * a.top_k)];
+    a.parent[at] = has_parent ? pid : -1;
+    a.score[at] = sc;
+    a.q_row[at] = a.q_row_base + (int)(2 * row) + e;
+  }
+  s_sc[t] = sc;
+  if (t == 0) s_first = INT_MAX;
+  __syncthreads();
+  int rank = 0;
+#pragma unroll 8
+  for (int i = 0; i < kTreeThreads; ++i) rank += beats(s_sc[i], i, sc, t);
+  const int sel = (valid && rank < a.width) ? 1 : 0;
+  s_sel[t] = sel;
+  __syncthreads();
+  int slot = 0;
+#pragma unroll 8
+  for (int i = 0; i < kTreeThreads; ++i) slot += (i < t) ? s_sel[i] : 0;
+  int total = 0;
+#pragma unroll 8
+  for (int i = 0; i < kTreeThreads; ++i) total += s_sel[i];
+  if (sel) {
+    a.frontier_out[(long long)b * a.width + slot] = id;
+    if (slot == 0) s_first = id;
+  }
+  __syncthreads();
+  // fewer new nodes than frontier slots: the rest repeats the first entry (-1 if there is none)
+  if (t >= total && t < a.width) a.frontier_out[(long long)b * a.width + t] = s_first == INT_MAX ? -1 : s_first;
+  if (t == 0) a.n_nodes[b] = min(n0 + C, a.max_nodes);
+}
+
+__global__ __launch_bounds__(kTreeThreads) void finalize_kernel(TreeFinalArgs a) {
+  __shared__ float s_sc[kMaxGrowNodes];
+  __shared__ short s_keep[kMaxGrowNodes];
+  __shared__ short s_new[kMaxGrowNodes];
+  const int b = blockIdx.x, t = threadIdx.x;
+  const int n = min(a.n_nodes[b], a.max_nodes);
+  const long long base = (long long)b * a.max_nodes;
+  for (int i = t; i < kMaxGrowNodes; i += kTreeThreads) s_sc[i] = i < n ? a.score[base + i] : -INFINITY;
+  __syncthreads();
+  for (int i = t; i < kMaxGrowNodes; i += kTreeThreads) {
+    int rank = 0;
+    const float sc = s_sc[i];
+    if (i < n) {
+#pragma unroll 8
+      for (int j = 0; j < n; ++j) rank += beats(s_sc[j], j, sc, i);
+    }
+    s_keep[i] = (i < n && rank < a.n_keep) ? 1 : 0;
+  }
+  __syncthreads();
+  for (int i = t; i < n; i += kTreeThreads) {
+    int before = 0;
+#pragma unroll 8
+    for (int j = 0; j < i; ++j) before += s_keep[j];
+    s_new[i] = (short)before;
+  }
+  __syncthreads();
+  for (int i = t; i < n; i += kTreeThreads) {
+    if (!s_keep[i]) continue;
+    const long long o = (long long)b * a.n_keep + s_new[i];
+    const int pid = a.parent[base + i];
+    a.out_tokens[o] = a.tokens[base + i];
+    a.out_parent[o] = (pid >= 0 && pid < i) ? (int)s_new[pid] : -1;  // (a kept node's parent is kept)
+    a.out_q_row[o] = a.q_row[base + i];
+    if (a.out_old) a.out_old[o] = i;
+  }
+  const int n_valid = min(n, a.n_keep);
+  for (int i = n_valid + t; i < a.n_keep; i += kTreeThreads) {  // a tree with fewer nodes than asked for
+    const long long o = (long long)b * a.n_keep + i;
+    a.out_tokens[o] = -1;
+    a.out_parent[o] = -1;
+    a.out_q_row[o] = 0;
+    if (a.out_old) a.out_old[o] = -1;
+  }
+  if (t == 0) a.n_valid[b] = n_valid;
+}
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(256) void gather_rows_kernel(const float* __restrict__ q_all, const int* __restrict__ q_row,
+                                                          float* __restrict__ out, int vocab, long long n_q_rows) {
+  const long long node = blockIdx.x;
+  long long r = q_row[node];
+  r = r < 0 ? 0 : (r >= n_q_rows ? n_q_rows - 1 : r);  // must not fault on a bad row number
+  const float* src = q_all + r * vocab;
+  float* dst = out + node * vocab;
+  const bool vec = (vocab & 3) == 0 && ((reinterpret_cast<size_t>(q_all) | reinterpret_cast<size_t>(out)) & 15) == 0;
+  if (vec) {
+    for (int c = blockIdx.y * 256 + threadIdx.x; c < vocab / 4; c += 256 * gridDim.y)
+      reinterpret_cast<floatx4*>(dst)[c] = reinterpret_cast<const floatx4*>(src)[c];
+  } else {
+    for (int c = blockIdx.y * 256 + threadIdx.x; c < vocab; c += 256 * gridDim.y) dst[c] = src[c];
+  }
+}
+
+}  // namespace
+
+int tree_max_nodes() { return kMaxGrowNodes; }
+
+hipError_t launch_tree_grow(const TreeGrowArgs& a, hipStream_t stream) {
+  hipLaunchKernelGGL(grow_kernel, dim3(a.batch), dim3(kTreeThreads), 0, stream, a);
+  return hipGetLastError();
+}
+hipError_t launch_tree_finalize(const TreeFinalArgs& a, hipStream_t stream) {
+  hipLaunchKernelGGL(finalize_kernel, dim3(a.batch), dim3(kTreeThreads), 0, stream, a);
+  return hipGetLastError();
+}
+hipError_t launch_gather_rows(const float* q_all, const int* q_row, float* out, long long n_nodes, int vocab,
+                              long long n_q_rows, hipStream_t stream) {
+  const unsigned chunks = (unsigned)(vocab / 4096 < 1 ? 1 : (vocab / 4096 > 16 ? 16 : vocab / 4096));
+  hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)n_nodes, chunks), dim3(256), 0, stream, q_all, q_row, out,
+                     vocab, n_q_rows);
+  return hipGetLastError();
+}
+
+}  // namespace jk

@@ -109,4 +109,26 @@ struct MoeArgs {
 size_t moe_experts_workspace_bytes(int rows, int d_model, int d_ff, int n_experts);
 hipError_t launch_moe_experts(const MoeArgs& a, hipStream_t stream);
 
+// draft tree growth
+struct TreeGrowArgs {
+  int batch, n_front, top_k, width, max_nodes, q_row_base;
+  int32_t *tokens, *parent, *q_row, *n_nodes;  // state [batch][max_nodes], [batch]
+  float* score;
+  const int32_t* frontier_in;  // [batch][n_front] or null (the root)
+  const int32_t* cand_tok;     // [batch*n_front][2][top_k]
+  const float* cand_p;
+  int32_t* frontier_out;       // [batch][width]
+};
+struct TreeFinalArgs {
+  int batch, n_keep, max_nodes;
+  const int32_t *tokens, *parent, *q_row, *n_nodes;
+  const float* score;
+  int32_t *out_tokens, *out_parent, *out_q_row, *out_old, *n_valid;
+};
+int tree_max_nodes();
+hipError_t launch_tree_grow(const TreeGrowArgs& a, hipStream_t stream);
+hipError_t launch_tree_finalize(const TreeFinalArgs& a, hipStream_t stream);
+hipError_t launch_gather_rows(const float* q_all, const int* q_row, float* out, long long n_nodes, int vocab,
+                              long long n_q_rows, hipStream_t stream);
+
 }  // namespace jk

@@ -1,0 +1,163 @@
+"""GPU parity: jk_tree_grow / jk_tree_finalize / jk_gather_draft_probs (through the C ABI) against the
+tree-growth oracle, bit for bit (integer results; scores are single fp32 products on both sides), and one
+whole round on the device: experts -> heads -> tree -> verification attention -> acceptance."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2502_06282_amd as jk
+from oracle import accept_path as oracle_accept, draft_tree as dt
+from workloads import draft_head_inputs, moe_inputs
+
+pytestmark = pytest.mark.gpu
+
+
+def _cands(rng, rows, k, vocab=5000, ties=False):
+    p = np.sort(rng.random((rows, 2, k)).astype(np.float32), axis=2)[:, :, ::-1] * np.float32(0.9)
+    if ties:
+        p = np.round(p * 4) / 4
+    tok = rng.integers(0, vocab, size=(rows, 2, k)).astype(np.int32)
+    return tok, np.ascontiguousarray(p, dtype=np.float32)
+
+
+def _run_round(seed, B, depth, k, width, max_nodes, n_keep, ties=False):
+    rng = np.random.default_rng(seed)
+    state = jk.TreeState(B, max_nodes)
+    oracles = [dt.TreeState() for _ in range(B)]
+    fronts = [[-1] for _ in range(B)]
+    frontier = None
+    base = 0
+    for d in range(depth):
+        nf = 1 if frontier is None else frontier.shape[1]
+        tok, p = _cands(rng, B * nf, k, ties=ties)
+        frontier = jk.tree_grow(state, frontier, torch.from_numpy(tok).cuda(), torch.from_numpy(p).cuda(), width, base)
+        torch.cuda.synchronize()
+        got = frontier.cpu().numpy()
+        for b in range(B):
+            fronts[b] = dt.grow(oracles[b], fronts[b], tok[b * nf:(b + 1) * nf], p[b * nf:(b + 1) * nf], width,
+                                max_nodes, base + 2 * b * nf)
+            ref = fronts[b] + [fronts[b][0] if fronts[b] else -1] * (width - len(fronts[b]))
+            assert got[b].tolist() == ref, (d, b)
+            fronts[b] = ref
+        base += 2 * B * nf
+    n_nodes = state.n_nodes.cpu().numpy()
+    for b in range(B):
+        n = len(oracles[b].tokens)
+        assert n_nodes[b] == n
+        assert state.tokens[b, :n].cpu().tolist() == oracles[b].tokens
+        assert state.parent[b, :n].cpu().tolist() == oracles[b].parent
+        assert state.q_row[b, :n].cpu().tolist() == oracles[b].q_row
+        np.testing.assert_array_equal(state.score[b, :n].cpu().numpy(), np.asarray(oracles[b].score, dtype=np.float32))
+    tokens, parent, q_row, old, n_valid = jk.tree_finalize(state, n_keep)
+    torch.cuda.synchronize()
+    for b in range(B):
+        rt, rp, rq, ro = dt.finalize(oracles[b], n_keep)
+        nv = len(ro)
+        assert int(n_valid[b]) == nv
+        assert tokens[b, :nv].cpu().tolist() == rt.tolist()
+        assert parent[b, :nv].cpu().tolist() == rp.tolist()
+        assert q_row[b, :nv].cpu().tolist() == rq.tolist()
+        assert old[b, :nv].cpu().tolist() == ro.tolist()
+        assert (tokens[b, nv:] == -1).all() and (parent[b, nv:] == -1).all()
+        if nv == n_keep:
+            assert jk.validate_tree(parent[b].cpu().numpy()) == 0
+    return state, tokens, parent, q_row
+
+
+@pytest.mark.parametrize("B,depth,k,width,max_nodes,n_keep", [(3, 4, 5, 5, 512, 60), (1, 6, 5, 5, 1024, 100),
+                                                            (4, 3, 1, 1, 64, 3), (2, 5, 16, 8, 1024, 128),
+                                                            (2, 3, 2, 3, 256, 20)])
+def test_growth_and_cut_match_the_oracle(B, depth, k, width, max_nodes, n_keep):
+    _run_round(B * 100 + depth, B, depth, k, width, max_nodes, n_keep)
+
+
+def test_equal_scores_and_capacity():
+    _run_round(7, 2, 4, 4, 4, 512, 40, ties=True)
+    _run_round(8, 2, 4, 5, 5, 40, 40)        # the node arrays fill up: the tail of the last depths is dropped
+    _run_round(9, 1, 2, 2, 3, 64, 30)        # fewer nodes than asked for: the rest of the output says so
+
+
+def test_gather_draft_probs():
+    rng = np.random.default_rng(1)
+    q_all = rng.random((37, 1003)).astype(np.float32)
+    rows = rng.integers(0, 37, size=(3, 11)).astype(np.int32)
+    out = jk.gather_draft_probs(torch.from_numpy(q_all).cuda(), torch.from_numpy(rows).cuda())
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(out.cpu().numpy(), q_all[rows])
+    bad = rows.copy()
+    bad[0, 0], bad[1, 1] = -5, 99                      # clamped, must not fault
+    out = jk.gather_draft_probs(torch.from_numpy(q_all).cuda(), torch.from_numpy(bad).cuda())
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(out.cpu().numpy(), q_all[np.clip(bad, 0, 36)])
+    q4 = rng.random((5, 1024)).astype(np.float32)      # vector path
+    r4 = rng.integers(0, 5, size=(2, 3)).astype(np.int32)
+    out = jk.gather_draft_probs(torch.from_numpy(q4).cuda(), torch.from_numpy(r4).cuda())
+    np.testing.assert_array_equal(out.cpu().numpy(), q4[r4])
+
+
+def test_whole_round_on_the_device():
+    """Random weights: hidden states -> experts -> heads -> tree (3 depths) -> cut -> dense draft distributions ->
+    speculative-sampling acceptance.  Every node's token is one of its distribution's top-k, its draft probability
+    is positive, the tree is a valid input of the verification calls, and the acceptance result equals the
+    oracle's on the same tree."""
+    B, d, F, N, V, k, width, depth, n_keep = 2, 256, 384, 4, 2000, 4, 3, 3, 20
+    w_head = torch.from_numpy(draft_head_inputs(1, d, V, seed=3)["w_head"]).cuda().to(torch.bfloat16)
+    state = jk.TreeState(B, 256)
+    frontier, base = None, 0
+    q_bufs, cand_toks = [], []
+    for dep in range(depth):
+        nf = 1 if frontier is None else frontier.shape[1]
+        x = moe_inputs(B * nf, d, F, N, seed=10 + dep)     # (the draft layer's attention is not part of the library)
+        dev = lambda key: torch.from_numpy(x[key]).cuda().to(torch.bfloat16)
+        f_top, s_top, idx, _ = jk.moe_experts(dev("u"), dev("centroids"), dev("w_gate"), dev("w_up"), dev("w_down"), False)
+        lg, q, tk, tp = jk.draft_heads(f_top, s_top, w_head, jk.JK_HEADS_DECOUPLED, 1.0, k)
+        frontier = jk.tree_grow(state, frontier, tk.reshape(B * nf, 2, k), tp.reshape(B * nf, 2, k), width, base)
+        q_bufs.append(q.reshape(-1, V))
+        cand_toks.append(tk.reshape(-1, k))
+        base += 2 * B * nf
+    q_all = torch.cat(q_bufs, 0).contiguous()
+    tokens, parent, q_row, old, n_valid = jk.tree_finalize(state, n_keep)
+    draft_probs = jk.gather_draft_probs(q_all, q_row)
+    torch.cuda.synchronize()
+    assert n_valid.cpu().tolist() == [n_keep] * B
+    all_cands = torch.cat(cand_toks, 0).cpu().numpy()
+    tok_h, par_h, qr_h, dp_h = tokens.cpu().numpy(), parent.cpu().numpy(), q_row.cpu().numpy(), draft_probs.cpu().numpy()
+    for b in range(B):
+        assert jk.validate_tree(par_h[b]) == 0
+        for i in range(n_keep):
+            assert tok_h[b, i] in all_cands[qr_h[b, i]]
+            assert dp_h[b, i, tok_h[b, i]] > 0
+            np.testing.assert_allclose(dp_h[b, i].sum(), 1.0, rtol=1e-4)
+    rng = np.random.default_rng(5)
+    logits = (rng.standard_normal((B, n_keep + 1, V)) * 2).astype(np.float32)
+    for b in range(B):                                   # make the drafts plausible for the target
+        for i in range(n_keep):
+            logits[b, par_h[b, i] + 1, tok_h[b, i]] += 6.0
+    uni = rng.random((B, n_keep + 1)).astype(np.float32)
+    path, alen, bonus = jk.accept_path(tokens, parent, torch.from_numpy(logits).cuda(), jk.JK_SAMPLE, 1.0,
+                                       draft_probs, torch.from_numpy(uni).cuda(), max_depth=depth)
+    torch.cuda.synchronize()
+    checked = 0
+    for b in range(B):
+        r = oracle_accept(tok_h[b], par_h[b], logits[b], "sample", temperature=1.0, draft_probs=dp_h[b], uniforms=uni[b])
+        if r.min_margin > 1e-9:
+            assert path[b, : int(alen[b])].cpu().tolist() == r.path[:depth] and int(bonus[b]) == r.bonus_token
+            checked += 1
+    assert checked >= 1
+
+
+def test_argument_errors():
+    state = jk.TreeState(1, 64)
+    tok = torch.zeros((1, 2, 200), dtype=torch.int32, device="cuda")
+    p = torch.zeros((1, 2, 200), dtype=torch.float32, device="cuda")
+    with pytest.raises(jk.JakiroError) as e:           # 400 candidates in one call
+        jk.tree_grow(state, None, tok, p, 4, 0)
+    assert e.value.status == 3
+    with pytest.raises(jk.JakiroError) as e:
+        jk.tree_finalize(state, 65)
+    assert e.value.status == 1
+    big = jk.TreeState(1, 2048)
+    with pytest.raises(jk.JakiroError) as e:
+        jk.tree_grow(big, None, tok[:, :, :4].contiguous(), p[:, :, :4].contiguous(), 4, 0)
+    assert e.value.status == 3
+    torch.cuda.synchronize()
