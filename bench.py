@@ -348,6 +348,35 @@ def main():
                                 "weight_stream_GBps": round(n_used * 3 * d_model * d_ff * 2 / (mo_us * 1e-6) / 1e9, 1),
                                 "note": "one jk_moe_experts call: router, top-2, expert MLPs of the selected experts"}
         del mo_w
+        # tree growth from the heads' candidates: one depth (5 frontier nodes per sequence), the cut to the
+        # workload's tree size and the dense draft distributions for the acceptance call
+        tg_front = 5
+        tg_state = jk.TreeState(cfg.batch, 512)
+        tg_tok = torch.randint(0, cfg.vocab, (cfg.batch * tg_front, 2, 10), dtype=torch.int32, device=dev, generator=gen)
+        tg_p = torch.rand((cfg.batch * tg_front, 2, 10), device=dev, generator=gen).sort(dim=2, descending=True).values
+        tg_root_tok, tg_root_p = tg_tok[: cfg.batch].contiguous(), tg_p[: cfg.batch].contiguous()
+        tg_q = torch.rand((2 * cfg.batch * (1 + 2 * tg_front), cfg.vocab), device=dev, generator=gen)
+
+        def tree_pass():
+            tg_state.reset()
+            fr = jk.tree_grow(tg_state, None, tg_root_tok, tg_root_p, tg_front, 0)
+            for dpt in range(2):
+                fr = jk.tree_grow(tg_state, fr, tg_tok, tg_p, tg_front, 2 * cfg.batch * (1 + dpt * tg_front))
+            out = jk.tree_finalize(tg_state, cfg.n_tree)
+            return jk.gather_draft_probs(tg_q, out[2])
+        tree_pass()
+        torch.cuda.synchronize()
+        et0, et1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        et0.record()
+        for _ in range(10):
+            tree_pass()
+        et1.record()
+        torch.cuda.synchronize()
+        draft["tree_build"] = {"us_per_round": round(et0.elapsed_time(et1) * 1e3 / 10, 1), "depths": 3,
+                               "nodes_kept": cfg.n_tree,
+                               "note": "3 jk_tree_grow + jk_tree_finalize + jk_gather_draft_probs, eager launches "
+                                       "(includes torch's output allocations)"}
+        del tg_q
 
     for _ in range(args.copy_calibration):
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
