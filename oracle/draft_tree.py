@@ -80,3 +80,40 @@ def finalize(state: TreeState, n_keep: int) -> Tuple[np.ndarray, np.ndarray, np.
             np.asarray([new_id[state.parent[i]] for i in kept], dtype=np.int64),
             np.asarray([state.q_row[i] for i in kept], dtype=np.int64),
             np.asarray(kept, dtype=np.int64))
+
+
+def grow_parallel_tail(state: TreeState, frontier: Sequence[int], cand_tok: np.ndarray, cand_p: np.ndarray,
+                       k1: int, k2: int, width: int, max_nodes: int, q_row_base: int) -> None:
+    """The last draft pass when the two heads are the mixture head and the contrastive head (Section 3.2,
+    Eq. 6-8): the mixture head's candidates are the next level as usual, and the contrastive head, which
+    predicts one position further from the same features, supplies the level after it without another pass
+    of the draft model.
+
+    Reading: every frontier node f gets the first k1 candidates of its mixture list (cand_*[f][0]) as
+    children; then each of the `width` best children (ties to the lower index), in index order, gets the
+    first k2 candidates of its parent's contrastive list (cand_*[f][1]) as children.  All children are
+    numbered before all grandchildren.  Scores multiply as in `grow`; the distribution rows are
+    q_row_base + 2 f for children and q_row_base + 2 f + 1 for grandchildren."""
+    children, slot_of = [], {}
+    for f, pid in enumerate(frontier):
+        ps = np.float32(1.0) if pid < 0 else state.score[pid]
+        for j in range(k1):
+            if len(state.tokens) >= max_nodes:
+                continue
+            c = len(state.tokens)
+            children.append(c)
+            slot_of[c] = f
+            state.tokens.append(int(cand_tok[f, 0, j]))
+            state.parent.append(int(pid))
+            state.score.append(np.float32(ps * np.float32(cand_p[f, 0, j])))
+            state.q_row.append(q_row_base + 2 * f)
+    best = sorted(sorted(children, key=lambda i: (-float(state.score[i]), i))[:width])
+    for c in best:
+        f = slot_of[c]
+        for j in range(k2):
+            if len(state.tokens) >= max_nodes:
+                continue
+            state.tokens.append(int(cand_tok[f, 1, j]))
+            state.parent.append(c)
+            state.score.append(np.float32(state.score[c] * np.float32(cand_p[f, 1, j])))
+            state.q_row.append(q_row_base + 2 * f + 1)

@@ -101,3 +101,42 @@ def test_ties_go_to_the_lower_index_and_capacity_drops_the_tail():
     fr = dt.grow(st, [-1], tok, p, width=3, max_nodes=6, q_row_base=0)
     assert len(st.tokens) == 6 and fr == [0, 1, 2]
     assert dt.finalize(st, 4)[3].tolist() == [0, 1, 2, 3]
+
+
+def test_parallel_tail_hand_worked_and_invariants():
+    st = dt.TreeState()
+    fr = dt.grow(st, [-1], np.array([[[1, 2], [3, 4]]]), np.array([[[0.5, 0.25], [0.125, 0.0625]]], dtype=np.float32),
+                 width=2, max_nodes=64, q_row_base=0)
+    assert fr == [0, 1]
+    tok = np.array([[[10, 11, 12], [20, 21, 22]], [[30, 31, 32], [40, 41, 42]]])
+    p = np.array([[[0.5, 0.25, 0.125], [0.5, 0.5, 0.25]], [[1.0, 0.5, 0.25], [0.25, 0.125, 0.0625]]], dtype=np.float32)
+    dt.grow_parallel_tail(st, fr, tok, p, k1=2, k2=2, width=3, max_nodes=64, q_row_base=2)
+    # children: 4,5 under node 0 (0.25, 0.125), 6,7 under node 1 (0.25, 0.125); best three: 4, 6, 5
+    assert st.tokens[4:8] == [10, 11, 30, 31] and st.parent[4:8] == [0, 0, 1, 1] and st.q_row[4:8] == [2, 2, 4, 4]
+    assert [float(s) for s in st.score[4:8]] == [0.25, 0.125, 0.25, 0.125]
+    # grandchildren in index order of the chosen children 4, 5, 6, each with its parent's contrastive list
+    assert st.parent[8:] == [4, 4, 5, 5, 6, 6]
+    assert st.tokens[8:] == [20, 21, 20, 21, 40, 41]
+    assert st.q_row[8:] == [3, 3, 3, 3, 5, 5]
+    assert [float(s) for s in st.score[8:]] == [0.125, 0.125, 0.0625, 0.0625, 0.0625, 0.03125]
+    # invariants on a random case
+    rng = np.random.default_rng(3)
+    st = dt.TreeState()
+    fr = dt.grow(st, [-1], rng.integers(0, 99, (1, 2, 4)), np.sort(rng.random((1, 2, 4)).astype(np.float32))[:, :, ::-1],
+                 3, 200, 0)
+    n0 = len(st.tokens)
+    tok = rng.integers(0, 99, (3, 2, 5))
+    p = np.sort(rng.random((3, 2, 5)).astype(np.float32), axis=2)[:, :, ::-1]
+    dt.grow_parallel_tail(st, fr, tok, p, 4, 3, 5, 200, 2)
+    par = np.array(st.parent)
+    kids = [i for i in range(n0, len(par)) if par[i] in fr]
+    grand = [i for i in range(n0, len(par)) if par[i] >= n0]
+    assert len(kids) == 12 and len(grand) == 15 and max(kids) < min(grand)
+    assert all(st.q_row[i] % 2 == 0 for i in kids) and all(st.q_row[i] % 2 == 1 for i in grand)
+    for g in grand:                                # a grandchild's list is its grandparent's contrastive list
+        f = fr.index(par[par[g]])
+        assert st.tokens[g] in tok[f, 1, :3] and st.q_row[g] == st.q_row[par[g]] + 1
+        assert st.score[g] <= st.score[par[g]]
+    expanded = sorted(set(par[g] for g in grand))
+    rest = [c for c in kids if c not in expanded]
+    assert all(float(st.score[c]) <= min(float(st.score[e]) for e in expanded) for c in rest)
