@@ -372,6 +372,19 @@ jk_status jk_tree_grow(const jk_tree_state* state, int32_t batch, int32_t n_fron
                        int32_t q_row_base, const int32_t* frontier_in, const int32_t* cand_tokens,
                        const float* cand_probs, int32_t* frontier_out, void* hip_stream);
 
+/* The last draft pass when jk_draft_heads ran in JK_HEADS_CONTRASTIVE mode (Section 3.2, Eq. 6-8:
+ * the contrastive head predicts one position further than the mixture head from the same
+ * features, which saves one pass of the draft model).  Reading: every frontier node gets the
+ * first k1 candidates of its mixture list (head 0) as children; then each of the `width` best
+ * children (ties to the lower index), in index order, gets the first k2 candidates of its
+ * parent's contrastive list (head 1) as children.  All children are numbered before all
+ * grandchildren; q_row is q_row_base + 2 (b n_front + f) for children and one more for
+ * grandchildren.  cand_tokens / cand_probs as for jk_tree_grow with lists of top_k entries;
+ * k1, k2 <= top_k, n_front * k1 <= 256, width * k2 <= 256. */
+jk_status jk_tree_grow_tail(const jk_tree_state* state, int32_t batch, int32_t n_front, int32_t top_k, int32_t k1,
+                            int32_t k2, int32_t width, int32_t q_row_base, const int32_t* frontier_in,
+                            const int32_t* cand_tokens, const float* cand_probs, void* hip_stream);
+
 jk_status jk_tree_finalize(const jk_tree_state* state, int32_t batch, int32_t n_keep, int32_t* tree_tokens,
                            int32_t* parent, int32_t* q_row, int32_t* old_index, int32_t* n_valid, void* hip_stream);
 

@@ -66,7 +66,7 @@ class PagedKV(ctypes.Structure):
 
 EXPORTS = ("jk_tree_verify_attention_workspace", "jk_tree_verify_attention", "jk_tree_verify_attention_paged",
            "jk_commit_path_layers_paged", "jk_accept_path_workspace",
-           "jk_accept_path", "jk_draft_heads_workspace", "jk_draft_heads", "jk_moe_experts_workspace", "jk_moe_experts", "jk_tree_grow", "jk_tree_finalize", "jk_gather_draft_probs", "jk_commit_path", "jk_commit_path_layers", "jk_workspace_init", "jk_stream_read_probe", "jk_validate_tree", "jk_status_string", "jk_version")
+           "jk_accept_path", "jk_draft_heads_workspace", "jk_draft_heads", "jk_moe_experts_workspace", "jk_moe_experts", "jk_tree_grow", "jk_tree_grow_tail", "jk_tree_finalize", "jk_gather_draft_probs", "jk_commit_path", "jk_commit_path_layers", "jk_workspace_init", "jk_stream_read_probe", "jk_validate_tree", "jk_status_string", "jk_version")
 
 
 def library_path() -> str:
@@ -112,6 +112,8 @@ def lib() -> ctypes.CDLL:
         l.jk_moe_experts.argtypes = [ctypes.POINTER(MoeDesc), vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         l.jk_tree_grow.restype = i32
         l.jk_tree_grow.argtypes = [ctypes.POINTER(TreeStateDesc), i32, i32, i32, i32, i32, vp, vp, vp, vp, vp]
+        l.jk_tree_grow_tail.restype = i32
+        l.jk_tree_grow_tail.argtypes = [ctypes.POINTER(TreeStateDesc), i32, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp]
         l.jk_tree_finalize.restype = i32
         l.jk_tree_finalize.argtypes = [ctypes.POINTER(TreeStateDesc), i32, i32, vp, vp, vp, vp, vp, vp]
         l.jk_gather_draft_probs.restype = i32
@@ -584,6 +586,21 @@ def tree_grow(state: TreeState, frontier_in, cand_tokens, cand_probs, width: int
     if st != 0:
         raise JakiroError(st, "jk_tree_grow")
     return out
+
+
+def tree_grow_tail(state: TreeState, frontier_in, cand_tokens, cand_probs, k1: int, k2: int, width: int,
+                   q_row_base: int, stream=None) -> None:
+    """jk_tree_grow_tail: children from head 0's lists, grandchildren from head 1's (contrastive mode)."""
+    B = state.batch
+    n_front = 1 if frontier_in is None else int(frontier_in.shape[1])
+    rows, two, k = cand_tokens.shape
+    if rows != B * n_front or two != 2 or tuple(cand_probs.shape) != (rows, 2, k):
+        raise ValueError("cand_tokens / cand_probs must be [B*n_front, 2, k]")
+    d = state.desc()
+    st = lib().jk_tree_grow_tail(ctypes.byref(d), B, n_front, int(k), int(k1), int(k2), int(width), int(q_row_base),
+                                 _ptr(frontier_in), _ptr(cand_tokens), _ptr(cand_probs), _stream_handle(stream))
+    if st != 0:
+        raise JakiroError(st, "jk_tree_grow_tail")
 
 
 def tree_finalize(state: TreeState, n_keep: int, stream=None):

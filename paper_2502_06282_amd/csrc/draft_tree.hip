@@ -75,6 +75,66 @@ __global__ __launch_bounds__(kTreeThreads) void grow_kernel(TreeGrowArgs a) {
   if (t == 0) a.n_nodes[b] = min(n0 + C, a.max_nodes);
 }
 
+// The last draft pass with a mixture head and a contrastive head (Section 3.2): children from
+// head 0's list, then the `width` best children get head 1's list of their parent as children.
+__global__ __launch_bounds__(kTreeThreads) void grow_tail_kernel(TreeGrowArgs a, int k1, int k2) {
+  __shared__ float s_sc[kTreeThreads];
+  __shared__ int s_sel[kTreeThreads];
+  __shared__ int s_child[kTreeThreads];  // chosen children by slot: node id, frontier slot
+  __shared__ int s_slot_f[kTreeThreads];
+  const int b = blockIdx.x, t = threadIdx.x;
+  const int C = a.n_front * k1;
+  const int n0 = a.n_nodes[b];
+  const int id = n0 + t;
+  const bool valid = t < C && id < a.max_nodes;
+  const long long base = (long long)b * a.max_nodes;
+  float sc = -INFINITY;
+  const int f = t / k1, j = t - f * k1;
+  if (valid) {
+    const long long row = (long long)b * a.n_front + f;
+    const int pid = a.frontier_in ? a.frontier_in[row] : -1;
+    const bool has_parent = pid >= 0 && pid < n0;
+    const float ps = has_parent ? a.score[base + pid] : 1.0f;
+    sc = ps * a.cand_p[row * 2 * a.top_k + j];
+    a.tokens[base + id] = a.cand_tok[row * 2 * a.top_k + j];
+    a.parent[base + id] = has_parent ? pid : -1;
+    a.score[base + id] = sc;
+    a.q_row[base + id] = a.q_row_base + (int)(2 * row);
+  }
+  s_sc[t] = sc;
+  __syncthreads();
+  int rank = 0;
+#pragma unroll 8
+  for (int i = 0; i < kTreeThreads; ++i) rank += beats(s_sc[i], i, sc, t);
+  const int sel = (valid && rank < a.width) ? 1 : 0;
+  s_sel[t] = sel;
+  __syncthreads();
+  int slot = 0, total = 0;
+#pragma unroll 8
+  for (int i = 0; i < kTreeThreads; ++i) {
+    slot += (i < t) ? s_sel[i] : 0;
+    total += s_sel[i];
+  }
+  if (sel) {
+    s_child[slot] = id;
+    s_slot_f[slot] = f;
+  }
+  __syncthreads();
+  const int n1 = min(n0 + C, a.max_nodes);
+  const int G = total * k2;
+  const int gid = n1 + t;
+  if (t < G && gid < a.max_nodes) {
+    const int s = t / k2, j2 = t - s * k2;
+    const int c = s_child[s];
+    const long long row = (long long)b * a.n_front + s_slot_f[s];
+    a.tokens[base + gid] = a.cand_tok[(row * 2 + 1) * a.top_k + j2];
+    a.parent[base + gid] = c;
+    a.score[base + gid] = s_sc[c - n0] * a.cand_p[(row * 2 + 1) * a.top_k + j2];
+    a.q_row[base + gid] = a.q_row_base + (int)(2 * row) + 1;
+  }
+  if (t == 0) a.n_nodes[b] = min(n1 + G, a.max_nodes);
+}
+
 __global__ __launch_bounds__(kTreeThreads) void finalize_kernel(TreeFinalArgs a) {
   __shared__ float s_sc[kMaxGrowNodes];
   __shared__ short s_keep[kMaxGrowNodes];
@@ -145,6 +205,10 @@ int tree_max_nodes() { return kMaxGrowNodes; }
 
 hipError_t launch_tree_grow(const TreeGrowArgs& a, hipStream_t stream) {
   hipLaunchKernelGGL(grow_kernel, dim3(a.batch), dim3(kTreeThreads), 0, stream, a);
+  return hipGetLastError();
+}
+hipError_t launch_tree_grow_tail(const TreeGrowArgs& a, int k1, int k2, hipStream_t stream) {
+  hipLaunchKernelGGL(grow_tail_kernel, dim3(a.batch), dim3(kTreeThreads), 0, stream, a, k1, k2);
   return hipGetLastError();
 }
 hipError_t launch_tree_finalize(const TreeFinalArgs& a, hipStream_t stream) {

@@ -161,3 +161,36 @@ def test_argument_errors():
         jk.tree_grow(big, None, tok[:, :, :4].contiguous(), p[:, :, :4].contiguous(), 4, 0)
     assert e.value.status == 3
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("B,k,k1,k2,width,max_nodes", [(2, 5, 5, 5, 5, 512), (3, 4, 2, 3, 7, 256), (1, 8, 8, 8, 32, 1024),
+                                                      (2, 6, 6, 4, 4, 60)])
+def test_parallel_tail_matches_the_oracle(B, k, k1, k2, width, max_nodes):
+    rng = np.random.default_rng(B * 10 + k)
+    state = jk.TreeState(B, max_nodes)
+    oracles = [dt.TreeState() for _ in range(B)]
+    tok, p = _cands(rng, B, k)
+    front_w = 4
+    frontier = jk.tree_grow(state, None, torch.from_numpy(tok).cuda(), torch.from_numpy(p).cuda(), front_w, 0)
+    fronts = [dt.grow(oracles[b], [-1], tok[b:b + 1], p[b:b + 1], front_w, max_nodes, 2 * b) for b in range(B)]
+    tok, p = _cands(rng, B * front_w, k)
+    base = 2 * B
+    jk.tree_grow_tail(state, frontier, torch.from_numpy(tok).cuda(), torch.from_numpy(p).cuda(), k1, k2, width, base)
+    torch.cuda.synchronize()
+    for b in range(B):
+        dt.grow_parallel_tail(oracles[b], fronts[b], tok[b * front_w:(b + 1) * front_w], p[b * front_w:(b + 1) * front_w],
+                              k1, k2, width, max_nodes, base + 2 * b * front_w)
+        n = len(oracles[b].tokens)
+        assert int(state.n_nodes[b]) == n
+        assert state.tokens[b, :n].cpu().tolist() == oracles[b].tokens
+        assert state.parent[b, :n].cpu().tolist() == oracles[b].parent
+        assert state.q_row[b, :n].cpu().tolist() == oracles[b].q_row
+        np.testing.assert_array_equal(state.score[b, :n].cpu().numpy(), np.asarray(oracles[b].score, dtype=np.float32))
+    n_keep = min(40, max_nodes)
+    tokens, parent, q_row, old, n_valid = jk.tree_finalize(state, n_keep)
+    torch.cuda.synchronize()
+    for b in range(B):
+        rt, rp, rq, ro = dt.finalize(oracles[b], n_keep)
+        nv = len(ro)
+        assert int(n_valid[b]) == nv and parent[b, :nv].cpu().tolist() == rp.tolist()
+        assert tokens[b, :nv].cpu().tolist() == rt.tolist() and q_row[b, :nv].cpu().tolist() == rq.tolist()
