@@ -815,9 +815,19 @@ MoePlan moe_plan(int rows, int d, int f, int n) {
 }
 
 struct RowPlan {
-  int parts, part_len;
-  size_t x_bytes, ms_off, cv_off, ci_off, mz_off, total;
+  int parts, part_len, ksplit;
+  size_t x_bytes, ms_off, cv_off, ci_off, mz_off, part_off, total;
 };
+
+// logits = sum of the k parts' partial products (fixed order)
+__global__ __launch_bounds__(256) void sum_parts_kernel(const float* __restrict__ part, float* __restrict__ out,
+                                                        long long n, int ksplit) {
+  for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += (long long)gridDim.x * 256) {
+    float v = part[i];
+    for (int z = 1; z < ksplit; ++z) v += part[i + z * n];
+    out[i] = v;
+  }
+}
 RowPlan row_plan(int rows, int d_model, int vocab) {
   RowPlan r;
   const size_t m = 2 * (size_t)rows, m_pad = (m + 31) / 32 * 32;
@@ -829,7 +839,12 @@ RowPlan row_plan(int rows, int d_model, int vocab) {
   r.cv_off = r.ms_off + up(m * r.parts * 2 * 4);
   r.ci_off = r.cv_off + up(m * r.parts * kMaxTopK * 4);
   r.mz_off = r.ci_off + up(m * r.parts * kMaxTopK * 4);
-  r.total = r.mz_off + up(m * 2 * 4);
+  r.part_off = r.mz_off + up(m * 2 * 4);
+  // a small vocabulary gives few 512-row strips: split k until the chip is full (partials of at most 64 MB)
+  r.ksplit = pick_ksplit(vocab, d_model, (int)(m_pad / 32), 1, device_cu_count());
+  while (r.ksplit > 1 && (size_t)r.ksplit * m * vocab * 4 > ((size_t)64 << 20)) --r.ksplit;
+  while (r.ksplit > 1 && (d_model % (128 * r.ksplit) != 0 || d_model / r.ksplit < 512)) --r.ksplit;
+  r.total = r.part_off + (r.ksplit > 1 ? up((size_t)r.ksplit * m * vocab * 4) : 0);
   return r;
 }
 
@@ -857,9 +872,16 @@ hipError_t launch_draft_heads(const DraftHeadsArgs& a, hipStream_t stream) {
   gp.m = m; gp.n = a.vocab; gp.k = a.d_model;
   gp.ldw = a.d_model; gp.ldy = a.vocab;
   gp.batch = 1; gp.x_batch = gp.w_batch = gp.y_batch = 0; gp.used = nullptr;
-  gp.ksplit = 1; gp.y_split = 0;
+  gp.ksplit = rp.ksplit; gp.y_split = (long long)m * a.vocab;
+  if (rp.ksplit > 1) gp.y = reinterpret_cast<float*>(ws + rp.part_off);
   e = launch_gemm(gp, stream);
   if (e != hipSuccess) return e;
+  if (rp.ksplit > 1) {
+    const long long n_out = (long long)m * a.vocab;
+    const unsigned grid = (unsigned)((n_out + 1023) / 1024 < 2048 ? (n_out + 1023) / 1024 : 2048);
+    hipLaunchKernelGGL(sum_parts_kernel, dim3(grid), dim3(256), 0, stream, gp.y, a.logits, n_out, rp.ksplit);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
 
   SoftParams sp;
   sp.logits = a.logits; sp.probs = a.draft_probs; sp.tk_ids = a.topk_tokens; sp.tk_probs = a.topk_probs;

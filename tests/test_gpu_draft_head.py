@@ -61,7 +61,8 @@ def _exact_inputs(rows, d, vocab, seed):
             "w_head": (rng.integers(-1, 2, size=(vocab, d)) * 0.125).astype(np.float32)}
 
 
-@pytest.mark.parametrize("rows,d,vocab", [(3, 256, 1000), (16, 128, 130), (17, 384, 4099), (128, 256, 513)])
+@pytest.mark.parametrize("rows,d,vocab", [(3, 256, 1000), (16, 128, 130), (17, 384, 4099), (128, 256, 513),
+                                            (5, 1024, 3000), (40, 2048, 700)])   # the last two split k
 def test_exact_arithmetic_inputs_are_bit_exact(rows, d, vocab):
     _check(_exact_inputs(rows, d, vocab, rows), exact=True)
     _check(_exact_inputs(rows, d, vocab, rows + 1), mode=jk.JK_HEADS_CONTRASTIVE, alpha=0.5, beta=2.0, exact=True)
