@@ -391,6 +391,20 @@ jk_status jk_tree_finalize(const jk_tree_state* state, int32_t batch, int32_t n_
 jk_status jk_gather_draft_probs(int32_t batch, int32_t n_tree, int32_t vocab, const float* q_all, int64_t n_q_rows,
                                 const int32_t* q_row, float* draft_probs, void* hip_stream);
 
+/* The draft layer's remaining dense pieces (Section 3.1.1: a reduction layer in front of one
+ * decoder attention layer; Eq. 1: u = Attn(h) + h) are plain linear layers on few rows around
+ * jk_tree_verify_attention:  out = x . w^T (+ residual), bf16 operands, fp32 accumulation, on
+ * the same weight-streaming MFMA kernel as the heads and the experts.
+ *   m 1..256 rows;  k a multiple of 128;  n >= 1
+ *   x        device bf16 [m][k];  w device bf16 [n][k];  both 16-byte aligned
+ *   residual device bf16 [m][n], added in fp32; may be NULL
+ *   out_bf16 device bf16 [m][n] (one rounding) and/or out_f32 device fp32 [m][n]; at least one
+ *   workspace jk_linear_workspace(m, n, k) bytes, 256-byte aligned */
+size_t jk_linear_workspace(int32_t m, int32_t n, int32_t k);
+
+jk_status jk_linear(int32_t m, int32_t n, int32_t k, const void* x, const void* w, const void* residual,
+                    void* out_bf16, float* out_f32, void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Zero-fills a workspace with a small kernel on `hip_stream` (safe under HIP-graph
  * capture).  Needed once per workspace before its first jk_accept_path call: the
  * cooperative sampling walk synchronises its workgroups through tagged words in

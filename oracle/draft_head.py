@@ -156,3 +156,29 @@ def draft_heads(f_top: np.ndarray, s_top: np.ndarray, w_head: np.ndarray, mode: 
     q = draft_distribution(logits, temperature)
     ids = top_candidates(logits, k)
     return logits, q, ids, np.take_along_axis(q, ids, axis=-1)
+
+
+def linear(x: np.ndarray, w: np.ndarray, residual=None) -> np.ndarray:
+    """x [m,k], w [n,k] -> x w^T (+ residual)."""
+    y = np.asarray(x, np.float64) @ np.asarray(w, np.float64).T
+    return y if residual is None else y + np.asarray(residual, np.float64)
+
+
+def draft_attention_block(h: np.ndarray, wq: np.ndarray, wk: np.ndarray, wv: np.ndarray, wo: np.ndarray,
+                          k_cache: np.ndarray, v_cache: np.ndarray, parent: np.ndarray, n_heads: int,
+                          n_kv_heads: int) -> np.ndarray:
+    """Eq. 1 for the tree nodes of one sequence: u = Attn(h) + h with the attention of one decoder layer
+    over the draft layer's own key/value cache plus the nodes' tree ancestors (the draft model sees the
+    same tree the target will verify).  h [T,d]; wq, wo [d,d]; wk, wv [n_kv_heads*D, d];
+    k_cache, v_cache [L, n_kv_heads, D].  Position encodings are outside (applied to q and k by the caller,
+    here: none)."""
+    from .tree_attention import tree_verify_attention
+    T, d = h.shape
+    D = d // n_heads
+    q = linear(h, wq).reshape(1, T, n_heads, D)
+    kt = linear(h, wk).reshape(1, T, n_kv_heads, D)
+    vt = linear(h, wv).reshape(1, T, n_kv_heads, D)
+    L = k_cache.shape[0]
+    attn = tree_verify_attention(q, np.asarray(k_cache, np.float64)[None], np.asarray(v_cache, np.float64)[None], kt, vt,
+                                 parent=np.asarray(parent)[None], prefix_len=[L])
+    return linear(attn.reshape(T, d), wo, residual=h)

@@ -66,7 +66,7 @@ class PagedKV(ctypes.Structure):
 
 EXPORTS = ("jk_tree_verify_attention_workspace", "jk_tree_verify_attention", "jk_tree_verify_attention_paged",
            "jk_commit_path_layers_paged", "jk_accept_path_workspace",
-           "jk_accept_path", "jk_draft_heads_workspace", "jk_draft_heads", "jk_moe_experts_workspace", "jk_moe_experts", "jk_tree_grow", "jk_tree_grow_tail", "jk_tree_finalize", "jk_gather_draft_probs", "jk_commit_path", "jk_commit_path_layers", "jk_workspace_init", "jk_stream_read_probe", "jk_validate_tree", "jk_status_string", "jk_version")
+           "jk_accept_path", "jk_draft_heads_workspace", "jk_draft_heads", "jk_moe_experts_workspace", "jk_moe_experts", "jk_linear_workspace", "jk_linear", "jk_tree_grow", "jk_tree_grow_tail", "jk_tree_finalize", "jk_gather_draft_probs", "jk_commit_path", "jk_commit_path_layers", "jk_workspace_init", "jk_stream_read_probe", "jk_validate_tree", "jk_status_string", "jk_version")
 
 
 def library_path() -> str:
@@ -110,6 +110,10 @@ def lib() -> ctypes.CDLL:
         l.jk_moe_experts_workspace.argtypes = [ctypes.POINTER(MoeDesc)]
         l.jk_moe_experts.restype = i32
         l.jk_moe_experts.argtypes = [ctypes.POINTER(MoeDesc), vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        l.jk_linear_workspace.restype = sz
+        l.jk_linear_workspace.argtypes = [i32, i32, i32]
+        l.jk_linear.restype = i32
+        l.jk_linear.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
         l.jk_tree_grow.restype = i32
         l.jk_tree_grow.argtypes = [ctypes.POINTER(TreeStateDesc), i32, i32, i32, i32, i32, vp, vp, vp, vp, vp]
         l.jk_tree_grow_tail.restype = i32
@@ -631,4 +635,28 @@ def gather_draft_probs(q_all, q_row, stream=None):
     st = lib().jk_gather_draft_probs(B, N, V, _ptr(q_all), n_rows, _ptr(q_row), _ptr(out), _stream_handle(stream))
     if st != 0:
         raise JakiroError(st, "jk_gather_draft_probs")
+    return out
+
+
+def linear(x, w, residual=None, out_dtype=None, stream=None):
+    """jk_linear: x bf16 [m,k], w bf16 [n,k], residual bf16 [m,n] or None -> x @ w.T (+ residual) as bf16
+    (default) or float32 (out_dtype=torch.float32)."""
+    import torch
+    m, k = x.shape
+    n = w.shape[0]
+    for t in (x, w, residual):
+        if t is not None and (t.dtype != torch.bfloat16 or not t.is_contiguous()):
+            raise TypeError("x, w and residual must be contiguous bfloat16")
+    if w.shape[1] != k or (residual is not None and tuple(residual.shape) != (m, n)):
+        raise ValueError("x [m,k], w [n,k], residual [m,n]")
+    f32 = out_dtype == torch.float32
+    out = torch.empty((m, n), dtype=torch.float32 if f32 else torch.bfloat16, device=x.device)
+    need = int(lib().jk_linear_workspace(m, n, k))
+    if need == 0:
+        raise JakiroError(3, "jk_linear_workspace")
+    ws = torch.empty(need, dtype=torch.uint8, device=x.device)
+    st = lib().jk_linear(m, n, k, _ptr(x), _ptr(w), _ptr(residual), None if f32 else _ptr(out),
+                         _ptr(out) if f32 else None, _ptr(ws), need, _stream_handle(stream))
+    if st != 0:
+        raise JakiroError(st, "jk_linear")
     return out

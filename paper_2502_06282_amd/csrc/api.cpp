@@ -458,6 +458,27 @@ jk_status jk_gather_draft_probs(int32_t batch, int32_t n_tree, int32_t vocab, co
              : JK_ERR_HIP;
 }
 
+static bool linear_shape_ok(int32_t m, int32_t n, int32_t k) {
+  return m >= 1 && m <= 256 && n >= 1 && k >= 128 && k % 128 == 0 && k <= (1 << 20) && n <= (1 << 24);
+}
+
+size_t jk_linear_workspace(int32_t m, int32_t n, int32_t k) {
+  return linear_shape_ok(m, n, k) ? linear_workspace_bytes(m, n, k) : 0;
+}
+
+jk_status jk_linear(int32_t m, int32_t n, int32_t k, const void* x, const void* w, const void* residual,
+                    void* out_bf16, float* out_f32, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!x || !w || (!out_bf16 && !out_f32) || m < 1 || n < 1 || k < 1) return JK_ERR_INVALID_ARG;
+  if (reinterpret_cast<uintptr_t>(x) % 16 || reinterpret_cast<uintptr_t>(w) % 16) return JK_ERR_INVALID_ARG;
+  if (!linear_shape_ok(m, n, k)) return JK_ERR_UNSUPPORTED;
+  if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256 || workspace_bytes < linear_workspace_bytes(m, n, k))
+    return JK_ERR_WORKSPACE;
+  LinearArgs a;
+  a.m = m; a.n = n; a.k = k; a.x = x; a.w = w; a.residual = residual; a.out_f32 = out_f32; a.out_bf16 = out_bf16;
+  a.workspace = workspace;
+  return launch_linear(a, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? JK_OK : JK_ERR_HIP;
+}
+
 jk_status jk_workspace_init(void* workspace, size_t workspace_bytes, void* hip_stream) {
   if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256) return JK_ERR_WORKSPACE;
   return launch_zero_fill(workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream)) == hipSuccess

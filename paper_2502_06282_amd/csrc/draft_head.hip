@@ -7,11 +7,14 @@
 // Kernels:
 //   head_inputs_kernel     X[2R (padded to 32), d] bf16 from f_top, s_top (elementwise, tiny)
 //   skinny_gemm_kernel     Y[M, N] fp32 = X[M, K] . W[N, K]^T with M <= 256: the weight matrix
-//                          (gigabytes for an output embedding) is streamed from HBM exactly once,
-//                          straight into MFMA operand registers; X is small, is shared by all
-//                          workgroups through L2 and staged per 64-wide k block in LDS.
+//                          (gigabytes for an output embedding) is streamed from HBM exactly once;
+//                          both operands are staged HBM/L2 -> LDS in swizzled 64-byte row segments
+//                          and read from there in MFMA layout.  Batched over experts and split
+//                          along k where a projection alone would not fill the chip.
 //   row_parts_kernel, row_merge_kernel, row_probs_kernel   per logits row: maximum, normaliser,
 //                          top-k by value (ties to the lower token id), probabilities.
+//   router_kernel, gated_act_kernel, select_kernel   the draft layer's router (Eq. 2, 5) and what
+//                          surrounds the experts' three projections (Eq. 3).
 #include <climits>
 
 #include "jk_internal.h"
@@ -80,7 +83,7 @@ constexpr int kGemmThreads = 512;  // 8 waves
 constexpr int kKB = 32;            // k extent of one main-loop step (two MFMA k steps): 64 bytes per row
 
 struct GemmParams {
-  const uint16_t* x;  // [MB*32][k] bf16, rows >= m are readable (zero or anything: not stored)
+  const uint16_t* x;  // [m][k] bf16
   const uint16_t* w;  // [n][ldw] bf16
   float* y;           // [m][ldy]
   int m, n, k;
@@ -198,7 +201,8 @@ __global__ __launch_bounds__(kGemmThreads, 1) void skinny_gemm_kernel(GemmParams
   // X transfer q (16 rows) belongs to wave q % 8: at most two per wave (MB <= 8)
   const int cx = (wave < C::NXI ? 1 : 0) + (wave + 8 < C::NXI ? 1 : 0);
 #pragma unroll
-  for (int t = 0; t < 2; ++t) voff_x[t] = (unsigned)((16 * (wave + 8 * t) + sub) * p.k * 2) + piece;
+  for (int t = 0; t < 2; ++t)  // rows past the end repeat the last one (their results are never stored)
+    voff_x[t] = (unsigned)((long long)min(16 * (wave + 8 * t) + sub, p.m - 1) * p.k * 2) + piece;
   const uint16_t* w_strip = uniform_ptr(p.w + strip0 * p.ldw);
   const unsigned w_ring = (unsigned)(wave * C::W_WAVE);
 
@@ -814,6 +818,33 @@ MoePlan moe_plan(int rows, int d, int f, int n) {
   return m;
 }
 
+
+// ------------------------------------------------------------------ plain linear layer
+struct LinFinishParams {
+  const float* part;        // [ksplit][m*n]
+  const uint16_t* residual; // [m*n] bf16 or null
+  float* out_f32;           // or null
+  uint16_t* out_bf16;       // or null
+  long long n_out;
+  int ksplit;
+};
+__global__ __launch_bounds__(256) void linear_finish_kernel(LinFinishParams p) {
+  for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < p.n_out; i += (long long)gridDim.x * 256) {
+    float v = p.part[i];
+    for (int z = 1; z < p.ksplit; ++z) v += p.part[i + z * p.n_out];
+    if (p.residual) v += __uint_as_float((unsigned)p.residual[i] << 16);
+    if (p.out_f32) p.out_f32[i] = v;
+    if (p.out_bf16) p.out_bf16[i] = (uint16_t)bf16_bits_rne(v);
+  }
+}
+
+int linear_ksplit(int m, int n, int k) {
+  int s = pick_ksplit(n, k, (m + 31) / 32, 1, device_cu_count());
+  while (s > 1 && (size_t)s * m * n * 4 > ((size_t)64 << 20)) --s;
+  while (s > 1 && (k % (128 * s) != 0 || k / s < 512)) --s;
+  return s;
+}
+
 struct RowPlan {
   int parts, part_len, ksplit;
   size_t x_bytes, ms_off, cv_off, ci_off, mz_off, part_off, total;
@@ -953,6 +984,29 @@ hipError_t launch_moe_experts(const MoeArgs& a, hipStream_t stream) {
   sp.ksplit = mp.split2; sp.split_stride = gp.y_split;
   const unsigned chunks = (unsigned)(a.d_model / 512 < 8 ? (a.d_model / 512 > 0 ? a.d_model / 512 : 1) : 8);
   hipLaunchKernelGGL(select_kernel, dim3(a.rows, chunks), dim3(256), 0, stream, sp);
+  return hipGetLastError();
+}
+
+size_t linear_workspace_bytes(int m, int n, int k) {
+  return ((size_t)linear_ksplit(m, n, k) * m * n * 4 + 255) / 256 * 256;
+}
+
+hipError_t launch_linear(const LinearArgs& a, hipStream_t stream) {
+  const int ks = linear_ksplit(a.m, a.n, a.k);
+  const bool direct = ks == 1 && !a.residual && !a.out_bf16 && a.out_f32;
+  GemmParams gp;
+  gp.x = static_cast<const uint16_t*>(a.x); gp.w = static_cast<const uint16_t*>(a.w);
+  gp.y = direct ? a.out_f32 : static_cast<float*>(a.workspace);
+  gp.m = a.m; gp.n = a.n; gp.k = a.k; gp.ldw = a.k; gp.ldy = a.n;
+  gp.batch = 1; gp.x_batch = gp.w_batch = gp.y_batch = 0; gp.used = nullptr;
+  gp.ksplit = ks; gp.y_split = (long long)a.m * a.n;
+  hipError_t e = launch_gemm(gp, stream);
+  if (e != hipSuccess || direct) return e;
+  LinFinishParams fp;
+  fp.part = gp.y; fp.residual = static_cast<const uint16_t*>(a.residual); fp.out_f32 = a.out_f32;
+  fp.out_bf16 = static_cast<uint16_t*>(a.out_bf16); fp.n_out = (long long)a.m * a.n; fp.ksplit = ks;
+  const unsigned grid = (unsigned)((fp.n_out + 1023) / 1024 < 2048 ? (fp.n_out + 1023) / 1024 : 2048);
+  hipLaunchKernelGGL(linear_finish_kernel, dim3(grid), dim3(256), 0, stream, fp);
   return hipGetLastError();
 }
 

@@ -132,4 +132,15 @@ hipError_t launch_tree_finalize(const TreeFinalArgs& a, hipStream_t stream);
 hipError_t launch_gather_rows(const float* q_all, const int* q_row, float* out, long long n_nodes, int vocab,
                               long long n_q_rows, hipStream_t stream);
 
+// plain linear layer on the skinny GEMM
+struct LinearArgs {
+  int m, n, k;
+  const void *x, *w, *residual;
+  float* out_f32;
+  void* out_bf16;
+  void* workspace;
+};
+size_t linear_workspace_bytes(int m, int n, int k);
+hipError_t launch_linear(const LinearArgs& a, hipStream_t stream);
+
 }  // namespace jk

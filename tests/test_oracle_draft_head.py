@@ -175,3 +175,25 @@ def test_planted_mistakes_are_caught(plant):
         good = dh.dual_head_logits(f_top, s_top, w, dh.DECOUPLED)
         bad = dh.dual_head_logits(f_top, s_top[:, ::-1], w, dh.DECOUPLED)
         assert not np.allclose(good, bad)
+
+
+def test_linear_and_attention_block_against_library_routines():
+    rng = np.random.default_rng(11)
+    x, w, r = rng.normal(size=(5, 16)), rng.normal(size=(7, 16)), rng.normal(size=(5, 7))
+    ref = torch.nn.functional.linear(torch.tensor(x), torch.tensor(w)).numpy() + r
+    np.testing.assert_allclose(dh.linear(x, w, r), ref, rtol=1e-13)
+    # Eq. 1 on a chain of T nodes after L cached rows = causal attention of a decoder layer + residual
+    T, L, H, D = 6, 9, 4, 8
+    d = H * D
+    h = rng.normal(size=(T, d))
+    wq, wk, wv, wo = (rng.normal(size=(d, d)) / np.sqrt(d) for _ in range(4))
+    kc, vc = rng.normal(size=(L, H, D)), rng.normal(size=(L, H, D))
+    u = dh.draft_attention_block(h, wq, wk, wv, wo, kc, vc, np.arange(-1, T - 1), H, H)
+    th = torch.tensor(h)
+    q = torch.nn.functional.linear(th, torch.tensor(wq)).reshape(T, H, D).transpose(0, 1)
+    k = torch.cat([torch.tensor(kc), torch.nn.functional.linear(th, torch.tensor(wk)).reshape(T, H, D)]).transpose(0, 1)
+    v = torch.cat([torch.tensor(vc), torch.nn.functional.linear(th, torch.tensor(wv)).reshape(T, H, D)]).transpose(0, 1)
+    mask = torch.ones(T, L + T, dtype=torch.bool).tril(diagonal=L)
+    att = torch.nn.functional.scaled_dot_product_attention(q, k, v, attn_mask=mask).transpose(0, 1).reshape(T, d)
+    ref = torch.nn.functional.linear(att, torch.tensor(wo)).numpy() + h
+    np.testing.assert_allclose(u, ref, rtol=1e-10, atol=1e-12)
