@@ -93,6 +93,10 @@ struct GemmParams {
   int batch;
   long long x_batch, w_batch, y_batch;
   const int* used;
+  // a second weight tensor over the same X (the experts' gate and up projections in one launch):
+  // blockIdx.y in [batch, 2 batch) takes w2 / y2
+  const uint16_t* w2;
+  float* y2;
   // split of the k range (blockIdx.z): every part writes its own partial output, y_split elements
   // apart; whoever reads y adds them up in a fixed order
   int ksplit;
@@ -171,10 +175,16 @@ __global__ __launch_bounds__(kGemmThreads, 1) void skinny_gemm_kernel(GemmParams
   using C = GemmCfg<MB>;
   constexpr int NBW = C::NBW;
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];  // the kernel's only LDS: offset 0
-  if (p.used && p.used[blockIdx.y] == 0) return;  // (the whole workgroup: nobody waits at a barrier)
-  p.x += (long long)blockIdx.y * p.x_batch;
-  p.w += (long long)blockIdx.y * p.w_batch;
-  p.y += (long long)blockIdx.y * p.y_batch + (long long)blockIdx.z * p.y_split;
+  int e = blockIdx.y;
+  if (e >= p.batch) {
+    e -= p.batch;
+    p.w = p.w2;
+    p.y = p.y2;
+  }
+  if (p.used && p.used[e] == 0) return;  // (the whole workgroup: nobody waits at a barrier)
+  p.x += (long long)e * p.x_batch;
+  p.w += (long long)e * p.w_batch;
+  p.y += (long long)e * p.y_batch + (long long)blockIdx.z * p.y_split;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 31, h = lane >> 5;
   const long long strip0 = (long long)blockIdx.x * C::STRIP;
@@ -303,7 +313,7 @@ hipError_t launch_gemm_mb(const GemmParams& p, hipStream_t stream) {
     lds_limit_raised = true;
   }
   const unsigned grid = (unsigned)((p.n + GemmCfg<MB>::STRIP - 1) / GemmCfg<MB>::STRIP);
-  hipLaunchKernelGGL(skinny_gemm_kernel<MB>, dim3(grid, (unsigned)p.batch, (unsigned)p.ksplit), dim3(kGemmThreads),
+  hipLaunchKernelGGL(skinny_gemm_kernel<MB>, dim3(grid, (unsigned)(p.batch * (p.w2 ? 2 : 1)), (unsigned)p.ksplit), dim3(kGemmThreads),
                      GemmCfg<MB>::SMEM, stream, p);
   return hipGetLastError();
 }
@@ -679,6 +689,7 @@ __global__ __launch_bounds__(256) void router_kernel(RouterParams p) {
   for (int j = wave; j < p.n_experts; j += 4) {
     const u32x4* e = reinterpret_cast<const u32x4*>(p.centroids + (long long)j * p.d);
     float acc = 0.f;
+#pragma unroll 8
     for (int c = lane; c < p.d / 8; c += 64) {
       const u32x4 a = src[c], b = e[c];
 #pragma unroll
@@ -806,7 +817,7 @@ MoePlan moe_plan(int rows, int d, int f, int n) {
   auto up = [](size_t v) { return (v + 255) / 256 * 256; };
   m.rows_pad = (rows + 31) / 32 * 32;
   const int cus = device_cu_count();
-  m.split1 = pick_ksplit(f, d, m.rows_pad / 32, n, cus);
+  m.split1 = pick_ksplit(f, d, m.rows_pad / 32, 2 * n, cus);  // gate and up in one launch
   m.split2 = pick_ksplit(d, f, m.rows_pad / 32, n, cus);
   m.x_off = 0;
   m.used_off = up((size_t)m.rows_pad * d * 2);
@@ -902,7 +913,7 @@ hipError_t launch_draft_heads(const DraftHeadsArgs& a, hipStream_t stream) {
   gp.y = a.logits;
   gp.m = m; gp.n = a.vocab; gp.k = a.d_model;
   gp.ldw = a.d_model; gp.ldy = a.vocab;
-  gp.batch = 1; gp.x_batch = gp.w_batch = gp.y_batch = 0; gp.used = nullptr;
+  gp.batch = 1; gp.x_batch = gp.w_batch = gp.y_batch = 0; gp.used = nullptr; gp.w2 = nullptr; gp.y2 = nullptr;
   gp.ksplit = rp.ksplit; gp.y_split = (long long)m * a.vocab;
   if (rp.ksplit > 1) gp.y = reinterpret_cast<float*>(ws + rp.part_off);
   e = launch_gemm(gp, stream);
@@ -958,9 +969,9 @@ hipError_t launch_moe_experts(const MoeArgs& a, hipStream_t stream) {
   gp.y_batch = (long long)a.rows * a.d_ff; gp.used = used;
   gp.ksplit = mp.split1; gp.y_split = (long long)a.n_experts * a.rows * a.d_ff;
   gp.w = static_cast<const uint16_t*>(a.w_gate); gp.y = reinterpret_cast<float*>(ws + mp.g_off);
-  if ((e = launch_gemm(gp, stream)) != hipSuccess) return e;
-  gp.w = static_cast<const uint16_t*>(a.w_up); gp.y = reinterpret_cast<float*>(ws + mp.up_off);
-  if ((e = launch_gemm(gp, stream)) != hipSuccess) return e;
+  gp.w2 = static_cast<const uint16_t*>(a.w_up); gp.y2 = reinterpret_cast<float*>(ws + mp.up_off);
+  if ((e = launch_gemm(gp, stream)) != hipSuccess) return e;  // gate and up projections of all experts
+  gp.w2 = nullptr; gp.y2 = nullptr;
 
   ActParams ap;
   ap.g = reinterpret_cast<const float*>(ws + mp.g_off); ap.up = reinterpret_cast<const float*>(ws + mp.up_off);
@@ -998,7 +1009,7 @@ hipError_t launch_linear(const LinearArgs& a, hipStream_t stream) {
   gp.x = static_cast<const uint16_t*>(a.x); gp.w = static_cast<const uint16_t*>(a.w);
   gp.y = direct ? a.out_f32 : static_cast<float*>(a.workspace);
   gp.m = a.m; gp.n = a.n; gp.k = a.k; gp.ldw = a.k; gp.ldy = a.n;
-  gp.batch = 1; gp.x_batch = gp.w_batch = gp.y_batch = 0; gp.used = nullptr;
+  gp.batch = 1; gp.x_batch = gp.w_batch = gp.y_batch = 0; gp.used = nullptr; gp.w2 = nullptr; gp.y2 = nullptr;
   gp.ksplit = ks; gp.y_split = (long long)a.m * a.n;
   hipError_t e = launch_gemm(gp, stream);
   if (e != hipSuccess || direct) return e;

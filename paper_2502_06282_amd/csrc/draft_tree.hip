@@ -33,7 +33,7 @@ __global__ __launch_bounds__(kTreeThreads) void grow_kernel(TreeGrowArgs a) {
   __shared__ int s_first;
   const int b = blockIdx.x, t = threadIdx.x;
   const int C = a.n_front * 2 * a.top_k;
-  const int n0 = a.n_nodes[b];
+  const int n0 = min(max(a.n_nodes[b], 0), a.max_nodes);  // (a count the caller forgot to clear must not fault)
   const int id = n0 + t;
   const bool valid = t < C && id < a.max_nodes;
   float sc = -INFINITY;
@@ -84,7 +84,7 @@ __global__ __launch_bounds__(kTreeThreads) void grow_tail_kernel(TreeGrowArgs a,
   __shared__ int s_slot_f[kTreeThreads];
   const int b = blockIdx.x, t = threadIdx.x;
   const int C = a.n_front * k1;
-  const int n0 = a.n_nodes[b];
+  const int n0 = min(max(a.n_nodes[b], 0), a.max_nodes);
   const int id = n0 + t;
   const bool valid = t < C && id < a.max_nodes;
   const long long base = (long long)b * a.max_nodes;
@@ -140,7 +140,7 @@ __global__ __launch_bounds__(kTreeThreads) void finalize_kernel(TreeFinalArgs a)
   __shared__ short s_keep[kMaxGrowNodes];
   __shared__ short s_new[kMaxGrowNodes];
   const int b = blockIdx.x, t = threadIdx.x;
-  const int n = min(a.n_nodes[b], a.max_nodes);
+  const int n = min(max(a.n_nodes[b], 0), a.max_nodes);
   const long long base = (long long)b * a.max_nodes;
   for (int i = t; i < kMaxGrowNodes; i += kTreeThreads) s_sc[i] = i < n ? a.score[base + i] : -INFINITY;
   __syncthreads();
