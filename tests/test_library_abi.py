@@ -68,3 +68,30 @@ def test_null_arguments_are_rejected_before_any_launch(lib):
     assert st == 1
     st = lib.jk_accept_path(1, 4, 100, 4, None, None, None, 0, 1.0, None, None, None, None, None, None, 0, None)
     assert st == 1
+
+
+def test_draft_layer_workspace_queries_and_argument_checks_are_host_only(lib):
+    n = lib.jk_draft_heads_workspace(80, 4096, 128256)
+    assert n > 0 and n % 256 == 0
+    assert lib.jk_draft_heads_workspace(10, 4096, 128256) < n
+    assert lib.jk_draft_heads_workspace(129, 4096, 128256) == 0      # too many rows
+    assert lib.jk_draft_heads_workspace(10, 4000, 128256) == 0       # width not a multiple of 128
+    assert lib.jk_draft_heads_workspace(10, 4096, 0) == 0
+    d = binding.MoeDesc(10, 4096, 4096, 8)
+    m = lib.jk_moe_experts_workspace(ctypes.byref(d))
+    assert m > 0 and m % 256 == 0
+    assert lib.jk_moe_experts_workspace(ctypes.byref(binding.MoeDesc(10, 4096, 4096, 1))) == 0   # no top-2 of one
+    assert lib.jk_moe_experts_workspace(ctypes.byref(binding.MoeDesc(10, 4096, 1000, 8))) == 0
+    assert lib.jk_moe_experts_workspace(None) == 0
+    assert lib.jk_linear_workspace(10, 4096, 4096) > 0
+    assert lib.jk_linear_workspace(300, 4096, 4096) == 0 and lib.jk_linear_workspace(10, 4096, 100) == 0
+    # null pointers and bad shapes are rejected before any launch
+    hd = binding.DraftHeadsDesc(10, 4096, 1000, 5, 0, 1.0, 0.0, 0.0)
+    assert lib.jk_draft_heads(ctypes.byref(hd), None, None, None, None, None, None, None, None, 0, None) == 1
+    assert lib.jk_moe_experts(ctypes.byref(d), None, None, None, None, None, None, None, None, None, None, 0, None) == 1
+    assert lib.jk_linear(4, 8, 256, None, None, None, None, None, None, 0, None) == 1
+    st = binding.TreeStateDesc(None, None, None, None, None, 64)
+    assert lib.jk_tree_grow(ctypes.byref(st), 1, 1, 4, 4, 0, None, None, None, None, None) == 1
+    assert lib.jk_tree_grow_tail(ctypes.byref(st), 1, 1, 4, 2, 2, 4, 0, None, None, None, None) == 1
+    assert lib.jk_tree_finalize(ctypes.byref(st), 1, 8, None, None, None, None, None, None) == 1
+    assert lib.jk_gather_draft_probs(1, 4, 100, None, 10, None, None, None) == 1
