@@ -17,6 +17,7 @@
 //                          surrounds the experts' three projections (Eq. 3).
 #include <climits>
 
+#include "jk_device.h"
 #include "jk_internal.h"
 
 namespace jk {
@@ -106,28 +107,9 @@ struct GemmParams {
 typedef __attribute__((address_space(3))) const bf16x8 lds_bf16x8_t;
 __device__ __forceinline__ bf16x8 lds_read16(unsigned addr) { return *(lds_bf16x8_t*)(size_t)addr; }
 
-// 16 bytes per lane from global memory straight into LDS (global_load_lds_dwordx4): lane l lands
-// at lds_base + 16 l and fetches base + voff (wave-uniform base in scalar registers, the lane's
-// 32-bit byte offset).  Inline assembly, so that the compiler's own bookkeeping does not make
-// every LDS read wait for all transfers in flight; the kernel counts them itself (wait_vm).
-__device__ __forceinline__ void dma16(const uint16_t* base, unsigned voff, unsigned lds_base) {
-  const unsigned m = __builtin_amdgcn_readfirstlane(lds_base);
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(m), "v"(voff), "s"(base)
-               : "memory", "m0");
-}
-__device__ __forceinline__ const uint16_t* uniform_ptr(const uint16_t* p) {
-  const unsigned long long v = reinterpret_cast<unsigned long long>(p);
-  const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v);
-  const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
-  return reinterpret_cast<const uint16_t*>(((unsigned long long)hi << 32) | lo);
-}
-// wait until at most N of this wave's transfers are outstanding (they complete in issue order)
-template <int N>
-__device__ __forceinline__ void wait_vm() {
-  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit field");
-  __builtin_amdgcn_s_waitcnt(((N & 0xF) | ((N >> 4) << 14)) | 0x0F70);
-  asm volatile("" ::: "memory");
-}
+using dev::dma16;
+using dev::uniform_ptr;
+using dev::wait_vm;
 
 // Plan of one workgroup (one per CU, 8 waves).  Every wave owns NBW 32-row blocks of the weight
 // strip and all MB 32-row blocks of X: NBW * MB accumulator tiles of 16 registers.  LDS holds a

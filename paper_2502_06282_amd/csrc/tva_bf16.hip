@@ -31,6 +31,7 @@
 // each lane fetches the 16-byte chunk that the XOR swizzle maps to its LDS
 // slot, so that both the 128-bit K reads and the transpose V reads are free of
 // bank conflicts.
+#include "jk_device.h"
 #include "jk_internal.h"
 
 namespace jk {
@@ -123,33 +124,14 @@ struct Geo {
   }
 };
 
-// 16 bytes per lane straight from global memory into LDS (global_load_lds_dwordx4): lane l
-// of the wave lands at lds_base + 16*l and fetches base + voff (a wave-uniform 64-bit base
-// in scalar registers plus the lane's unsigned 32-bit byte offset).  Written as inline
-// assembly so that the compiler does not know about the transfer: its own bookkeeping
-// would make every later LDS read wait for ALL outstanding transfers, which would
-// serialise the multi-stage ring.  The kernel orders transfers and reads itself
-// (wait_dma + __syncthreads).
-__device__ __forceinline__ void dma16(const uint16_t* base, unsigned voff, unsigned lds_base) {
-  const unsigned m = __builtin_amdgcn_readfirstlane(lds_base);  // wave-uniform by construction
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(m), "v"(voff), "s"(base)
-               : "memory", "m0");
-}
-
-// A wave-uniform pointer, made so for the compiler (scalar registers)
-__device__ __forceinline__ const uint16_t* uniform_ptr(const uint16_t* p) {
-  const unsigned long long v = reinterpret_cast<unsigned long long>(p);
-  const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v);
-  const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
-  return reinterpret_cast<const uint16_t*>(((unsigned long long)hi << 32) | lo);
-}
+using dev::dma16;
+using dev::uniform_ptr;
 
 // Wait until at most `rounds_behind` rounds of this wave's transfers are still in flight
 // (they complete in issue order).  The count must be an immediate, hence the switch.
 template <int STEP>
 __device__ __forceinline__ void wait_dma(int rounds_behind) {
-  // s_waitcnt immediate on gfx9: vmcnt in bits [3:0] and [15:14]; expcnt/lgkmcnt left at their maxima
-#define JK_VM(n) __builtin_amdgcn_s_waitcnt((((n) & 0xF) | (((n) >> 4) << 14)) | 0x0F70)
+#define JK_VM(n) __builtin_amdgcn_s_waitcnt(dev::vmcnt_imm(n))
   switch (rounds_behind) {
     case 0: JK_VM(0); break;
     case 1: JK_VM(STEP); break;
