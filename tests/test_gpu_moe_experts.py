@@ -165,3 +165,45 @@ def test_argument_errors():
         jk.prepare_moe_experts(*a, f_top, s_top, idx, None, small).launch()
     assert e.value.status == 4
     torch.cuda.synchronize()
+
+
+def test_draft_step_captured_in_a_hip_graph_replays_bit_for_bit():
+    """Experts -> heads as prepared calls sharing their workspaces, captured in a HIP graph and replayed with
+    eager work between the replays: every replay reproduces the eager results bit for bit (stale workspace
+    contents must not matter: the expert flags, partial sums and candidate lists are rewritten by every call)."""
+    R, d, F, N, V, k = 24, 512, 1024, 4, 9000, 8
+    x = moe_inputs(R, d, F, N, seed=8)
+    w_head = _dev(draft_head_inputs(1, d, V, seed=8)["w_head"])
+    a = [_dev(x[key]) for key in ("u", "centroids", "w_gate", "w_up", "w_down")]
+    dev = "cuda"
+    f_top = torch.empty((R, 2, d), dtype=torch.bfloat16, device=dev)
+    s_top = torch.empty((R, 2), device=dev)
+    idx = torch.empty((R, 2), dtype=torch.int32, device=dev)
+    lg = torch.empty((R, 2, V), device=dev)
+    q = torch.empty((R, 2, V), device=dev)
+    tk = torch.empty((R, 2, k), dtype=torch.int32, device=dev)
+    tp = torch.empty((R, 2, k), device=dev)
+    ws1 = torch.empty(jk.moe_experts_workspace(R, d, F, N), dtype=torch.uint8, device=dev)
+    ws2 = torch.empty(jk.draft_heads_workspace(R, d, V), dtype=torch.uint8, device=dev)
+    c1 = jk.prepare_moe_experts(*a, f_top, s_top, idx, None, ws1)
+    c2 = jk.prepare_draft_heads(f_top, s_top, w_head, jk.JK_HEADS_CONTRASTIVE, 0.8, k, 0.3, 1.1, lg, q, tk, tp, ws2)
+    c1.launch()
+    c2.launch()
+    torch.cuda.synchronize()
+    outs = (f_top, s_top, idx, lg, q, tk, tp)
+    eager = [o.clone() for o in outs]
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=torch.cuda.Stream()):
+        c1.launch()
+        c2.launch()
+    for rep in range(3):
+        for o in outs:
+            o.zero_()
+        ws1.random_(0, 255)
+        ws2.random_(0, 255)
+        junk = torch.randn(1 << 20, device=dev).sum()
+        g.replay()
+        torch.cuda.synchronize()
+        for o, e in zip(outs, eager):
+            assert torch.equal(o, e), f"replay {rep} differs from the eager result"
+        assert torch.isfinite(junk)
