@@ -194,3 +194,21 @@ def test_parallel_tail_matches_the_oracle(B, k, k1, k2, width, max_nodes):
         nv = len(ro)
         assert int(n_valid[b]) == nv and parent[b, :nv].cpu().tolist() == rp.tolist()
         assert tokens[b, :nv].cpu().tolist() == rt.tolist() and q_row[b, :nv].cpu().tolist() == rq.tolist()
+
+
+def test_example_round_runs_and_is_consistent():
+    """The example that strings all calls of a round together (draft passes, tree, verification, acceptance,
+    commit): the tree it builds is valid, the accepted path follows tree edges, lengths advance by accept_len."""
+    from paper_2502_06282_amd import example_round
+    r = example_round.run(batch=2, seed=1, verbose=False)
+    par = r["parent"].cpu().numpy()
+    path, alen = r["path"].cpu().numpy(), r["accept_len"].cpu().numpy()
+    for b in range(2):
+        assert jk.validate_tree(par[b]) == 0
+        prev = -1
+        for i in range(int(alen[b])):
+            assert par[b, path[b, i]] == prev
+            prev = path[b, i]
+        assert int(r["prefix_len"][b]) == 256 + int(alen[b])
+        assert 0 <= int(r["bonus"][b]) < 8000
+    assert all(torch.isfinite(o.float()).all() for o in r["outs"])
