@@ -62,13 +62,13 @@ def _exact_inputs(rows, d, vocab, seed):
 
 
 @pytest.mark.parametrize("rows,d,vocab", [(3, 256, 1000), (16, 128, 130), (17, 384, 4099), (128, 256, 513),
-                                            (5, 1024, 3000), (40, 2048, 700)])   # the last two split k
+                                            (5, 1024, 3000), (40, 2048, 700), (90, 256, 600)])   # two of them split k
 def test_exact_arithmetic_inputs_are_bit_exact(rows, d, vocab):
     _check(_exact_inputs(rows, d, vocab, rows), exact=True)
     _check(_exact_inputs(rows, d, vocab, rows + 1), mode=jk.JK_HEADS_CONTRASTIVE, alpha=0.5, beta=2.0, exact=True)
 
 
-@pytest.mark.parametrize("rows", [1, 5, 16, 33, 40, 64, 80, 100, 128])
+@pytest.mark.parametrize("rows", [1, 5, 16, 33, 40, 64, 80, 90, 100, 128])   # 1..8 row blocks of 32
 def test_random_inputs_every_row_block_count(rows):
     _check(draft_head_inputs(rows, 512, 4096 + 37 * (rows % 4), seed=rows), top_k=10)
 
