@@ -664,6 +664,20 @@ __global__ __launch_bounds__((Plan<D, WM, WN, KT, PAGED>::THREADS), (Plan<D, WM,
     re = re < R ? re : R;
     ts.t_begin = rb * TPR < nt ? rb * TPR : nt;
     ts.t_end = re * TPR < nt ? re * TPR : nt;
+    if (KT == 2 && WN == 1) {
+      // One wave column taking tile pairs: a lone full tile costs about half a round (see the
+      // loop), so the same sharing is done in tiles; an odd share ends with such a tile.
+      const int slow_t = nt - len / kTileKeys;
+      const int share_t = div_mg(nt, p.mg_splits);
+      const int extra_t = slow_t < share_t / 2 ? slow_t : share_t / 2;
+      const int ntv = nt + extra_t;
+      const int base_t = div_mg(ntv, p.mg_splits);
+      const int rem_t = ntv - base_t * splits;
+      int tb = split * base_t + (split < rem_t ? split : rem_t);
+      int te = tb + base_t + (split < rem_t ? 1 : 0);
+      ts.t_begin = tb < nt ? tb : nt;
+      ts.t_end = te < nt ? te : nt;
+    }
   };
   const unsigned ring_addr = (unsigned)(size_t)LDS_PTR(unsigned char, ring);  // a multiple of 1024
   const unsigned k_lane = G_::k_lane(lane), v_lane = G_::v_lane(lane);
@@ -789,6 +803,10 @@ __global__ __launch_bounds__((Plan<D, WM, WN, KT, PAGED>::THREADS), (Plan<D, WM,
     const unsigned tile_a = ring_addr + (r % NR) * STAGE_BYTES + wn * KT * 2 * TILE_BYTES;  // K of the first tile
     if (KT == 2 && (tb + 2) * kTileKeys <= L && tb + 2 <= ts.t_end) {
       PairPipe<D>::run(st, tile_a + k_lane, tile_a + TILE_BYTES + v_lane, scale_log2);  // two full prefix tiles
+    } else if (KT == 2 && WN == 1 && tb + 1 == ts.t_end && (tb + 1) * kTileKeys <= L) {
+      floatx16 s0, s1;  // a lone full prefix tile at the end of the split: no mask, half the work
+      qk_tiles<D, 1>(st, tile_a + k_lane, s0, s1);
+      softmax_pv<D, 1>(st, s0, s1, tile_a + TILE_BYTES + v_lane, scale_log2);
     } else if (tb < ts.t_end) {
       int mode, nvalid;
       unsigned int bits;
