@@ -2,7 +2,7 @@
  * libjakiro_verify -- tree verification for Jakiro-style speculative decoding
  * on AMD MI355X (gfx950).  C ABI: plain pointers and sizes only.
  *
- * The two calls follow the verification and refinement steps of speculative
+ * The two central calls follow the verification and refinement steps of speculative
  * decoding as the paper states them (Section 2.1, steps 2 and 3), applied to
  * the draft token TREE that Jakiro's two experts build (Section 3.1.2: at
  * every depth each activated expert proposes its own top-k candidates, the
@@ -19,6 +19,12 @@
  *       probability min(1, p/q); on rejection continue with
  *       norm(max(0, p - q)), Section 2.1), returning the accepted
  *       root-to-leaf path and the extra ("bonus") token.
+ *
+ * Around them: jk_commit_path* (the accepted path's K/V rows join the cache),
+ * the paged-cache variants, and the draft side of a round (Section 3.1.2, 3.2):
+ * jk_linear, jk_moe_experts, jk_draft_heads, jk_tree_grow / _tail / _finalize and
+ * jk_gather_draft_probs produce the tree_tokens, parent[] and draft_probs that
+ * the two central calls take.
  *
  * Conventions
  *   - "device" pointers are HIP device memory of the current device; "host"
