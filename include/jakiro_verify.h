@@ -196,6 +196,20 @@ jk_status jk_accept_path(int32_t batch, int32_t n_tree, int32_t vocab, int32_t m
                          int32_t* out_accept_len, int32_t* out_bonus_token, void* workspace,
                          size_t workspace_bytes, void* hip_stream);
 
+/* jk_accept_path with the draft distributions addressed through a row table instead of a
+ * dense [batch][n_tree][vocab] array: node k of sequence b is tested against
+ * draft_rows_all[draft_row[b][k]][:] (fp32 [n_draft_rows][vocab]; a row number outside the
+ * table is clamped).  This is what jk_tree_finalize's q_row output and the draft_probs
+ * buffers of the round's jk_draft_heads calls are, so the draft side's output can be
+ * verified without copying 4 * vocab bytes per node (jk_gather_draft_probs).  Everything
+ * else as for jk_accept_path; draft_row is device int32 [batch][n_tree] (JK_SAMPLE only). */
+jk_status jk_accept_path_rows(int32_t batch, int32_t n_tree, int32_t vocab, int32_t max_depth,
+                              const int32_t* tree_tokens, const int32_t* parent, const float* target_logits,
+                              int32_t mode, float temperature, const float* draft_rows_all, int64_t n_draft_rows,
+                              const int32_t* draft_row, const float* uniforms, int32_t* out_path,
+                              int32_t* out_accept_len, int32_t* out_bonus_token, void* workspace,
+                              size_t workspace_bytes, void* hip_stream);
+
 /* Commit of the accepted path to one layer's KV cache (Section 2.1 step 3:
  * accepted tokens are appended to the sequence, the rest of the draft is
  * dropped).  For every sequence b and i < n_b the K and V rows (all KV heads) of

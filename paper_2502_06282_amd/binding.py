@@ -66,7 +66,7 @@ class PagedKV(ctypes.Structure):
 
 EXPORTS = ("jk_tree_verify_attention_workspace", "jk_tree_verify_attention", "jk_tree_verify_attention_paged",
            "jk_commit_path_layers_paged", "jk_accept_path_workspace",
-           "jk_accept_path", "jk_draft_heads_workspace", "jk_draft_heads", "jk_moe_experts_workspace", "jk_moe_experts", "jk_linear_workspace", "jk_linear", "jk_tree_grow", "jk_tree_grow_tail", "jk_tree_finalize", "jk_gather_draft_probs", "jk_commit_path", "jk_commit_path_layers", "jk_workspace_init", "jk_stream_read_probe", "jk_validate_tree", "jk_status_string", "jk_version")
+           "jk_accept_path", "jk_accept_path_rows", "jk_draft_heads_workspace", "jk_draft_heads", "jk_moe_experts_workspace", "jk_moe_experts", "jk_linear_workspace", "jk_linear", "jk_tree_grow", "jk_tree_grow_tail", "jk_tree_finalize", "jk_gather_draft_probs", "jk_commit_path", "jk_commit_path_layers", "jk_workspace_init", "jk_stream_read_probe", "jk_validate_tree", "jk_status_string", "jk_version")
 
 
 def library_path() -> str:
@@ -98,6 +98,9 @@ def lib() -> ctypes.CDLL:
         l.jk_accept_path.restype = i32
         l.jk_accept_path.argtypes = [i32, i32, i32, i32, vp, vp, vp, i32, ctypes.c_float, vp, vp, vp, vp,
                                      vp, vp, sz, vp]
+        l.jk_accept_path_rows.restype = i32
+        l.jk_accept_path_rows.argtypes = [i32, i32, i32, i32, vp, vp, vp, i32, ctypes.c_float, vp, ctypes.c_int64, vp,
+                                          vp, vp, vp, vp, vp, sz, vp]
         l.jk_commit_path.restype = i32
         l.jk_commit_path.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp, i32, i32, vp, i32, vp]
         l.jk_commit_path_layers.restype = i32
@@ -660,3 +663,36 @@ def linear(x, w, residual=None, out_dtype=None, stream=None):
     if st != 0:
         raise JakiroError(st, "jk_linear")
     return out
+
+
+def accept_path_rows(tree_tokens, parent, target_logits, q_all, q_row, uniforms, temperature: float = 1.0,
+                     max_depth: Optional[int] = None, workspace=None, stream=None):
+    """jk_accept_path_rows (speculative sampling): like accept_path, with node k of sequence b tested against
+    q_all[q_row[b, k]] (q_all fp32 [n_rows, V] contiguous, q_row int32 [B, N]) instead of a dense draft_probs."""
+    import torch
+    B, N = tree_tokens.shape
+    V = target_logits.shape[-1]
+    if max_depth is None:
+        max_depth = N
+    for t in (tree_tokens, parent, q_row):
+        if t.dtype != torch.int32 or not t.is_contiguous():
+            raise TypeError("tree_tokens, parent and q_row must be contiguous int32")
+    for t in (target_logits, q_all, uniforms):
+        if t.dtype != torch.float32 or not t.is_contiguous():
+            raise TypeError("logits, q_all and uniforms must be contiguous float32")
+    if q_all.shape[-1] != V or tuple(q_row.shape) != (B, N):
+        raise ValueError("q_all [n_rows, V], q_row [B, N]")
+    dev = tree_tokens.device
+    path = torch.empty((B, max_depth), dtype=torch.int32, device=dev)
+    alen = torch.empty((B,), dtype=torch.int32, device=dev)
+    bonus = torch.empty((B,), dtype=torch.int32, device=dev)
+    need = accept_path_workspace(B, N, V, JK_SAMPLE)
+    if workspace is None:
+        workspace = torch.zeros(need, dtype=torch.uint8, device=dev)
+    st = lib().jk_accept_path_rows(B, N, V, int(max_depth), _ptr(tree_tokens), _ptr(parent), _ptr(target_logits),
+                                   JK_SAMPLE, float(temperature), _ptr(q_all), q_all.numel() // V, _ptr(q_row),
+                                   _ptr(uniforms), _ptr(path), _ptr(alen), _ptr(bonus), _ptr(workspace),
+                                   workspace.numel() * workspace.element_size(), _stream_handle(stream))
+    if st != 0:
+        raise JakiroError(st, "jk_accept_path_rows")
+    return path, alen, bonus

@@ -173,6 +173,8 @@ struct WalkParams {
   double temp;
   const int *tokens, *parent;
   const float *logits, *draft, *uniforms;
+  const int* draft_row;  // or null: row b*n_tree + k
+  long long n_draft_rows;
   const float* pmax;
   const double* psum;
   double* resid;  // [batch][2][vocab] unnormalised residuals (ping-pong)
@@ -233,7 +235,12 @@ __global__ __launch_bounds__(kWalkThreads) void walk_sample_kernel(WalkParams p)
       if (par_s[j] == c) { child = j; break; }
     if (child < 0) break;
     const int x = min(max(tok[child], 0), V - 1);  // a token id outside the vocabulary must not fault
-    const float* qk = p.draft + ((long long)b * N + child) * V;
+    long long qr = (long long)b * N + child;
+    if (p.draft_row) {
+      qr = p.draft_row[qr];
+      qr = qr < 0 ? 0 : (qr >= p.n_draft_rows ? p.n_draft_rows - 1 : qr);
+    }
+    const float* qk = p.draft + qr * V;
     const double lhs = (double)uni[child] * (double)qk[x];
     const double rhs = prob(x);
     if (lhs < rhs) {
@@ -370,6 +377,7 @@ hipError_t launch_accept(const AcceptArgs& a, hipStream_t stream) {
   wp.temp = temp;
   wp.tokens = a.tokens; wp.parent = a.parent;
   wp.logits = a.logits; wp.draft = a.draft_probs; wp.uniforms = a.uniforms;
+  wp.draft_row = a.draft_row; wp.n_draft_rows = a.n_draft_rows;
   wp.pmax = pmax; wp.psum = psum; wp.resid = resid;
   wp.out_path = a.out_path; wp.out_len = a.out_len; wp.out_bonus = a.out_bonus;
   hipLaunchKernelGGL(walk_sample_kernel, dim3(a.batch), dim3(kWalkThreads), 0, stream, wp);

@@ -39,6 +39,8 @@ struct CoopParams {
   double inv_temp;  // 1 / temperature
   const int *tokens, *parent;
   const float *logits, *draft, *uniforms;
+  const int* draft_row;  // or null: row b*n_tree + k of draft
+  long long n_draft_rows;
   unsigned long long* epoch;  // [batch] workspace words, each bumped once per call by its tree
   Slot* slots;                // [batch][2][W]
   int *out_path, *out_len, *out_bonus;
@@ -94,6 +96,16 @@ __global__ __launch_bounds__(kCoopThreads) void walk_sample_coop_kernel(CoopPara
   if (tid == 0) s_fail = 0;
   const unsigned long long epoch = __hip_atomic_load(p.epoch + b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   __syncthreads();
+
+  // the draft distribution of node k (a row of p.draft)
+  auto q_of = [&](int k) -> const float* {
+    long long r = (long long)b * N + k;
+    if (p.draft_row) {
+      r = p.draft_row[r];
+      r = r < 0 ? 0 : (r >= p.n_draft_rows ? p.n_draft_rows - 1 : r);  // a bad row number must not fault
+    }
+    return p.draft + r * V;
+  };
 
   // smallest j >= from with parent c, or -1: every wave looks at all (at most 128) nodes, two
   // per lane, so no barrier is needed and all waves get the same answer
@@ -216,9 +228,9 @@ __global__ __launch_bounds__(kCoopThreads) void walk_sample_coop_kernel(CoopPara
     float v = 0.f;
     if (tid < n_list) {
       const int kq = tid < n_rej ? rej_k[tid] : extra;
-      v = p.draft[((long long)b * N + kq) * V + x];
+      v = q_of(kq)[x];
     } else if (tid == n_list) {
-      v = p.draft[((long long)b * N + child) * V + x];
+      v = q_of(child)[x];
     } else if (tid == n_list + 1) {
       v = row[x];
     }
@@ -240,7 +252,7 @@ __global__ __launch_bounds__(kCoopThreads) void walk_sample_coop_kernel(CoopPara
   bool have_pf = false;     // pf_q[] and qreg[] already hold `child`'s data
   float qreg[kPer];         // q_child over my slice
   while (!s_fail && child >= 0) {
-    const float* qk = p.draft + ((long long)b * N + child) * V;
+    const float* qk = q_of(child);
     if (!have_pf) {
       const float v = gather_issue(child, n_rej, -1);
 #pragma unroll
@@ -283,7 +295,7 @@ __global__ __launch_bounds__(kCoopThreads) void walk_sample_coop_kernel(CoopPara
     float qnext[kPer];
     if (nxt_child >= 0) {
       pv = gather_issue(nxt_child, n_rej, child);
-      const float* qn = p.draft + ((long long)b * N + nxt_child) * V;
+      const float* qn = q_of(nxt_child);
 #pragma unroll
       for (int u = 0; u < kPer; ++u) {
         const int i = tid + u * kCoopThreads;
@@ -427,6 +439,7 @@ hipError_t launch_accept_coop(const AcceptArgs& a, void* coop_ws, int W, int sli
   cp.inv_temp = 1.0 / (double)a.temperature;
   cp.tokens = a.tokens; cp.parent = a.parent;
   cp.logits = a.logits; cp.draft = a.draft_probs; cp.uniforms = a.uniforms;
+  cp.draft_row = a.draft_row; cp.n_draft_rows = a.n_draft_rows;
   cp.epoch = static_cast<unsigned long long*>(coop_ws);
   cp.slots = reinterpret_cast<Slot*>(static_cast<char*>(coop_ws) + coop_header_bytes(a.batch));
   cp.out_path = a.out_path; cp.out_len = a.out_len; cp.out_bonus = a.out_bonus;

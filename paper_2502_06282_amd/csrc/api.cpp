@@ -228,11 +228,12 @@ size_t jk_accept_path_workspace(int32_t batch, int32_t n_tree, int32_t vocab, in
   return accept_workspace_bytes(batch, n_tree, vocab, mode);
 }
 
-jk_status jk_accept_path(int32_t batch, int32_t n_tree, int32_t vocab, int32_t max_depth,
-                         const int32_t* tree_tokens, const int32_t* parent, const float* target_logits,
-                         int32_t mode, float temperature, const float* draft_probs, const float* uniforms,
-                         int32_t* out_path, int32_t* out_accept_len, int32_t* out_bonus_token, void* workspace,
-                         size_t workspace_bytes, void* hip_stream) {
+static jk_status accept_common(int32_t batch, int32_t n_tree, int32_t vocab, int32_t max_depth,
+                               const int32_t* tree_tokens, const int32_t* parent, const float* target_logits,
+                               int32_t mode, float temperature, const float* draft_probs, const int32_t* draft_row,
+                               int64_t n_draft_rows, const float* uniforms, int32_t* out_path,
+                               int32_t* out_accept_len, int32_t* out_bonus_token, void* workspace,
+                               size_t workspace_bytes, void* hip_stream) {
   if (batch < 1 || vocab < 1 || max_depth < 1) return JK_ERR_INVALID_ARG;
   if (n_tree < 1) return JK_ERR_INVALID_ARG;
   if (n_tree > JK_MAX_TREE) return JK_ERR_UNSUPPORTED;
@@ -244,6 +245,7 @@ jk_status jk_accept_path(int32_t batch, int32_t n_tree, int32_t vocab, int32_t m
   if (mode == JK_SAMPLE) {
     if (!draft_probs || !uniforms) return JK_ERR_INVALID_ARG;
     if (!(temperature > 0.f) || !std::isfinite(temperature)) return JK_ERR_INVALID_ARG;
+    if (draft_row && n_draft_rows < 1) return JK_ERR_INVALID_ARG;
   }
   const size_t need = accept_workspace_bytes(batch, n_tree, vocab, mode);
   if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256) return JK_ERR_WORKSPACE;
@@ -253,9 +255,32 @@ jk_status jk_accept_path(int32_t batch, int32_t n_tree, int32_t vocab, int32_t m
   a.temperature = temperature;
   a.tokens = tree_tokens; a.parent = parent; a.logits = target_logits;
   a.draft_probs = draft_probs; a.uniforms = uniforms;
+  a.draft_row = draft_row; a.n_draft_rows = n_draft_rows;
   a.out_path = out_path; a.out_len = out_accept_len; a.out_bonus = out_bonus_token;
   a.workspace = workspace;
   return launch_accept(a, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? JK_OK : JK_ERR_HIP;
+}
+
+jk_status jk_accept_path(int32_t batch, int32_t n_tree, int32_t vocab, int32_t max_depth,
+                         const int32_t* tree_tokens, const int32_t* parent, const float* target_logits,
+                         int32_t mode, float temperature, const float* draft_probs, const float* uniforms,
+                         int32_t* out_path, int32_t* out_accept_len, int32_t* out_bonus_token, void* workspace,
+                         size_t workspace_bytes, void* hip_stream) {
+  return accept_common(batch, n_tree, vocab, max_depth, tree_tokens, parent, target_logits, mode, temperature,
+                       draft_probs, nullptr, 0, uniforms, out_path, out_accept_len, out_bonus_token, workspace,
+                       workspace_bytes, hip_stream);
+}
+
+jk_status jk_accept_path_rows(int32_t batch, int32_t n_tree, int32_t vocab, int32_t max_depth,
+                              const int32_t* tree_tokens, const int32_t* parent, const float* target_logits,
+                              int32_t mode, float temperature, const float* draft_rows_all, int64_t n_draft_rows,
+                              const int32_t* draft_row, const float* uniforms, int32_t* out_path,
+                              int32_t* out_accept_len, int32_t* out_bonus_token, void* workspace,
+                              size_t workspace_bytes, void* hip_stream) {
+  if (mode == JK_SAMPLE && !draft_row) return JK_ERR_INVALID_ARG;
+  return accept_common(batch, n_tree, vocab, max_depth, tree_tokens, parent, target_logits, mode, temperature,
+                       draft_rows_all, draft_row, n_draft_rows, uniforms, out_path, out_accept_len, out_bonus_token,
+                       workspace, workspace_bytes, hip_stream);
 }
 
 static jk_status commit_common(const jk_attn_desc* desc, const jk_paged_kv* pages, int n_layers, const void* k_tree, const void* v_tree,

@@ -57,6 +57,10 @@ struct AcceptArgs {
   const float *logits, *draft_probs, *uniforms;
   int32_t *out_path, *out_len, *out_bonus;
   void* workspace;
+  // optional indirection: node k of sequence b uses row draft_row[b*n_tree + k] (clamped into
+  // [0, n_draft_rows)) of draft_probs instead of row b*n_tree + k
+  const int32_t* draft_row;
+  long long n_draft_rows;
 };
 size_t accept_workspace_bytes(int batch, int n_tree, int vocab, int mode);
 hipError_t launch_accept(const AcceptArgs& a, hipStream_t stream);

@@ -5,10 +5,11 @@ which order.  Run on an MI355X:  python -m paper_2502_06282_amd.example_round
   draft, per depth      jk_linear (reduction layer and q/k/v/o projections of Eq. 1) + jk_tree_verify_attention over
                         the draft layer's own cache -> jk_moe_experts (Eq. 2, 3, 5) -> jk_draft_heads (Eq. 4) ->
                         jk_tree_grow
-  after the last depth  jk_tree_finalize, jk_gather_draft_probs
+  after the last depth  jk_tree_finalize
   verify                jk_tree_verify_attention per target layer (the target's projections and MLPs are not
                         part of this library: q/k/v and the logits are random here)
-  refine                jk_accept_path (speculative sampling), jk_commit_path_layers
+  refine                jk_accept_path_rows (speculative sampling against the draft passes' distributions, addressed
+                        through the tree's row table), jk_commit_path
 
 torch is used for device memory, random numbers and row gathers of the hidden states; every step of the
 method itself runs in the library.
@@ -71,7 +72,7 @@ def run(batch=2, d_model=512, n_heads=4, head_dim=128, d_ff=512, n_experts=4, vo
         par_slot = (torch.gather(state.q_row, 1, fl) - (q_base - 2 * rows)) // 2      # row of the parent in this pass
         feat_parent = f_mix[par_slot.reshape(-1).long()].reshape(batch, width, d)
     tokens, parent, q_row, old, n_valid = jk.tree_finalize(state, n_tree)
-    draft_probs = jk.gather_draft_probs(torch.cat(q_rows, 0).contiguous(), q_row)
+    q_all = torch.cat(q_rows, 0).contiguous()      # (a serving loop writes the passes' distributions into one buffer)
 
     # verification: the target's attention layers over the tree (random q/k/v), then its logits (random, with
     # the draft tokens made likely so that something is accepted)
@@ -87,7 +88,7 @@ def run(batch=2, d_model=512, n_heads=4, head_dim=128, d_ff=512, n_experts=4, vo
     for b in range(batch):
         logits[b, rows_of[b], tokens[b].long().clamp(min=0)] += 6.0
     uniforms = torch.rand((batch, n_tree + 1), device=dev, generator=g)
-    path, alen, bonus = jk.accept_path(tokens, parent, logits, jk.JK_SAMPLE, 1.0, draft_probs, uniforms, max_depth=depth)
+    path, alen, bonus = jk.accept_path_rows(tokens, parent, logits, q_all, q_row, uniforms, 1.0, max_depth=depth)
     for l in layers:
         jk.commit_path(l["k_tree"], l["v_tree"], l["k_cache"], l["v_cache"], path, alen, plen, advance=l is layers[-1])
     torch.cuda.synchronize()

@@ -212,3 +212,38 @@ def test_example_round_runs_and_is_consistent():
         assert int(r["prefix_len"][b]) == 256 + int(alen[b])
         assert 0 <= int(r["bonus"][b]) < 8000
     assert all(torch.isfinite(o.float()).all() for o in r["outs"])
+
+
+def test_acceptance_through_the_row_table_equals_the_dense_call():
+    """jk_accept_path_rows on (q_all, q_row) gives exactly what jk_accept_path gives on the gathered dense array,
+    for the cooperative walk (large vocabulary) and the single-workgroup walk (forced), bad row numbers clamped."""
+    import os
+    rng = np.random.default_rng(4)
+    for V, B, N in ((5000, 3, 17), (40000, 2, 30)):
+        n_rows = 23
+        q_all = rng.dirichlet(np.full(V, 0.05), size=n_rows).astype(np.float32)
+        q_row = rng.integers(0, n_rows, size=(B, N)).astype(np.int32)
+        q_row[0, 0] = n_rows + 5                       # clamped to the last row
+        parent = np.stack([np.concatenate([[-1], rng.integers(-1, np.arange(1, N))]) for _ in range(B)]).astype(np.int32)
+        dense = q_all[np.clip(q_row, 0, n_rows - 1)]
+        tokens = np.zeros((B, N), dtype=np.int32)
+        for b in range(B):
+            for i in range(N):
+                tokens[b, i] = rng.choice(V, p=dense[b, i].astype(np.float64) / dense[b, i].astype(np.float64).sum())
+        logits = (rng.standard_normal((B, N + 1, V)) * 2).astype(np.float32)
+        for b in range(B):
+            for i in range(N):
+                logits[b, parent[b, i] + 1, tokens[b, i]] += 5.0
+        uni = rng.random((B, N + 1)).astype(np.float32)
+        t = lambda a: torch.from_numpy(a).cuda()
+        for single in ("0", "1"):
+            os.environ["JK_ACCEPT_SINGLE"] = single
+            try:
+                ref = jk.accept_path(t(tokens), t(parent), t(logits), jk.JK_SAMPLE, 0.9, t(dense), t(uni))
+                got = jk.accept_path_rows(t(tokens), t(parent), t(logits), t(q_all), t(q_row), t(uni), 0.9)
+                torch.cuda.synchronize()
+            finally:
+                os.environ.pop("JK_ACCEPT_SINGLE", None)
+            for a, b_ in zip(ref, got):
+                assert torch.equal(a, b_)
+            assert int(ref[1].min()) >= 0
