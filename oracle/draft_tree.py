@@ -117,3 +117,26 @@ def grow_parallel_tail(state: TreeState, frontier: Sequence[int], cand_tok: np.n
             state.parent.append(c)
             state.score.append(np.float32(state.score[c] * np.float32(cand_p[f, 1, j])))
             state.q_row.append(q_row_base + 2 * f + 1)
+
+
+def fill_static(state: TreeState, frontier: Sequence[int], cand_tok: np.ndarray, cand_p: np.ndarray,
+                slot: Sequence[int], expert: Sequence[int], rank: Sequence[int], max_nodes: int,
+                q_row_base: int) -> List[int]:
+    """One depth of a predefined (static) tree shape (Section 3.1.2: the two candidate lists can also fill a
+    predefined tree): new node j hangs under frontier node frontier[slot[j]] and takes candidate rank[j] of
+    that node's list of expert[j] (0 = left, 1 = right).  The shape is the caller's; nodes are appended in
+    the order given.  Returns the indices of the appended nodes (-1 for nodes dropped at the capacity)."""
+    ids = []
+    for j in range(len(slot)):
+        f, e, r = int(slot[j]), int(expert[j]), int(rank[j])
+        pid = int(frontier[f])
+        ps = np.float32(1.0) if pid < 0 else state.score[pid]
+        if len(state.tokens) >= max_nodes:
+            ids.append(-1)
+            continue
+        ids.append(len(state.tokens))
+        state.tokens.append(int(cand_tok[f, e, r]))
+        state.parent.append(pid)
+        state.score.append(np.float32(ps * np.float32(cand_p[f, e, r])))
+        state.q_row.append(q_row_base + 2 * f + e)
+    return ids

@@ -140,3 +140,31 @@ def test_parallel_tail_hand_worked_and_invariants():
     expanded = sorted(set(par[g] for g in grand))
     rest = [c for c in kids if c not in expanded]
     assert all(float(st.score[c]) <= min(float(st.score[e]) for e in expanded) for c in rest)
+
+
+def test_static_fill_reduces_to_growth_for_the_full_shape_and_follows_a_given_shape():
+    rng = np.random.default_rng(5)
+    k, nf = 3, 2
+    tok0, p0 = rng.integers(0, 99, (1, 2, k)), np.sort(rng.random((1, 2, k)).astype(np.float32))[:, :, ::-1]
+    tok1, p1 = rng.integers(0, 99, (nf, 2, k)), np.sort(rng.random((nf, 2, k)).astype(np.float32), axis=2)[:, :, ::-1]
+    a, b = dt.TreeState(), dt.TreeState()
+    fr_a = dt.grow(a, [-1], tok0, p0, nf, 100, 0)
+    ids = dt.fill_static(b, [-1], tok0, p0, [0] * (2 * k), [0] * k + [1] * k, list(range(k)) * 2, 100, 0)
+    assert ids == list(range(2 * k)) and (a.tokens, a.parent, a.q_row) == (b.tokens, b.parent, b.q_row)
+    assert [float(x) for x in a.score] == [float(x) for x in b.score]
+    # the full shape under the same frontier gives the same nodes as growth
+    dt.grow(a, fr_a, tok1, p1, nf, 100, 2)
+    full = [(f, e, r) for f in range(nf) for e in range(2) for r in range(k)]
+    dt.fill_static(b, fr_a, tok1, p1, [s[0] for s in full], [s[1] for s in full], [s[2] for s in full], 100, 2)
+    assert (a.tokens, a.parent, a.q_row) == (b.tokens, b.parent, b.q_row)
+    # a sparse shape: second frontier node only, right expert's best, then left expert's third
+    c = dt.TreeState()
+    dt.grow(c, [-1], tok0, p0, nf, 100, 0)
+    ids = dt.fill_static(c, fr_a, tok1, p1, [1, 1], [1, 0], [0, 2], 100, 2)
+    assert ids == [2 * k, 2 * k + 1]
+    assert c.tokens[-2:] == [int(tok1[1, 1, 0]), int(tok1[1, 0, 2])] and c.parent[-2:] == [fr_a[1]] * 2
+    assert c.q_row[-2:] == [2 + 3, 2 + 2]
+    assert float(c.score[-1]) == float(np.float32(c.score[fr_a[1]] * p1[1, 0, 2]))
+    # capacity
+    d = dt.TreeState()
+    assert dt.fill_static(d, [-1], tok0, p0, [0, 0, 0], [0, 0, 1], [0, 1, 0], 2, 0) == [0, 1, -1]
