@@ -405,6 +405,21 @@ jk_status jk_tree_grow_tail(const jk_tree_state* state, int32_t batch, int32_t n
                             int32_t k2, int32_t width, int32_t q_row_base, const int32_t* frontier_in,
                             const int32_t* cand_tokens, const float* cand_probs, void* hip_stream);
 
+/* One depth of a PREDEFINED tree shape (Section 3.1.2: the two candidate lists can also fill
+ * a static tree): new node j (j < n_new, appended in this order) hangs under frontier node
+ * frontier_in[b][shape_slot[j]] and takes candidate shape_rank[j] of that node's list of
+ * expert shape_expert[j] (0 = left, 1 = right); score and q_row as in jk_tree_grow.  The
+ * shape arrays are device int32 [n_new], the same for every sequence (entries outside their
+ * ranges are clamped).  frontier_out[b][i] (may be NULL with n_next = 0) is the index of new
+ * node next_index[i]: the parents of the next depth; new_ids (device int32 [batch][n_new], may
+ * be NULL) receives the indices of all new nodes (-1 for nodes dropped at max_nodes).
+ * n_new <= 4096. */
+jk_status jk_tree_fill_static(const jk_tree_state* state, int32_t batch, int32_t n_front, int32_t top_k,
+                              int32_t q_row_base, const int32_t* frontier_in, const int32_t* cand_tokens,
+                              const float* cand_probs, const int32_t* shape_slot, const int32_t* shape_expert,
+                              const int32_t* shape_rank, int32_t n_new, const int32_t* next_index, int32_t n_next,
+                              int32_t* frontier_out, int32_t* new_ids, void* hip_stream);
+
 jk_status jk_tree_finalize(const jk_tree_state* state, int32_t batch, int32_t n_keep, int32_t* tree_tokens,
                            int32_t* parent, int32_t* q_row, int32_t* old_index, int32_t* n_valid, void* hip_stream);
 

@@ -66,7 +66,7 @@ class PagedKV(ctypes.Structure):
 
 EXPORTS = ("jk_tree_verify_attention_workspace", "jk_tree_verify_attention", "jk_tree_verify_attention_paged",
            "jk_commit_path_layers_paged", "jk_accept_path_workspace",
-           "jk_accept_path", "jk_accept_path_rows", "jk_draft_heads_workspace", "jk_draft_heads", "jk_moe_experts_workspace", "jk_moe_experts", "jk_linear_workspace", "jk_linear", "jk_tree_grow", "jk_tree_grow_tail", "jk_tree_finalize", "jk_gather_draft_probs", "jk_commit_path", "jk_commit_path_layers", "jk_workspace_init", "jk_stream_read_probe", "jk_validate_tree", "jk_status_string", "jk_version")
+           "jk_accept_path", "jk_accept_path_rows", "jk_draft_heads_workspace", "jk_draft_heads", "jk_moe_experts_workspace", "jk_moe_experts", "jk_linear_workspace", "jk_linear", "jk_tree_grow", "jk_tree_grow_tail", "jk_tree_fill_static", "jk_tree_finalize", "jk_gather_draft_probs", "jk_commit_path", "jk_commit_path_layers", "jk_workspace_init", "jk_stream_read_probe", "jk_validate_tree", "jk_status_string", "jk_version")
 
 
 def library_path() -> str:
@@ -121,6 +121,9 @@ def lib() -> ctypes.CDLL:
         l.jk_tree_grow.argtypes = [ctypes.POINTER(TreeStateDesc), i32, i32, i32, i32, i32, vp, vp, vp, vp, vp]
         l.jk_tree_grow_tail.restype = i32
         l.jk_tree_grow_tail.argtypes = [ctypes.POINTER(TreeStateDesc), i32, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp]
+        l.jk_tree_fill_static.restype = i32
+        l.jk_tree_fill_static.argtypes = [ctypes.POINTER(TreeStateDesc), i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, i32,
+                                          vp, i32, vp, vp, vp]
         l.jk_tree_finalize.restype = i32
         l.jk_tree_finalize.argtypes = [ctypes.POINTER(TreeStateDesc), i32, i32, vp, vp, vp, vp, vp, vp]
         l.jk_gather_draft_probs.restype = i32
@@ -608,6 +611,31 @@ def tree_grow_tail(state: TreeState, frontier_in, cand_tokens, cand_probs, k1: i
                                  _ptr(frontier_in), _ptr(cand_tokens), _ptr(cand_probs), _stream_handle(stream))
     if st != 0:
         raise JakiroError(st, "jk_tree_grow_tail")
+
+
+def tree_fill_static(state: TreeState, frontier_in, cand_tokens, cand_probs, shape_slot, shape_expert, shape_rank,
+                     next_index, q_row_base: int, stream=None):
+    """jk_tree_fill_static.  shape_* int32 [n_new] device tensors; next_index int32 [n_next] or None.
+    Returns (frontier_out int32 [B,n_next] or None, new_ids int32 [B,n_new])."""
+    import torch
+    B = state.batch
+    n_front = 1 if frontier_in is None else int(frontier_in.shape[1])
+    rows, two, k = cand_tokens.shape
+    if rows != B * n_front or two != 2 or tuple(cand_probs.shape) != (rows, 2, k):
+        raise ValueError("cand_tokens / cand_probs must be [B*n_front, 2, k]")
+    n_new = int(shape_slot.numel())
+    n_next = 0 if next_index is None else int(next_index.numel())
+    dev = cand_tokens.device
+    new_ids = torch.empty((B, n_new), dtype=torch.int32, device=dev)
+    out = torch.empty((B, n_next), dtype=torch.int32, device=dev) if n_next else None
+    d = state.desc()
+    st = lib().jk_tree_fill_static(ctypes.byref(d), B, n_front, int(k), int(q_row_base), _ptr(frontier_in),
+                                   _ptr(cand_tokens), _ptr(cand_probs), _ptr(shape_slot), _ptr(shape_expert),
+                                   _ptr(shape_rank), n_new, _ptr(next_index), n_next, _ptr(out), _ptr(new_ids),
+                                   _stream_handle(stream))
+    if st != 0:
+        raise JakiroError(st, "jk_tree_fill_static")
+    return out, new_ids
 
 
 def tree_finalize(state: TreeState, n_keep: int, stream=None):

@@ -459,6 +459,30 @@ jk_status jk_tree_grow_tail(const jk_tree_state* state, int32_t batch, int32_t n
   return launch_tree_grow_tail(a, k1, k2, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? JK_OK : JK_ERR_HIP;
 }
 
+jk_status jk_tree_fill_static(const jk_tree_state* state, int32_t batch, int32_t n_front, int32_t top_k,
+                              int32_t q_row_base, const int32_t* frontier_in, const int32_t* cand_tokens,
+                              const float* cand_probs, const int32_t* shape_slot, const int32_t* shape_expert,
+                              const int32_t* shape_rank, int32_t n_new, const int32_t* next_index, int32_t n_next,
+                              int32_t* frontier_out, int32_t* new_ids, void* hip_stream) {
+  if (!tree_state_ok(state) || !cand_tokens || !cand_probs || !shape_slot || !shape_expert || !shape_rank)
+    return JK_ERR_INVALID_ARG;
+  if (batch < 1 || n_front < 1 || top_k < 1 || n_new < 1 || n_next < 0 || q_row_base < 0) return JK_ERR_INVALID_ARG;
+  if (!frontier_in && n_front != 1) return JK_ERR_INVALID_ARG;
+  if (n_next > 0 && (!next_index || !frontier_out)) return JK_ERR_INVALID_ARG;
+  if (state->max_nodes > tree_max_nodes() || n_new > 4096 || n_next > 4096 || batch > 65535) return JK_ERR_UNSUPPORTED;
+  TreeGrowArgs a;
+  a.batch = batch; a.n_front = n_front; a.top_k = top_k; a.width = n_next; a.max_nodes = state->max_nodes;
+  a.q_row_base = q_row_base;
+  a.tokens = state->tokens; a.parent = state->parent; a.q_row = state->q_row; a.n_nodes = state->n_nodes;
+  a.score = state->score;
+  a.frontier_in = frontier_in; a.cand_tok = cand_tokens; a.cand_p = cand_probs;
+  a.frontier_out = n_next > 0 ? frontier_out : nullptr;
+  return launch_tree_fill_static(a, shape_slot, shape_expert, shape_rank, n_new, next_index, n_next, new_ids,
+                                 static_cast<hipStream_t>(hip_stream)) == hipSuccess
+             ? JK_OK
+             : JK_ERR_HIP;
+}
+
 jk_status jk_tree_finalize(const jk_tree_state* state, int32_t batch, int32_t n_keep, int32_t* tree_tokens,
                            int32_t* parent, int32_t* q_row, int32_t* old_index, int32_t* n_valid, void* hip_stream) {
   if (!tree_state_ok(state) || !tree_tokens || !parent || !q_row || !n_valid) return JK_ERR_INVALID_ARG;

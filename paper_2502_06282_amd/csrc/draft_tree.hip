@@ -135,6 +135,43 @@ __global__ __launch_bounds__(kTreeThreads) void grow_tail_kernel(TreeGrowArgs a,
   if (t == 0) a.n_nodes[b] = min(n1 + G, a.max_nodes);
 }
 
+// One depth of a predefined tree shape: new node j hangs under frontier slot shape_slot[j] and
+// takes candidate shape_rank[j] of that slot's list of expert shape_expert[j].
+__global__ __launch_bounds__(kTreeThreads) void fill_static_kernel(TreeGrowArgs a, const int* __restrict__ shape_slot,
+                                                                   const int* __restrict__ shape_expert,
+                                                                   const int* __restrict__ shape_rank, int n_new,
+                                                                   const int* __restrict__ next_index, int n_next,
+                                                                   int* __restrict__ new_ids) {
+  const int b = blockIdx.x, t = threadIdx.x;
+  const int n0 = min(max(a.n_nodes[b], 0), a.max_nodes);
+  const long long base = (long long)b * a.max_nodes;
+  for (int j = t; j < n_new; j += kTreeThreads) {
+    const int id = n0 + j;
+    const bool valid = id < a.max_nodes;
+    if (valid) {
+      const int f = min(max(shape_slot[j], 0), a.n_front - 1);
+      const int e = shape_expert[j] != 0 ? 1 : 0;
+      const int r = min(max(shape_rank[j], 0), a.top_k - 1);
+      const long long row = (long long)b * a.n_front + f;
+      const int pid = a.frontier_in ? a.frontier_in[row] : -1;
+      const bool has_parent = pid >= 0 && pid < n0;
+      const float ps = has_parent ? a.score[base + pid] : 1.0f;
+      a.tokens[base + id] = a.cand_tok[(row * 2 + e) * a.top_k + r];
+      a.parent[base + id] = has_parent ? pid : -1;
+      a.score[base + id] = ps * a.cand_p[(row * 2 + e) * a.top_k + r];
+      a.q_row[base + id] = a.q_row_base + (int)(2 * row) + e;
+    }
+    if (new_ids) new_ids[(long long)b * n_new + j] = valid ? id : -1;
+  }
+  if (a.frontier_out)
+    for (int i = t; i < n_next; i += kTreeThreads) {
+      const int j = min(max(next_index[i], 0), n_new - 1);
+      a.frontier_out[(long long)b * n_next + i] = n0 + j < a.max_nodes ? n0 + j : -1;
+    }
+  __syncthreads();  // everybody has read n_nodes
+  if (t == 0) a.n_nodes[b] = min(n0 + n_new, a.max_nodes);
+}
+
 __global__ __launch_bounds__(kTreeThreads) void finalize_kernel(TreeFinalArgs a) {
   __shared__ float s_sc[kMaxGrowNodes];
   __shared__ short s_keep[kMaxGrowNodes];
@@ -209,6 +246,12 @@ hipError_t launch_tree_grow(const TreeGrowArgs& a, hipStream_t stream) {
 }
 hipError_t launch_tree_grow_tail(const TreeGrowArgs& a, int k1, int k2, hipStream_t stream) {
   hipLaunchKernelGGL(grow_tail_kernel, dim3(a.batch), dim3(kTreeThreads), 0, stream, a, k1, k2);
+  return hipGetLastError();
+}
+hipError_t launch_tree_fill_static(const TreeGrowArgs& a, const int* slot, const int* expert, const int* rank, int n_new,
+                                   const int* next_index, int n_next, int* new_ids, hipStream_t stream) {
+  hipLaunchKernelGGL(fill_static_kernel, dim3(a.batch), dim3(kTreeThreads), 0, stream, a, slot, expert, rank, n_new,
+                     next_index, n_next, new_ids);
   return hipGetLastError();
 }
 hipError_t launch_tree_finalize(const TreeFinalArgs& a, hipStream_t stream) {

@@ -132,6 +132,8 @@ struct TreeFinalArgs {
 int tree_max_nodes();
 hipError_t launch_tree_grow(const TreeGrowArgs& a, hipStream_t stream);
 hipError_t launch_tree_grow_tail(const TreeGrowArgs& a, int k1, int k2, hipStream_t stream);
+hipError_t launch_tree_fill_static(const TreeGrowArgs& a, const int* slot, const int* expert, const int* rank, int n_new,
+                                   const int* next_index, int n_next, int* new_ids, hipStream_t stream);
 hipError_t launch_tree_finalize(const TreeFinalArgs& a, hipStream_t stream);
 hipError_t launch_gather_rows(const float* q_all, const int* q_row, float* out, long long n_nodes, int vocab,
                               long long n_q_rows, hipStream_t stream);

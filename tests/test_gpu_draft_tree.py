@@ -247,3 +247,54 @@ def test_acceptance_through_the_row_table_equals_the_dense_call():
             for a, b_ in zip(ref, got):
                 assert torch.equal(a, b_)
             assert int(ref[1].min()) >= 0
+
+
+def test_static_shape_fill_matches_the_oracle_and_rebuilds_the_predefined_tree():
+    """The predefined 28-node tree of workload c7, filled depth by depth from random candidate lists: the first
+    half of a node's children (rounded up) take the left expert's best candidates, the rest the right expert's."""
+    from workloads import static_tree, tree_depths
+    shape_parent = static_tree()
+    depth_of = tree_depths(shape_parent)
+    N, B, k = len(shape_parent), 3, 4
+    rng = np.random.default_rng(6)
+    state = jk.TreeState(B, 64)
+    oracles = [dt.TreeState() for _ in range(B)]
+    frontier_nodes = [-1]                       # shape nodes whose children come next (-1: the root)
+    frontier_dev, fronts = None, [[-1] for _ in range(B)]
+    base = 0
+    t32 = lambda a: torch.tensor(a, dtype=torch.int32, device="cuda")
+    for d in range(1, int(depth_of.max()) + 1):
+        new = [i for i in range(N) if depth_of[i] == d]
+        slot, expert, rank = [], [], []
+        for p in frontier_nodes:
+            ch = [i for i in new if shape_parent[i] == p]
+            n_left = (len(ch) + 1) // 2
+            for j, _ in enumerate(ch):
+                slot.append(frontier_nodes.index(p))
+                expert.append(0 if j < n_left else 1)
+                rank.append(j if j < n_left else j - n_left)
+        nxt_nodes = [i for i in new if (shape_parent == i).any()]
+        next_index = [new.index(i) for i in nxt_nodes]
+        nf = len(frontier_nodes)
+        tok, p = _cands(rng, B * nf, k)
+        fo, ids = jk.tree_fill_static(state, frontier_dev, torch.from_numpy(tok).cuda(), torch.from_numpy(p).cuda(),
+                                      t32(slot), t32(expert), t32(rank), t32(next_index) if next_index else None, base)
+        torch.cuda.synchronize()
+        for b in range(B):
+            got_ids = dt.fill_static(oracles[b], fronts[b], tok[b * nf:(b + 1) * nf], p[b * nf:(b + 1) * nf], slot, expert,
+                                     rank, 64, base + 2 * b * nf)
+            assert ids[b].cpu().tolist() == got_ids
+            fronts[b] = [got_ids[j] for j in next_index]
+            if next_index:
+                assert fo[b].cpu().tolist() == fronts[b]
+        frontier_nodes, frontier_dev = nxt_nodes, fo
+        base += 2 * B * nf
+    tokens, parent, q_row, old, n_valid = jk.tree_finalize(state, N)
+    torch.cuda.synchronize()
+    for b in range(B):
+        assert int(state.n_nodes[b]) == N and int(n_valid[b]) == N
+        assert state.tokens[b, :N].cpu().tolist() == oracles[b].tokens
+        assert state.q_row[b, :N].cpu().tolist() == oracles[b].q_row
+        np.testing.assert_array_equal(state.score[b, :N].cpu().numpy(), np.asarray(oracles[b].score, dtype=np.float32))
+        assert parent[b].cpu().tolist() == shape_parent.tolist()       # the predefined tree, as the verification takes it
+        assert old[b].cpu().tolist() == list(range(N))

@@ -95,3 +95,9 @@ def test_draft_layer_workspace_queries_and_argument_checks_are_host_only(lib):
     assert lib.jk_tree_grow_tail(ctypes.byref(st), 1, 1, 4, 2, 2, 4, 0, None, None, None, None) == 1
     assert lib.jk_tree_finalize(ctypes.byref(st), 1, 8, None, None, None, None, None, None) == 1
     assert lib.jk_gather_draft_probs(1, 4, 100, None, 10, None, None, None) == 1
+
+
+def test_static_fill_argument_checks_are_host_only(lib):
+    st = binding.TreeStateDesc(None, None, None, None, None, 64)
+    assert lib.jk_tree_fill_static(ctypes.byref(st), 1, 1, 4, 0, None, None, None, None, None, None, 4, None, 0, None,
+                                   None, None) == 1
