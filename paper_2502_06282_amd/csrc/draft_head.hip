@@ -149,9 +149,10 @@ struct GemmCfg {
 // read straight from global memory would touch 32 cache lines per instruction and use 32 bytes
 // of each).  The strip is wide (up to 512 weight rows) because every workgroup has to pull all
 // of X through the same path as its weights: X traffic is (m / strip) of the weight traffic.
-// A row's four 16-byte pieces are stored XOR-swizzled with bits 1-2 of the row number (the
-// transfer fetches piece s ^ key into slot s), so that an operand read (32 rows, one piece of
-// each) spreads over all banks.
+// A row's four 16-byte pieces are stored XOR-swizzled with key(row) = (row >> 2) & 3 (the transfer
+// fetches piece s ^ key into slot s).  Measured with SQ_LDS_BANK_CONFLICT: this key (like bits 3-4 of
+// the row) gives no conflict cycles at all for an operand read (32 rows, one piece of each), bits
+// 0-1 or 1-2 cost four cycles per read.
 template <int MB>
 __global__ __launch_bounds__(kGemmThreads, 1) void skinny_gemm_kernel(GemmParams p) {
   using C = GemmCfg<MB>;
@@ -183,7 +184,8 @@ __global__ __launch_bounds__(kGemmThreads, 1) void skinny_gemm_kernel(GemmParams
 
   // transfer geometry: one instruction covers 16 rows, lane l -> row l / 4 of them, slot l % 4
   const int sub = lane >> 2, slot = lane & 3;
-  const unsigned piece = (unsigned)((slot ^ ((sub >> 1) & 3)) << 4);
+  // slot `slot` of a row holds piece slot ^ key(row), key(row) = (row >> 2) & 3 (the same for every 16-row transfer)
+  const unsigned piece = (unsigned)((slot ^ ((sub >> 2) & 3)) << 4);
   unsigned voff_w[C::NWI], voff_x[2];
 #pragma unroll
   for (int i = 0; i < C::NWI; ++i) {
@@ -222,7 +224,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void skinny_gemm_kernel(GemmParams
   // operand read addresses within a slab: row r of a 32-row block (64 bytes per row), piece
   // 2 j + h of MFMA k step j, swizzled
   const unsigned rd = (unsigned)(r * 64);
-  const unsigned key = (unsigned)((r >> 1) & 3);
+  const unsigned key = (unsigned)((r >> 2) & 3);
 
 #pragma unroll
   for (int s = 0; s < C::DX - 1; ++s) issue_x(s);
