@@ -317,15 +317,15 @@ hipError_t launch_gemm(const GemmParams& p, hipStream_t stream) {
 }
 
 // ------------------------------------------------------------------ softmax + top-k per logits row
-// A row (a vocabulary of 10^5 entries) is cut into parts of at most 16 384 entries so that the
+// A row (a vocabulary of 10^5 entries) is cut into parts of at most 8 192 entries so that the
 // work spreads over all CUs:
 //   row_parts_kernel   per (row, part): maximum, sum of exp((x - max) / T), the part's k best
 //   row_merge_kernel   per row: the row's maximum and normaliser from the parts' pairs, the k
 //                      best of the parts' candidates, their probabilities
 //   row_probs_kernel   per (row, part): q = exp((x - max) / T) / Z      (skipped if not asked for)
 constexpr int kPartThreads = 256;
-constexpr int kPartPerThread = 64;                             // entries a thread holds in registers
-constexpr int kPartMax = kPartThreads * kPartPerThread;        // 16 384
+constexpr int kPartPerThread = 32;                             // entries a thread holds in registers
+constexpr int kPartMax = kPartThreads * kPartPerThread;        // 8 192
 constexpr int kMaxTopK = 16;
 
 struct SoftParams {
@@ -535,9 +535,9 @@ __global__ __launch_bounds__(kPartThreads) void row_parts_kernel(SoftParams p) {
   }
 }
 
-// one wave per row
-__global__ __launch_bounds__(64) void row_merge_kernel(SoftParams p) {
-  const int lane = threadIdx.x, row = blockIdx.x, K = p.k, P = p.parts;
+// one workgroup of four waves per row; every wave reduces the parts' (max, sum) pairs for itself
+__global__ __launch_bounds__(256) void row_merge_kernel(SoftParams p) {
+  const int tid = threadIdx.x, lane = tid & 63, row = blockIdx.x, K = p.k, P = p.parts;
   const float* ms = p.part_ms + (long long)row * P * 2;
   float m = -INFINITY;
   for (int i = lane; i < P; i += 64) m = fmaxf(m, ms[2 * i]);
@@ -552,35 +552,28 @@ __global__ __launch_bounds__(64) void row_merge_kernel(SoftParams p) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) z += __shfl_xor(z, o);
   const float inv_z = (float)(1.0 / z);
-  if (lane == 0) {
+  if (tid == 0) {
     p.row_mz[2 * row] = m_use;
     p.row_mz[2 * row + 1] = inv_z;
   }
   const float* cv = p.part_cv + (long long)row * P * K;
   const int* ci = p.part_ci + (long long)row * P * K;
   const int n = P * K;
-  auto emit = [&](int round, const Best& b) {
-    if (lane == 0) {
-      const bool ok = b.id >= 0 && b.id < p.vocab;
-      p.tk_ids[(long long)row * K + round] = ok ? b.id : 0;
-      p.tk_probs[(long long)row * K + round] = ok ? expf((b.v - m_use) * p.inv_temp) * inv_z : 0.f;
-    }
-  };
-  if (n <= 256) {  // the usual case: every candidate finds its place by counting those that beat it
-    __shared__ float mv[256];
-    __shared__ int mi[256];
-    for (int i = lane; i < n; i += 64) {
+  if (n <= 1024) {  // the usual case: every candidate finds its place by counting those that beat it
+    __shared__ float mv[1024];
+    __shared__ int mi[1024];
+    for (int i = tid; i < n; i += 256) {
       mv[i] = cv[i];
       mi[i] = ci[i];
     }
     // places that no candidate claims (fewer than k candidates in the whole row) read "none";
-    // the winners' stores below come later in this wave's program order
-    if (lane < K) {
-      p.tk_ids[(long long)row * K + lane] = 0;
-      p.tk_probs[(long long)row * K + lane] = 0.f;
+    // the barrier orders these stores before the winners'
+    if (tid < K) {
+      p.tk_ids[(long long)row * K + tid] = 0;
+      p.tk_probs[(long long)row * K + tid] = 0.f;
     }
     __syncthreads();
-    for (int j = lane; j < n; j += 64) {
+    for (int j = tid; j < n; j += 256) {
       const float v = mv[j];
       const int id = mi[j];
       if (id < 0 || id >= p.vocab) continue;  // an exhausted part's filler
@@ -594,6 +587,7 @@ __global__ __launch_bounds__(64) void row_merge_kernel(SoftParams p) {
     }
     return;
   }
+  if (tid >= 64) return;  // very many parts: one wave, k selection passes over the candidates in memory
   float pv = INFINITY;
   int pi = -1;
   for (int round = 0; round < K; ++round) {
@@ -609,7 +603,11 @@ __global__ __launch_bounds__(64) void row_merge_kernel(SoftParams p) {
       }
     }
     const Best b = wave_best(bv, bi);
-    emit(round, b);
+    if (lane == 0) {
+      const bool ok = b.id >= 0 && b.id < p.vocab;
+      p.tk_ids[(long long)row * K + round] = ok ? b.id : 0;
+      p.tk_probs[(long long)row * K + round] = ok ? expf((b.v - m_use) * p.inv_temp) * inv_z : 0.f;
+    }
     pv = b.v;
     pi = b.id;
   }
@@ -919,7 +917,7 @@ hipError_t launch_draft_heads(const DraftHeadsArgs& a, hipStream_t stream) {
   sp.inv_temp = 1.0f / a.temperature;
   hipLaunchKernelGGL(row_parts_kernel, dim3(m * rp.parts), dim3(kPartThreads), 0, stream, sp);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  hipLaunchKernelGGL(row_merge_kernel, dim3(m), dim3(64), 0, stream, sp);
+  hipLaunchKernelGGL(row_merge_kernel, dim3(m), dim3(256), 0, stream, sp);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if (a.draft_probs) {
     hipLaunchKernelGGL(row_probs_kernel, dim3(m * rp.parts), dim3(kPartThreads), 0, stream, sp);
