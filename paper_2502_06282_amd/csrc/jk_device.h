@@ -40,5 +40,21 @@ __device__ __forceinline__ void wait_vm() {
   asm volatile("" ::: "memory");
 }
 
+// Stores that go through to memory at once (system scope: sc0 sc1), for results that
+// nothing in the same kernel reads again.  An ordinary store leaves its line dirty in the
+// XCD's L2, and the write-back of all such lines is part of the kernel's end: megabytes of
+// results written in the last microsecond of a short kernel then lengthen it measurably.
+typedef unsigned int store_u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int store_u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void store_through(void* dst, store_u32x4 v) {
+  asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" ::"v"(dst), "v"(v) : "memory");
+}
+__device__ __forceinline__ void store_through(void* dst, store_u32x2 v) {
+  asm volatile("global_store_dwordx2 %0, %1, off sc0 sc1" ::"v"(dst), "v"(v) : "memory");
+}
+__device__ __forceinline__ void store_through(void* dst, unsigned int v) {
+  asm volatile("global_store_dword %0, %1, off sc0 sc1" ::"v"(dst), "v"(v) : "memory");
+}
+
 }  // namespace dev
 }  // namespace jk

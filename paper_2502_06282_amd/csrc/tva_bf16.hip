@@ -60,6 +60,16 @@ __device__ __forceinline__ bf16x8 lds_read_tr2(unsigned addr, unsigned second) {
 }
 
 constexpr int kWaveRows = 32;   // query rows per wave
+#ifndef JK_SPREAD
+#define JK_SPREAD 1
+#endif
+#ifndef JK_VFB
+#define JK_VFB 0
+#endif
+#ifndef JK_VAE
+#define JK_VAE 0
+#endif
+constexpr int kSpread = JK_SPREAD;  // score phases of a pipelined tile pair that carry the next round's transfers (0: none)
 
 struct KParams {
   const uint16_t *q, *kc, *vc, *kt, *vt;
@@ -75,6 +85,7 @@ struct KParams {
   // block_table[b * max_blocks + t / page_size], slot t % page_size; tpp = 32-key tiles per page
   const int32_t* block_table;
   int max_blocks, tpp, n_pages;
+  int through;  // bit 0: outputs and partials, bit 1: the partials' (max, sum) pairs go through to memory (see the epilogue)
   long long page_stride;
   unsigned long long mg_tpp;
 };
@@ -255,6 +266,43 @@ __device__ __forceinline__ void dma_round(int r, const TileSrc& ts, const LaneCh
   }
 }
 
+// The transfers of a round of full prefix tiles of a contiguous cache, one at a time: piece
+// k = chunk k % N of tile k / N of the round.  Issued between the MFMAs of the tile loop: all
+// waves of a workgroup leave the barrier together, and a burst of transfers from every wave
+// queues up in front of the CU's one address unit (1 KB = 16 cycles each) while the waves
+// wait to get rid of them with nothing else issued.
+template <int D, int NW, int TPR>
+struct RoundPieces {
+  static constexpr int N = LaneChunks<D, NW>::N;
+  static constexpr int PIECES = TPR * N;
+  const uint16_t* base;  // first tile of the round
+  long long tile_elems;
+  unsigned slot;
+  const LaneChunks<D, NW>* lc;
+  __device__ __forceinline__ void issue(int k) const {
+    const int w = k / N, i = k % N;
+    dma16(base + w * tile_elems, lc->off[i], slot + w * 2 * Geo<D>::TILE_BYTES + lc->lds[i]);
+  }
+  // pieces [P * step / steps, P * (step + 1) / steps): an even share for each of `steps` places
+  __device__ __forceinline__ void share(int step, int steps) const {
+    // (fenced: left alone, the compiler gathers the MFMAs in front of the transfers)
+    if (PIECES * step / steps < PIECES * (step + 1) / steps) __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int k = 0; k < PIECES; ++k)
+      if (k >= PIECES * step / steps && k < PIECES * (step + 1) / steps) issue(k);
+    if (PIECES * step / steps < PIECES * (step + 1) / steps) __builtin_amdgcn_sched_barrier(0);
+  }
+};
+
+// Largest of a lane's 16 scores of a tile, as a tree three levels deep: a chain of fifteen
+// dependent maxima would spend its latency with nothing else to issue.
+__device__ __forceinline__ float max16(const floatx16& s) {
+  const float a = fmaxf(fmaxf(s[0], s[1]), s[2]), b = fmaxf(fmaxf(s[3], s[4]), s[5]);
+  const float c = fmaxf(fmaxf(s[6], s[7]), s[8]), d = fmaxf(fmaxf(s[9], s[10]), s[11]);
+  const float e = fmaxf(fmaxf(s[12], s[13]), s[14]);
+  return fmaxf(fmaxf(fmaxf(a, b), c), fmaxf(fmaxf(d, e), s[15]));
+}
+
 // Per-wave state of the online softmax and the output accumulation (32 query rows).
 template <int D>
 struct WaveState {
@@ -324,8 +372,8 @@ __device__ __forceinline__ void mask_tile(floatx16& sacc, int mask_mode, int nva
 // in s0 (and s1); v0 / v1 are their V tiles in LDS.  Two tiles share one running-maximum
 // update, and their independent MFMA chains fill each other's latencies.
 template <int D, int KT>
-__device__ __forceinline__ void softmax_pv(WaveState<D>& st, const floatx16& s0, const floatx16& s1,
-                                           unsigned v_addr, float scale_log2) {
+__device__ __forceinline__ void softmax_probs(WaveState<D>& st, const floatx16& s0, const floatx16& s1,
+                                              float scale_log2, bf16x8 (&pb)[2 * KT]) {
   using G_ = Geo<D>;
   constexpr int DB = G_::DB;
   // The reference maximum m of a row moves only when the round's maximum exceeds it by more
@@ -333,13 +381,8 @@ __device__ __forceinline__ void softmax_pv(WaveState<D>& st, const floatx16& s0,
   // the rescale of the accumulators becomes rare.  The result is unchanged: weights, their
   // sum and the accumulators all carry the same reference.
   constexpr float kLazy = 8.f;
-  float tmax = fmaxf(s0[0], s0[1]);
-#pragma unroll
-  for (int i = 2; i < 16; ++i) tmax = fmaxf(tmax, s0[i]);
-  if (KT == 2) {
-#pragma unroll
-    for (int i = 0; i < 16; ++i) tmax = fmaxf(tmax, s1[i]);
-  }
+  float tmax = max16(s0);
+  if (KT == 2) tmax = fmaxf(tmax, max16(s1));
   tmax = half_swap_max(tmax) * scale_log2;
   const float m_old = st.m;
   const bool up = tmax > m_old + kLazy;  // false for tmax = -inf; true for the first visible key
@@ -349,7 +392,6 @@ __device__ __forceinline__ void softmax_pv(WaveState<D>& st, const floatx16& s0,
   const bool moved = up && (m_old != -INFINITY);  // accumulators are still zero before the first key
   st.m = m_ref;
   // probabilities become bf16 B operands of the value product
-  bf16x8 pb[2 * KT];
   float lsum = 0.f;
 #pragma unroll
   for (int kt = 0; kt < KT; ++kt)
@@ -369,6 +411,15 @@ __device__ __forceinline__ void softmax_pv(WaveState<D>& st, const floatx16& s0,
 #pragma unroll
       for (int i = 0; i < 16; ++i) st.o[db][i] *= alpha;
   }
+}
+
+template <int D, int KT>
+__device__ __forceinline__ void softmax_pv(WaveState<D>& st, const floatx16& s0, const floatx16& s1,
+                                           unsigned v_addr, float scale_log2) {
+  using G_ = Geo<D>;
+  constexpr int DB = G_::DB;
+  bf16x8 pb[2 * KT];
+  softmax_probs<D, KT>(st, s0, s1, scale_log2, pb);
   // ---- O^T += V^T . P^T
 #pragma unroll
   for (int kt = 0; kt < KT; ++kt)
@@ -380,6 +431,42 @@ __device__ __forceinline__ void softmax_pv(WaveState<D>& st, const floatx16& s0,
                                        8 * G_::ROW_BYTES);
         st.o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pb[2 * kt + j], st.o[db], 0, 0, 0);
       }
+}
+
+// One unmasked tile on its own (the odd last tile of a split: everybody else waits for the
+// splits that have one).  All LDS operands are requested before the first MFMA, the K
+// fragments first: the V fragments then arrive under the score product and the softmax
+// instead of in front of the value product.
+template <int D>
+__device__ __forceinline__ void lone_tile(WaveState<D>& st, unsigned k_addr, unsigned v_addr, float scale_log2) {
+  using G_ = Geo<D>;
+  constexpr int DK = G_::DK, DB = G_::DB;
+  bf16x8 kf[DK], vf[2 * DB];
+#pragma unroll
+  for (int ks = 0; ks < DK; ++ks) kf[ks] = lds_read128(k_addr ^ (ks << 5));
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+      vf[j * DB + db] = lds_read_tr2((v_addr ^ (db << 6)) + 16 * j * G_::ROW_BYTES, 8 * G_::ROW_BYTES);
+  __builtin_amdgcn_sched_barrier(0);
+  floatx16 a0, a1, s0;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) a0[i] = a1[i] = 0.f;
+#pragma unroll
+  for (int ks = 0; ks < DK; ks += 2) {  // two chains: a dependent MFMA issues only every other slot
+    a0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], st.q[ks], a0, 0, 0, 0);
+    a1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks + 1], st.q[ks + 1], a1, 0, 0, 0);
+  }
+#pragma unroll
+  for (int i = 0; i < 16; ++i) s0[i] = a0[i] + a1[i];
+  bf16x8 pb[2];
+  softmax_probs<D, 1>(st, s0, s0, scale_log2, pb);
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+      st.o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[j * DB + db], pb[j], st.o[db], 0, 0, 0);
 }
 
 // Two unmasked tiles A, B of a round, software-pipelined by hand.  Within one tile the score
@@ -400,10 +487,7 @@ struct PairPipe {
   // still to be added to them
   static __device__ __forceinline__ float new_reference(WaveState<D>& st, const floatx16& s, float scale_log2,
                                                         float& alpha, bool& moved) {
-    float tmax = fmaxf(s[0], s[1]);
-#pragma unroll
-    for (int i = 2; i < 16; ++i) tmax = fmaxf(tmax, s[i]);
-    tmax = half_swap_max(tmax) * scale_log2;
+    const float tmax = half_swap_max(max16(s)) * scale_log2;
     const float m_old = st.m;
     const bool up = tmax > m_old + kLazy;
     const float m_ref = up ? tmax : m_old;
@@ -434,7 +518,11 @@ struct PairPipe {
   }
 
   // k_addr / v_addr: LDS byte address of tile A's K / V tile plus the lane's Geo::k_lane / v_lane
-  static __device__ __forceinline__ void run(WaveState<D>& st, unsigned k_addr, unsigned v_addr, float scale_log2) {
+  // `next`: the transfers of the round that refills the ring (SPREAD > 0), issued between the
+  // MFMAs of the first SPREAD score phases
+  template <int SPREAD, class Pieces>
+  static __device__ __forceinline__ void run(WaveState<D>& st, unsigned k_addr, unsigned v_addr, float scale_log2,
+                                             const Pieces& next) {
     static_assert(DK == 8 || DK == 4, "head_dim 128 or 64");
     constexpr unsigned kNextTile = 2 * G_::TILE_BYTES;  // tile B's K (V) tile follows tile A's K and V
     auto v_frag = [&](unsigned tile_off, int j, int db) {
@@ -442,7 +530,12 @@ struct PairPipe {
     };
     // LDS operands are fetched a whole phase ahead of the MFMAs that use them: a read issued
     // just before its MFMA would expose the LDS latency eight times per phase
-    bf16x8 kf[DK], vf[2 * DB];
+    bf16x8 kf[DK], vfA[2 * DB];
+#if JK_VFB
+    bf16x8 vfB[2 * DB];
+#else
+    bf16x8 (&vfB)[2 * DB] = vfA;
+#endif
 
     // ---- S(A)
     floatx16 sA, sB;
@@ -451,52 +544,82 @@ struct PairPipe {
 #pragma unroll
     for (int ks = 0; ks < DK; ++ks) kf[ks] = lds_read128(k_addr ^ (ks << 5));
 #pragma unroll
-    for (int ks = 0; ks < DK; ++ks) sA = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], st.q[ks], sA, 0, 0, 0);
+    for (int ks = 0; ks < DK; ++ks) {
+      sA = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], st.q[ks], sA, 0, 0, 0);
+      if (SPREAD > 0) next.share(ks, DK * SPREAD);
+    }
     // (scheduling fences between the phases: left alone, the compiler hoists the next phase's
     // LDS reads above this phase and runs out of registers)
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int ks = 0; ks < DK; ++ks) kf[ks] = lds_read128((k_addr ^ (ks << 5)) + kNextTile);  // lands while the chain drains
+#if JK_VAE
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int db = 0; db < DB; ++db) vfA[j * DB + db] = v_frag(0, j, db);
+#endif
 
-    // ---- softmax(A) between the MFMAs of S(B)
+    // ---- softmax(A) between the MFMAs of S(B).  The first half of S(B) is issued ahead of
+    // the running-maximum update of A (a chain of dependent vector instructions that waits
+    // for the last MFMA of S(A)): the matrix unit works through them meanwhile.
     bf16x8 pA[2], pB[2];
     float lsum = 0.f;
     float alpha;
     bool moved;
+#pragma unroll
+    for (int ks = 0; ks < DK / 2; ++ks) {
+      sB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], st.q[ks], sB, 0, 0, 0);
+      if (SPREAD > 1) next.share(DK + ks, DK * SPREAD);
+    }
+    __builtin_amdgcn_sched_barrier(0);
     const float mA = new_reference(st, sA, scale_log2, alpha, moved);
     rescale(st, alpha, moved);
 #pragma unroll
-    for (int ks = 0; ks < DK; ++ks) {
+    for (int ks = DK / 2; ks < DK; ++ks) {
       sB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], st.q[ks], sB, 0, 0, 0);
+      if (SPREAD > 1) next.share(DK + ks, DK * SPREAD);
 #pragma unroll
-      for (int i = ks * (8 / DK); i < (ks + 1) * (8 / DK); ++i) two_probs(sA, i, scale_log2, mA, lsum, pA);
+      for (int i = (ks - DK / 2) * (16 / DK); i < (ks - DK / 2 + 1) * (16 / DK); ++i)
+        two_probs(sA, i, scale_log2, mA, lsum, pA);
     }
     st.l += lsum;
     __builtin_amdgcn_sched_barrier(0);
 
-    // ---- softmax(B) between the MFMAs of O += V(A)^T . P(A)^T
+    // ---- softmax(B) between the MFMAs of O += V(A)^T . P(A)^T, in the same way; the V
+    // fragments of B are requested now and arrive under this phase
+#if !JK_VAE
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
-      for (int db = 0; db < DB; ++db) vf[j * DB + db] = v_frag(0, j, db);
+      for (int db = 0; db < DB; ++db) vfA[j * DB + db] = v_frag(0, j, db);
+#endif
+#if JK_VFB
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int db = 0; db < DB; ++db) vfB[j * DB + db] = v_frag(kNextTile, j, db);
+#endif
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+      st.o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfA[db], pA[0], st.o[db], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
     lsum = 0.f;
     const float mB = new_reference(st, sB, scale_log2, alpha, moved);  // accumulators: after P(A) V(A) below
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int db = 0; db < DB; ++db) {
+      st.o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfA[DB + db], pA[1], st.o[db], 0, 0, 0);
 #pragma unroll
-      for (int db = 0; db < DB; ++db) {
-        st.o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[j * DB + db], pA[j], st.o[db], 0, 0, 0);
-        constexpr int PER = 8 / (2 * DB);  // pairs of scores per MFMA
-#pragma unroll
-        for (int i = (j * DB + db) * PER; i < (j * DB + db + 1) * PER; ++i)
-          two_probs(sB, i, scale_log2, mB, lsum, pB);
-      }
+      for (int i = db * (8 / DB); i < (db + 1) * (8 / DB); ++i) two_probs(sB, i, scale_log2, mB, lsum, pB);
+    }
     st.l += lsum;
     __builtin_amdgcn_sched_barrier(0);
+#if !JK_VFB
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
-      for (int db = 0; db < DB; ++db) vf[j * DB + db] = v_frag(kNextTile, j, db);
+      for (int db = 0; db < DB; ++db) vfB[j * DB + db] = v_frag(kNextTile, j, db);
+#endif
     rescale(st, alpha, moved);
 
     // ---- O += V(B)^T . P(B)^T
@@ -504,7 +627,7 @@ struct PairPipe {
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int db = 0; db < DB; ++db)
-        st.o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[j * DB + db], pB[j], st.o[db], 0, 0, 0);
+        st.o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfB[j * DB + db], pB[j], st.o[db], 0, 0, 0);
   }
 };
 
@@ -626,8 +749,12 @@ __global__ __launch_bounds__((Plan<D, WM, WN, KT, PAGED>::THREADS), (Plan<D, WM,
 #pragma unroll
     for (int ks = 0; ks < DK; ++ks) q_raw[ks] = *reinterpret_cast<const u32x4*>(src + ks * 16);  // clamped row: in bounds
   }
-  int my_parent = -1;
-  if (tid < T) my_parent = p.parent[(long long)b * T + tid];
+  // (the first wave builds the ancestor sets, nodes lane and lane + 64)
+  int parent_lo = -1, parent_hi = -1;
+  if (wave == 0) {
+    if (lane < T) parent_lo = p.parent[(long long)b * T + lane];
+    if (lane + 64 < T) parent_hi = p.parent[(long long)b * T + lane + 64];
+  }
 
   // ---- tile range of this split.  The prefix length is still on its way: start the K/V
   // stream on the assumption that it equals the host's upper bound (the usual case); if it
@@ -734,27 +861,44 @@ __global__ __launch_bounds__((Plan<D, WM, WN, KT, PAGED>::THREADS), (Plan<D, WM,
   // ---- ancestor sets (only workgroups that reach tree tiles need them), by pointer
   // doubling: after k steps a node knows its nearest 2^k ancestors-or-self and its 2^k-th
   // ancestor, so the number of steps is logarithmic in the depth of the tree rather than
-  // the depth itself (every step is a round trip through LDS)
-  if (has_tree) {
-    int up = -1;
-    unsigned long long lo = 0, hi = 0;
-    if (tid < T) {
-      up = (my_parent >= -1 && my_parent < tid) ? my_parent : -1;  // indices strictly decrease towards the root
-      if (tid < 64) lo = 1ull << tid; else hi = 1ull << (tid - 64);
-    }
+  // the depth itself (every step is a round trip through LDS).  One wave does it alone, two
+  // nodes per lane: the LDS operations of a wave complete in program order, so the steps
+  // need no barrier (as rounds of the whole workgroup, with two or three barriers each, the
+  // same steps took three times as long, and the split that owns the tree tiles is the one
+  // the others wait for).  The barrier of the first round publishes the sets: tree tiles
+  // are masked inside the loop only.
+  if (has_tree && wave == 0) {
+    const int n_lo = lane, n_hi = lane + 64;
+    int up_lo = (parent_lo >= -1 && parent_lo < n_lo) ? parent_lo : -1;  // indices strictly decrease towards the root
+    int up_hi = (parent_hi >= -1 && parent_hi < n_hi) ? parent_hi : -1;  // (-1 as well for lanes past the tree)
+    unsigned long long lo_lo = n_lo < T ? 1ull << n_lo : 0ull, hi_lo = 0ull;  // node lane: bit < 64
+    unsigned long long lo_hi = 0ull, hi_hi = n_hi < T ? 1ull << lane : 0ull;  // node lane + 64: bit >= 64
+    const bool two = T > 64;  // uniform
     for (;;) {
-      if (tid < T) {
-        par_s[tid] = up;
-        anc[2 * tid] = lo;
-        anc[2 * tid + 1] = hi;
+      par_s[n_lo] = up_lo;
+      anc[2 * n_lo] = lo_lo;
+      anc[2 * n_lo + 1] = hi_lo;
+      if (two) {
+        par_s[n_hi] = up_hi;
+        anc[2 * n_hi] = lo_hi;
+        anc[2 * n_hi + 1] = hi_hi;
       }
-      if (!__syncthreads_or(up >= 0)) break;  // nobody has an ancestor left to fold in: LDS holds the sets
-      if (up >= 0) {
-        lo |= anc[2 * up];
-        hi |= anc[2 * up + 1];
-        up = par_s[up];
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      if (!__any(up_lo >= 0 || up_hi >= 0)) break;  // nobody has an ancestor left to fold in: LDS holds the sets
+      if (up_lo >= 0) {
+        lo_lo |= anc[2 * up_lo];
+        hi_lo |= anc[2 * up_lo + 1];
+        up_lo = par_s[up_lo];
       }
-      __syncthreads();  // every read of this step precedes the next step's writes
+      if (two && up_hi >= 0) {
+        lo_hi |= anc[2 * up_hi];
+        hi_hi |= anc[2 * up_hi + 1];
+        up_hi = par_s[up_hi];
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");  // every read of this step precedes the next step's writes
+      __builtin_amdgcn_wave_barrier();
     }
   }
 
@@ -797,16 +941,26 @@ __global__ __launch_bounds__((Plan<D, WM, WN, KT, PAGED>::THREADS), (Plan<D, WM,
     wait_dma<DMA_PER_ROUND>(ahead < NR - 2 ? ahead : NR - 2);
     __syncthreads();
     if (r == 0) JK_TS(4);
-    if (r + NR - 1 < n_rounds)
-      dma_round<D, NW, TPR, PAGED>(r + NR - 1, ts, lc, ring_addr + ((r + NR - 1) % NR) * STAGE_BYTES);
     const int tb = ts.t_begin + (r * WN + wn) * KT;
     const unsigned tile_a = ring_addr + (r % NR) * STAGE_BYTES + wn * KT * 2 * TILE_BYTES;  // K of the first tile
-    if (KT == 2 && (tb + 2) * kTileKeys <= L && tb + 2 <= ts.t_end) {
-      PairPipe<D>::run(st, tile_a + k_lane, tile_a + TILE_BYTES + v_lane, scale_log2);  // two full prefix tiles
+    const bool pair = KT == 2 && (tb + 2) * kTileKeys <= L && tb + 2 <= ts.t_end;  // two full prefix tiles
+    // the refill of the ring: on its own, or (full prefix tiles behind a pipelined pair)
+    // piece by piece between the pair's MFMAs
+    RoundPieces<D, NW, TPR> next;
+    const int t_next = ts.t_begin + (r + NR - 1) * TPR;
+    const bool refill = r + NR - 1 < n_rounds;
+    const bool spread = kSpread > 0 && !PAGED && WN == 1 && refill && pair && (t_next + TPR) * kTileKeys <= L;
+    if (refill && !spread) dma_round<D, NW, TPR, PAGED>(r + NR - 1, ts, lc, ring_addr + ((r + NR - 1) % NR) * STAGE_BYTES);
+    if (pair && spread) {
+      next.tile_elems = (long long)kTileKeys * ts.kc_sl;
+      next.base = lc.cache + (long long)t_next * next.tile_elems;
+      next.slot = ring_addr + ((r + NR - 1) % NR) * STAGE_BYTES;
+      next.lc = &lc;
+      PairPipe<D>::template run<kSpread>(st, tile_a + k_lane, tile_a + TILE_BYTES + v_lane, scale_log2, next);
+    } else if (pair) {
+      PairPipe<D>::template run<0>(st, tile_a + k_lane, tile_a + TILE_BYTES + v_lane, scale_log2, next);
     } else if (KT == 2 && WN == 1 && tb + 1 == ts.t_end && (tb + 1) * kTileKeys <= L) {
-      floatx16 s0, s1;  // a lone full prefix tile at the end of the split: no mask, half the work
-      qk_tiles<D, 1>(st, tile_a + k_lane, s0, s1);
-      softmax_pv<D, 1>(st, s0, s1, tile_a + TILE_BYTES + v_lane, scale_log2);
+      lone_tile<D>(st, tile_a + k_lane, tile_a + TILE_BYTES + v_lane, scale_log2);  // no mask, half the work
     } else if (tb < ts.t_end) {
       int mode, nvalid;
       unsigned int bits;
@@ -884,7 +1038,10 @@ __global__ __launch_bounds__((Plan<D, WM, WN, KT, PAGED>::THREADS), (Plan<D, WM,
     // split, and are the largest avoidable traffic of a call.
     const float mul = splits == 1 ? 1.f / lsum : 1.f;  // lsum > 0: every row sees at least its own tree key
     const long long prow0 = ((long long)unit_id * splits + split) * p.m_pad + qtile * QROWS + wm * kWaveRows;
-    if (splits > 1 && row_ok && g == 0) p.part_ml[prow0 + c32] = make_float2(mx, lsum);
+    if (splits > 1 && row_ok && g == 0) {
+      if (p.through & 2) dev::store_through(p.part_ml + prow0 + c32, dev::store_u32x2{__float_as_uint(mx), __float_as_uint(lsum)});
+      else p.part_ml[prow0 + c32] = make_float2(mx, lsum);
+    }
     unsigned char* patch = smem + P_::OBUF_BYTES + wm * P_::PATCH_BYTES;
     {
       unsigned char* prow = patch + c32 * P_::PATCH_LD;
@@ -920,7 +1077,8 @@ __global__ __launch_bounds__((Plan<D, WM, WN, KT, PAGED>::THREADS), (Plan<D, WM,
         } else {
           dst = reinterpret_cast<uint16_t*>(p.part_o) + (prow0 + rr) * D;
         }
-        *reinterpret_cast<u32x4*>(dst + chunk * 8) = v;
+        if (p.through & 1) dev::store_through(dst + chunk * 8, v);
+        else *reinterpret_cast<u32x4*>(dst + chunk * 8) = v;
       }
     }
   }
@@ -985,6 +1143,15 @@ hipError_t launch_tva_bf16(const AttnArgs& a, const AttnPlan& pl, hipStream_t st
   kp.tpp = a.block_table ? a.page_size / kTileKeys : 1;
   kp.page_stride = a.page_stride;
   kp.mg_tpp = magic(kp.tpp);
+  // Results written with ordinary stores stay dirty in the XCDs' L2s until the end of the
+  // kernel writes them back.  When the whole grid is resident at once (every workgroup ends
+  // within the same microsecond) that write-back is exposed, and stores that go through to
+  // memory at once measured faster (c3 -0.2 us, c2 -0.65 us per call); with several
+  // workgroups per CU in turn, dirty lines of finished workgroups drain while the others
+  // compute, and ordinary stores measured faster (c4 +0.8 us with write-through).  The small
+  // (max, sum) pairs: through only for the 2x2 arrangement (c2 -0.35 us; c3, 4x1: +0.25 us).
+  const bool one_wave = work <= (long long)device_cu_count();
+  kp.through = (one_wave ? 1 : 0) | (one_wave && pl.wn > 1 ? 2 : 0);
   const int key = (d.head_dim * 1000 + pl.wm * 100 + pl.wn * 10 + pl.kt) * 2 + (a.block_table ? 1 : 0);
 #define JK_CASE(D_, WM_, WN_, KT_)                                                                  \
   case ((D_) * 1000 + (WM_) * 100 + (WN_) * 10 + (KT_)) * 2: return launch_one<D_, WM_, WN_, KT_, false>(kp, stream); \

@@ -4,6 +4,7 @@
 // which is the same softmax-weighted sum the unsplit definition gives
 // (Section 2.1 step 2 of the paper defines the result; the split is an
 // implementation device of this library).
+#include "jk_device.h"
 #include "jk_internal.h"
 
 namespace jk {
@@ -217,7 +218,7 @@ __global__ __launch_bounds__(256) void tva_combine_bf16_kernel(CParams p) {
     bf16x2 o;
     o[0] = (__bf16)(acc0 * inv);
     o[1] = (__bf16)(acc1 * inv);
-    *reinterpret_cast<unsigned*>(dst) = __builtin_bit_cast(unsigned, o);
+    dev::store_through(dst, __builtin_bit_cast(unsigned, o));  // through to memory: nothing here reads it again
   } else {
     const __bf16 o = (__bf16)(acc0 * inv);
     *dst = __builtin_bit_cast(uint16_t, o);
