@@ -63,12 +63,6 @@ constexpr int kWaveRows = 32;   // query rows per wave
 #ifndef JK_SPREAD
 #define JK_SPREAD 1
 #endif
-#ifndef JK_VFB
-#define JK_VFB 0
-#endif
-#ifndef JK_VAE
-#define JK_VAE 0
-#endif
 constexpr int kSpread = JK_SPREAD;  // score phases of a pipelined tile pair that carry the next round's transfers (0: none)
 
 struct KParams {
@@ -177,12 +171,24 @@ template <int D, int NW>
 struct LaneChunks {
   static constexpr int N = 2 * Geo<D>::NB / NW;
   static_assert(N >= 1 && Geo<D>::NB % N == 0, "a wave's transfers stay within K or within V");
-  int row[N];             // tile row
-  unsigned col_b[N];      // byte offset of the chunk inside the row
   unsigned off[N];        // byte offset of the chunk from the first row of a full cache tile
   unsigned lds[N];        // byte offset inside the K+V tile pair
   const uint16_t* cache;  // K or V cache of this (sequence, KV head), wave-uniform
   const uint16_t* tree;   // K or V of the tree
+  int wave, lane;
+  // tile row and byte offset inside the row of chunk i: recomputed where the rare clamped
+  // transfers need them rather than held in registers across the tile loop
+  __device__ __forceinline__ void where(int i, int& row, unsigned& col_b) const {
+    using G_ = Geo<D>;
+    constexpr int RPB = 64 / G_::CPR;
+    const int is_v = (wave * N) / G_::NB;
+    const int blk = (wave * N + i) % G_::NB;
+    row = blk * RPB + lane / G_::CPR;
+    const int pc = lane % G_::CPR;
+    const int kcol = pc ^ G_::kswz(row);                                  // K: 16-byte chunks swizzled
+    const int vcol = (((pc >> 2) ^ G_::vswz(row)) << 2) | (pc & 3);       // V: 64-byte blocks swizzled
+    col_b = (unsigned)(is_v ? vcol : kcol) * 16u;
+  }
 };
 
 template <int D, int NW>
@@ -195,16 +201,15 @@ __device__ __forceinline__ void lane_chunks(LaneChunks<D, NW>& lc, int wave, int
   const int is_v = (wave * N) / G_::NB;
   lc.cache = uniform_ptr(is_v ? vc : kc);
   lc.tree = uniform_ptr(is_v ? vt : kt);
+  lc.wave = wave;
+  lc.lane = lane;
 #pragma unroll
   for (int i = 0; i < N; ++i) {
     const int blk = (wave * N + i) % G_::NB;
-    const int row = blk * RPB + lane / G_::CPR;
-    const int pc = lane % G_::CPR;
-    const int kcol = pc ^ G_::kswz(row);                                  // K: 16-byte chunks swizzled
-    const int vcol = (((pc >> 2) ^ G_::vswz(row)) << 2) | (pc & 3);       // V: 64-byte blocks swizzled
-    lc.row[i] = row;
-    lc.col_b[i] = (unsigned)(is_v ? vcol : kcol) * 16u;
-    lc.off[i] = (unsigned)row * (unsigned)ts.kc_sl * 2u + lc.col_b[i];  // < 2^31: strides are bounded by the host
+    int row;
+    unsigned col_b;
+    lc.where(i, row, col_b);
+    lc.off[i] = (unsigned)row * (unsigned)ts.kc_sl * 2u + col_b;  // < 2^31: strides are bounded by the host
     lc.lds[i] = is_v * G_::TILE_BYTES + blk * 1024;
   }
 }
@@ -260,8 +265,11 @@ __device__ __forceinline__ void dma_round(int r, const TileSrc& ts, const LaneCh
     const uint16_t* base = tree ? lc.tree + (long long)key0 * rs : prefix_tile_base<PAGED>(ts, lc.cache, t);
 #pragma unroll
     for (int i = 0; i < N; ++i) {
-      const int rr = lc.row[i] < last ? lc.row[i] : last;
-      dma16(base, (unsigned)rr * (unsigned)rs * 2u + lc.col_b[i], dst + lc.lds[i]);
+      int row;
+      unsigned col_b;
+      lc.where(i, row, col_b);
+      const int rr = row < last ? row : last;
+      dma16(base, (unsigned)rr * (unsigned)rs * 2u + col_b, dst + lc.lds[i]);
     }
   }
 }
@@ -475,36 +483,28 @@ __device__ __forceinline__ void lone_tile(WaveState<D>& st, unsigned k_addr, uns
 // would use the two units one after the other.  Here the vector work of one tile is written
 // between the MFMAs of the other:
 //   S(A) | softmax(A) with S(B) | softmax(B) with O += P(A) V(A) | O += P(B) V(B)
-// Each tile updates the running maximum on its own (same lazy rule as softmax_pv).
 template <int D>
 struct PairPipe {
   using G_ = Geo<D>;
   static constexpr int DK = G_::DK, DB = G_::DB;
   static constexpr float kLazy = 8.f;
 
-  // running-maximum update for one tile's scores: returns the reference to subtract; the sum
-  // is rescaled here, the accumulators by rescale() once nothing at the old reference is
-  // still to be added to them
-  static __device__ __forceinline__ float new_reference(WaveState<D>& st, const floatx16& s, float scale_log2,
-                                                        float& alpha, bool& moved) {
+  // The pipelined pair never rescales the accumulators.  A row's reference m is fixed by the
+  // first tile it sees (its maximum) or by the general path (which moves it, lazily, with a
+  // rescale), and probabilities 2^(s - m) are allowed to grow: bf16 and fp32 have eight
+  // exponent bits, so weights up to 2^kFrame lose no precision, and sums over 2^24 keys stay
+  // far below 2^127.  A conditional rescale of the 64 accumulator registers inside the pair
+  // costs the path that skips it a copy of all of them per tile pair (the compiler gives the
+  // rescaled block new registers) and 64 registers of pressure where it sits.  A score more
+  // than 2^kFrame above the reference (about 44 nats: a degenerate softmax) raises `left`;
+  // the workgroup then repeats its whole split on the general path (see the tile loop).
+  static constexpr float kFrame = 64.f;
+  static __device__ __forceinline__ float reference(WaveState<D>& st, const floatx16& s, float scale_log2, bool& left) {
     const float tmax = half_swap_max(max16(s)) * scale_log2;
-    const float m_old = st.m;
-    const bool up = tmax > m_old + kLazy;
-    const float m_ref = up ? tmax : m_old;
-    const float m_use = (m_ref == -INFINITY) ? 0.f : m_ref;
-    alpha = up ? fast_exp2(m_old - m_use) : 1.f;
-    moved = up && (m_old != -INFINITY);
-    st.m = m_ref;
-    st.l *= alpha;
-    return m_use;
-  }
-  static __device__ __forceinline__ void rescale(WaveState<D>& st, float alpha, bool moved) {
-    if (__any(moved)) {
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) st.o[db][i] *= alpha;
-    }
+    const float m = (st.m == -INFINITY) ? tmax : st.m;  // (an unmasked tile of finite scores: tmax is finite)
+    left = left || !(tmax <= m + kFrame);               // (also for NaN)
+    st.m = m;
+    return m;
   }
 
   // two scores -> probabilities (elements 2*i, 2*i+1 of the tile) into their bf16 operand slot
@@ -522,7 +522,7 @@ struct PairPipe {
   // MFMAs of the first SPREAD score phases
   template <int SPREAD, class Pieces>
   static __device__ __forceinline__ void run(WaveState<D>& st, unsigned k_addr, unsigned v_addr, float scale_log2,
-                                             const Pieces& next) {
+                                             const Pieces& next, bool& left) {
     static_assert(DK == 8 || DK == 4, "head_dim 128 or 64");
     constexpr unsigned kNextTile = 2 * G_::TILE_BYTES;  // tile B's K (V) tile follows tile A's K and V
     auto v_frag = [&](unsigned tile_off, int j, int db) {
@@ -530,14 +530,9 @@ struct PairPipe {
     };
     // LDS operands are fetched a whole phase ahead of the MFMAs that use them: a read issued
     // just before its MFMA would expose the LDS latency eight times per phase
-    bf16x8 kf[DK], vfA[2 * DB];
-#if JK_VFB
-    bf16x8 vfB[2 * DB];
-#else
-    bf16x8 (&vfB)[2 * DB] = vfA;
-#endif
+    bf16x8 kf[DK], vfA[2 * DB], vfB[2 * DB];
 
-    // ---- S(A)
+    // ---- S(A), and between its MFMAs the transfers of the next round
     floatx16 sA, sB;
 #pragma unroll
     for (int i = 0; i < 16; ++i) sA[i] = sB[i] = 0.f;
@@ -553,28 +548,19 @@ struct PairPipe {
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int ks = 0; ks < DK; ++ks) kf[ks] = lds_read128((k_addr ^ (ks << 5)) + kNextTile);  // lands while the chain drains
-#if JK_VAE
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int db = 0; db < DB; ++db) vfA[j * DB + db] = v_frag(0, j, db);
-#endif
 
     // ---- softmax(A) between the MFMAs of S(B).  The first half of S(B) is issued ahead of
     // the running-maximum update of A (a chain of dependent vector instructions that waits
     // for the last MFMA of S(A)): the matrix unit works through them meanwhile.
     bf16x8 pA[2], pB[2];
     float lsum = 0.f;
-    float alpha;
-    bool moved;
 #pragma unroll
     for (int ks = 0; ks < DK / 2; ++ks) {
       sB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], st.q[ks], sB, 0, 0, 0);
       if (SPREAD > 1) next.share(DK + ks, DK * SPREAD);
     }
     __builtin_amdgcn_sched_barrier(0);
-    const float mA = new_reference(st, sA, scale_log2, alpha, moved);
-    rescale(st, alpha, moved);
+    const float mA = reference(st, sA, scale_log2, left);
 #pragma unroll
     for (int ks = DK / 2; ks < DK; ++ks) {
       sB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], st.q[ks], sB, 0, 0, 0);
@@ -586,26 +572,22 @@ struct PairPipe {
     st.l += lsum;
     __builtin_amdgcn_sched_barrier(0);
 
-    // ---- softmax(B) between the MFMAs of O += V(A)^T . P(A)^T, in the same way; the V
-    // fragments of B are requested now and arrive under this phase
-#if !JK_VAE
+    // ---- softmax(B) between the MFMAs of O += V(A)^T . P(A)^T, in the same way.  The V
+    // fragments of B are requested with those of A and arrive under this phase.
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int db = 0; db < DB; ++db) vfA[j * DB + db] = v_frag(0, j, db);
-#endif
-#if JK_VFB
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int db = 0; db < DB; ++db) vfB[j * DB + db] = v_frag(kNextTile, j, db);
-#endif
 #pragma unroll
     for (int db = 0; db < DB; ++db)
       st.o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfA[db], pA[0], st.o[db], 0, 0, 0);
     __builtin_amdgcn_sched_barrier(0);
     lsum = 0.f;
-    const float mB = new_reference(st, sB, scale_log2, alpha, moved);  // accumulators: after P(A) V(A) below
+    const float mB = reference(st, sB, scale_log2, left);
 #pragma unroll
     for (int db = 0; db < DB; ++db) {
       st.o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfA[DB + db], pA[1], st.o[db], 0, 0, 0);
@@ -614,13 +596,6 @@ struct PairPipe {
     }
     st.l += lsum;
     __builtin_amdgcn_sched_barrier(0);
-#if !JK_VFB
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int db = 0; db < DB; ++db) vfB[j * DB + db] = v_frag(kNextTile, j, db);
-#endif
-    rescale(st, alpha, moved);
 
     // ---- O += V(B)^T . P(B)^T
 #pragma unroll
@@ -662,7 +637,7 @@ struct Plan {
   static constexpr int UNION_BYTES = RING_BYTES > EPI_BYTES ? RING_BYTES : EPI_BYTES;
   static constexpr int ML_BYTES = NW * kWaveRows * 8;
   static constexpr int PAGES_BYTES = PAGED ? kMaxPagesPerSplit * 4 : 0;
-  static constexpr int SMEM = UNION_BYTES + ML_BYTES + JK_MAX_TREE * 16 + JK_MAX_TREE * 4 + PAGES_BYTES;
+  static constexpr int SMEM = UNION_BYTES + ML_BYTES + JK_MAX_TREE * 16 + JK_MAX_TREE * 4 + 16 + PAGES_BYTES;
   static constexpr int WGS_PER_CU = 2 * SMEM <= 160 * 1024 && NW <= 4 ? 2 : 1;
   static constexpr int REG_WGS = NW <= 4 ? 2 : 1;  // register budget: at most 256 VGPRs, no detour through AGPRs
   static_assert(SMEM <= 160 * 1024, "LDS budget");
@@ -688,7 +663,8 @@ __global__ __launch_bounds__((Plan<D, WM, WN, KT, PAGED>::THREADS), (Plan<D, WM,
   float2* mlbuf = reinterpret_cast<float2*>(smem + P_::UNION_BYTES);              // [WN-1][QROWS]
   unsigned long long* anc = reinterpret_cast<unsigned long long*>(smem + P_::UNION_BYTES + P_::ML_BYTES);  // [128][2]
   int* par_s = reinterpret_cast<int*>(smem + P_::UNION_BYTES + P_::ML_BYTES + JK_MAX_TREE * 16);           // [128]
-  int* pg_s = par_s + JK_MAX_TREE;                                                                         // [1024], paged caches only
+  int* repeat_s = par_s + JK_MAX_TREE;  // set by a wave whose scores left the pipelined pairs' fixed reference frame
+  int* pg_s = repeat_s + 4;             // [1024], paged caches only
 
   JK_TS(0);
   // ---- touch every 64-byte line of the kernel arguments at once: the compiler fetches them
@@ -936,30 +912,41 @@ __global__ __launch_bounds__((Plan<D, WM, WN, KT, PAGED>::THREADS), (Plan<D, WM,
   // (r*WN + wn)*KT .. +KT-1 of the split.  Before the barrier a wave waits for its own
   // transfers of round r; after the barrier every wave's have landed, and every wave has
   // finished round r-1, whose slot is therefore free for round r+NR-1.
+  //
+  // The pipelined pairs work in a fixed reference frame (see PairPipe).  If a score leaves it,
+  // the wave says so in LDS after the loop, and the workgroup runs the loop once more, from
+  // its first round, on the general path only (lazy rescale): rare, and the pairs stay free
+  // of any conditional touch of the accumulators.
+  bool left = false;     // this lane's row left the frame
+  bool general = false;  // uniform: the repeat
+  if (KT == 2 && tid == 0) *repeat_s = 0;  // (read behind the barrier that follows the loop)
+  for (;;) {
   for (int r = 0; r < n_rounds; ++r) {
-    const int ahead = n_rounds - 1 - r;  // rounds issued after r: min(NR-2, ahead)
-    wait_dma<DMA_PER_ROUND>(ahead < NR - 2 ? ahead : NR - 2);
-    __syncthreads();
-    if (r == 0) JK_TS(4);
+    // (what the round will do is worked out in front of the barrier: scalar arithmetic that
+    // would otherwise stand between the barrier and the round's first LDS reads)
     const int tb = ts.t_begin + (r * WN + wn) * KT;
     const unsigned tile_a = ring_addr + (r % NR) * STAGE_BYTES + wn * KT * 2 * TILE_BYTES;  // K of the first tile
-    const bool pair = KT == 2 && (tb + 2) * kTileKeys <= L && tb + 2 <= ts.t_end;  // two full prefix tiles
+    const bool pair = KT == 2 && !general && (tb + 2) * kTileKeys <= L && tb + 2 <= ts.t_end;  // two full prefix tiles
     // the refill of the ring: on its own, or (full prefix tiles behind a pipelined pair)
     // piece by piece between the pair's MFMAs
     RoundPieces<D, NW, TPR> next;
     const int t_next = ts.t_begin + (r + NR - 1) * TPR;
     const bool refill = r + NR - 1 < n_rounds;
     const bool spread = kSpread > 0 && !PAGED && WN == 1 && refill && pair && (t_next + TPR) * kTileKeys <= L;
+    next.tile_elems = (long long)kTileKeys * ts.kc_sl;
+    next.base = lc.cache + (long long)t_next * next.tile_elems;
+    next.slot = ring_addr + ((r + NR - 1) % NR) * STAGE_BYTES;
+    next.lc = &lc;
+    const int ahead = n_rounds - 1 - r;  // rounds issued after r: min(NR-2, ahead)
+    wait_dma<DMA_PER_ROUND>(ahead < NR - 2 ? ahead : NR - 2);
+    __syncthreads();
+    if (r == 0) JK_TS(4);
     if (refill && !spread) dma_round<D, NW, TPR, PAGED>(r + NR - 1, ts, lc, ring_addr + ((r + NR - 1) % NR) * STAGE_BYTES);
     if (pair && spread) {
-      next.tile_elems = (long long)kTileKeys * ts.kc_sl;
-      next.base = lc.cache + (long long)t_next * next.tile_elems;
-      next.slot = ring_addr + ((r + NR - 1) % NR) * STAGE_BYTES;
-      next.lc = &lc;
-      PairPipe<D>::template run<kSpread>(st, tile_a + k_lane, tile_a + TILE_BYTES + v_lane, scale_log2, next);
+      PairPipe<D>::template run<kSpread>(st, tile_a + k_lane, tile_a + TILE_BYTES + v_lane, scale_log2, next, left);
     } else if (pair) {
-      PairPipe<D>::template run<0>(st, tile_a + k_lane, tile_a + TILE_BYTES + v_lane, scale_log2, next);
-    } else if (KT == 2 && WN == 1 && tb + 1 == ts.t_end && (tb + 1) * kTileKeys <= L) {
+      PairPipe<D>::template run<0>(st, tile_a + k_lane, tile_a + TILE_BYTES + v_lane, scale_log2, next, left);
+    } else if (KT == 2 && WN == 1 && !general && tb + 1 == ts.t_end && (tb + 1) * kTileKeys <= L) {
       lone_tile<D>(st, tile_a + k_lane, tile_a + TILE_BYTES + v_lane, scale_log2);  // no mask, half the work
     } else if (tb < ts.t_end) {
       int mode, nvalid;
@@ -975,16 +962,35 @@ __global__ __launch_bounds__((Plan<D, WM, WN, KT, PAGED>::THREADS), (Plan<D, WM,
       softmax_pv<D, KT>(st, s0, s1, tile_a + TILE_BYTES + v_lane, scale_log2);
     }
   }
+  if (KT == 2 && !general && left) *repeat_s = 1;
   JK_TS(5);
-  __syncthreads();  // every wave is done with the ring before it becomes the epilogue buffer
+  __syncthreads();  // every wave is done with the ring before it becomes the epilogue buffer (or is filled again)
+  if (KT != 2 || general || __builtin_amdgcn_readfirstlane(*repeat_s) == 0) break;
+  general = true;
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) st.o[db][i] = 0.f;
+  st.m = -INFINITY;
+  st.l = 0.f;
+#pragma unroll
+  for (int r = 0; r < NR - 1; ++r)
+    if (r < n_rounds) dma_round<D, NW, TPR, PAGED>(r, ts, lc, ring_addr + r * STAGE_BYTES);
+  }
 
   // ---- epilogue: the waves of key column 0 own the result of their 32 rows.  The other
   // columns park their O^T and (max, sum) in LDS (the ring is dead by now); the owners fold
   // them into their own accumulators, register for register (all waves share one layout),
   // and store straight from that layout: lane (row, g) holds, per 32-wide block db and
   // quarter q4, the 4 columns 32*db + 8*q4 + 4*g .. +3 of its row.
+  // (the lane's indices are worked out afresh, from the execution mask: kept in registers
+  // across the tile loop, which has none to spare, they - or the thread id they come from -
+  // are spilled to memory and read back here)
+  const int lane_e = __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+  const int c32_e = lane_e & 31, g_e = lane_e >> 5;
+  const bool row_ok_e = qtile * QROWS + wm * kWaveRows + c32_e < M;
   const float l_own = half_swap_sum(st.l);
-  const int row = wm * kWaveRows + c32;
+  const int row = wm * kWaveRows + c32_e;
   if (wn != 0) {
     float* orow = obuf + ((size_t)(wn - 1) * QROWS + row) * G_::O_LD;
 #pragma unroll
@@ -992,9 +998,9 @@ __global__ __launch_bounds__((Plan<D, WM, WN, KT, PAGED>::THREADS), (Plan<D, WM,
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4) {
         float4 v = make_float4(st.o[db][4 * q4], st.o[db][4 * q4 + 1], st.o[db][4 * q4 + 2], st.o[db][4 * q4 + 3]);
-        *reinterpret_cast<float4*>(orow + 32 * db + 8 * q4 + 4 * g) = v;
+        *reinterpret_cast<float4*>(orow + 32 * db + 8 * q4 + 4 * g_e) = v;
       }
-    if (g == 0) mlbuf[(wn - 1) * QROWS + row] = make_float2(st.m, l_own);
+    if (g_e == 0) mlbuf[(wn - 1) * QROWS + row] = make_float2(st.m, l_own);
   }
   if (WN > 1) __syncthreads();
   JK_TS(6);
@@ -1021,7 +1027,7 @@ __global__ __launch_bounds__((Plan<D, WM, WN, KT, PAGED>::THREADS), (Plan<D, WM,
         for (int db = 0; db < DB; ++db)
 #pragma unroll
           for (int q4 = 0; q4 < 4; ++q4) {
-            const float4 v = *reinterpret_cast<const float4*>(orow + 32 * db + 8 * q4 + 4 * g);
+            const float4 v = *reinterpret_cast<const float4*>(orow + 32 * db + 8 * q4 + 4 * g_e);
             st.o[db][4 * q4] = fmaf(v.x, wgt, st.o[db][4 * q4]);
             st.o[db][4 * q4 + 1] = fmaf(v.y, wgt, st.o[db][4 * q4 + 1]);
             st.o[db][4 * q4 + 2] = fmaf(v.z, wgt, st.o[db][4 * q4 + 2]);
@@ -1038,13 +1044,13 @@ __global__ __launch_bounds__((Plan<D, WM, WN, KT, PAGED>::THREADS), (Plan<D, WM,
     // split, and are the largest avoidable traffic of a call.
     const float mul = splits == 1 ? 1.f / lsum : 1.f;  // lsum > 0: every row sees at least its own tree key
     const long long prow0 = ((long long)unit_id * splits + split) * p.m_pad + qtile * QROWS + wm * kWaveRows;
-    if (splits > 1 && row_ok && g == 0) {
-      if (p.through & 2) dev::store_through(p.part_ml + prow0 + c32, dev::store_u32x2{__float_as_uint(mx), __float_as_uint(lsum)});
-      else p.part_ml[prow0 + c32] = make_float2(mx, lsum);
+    if (splits > 1 && row_ok_e && g_e == 0) {
+      if (p.through & 2) dev::store_through(p.part_ml + prow0 + c32_e, dev::store_u32x2{__float_as_uint(mx), __float_as_uint(lsum)});
+      else p.part_ml[prow0 + c32_e] = make_float2(mx, lsum);
     }
     unsigned char* patch = smem + P_::OBUF_BYTES + wm * P_::PATCH_BYTES;
     {
-      unsigned char* prow = patch + c32 * P_::PATCH_LD;
+      unsigned char* prow = patch + c32_e * P_::PATCH_LD;
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -1057,13 +1063,13 @@ __global__ __launch_bounds__((Plan<D, WM, WN, KT, PAGED>::THREADS), (Plan<D, WM,
           uint2 pk;
           pk.x = __builtin_bit_cast(unsigned int, lo);
           pk.y = __builtin_bit_cast(unsigned int, hi);
-          *reinterpret_cast<uint2*>(prow + (32 * db + 8 * q4 + 4 * g) * 2) = pk;
+          *reinterpret_cast<uint2*>(prow + (32 * db + 8 * q4 + 4 * g_e) * 2) = pk;
         }
     }
     // (same wave wrote and reads: LDS operations of a wave complete in order)
     constexpr int CPR = G_::CPR;             // 16-byte chunks per row
     constexpr int RPI = 64 / CPR;            // rows per store instruction
-    const int chunk = lane % CPR, rsub = lane / CPR;
+    const int chunk = lane_e % CPR, rsub = lane_e / CPR;
 #pragma unroll
     for (int k = 0; k < kWaveRows / RPI; ++k) {
       const int rr = k * RPI + rsub;                               // row of the wave

@@ -95,6 +95,32 @@ def test_bf16_peaked_softmax():
     check_attention(x, par, [600], "bf16", BF16_TOL, rel_tol=2e-2)
 
 
+@pytest.mark.parametrize("where", [40, 1500, 2999])
+@pytest.mark.parametrize("splits", ["1", "3", ""])
+def test_bf16_outlier_key_far_above_everything_before_it(monkeypatch, where, splits):
+    """One key whose score for one query row lies about 130 binary orders of magnitude above the
+    rest (a multiple of that row's own query vector).  The two-tile fast path of the 4x1 arrangement
+    keeps a fixed reference per row and cannot hold such a jump when the key comes late: the
+    workgroup has to notice and repeat its split on the general path.  Early (first tile), in the
+    middle and in the last full tile of the prefix; one split, three, and the planner's choice."""
+    if splits:
+        monkeypatch.setenv("JK_ATTN_SPLITS", splits)
+    monkeypatch.setenv("JK_ATTN_WM", "4")
+    monkeypatch.setenv("JK_ATTN_WN", "1")
+    cfg = _cfg("c3_llama3_8b", prefix_len=3008, n_q_heads=8, n_kv_heads=2)
+    par = tree_for_config(cfg)
+    x = attention_inputs(cfg, seed=where, scale_mult=np.sqrt(128.0))
+    node, head = 7, 5                                   # query row of KV head 1
+    x["k_cache"][0, where, 1] = round_to_bf16(8.0 * x["q"][0, node, head])
+    # (rows with a near one-hot softmax return single V rows, entries up to about 4.5: the bf16 roundings
+    # of the split partial and of the result, 2^-8 relative each, exceed the absolute bound of the
+    # averaged rows, so the absolute bound here is 2^-7 of that magnitude; the relative one stays)
+    got, ref = check_attention(x, par, [3008], "bf16", 2.0 ** -7 * 4.5, rel_tol=1.5e-2)
+    # that row's softmax is one-hot on the planted key
+    v = x["v_cache"][0, where, 1].astype(np.float64)
+    assert np.abs(got[0, node, head] - v).max() <= 2.0 ** -7 * np.abs(v).max() + 1e-6
+
+
 def test_bf16_custom_scale_and_strided_cache():
     import paper_2502_06282_amd as jk
     from oracle import tree_verify_attention as oracle_attention
