@@ -441,42 +441,6 @@ __device__ __forceinline__ void softmax_pv(WaveState<D>& st, const floatx16& s0,
       }
 }
 
-// One unmasked tile on its own (the odd last tile of a split: everybody else waits for the
-// splits that have one).  All LDS operands are requested before the first MFMA, the K
-// fragments first: the V fragments then arrive under the score product and the softmax
-// instead of in front of the value product.
-template <int D>
-__device__ __forceinline__ void lone_tile(WaveState<D>& st, unsigned k_addr, unsigned v_addr, float scale_log2) {
-  using G_ = Geo<D>;
-  constexpr int DK = G_::DK, DB = G_::DB;
-  bf16x8 kf[DK], vf[2 * DB];
-#pragma unroll
-  for (int ks = 0; ks < DK; ++ks) kf[ks] = lds_read128(k_addr ^ (ks << 5));
-#pragma unroll
-  for (int j = 0; j < 2; ++j)
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-      vf[j * DB + db] = lds_read_tr2((v_addr ^ (db << 6)) + 16 * j * G_::ROW_BYTES, 8 * G_::ROW_BYTES);
-  __builtin_amdgcn_sched_barrier(0);
-  floatx16 a0, a1, s0;
-#pragma unroll
-  for (int i = 0; i < 16; ++i) a0[i] = a1[i] = 0.f;
-#pragma unroll
-  for (int ks = 0; ks < DK; ks += 2) {  // two chains: a dependent MFMA issues only every other slot
-    a0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], st.q[ks], a0, 0, 0, 0);
-    a1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks + 1], st.q[ks + 1], a1, 0, 0, 0);
-  }
-#pragma unroll
-  for (int i = 0; i < 16; ++i) s0[i] = a0[i] + a1[i];
-  bf16x8 pb[2];
-  softmax_probs<D, 1>(st, s0, s0, scale_log2, pb);
-#pragma unroll
-  for (int j = 0; j < 2; ++j)
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-      st.o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[j * DB + db], pb[j], st.o[db], 0, 0, 0);
-}
-
 // Two unmasked tiles A, B of a round, software-pipelined by hand.  Within one tile the score
 // product (MFMA), the softmax (vector ALU, a quarter-rate exponential per score) and the
 // value product (MFMA) depend on each other, and a lone wave on its SIMD issues in order: it
@@ -605,6 +569,50 @@ struct PairPipe {
         st.o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfB[j * DB + db], pB[j], st.o[db], 0, 0, 0);
   }
 };
+
+// One unmasked tile on its own: the odd last tile of a split of the 4x1 arrangement (everybody
+// else waits for the splits that have one).  All LDS operands are requested before the first
+// MFMA, the K fragments first: the V fragments then arrive under the score product and the
+// softmax instead of in front of the value product.  Same fixed reference frame as the
+// pipelined pair: no rescale of the accumulators here.  (For the one-tile rounds of the 2x2
+// arrangement this path measured slower than the general one - 63 registers more, and those
+// shapes are not bound by the tile arithmetic.)
+template <int D>
+__device__ __forceinline__ void lone_tile(WaveState<D>& st, unsigned k_addr, unsigned v_addr, float scale_log2,
+                                          bool& left) {
+  using G_ = Geo<D>;
+  constexpr int DK = G_::DK, DB = G_::DB;
+  bf16x8 kf[DK], vf[2 * DB];
+#pragma unroll
+  for (int ks = 0; ks < DK; ++ks) kf[ks] = lds_read128(k_addr ^ (ks << 5));
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+      vf[j * DB + db] = lds_read_tr2((v_addr ^ (db << 6)) + 16 * j * G_::ROW_BYTES, 8 * G_::ROW_BYTES);
+  __builtin_amdgcn_sched_barrier(0);
+  floatx16 a0, a1, s0;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) a0[i] = a1[i] = 0.f;
+#pragma unroll
+  for (int ks = 0; ks < DK; ks += 2) {  // two chains: a dependent MFMA issues only every other slot
+    a0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], st.q[ks], a0, 0, 0, 0);
+    a1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks + 1], st.q[ks + 1], a1, 0, 0, 0);
+  }
+#pragma unroll
+  for (int i = 0; i < 16; ++i) s0[i] = a0[i] + a1[i];
+  const float m = PairPipe<D>::reference(st, s0, scale_log2, left);
+  bf16x8 pb[2];
+  float lsum = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) PairPipe<D>::two_probs(s0, i, scale_log2, m, lsum, pb);
+  st.l += lsum;
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+      st.o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[j * DB + db], pb[j], st.o[db], 0, 0, 0);
+}
 
 // Profiling build only (-DJK_TIMING, not part of the shipped library): thread 0 of every
 // workgroup records the 100 MHz wall clock at eight points of the kernel (entry, speculative
@@ -947,7 +955,7 @@ __global__ __launch_bounds__((Plan<D, WM, WN, KT, PAGED>::THREADS), (Plan<D, WM,
     } else if (pair) {
       PairPipe<D>::template run<0>(st, tile_a + k_lane, tile_a + TILE_BYTES + v_lane, scale_log2, next, left);
     } else if (KT == 2 && WN == 1 && !general && tb + 1 == ts.t_end && (tb + 1) * kTileKeys <= L) {
-      lone_tile<D>(st, tile_a + k_lane, tile_a + TILE_BYTES + v_lane, scale_log2);  // no mask, half the work
+      lone_tile<D>(st, tile_a + k_lane, tile_a + TILE_BYTES + v_lane, scale_log2, left);  // no mask, half the work
     } else if (tb < ts.t_end) {
       int mode, nvalid;
       unsigned int bits;
