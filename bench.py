@@ -98,6 +98,9 @@ def main():
     ap.add_argument("--no-draft-heads", action="store_true", help="skip the jk_draft_heads timing (extra field)")
     ap.add_argument("--draft-rows", type=int, default=0, help="hidden states per jk_draft_heads call "
                     "(default: 10 per sequence of the workload)")
+    ap.add_argument("--kv-layout", choices=("token", "head"), default="token",
+                    help="storage order of the K/V caches: [B, L, Hkv, D] (token-major, the default) or "
+                    "[B, Hkv, L, D] (head-major: each KV head's stream contiguous), passed through the strides")
     ap.add_argument("--no-graph", action="store_true", help="issue every library call from Python instead of "
                     "replaying the step's two HIP graphs")
     ap.add_argument("--copy-calibration", type=int, default=0,
@@ -129,6 +132,9 @@ def main():
         if l == 0:
             x0 = x
         layers.append({k: torch.from_numpy(v).to(dev).to(tdt) for k, v in x.items()})
+        if args.kv_layout == "head":
+            for name in ("k_cache", "v_cache"):
+                layers[-1][name] = layers[-1][name].permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
     acc = accept_inputs(cfg, par)
     mode = jk.JK_GREEDY if cfg.mode == "greedy" else jk.JK_SAMPLE
     tokens = torch.from_numpy(acc["tokens"]).to(dev)
