@@ -451,8 +451,6 @@ template <int D>
 struct PairPipe {
   using G_ = Geo<D>;
   static constexpr int DK = G_::DK, DB = G_::DB;
-  static constexpr float kLazy = 8.f;
-
   // The pipelined pair never rescales the accumulators.  A row's reference m is fixed by the
   // first tile it sees (its maximum) or by the general path (which moves it, lazily, with a
   // rescale), and probabilities 2^(s - m) are allowed to grow: bf16 and fp32 have eight
