@@ -378,11 +378,28 @@ def main():
             tree_pass()
         et1.record()
         torch.cuda.synchronize()
-        draft["tree_build"] = {"us_per_round": round(et0.elapsed_time(et1) * 1e3 / 10, 1), "depths": 3,
-                               "nodes_kept": cfg.n_tree,
-                               "note": "3 jk_tree_grow + jk_tree_finalize + jk_gather_draft_probs, eager launches "
-                                       "(includes torch's output allocations)"}
-        del tg_q
+        eager_us = et0.elapsed_time(et1) * 1e3 / 10
+        # the same round as one HIP graph (what a serving loop would replay): launch gaps instead of
+        # Python and allocator time between the seven small kernels
+        ref_q = tree_pass()
+        torch.cuda.synchronize()
+        g_tree = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g_tree, stream=torch.cuda.Stream()):
+            graph_q = tree_pass()
+        g_tree.replay()
+        torch.cuda.synchronize()
+        if not torch.equal(graph_q, ref_q):
+            sys.exit("bench.py: the captured tree build differs from the eager one")
+        et0.record()
+        for _ in range(10):
+            g_tree.replay()
+        et1.record()
+        torch.cuda.synchronize()
+        draft["tree_build"] = {"us_per_round": round(et0.elapsed_time(et1) * 1e3 / 10, 1),
+                               "us_per_round_eager": round(eager_us, 1), "depths": 3, "nodes_kept": cfg.n_tree,
+                               "note": "3 jk_tree_grow + jk_tree_finalize + jk_gather_draft_probs; HIP-graph replay, "
+                                       "and eager launches (which include torch's output allocations)"}
+        del tg_q, graph_q, ref_q, g_tree
 
     for _ in range(args.copy_calibration):
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)

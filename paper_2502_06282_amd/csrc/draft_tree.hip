@@ -27,12 +27,32 @@ __device__ __forceinline__ int beats(float av, int ai, float bv, int bi) {
   return (int)(av > bv) | ((int)(av == bv) & (int)(ai < bi));
 }
 
+// How many threads with a smaller index raised `flag`, and how many did in all: ballots within
+// the waves, the four wave totals through LDS (s_cnt: kTreeThreads / 64 ints; the caller's
+// later use of it must follow a barrier).
+__device__ __forceinline__ int count_before(bool flag, int t, int* s_cnt, int& total) {
+  const unsigned long long m = __ballot(flag);
+  const int lane = t & 63, wave = t >> 6;
+  const int in_wave = __popcll(m & ((1ull << lane) - 1ull));
+  if (lane == 0) s_cnt[wave] = __popcll(m);
+  __syncthreads();
+  int before = in_wave;
+  total = 0;
+#pragma unroll
+  for (int w = 0; w < kTreeThreads / 64; ++w) {
+    const int c = s_cnt[w];
+    before += w < wave ? c : 0;
+    total += c;
+  }
+  return before;
+}
+
 __global__ __launch_bounds__(kTreeThreads) void grow_kernel(TreeGrowArgs a) {
   __shared__ float s_sc[kTreeThreads];
-  __shared__ int s_sel[kTreeThreads];
+  __shared__ int s_cnt[kTreeThreads / 64];
   __shared__ int s_first;
   const int b = blockIdx.x, t = threadIdx.x;
-  const int C = a.n_front * 2 * a.top_k;
+  const int C = a.n_front * 2 * a.top_k;  // <= kTreeThreads (checked by the host)
   const int n0 = min(max(a.n_nodes[b], 0), a.max_nodes);  // (a count the caller forgot to clear must not fault)
   const int id = n0 + t;
   const bool valid = t < C && id < a.max_nodes;
@@ -53,18 +73,12 @@ __global__ __launch_bounds__(kTreeThreads) void grow_kernel(TreeGrowArgs a) {
   s_sc[t] = sc;
   if (t == 0) s_first = INT_MAX;
   __syncthreads();
-  int rank = 0;
+  int rank = 0;  // (entries from C on hold -inf and a larger index: they beat nobody)
 #pragma unroll 8
-  for (int i = 0; i < kTreeThreads; ++i) rank += beats(s_sc[i], i, sc, t);
-  const int sel = (valid && rank < a.width) ? 1 : 0;
-  s_sel[t] = sel;
-  __syncthreads();
-  int slot = 0;
-#pragma unroll 8
-  for (int i = 0; i < kTreeThreads; ++i) slot += (i < t) ? s_sel[i] : 0;
-  int total = 0;
-#pragma unroll 8
-  for (int i = 0; i < kTreeThreads; ++i) total += s_sel[i];
+  for (int i = 0; i < C; ++i) rank += beats(s_sc[i], i, sc, t);
+  const bool sel = valid && rank < a.width;
+  int total;
+  const int slot = count_before(sel, t, s_cnt, total);
   if (sel) {
     a.frontier_out[(long long)b * a.width + slot] = id;
     if (slot == 0) s_first = id;
@@ -79,7 +93,7 @@ __global__ __launch_bounds__(kTreeThreads) void grow_kernel(TreeGrowArgs a) {
 // head 0's list, then the `width` best children get head 1's list of their parent as children.
 __global__ __launch_bounds__(kTreeThreads) void grow_tail_kernel(TreeGrowArgs a, int k1, int k2) {
   __shared__ float s_sc[kTreeThreads];
-  __shared__ int s_sel[kTreeThreads];
+  __shared__ int s_cnt[kTreeThreads / 64];
   __shared__ int s_child[kTreeThreads];  // chosen children by slot: node id, frontier slot
   __shared__ int s_slot_f[kTreeThreads];
   const int b = blockIdx.x, t = threadIdx.x;
@@ -105,16 +119,10 @@ __global__ __launch_bounds__(kTreeThreads) void grow_tail_kernel(TreeGrowArgs a,
   __syncthreads();
   int rank = 0;
 #pragma unroll 8
-  for (int i = 0; i < kTreeThreads; ++i) rank += beats(s_sc[i], i, sc, t);
-  const int sel = (valid && rank < a.width) ? 1 : 0;
-  s_sel[t] = sel;
-  __syncthreads();
-  int slot = 0, total = 0;
-#pragma unroll 8
-  for (int i = 0; i < kTreeThreads; ++i) {
-    slot += (i < t) ? s_sel[i] : 0;
-    total += s_sel[i];
-  }
+  for (int i = 0; i < C; ++i) rank += beats(s_sc[i], i, sc, t);
+  const bool sel = valid && rank < a.width;
+  int total;
+  const int slot = count_before(sel, t, s_cnt, total);
   if (sel) {
     s_child[slot] = id;
     s_slot_f[slot] = f;
@@ -176,6 +184,7 @@ __global__ __launch_bounds__(kTreeThreads) void finalize_kernel(TreeFinalArgs a)
   __shared__ float s_sc[kMaxGrowNodes];
   __shared__ short s_keep[kMaxGrowNodes];
   __shared__ short s_new[kMaxGrowNodes];
+  __shared__ int s_cnt[kTreeThreads / 64];
   const int b = blockIdx.x, t = threadIdx.x;
   const int n = min(max(a.n_nodes[b], 0), a.max_nodes);
   const long long base = (long long)b * a.max_nodes;
@@ -191,13 +200,15 @@ __global__ __launch_bounds__(kTreeThreads) void finalize_kernel(TreeFinalArgs a)
     s_keep[i] = (i < n && rank < a.n_keep) ? 1 : 0;
   }
   __syncthreads();
-  for (int i = t; i < n; i += kTreeThreads) {
-    int before = 0;
-#pragma unroll 8
-    for (int j = 0; j < i; ++j) before += s_keep[j];
-    s_new[i] = (short)before;
+  int carried = 0;  // kept nodes in the chunks before this one (the same in every thread)
+  for (int i0 = 0; i0 < n; i0 += kTreeThreads) {
+    const int i = i0 + t;
+    int total;
+    const int before = count_before(i < n && s_keep[i], t, s_cnt, total);
+    if (i < n) s_new[i] = (short)(carried + before);
+    carried += total;
+    __syncthreads();  // s_cnt is written again by the next chunk
   }
-  __syncthreads();
   for (int i = t; i < n; i += kTreeThreads) {
     if (!s_keep[i]) continue;
     const long long o = (long long)b * a.n_keep + s_new[i];
