@@ -124,6 +124,20 @@ def test_bf16_outlier_key_far_above_everything_before_it(monkeypatch, where, spl
     assert np.abs(got[0, node, head] - v).max() <= 2.0 ** -7 * np.abs(v).max() + 1e-6
 
 
+def test_bf16_outlier_key_head_dim_64(monkeypatch):
+    """The same repeat on the general path with 64-wide heads (half as many MFMAs per phase)."""
+    monkeypatch.setenv("JK_ATTN_WM", "4")
+    monkeypatch.setenv("JK_ATTN_WN", "1")
+    cfg = _cfg("c3_llama3_8b", prefix_len=1100, n_q_heads=8, n_kv_heads=2, head_dim=64)
+    par = tree_for_config(cfg)
+    x = attention_inputs(cfg, seed=5, scale_mult=np.sqrt(64.0))
+    node, head = 3, 1
+    x["k_cache"][0, 900, 0] = round_to_bf16(12.0 * x["q"][0, node, head])
+    got, ref = check_attention(x, par, [1100], "bf16", 3 * 2.0 ** -9 * 4.5, rel_tol=1.5e-2)
+    v = x["v_cache"][0, 900, 0].astype(np.float64)
+    assert np.abs(got[0, node, head] - v).max() <= 2.0 ** -7 * np.abs(v).max() + 1e-6
+
+
 def test_bf16_custom_scale_and_strided_cache():
     import paper_2502_06282_amd as jk
     from oracle import tree_verify_attention as oracle_attention

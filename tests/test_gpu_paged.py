@@ -48,6 +48,34 @@ def test_paged_attention_matches_oracle_and_contiguous(monkeypatch, wm, wn, page
         assert torch.equal(got, cont)          # same arithmetic in the same order, only the addresses differ
 
 
+def test_paged_attention_repeats_a_split_that_leaves_the_fixed_frame(monkeypatch):
+    """A late key far above everything before it for one query row: the two-tile fast path of the 4x1
+    arrangement gives up and the workgroup streams its split again on the general path, through the page
+    table once more.  Bitwise equal to the contiguous call, which takes the same decisions."""
+    monkeypatch.setenv("JK_ATTN_WM", "4")
+    monkeypatch.setenv("JK_ATTN_WN", "1")
+    monkeypatch.setenv("JK_ATTN_SPLITS", "2")
+    cfg = CONFIGS["c3_llama3_8b"].with_(batch=1, prefix_len=2048, n_q_heads=8, n_kv_heads=2)
+    par = tree_for_config(cfg, seed=3)
+    x = {k: round_to_bf16(v) for k, v in attention_inputs(cfg, seed=3, scale_mult=np.sqrt(128.0)).items()}
+    x["k_cache"][0, 1777, 0] = round_to_bf16(8.0 * x["q"][0, 11, 2])
+    (kp, vp), table = paged_layout(x["k_cache"], x["v_cache"], 64, seed=3)
+    ref = oracle_attention(**x, parent=par, prefix_len=[2048])
+    parent = torch.from_numpy(par).cuda()
+    pl = torch.tensor([2048], dtype=torch.int32).cuda()
+    got = jk.tree_verify_attention_paged(_dev(x["q"]), _dev(kp), _dev(vp), torch.from_numpy(table).cuda(),
+                                         _dev(x["k_tree"]), _dev(x["v_tree"]), parent, pl, max_prefix_len=2048)
+    cont = jk.tree_verify_attention(_dev(x["q"]), _dev(x["k_cache"]), _dev(x["v_cache"]), _dev(x["k_tree"]),
+                                    _dev(x["v_tree"]), parent, pl, max_prefix_len=2048)
+    torch.cuda.synchronize()
+    g = got.float().cpu().numpy()
+    assert np.isfinite(g).all()
+    assert np.abs(g - ref).max() <= 3 * 2.0 ** -9 * 4.5 and np.abs(g - ref).max() <= 1.5e-2 * np.abs(ref).max()
+    v = x["v_cache"][0, 1777, 0].astype(np.float64)
+    assert np.abs(g[0, 11, 2] - v).max() <= 2.0 ** -7 * np.abs(v).max() + 1e-6
+    assert torch.equal(got, cont)
+
+
 def test_paged_attention_full_size_c3():
     cfg = CONFIGS["c3_llama3_8b"]
     par, x, kp, vp, table = _paged_case(cfg, 128, cfg.prefix_len)
