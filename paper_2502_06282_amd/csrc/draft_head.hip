@@ -89,11 +89,14 @@ struct GemmParams {
   float* y;           // [m][ldy]
   int m, n, k;
   long long ldw, ldy;
-  // batch (blockIdx.y): element offsets between consecutive problems; `used` (device, may be null)
-  // switches single problems off
+  // batch (blockIdx.y): element offsets between consecutive problems; `sel` (device, may be null):
+  // n_sel problem numbers, a problem that none of them names is switched off (the experts no
+  // row selected; every workgroup scans the list itself: at most 256 entries, and no flag array
+  // that a launch of its own would have to clear first)
   int batch;
   long long x_batch, w_batch, y_batch;
-  const int* used;
+  const int* sel;
+  int n_sel;
   // a second weight tensor over the same X (the experts' gate and up projections in one launch):
   // blockIdx.y in [batch, 2 batch) takes w2 / y2
   const uint16_t* w2;
@@ -164,7 +167,11 @@ __global__ __launch_bounds__(kGemmThreads, 1) void skinny_gemm_kernel(GemmParams
     p.w = p.w2;
     p.y = p.y2;
   }
-  if (p.used && p.used[e] == 0) return;  // (the whole workgroup: nobody waits at a barrier)
+  if (p.sel) {  // every wave scans the whole list itself: the same answer in all of them, no LDS, no barrier
+    int mine = 0;
+    for (int i = threadIdx.x & 63; i < p.n_sel; i += 64) mine |= (int)(p.sel[i] == e);
+    if (!__any(mine)) return;  // (the whole workgroup: nobody waits at a later barrier)
+  }
   p.x += (long long)e * p.x_batch;
   p.w += (long long)e * p.w_batch;
   p.y += (long long)e * p.y_batch + (long long)blockIdx.z * p.y_split;
@@ -647,17 +654,12 @@ struct RouterParams {
   uint16_t* x;                // [rows padded to 32][d] bf16: copy of u, zero rows behind it
   float* s_top;               // [rows][2]
   int* idx;                   // [rows][2]
-  int* used;                  // [n_experts], zeroed by clear_flags_kernel before
   int rows, d, n_experts;
 };
 
-__global__ void clear_flags_kernel(int* used, int n) {
-  if ((int)threadIdx.x < n) used[threadIdx.x] = 0;
-}
-
 // One workgroup per (padded) row: copies the row into the GEMM's padded input, and for real rows
 // computes the router scores s_j = softmax_j(u . e_j) (Eq. 2; fp32), picks the two largest (Eq. 5,
-// K = 2, ties to the lower expert) and flags the chosen experts as used.
+// K = 2, ties to the lower expert).
 __global__ __launch_bounds__(256) void router_kernel(RouterParams p) {
   __shared__ float score[kMaxExperts];
   const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -668,18 +670,29 @@ __global__ __launch_bounds__(256) void router_kernel(RouterParams p) {
   }
   const u32x4* src = reinterpret_cast<const u32x4*>(p.u + (long long)row * p.d);
   for (int c = tid; c < p.d / 8; c += 256) dst[c] = src[c];
-  for (int j = wave; j < p.n_experts; j += 4) {
-    const u32x4* e = reinterpret_cast<const u32x4*>(p.centroids + (long long)j * p.d);
-    float acc = 0.f;
-#pragma unroll 8
+  for (int j0 = wave; j0 < p.n_experts; j0 += 8) {  // two experts per pass: their loads share the trip to memory
+    const bool two = j0 + 4 < p.n_experts;
+    const u32x4* e0 = reinterpret_cast<const u32x4*>(p.centroids + (long long)j0 * p.d);
+    const u32x4* e1 = reinterpret_cast<const u32x4*>(p.centroids + (long long)(two ? j0 + 4 : j0) * p.d);
+    float acc0 = 0.f, acc1 = 0.f;
+#pragma unroll 4
     for (int c = lane; c < p.d / 8; c += 64) {
-      const u32x4 a = src[c], b = e[c];
+      const u32x4 a = src[c], b0 = e0[c], b1 = e1[c];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) acc += bf16_lo(a[i]) * bf16_lo(b[i]) + bf16_hi(a[i]) * bf16_hi(b[i]);
+      for (int i = 0; i < 4; ++i) {
+        acc0 += bf16_lo(a[i]) * bf16_lo(b0[i]) + bf16_hi(a[i]) * bf16_hi(b0[i]);
+        acc1 += bf16_lo(a[i]) * bf16_lo(b1[i]) + bf16_hi(a[i]) * bf16_hi(b1[i]);
+      }
     }
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
-    if (lane == 0) score[j] = acc;
+    for (int o = 32; o > 0; o >>= 1) {
+      acc0 += __shfl_xor(acc0, o);
+      acc1 += __shfl_xor(acc1, o);
+    }
+    if (lane == 0) {
+      score[j0] = acc0;
+      if (two) score[j0 + 4] = acc1;
+    }
   }
   __syncthreads();
   if (tid == 0) {
@@ -697,15 +710,13 @@ __global__ __launch_bounds__(256) void router_kernel(RouterParams p) {
     p.s_top[2 * row + 1] = expf(score[i2] - m) / z;
     p.idx[2 * row] = i1;
     p.idx[2 * row + 1] = i2;
-    p.used[i1] = 1;  // (several rows may write the same 1)
-    p.used[i2] = 1;
   }
 }
 
 struct ActParams {
   const float *g, *up;  // [ksplit][n_experts][rows][f] fp32: partial gate and up projections
   uint16_t* h;          // [n_experts][rows padded to 32][f] bf16
-  const int* used;
+  const int* sel;  // [2 rows]: the experts the rows selected
   int rows, rows_pad, f, ksplit;
   long long split_stride;
 };
@@ -713,7 +724,11 @@ struct ActParams {
 // h = silu(gate) * up, rounded to bf16 once; padding rows are zero-filled
 __global__ __launch_bounds__(256) void gated_act_kernel(ActParams p) {
   const int e = blockIdx.y, row = blockIdx.x;
-  if (p.used[e] == 0) return;
+  {
+    int mine = 0;
+    for (int i = threadIdx.x & 63; i < 2 * p.rows; i += 64) mine |= (int)(p.sel[i] == e);
+    if (!__any(mine)) return;  // nobody selected this expert (every wave finds the same)
+  }
   uint16_t* h = p.h + ((long long)e * p.rows_pad + row) * p.f;
   if (row >= p.rows) {
     for (int c = threadIdx.x; c < p.f / 8; c += 256) reinterpret_cast<u32x4*>(h)[c] = u32x4{0u, 0u, 0u, 0u};
@@ -779,7 +794,7 @@ __global__ __launch_bounds__(256) void select_kernel(SelectParams p) {
 
 struct MoePlan {
   int rows_pad, split1, split2;
-  size_t x_off, used_off, g_off, up_off, h_off, y_off, total;
+  size_t x_off, g_off, up_off, h_off, y_off, total;
 };
 // k parts so that a projection with few output columns still fills the chip: a workgroup can
 // pull only a fixed share of the memory bandwidth, so the weight stream needs about one
@@ -802,8 +817,7 @@ MoePlan moe_plan(int rows, int d, int f, int n) {
   m.split1 = pick_ksplit(f, d, m.rows_pad / 32, 2 * n, cus);  // gate and up in one launch
   m.split2 = pick_ksplit(d, f, m.rows_pad / 32, n, cus);
   m.x_off = 0;
-  m.used_off = up((size_t)m.rows_pad * d * 2);
-  m.g_off = m.used_off + up((size_t)kMaxExperts * 4);
+  m.g_off = up((size_t)m.rows_pad * d * 2);
   m.up_off = m.g_off + up((size_t)m.split1 * n * rows * f * 4);
   m.h_off = m.up_off + up((size_t)m.split1 * n * rows * f * 4);
   m.y_off = m.h_off + up((size_t)n * m.rows_pad * f * 2);
@@ -895,7 +909,7 @@ hipError_t launch_draft_heads(const DraftHeadsArgs& a, hipStream_t stream) {
   gp.y = a.logits;
   gp.m = m; gp.n = a.vocab; gp.k = a.d_model;
   gp.ldw = a.d_model; gp.ldy = a.vocab;
-  gp.batch = 1; gp.x_batch = gp.w_batch = gp.y_batch = 0; gp.used = nullptr; gp.w2 = nullptr; gp.y2 = nullptr;
+  gp.batch = 1; gp.x_batch = gp.w_batch = gp.y_batch = 0; gp.sel = nullptr; gp.n_sel = 0; gp.w2 = nullptr; gp.y2 = nullptr;
   gp.ksplit = rp.ksplit; gp.y_split = (long long)m * a.vocab;
   if (rp.ksplit > 1) gp.y = reinterpret_cast<float*>(ws + rp.part_off);
   e = launch_gemm(gp, stream);
@@ -933,14 +947,11 @@ size_t moe_experts_workspace_bytes(int rows, int d_model, int d_ff, int n_expert
 hipError_t launch_moe_experts(const MoeArgs& a, hipStream_t stream) {
   const MoePlan mp = moe_plan(a.rows, a.d_model, a.d_ff, a.n_experts);
   char* ws = static_cast<char*>(a.workspace);
-  int* used = reinterpret_cast<int*>(ws + mp.used_off);
   hipError_t e;
-  hipLaunchKernelGGL(clear_flags_kernel, dim3(1), dim3(kMaxExperts), 0, stream, used, a.n_experts);
-  if ((e = hipGetLastError()) != hipSuccess) return e;
   RouterParams rp;
   rp.u = static_cast<const uint16_t*>(a.u); rp.centroids = static_cast<const uint16_t*>(a.centroids);
   rp.x = reinterpret_cast<uint16_t*>(ws + mp.x_off);
-  rp.s_top = a.s_top; rp.idx = a.expert_idx; rp.used = used;
+  rp.s_top = a.s_top; rp.idx = a.expert_idx;
   rp.rows = a.rows; rp.d = a.d_model; rp.n_experts = a.n_experts;
   hipLaunchKernelGGL(router_kernel, dim3(mp.rows_pad), dim3(256), 0, stream, rp);
   if ((e = hipGetLastError()) != hipSuccess) return e;
@@ -948,7 +959,7 @@ hipError_t launch_moe_experts(const MoeArgs& a, hipStream_t stream) {
   GemmParams gp;
   gp.x = rp.x; gp.m = a.rows; gp.n = a.d_ff; gp.k = a.d_model; gp.ldw = a.d_model; gp.ldy = a.d_ff;
   gp.batch = a.n_experts; gp.x_batch = 0; gp.w_batch = (long long)a.d_ff * a.d_model;
-  gp.y_batch = (long long)a.rows * a.d_ff; gp.used = used;
+  gp.y_batch = (long long)a.rows * a.d_ff; gp.sel = a.expert_idx; gp.n_sel = 2 * a.rows;
   gp.ksplit = mp.split1; gp.y_split = (long long)a.n_experts * a.rows * a.d_ff;
   gp.w = static_cast<const uint16_t*>(a.w_gate); gp.y = reinterpret_cast<float*>(ws + mp.g_off);
   gp.w2 = static_cast<const uint16_t*>(a.w_up); gp.y2 = reinterpret_cast<float*>(ws + mp.up_off);
@@ -957,7 +968,7 @@ hipError_t launch_moe_experts(const MoeArgs& a, hipStream_t stream) {
 
   ActParams ap;
   ap.g = reinterpret_cast<const float*>(ws + mp.g_off); ap.up = reinterpret_cast<const float*>(ws + mp.up_off);
-  ap.h = reinterpret_cast<uint16_t*>(ws + mp.h_off); ap.used = used;
+  ap.h = reinterpret_cast<uint16_t*>(ws + mp.h_off); ap.sel = a.expert_idx;
   ap.rows = a.rows; ap.rows_pad = mp.rows_pad; ap.f = a.d_ff;
   ap.ksplit = mp.split1; ap.split_stride = gp.y_split;
   hipLaunchKernelGGL(gated_act_kernel, dim3(mp.rows_pad, a.n_experts), dim3(256), 0, stream, ap);
@@ -991,7 +1002,7 @@ hipError_t launch_linear(const LinearArgs& a, hipStream_t stream) {
   gp.x = static_cast<const uint16_t*>(a.x); gp.w = static_cast<const uint16_t*>(a.w);
   gp.y = direct ? a.out_f32 : static_cast<float*>(a.workspace);
   gp.m = a.m; gp.n = a.n; gp.k = a.k; gp.ldw = a.k; gp.ldy = a.n;
-  gp.batch = 1; gp.x_batch = gp.w_batch = gp.y_batch = 0; gp.used = nullptr; gp.w2 = nullptr; gp.y2 = nullptr;
+  gp.batch = 1; gp.x_batch = gp.w_batch = gp.y_batch = 0; gp.sel = nullptr; gp.n_sel = 0; gp.w2 = nullptr; gp.y2 = nullptr;
   gp.ksplit = ks; gp.y_split = (long long)a.m * a.n;
   hipError_t e = launch_gemm(gp, stream);
   if (e != hipSuccess || direct) return e;

@@ -170,7 +170,7 @@ def test_argument_errors():
 def test_draft_step_captured_in_a_hip_graph_replays_bit_for_bit():
     """Experts -> heads as prepared calls sharing their workspaces, captured in a HIP graph and replayed with
     eager work between the replays: every replay reproduces the eager results bit for bit (stale workspace
-    contents must not matter: the expert flags, partial sums and candidate lists are rewritten by every call)."""
+    contents must not matter: partial sums and candidate lists are rewritten by every call)."""
     R, d, F, N, V, k = 24, 512, 1024, 4, 9000, 8
     x = moe_inputs(R, d, F, N, seed=8)
     w_head = _dev(draft_head_inputs(1, d, V, seed=8)["w_head"])
