@@ -1,5 +1,5 @@
-"""GPU parity on seeded random shapes: jk_tree_verify_attention (bf16) and jk_accept_path against the
-oracles, over batch sizes, head groupings, head widths, tree sizes and shapes, ragged prefix lengths,
+"""GPU parity on seeded random shapes: jk_tree_verify_attention (bf16), jk_accept_path and the draft-side
+calls against the oracles, over batch sizes, head groupings, head widths, tree sizes and shapes, ragged prefix lengths,
 cache capacities above the lengths, both wave arrangements and forced split counts (including more splits
 than tiles), with an occasional key far above every other score of one query row (the fast path of the
 4x1 arrangement then has to repeat its split on the general path).  Same bounds as the fixed cases: 2e-2
@@ -119,3 +119,42 @@ def test_accept_random_shapes(monkeypatch, block):
             assert (path[b, alen[b]:] == -1).all(), what
             assert bonus[b] == r.bonus_token, what
     assert compared >= 20
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_draft_side_random_shapes(seed):
+    """The draft-side calls on random shapes within their documented limits, checked with the fixed cases'
+    own helpers (bounds and decisions as described there)."""
+    import test_gpu_draft_head as heads
+    import test_gpu_draft_tree as tree
+    import test_gpu_linear as lin
+    import test_gpu_moe_experts as moe
+    from oracle import draft_head as dh
+    from workloads import draft_head_inputs, moe_inputs
+    rng = np.random.default_rng(4242 + seed)
+    for i in range(4):
+        rows, d = int(rng.integers(1, 129)), 128 * int(rng.integers(1, 9))
+        V, k = int(rng.integers(17, 20000)), int(rng.integers(1, 17))
+        mode, temp = int(rng.integers(0, 2)), float(rng.uniform(0.3, 3.0))
+        heads._check(draft_head_inputs(rows, d, V, seed=10 * seed + i), mode, temp, k, 0.4, 0.9)
+        heads._check(heads._exact_inputs(rows, d, V, 10 * seed + i), exact=True, top_k=min(k, 5))
+    for i in range(3):
+        rows, d = int(rng.integers(1, 129)), 128 * int(rng.integers(1, 5))
+        f, n = 128 * int(rng.integers(1, 9)), int(rng.integers(2, 10))
+        x = moe_inputs(rows, d, f, n, seed=100 + 10 * seed + i)
+        s = dh.router_scores(x["u"], x["centroids"])
+        srt = -np.sort(-s, axis=1)
+        gaps = np.minimum(srt[:, 0] - srt[:, 1], srt[:, 1] - srt[:, 2] if n > 2 else np.inf)
+        if (gaps > 1e-4).all():       # (a row whose top-2 choice hangs on the last bits cannot be compared)
+            moe._check(x)
+    for i in range(3):
+        B, k = int(rng.integers(1, 5)), int(rng.integers(1, 9))
+        width, depth = min(int(rng.integers(1, 9)), 2 * k), int(rng.integers(1, 6))
+        if width * 2 * k > 256:
+            continue
+        mx = int(rng.integers(16, 1025))
+        keep = int(rng.integers(1, min(mx, 128) + 1))
+        tree._run_round(200 + 10 * seed + i, B, depth, k, width, mx, keep, ties=bool(i % 2))
+    for i in range(3):
+        lin.test_exact_arithmetic_inputs_are_bit_exact(int(rng.integers(1, 257)), int(rng.integers(1, 3000)),
+                                                       128 * int(rng.integers(1, 17)))
