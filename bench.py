@@ -31,7 +31,7 @@ HBM_PEAK_GBPS = 8000.0
 # HBM bytes per tva_bf16_kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (KiB per
 # dispatch), each scaled by the same counter's reading for a 256 MiB device copy (factors 2.00 and
 # 1.00); source: profiles/tva_bf16_c3_hbm_traffic.md.  {workload: bytes} or None if not measured.
-MEASURED_TRAFFIC = {"c3_llama3_8b": 25921091}
+MEASURED_TRAFFIC = {"c3_llama3_8b": 25920318}
 
 
 def attn_bytes(cfg) -> int:
