@@ -82,19 +82,24 @@ bool make_attn_plan(const jk_attn_desc& d, int max_prefix_len, AttnPlan* pl) {
         if (s > kMaxSplits) continue;
         // Estimated time of a call, in microseconds, from what was measured on an MI355X at
         // head_dim 128: a workgroup runs a round (2 tiles per key column) in about 0.95 us as
-        // 2x2 waves and 1.4 us as 4x1 waves (which cover twice the rows, hand-pipelined);
+        // 2x2 waves and 1.33 us as 4x1 waves (which cover twice the rows, hand-pipelined);
         // workgroups beyond one per CU share its throughput; the K/V stream (re-read from L2
         // by the row tiles at a quarter of the price) moves at about 4 TB/s while every CU
         // pulls, so CUs with one workgroup more than the average stretch it; partial outputs
         // (bf16, written, flushed at the kernel boundary and read back) cost about 0.28 us per MB.
-        const double t_round = (wn == 1 ? 1.4 : 0.95) * d.head_dim / 128.0;
+        const double t_round = (wn == 1 ? 1.33 : 0.95) * d.head_dim / 128.0;
         const double rounds = (double)((n_tiles + wn * kt - 1) / (wn * kt)) / (double)s;
         const double per_cu = (double)(wgs * s) / slots;
-        const double share = per_cu > 1.0 ? per_cu + 0.5 : 1.0;  // + half a workgroup of tail
+        // 4x1 workgroups that share a CU overlap each other's matrix and vector phases: two of
+        // them take 1.58 times one's time (measured on c5), plus a part of a workgroup of tail
+        const double share = per_cu > 1.0 ? (wn == 1 ? 0.79 * (per_cu + 0.3) : per_cu + 0.5) : 1.0;
         const double imbalance = per_cu > 1.0 ? std::ceil(per_cu) / per_cu : 1.0;
         const double loop_us = rounds * t_round * share;
         const double stream_us = imbalance * (double)units * kv_bytes * (1.0 + 0.25 * (n_qtiles - 1)) / 4.0e6;
-        const double partial_us = s > 1 ? 0.28e-6 * (double)units * s * pl->m_rows * d.head_dim * 2.0 : 0.0;
+        // (partials: 0.28 us per MB when the grid is one turn of workgroups and they are stored
+        // through to memory, 0.4 when they take the ordinary route and the merge kernel is large)
+        const double partial_us =
+            s > 1 ? (per_cu > 1.0 && wn == 1 ? 0.4e-6 : 0.28e-6) * (double)units * s * pl->m_rows * d.head_dim * 2.0 : 0.0;
         const double cost = (loop_us > stream_us ? loop_us : stream_us) + partial_us;
         if (!have || cost < best_cost) {
           have = true;
