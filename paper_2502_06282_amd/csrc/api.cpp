@@ -67,14 +67,10 @@ bool make_attn_plan(const jk_attn_desc& d, int max_prefix_len, AttnPlan* pl) {
       const long long wgs = units * n_qtiles;
       const int kt = wn == 1 ? 2 : 1;  // a lone key column pairs its tiles (hand-pipelined two-tile path)
       const int max_by_tiles = n_tiles / (2 * wn * kt) > 0 ? n_tiles / (2 * wn * kt) : 1;  // >= 2 rounds per split
-      // split counts worth a look: one workgroup per CU, (nearly) two, and a few multiples
-      // (smaller workgroups even out the load when there are more of them than CUs)
-      const long long s1 = (slots + wgs - 1) / wgs;
-      const long long cand[6] = {s1, 2 * slots / wgs, (2 * slots + wgs - 1) / wgs, 2 * s1, 4 * s1, 8 * s1};
-      for (int ci = 0; ci < 6; ++ci) {
-        long long s = cand[ci] < 1 ? 1 : cand[ci];
-        if (s > max_by_tiles) s = max_by_tiles;
-        if (s > kMaxSplits) s = kMaxSplits;
+      // every split count that leaves a split at least two rounds is priced
+      const long long s_top = forced_s >= 1 && forced_s <= kMaxSplits ? 1 : (max_by_tiles < kMaxSplits ? max_by_tiles : kMaxSplits);
+      for (long long sc = 1; sc <= s_top; ++sc) {
+        long long s = sc;
         if (forced_s >= 1 && forced_s <= kMaxSplits) s = forced_s;
         // a split's tiles stay within what a workgroup can keep page ids for (paged caches)
         const long long s_min = (n_tiles + kMaxTilesPerSplit - 1) / kMaxTilesPerSplit;
@@ -88,19 +84,27 @@ bool make_attn_plan(const jk_attn_desc& d, int max_prefix_len, AttnPlan* pl) {
         // pulls, so CUs with one workgroup more than the average stretch it; partial outputs
         // (bf16, written, flushed at the kernel boundary and read back) cost about 0.28 us per MB.
         const double t_round = (wn == 1 ? 1.33 : 0.95) * d.head_dim / 128.0;
-        const double rounds = (double)((n_tiles + wn * kt - 1) / (wn * kt)) / (double)s;
+        // rounds of the longest split: the 4x1 arrangement deals tiles (an odd last tile costs about
+        // half a round), the 2x2 arrangement whole rounds
+        const double rounds = wn == 1 ? 0.5 * (double)((n_tiles + s - 1) / s)
+                                      : (double)(((n_tiles + wn * kt - 1) / (wn * kt) + s - 1) / s);
         const double per_cu = (double)(wgs * s) / slots;
         // 4x1 workgroups that share a CU overlap each other's matrix and vector phases: two of
         // them take 1.58 times one's time (measured on c5), plus a part of a workgroup of tail
-        const double share = per_cu > 1.0 ? (wn == 1 ? 0.79 * (per_cu + 0.3) : per_cu + 0.5) : 1.0;
+        const double share =
+            per_cu > 1.0 ? (wn == 1 ? 0.79 * (per_cu + 0.3 > 2.0 ? per_cu + 0.3 : 2.0) : per_cu + 0.5) : 1.0;
         const double imbalance = per_cu > 1.0 ? std::ceil(per_cu) / per_cu : 1.0;
         const double loop_us = rounds * t_round * share;
-        const double stream_us = imbalance * (double)units * kv_bytes * (1.0 + 0.25 * (n_qtiles - 1)) / 4.0e6;
+        // (a CU pulls about 22 GB/s on its own: fewer workgroups than CUs stream slower than 4 TB/s)
+        const double active = (double)(wgs * s < slots ? wgs * s : slots);
+        const double rate = active * 22.0e3 < 4.0e6 ? active * 22.0e3 : 4.0e6;  // bytes per microsecond
+        const double stream_us = imbalance * (double)units * kv_bytes * (1.0 + 0.25 * (n_qtiles - 1)) / rate;
         // (partials: 0.28 us per MB when the grid is one turn of workgroups and they are stored
         // through to memory, 0.4 when they take the ordinary route and the merge kernel is large)
         const double partial_us =
             s > 1 ? (per_cu > 1.0 && wn == 1 ? 0.4e-6 : 0.28e-6) * (double)units * s * pl->m_rows * d.head_dim * 2.0 : 0.0;
-        const double cost = (loop_us > stream_us ? loop_us : stream_us) + partial_us;
+        // (near ties go to the count that gives every CU a workgroup: 2 % for an idle CU)
+        const double cost = ((loop_us > stream_us ? loop_us : stream_us) + partial_us) * (active < slots ? 1.02 : 1.0);
         if (!have || cost < best_cost) {
           have = true;
           best_cost = cost;
