@@ -70,7 +70,7 @@ def test_paged_attention_repeats_a_split_that_leaves_the_fixed_frame(monkeypatch
     torch.cuda.synchronize()
     g = got.float().cpu().numpy()
     assert np.isfinite(g).all()
-    assert np.abs(g - ref).max() <= 3 * 2.0 ** -9 * 4.5 and np.abs(g - ref).max() <= 1.5e-2 * np.abs(ref).max()
+    assert np.abs(g - ref).max() <= 3 * 2.0 ** -8 * 4.5 and np.abs(g - ref).max() <= 1.5e-2 * np.abs(ref).max()
     v = x["v_cache"][0, 1777, 0].astype(np.float64)
     assert np.abs(g[0, 11, 2] - v).max() <= 2.0 ** -7 * np.abs(v).max() + 1e-6
     assert torch.equal(got, cont)

@@ -3,8 +3,8 @@ calls against the oracles, over batch sizes, head groupings, head widths, tree s
 cache capacities above the lengths, both wave arrangements and forced split counts (including more splits
 than tiles), with an occasional key far above every other score of one query row (the fast path of the
 4x1 arrangement then has to repeat its split on the general path).  Same bounds as the fixed cases: 2e-2
-absolute for bf16 attention (rows that are near one-hot because of a planted key: relative bound only) and
-2e-2 relative to max|out|; acceptance bit-exact on seeds whose decisions have a margin above 1e-9."""
+absolute for bf16 attention (3 * 2^-8 max|v| where that is larger: inputs here are not scaled down like the
+workloads') and 2e-2 relative to max|out|; acceptance bit-exact on seeds whose decisions have a margin above 1e-9."""
 import numpy as np
 import pytest
 import torch
@@ -63,7 +63,14 @@ def test_attention_random_shapes(monkeypatch, block):
         got = gpu_attention(x, par, lens, "bf16")
         assert np.isfinite(got).all(), what
         err = np.abs(got - ref).max()
-        assert (err <= 2e-2 or planted) and err <= 2e-2 * max(np.abs(ref).max(), 1e-30), f"{what}: error {err:.3e}"
+        # Inputs here are N(0, 1), not the workloads' 0.09: rows that see few keys, or one key far above the
+        # rest, return (nearly) single V rows.  An output is sum_j p_j v_j / l with the p_j rounded to bf16,
+        # the split partial rounded to bf16 and the result rounded to bf16 (unit roundoff 2^-8 each), so its
+        # error is at most 3 * 2^-8 * max|v| (a near one-hot row whose largest weight is not a power of two really
+        # shows the first of the three: the numerator carries the rounded weight, the denominator the exact one); the relative bound is the workloads' 2e-2.
+        peak_v = max(np.abs(x["v_cache"]).max() if Lmax > 0 else 0.0, np.abs(x["v_tree"]).max())
+        peak = np.abs(ref).max()
+        assert err <= max(2e-2, 3 * 2.0 ** -8 * peak_v) and err <= 2e-2 * max(peak, 1e-30), f"{what}: error {err:.3e}"
 
 
 @pytest.mark.parametrize("block", range(4))
