@@ -177,9 +177,15 @@ size_t jk_accept_path_workspace(int32_t batch, int32_t n_tree, int32_t vocab, in
  *   draft_probs   device fp32  [batch, n_tree, vocab]; required by JK_SAMPLE, else may be NULL
  *   uniforms      device fp32  [batch, n_tree+1] in [0,1); required by JK_SAMPLE
  *   out_path        device int32 [batch, max_depth]: accepted node ids, root-most first, -1 padded
- *   out_accept_len  device int32 [batch]: number of accepted nodes (capped at max_depth)
- *   out_bonus_token device int32 [batch]
+ *   out_accept_len  device int32 [batch]: number of accepted nodes, at most max_depth
+ *   out_bonus_token device int32 [batch]: the token that follows the last accepted node
  *   workspace     device, >= jk_accept_path_workspace(...) bytes
+ *
+ * max_depth stops the descent: after max_depth accepted nodes the children of the
+ * last one are not examined and the bonus token comes from that node's own row
+ * (argmax, or a draw from its softmax), i.e. the result is that of the same tree
+ * cut below depth max_depth, and path[:accept_len] + bonus is always a sequence
+ * the target model itself would have produced.
  *
  * Supported: 1 <= n_tree <= JK_MAX_TREE, vocab >= 1, max_depth >= 1.  Token ids
  * outside [0, vocab) are clamped into the range.  JK_SAMPLE runs several

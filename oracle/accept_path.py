@@ -47,11 +47,13 @@ def _children(parent: Sequence[int], c: int) -> List[int]:
     return [k for k in range(len(parent)) if parent[k] == c]
 
 
-def _greedy(tokens, parent, logits) -> AcceptResult:
+def _greedy(tokens, parent, logits, max_depth) -> AcceptResult:
     c = -1
     path: List[int] = []
     while True:
         t_star = int(np.argmax(logits[c + 1]))          # first maximum = lowest id on ties
+        if max_depth is not None and len(path) >= max_depth:
+            return AcceptResult(path, len(path), t_star)  # the walk may go no deeper: c's own row gives the token
         nxt = None
         for k in _children(parent, c):                   # left to right
             if int(tokens[k]) == t_star:
@@ -63,7 +65,7 @@ def _greedy(tokens, parent, logits) -> AcceptResult:
         c = nxt
 
 
-def _sample(tokens, parent, logits, draft_probs, uniforms, temperature, ftype) -> AcceptResult:
+def _sample(tokens, parent, logits, draft_probs, uniforms, temperature, ftype, max_depth) -> AcceptResult:
     n = len(parent)
     res = AcceptResult([], 0, -1)
 
@@ -77,6 +79,8 @@ def _sample(tokens, parent, logits, draft_probs, uniforms, temperature, ftype) -
         e = np.exp(z - z.max())
         p = e / e.sum()
         accepted = None
+        if max_depth is not None and len(res.path) >= max_depth:
+            break                                        # no deeper: the token after c comes from c's untouched row
         for k in _children(parent, c):
             x = int(tokens[k])
             qk = np.asarray(draft_probs[k], dtype=ftype)
@@ -118,23 +122,28 @@ def _sample(tokens, parent, logits, draft_probs, uniforms, temperature, ftype) -
 def accept_path(tree_tokens: np.ndarray, parent: np.ndarray, target_logits: np.ndarray,
                 mode: str = "greedy", draft_probs: Optional[np.ndarray] = None,
                 uniforms: Optional[np.ndarray] = None, temperature: float = 1.0,
-                ftype=np.float64) -> AcceptResult:
+                ftype=np.float64, max_depth: Optional[int] = None) -> AcceptResult:
     """One tree.  tree_tokens [N], parent [N], target_logits [N+1, V];
     mode "greedy" or "sample"; sample also needs draft_probs [N, V] and
     uniforms [N+1] (entry k tests node k, entry N draws the final token).
     ftype is the arithmetic type of the sampling walk (float64; float32 only to
-    show that decisions do not hinge on precision)."""
+    show that decisions do not hinge on precision).  max_depth (optional) stops
+    the descent after that many accepted nodes: the children of the last one are
+    not examined, and the final token is taken from that node's own row, exactly
+    as if the tree had been cut below that depth (which is how the cap is pinned)."""
     parent = [int(x) for x in parent]
     for i, pa in enumerate(parent):
         if not (-1 <= pa < i):
             raise ValueError(f"parent[{i}]={pa} violates -1 <= parent[i] < i")
+    if max_depth is not None and max_depth < 1:
+        raise ValueError("max_depth must be at least 1")
     if mode == "greedy":
-        return _greedy(tree_tokens, parent, np.asarray(target_logits))
+        return _greedy(tree_tokens, parent, np.asarray(target_logits), max_depth)
     if mode == "sample":
         if draft_probs is None or uniforms is None:
             raise ValueError("sample mode needs draft_probs and uniforms")
         if not temperature > 0:
             raise ValueError("temperature must be positive")
         return _sample(tree_tokens, parent, target_logits, draft_probs, uniforms,
-                       temperature, ftype)
+                       temperature, ftype, max_depth)
     raise ValueError(f"unknown mode {mode!r}")

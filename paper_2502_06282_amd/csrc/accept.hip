@@ -140,18 +140,19 @@ __global__ __launch_bounds__(128) void walk_greedy_kernel(int n_tree, int nch, i
     const int p0 = in0 ? par_s[lane] : -2, p1 = in1 ? par_s[lane + 64] : -2;
     const bool ok0 = in0 && ok[lane], ok1 = in1 && ok[lane + 64];
     int c = -1, len = 0;
-    for (;;) {  // nodes are numbered topologically: a child has a larger index than its parent
+    // (nodes are numbered topologically: a child has a larger index than its parent; the walk
+    // stops at max_depth accepted nodes, and the extra token then comes from the last one's row)
+    while (len < max_depth) {
       const unsigned long long m0 = __ballot(ok0 && p0 == c), m1 = __ballot(ok1 && p1 == c);
       const int k = m0 ? __ffsll((long long)m0) - 1 : (m1 ? 63 + __ffsll((long long)m1) : -1);
       if (k < 0) break;
-      if (len < max_depth && lane == 0) out_path[(long long)b * max_depth + len] = k;
+      if (lane == 0) out_path[(long long)b * max_depth + len] = k;
       ++len;
       c = k;
     }
     if (lane != 0) return;
-    const int capped = len < max_depth ? len : max_depth;
-    for (int i = capped; i < max_depth; ++i) out_path[(long long)b * max_depth + i] = -1;
-    out_len[b] = capped;
+    for (int i = len; i < max_depth; ++i) out_path[(long long)b * max_depth + i] = -1;
+    out_len[b] = len;
     out_bonus[b] = amax[c + 1];
   }
 }
@@ -228,7 +229,7 @@ __global__ __launch_bounds__(kWalkThreads) void walk_sample_kernel(WalkParams p)
 
   load_row_stats(0);
   int k = 0;  // children of c are searched from k upwards (topological numbering)
-  while (true) {
+  while (len < p.max_depth) {  // (at the cap the token after c comes from c's own row, untouched)
     // next child of c, left to right
     int child = -1;
     for (int j = k; j < N; ++j)
@@ -244,7 +245,7 @@ __global__ __launch_bounds__(kWalkThreads) void walk_sample_kernel(WalkParams p)
     const double lhs = (double)uni[child] * (double)qk[x];
     const double rhs = prob(x);
     if (lhs < rhs) {
-      if (len < p.max_depth && tid == 0) p.out_path[(long long)b * p.max_depth + len] = child;
+      if (tid == 0) p.out_path[(long long)b * p.max_depth + len] = child;
       ++len;
       c = child;
       k = child + 1;
@@ -310,9 +311,8 @@ __global__ __launch_bounds__(kWalkThreads) void walk_sample_kernel(WalkParams p)
   }
   __syncthreads();
   if (tid == 0) {
-    const int capped = len < p.max_depth ? len : p.max_depth;
-    for (int i = capped; i < p.max_depth; ++i) p.out_path[(long long)b * p.max_depth + i] = -1;
-    p.out_len[b] = capped;
+    for (int i = len; i < p.max_depth; ++i) p.out_path[(long long)b * p.max_depth + i] = -1;
+    p.out_len[b] = len;
     p.out_bonus[b] = s_found < 0 ? 0 : s_found;
   }
 }

@@ -269,14 +269,15 @@ __global__ __launch_bounds__(kCoopThreads) void walk_sample_coop_kernel(CoopPara
     for (int i = 0; i < n_rej; ++i) px = fmax(0.0, px - (double)pf_q[i]) * rej_inv[i];
     const double lhs = (double)uni_s[child] * (double)pf_q[n_rej];
     if (lhs < px) {
-      if (len < p.max_depth && tid == 0 && w == 0) p.out_path[(long long)b * p.max_depth + len] = child;
+      if (tid == 0 && w == 0) p.out_path[(long long)b * p.max_depth + len] = child;
       ++len;
       c = child;
       n_rej = 0;
       have_pf = false;
       __syncthreads();  // pf_q is rewritten for the first child
       load_row(c + 1);
-      child = find_child(c, c + 1);
+      // at max_depth accepted nodes the walk stops: the token after c is drawn from c's own row
+      child = len < p.max_depth ? find_child(c, c + 1) : -1;
       continue;
     }
     // rejected: candidate residual of my slice and its mass
@@ -395,7 +396,7 @@ __global__ __launch_bounds__(kCoopThreads) void walk_sample_coop_kernel(CoopPara
         }
       }
       if (tid == 0) {
-        const int capped = len < p.max_depth ? len : p.max_depth;
+        const int capped = len;  // (the walk itself stops at max_depth)
         if (mine || (!any && w == 0)) {
           p.out_bonus[b] = mine ? s_found : (last_any < 0 ? 0 : last_any);
         }

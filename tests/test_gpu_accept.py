@@ -28,13 +28,13 @@ def _gpu_accept(a, par, mode, temperature=1.0, max_depth=None):
     return path.cpu().numpy(), alen.cpu().numpy(), bonus.cpu().numpy()
 
 
-def _compare(a, par, mode, temperature=1.0):
-    path, alen, bonus = _gpu_accept(a, par, mode, temperature)
+def _compare(a, par, mode, temperature=1.0, max_depth=None):
+    path, alen, bonus = _gpu_accept(a, par, mode, temperature, max_depth)
     skipped = 0
     for b in range(par.shape[0]):
         r = oracle_accept(a["tokens"][b], par[b], a["logits"][b], mode,
                           None if a["draft_probs"] is None else a["draft_probs"][b],
-                          None if a["uniforms"] is None else a["uniforms"][b], temperature)
+                          None if a["uniforms"] is None else a["uniforms"][b], temperature, max_depth=max_depth)
         if mode == "sample" and r.min_margin <= MARGIN:
             skipped += 1
             continue
@@ -104,8 +104,37 @@ def test_greedy_first_child_chain_and_max_depth_cap():
             break
         c = int(kids[0]); expect.append(c)
     assert path[0, :alen[0]].tolist() == expect and len(expect) >= 2
-    path2, alen2, bonus2 = _gpu_accept(a, par, "greedy", max_depth=1)
-    assert alen2[0] == 1 and path2.shape == (1, 1) and path2[0, 0] == path[0, 0] and bonus2[0] == bonus[0]
+    # a depth cap stops the walk: the token after the last kept node is that node's own top-1,
+    # not the one found further down (path[:len] + bonus must stay a sequence of the target's)
+    for cap in (1, 2):
+        _compare(a, par, "greedy", max_depth=cap)
+        path2, alen2, bonus2 = _gpu_accept(a, par, "greedy", max_depth=cap)
+        assert alen2[0] == cap and path2.shape == (1, cap) and path2[0].tolist() == expect[:cap]
+        assert bonus2[0] == int(np.argmax(a["logits"][0, expect[cap - 1] + 1]))
+
+
+@pytest.mark.parametrize("single", [False, True])
+def test_sample_max_depth_cap(single, monkeypatch):
+    """Sampling walks that go deep (draft distributions close to the target's), cut at every depth:
+    cooperative and single-workgroup walks against the oracle's capped walk."""
+    if single:
+        monkeypatch.setenv("JK_ACCEPT_SINGLE", "1")
+    cfg = CONFIGS["c3_llama3_8b"].with_(vocab=3001, batch=4)
+    par = tree_for_config(cfg, seed=7)
+    a = accept_inputs(cfg, par, seed=7)
+    lg = a["logits"].astype(np.float64)
+    for b in range(cfg.batch):
+        for k in range(cfg.n_tree):
+            row = lg[b, par[b, k] + 1]
+            e = np.exp(row - row.max())
+            a["draft_probs"][b, k] = (0.97 * e / e.sum() + 0.03 * a["draft_probs"][b, k]).astype(np.float32)
+            if k == int(np.nonzero(par[b] == par[b, k])[0][0]):
+                a["tokens"][b, k] = int(np.argmax(row))  # first children carry the likeliest token
+    full = [oracle_accept(a["tokens"][b], par[b], a["logits"][b], "sample", a["draft_probs"][b], a["uniforms"][b]).accept_len
+            for b in range(cfg.batch)]
+    assert max(full) >= 3
+    for cap in (1, 2, 3):
+        assert _compare(a, par, "sample", max_depth=cap) == 0
 
 
 @pytest.mark.parametrize("seed", range(6))

@@ -359,3 +359,52 @@ def test_argument_errors():
     with pytest.raises(ValueError):
         accept_path(np.array([1]), np.array([-1]), np.zeros((2, 3)), "sample",
                     np.ones((1, 3)) / 3, np.zeros(2), temperature=0.0)
+
+
+def _cut_tree(par, depth_cap):
+    """Nodes of depth <= depth_cap, in their old order, with parents renumbered; returns (new parent, kept old ids)."""
+    depth = tree_depths(par)
+    keep = [i for i in range(len(par)) if depth[i] <= depth_cap]
+    new_id = {old: new for new, old in enumerate(keep)}
+    return np.array([new_id.get(int(par[i]), -1) for i in keep], dtype=np.int32), keep
+
+
+@pytest.mark.parametrize("mode", ["greedy", "sample"])
+@pytest.mark.parametrize("cap", [1, 2, 3])
+def test_max_depth_equals_the_tree_cut_below_that_depth(mode, cap):
+    """Pin of the depth cap: stopping after `cap` accepted nodes must give what the same walk gives on
+    the tree with every deeper node removed (path, and the token that follows it).  Section 2.1 step 3:
+    the emitted sequence is accepted tokens + one token of the target's own distribution at the stop."""
+    hits = 0
+    for seed in range(12):
+        if mode == "greedy":
+            cfg = CONFIGS["c2_vicuna7b"].with_(vocab=300, hit_prob=0.9)
+        else:
+            cfg = CONFIGS["c3_llama3_8b"].with_(vocab=40)
+        par = tree_for_config(cfg, seed=seed)[0]
+        a = accept_inputs(cfg, par[None], seed=seed)
+        q = None if a["draft_probs"] is None else a["draft_probs"][0]
+        u = None if a["uniforms"] is None else a["uniforms"][0]
+        if mode == "sample":  # draft distributions close to the target's, so that the walk goes deep
+            q = np.stack([0.97 * _softmax(a["logits"][0][par[k] + 1].astype(np.float64)) + 0.03 * q[k] for k in range(len(par))])
+            for k in range(len(par)):  # first children carry their parent row's likeliest token: accepted almost surely
+                if k == min(j for j in range(len(par)) if par[j] == par[k]) and seed % 3:
+                    a["tokens"][0][k] = int(np.argmax(a["logits"][0][par[k] + 1]))
+        full = accept_path(a["tokens"][0], par, a["logits"][0], mode, q, u)
+        capped = accept_path(a["tokens"][0], par, a["logits"][0], mode, q, u, max_depth=cap)
+        par_c, keep = _cut_tree(par, cap)
+        rows = [0] + [k + 1 for k in keep]
+        cut = accept_path(a["tokens"][0][keep], par_c, a["logits"][0][rows], mode,
+                          None if q is None else q[keep], None if u is None else np.concatenate([u[keep], u[-1:]]))
+        assert capped.path == [keep[k] for k in cut.path]
+        assert capped.accept_len == cut.accept_len <= cap
+        assert capped.bonus_token == cut.bonus_token
+        assert capped.path == full.path[:cap]
+        if full.accept_len > cap:
+            hits += 1
+            # the cap must not skip tokens: the token after the last kept node is drawn from that node's row
+            if mode == "greedy":
+                assert capped.bonus_token == int(np.argmax(a["logits"][0][capped.path[-1] + 1]))
+        elif full.accept_len < cap:  # (at exactly `cap` the uncapped walk still tried the last node's children)
+            assert capped.bonus_token == full.bonus_token
+    assert hits >= 1, "the cap never cut a walk: the test would prove nothing"
