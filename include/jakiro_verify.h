@@ -64,13 +64,15 @@ typedef enum {
   JK_ERR_BAD_TREE = 2,    /* jk_validate_tree only */
   JK_ERR_UNSUPPORTED = 3, /* shape outside the supported set (see each call) */
   JK_ERR_WORKSPACE = 4,   /* workspace missing, misaligned or too small */
-  JK_ERR_HIP = 5          /* a HIP runtime call failed (launch configuration, bad stream) */
+  JK_ERR_HIP = 5,         /* a HIP runtime call failed (launch configuration, bad stream) */
+  JK_ERR_SCRATCH_LIMIT = 6 /* jk_accept_path_greedy_static only: the input needs more than JK_STATIC_SCRATCH_BYTES */
 } jk_status;
 
 typedef enum { JK_BF16 = 0, JK_F32 = 1 } jk_dtype;
 typedef enum { JK_GREEDY = 0, JK_SAMPLE = 1 } jk_mode;
 
 #define JK_MAX_TREE 128 /* largest supported number of tree nodes */
+#define JK_STATIC_SCRATCH_BYTES (1 << 20) /* the library's built-in scratch buffer (jk_accept_path_greedy_static) */
 
 /* Shape and layout of one attention call.  Strides are in ELEMENTS; the
  * innermost (head_dim) index is contiguous; for JK_BF16 every base pointer
@@ -201,6 +203,25 @@ jk_status jk_accept_path(int32_t batch, int32_t n_tree, int32_t vocab, int32_t m
                          const float* draft_probs, const float* uniforms, int32_t* out_path,
                          int32_t* out_accept_len, int32_t* out_bonus_token, void* workspace,
                          size_t workspace_bytes, void* hip_stream);
+
+/* jk_accept_path in JK_GREEDY mode for callers that cannot allocate device memory or hand
+ * over a workspace: code running under HIP-graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  Same arguments, results and kernels as jk_accept_path(...,
+ * JK_GREEDY, ...) minus the workspace: the per-chunk (max, argmax) partials live in a buffer
+ * of JK_STATIC_SCRATCH_BYTES that is part of the library's device image (one copy per GPU the
+ * library runs on, held until the process ends).  The call allocates and frees nothing.
+ *
+ * Limit: batch * (n_tree + 1) * ceil(vocab / 4096) * 8 bytes (each of the two partial arrays
+ * rounded up to 256 bytes) must fit JK_STATIC_SCRATCH_BYTES; larger inputs return
+ * JK_ERR_SCRATCH_LIMIT and launch nothing (61 rows x 128 256 entries need 16 KB, 65 535 rows
+ * x 4096 entries 512 KB).  All calls on one GPU share that GPU's buffer: calls that overlap
+ * in time on one GPU (different streams, different host threads) race and must be ordered
+ * by the caller.  Nothing in the buffer needs to start at zero: every partial a call reads,
+ * the same call has written.  Other return codes as for jk_accept_path. */
+jk_status jk_accept_path_greedy_static(int32_t batch, int32_t n_tree, int32_t vocab, int32_t max_depth,
+                                       const int32_t* tree_tokens, const int32_t* parent,
+                                       const float* target_logits, int32_t* out_path,
+                                       int32_t* out_accept_len, int32_t* out_bonus_token, void* hip_stream);
 
 /* jk_accept_path with the draft distributions addressed through a row table instead of a
  * dense [batch][n_tree][vocab] array: node k of sequence b is tested against

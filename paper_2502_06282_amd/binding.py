@@ -66,7 +66,7 @@ class PagedKV(ctypes.Structure):
 
 EXPORTS = ("jk_tree_verify_attention_workspace", "jk_tree_verify_attention", "jk_tree_verify_attention_paged",
            "jk_commit_path_layers_paged", "jk_accept_path_workspace",
-           "jk_accept_path", "jk_accept_path_rows", "jk_draft_heads_workspace", "jk_draft_heads", "jk_moe_experts_workspace", "jk_moe_experts", "jk_linear_workspace", "jk_linear", "jk_tree_grow", "jk_tree_grow_tail", "jk_tree_fill_static", "jk_tree_finalize", "jk_gather_draft_probs", "jk_commit_path", "jk_commit_path_layers", "jk_workspace_init", "jk_stream_read_probe", "jk_validate_tree", "jk_status_string", "jk_version")
+           "jk_accept_path", "jk_accept_path_greedy_static", "jk_accept_path_rows", "jk_draft_heads_workspace", "jk_draft_heads", "jk_moe_experts_workspace", "jk_moe_experts", "jk_linear_workspace", "jk_linear", "jk_tree_grow", "jk_tree_grow_tail", "jk_tree_fill_static", "jk_tree_finalize", "jk_gather_draft_probs", "jk_commit_path", "jk_commit_path_layers", "jk_workspace_init", "jk_stream_read_probe", "jk_validate_tree", "jk_status_string", "jk_version")
 
 
 def library_path() -> str:
@@ -277,6 +277,30 @@ def accept_path(tree_tokens, parent, target_logits, mode: int = JK_GREEDY, tempe
     if st != 0:
         raise JakiroError(st, "jk_accept_path")
     return path, alen, bonus
+
+
+def accept_path_greedy_static(tree_tokens, parent, target_logits, out_path, out_accept_len, out_bonus_token,
+                              stream=None) -> None:
+    """jk_accept_path_greedy_static: greedy acceptance without a workspace (the library's built-in scratch
+    buffer); the caller passes every output tensor, the call allocates nothing.  out_path int32 [B, max_depth]."""
+    import torch
+    B, N = tree_tokens.shape
+    V = target_logits.shape[-1]
+    for t in (tree_tokens, parent, out_path, out_accept_len, out_bonus_token):
+        if t.dtype != torch.int32 or not t.is_contiguous():
+            raise TypeError("tokens, parent and the outputs must be contiguous int32")
+    if target_logits.dtype != torch.float32 or not target_logits.is_contiguous() or target_logits.shape != (B, N + 1, V):
+        raise TypeError("target_logits must be contiguous float32 [B, N+1, V]")
+    if out_path.dim() != 2 or out_path.shape[0] != B or out_accept_len.numel() != B or out_bonus_token.numel() != B:
+        raise ValueError("outputs must be [B, max_depth], [B], [B]")
+    fn = lib().jk_accept_path_greedy_static
+    vp, i32 = ctypes.c_void_p, ctypes.c_int32
+    fn.restype = i32
+    fn.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
+    st = fn(B, N, V, int(out_path.shape[1]), _ptr(tree_tokens), _ptr(parent), _ptr(target_logits), _ptr(out_path),
+            _ptr(out_accept_len), _ptr(out_bonus_token), _stream_handle(stream))
+    if st != 0:
+        raise JakiroError(st, "jk_accept_path_greedy_static")
 
 
 class PreparedCall:

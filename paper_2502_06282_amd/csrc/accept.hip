@@ -21,6 +21,7 @@
 //                       arithmetic is fp64: the inverse-CDF draw resolves steps
 //                       of ~1/vocab, which fp32 terms cannot do reproducibly
 #include <cstdlib>
+#include <mutex>
 
 #include "jk_internal.h"
 
@@ -317,6 +318,34 @@ __global__ __launch_bounds__(kWalkThreads) void walk_sample_kernel(WalkParams p)
   }
 }
 
+// ------------------------------------------------------------------ library-owned scratch
+// For the entry point that takes no workspace (callers that cannot allocate device memory):
+// the (max, argmax) partials of the greedy walk live in this array instead.  Every GPU the
+// library runs on holds its own copy at its own address until the process ends; in host code
+// the array's name is only a handle for hipGetSymbolAddress, never a device address.
+static __device__ __align__(256) unsigned char scratch[JK_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each device, looked up once
+
+hipError_t scratch_address(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));  // the current device's copy
+    if (e != hipSuccess) return e;
+    if (!ptr) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
+
 struct WsLayout {
   size_t coop, pmax, pidx, psum, resid, total;
 };
@@ -341,6 +370,32 @@ WsLayout ws_layout(int batch, int n_tree, int vocab, int mode) {
 
 size_t accept_workspace_bytes(int batch, int n_tree, int vocab, int mode) {
   return ws_layout(batch, n_tree, vocab, mode).total;
+}
+
+size_t accept_greedy_static_bytes(int batch, int n_tree, int vocab) {
+  return ws_layout(batch, n_tree, vocab, JK_GREEDY).total;
+}
+
+// Greedy acceptance with the partials in the library's own scratch array: the same two
+// kernels as launch_accept, no workspace argument, nothing allocated.  Nothing in the array
+// needs clearing: every partial the walk reads is written by the reduction of the same call.
+hipError_t launch_accept_greedy_static(const AcceptArgs& a, hipStream_t stream) {
+  void* base = nullptr;
+  hipError_t e = scratch_address(&base);
+  if (e != hipSuccess) return e;
+  const WsLayout w = ws_layout(a.batch, a.n_tree, a.vocab, JK_GREEDY);
+  if (w.total > (size_t)JK_STATIC_SCRATCH_BYTES) return hipErrorInvalidValue;  // (checked by the caller too)
+  char* ws = static_cast<char*>(base);
+  float* pmax = reinterpret_cast<float*>(ws + w.pmax);
+  int* pidx = reinterpret_cast<int*>(ws + w.pidx);
+  const int nch = n_chunks(a.vocab);
+  hipLaunchKernelGGL(row_reduce_kernel<false>, dim3(nch, a.batch * (a.n_tree + 1)), dim3(256), 0, stream, a.logits,
+                     a.vocab, 1.0, pmax, pidx, static_cast<double*>(nullptr));
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(walk_greedy_kernel, dim3(a.batch), dim3(128), 0, stream, a.n_tree, nch, a.max_depth, a.tokens,
+                     a.parent, pmax, pidx, a.out_path, a.out_len, a.out_bonus);
+  return hipGetLastError();
 }
 
 hipError_t launch_accept(const AcceptArgs& a, hipStream_t stream) {

@@ -280,6 +280,27 @@ jk_status jk_accept_path(int32_t batch, int32_t n_tree, int32_t vocab, int32_t m
                        workspace_bytes, hip_stream);
 }
 
+jk_status jk_accept_path_greedy_static(int32_t batch, int32_t n_tree, int32_t vocab, int32_t max_depth,
+                                       const int32_t* tree_tokens, const int32_t* parent,
+                                       const float* target_logits, int32_t* out_path, int32_t* out_accept_len,
+                                       int32_t* out_bonus_token, void* hip_stream) {
+  if (batch < 1 || vocab < 1 || max_depth < 1 || n_tree < 1) return JK_ERR_INVALID_ARG;
+  if (n_tree > JK_MAX_TREE) return JK_ERR_UNSUPPORTED;
+  if (!tree_tokens || !parent || !target_logits || !out_path || !out_accept_len || !out_bonus_token)
+    return JK_ERR_INVALID_ARG;
+  if (reinterpret_cast<uintptr_t>(target_logits) % 16) return JK_ERR_INVALID_ARG;
+  if ((long long)batch * (n_tree + 1) > 65535) return JK_ERR_UNSUPPORTED;
+  if (accept_greedy_static_bytes(batch, n_tree, vocab) > (size_t)JK_STATIC_SCRATCH_BYTES) return JK_ERR_SCRATCH_LIMIT;
+  AcceptArgs a;
+  a.batch = batch; a.n_tree = n_tree; a.vocab = vocab; a.max_depth = max_depth; a.mode = JK_GREEDY;
+  a.temperature = 1.f;
+  a.tokens = tree_tokens; a.parent = parent; a.logits = target_logits;
+  a.draft_probs = nullptr; a.uniforms = nullptr; a.draft_row = nullptr; a.n_draft_rows = 0;
+  a.out_path = out_path; a.out_len = out_accept_len; a.out_bonus = out_bonus_token;
+  a.workspace = nullptr;
+  return launch_accept_greedy_static(a, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? JK_OK : JK_ERR_HIP;
+}
+
 jk_status jk_accept_path_rows(int32_t batch, int32_t n_tree, int32_t vocab, int32_t max_depth,
                               const int32_t* tree_tokens, const int32_t* parent, const float* target_logits,
                               int32_t mode, float temperature, const float* draft_rows_all, int64_t n_draft_rows,
@@ -565,6 +586,7 @@ const char* jk_status_string(int32_t status) {
     case JK_ERR_UNSUPPORTED: return "unsupported shape";
     case JK_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case JK_ERR_HIP: return "HIP runtime error";
+    case JK_ERR_SCRATCH_LIMIT: return "input too large for the library's built-in scratch buffer";
     default: return "unknown status";
   }
 }

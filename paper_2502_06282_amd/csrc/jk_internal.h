@@ -64,6 +64,8 @@ struct AcceptArgs {
 };
 size_t accept_workspace_bytes(int batch, int n_tree, int vocab, int mode);
 hipError_t launch_accept(const AcceptArgs& a, hipStream_t stream);
+size_t accept_greedy_static_bytes(int batch, int n_tree, int vocab);
+hipError_t launch_accept_greedy_static(const AcceptArgs& a, hipStream_t stream);
 int device_cu_count();
 
 struct CommitArgs {
