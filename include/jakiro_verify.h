@@ -31,10 +31,13 @@
  *     pointers are ordinary host memory.  The caller owns every buffer.  The
  *     library allocates no device memory and keeps no state between calls;
  *     scratch comes from the caller's workspace (sizes from the *_workspace
- *     functions; 256-byte aligned).  A workspace handed to jk_accept_path must
- *     have been zero-filled once (jk_workspace_init, or any other means) before
- *     its first use; after that it can be reused for any number of calls of any
- *     shape it is large enough for.
+ *     functions; 256-byte aligned).  A workspace handed to jk_accept_path or
+ *     jk_tree_verify_attention(_paged) must have been zero-filled once
+ *     (jk_workspace_init, or any other means; of an attention workspace only the
+ *     first JK_WORKSPACE_HEADER_BYTES matter) before its first use; after that it can be reused for
+ *     any number of calls of any shape it is large enough for.  Those bytes hold
+ *     the sticky device error word (jk_last_device_error) and the words through
+ *     which workgroups of one call meet; the calls leave them consistent.
  *   - Calls enqueue work on `hip_stream` (a hipStream_t, NULL = default
  *     stream) and return without synchronising.  Outputs are valid once the
  *     stream has reached that point.  Calls that share a workspace must be
@@ -45,8 +48,11 @@
  *     committed prefix (several such nodes are allowed), and -1 <= parent[i] < i
  *     (any topological numbering, e.g. BFS).  Children of one parent are
  *     ordered left to right by increasing index.  The array lives on the
- *     device, so the library cannot check it: a node whose entry violates the
- *     rule is treated as having parent -1.  jk_validate_tree checks a host copy.
+ *     device, so the library cannot check it on the host: a node whose entry
+ *     violates the rule is treated as having parent -1, and the kernel that
+ *     repaired it sets JK_DEVERR_BAD_TREE in the workspace's error word
+ *     (Section 3.1.2: candidates form a tree; a repaired tree is not the one
+ *     the caller drafted).  jk_validate_tree checks a host copy.
  */
 #ifndef JAKIRO_VERIFY_H
 #define JAKIRO_VERIFY_H
@@ -72,6 +78,7 @@ typedef enum { JK_BF16 = 0, JK_F32 = 1 } jk_dtype;
 typedef enum { JK_GREEDY = 0, JK_SAMPLE = 1 } jk_mode;
 
 #define JK_MAX_TREE 128 /* largest supported number of tree nodes */
+#define JK_WORKSPACE_HEADER_BYTES 32768 /* start of an attention workspace that must be zero before its first use */
 #define JK_STATIC_SCRATCH_BYTES (1 << 20) /* the library's built-in scratch buffer (jk_accept_path_greedy_static) */
 
 /* Shape and layout of one attention call.  Strides are in ELEMENTS; the
@@ -468,11 +475,60 @@ jk_status jk_linear(int32_t m, int32_t n, int32_t k, const void* x, const void* 
                     void* out_bf16, float* out_f32, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Zero-fills a workspace with a small kernel on `hip_stream` (safe under HIP-graph
- * capture).  Needed once per workspace before its first jk_accept_path call: the
- * cooperative sampling walk synchronises its workgroups through tagged words in
- * the workspace and relies on tags only ever growing.  Returns JK_ERR_WORKSPACE for
- * a null or misaligned pointer. */
+ * capture).  Needed once per workspace before its first jk_accept_path or
+ * jk_tree_verify_attention(_paged) call: the cooperative sampling walk synchronises
+ * its workgroups through tagged words in the workspace and relies on tags only ever
+ * growing, the attention kernel counts the arrivals of a row tile's key splits in
+ * words that every call returns to zero, and the error word is sticky.  Returns
+ * JK_ERR_WORKSPACE for a null or misaligned pointer. */
 jk_status jk_workspace_init(void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Device-side findings of the calls that used `workspace` (an attention or acceptance
+ * workspace) since it was last zero-filled: the OR of the JK_DEVERR_* bits below, or -1 if
+ * the word cannot be read.  Synchronous: copies one word from the device (hipMemcpy), so call
+ * it after the work of interest has been synchronised, never under stream capture.  The word
+ * is sticky; jk_workspace_init clears it.  (The tree of Section 3.1.2 and the token ids live in
+ * device memory, so the host-side checks of the entry points cannot see them: a kernel that
+ * meets a bad entry repairs it - parent -1, token or page id clamped - and records the fact.) */
+#define JK_DEVERR_BAD_TREE 1    /* a parent[] entry outside [-1, i-1] was treated as -1 */
+#define JK_DEVERR_BAD_TOKEN 2   /* a token id outside [0, vocab) was clamped (sampling walk) */
+#define JK_DEVERR_BAD_PAGE 4    /* a block-table entry outside [0, n_pages) was clamped */
+#define JK_DEVERR_MERGE_WAIT 8  /* attention: a workgroup stopped waiting for its key splits' partners; the
+                                   result is still complete once every workgroup has run (the last one to
+                                   arrive merges what the others left), but the call was slow */
+#define JK_DEVERR_WALK_WAIT 16  /* sampling walk: a tree's workgroups did not meet; accept_len = -1 for it */
+int32_t jk_last_device_error(const void* workspace);
+
+/* How the next jk_tree_verify_attention(_paged) call with this descriptor and bound would be cut
+ * into workgroups on the current device (for reports and tests; the plan is the library's own
+ * business and may change): plan_out[0..5] = waves along the query rows, waves along the keys,
+ * 32-key tiles per wave and round, row tiles, key splits, 1 if the splits are merged inside the
+ * attention kernel (0: by a second kernel; always 0 for the fp32 path and for one split). */
+jk_status jk_tree_verify_attention_plan(const jk_attn_desc* desc, int32_t max_prefix_len, int32_t* plan_out);
+
+/* Once per device and process, before the first jk_tree_verify_attention call that should merge
+ * its key splits inside the attention kernel: launches a small probe on `hip_stream` that records
+ * on which XCD consecutive workgroups run, WAITS for it (the only call besides
+ * jk_last_device_error that synchronises), and remembers the answer for the current device.  The
+ * merge inside the kernel lets the workgroups of one row tile meet in one XCD's L2 and is only
+ * used on a device where workgroups n and n + 8 were seen to share an XCD; without jk_init (or
+ * where the probe says otherwise) attention uses a second, merging kernel launch instead - same
+ * results, bit for bit.  Must not be called under stream capture.  Returns JK_ERR_HIP on failure. */
+jk_status jk_init(void* hip_stream);
+
+/* Overrides for experiments and tests; nothing in normal use needs them.  The library's launch
+ * plans are functions of the descriptors and the device; these knobs force parts of them.
+ * Process-wide, not thread-safe against concurrent calls.  Names: "attn_wm", "attn_wn" (wave
+ * arrangement of the bf16 attention kernel: 4x1 or 2x2; 0 = automatic), "attn_splits" (key
+ * splits, 0 = automatic), "attn_fused" (-1 automatic, 0 never merge inside the kernel, 1 whenever
+ * the grid allows it), "accept_single" (1: one-workgroup sampling walk), "spin_limit" (polls of
+ * the bounded waits; -1 default, 0 = give up at once: the give-up paths run with every kernel
+ * ending normally), "verbose" (1: print attention plans to stderr).  The same knobs are seeded
+ * once, when the library is loaded, from the environment variables JK_ATTN_WM, JK_ATTN_WN,
+ * JK_ATTN_SPLITS, JK_ATTN_FUSED, JK_ACCEPT_SINGLE, JK_SPIN_LIMIT, JK_ATTN_VERBOSE.  With an
+ * override in force jk_tree_verify_attention_workspace answers for the forced plan.
+ * Returns JK_ERR_INVALID_ARG for an unknown name. */
+jk_status jk_set_tuning(const char* name, int32_t value);
 
 /* Measurement aid, not part of the method: enqueues a kernel that only streams `bytes`
  * bytes (device, 16-byte aligned) with 128-bit loads.  Timing it gives the ceiling that an

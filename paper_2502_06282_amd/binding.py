@@ -15,6 +15,8 @@ _LIB_PATH = os.path.join(_HERE, "libjakiro_verify.so")
 
 JK_BF16, JK_F32 = 0, 1
 JK_GREEDY, JK_SAMPLE = 0, 1
+JK_DEVERR_BAD_TREE, JK_DEVERR_BAD_TOKEN, JK_DEVERR_BAD_PAGE, JK_DEVERR_MERGE_WAIT, JK_DEVERR_WALK_WAIT = 1, 2, 4, 8, 16
+JK_WORKSPACE_HEADER_BYTES = 32768
 JK_HEADS_DECOUPLED, JK_HEADS_CONTRASTIVE = 0, 1
 MAX_TREE = 128
 
@@ -64,9 +66,9 @@ class PagedKV(ctypes.Structure):
                 ("n_pages", ctypes.c_int32), ("page_stride", ctypes.c_int64)]
 
 
-EXPORTS = ("jk_tree_verify_attention_workspace", "jk_tree_verify_attention", "jk_tree_verify_attention_paged",
+EXPORTS = ("jk_tree_verify_attention_workspace", "jk_tree_verify_attention_plan", "jk_tree_verify_attention", "jk_tree_verify_attention_paged",
            "jk_commit_path_layers_paged", "jk_accept_path_workspace",
-           "jk_accept_path", "jk_accept_path_greedy_static", "jk_accept_path_rows", "jk_draft_heads_workspace", "jk_draft_heads", "jk_moe_experts_workspace", "jk_moe_experts", "jk_linear_workspace", "jk_linear", "jk_tree_grow", "jk_tree_grow_tail", "jk_tree_fill_static", "jk_tree_finalize", "jk_gather_draft_probs", "jk_commit_path", "jk_commit_path_layers", "jk_workspace_init", "jk_stream_read_probe", "jk_validate_tree", "jk_status_string", "jk_version")
+           "jk_accept_path", "jk_accept_path_greedy_static", "jk_accept_path_rows", "jk_draft_heads_workspace", "jk_draft_heads", "jk_moe_experts_workspace", "jk_moe_experts", "jk_linear_workspace", "jk_linear", "jk_tree_grow", "jk_tree_grow_tail", "jk_tree_fill_static", "jk_tree_finalize", "jk_gather_draft_probs", "jk_commit_path", "jk_commit_path_layers", "jk_workspace_init", "jk_init", "jk_set_tuning", "jk_last_device_error", "jk_stream_read_probe", "jk_validate_tree", "jk_status_string", "jk_version")
 
 
 def library_path() -> str:
@@ -130,6 +132,14 @@ def lib() -> ctypes.CDLL:
         l.jk_gather_draft_probs.argtypes = [i32, i32, i32, vp, ctypes.c_int64, vp, vp, vp]
         l.jk_workspace_init.restype = i32
         l.jk_workspace_init.argtypes = [vp, sz, vp]
+        l.jk_tree_verify_attention_plan.restype = i32
+        l.jk_tree_verify_attention_plan.argtypes = [ctypes.POINTER(AttnDesc), i32, ctypes.POINTER(i32)]
+        l.jk_init.restype = i32
+        l.jk_init.argtypes = [vp]
+        l.jk_set_tuning.restype = i32
+        l.jk_set_tuning.argtypes = [ctypes.c_char_p, i32]
+        l.jk_last_device_error.restype = i32
+        l.jk_last_device_error.argtypes = [vp]
         l.jk_stream_read_probe.restype = i32
         l.jk_stream_read_probe.argtypes = [vp, sz, vp, vp]
         l.jk_validate_tree.restype = i32
@@ -156,10 +166,45 @@ def _ptr(t) -> Optional[int]:
     return None if t is None else t.data_ptr()
 
 
+_initialised_devices = set()
+
+
 def _stream_handle(stream) -> Optional[int]:
+    """The hipStream_t of `stream` (default: torch's current stream).  The first use on a device also runs
+    jk_init there (a short synchronous probe), unless that stream is being captured into a graph."""
     import torch
     s = torch.cuda.current_stream() if stream is None else stream
-    return s.cuda_stream or None
+    handle = s.cuda_stream or None
+    dev = torch.cuda.current_device()
+    if dev not in _initialised_devices and not torch.cuda.is_current_stream_capturing():
+        st = lib().jk_init(handle)
+        if st != 0:
+            raise JakiroError(st, "jk_init")
+        _initialised_devices.add(dev)
+    return handle
+
+
+def _new_workspace(nbytes: int, device, stream):
+    """A zero-filled workspace whose fill is ordered on the stream the library call will use, and which the
+    caching allocator will not hand out again while that stream may still be using it."""
+    import torch
+    s = torch.cuda.current_stream(device) if stream is None else stream
+    with torch.cuda.stream(s):
+        ws = torch.zeros(nbytes, dtype=torch.uint8, device=device)
+    ws.record_stream(s)
+    return ws
+
+
+def set_tuning(name: str, value: int) -> None:
+    """jk_set_tuning: force part of a launch plan (experiments and tests)."""
+    st = lib().jk_set_tuning(name.encode(), int(value))
+    if st != 0:
+        raise JakiroError(st, f"jk_set_tuning({name})")
+
+
+def last_device_error(workspace) -> int:
+    """jk_last_device_error: the sticky JK_DEVERR_* bits of an attention or acceptance workspace (synchronous)."""
+    return int(lib().jk_last_device_error(_ptr(workspace)))
 
 
 def _make_desc(q, k_cache, k_tree, out, scale: float) -> AttnDesc:
@@ -184,6 +229,17 @@ def _make_desc(q, k_cache, k_tree, out, scale: float) -> AttnDesc:
 def tree_verify_attention_workspace(q, k_cache, k_tree, max_prefix_len: int, scale: float = 0.0) -> int:
     d = _make_desc(q, k_cache, k_tree, q, scale)
     return int(lib().jk_tree_verify_attention_workspace(ctypes.byref(d), int(max_prefix_len)))
+
+
+def tree_verify_attention_plan(q, k_cache, k_tree, max_prefix_len: int, scale: float = 0.0) -> dict:
+    """jk_tree_verify_attention_plan as a dict (wm, wn, kt, row_tiles, splits, fused)."""
+    _stream_handle(None)  # (the plan depends on jk_init having run on this device)
+    d = _make_desc(q, k_cache, k_tree, q, scale)
+    out = (ctypes.c_int32 * 6)()
+    st = lib().jk_tree_verify_attention_plan(ctypes.byref(d), int(max_prefix_len), out)
+    if st != 0:
+        raise JakiroError(st, "jk_tree_verify_attention_plan")
+    return dict(zip(("wm", "wn", "kt", "row_tiles", "splits", "fused"), [int(v) for v in out]))
 
 
 def tree_verify_attention(q, k_cache, v_cache, k_tree, v_tree, parent, prefix_len,
@@ -213,7 +269,7 @@ def tree_verify_attention(q, k_cache, v_cache, k_tree, v_tree, parent, prefix_le
     if need == 0:
         raise JakiroError(3, "jk_tree_verify_attention_workspace")
     if workspace is None:
-        workspace = torch.zeros(need, dtype=torch.uint8, device=q.device)  # must start zero-filled
+        workspace = _new_workspace(need, q.device, stream)
     st = lib().jk_tree_verify_attention(ctypes.byref(d), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(k_tree),
                                         _ptr(v_tree), _ptr(parent), _ptr(prefix_len), int(max_prefix_len),
                                         _ptr(out), _ptr(workspace), workspace.numel() * workspace.element_size(),
@@ -269,7 +325,7 @@ def accept_path(tree_tokens, parent, target_logits, mode: int = JK_GREEDY, tempe
     if need == 0:
         raise JakiroError(3, "jk_accept_path_workspace")
     if workspace is None:
-        workspace = torch.zeros(need, dtype=torch.uint8, device=dev)  # must start zero-filled
+        workspace = _new_workspace(need, dev, stream)
     st = lib().jk_accept_path(B, N, V, int(max_depth), _ptr(tree_tokens), _ptr(parent), _ptr(target_logits),
                               int(mode), float(temperature), _ptr(draft_probs), _ptr(uniforms), _ptr(path),
                               _ptr(alen), _ptr(bonus), _ptr(workspace),
@@ -427,7 +483,7 @@ def tree_verify_attention_paged(q, k_pool, v_pool, block_table, k_tree, v_tree, 
         need = int(lib().jk_tree_verify_attention_workspace(ctypes.byref(d), int(max_prefix_len)))
         if need == 0:
             raise JakiroError(3, "jk_tree_verify_attention_workspace")
-        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+        workspace = _new_workspace(need, q.device, stream)
     prepare_tree_verify_attention_paged(q, k_pool, v_pool, block_table, k_tree, v_tree, parent, prefix_len, out,
                                         workspace, max_prefix_len, scale).launch(stream)
     return out
@@ -740,7 +796,7 @@ def accept_path_rows(tree_tokens, parent, target_logits, q_all, q_row, uniforms,
     bonus = torch.empty((B,), dtype=torch.int32, device=dev)
     need = accept_path_workspace(B, N, V, JK_SAMPLE)
     if workspace is None:
-        workspace = torch.zeros(need, dtype=torch.uint8, device=dev)
+        workspace = _new_workspace(need, dev, stream)
     st = lib().jk_accept_path_rows(B, N, V, int(max_depth), _ptr(tree_tokens), _ptr(parent), _ptr(target_logits),
                                    JK_SAMPLE, float(temperature), _ptr(q_all), q_all.numel() // V, _ptr(q_row),
                                    _ptr(uniforms), _ptr(path), _ptr(alen), _ptr(bonus), _ptr(workspace),

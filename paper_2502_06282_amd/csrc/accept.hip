@@ -98,7 +98,16 @@ __global__ __launch_bounds__(256) void row_reduce_kernel(const float* __restrict
   if (tid == 0) { pmax[slot] = best; psum[slot] = s_sum[0] + s_sum[1] + s_sum[2] + s_sum[3]; }
 }
 
-__device__ __forceinline__ int sanitize_parent(int pa, int k) { return (pa >= -1 && pa < k) ? pa : -1; }
+// A parent entry that breaks -1 <= parent[k] < k counts as -1, and a token id outside the vocabulary is
+// clamped into it; either is recorded in the workspace's sticky error word (err may be null).
+__device__ __forceinline__ void report(unsigned* err, unsigned bit) {
+  if (err) __hip_atomic_fetch_or(err, bit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ int sanitize_parent(int pa, int k, unsigned* err) {
+  if (pa >= -1 && pa < k) return pa;
+  report(err, kDevErrBadTree);
+  return -1;
+}
 
 // ------------------------------------------------------------------ greedy walk
 __global__ __launch_bounds__(128) void walk_greedy_kernel(int n_tree, int nch, int max_depth,
@@ -106,7 +115,8 @@ __global__ __launch_bounds__(128) void walk_greedy_kernel(int n_tree, int nch, i
                                                           const int* __restrict__ parent,
                                                           const float* __restrict__ pmax,
                                                           const int* __restrict__ pidx, int* __restrict__ out_path,
-                                                          int* __restrict__ out_len, int* __restrict__ out_bonus) {
+                                                          int* __restrict__ out_len, int* __restrict__ out_bonus,
+                                                          unsigned* err) {
   __shared__ int amax[JK_MAX_TREE + 1];
   __shared__ int par_s[JK_MAX_TREE];
   __shared__ int ok[JK_MAX_TREE];
@@ -131,7 +141,7 @@ __global__ __launch_bounds__(128) void walk_greedy_kernel(int n_tree, int nch, i
     }
     amax[r] = (bi == 0x7fffffff) ? 0 : bi;  // a row of -inf only: id 0, the first maximum
   }
-  if (tid < n_tree) par_s[tid] = sanitize_parent(parent[(long long)b * n_tree + tid], tid);
+  if (tid < n_tree) par_s[tid] = sanitize_parent(parent[(long long)b * n_tree + tid], tid, err);
   __syncthreads();
   if (tid < n_tree) ok[tid] = (tokens[(long long)b * n_tree + tid] == amax[par_s[tid] + 1]);
   __syncthreads();
@@ -181,6 +191,7 @@ struct WalkParams {
   const double* psum;
   double* resid;  // [batch][2][vocab] unnormalised residuals (ping-pong)
   int *out_path, *out_len, *out_bonus;
+  unsigned* err;  // the workspace's sticky device error word
 };
 
 __global__ __launch_bounds__(kWalkThreads) void walk_sample_kernel(WalkParams p) {
@@ -192,7 +203,11 @@ __global__ __launch_bounds__(kWalkThreads) void walk_sample_kernel(WalkParams p)
   const int b = blockIdx.x, tid = threadIdx.x;
   const int N = p.n_tree, V = p.vocab;
   const int rows = N + 1;
-  if (tid < N) par_s[tid] = sanitize_parent(p.parent[(long long)b * N + tid], tid);
+  if (tid < N) {
+    par_s[tid] = sanitize_parent(p.parent[(long long)b * N + tid], tid, p.err);
+    const int t = p.tokens[(long long)b * N + tid];
+    if (t < 0 || t >= V) report(p.err, kDevErrBadToken);
+  }
   __syncthreads();
 
   const int* tok = p.tokens + (long long)b * N;
@@ -346,15 +361,24 @@ hipError_t scratch_address(void** out) {
   return hipSuccess;
 }
 
+// Where do consecutive workgroups run?  Every workgroup of a small grid records the id of the XCD
+// it is on (the attention kernel merges its key splits inside one XCD's L2 and relies on the
+// hardware dealing workgroup n to XCD n mod 8).
+__global__ void xcd_probe_kernel(unsigned* out) {
+  unsigned id;
+  asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(id));
+  if (threadIdx.x == 0) out[blockIdx.x] = id & 0xfu;
+}
+
 struct WsLayout {
-  size_t coop, pmax, pidx, psum, resid, total;
+  size_t coop, pmax, pidx, psum, resid, total;  // (the error word's header sits in front of them)
 };
 WsLayout ws_layout(int batch, int n_tree, int vocab, int mode) {
   WsLayout w{};
   const size_t rows = (size_t)batch * (n_tree + 1);
   const size_t slots = rows * n_chunks(vocab);
   auto up = [](size_t x) { return (x + 255) / 256 * 256; };
-  size_t off = 0;
+  size_t off = kWsErrBytes;
   // the exchange table of the cooperative walk comes first: its per-tree epoch words keep
   // their place whatever the other sizes are, so a workspace needs zeroing only once
   w.coop = off; off += (mode == JK_SAMPLE) ? up(accept_coop_bytes(batch)) : 0;
@@ -370,6 +394,27 @@ WsLayout ws_layout(int batch, int n_tree, int vocab, int mode) {
 
 size_t accept_workspace_bytes(int batch, int n_tree, int vocab, int mode) {
   return ws_layout(batch, n_tree, vocab, mode).total;
+}
+
+// Synchronous, for jk_init: resolves the scratch array of the current device and runs the probe
+// in it.  *round_robin: workgroups whose numbers agree modulo 8 were all on one XCD.
+hipError_t probe_xcd_placement(hipStream_t stream, bool* round_robin) {
+  constexpr int kProbeWgs = 256;
+  void* base = nullptr;
+  hipError_t e = scratch_address(&base);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(xcd_probe_kernel, dim3(kProbeWgs), dim3(64), 0, stream, static_cast<unsigned*>(base));
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  unsigned ids[kProbeWgs];
+  e = hipMemcpyAsync(ids, base, sizeof(ids), hipMemcpyDeviceToHost, stream);
+  if (e != hipSuccess) return e;
+  e = hipStreamSynchronize(stream);
+  if (e != hipSuccess) return e;
+  bool ok = true;
+  for (int n = 8; n < kProbeWgs; ++n) ok = ok && ids[n] == ids[n & 7];
+  *round_robin = ok;
+  return hipSuccess;
 }
 
 size_t accept_greedy_static_bytes(int batch, int n_tree, int vocab) {
@@ -394,7 +439,7 @@ hipError_t launch_accept_greedy_static(const AcceptArgs& a, hipStream_t stream) 
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(walk_greedy_kernel, dim3(a.batch), dim3(128), 0, stream, a.n_tree, nch, a.max_depth, a.tokens,
-                     a.parent, pmax, pidx, a.out_path, a.out_len, a.out_bonus);
+                     a.parent, pmax, pidx, a.out_path, a.out_len, a.out_bonus, static_cast<unsigned*>(nullptr));
   return hipGetLastError();
 }
 
@@ -413,13 +458,14 @@ hipError_t launch_accept(const AcceptArgs& a, hipStream_t stream) {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(walk_greedy_kernel, dim3(a.batch), dim3(128), 0, stream, a.n_tree, nch, a.max_depth,
-                       a.tokens, a.parent, pmax, pidx, a.out_path, a.out_len, a.out_bonus);
+                       a.tokens, a.parent, pmax, pidx, a.out_path, a.out_len, a.out_bonus,
+                       reinterpret_cast<unsigned*>(ws));
     return hipGetLastError();
   }
   {
     int W = 0, slice = 0;
-    const char* force = std::getenv("JK_ACCEPT_SINGLE");  // tuning/testing: force the one-workgroup walk
-    if (!(force && force[0] == '1') && accept_coop_plan(a.batch, a.vocab, device_cu_count(), &W, &slice))
+    // (tuning/testing: accept_single forces the one-workgroup walk)
+    if (!tuning().accept_single && accept_coop_plan(a.batch, a.vocab, device_cu_count(), &W, &slice))
       return launch_accept_coop(a, ws + w.coop, W, slice, stream);
   }
   const double temp = (double)a.temperature;
@@ -435,6 +481,7 @@ hipError_t launch_accept(const AcceptArgs& a, hipStream_t stream) {
   wp.draft_row = a.draft_row; wp.n_draft_rows = a.n_draft_rows;
   wp.pmax = pmax; wp.psum = psum; wp.resid = resid;
   wp.out_path = a.out_path; wp.out_len = a.out_len; wp.out_bonus = a.out_bonus;
+  wp.err = reinterpret_cast<unsigned*>(ws);
   hipLaunchKernelGGL(walk_sample_kernel, dim3(a.batch), dim3(kWalkThreads), 0, stream, wp);
   return hipGetLastError();
 }

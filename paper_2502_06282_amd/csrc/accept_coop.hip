@@ -44,6 +44,7 @@ struct CoopParams {
   unsigned long long* epoch;  // [batch] workspace words, each bumped once per call by its tree
   Slot* slots;                // [batch][2][W]
   int *out_path, *out_len, *out_bonus;
+  unsigned* err;  // the workspace's sticky device error word
 };
 
 __device__ __forceinline__ double block_sum(double v, double* red) {
@@ -245,6 +246,10 @@ __global__ __launch_bounds__(kCoopThreads) void walk_sample_coop_kernel(CoopPara
   if (tid < N) {
     par_s[tid] = (pa_reg >= -1 && pa_reg < tid) ? pa_reg : -1;
     tok_s[tid] = min(max(tok_reg, 0), V - 1);  // a token id outside the vocabulary must not fault
+    if (w == 0) {  // both repairs are recorded in the workspace's error word
+      if (par_s[tid] != pa_reg) __hip_atomic_fetch_or(p.err, kDevErrBadTree, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (tok_s[tid] != tok_reg) __hip_atomic_fetch_or(p.err, kDevErrBadToken, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
   }
   if (tid <= N) uni_s[tid] = uni_reg;
   __syncthreads();
@@ -410,6 +415,7 @@ __global__ __launch_bounds__(kCoopThreads) void walk_sample_coop_kernel(CoopPara
   if (s_fail && tid == 0 && w == 0) {
     p.out_len[b] = -1;
     p.out_bonus[b] = -1;
+    __hip_atomic_fetch_or(p.err, kDevErrWalkWait, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
   // every workgroup of this tree read the epoch before its first exchange, and nobody gets
   // here before having exchanged with all of them: safe to advance it for the next call
@@ -436,6 +442,7 @@ bool accept_coop_plan(int batch, int vocab, int cus, int* W, int* slice) {
 
 hipError_t launch_accept_coop(const AcceptArgs& a, void* coop_ws, int W, int slice, hipStream_t stream) {
   CoopParams cp;
+  cp.err = static_cast<unsigned*>(a.workspace);
   cp.n_tree = a.n_tree; cp.vocab = a.vocab; cp.max_depth = a.max_depth; cp.W = W; cp.slice = slice;
   cp.inv_temp = 1.0 / (double)a.temperature;
   cp.tokens = a.tokens; cp.parent = a.parent;

@@ -24,6 +24,39 @@ int device_cu_count() {
 }
 
 namespace {
+int env_int(const char* name, int fallback) {
+  const char* e = std::getenv(name);
+  return e && *e ? std::atoi(e) : fallback;
+}
+Tuning tuning_from_env() {
+  Tuning t;
+  t.attn_wm = env_int("JK_ATTN_WM", 0);
+  t.attn_wn = env_int("JK_ATTN_WN", 0);
+  t.attn_splits = env_int("JK_ATTN_SPLITS", 0);
+  t.attn_fused = env_int("JK_ATTN_FUSED", -1);
+  t.accept_single = env_int("JK_ACCEPT_SINGLE", 0);
+  t.spin_limit = env_int("JK_SPIN_LIMIT", -1);
+  t.verbose = env_int("JK_ATTN_VERBOSE", 0);
+  return t;
+}
+}  // namespace
+
+Tuning& tuning() {
+  static Tuning t = tuning_from_env();  // the environment is read once, here
+  return t;
+}
+
+namespace {
+constexpr int kMaxDevices = 64;
+int g_xcd_state[kMaxDevices];  // per device: 0 not checked (jk_init not called), 1 round-robin verified, 2 not round-robin
+}  // namespace
+
+bool xcd_placement_verified() {
+  int dev = -1;
+  return hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < kMaxDevices && g_xcd_state[dev] == 1;
+}
+
+namespace {
 bool desc_ok(const jk_attn_desc& d) {
   if (d.batch < 1 || d.n_tree < 1 || d.n_tree > JK_MAX_TREE) return false;
   if (d.n_q_heads < 1 || d.n_kv_heads < 1 || d.n_q_heads % d.n_kv_heads) return false;
@@ -37,7 +70,7 @@ bool shape_supported(const jk_attn_desc& d) {
 }
 }  // namespace
 
-bool make_attn_plan(const jk_attn_desc& d, int max_prefix_len, AttnPlan* pl) {
+bool make_attn_plan(const jk_attn_desc& d, int max_prefix_len, bool fused_allowed, AttnPlan* pl) {
   if (!desc_ok(d) || !shape_supported(d) || max_prefix_len < 0 || max_prefix_len > (1 << 24)) return false;
   const int G = d.n_q_heads / d.n_kv_heads;
   pl->m_rows = d.n_tree * G;
@@ -50,10 +83,9 @@ bool make_attn_plan(const jk_attn_desc& d, int max_prefix_len, AttnPlan* pl) {
     const int n_tiles = (max_prefix_len + kTileKeys - 1) / kTileKeys + (d.n_tree + kTileKeys - 1) / kTileKeys;
     const double kv_bytes = 2.0 * (max_prefix_len + d.n_tree) * d.head_dim * 2.0;
     const int slots = device_cu_count();  // one workgroup per CU measured best (partials cost more than idle slots)
-    int forced_wm = 0, forced_wn = 0, forced_s = 0;
-    if (const char* e = std::getenv("JK_ATTN_WM")) forced_wm = std::atoi(e);       // tuning overrides
-    if (const char* e = std::getenv("JK_ATTN_WN")) forced_wn = std::atoi(e);
-    if (const char* e = std::getenv("JK_ATTN_SPLITS")) forced_s = std::atoi(e);
+    const Tuning& tn = tuning();
+    const int forced_wm = tn.attn_wm, forced_wn = tn.attn_wn, forced_s = tn.attn_splits;  // tuning overrides
+    const int fused_mode = !fused_allowed ? 0 : tn.attn_fused;  // 0 never, 1 whenever possible, -1 when it pays
     static const int kArr[][2] = {{2, 2}, {4, 1}};  // waves along rows x along keys
     bool forced_ok = false;
     for (const auto& a : kArr) forced_ok |= (a[0] == forced_wm && a[1] == forced_wn);
@@ -86,8 +118,24 @@ bool make_attn_plan(const jk_attn_desc& d, int max_prefix_len, AttnPlan* pl) {
         const double t_round = (wn == 1 ? 1.33 : 0.95) * d.head_dim / 128.0;
         // rounds of the longest split: the 4x1 arrangement deals tiles (an odd last tile costs about
         // half a round), the 2x2 arrangement whole rounds
-        const double rounds = wn == 1 ? 0.5 * (double)((n_tiles + s - 1) / s)
-                                      : (double)(((n_tiles + wn * kt - 1) / (wn * kt) + s - 1) / s);
+        double rounds;
+        if (wn == 1) {
+          // (the kernel's own dealing: pairs of full prefix tiles evenly, the tail - two pairs a tile -
+          // with the last split)
+          const long long P = (max_prefix_len / kTileKeys) / 2, tail = n_tiles - 2 * P;
+          if (s == 1) {
+            rounds = (double)(P + 2 * tail);
+          } else {
+            const long long per = (P + 2 * tail + s - 1) / s;
+            long long p_last = per - 2 * tail;
+            p_last = p_last < 0 ? 0 : (p_last > P ? P : p_last);
+            const long long rest = P - p_last, most = (rest + s - 2) / (s - 1);
+            const long long last = p_last + 2 * tail;
+            rounds = (double)(most > last ? most : last);
+          }
+        } else {
+          rounds = (double)(((n_tiles + wn * kt - 1) / (wn * kt) + s - 1) / s);
+        }
         const double per_cu = (double)(wgs * s) / slots;
         // 4x1 workgroups that share a CU overlap each other's matrix and vector phases: two of
         // them take 1.58 times one's time (measured on c5), plus a part of a workgroup of tail
@@ -99,22 +147,44 @@ bool make_attn_plan(const jk_attn_desc& d, int max_prefix_len, AttnPlan* pl) {
         const double active = (double)(wgs * s < slots ? wgs * s : slots);
         const double rate = active * 22.0e3 < 4.0e6 ? active * 22.0e3 : 4.0e6;  // bytes per microsecond
         const double stream_us = imbalance * (double)units * kv_bytes * (1.0 + 0.25 * (n_qtiles - 1)) / rate;
-        // (partials: 0.28 us per MB when the grid is one turn of workgroups and they are stored
-        // through to memory, 0.4 when they take the ordinary route and the merge kernel is large)
-        const double partial_us =
-            s > 1 ? (per_cu > 1.0 && wn == 1 ? 0.4e-6 : 0.28e-6) * (double)units * s * pl->m_rows * d.head_dim * 2.0 : 0.0;
+        // Merge inside the kernel: possible when every workgroup is resident at once (here: at most
+        // one per CU, or two when forced) and the workgroup numbering puts all splits of a (unit, row
+        // tile) group on one XCD: logical ids are dealt to the 8 XCDs in contiguous ranges of
+        // total / 8, and a unit's ids are contiguous, so every unit's range must sit inside one.
+        // (and one thread per (row of a slice, split padded to a power of two); partials below 2^31 bytes)
+        int s_pow2 = 1;
+        while (s_pow2 < s) s_pow2 *= 2;
+        bool can_fuse = fused_mode != 0 && s > 1 && wgs <= kMaxFusedGroups &&
+                        ((q_rows + s - 1) / s) * s_pow2 <= 64 * wm * wn &&
+                        (double)units * s * n_qtiles * q_rows * d.head_dim * 2.0 < 2.0e9 &&
+                        wgs * s <= (long long)slots * 2;  // (two of these workgroups fit a CU: all resident)
+        if (can_fuse) {
+          const long long per_unit = s * n_qtiles, per_xcd = (wgs * s + 7) / 8;
+          for (long long u = 0; u < units && can_fuse; ++u)
+            can_fuse = (u * per_unit) / per_xcd == ((u + 1) * per_unit - 1) / per_xcd;
+        }
+        // Partials (bf16): merged inside the kernel they stay in L2 (written once, read once, about
+        // 2 us of exchange latency whatever their size plus 0.1 us per MB); with the stand-alone merge
+        // kernel they cost a second launch (about 3 us) and 0.28 us per MB when the grid is one turn
+        // of workgroups and they are stored through to memory, 0.4 when they take the ordinary route
+        const double part_mb = 1.0e-6 * (double)units * s * pl->m_rows * d.head_dim * 2.0;
+        const double partial_us = s <= 1 ? 0.0
+                                  : can_fuse ? 2.0 + 0.1 * part_mb
+                                             : 3.0 + (per_cu > 1.0 && wn == 1 ? 0.4 : 0.28) * part_mb;
         // (near ties go to the count that gives every CU a workgroup: 2 % for an idle CU)
         const double cost = ((loop_us > stream_us ? loop_us : stream_us) + partial_us) * (active < slots ? 1.02 : 1.0);
         if (!have || cost < best_cost) {
           have = true;
           best_cost = cost;
           pl->wm = wm; pl->wn = wn; pl->kt = kt; pl->q_rows = q_rows; pl->n_qtiles = n_qtiles; pl->splits = (int)s;
+          pl->fused = can_fuse ? 1 : 0;
         }
       }
     }
     if (!have) return false;
     pl->m_pad = pl->n_qtiles * pl->q_rows;
   } else {
+    pl->fused = 0;
     pl->wm = pl->wn = pl->kt = 1;
     pl->q_rows = 1;
     pl->n_qtiles = pl->m_rows;
@@ -129,11 +199,7 @@ bool make_attn_plan(const jk_attn_desc& d, int max_prefix_len, AttnPlan* pl) {
   const bool need_parts = (d.dtype == JK_F32) || pl->splits > 1;
   pl->part_o_bytes = need_parts ? up(rows * d.head_dim * (d.dtype == JK_BF16 ? 2 : sizeof(float))) : 0;
   pl->part_ml_bytes = need_parts ? up(rows * sizeof(float2)) : 0;
-  pl->total_bytes = pl->part_o_bytes + pl->part_ml_bytes;
-  if (pl->total_bytes == 0) pl->total_bytes = 256;  // never ask the caller for a zero-byte buffer
-  if (std::getenv("JK_ATTN_VERBOSE"))
-    std::fprintf(stderr, "jk attention plan: waves %dx%d, %d tile(s) per wave and round, %d row tile(s), %d split(s)\n",
-                 pl->wm, pl->wn, pl->kt, pl->n_qtiles, pl->splits);
+  pl->total_bytes = kAttnHeaderBytes + pl->part_o_bytes + pl->part_ml_bytes;
   return true;
 }
 
@@ -144,9 +210,22 @@ using namespace jk;
 extern "C" {
 
 size_t jk_tree_verify_attention_workspace(const jk_attn_desc* desc, int32_t max_prefix_len) {
+  // Whether the splits are merged inside the kernel depends on jk_init having verified the device,
+  // and the two plans may cut the work differently: the size covers both, so that it is a function
+  // of the descriptor and the bound alone.
+  AttnPlan a, b;
+  if (!desc || !make_attn_plan(*desc, max_prefix_len, false, &a) || !make_attn_plan(*desc, max_prefix_len, true, &b))
+    return 0;
+  return a.total_bytes > b.total_bytes ? a.total_bytes : b.total_bytes;
+}
+
+jk_status jk_tree_verify_attention_plan(const jk_attn_desc* desc, int32_t max_prefix_len, int32_t* plan_out) {
+  if (!desc || !plan_out) return JK_ERR_INVALID_ARG;
   AttnPlan pl;
-  if (!desc || !make_attn_plan(*desc, max_prefix_len, &pl)) return 0;
-  return pl.total_bytes;
+  if (!make_attn_plan(*desc, max_prefix_len, xcd_placement_verified(), &pl)) return JK_ERR_UNSUPPORTED;
+  plan_out[0] = pl.wm; plan_out[1] = pl.wn; plan_out[2] = pl.kt; plan_out[3] = pl.n_qtiles;
+  plan_out[4] = pl.splits; plan_out[5] = pl.fused;
+  return JK_OK;
 }
 
 static jk_status attention_common(const jk_attn_desc* desc, const jk_paged_kv* pages, const void* q,
@@ -182,15 +261,21 @@ static jk_status attention_common(const jk_attn_desc* desc, const jk_paged_kv* p
   }
 
   AttnPlan pl;
-  if (!make_attn_plan(d, max_prefix_len, &pl)) return JK_ERR_UNSUPPORTED;
+  if (!make_attn_plan(d, max_prefix_len, xcd_placement_verified(), &pl)) return JK_ERR_UNSUPPORTED;
   if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256) return JK_ERR_WORKSPACE;
   if (workspace_bytes < pl.total_bytes) return JK_ERR_WORKSPACE;
+  if (tuning().verbose)
+    std::fprintf(stderr, "jk attention plan: waves %dx%d, %d tile(s) per wave and round, %d row tile(s), %d split(s)%s\n",
+                 pl.wm, pl.wn, pl.kt, pl.n_qtiles, pl.splits, pl.fused ? ", merged in the kernel" : "");
 
   AttnArgs a;
   a.q = q; a.k_cache = k_cache; a.v_cache = v_cache; a.k_tree = k_tree; a.v_tree = v_tree;
   a.parent = parent; a.prefix_len = prefix_len; a.out = out;
-  a.part_o = reinterpret_cast<float*>(workspace);
-  a.part_ml = reinterpret_cast<float2*>(static_cast<char*>(workspace) + pl.part_o_bytes);
+  char* ws = static_cast<char*>(workspace);
+  a.err = reinterpret_cast<unsigned*>(ws);
+  a.sync = reinterpret_cast<unsigned*>(ws + kWsErrBytes);
+  a.part_o = reinterpret_cast<float*>(ws + kAttnHeaderBytes);
+  a.part_ml = reinterpret_cast<float2*>(ws + kAttnHeaderBytes + pl.part_o_bytes);
   a.d = d;
   a.max_prefix_len = max_prefix_len;
   a.block_table = pages ? pages->block_table : nullptr;
@@ -204,7 +289,7 @@ static jk_status attention_common(const jk_attn_desc* desc, const jk_paged_kv* p
   if (d.dtype == JK_BF16) {
     a.scale_log2 = scale * 1.44269504088896340736f;
     e = launch_tva_bf16(a, pl, stream);
-    if (e == hipSuccess && pl.splits > 1) e = launch_tva_combine(a, pl, stream);
+    if (e == hipSuccess && pl.splits > 1 && !pl.fused) e = launch_tva_combine(a, pl, stream);
   } else {
     a.scale_log2 = scale;  // the fp32 path works in natural units
     e = launch_tva_f32(a, pl, stream);
@@ -569,6 +654,37 @@ jk_status jk_stream_read_probe(const void* src, size_t bytes, void* sink, void* 
   if (!src || !sink || reinterpret_cast<uintptr_t>(src) % 16) return JK_ERR_INVALID_ARG;
   return launch_stream_read(src, bytes, sink, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? JK_OK
                                                                                                   : JK_ERR_HIP;
+}
+
+jk_status jk_init(void* hip_stream) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return JK_ERR_HIP;
+  bool rr = false;
+  if (probe_xcd_placement(static_cast<hipStream_t>(hip_stream), &rr) != hipSuccess) return JK_ERR_HIP;
+  g_xcd_state[dev] = rr ? 1 : 2;
+  return JK_OK;
+}
+
+jk_status jk_set_tuning(const char* name, int32_t value) {
+  if (!name) return JK_ERR_INVALID_ARG;
+  Tuning& t = tuning();
+  const struct { const char* name; int* field; } table[] = {
+      {"attn_wm", &t.attn_wm}, {"attn_wn", &t.attn_wn}, {"attn_splits", &t.attn_splits},
+      {"attn_fused", &t.attn_fused}, {"accept_single", &t.accept_single}, {"spin_limit", &t.spin_limit},
+      {"verbose", &t.verbose}};
+  for (const auto& e : table)
+    if (std::strcmp(name, e.name) == 0) {
+      *e.field = value;
+      return JK_OK;
+    }
+  return JK_ERR_INVALID_ARG;
+}
+
+int32_t jk_last_device_error(const void* workspace) {
+  if (!workspace) return -1;
+  unsigned word = 0;
+  if (hipMemcpy(&word, workspace, sizeof(word), hipMemcpyDeviceToHost) != hipSuccess) return -1;
+  return (int32_t)(word & 0x7fffffffu);
 }
 
 jk_status jk_validate_tree(const int32_t* parent_host, int32_t n_tree) {

@@ -25,10 +25,38 @@ struct AttnPlan {
   int m_rows;      // T * G query rows per KV head
   int m_pad;       // n_qtiles * q_rows
   int splits;      // KV splits
-  size_t part_o_bytes, part_ml_bytes, total_bytes;
+  int fused;       // bf16 path: the splits are merged inside the attention kernel (no second launch)
+  size_t part_o_bytes, part_ml_bytes, total_bytes;  // total = header + partials
 };
 
-bool make_attn_plan(const jk_attn_desc& d, int max_prefix_len, AttnPlan* plan);
+// Every attention and acceptance workspace starts with a header: 256 bytes whose first word is the
+// sticky device error word (jk_last_device_error), then, in an attention workspace, one 64-byte line
+// of synchronisation words per (unit, row tile) group for the merge inside the kernel.  The header
+// must be zero before the first use of a workspace and is kept consistent by the calls themselves.
+constexpr size_t kWsErrBytes = 256;
+constexpr int kMaxFusedGroups = 508;
+constexpr size_t kAttnHeaderBytes = kWsErrBytes + (size_t)kMaxFusedGroups * 64;  // 32 KiB
+static_assert(kAttnHeaderBytes == JK_WORKSPACE_HEADER_BYTES, "public constant");
+
+// Device error bits (public names in jakiro_verify.h)
+constexpr unsigned kDevErrBadTree = 1u, kDevErrBadToken = 2u, kDevErrBadPage = 4u, kDevErrMergeWait = 8u,
+                   kDevErrWalkWait = 16u;
+
+// Overrides for experiments and tests (jk_set_tuning; seeded once from the JK_* environment
+// variables when the library is loaded).  0 / -1 mean "let the library decide".
+struct Tuning {
+  int attn_wm = 0, attn_wn = 0, attn_splits = 0;
+  int attn_fused = -1;     // -1 automatic, 0 never, 1 whenever the grid allows it
+  int accept_single = 0;   // 1: one-workgroup sampling walk
+  int spin_limit = -1;     // polls of the bounded waits (-1: default)
+  int verbose = 0;
+};
+Tuning& tuning();
+
+// whether this device places consecutive workgroups round-robin over its XCDs (checked by jk_init)
+bool xcd_placement_verified();
+
+bool make_attn_plan(const jk_attn_desc& d, int max_prefix_len, bool fused_allowed, AttnPlan* plan);
 
 struct AttnArgs {
   const void *q, *k_cache, *v_cache, *k_tree, *v_tree;
@@ -37,6 +65,8 @@ struct AttnArgs {
   void* out;
   float* part_o;    // [B*Hkv][splits][m_pad][D], fp32 (fp32 path) or bf16 (bf16 path)
   float2* part_ml;  // [B*Hkv][splits][m_pad]  (running max in log2 units, sum)
+  unsigned* err;    // the workspace's device error word
+  unsigned* sync;   // the workspace's group synchronisation words (merge inside the kernel)
   jk_attn_desc d;
   int max_prefix_len;
   float scale_log2;  // softmax scale * log2(e)
@@ -66,6 +96,7 @@ size_t accept_workspace_bytes(int batch, int n_tree, int vocab, int mode);
 hipError_t launch_accept(const AcceptArgs& a, hipStream_t stream);
 size_t accept_greedy_static_bytes(int batch, int n_tree, int vocab);
 hipError_t launch_accept_greedy_static(const AcceptArgs& a, hipStream_t stream);
+hipError_t probe_xcd_placement(hipStream_t stream, bool* round_robin);
 int device_cu_count();
 
 struct CommitArgs {

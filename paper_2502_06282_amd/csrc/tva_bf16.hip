@@ -43,6 +43,7 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef short shortx4 __attribute__((ext_vector_type(4)));
 typedef short shortx8 __attribute__((ext_vector_type(8)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));  // native vector: plain loads/stores, no struct copies
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
 
@@ -73,6 +74,7 @@ struct KParams {
   float2* part_ml;
   int B, T, Hkv, G, M, m_pad, max_prefix, splits, n_qtiles, total_wgs;
   unsigned long long mg_qtiles, mg_splits, mg_hkv, mg_g;  // floor(2^32 / d) + 1: n / d == (n * mg) >> 32 for n * d < 2^32
+  unsigned long long mg_splits_m1;                        // the same for max(splits - 1, 1)
   long long q_sb, q_st, q_sh, kc_sb, kc_sl, kc_sh, kt_sb, kt_st, kt_sh, o_sb, o_st, o_sh;
   float scale_log2;
   // paged cache (block_table != nullptr): kc / vc are page pools, token t of sequence b lives in page
@@ -82,6 +84,14 @@ struct KParams {
   int through;  // bit 0: outputs and partials, bit 1: the partials' (max, sum) pairs go through to memory (see the epilogue)
   long long page_stride;
   unsigned long long mg_tpp;
+  // split merge inside this kernel (fused != 0; see merge_slice and the end of the kernel): sync = one
+  // 64-byte line of words per (unit, row tile) group in the workspace header, spin_limit = polls a
+  // workgroup spends waiting for its group before it leaves its slice to the group's last arriver
+  unsigned* sync;
+  unsigned* err;  // the workspace's sticky device error word
+  int fused;
+  unsigned spin_limit;
+  int merge_rows, merge_shift;  // rows per slice = ceil(tile rows / splits); splits padded to 2^merge_shift
 };
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -613,16 +623,218 @@ __device__ __forceinline__ void lone_tile(WaveState<D>& st, unsigned k_addr, uns
 }
 
 // Profiling build only (-DJK_TIMING, not part of the shipped library): thread 0 of every
-// workgroup records the 100 MHz wall clock at eight points of the kernel (entry, speculative
+// workgroup records the 100 MHz wall clock at points of the kernel (entry, speculative
 // transfers issued, prefix length known, transfers issued, first round landed, loop done,
-// columns parked, end); jk_debug_read_timing copies the table of the last launch to the host
+// columns parked, partials stored, arrived at the group word, group complete, end); jk_debug_read_timing copies the table of the last launch to the host
 // (grids of at most 4096 workgroups).  The phase times quoted in the design notes come from it.
 #ifdef JK_TIMING
-__device__ unsigned long long g_jk_ts[4096 * 8];
-#define JK_TS(i) do { if (threadIdx.x == 0) g_jk_ts[blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
+__device__ unsigned long long g_jk_ts[4096 * 16];
+#define JK_TS(i) do { if (threadIdx.x == 0) g_jk_ts[blockIdx.x * 16 + (i)] = wall_clock64(); } while (0)
 #else
 #define JK_TS(i) do { } while (0)
 #endif
+
+// ---------------------------------------------------------------- split merge inside the kernel
+// The workgroups that hold the S key splits of one (unit, row tile) group all run on one XCD
+// (the host only asks for this path when its workgroup numbering guarantees it and the
+// device's round-robin placement has been verified), so they can meet in that XCD's L2
+// without the whole-cache write-back an agent-scope release costs on a part with eight L2s:
+// partials are written with ordinary stores (a CU's vector cache writes through to L2; a
+// store is acknowledged, and counted off vmcnt, once L2 has it), arrivals are counted with
+// atomics that carry no device scope and therefore execute in that L2, and the partials are
+// read back with loads that miss the reader's vector cache (invalidated first).  This is the
+// hardware's own recipe for workgroup-scope synchronisation between CUs that share an L2.
+__device__ __forceinline__ unsigned l2_atomic_add(unsigned* p, unsigned x) {
+  unsigned v;
+  asm volatile("global_atomic_add %0, %1, %2, off sc0\n\ts_waitcnt vmcnt(0)" : "=v"(v) : "v"(p), "v"(x) : "memory");
+  return v;
+}
+__device__ __forceinline__ unsigned l2_atomic_or(unsigned* p, unsigned x) {
+  unsigned v;
+  asm volatile("global_atomic_or %0, %1, %2, off sc0\n\ts_waitcnt vmcnt(0)" : "=v"(v) : "v"(p), "v"(x) : "memory");
+  return v;
+}
+__device__ __forceinline__ unsigned l2_atomic_swap(unsigned* p, unsigned x) {
+  unsigned v;
+  asm volatile("global_atomic_swap %0, %1, %2, off sc0\n\ts_waitcnt vmcnt(0)" : "=v"(v) : "v"(p), "v"(x) : "memory");
+  return v;
+}
+__device__ __forceinline__ void l2_atomic_add_noret(unsigned* p, unsigned x) {
+  asm volatile("global_atomic_add %0, %1, off" ::"v"(p), "v"(x) : "memory");
+}
+
+// Group word: bits 0-7 arrivals of this call, bits 8-15 workgroups that gave up waiting, bits
+// 16-31 call number (epoch).  The last arriver adds 2^16 - S - (give-ups << 8): count and
+// give-ups return to zero and the epoch moves on, which is what the waiting workgroups look for.
+constexpr unsigned kSyncCountMask = 0xffu, kSyncGaveUpOne = 0x100u, kSyncEpochOne = 0x10000u;
+
+// Merge of rows [slice * R, (slice + 1) * R) of the group's row tile over all S splits, written to
+// the output.  16 bytes (8 columns) of a row per thread; the arithmetic per element is that of the
+// stand-alone merge kernel (splits in chunks of 8, running maximum), so both give the same bits.
+struct MergeArgs {
+  const float* part_o;
+  const float2* part_ml;
+  uint16_t* out;
+  int M, m_pad, splits, G;
+  unsigned long long mg_g;
+  long long o_sb, o_st, o_sh;
+};
+// Reductions over aligned groups of 2^sh lanes (sh uniform): within a row of 16 lanes by DPP
+// (quad permutes, then the mirrors of 8 and of 16 lanes: after the quads every lane of a quad
+// holds the quad's value, so a mirror pairs quads as well as an exchange would), across rows by shuffles.
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float x) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float group_max(float x, int sh) {
+  if (sh >= 1) x = fmaxf(x, dpp_f<0xB1>(x));   // quad_perm [1,0,3,2]
+  if (sh >= 2) x = fmaxf(x, dpp_f<0x4E>(x));   // quad_perm [2,3,0,1]
+  if (sh >= 3) x = fmaxf(x, dpp_f<0x141>(x));  // row_half_mirror
+  if (sh >= 4) x = fmaxf(x, dpp_f<0x140>(x));  // row_mirror
+  if (sh >= 5) x = fmaxf(x, __shfl_xor(x, 16));
+  if (sh >= 6) x = fmaxf(x, __shfl_xor(x, 32));
+  return x;
+}
+__device__ __forceinline__ float group_sum(float x, int sh) {
+  if (sh >= 1) x += dpp_f<0xB1>(x);
+  if (sh >= 2) x += dpp_f<0x4E>(x);
+  if (sh >= 3) x += dpp_f<0x141>(x);
+  if (sh >= 4) x += dpp_f<0x140>(x);
+  if (sh >= 5) x += __shfl_xor(x, 16);
+  if (sh >= 6) x += __shfl_xor(x, 32);
+  return x;
+}
+
+// Merge of one slice (R consecutive rows of a row tile) over all S splits, written to the output:
+//   m = max_s m_s,  l = sum_s l_s 2^(m_s - m),  out = sum_s O_s 2^(m_s - m) / l.
+// What limits it is the issue rate of a lone wave per SIMD (about eight cycles an instruction)
+// and the CU's one path to L2, so: everything that does not depend on the partials (row numbers,
+// byte offsets, the output address) is worked out by merge_prepare while the workgroup still
+// waits for its partners; then (A) one thread per (row, split) fetches that pair's (max, sum)
+// once, the 2^sh lanes of a row find the row's maximum and sum and park the normalised weight
+// 2^(m_s - m) / l in LDS, while (B) one thread per (row, 4 columns) has its 8 bytes of every
+// split's partial in flight and afterwards only multiplies and adds.  At most THREADS (row, split)
+// pairs exist per slice (R = ceil(tile rows / S), S padded to 2^sh), one per thread.
+struct MergeThread {
+  unsigned raw_off;   // byte offset of this thread's 8 bytes in split 0's partial (rows of the first pass)
+  unsigned ml_off;    // byte offset of this thread's (row, split) pair
+  unsigned dst_off;   // element offset of this thread's 4 output columns in `out` (first pass)
+  int r_b, row_lo, row_hi;
+  bool live_a, live_b;
+};
+
+template <int D, int THREADS, int QROWS>
+__device__ __forceinline__ MergeThread merge_prepare(const MergeArgs& p, int unit_id, int b, int kv, int slice, int R,
+                                                     int sh, int tile_row0, int tid) {
+  constexpr int CPR = D / 4;
+  MergeThread t;
+  const int S = p.splits;
+  t.row_lo = slice * R;
+  t.row_hi = min(QROWS, t.row_lo + R);
+  const int chunk = tid % CPR;
+  t.r_b = t.row_lo + tid / CPR;
+  const unsigned unit_row0 = (unsigned)(unit_id * S) * (unsigned)p.m_pad + (unsigned)tile_row0;  // (the host keeps the
+  t.live_b = t.r_b < t.row_hi && tile_row0 + t.r_b < p.M;                                        // partials below 2^31 bytes)
+  t.raw_off = ((unit_row0 + (unsigned)t.r_b) * (unsigned)D + (unsigned)chunk * 4u) * 2u;
+  const int ra = t.row_lo + (tid >> sh), sa = tid & ((1 << sh) - 1);
+  t.live_a = ra < t.row_hi && tile_row0 + ra < p.M && sa < S;
+  t.ml_off = (unit_row0 + (unsigned)ra + (unsigned)sa * (unsigned)p.m_pad) * 8u;
+  const int m = tile_row0 + (t.live_b ? t.r_b : 0);
+  const int node = div_mg(m, p.mg_g);
+  t.dst_off = (unsigned)(b * p.o_sb + node * p.o_st + (long long)(kv * p.G + (m - node * p.G)) * p.o_sh) + chunk * 4;
+  return t;
+}
+
+template <int D, int THREADS, int QROWS>
+__device__ __forceinline__ void merge_run(const MergeArgs& p, const MergeThread& t, int sh, int b, int kv, int tile_row0,
+                                          int tid, float* wbuf) {
+  constexpr int CPR = D / 4, RPP = THREADS / CPR;
+  if (t.row_lo >= t.row_hi) return;  // (uniform)
+  const int S = p.splits;
+  const unsigned char* part = reinterpret_cast<const unsigned char*>(p.part_o);
+  const unsigned po_step = (unsigned)p.m_pad * D * 2;  // bytes from one split's partial to the next
+  // ---- the (max, sum) pair of this thread's (row, split) first, then (B), first half: this thread's
+  // bytes of up to 16 splits go out (32-bit offsets from one base: an add per load)
+  float2 ml = make_float2(-INFINITY, 0.f);
+  if (t.live_a) ml = *reinterpret_cast<const float2*>(reinterpret_cast<const unsigned char*>(p.part_ml) + t.ml_off);
+  u32x2 raw[16];
+  {
+    unsigned off = t.raw_off;
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      raw[u] = u32x2{0u, 0u};
+      if (t.live_b && u < S) raw[u] = *reinterpret_cast<const u32x2*>(part + off);
+      off += po_step;
+    }
+  }
+  JK_TS(11);
+  // ---- (A): pair (row, split) of this thread
+  {
+    if (!(ml.y > 0.f)) ml = make_float2(-INFINITY, 0.f);  // an empty split carries no weight
+    const float mx = group_max(ml.x, sh);
+    const float w = fast_exp2(ml.x - ((mx == -INFINITY) ? 0.f : mx));  // exp2(-inf) = 0
+    const float l = group_sum(ml.y * w, sh);
+    // (l > 0 for a live row: it sees at least its own tree key; dead rows are not stored.  A row's
+    // weights start at a multiple of four floats, for the 16-byte reads below)
+    const int wsh = sh < 2 ? 2 : sh;
+    wbuf[((tid >> sh) << wsh) | (tid & ((1 << sh) - 1))] = w / l;
+  }
+  JK_TS(12);
+  __syncthreads();
+#ifdef JK_TIMING
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  JK_TS(13);
+#endif
+  // ---- (B), second half
+  for (int r = t.r_b, pass = 0; r < t.row_hi; r += RPP, ++pass) {
+    const bool live = tile_row0 + r < p.M;
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    const float* wrow = wbuf + ((r - t.row_lo) << (sh < 2 ? 2 : sh));
+    for (int s0 = 0; s0 < S; s0 += 16) {
+      if (pass > 0 || s0 > 0) {  // (beyond the first 16 splits of the first row: fetched here)
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+          raw[u] = u32x2{0u, 0u};
+          if (live && s0 + u < S)
+            raw[u] = *reinterpret_cast<const u32x2*>(part + ((unsigned)(s0 + u) * po_step + t.raw_off + (unsigned)(pass * RPP * D * 2)));
+        }
+      }
+      float w[16];
+#pragma unroll
+      for (int u = 0; u < 16; u += 4) {  // (slots beyond S hold zeros or other rows' weights; their data are zeros)
+        const float4 w4 = *reinterpret_cast<const float4*>(wrow + s0 + u);
+        w[u] = w4.x; w[u + 1] = w4.y; w[u + 2] = w4.z; w[u + 3] = w4.w;
+      }
+#pragma unroll
+      for (int u = 0; u < 16; ++u) {
+        const float wu = s0 + u < S ? w[u] : 0.f;
+        acc[0] = fmaf(__uint_as_float(raw[u][0] << 16), wu, acc[0]);
+        acc[1] = fmaf(__uint_as_float(raw[u][0] & 0xffff0000u), wu, acc[1]);
+        acc[2] = fmaf(__uint_as_float(raw[u][1] << 16), wu, acc[2]);
+        acc[3] = fmaf(__uint_as_float(raw[u][1] & 0xffff0000u), wu, acc[3]);
+      }
+    }
+    if (!live) continue;
+    u32x2 pk;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      bf16x2 o;
+      o[0] = (__bf16)acc[2 * h];
+      o[1] = (__bf16)acc[2 * h + 1];
+      pk[h] = __builtin_bit_cast(unsigned, o);
+    }
+    uint16_t* dst;
+    if (pass == 0) {
+      dst = p.out + t.dst_off;
+    } else {
+      const int m = tile_row0 + r;
+      const int node = div_mg(m, p.mg_g);
+      dst = p.out + b * p.o_sb + node * p.o_st + (long long)(kv * p.G + (m - node * p.G)) * p.o_sh + (tid % CPR) * 4;
+    }
+    *reinterpret_cast<u32x2*>(dst) = pk;  // (an ordinary store measured no slower than one through to memory here)
+  }
+  __syncthreads();  // wbuf is free again (another slice may follow)
+}
 
 // LDS plan of one workgroup, shared by the kernel and its launcher.
 template <int D, int WM, int WN, int KT, bool PAGED = false>
@@ -678,9 +890,9 @@ __global__ __launch_bounds__((Plan<D, WM, WN, KT, PAGED>::THREADS), (Plan<D, WM,
   {
     typedef __attribute__((address_space(4))) const unsigned kernarg_word;
     kernarg_word* ka = (kernarg_word*)__builtin_amdgcn_kernarg_segment_ptr();
-    static_assert(sizeof(KParams) > 256 && sizeof(KParams) <= 320, "five lines of kernel arguments");
-    const unsigned a0 = ka[0], a1 = ka[16], a2 = ka[32], a3 = ka[48], a4 = ka[64];
-    asm volatile("" ::"s"(a0), "s"(a1), "s"(a2), "s"(a3), "s"(a4));
+    static_assert(sizeof(KParams) > 320 && sizeof(KParams) <= 384, "six lines of kernel arguments");
+    const unsigned a0 = ka[0], a1 = ka[16], a2 = ka[32], a3 = ka[48], a4 = ka[64], a5 = ka[80];
+    asm volatile("" ::"s"(a0), "s"(a1), "s"(a2), "s"(a3), "s"(a4), "s"(a5));
   }
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -774,18 +986,31 @@ __global__ __launch_bounds__((Plan<D, WM, WN, KT, PAGED>::THREADS), (Plan<D, WM,
     ts.t_begin = rb * TPR < nt ? rb * TPR : nt;
     ts.t_end = re * TPR < nt ? re * TPR : nt;
     if (KT == 2 && WN == 1) {
-      // One wave column taking tile pairs: a lone full tile costs about half a round (see the
-      // loop), so the same sharing is done in tiles; an odd share ends with such a tile.
-      const int slow_t = nt - len / kTileKeys;
-      const int share_t = div_mg(nt, p.mg_splits);
-      const int extra_t = slow_t < share_t / 2 ? slow_t : share_t / 2;
-      const int ntv = nt + extra_t;
-      const int base_t = div_mg(ntv, p.mg_splits);
-      const int rem_t = ntv - base_t * splits;
-      int tb = split * base_t + (split < rem_t ? split : rem_t);
-      int te = tb + base_t + (split < rem_t ? 1 : 0);
-      ts.t_begin = tb < nt ? tb : nt;
-      ts.t_end = te < nt ? te : nt;
+      // One wave column taking tile pairs.  Everybody waits for the slowest split (the merge needs all
+      // partials), so the shares are dealt in what the loop is fast at: whole pairs of full prefix
+      // tiles, evenly.  What is left - an odd full tile, the ragged tile, the masked tree tiles, all of
+      // them on slower paths - goes to the last split, priced at two pairs a tile, and that split
+      // gets correspondingly fewer pairs (none at all if the tail is worth a whole share: the host
+      // may add a split for it, whose workgroups are short and share a CU with a regular one).
+      const int P = (len / kTileKeys) >> 1;  // pairs of full prefix tiles
+      const int tail = nt - 2 * P;
+      int tb = 0, te = nt;
+      if (splits > 1) {
+        const int per = div_mg(P + 2 * tail + splits - 1, p.mg_splits);  // ceil((P + 2 tail) / splits)
+        int p_last = per - 2 * tail;
+        p_last = p_last < 0 ? 0 : (p_last > P ? P : p_last);
+        const int rest = P - p_last;  // pairs of the other splits
+        const int base_p = div_mg(rest, p.mg_splits_m1), rem_p = rest - base_p * (splits - 1);
+        if (split == splits - 1) {
+          tb = 2 * rest;
+        } else {
+          const int pb = split * base_p + (split < rem_p ? split : rem_p);
+          tb = 2 * pb;
+          te = tb + 2 * (base_p + (split < rem_p ? 1 : 0));
+        }
+      }
+      ts.t_begin = tb;
+      ts.t_end = te;
     }
   };
   const unsigned ring_addr = (unsigned)(size_t)LDS_PTR(unsigned char, ring);  // a multiple of 1024
@@ -830,6 +1055,7 @@ __global__ __launch_bounds__((Plan<D, WM, WN, KT, PAGED>::THREADS), (Plan<D, WM,
       for (int i = tid; i < n_pg && i < kMaxPagesPerSplit; i += THREADS) {
         const int pi = ts.pg_first + i;
         int id = pi < p.max_blocks ? p.block_table[(long long)b * p.max_blocks + pi] : 0;
+        if (id < 0 || id >= p.n_pages) __hip_atomic_fetch_or(p.err, kDevErrBadPage, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         pg_s[i] = id < 0 ? 0 : (id >= p.n_pages ? p.n_pages - 1 : id);
       }
     }
@@ -853,6 +1079,13 @@ __global__ __launch_bounds__((Plan<D, WM, WN, KT, PAGED>::THREADS), (Plan<D, WM,
     const int n_lo = lane, n_hi = lane + 64;
     int up_lo = (parent_lo >= -1 && parent_lo < n_lo) ? parent_lo : -1;  // indices strictly decrease towards the root
     int up_hi = (parent_hi >= -1 && parent_hi < n_hi) ? parent_hi : -1;  // (-1 as well for lanes past the tree)
+    // an entry that breaks -1 <= parent[i] < i was just replaced by -1: say so in the workspace's error word
+    if (up_lo != parent_lo || up_hi != parent_hi) {
+      typedef __attribute__((address_space(4))) const KParams KArgs;
+      KArgs* late = (KArgs*)__builtin_amdgcn_kernarg_segment_ptr();
+      asm volatile("" : "+s"(late));  // (fetched here: not worth a scalar register pair across the kernel)
+      __hip_atomic_fetch_or(late->err, kDevErrBadTree, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
     unsigned long long lo_lo = n_lo < T ? 1ull << n_lo : 0ull, hi_lo = 0ull;  // node lane: bit < 64
     unsigned long long lo_hi = 0ull, hi_hi = n_hi < T ? 1ull << lane : 0ull;  // node lane + 64: bit >= 64
     const bool two = T > 64;  // uniform
@@ -1094,7 +1327,96 @@ __global__ __launch_bounds__((Plan<D, WM, WN, KT, PAGED>::THREADS), (Plan<D, WM,
       }
     }
   }
-  JK_TS(7);
+  if (splits > 1) {
+    // ---- merge of the group's splits in this kernel.  Every workgroup of the group owns the slice
+    // of R = ceil(QROWS / splits) rows numbered like its split and merges it once all partials are
+    // in L2.  Waiting is bounded: a workgroup that gives up records its slice in the group's mask
+    // and leaves; the group's last arriver, which never waits, then merges those slices as well,
+    // so the result is complete whenever every workgroup of the group runs, however late.
+    // (The arguments this part needs are fetched from the kernel-argument segment here rather than
+    // held in scalar registers across the tile loop, which has none to spare.)
+    typedef __attribute__((address_space(4))) const KParams KArgs;
+    KArgs* late = (KArgs*)__builtin_amdgcn_kernarg_segment_ptr();
+    asm volatile("" : "+s"(late));
+    const int tid_e = wave * 64 + lane_e;  // (the thread id, rebuilt: see the note on lane_e above)
+    if (late->fused) {
+      int* mode_s = repeat_s + 1;  // 0 leave, 1 merge own slice, 2 also the slices in mode_s[1..2]
+      // (what the merge of this workgroup's own slice needs besides the partials: computed now, while
+      // the partial stores travel and before the wait for the group)
+      MergeArgs ma;
+      ma.part_o = p.part_o; ma.part_ml = p.part_ml; ma.out = p.out;
+      ma.M = M; ma.m_pad = p.m_pad; ma.splits = splits; ma.G = G; ma.mg_g = p.mg_g;
+      ma.o_sb = p.o_sb; ma.o_st = p.o_st; ma.o_sh = p.o_sh;
+      const int merge_rows = late->merge_rows, merge_shift = late->merge_shift;
+      const int tile_row0 = qtile * QROWS;
+      const MergeThread mt = merge_prepare<D, THREADS, QROWS>(ma, unit_id, b, kv, split, merge_rows, merge_shift, tile_row0, tid_e);
+      JK_TS(7);
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's partial stores have reached L2
+      __syncthreads();
+      JK_TS(8);
+      if (tid_e == 0) {
+        unsigned* word = late->sync + (size_t)(unit_id * late->n_qtiles + qtile) * 16;
+        const unsigned S = (unsigned)splits;
+        const unsigned old = l2_atomic_add(word, 1u);
+        const unsigned epoch = old >> 16;
+        int mode = 1;
+        unsigned m_lo = 0u, m_hi = 0u;
+        if ((old & kSyncCountMask) == S - 1) {
+          const unsigned gave_up = (old >> 8) & 0xffu;
+          l2_atomic_add_noret(word, kSyncEpochOne - S - gave_up * kSyncGaveUpOne);
+          if (gave_up) {
+            mode = 2;
+            m_lo = l2_atomic_swap(word + 1, 0u);
+            m_hi = l2_atomic_swap(word + 2, 0u);
+          }
+        } else {
+          const unsigned limit = late->spin_limit;
+          unsigned polls = 0;
+          for (;;) {
+            const unsigned v = l2_atomic_add(word, 0u);
+            if ((v >> 16) != epoch || (v & kSyncCountMask) == S) break;
+            if (++polls > limit) {
+              l2_atomic_or(word + 1 + (split >> 5), 1u << (split & 31));
+              const unsigned v2 = l2_atomic_add(word, kSyncGaveUpOne);
+              // (complete after all, between the last poll and the mark: the last arriver has not seen
+              // the mark, so this slice is still ours; the stray mark only costs a later call a repeat)
+              if (!((v2 >> 16) != epoch || (v2 & kSyncCountMask) == S)) mode = 0;
+              __hip_atomic_fetch_or(late->err, kDevErrMergeWait, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              break;
+            }
+            __builtin_amdgcn_s_sleep(1);
+          }
+        }
+        mode_s[0] = mode;
+        mode_s[1] = (int)m_lo;
+        mode_s[2] = (int)m_hi;
+      }
+      __syncthreads();
+      JK_TS(9);
+      const int mode = __builtin_amdgcn_readfirstlane(mode_s[0]);
+      if (mode != 0) {
+        // (No line of the partials can sit in this CU's vector cache: the cache starts every kernel
+        // empty, this kernel reads partials nowhere else, and no partial is rewritten after the group
+        // is complete.  The loads below therefore go to L2 without an invalidate in front of them.)
+        asm volatile("" ::: "memory");
+        float* wbuf = reinterpret_cast<float*>(smem);  // (ring and epilogue buffers are dead: every wave is past its stores)
+        merge_run<D, THREADS, QROWS>(ma, mt, merge_shift, b, kv, tile_row0, tid_e, wbuf);
+        if (mode == 2) {
+          const unsigned long long left_over =
+              ((unsigned long long)(unsigned)mode_s[2] << 32) | (unsigned long long)(unsigned)mode_s[1];
+          for (int j = 0; j < splits; ++j)
+            if (j != split && ((left_over >> j) & 1ull)) {
+              const MergeThread mj = merge_prepare<D, THREADS, QROWS>(ma, unit_id, b, kv, j, merge_rows, merge_shift, tile_row0, tid_e);
+              merge_run<D, THREADS, QROWS>(ma, mj, merge_shift, b, kv, tile_row0, tid_e, wbuf);
+            }
+        }
+      }
+    }
+  }
+#ifdef JK_TIMING
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // (so that the last stamp includes the result stores)
+#endif
+  JK_TS(10);
 }
 
 template <int D, int WM, int WN, int KT, bool PAGED>
@@ -1146,6 +1468,7 @@ hipError_t launch_tva_bf16(const AttnArgs& a, const AttnPlan& pl, hipStream_t st
   auto magic = [](int d) { return (1ull << 32) / (unsigned long long)d + 1ull; };
   kp.mg_qtiles = magic(pl.n_qtiles);
   kp.mg_splits = magic(pl.splits);
+  kp.mg_splits_m1 = magic(pl.splits > 1 ? pl.splits - 1 : 1);
   kp.mg_hkv = magic(d.n_kv_heads);
   kp.mg_g = magic(kp.G);
 
@@ -1164,6 +1487,15 @@ hipError_t launch_tva_bf16(const AttnArgs& a, const AttnPlan& pl, hipStream_t st
   // (max, sum) pairs: through only for the 2x2 arrangement (c2 -0.35 us; c3, 4x1: +0.25 us).
   const bool one_wave = work <= (long long)device_cu_count();
   kp.through = (one_wave ? 1 : 0) | (one_wave && pl.wn > 1 ? 2 : 0);
+  // merged in the kernel: the partials are read back from L2, which ordinary stores leave them in
+  kp.fused = pl.fused;
+  if (pl.fused && pl.splits > 1) kp.through = 0;
+  kp.sync = a.sync;
+  kp.err = a.err;
+  kp.spin_limit = tuning().spin_limit >= 0 ? (unsigned)tuning().spin_limit : 4096u;  // about 2 ms of polling
+  kp.merge_rows = (pl.q_rows + pl.splits - 1) / pl.splits;
+  kp.merge_shift = 0;
+  while ((1 << kp.merge_shift) < pl.splits) ++kp.merge_shift;
   const int key = (d.head_dim * 1000 + pl.wm * 100 + pl.wn * 10 + pl.kt) * 2 + (a.block_table ? 1 : 0);
 #define JK_CASE(D_, WM_, WN_, KT_)                                                                  \
   case ((D_) * 1000 + (WM_) * 100 + (WN_) * 10 + (KT_)) * 2: return launch_one<D_, WM_, WN_, KT_, false>(kp, stream); \

@@ -18,6 +18,7 @@ struct FParams {
   const int32_t *parent, *prefix_len;
   float* part_o;
   float2* part_ml;
+  unsigned* err;  // the workspace's sticky device error word
   int B, T, Hkv, G, M, m_pad, D, max_prefix, splits;
   long long q_sb, q_st, q_sh, kc_sb, kc_sl, kc_sh, kt_sb, kt_st, kt_sh;
   float scale;
@@ -65,7 +66,10 @@ __global__ __launch_bounds__(256) void tva_f32_kernel(FParams p) {
 
   if (tid < p.T) {
     int pa = p.parent[(long long)b * p.T + tid];
-    par_s[tid] = (pa >= -1 && pa < tid) ? pa : -1;
+    const bool ok = pa >= -1 && pa < tid;
+    par_s[tid] = ok ? pa : -1;
+    if (!ok && split == 0 && m == 0 && kv == 0)  // reported once per sequence
+      __hip_atomic_fetch_or(p.err, kDevErrBadTree, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
   if (tid < D) qs[tid] = p.q[b * p.q_sb + node * p.q_st + (long long)(kv * p.G + hg) * p.q_sh + tid];
   __syncthreads();
@@ -162,6 +166,7 @@ hipError_t launch_tva_f32(const AttnArgs& a, const AttnPlan& pl, hipStream_t str
   fp.prefix_len = a.prefix_len;
   fp.part_o = a.part_o;
   fp.part_ml = a.part_ml;
+  fp.err = a.err;
   const jk_attn_desc& d = a.d;
   fp.B = d.batch; fp.T = d.n_tree; fp.Hkv = d.n_kv_heads; fp.G = d.n_q_heads / d.n_kv_heads;
   fp.M = pl.m_rows; fp.m_pad = pl.m_pad; fp.D = d.head_dim; fp.max_prefix = a.max_prefix_len;

@@ -27,3 +27,15 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture(autouse=True)
+def _default_tuning(request):
+    """GPU tests may force launch plans through jk_set_tuning: every test starts from, and leaves, the defaults."""
+    if "gpu" not in request.keywords or not _have_gpu():
+        yield
+        return
+    from gpu_util import reset_tuning
+    reset_tuning()
+    yield
+    reset_tuning()

@@ -7,6 +7,19 @@ import paper_2502_06282_amd as jk
 from oracle import tree_verify_attention as oracle_attention
 
 
+_KNOBS = {"attn_wm": 0, "attn_wn": 0, "attn_splits": 0, "attn_fused": -1, "accept_single": 0, "spin_limit": -1}
+
+
+def tune(name, value):
+    """Force part of a launch plan (jk_set_tuning); the autouse fixture in conftest.py undoes it after the test."""
+    jk.set_tuning(name, int(value))
+
+
+def reset_tuning():
+    for k, v in _KNOBS.items():
+        jk.set_tuning(k, v)
+
+
 def to_dev(x, dtype):
     tdt = torch.float32 if dtype == "f32" else torch.bfloat16
     return {k: torch.from_numpy(np.ascontiguousarray(v)).cuda().to(tdt) for k, v in x.items()}

@@ -11,6 +11,7 @@ import pytest
 import torch
 
 import paper_2502_06282_amd as jk
+from gpu_util import reset_tuning, tune
 from oracle import accept_path as oracle_accept
 from workloads import CONFIGS, accept_inputs, tree_for_config
 
@@ -118,7 +119,7 @@ def test_sample_max_depth_cap(single, monkeypatch):
     """Sampling walks that go deep (draft distributions close to the target's), cut at every depth:
     cooperative and single-workgroup walks against the oracle's capped walk."""
     if single:
-        monkeypatch.setenv("JK_ACCEPT_SINGLE", "1")
+        tune("accept_single", "1")
     cfg = CONFIGS["c3_llama3_8b"].with_(vocab=3001, batch=4)
     par = tree_for_config(cfg, seed=7)
     a = accept_inputs(cfg, par, seed=7)
@@ -210,7 +211,7 @@ def test_sample_single_workgroup_walk_agrees(monkeypatch):
     par = tree_for_config(cfg, seed=3)
     a = accept_inputs(cfg, par, seed=3)
     coop = _gpu_accept(a, par, "sample")
-    monkeypatch.setenv("JK_ACCEPT_SINGLE", "1")
+    tune("accept_single", "1")
     single = _gpu_accept(a, par, "sample")
     for x, y in zip(coop, single):
         assert (x == y).all()

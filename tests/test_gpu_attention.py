@@ -10,7 +10,7 @@ from workloads import CONFIGS, attention_inputs, coin_tree, round_to_bf16, tree_
 
 pytestmark = pytest.mark.gpu
 
-from gpu_util import check_attention, gpu_attention, oracle_attention  # noqa: E402
+from gpu_util import check_attention, gpu_attention, oracle_attention, reset_tuning, tune  # noqa: E402
 
 BF16_TOL, F32_TOL = 2e-2, 1e-5
 
@@ -106,9 +106,9 @@ def test_bf16_outlier_key_far_above_everything_before_it(monkeypatch, where, spl
     workgroup has to notice and repeat its split on the general path.  Early (first tile), in the
     middle and in the last full tile of the prefix; one split, three, and the planner's choice."""
     if splits:
-        monkeypatch.setenv("JK_ATTN_SPLITS", splits)
-    monkeypatch.setenv("JK_ATTN_WM", "4")
-    monkeypatch.setenv("JK_ATTN_WN", "1")
+        tune("attn_splits", splits)
+    tune("attn_wm", "4")
+    tune("attn_wn", "1")
     cfg = _cfg("c3_llama3_8b", prefix_len=3008, n_q_heads=8, n_kv_heads=2)
     par = tree_for_config(cfg)
     x = attention_inputs(cfg, seed=where, scale_mult=np.sqrt(128.0))
@@ -126,8 +126,8 @@ def test_bf16_outlier_key_far_above_everything_before_it(monkeypatch, where, spl
 
 def test_bf16_outlier_key_head_dim_64(monkeypatch):
     """The same repeat on the general path with 64-wide heads (half as many MFMAs per phase)."""
-    monkeypatch.setenv("JK_ATTN_WM", "4")
-    monkeypatch.setenv("JK_ATTN_WN", "1")
+    tune("attn_wm", "4")
+    tune("attn_wn", "1")
     cfg = _cfg("c3_llama3_8b", prefix_len=1100, n_q_heads=8, n_kv_heads=2, head_dim=64)
     par = tree_for_config(cfg)
     x = attention_inputs(cfg, seed=5, scale_mult=np.sqrt(64.0))
@@ -194,7 +194,7 @@ def test_bf16_split_invariance(monkeypatch):
     x = attention_inputs(cfg, scale_mult=np.sqrt(128.0))
     outs = []
     for s in ("1", "3", "8", "31"):
-        monkeypatch.setenv("JK_ATTN_SPLITS", s)
+        tune("attn_splits", s)
         outs.append(gpu_attention(x, par, [2000], "bf16"))
     for o in outs[1:]:
         assert np.abs(o - outs[0]).max() <= 2.0 ** -7 * np.abs(outs[0]).max()
@@ -206,13 +206,13 @@ def test_bf16_wave_arrangements(monkeypatch, wm, wn, L):
     """Both workgroup arrangements (the 4x1 one takes its tiles in hand-pipelined pairs) over prefix
     lengths that leave full pairs, a lone tile, a ragged tile and tree tiles in every position of a
     round, unsplit and with three splits."""
-    monkeypatch.setenv("JK_ATTN_WM", str(wm))
-    monkeypatch.setenv("JK_ATTN_WN", str(wn))
+    tune("attn_wm", str(wm))
+    tune("attn_wn", str(wn))
     cfg = _cfg("c3_llama3_8b", batch=2, prefix_len=L, n_q_heads=8, n_kv_heads=2)
     par = tree_for_config(cfg, seed=L)
     x = attention_inputs(cfg, seed=L, scale_mult=np.sqrt(128.0))
     for s in ("1", "3"):
-        monkeypatch.setenv("JK_ATTN_SPLITS", s)
+        tune("attn_splits", s)
         check_attention(x, par, [L, L // 2], "bf16", BF16_TOL, rel_tol=2e-2)
 
 
@@ -220,8 +220,8 @@ def test_bf16_wave_arrangements(monkeypatch, wm, wn, L):
 def test_bf16_prefix_shorter_than_bound(monkeypatch, wm, wn):
     """The first K/V transfers go out on the assumption prefix_len == max_prefix_len; here it is
     not, for one sequence by a lot and for the other by one key."""
-    monkeypatch.setenv("JK_ATTN_WM", str(wm))
-    monkeypatch.setenv("JK_ATTN_WN", str(wn))
+    tune("attn_wm", str(wm))
+    tune("attn_wn", str(wn))
     cfg = _cfg("c3_llama3_8b", batch=2, prefix_len=1500, n_q_heads=8, n_kv_heads=2)
     par = tree_for_config(cfg)
     x = attention_inputs(cfg, scale_mult=np.sqrt(128.0))
@@ -282,12 +282,16 @@ def _sampled_unit_check(cfg, x, par, got, n_samples, seed):
         assert err <= BF16_TOL and err <= 1.5e-2 * np.abs(ref).max(), (b, kv, err)
 
 
-def test_c3_full_size_graph_replay_as_benchmarked():
+@pytest.mark.parametrize("fused", [1, 0])
+def test_c3_full_size_graph_replay_as_benchmarked(fused):
     """The launch configuration bench.py times: prepared calls of several full-size c3 layers sharing
     one workspace, captured in a HIP graph and replayed, with eager work between the replays; every
     replay must reproduce the eager result bit for bit, and the result is checked against the oracle
-    on sampled KV heads."""
+    on sampled KV heads.  Both ways of merging the key splits: inside the attention kernel (the
+    workspace's header is zero-filled once and must stay consistent from call to call) and with the
+    second kernel; the partials behind the header are filled with noise before every replay."""
     import paper_2502_06282_amd as jk
+    tune("attn_fused", fused)
     cfg = CONFIGS["c3_llama3_8b"]
     par = tree_for_config(cfg)
     dev = torch.device("cuda")
@@ -299,6 +303,7 @@ def test_c3_full_size_graph_replay_as_benchmarked():
     outs = [torch.empty_like(l["q"]) for l in lys]
     ws = torch.empty(jk.tree_verify_attention_workspace(lys[0]["q"], lys[0]["k_cache"], lys[0]["k_tree"], cfg.prefix_len),
                      dtype=torch.uint8, device=dev)
+    jk.workspace_init(ws)
     calls = [jk.prepare_tree_verify_attention(l["q"], l["k_cache"], l["v_cache"], l["k_tree"], l["v_tree"], parent, plen,
                                               o, ws, max_prefix_len=cfg.prefix_len) for l, o in zip(lys, outs)]
     for c in calls:
@@ -312,7 +317,7 @@ def test_c3_full_size_graph_replay_as_benchmarked():
     for rep in range(3):
         for o in outs:
             o.fill_(float("nan"))
-        ws.random_(0, 255)                     # stale partials must not matter
+        ws[jk.JK_WORKSPACE_HEADER_BYTES:].random_(0, 255)   # stale partials must not matter
         junk = torch.randn(1 << 20, device=dev).sum()   # the program's own eager work between replays
         g.replay()
         torch.cuda.synchronize()
@@ -322,6 +327,120 @@ def test_c3_full_size_graph_replay_as_benchmarked():
     for l in (0, n_layers - 1):
         got = outs[l].float().cpu().numpy().astype(np.float64)
         _sampled_unit_check(cfg, xs[l], par, got, 3, 10 + l)
+    assert jk.last_device_error(ws) == 0
+
+
+def _attn_with_ws(x, par, plens, fused, ws=None, max_prefix_len=None):
+    """One bf16 call with an explicit workspace; returns (out as float64, workspace, plan)."""
+    import paper_2502_06282_amd as jk
+    from gpu_util import to_dev
+    tune("attn_fused", fused)
+    dv = to_dev(x, "bf16")
+    parent = torch.from_numpy(np.ascontiguousarray(par, dtype=np.int32)).cuda()
+    pl = torch.tensor(list(plens), dtype=torch.int32).cuda()
+    L = max_prefix_len if max_prefix_len is not None else dv["k_cache"].shape[1]
+    plan = jk.tree_verify_attention_plan(dv["q"], dv["k_cache"], dv["k_tree"], L)
+    if ws is None:
+        ws = torch.empty(jk.tree_verify_attention_workspace(dv["q"], dv["k_cache"], dv["k_tree"], L), dtype=torch.uint8,
+                         device="cuda")
+        ws.random_(0, 255)
+        jk.workspace_init(ws[: jk.JK_WORKSPACE_HEADER_BYTES])   # only the header needs to start at zero
+    out = jk.tree_verify_attention(dv["q"], dv["k_cache"], dv["v_cache"], dv["k_tree"], dv["v_tree"], parent, pl,
+                                   max_prefix_len=L, workspace=ws)
+    torch.cuda.synchronize()
+    return out.float().cpu().numpy().astype(np.float64), ws, plan
+
+
+@pytest.mark.parametrize("name,kw,arr,splits", [
+    ("c3_llama3_8b", {}, None, 0),                                            # the benchmarked plan
+    ("c3_llama3_8b", {"prefix_len": 1000}, (4, 1), 5),                        # rows per slice do not divide the tile
+    ("c3_llama3_8b", {"prefix_len": 4093, "n_tree": 128}, (4, 1), 16),        # ragged prefix, four tree tiles
+    ("c2_vicuna7b", {}, None, 0),                                             # 2x2 waves, 60 rows
+    ("c2_vicuna7b", {"prefix_len": 777, "n_q_heads": 16, "n_kv_heads": 16}, (2, 2), 7),
+    ("c3_llama3_8b", {"head_dim": 64, "prefix_len": 2048}, (4, 1), 8),
+    ("c3_llama3_8b", {"batch": 2, "n_q_heads": 16, "n_kv_heads": 4, "prefix_len": 3000}, None, 0),
+])
+def test_bf16_merge_inside_the_kernel_agrees_with_the_merge_kernel(name, kw, arr, splits):
+    """The key splits of a row tile are merged either by a second kernel or, when the grid allows it, by the
+    attention kernel's own workgroups meeting in their XCD's L2.  Both merge the same bf16 partials in fp32 (in a
+    different order of operations): the bf16 outputs may differ in the last place of an element, no more, and both
+    are within tolerance of the oracle."""
+    cfg = _cfg(name, **kw)
+    if arr:
+        tune("attn_wm", arr[0]); tune("attn_wn", arr[1])
+    if splits:
+        tune("attn_splits", splits)
+    par = tree_for_config(cfg)
+    x = attention_inputs(cfg, scale_mult=np.sqrt(float(cfg.head_dim)))
+    plens = [cfg.prefix_len] * cfg.batch
+    a, ws_a, plan_a = _attn_with_ws(x, par, plens, 1)
+    tune("attn_splits", plan_a["splits"])   # (left to itself the plan may cut the keys differently for the second kernel)
+    tune("attn_wm", plan_a["wm"]); tune("attn_wn", plan_a["wn"])
+    b, ws_b, plan_b = _attn_with_ws(x, par, plens, 0)
+    assert plan_a["fused"] == 1 and plan_b["fused"] == 0 and plan_a["splits"] == plan_b["splits"] > 1, (plan_a, plan_b)
+    assert np.isfinite(a).all()
+    # one bf16 ulp (at most 2^-7 relative), plus the fp32 rounding of the weighted sums where they cancel
+    assert (np.abs(a - b) <= 1.01 * 2.0 ** -7 * np.maximum(np.abs(a), np.abs(b)) + 1e-6 * np.abs(a).max()).all()
+    assert (a != b).mean() < 0.02
+    import paper_2502_06282_amd as jk
+    assert jk.last_device_error(ws_a) == 0 and jk.last_device_error(ws_b) == 0
+    if cfg.prefix_len <= 1000:
+        ref = oracle_attention(**x, parent=par, prefix_len=plens)
+        assert np.abs(a - ref).max() <= BF16_TOL
+
+
+def test_bf16_merge_inside_the_kernel_when_the_wait_expires():
+    """spin_limit 0: no workgroup waits for its partners.  Every workgroup but a group's last arriver records its
+    slice and leaves, the last arriver merges them all: same bits as the normal run, the workspace's error word
+    says that waits expired, and the workspace serves the next (normal) call unchanged."""
+    import paper_2502_06282_amd as jk
+    cfg = _cfg("c3_llama3_8b", prefix_len=2048)
+    par = tree_for_config(cfg)
+    x = attention_inputs(cfg, scale_mult=np.sqrt(128.0))
+    ref, ws0, plan = _attn_with_ws(x, par, [2048], 1)
+    assert plan["fused"] == 1 and jk.last_device_error(ws0) == 0
+    tune("spin_limit", 0)
+    got, ws, _ = _attn_with_ws(x, par, [2048], 1)
+    np.testing.assert_array_equal(got, ref)
+    assert jk.last_device_error(ws) & jk.JK_DEVERR_MERGE_WAIT
+    # the same workspace, normal waits again: header words were left consistent
+    tune("spin_limit", -1)
+    for _ in range(3):
+        again, _, _ = _attn_with_ws(x, par, [2048], 1, ws=ws)
+        np.testing.assert_array_equal(again, ref)
+    jk.workspace_init(ws[: jk.JK_WORKSPACE_HEADER_BYTES])
+    again, _, _ = _attn_with_ws(x, par, [2048], 1, ws=ws)
+    np.testing.assert_array_equal(again, ref)
+    assert jk.last_device_error(ws) == 0
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_bad_tree_is_repaired_and_reported(dtype):
+    """A parent entry outside [-1, i-1] lives in device memory where the host cannot check it: the kernels treat
+    the node as a child of the prefix and set JK_DEVERR_BAD_TREE in the workspace; a good tree leaves it clear."""
+    import paper_2502_06282_amd as jk
+    from gpu_util import to_dev
+    cfg = _cfg("c1_tiny") if dtype == "f32" else _cfg("c3_llama3_8b", prefix_len=300, n_q_heads=8, n_kv_heads=2)
+    par = tree_for_config(cfg)
+    x = attention_inputs(cfg, scale_mult=1.0 if dtype == "f32" else np.sqrt(128.0))
+    bad = par.copy()
+    bad[0, 5] = 7          # a parent that comes later
+    bad[0, 3] = -4         # and one below -1
+    fixed = par.copy()
+    fixed[0, 5] = fixed[0, 3] = -1
+    dv = to_dev(x, dtype)
+    pl = torch.tensor([cfg.prefix_len], dtype=torch.int32).cuda()
+    outs, errs = [], []
+    for p_ in (bad, fixed):
+        ws = torch.zeros(jk.tree_verify_attention_workspace(dv["q"], dv["k_cache"], dv["k_tree"], cfg.prefix_len),
+                         dtype=torch.uint8, device="cuda")
+        outs.append(jk.tree_verify_attention(dv["q"], dv["k_cache"], dv["v_cache"], dv["k_tree"], dv["v_tree"],
+                                             torch.from_numpy(p_).cuda(), pl, workspace=ws))
+        torch.cuda.synchronize()
+        errs.append(jk.last_device_error(ws))
+    assert torch.equal(outs[0], outs[1])
+    assert errs == [jk.JK_DEVERR_BAD_TREE, 0]
+    assert jk.validate_tree(bad[0]) == 2 and jk.validate_tree(fixed[0]) == 0
 
 
 def test_c4_full_size_sampled_units():

@@ -6,6 +6,7 @@ import pytest
 import torch
 
 import paper_2502_06282_amd as jk
+from gpu_util import reset_tuning, tune
 from oracle import accept_path as oracle_accept, draft_tree as dt
 from workloads import draft_head_inputs, moe_inputs
 
@@ -237,13 +238,13 @@ def test_acceptance_through_the_row_table_equals_the_dense_call():
         uni = rng.random((B, N + 1)).astype(np.float32)
         t = lambda a: torch.from_numpy(a).cuda()
         for single in ("0", "1"):
-            os.environ["JK_ACCEPT_SINGLE"] = single
+            tune("accept_single", single)
             try:
                 ref = jk.accept_path(t(tokens), t(parent), t(logits), jk.JK_SAMPLE, 0.9, t(dense), t(uni))
                 got = jk.accept_path_rows(t(tokens), t(parent), t(logits), t(q_all), t(q_row), t(uni), 0.9)
                 torch.cuda.synchronize()
             finally:
-                os.environ.pop("JK_ACCEPT_SINGLE", None)
+                reset_tuning()
             for a, b_ in zip(ref, got):
                 assert torch.equal(a, b_)
             assert int(ref[1].min()) >= 0

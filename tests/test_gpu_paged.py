@@ -6,6 +6,7 @@ import pytest
 import torch
 
 import paper_2502_06282_amd as jk
+from gpu_util import reset_tuning, tune
 from oracle import commit_path as oracle_commit, gather_pages, tree_verify_attention as oracle_attention
 from workloads import CONFIGS, attention_inputs, paged_layout, round_to_bf16, tree_for_config
 
@@ -27,8 +28,8 @@ def _paged_case(cfg, page_size, L, seed=0):
 @pytest.mark.parametrize("wm,wn", [(2, 2), (4, 1)], ids=["2x2", "4x1"])
 @pytest.mark.parametrize("page_size,L", [(32, 97), (64, 300), (128, 1000), (32, 0), (256, 515)])
 def test_paged_attention_matches_oracle_and_contiguous(monkeypatch, wm, wn, page_size, L):
-    monkeypatch.setenv("JK_ATTN_WM", str(wm))
-    monkeypatch.setenv("JK_ATTN_WN", str(wn))
+    tune("attn_wm", str(wm))
+    tune("attn_wn", str(wn))
     cfg = CONFIGS["c3_llama3_8b"].with_(batch=2, prefix_len=L, n_q_heads=8, n_kv_heads=2)
     par, x, kp, vp, table = _paged_case(cfg, page_size, max(L, 1), seed=L + page_size)
     plen = [L, L // 3]
@@ -36,7 +37,7 @@ def test_paged_attention_matches_oracle_and_contiguous(monkeypatch, wm, wn, page
     parent = torch.from_numpy(par).cuda()
     pl = torch.tensor(plen, dtype=torch.int32).cuda()
     for s in ("1", "3"):
-        monkeypatch.setenv("JK_ATTN_SPLITS", s)
+        tune("attn_splits", s)
         got = jk.tree_verify_attention_paged(_dev(x["q"]), _dev(kp), _dev(vp), torch.from_numpy(table).cuda(),
                                              _dev(x["k_tree"]), _dev(x["v_tree"]), parent, pl, max_prefix_len=max(L, 1))
         cont = jk.tree_verify_attention(_dev(x["q"]), _dev(x["k_cache"]), _dev(x["v_cache"]), _dev(x["k_tree"]),
@@ -52,9 +53,9 @@ def test_paged_attention_repeats_a_split_that_leaves_the_fixed_frame(monkeypatch
     """A late key far above everything before it for one query row: the two-tile fast path of the 4x1
     arrangement gives up and the workgroup streams its split again on the general path, through the page
     table once more.  Bitwise equal to the contiguous call, which takes the same decisions."""
-    monkeypatch.setenv("JK_ATTN_WM", "4")
-    monkeypatch.setenv("JK_ATTN_WN", "1")
-    monkeypatch.setenv("JK_ATTN_SPLITS", "2")
+    tune("attn_wm", "4")
+    tune("attn_wn", "1")
+    tune("attn_splits", "2")
     cfg = CONFIGS["c3_llama3_8b"].with_(batch=1, prefix_len=2048, n_q_heads=8, n_kv_heads=2)
     par = tree_for_config(cfg, seed=3)
     x = {k: round_to_bf16(v) for k, v in attention_inputs(cfg, seed=3, scale_mult=np.sqrt(128.0)).items()}

@@ -15,7 +15,7 @@ from workloads import CONFIGS, accept_inputs, attention_inputs, round_to_bf16
 
 pytestmark = pytest.mark.gpu
 
-from gpu_util import gpu_attention, oracle_attention  # noqa: E402
+from gpu_util import gpu_attention, oracle_attention, reset_tuning, tune  # noqa: E402
 
 
 def _random_parents(rng, B, T, reach):
@@ -39,13 +39,12 @@ def test_attention_random_shapes(monkeypatch, block):
         par = _random_parents(rng, B, T, 12)
         arr = [None, (2, 2), (4, 1)][int(rng.integers(0, 3))]
         splits = int(rng.choice([0, 0, 1, 2, 3, 5, 8, 16, 33]))
-        for k in ("JK_ATTN_WM", "JK_ATTN_WN", "JK_ATTN_SPLITS"):
-            monkeypatch.delenv(k, raising=False)
+        reset_tuning()
         if arr is not None:
-            monkeypatch.setenv("JK_ATTN_WM", str(arr[0]))
-            monkeypatch.setenv("JK_ATTN_WN", str(arr[1]))
+            tune("attn_wm", str(arr[0]))
+            tune("attn_wn", str(arr[1]))
         if splits:
-            monkeypatch.setenv("JK_ATTN_SPLITS", str(splits))
+            tune("attn_splits", str(splits))
         cfg = CONFIGS["c3_llama3_8b"].with_(batch=B, n_q_heads=Hkv * G, n_kv_heads=Hkv, head_dim=D,
                                              prefix_len=max(cap, 1), n_tree=T)
         x = attention_inputs(cfg, seed=case, scale_mult=np.sqrt(float(D)))
@@ -87,9 +86,9 @@ def test_accept_random_shapes(monkeypatch, block):
         closeness = float(rng.choice([0.0, 0.3, 0.7, 2.0]))
         if V >= 32000:
             B = min(B, 2)
-        monkeypatch.delenv("JK_ACCEPT_SINGLE", raising=False)
+        reset_tuning()
         if rng.random() < 0.25:
-            monkeypatch.setenv("JK_ACCEPT_SINGLE", "1")
+            tune("accept_single", "1")
         par = _random_parents(rng, B, T, 10)
         cfg = CONFIGS["c3_llama3_8b"].with_(vocab=V, batch=B, n_tree=T, mode=mode, hit_prob=0.0)
         a = accept_inputs(cfg, par, seed=case)
