@@ -31,6 +31,8 @@
 // each lane fetches the 16-byte chunk that the XOR swizzle maps to its LDS
 // slot, so that both the 128-bit K reads and the transpose V reads are free of
 // bank conflicts.
+#include <type_traits>
+
 #include "jk_device.h"
 #include "jk_internal.h"
 
@@ -471,30 +473,43 @@ struct PairPipe {
   // than 2^kFrame above the reference (about 44 nats: a degenerate softmax) raises `left`;
   // the workgroup then repeats its whole split on the general path (see the tile loop).
   static constexpr float kFrame = 64.f;
-  static __device__ __forceinline__ float reference(WaveState<D>& st, const floatx16& s, float scale_log2, bool& left) {
-    const float tmax = half_swap_max(max16(s)) * scale_log2;
-    const float m = (st.m == -INFINITY) ? tmax : st.m;  // (an unmasked tile of finite scores: tmax is finite)
-    left = left || !(tmax <= m + kFrame);               // (also for NaN)
+  // The reference of a row: the maximum of the first tile its split sees (FIRST: nothing has been
+  // accumulated for any row of the wave yet), kept from then on.  Later tiles do not even look for
+  // their maximum: a weight beyond 2^kFrame shows in the row's sum, which the tile loop tests once,
+  // after the last tile (left_frame below).
+  static __device__ __forceinline__ float reference(WaveState<D>& st, const floatx16& s, float scale_log2, bool first) {
+    if (!first) return st.m;  // (uniform)
+    const float tmax = half_swap_max(max16(s)) * scale_log2;  // (an unmasked tile of finite scores: finite)
+    const float m = (st.m == -INFINITY) ? tmax : st.m;
     st.m = m;
     return m;
   }
+  // whether a weight of this lane's row went beyond 2^kFrame (or was NaN): its sum tells
+  static __device__ __forceinline__ bool left_frame(const WaveState<D>& st) { return !(st.l < 1.8446744e19f); }
 
-  // two scores -> probabilities (elements 2*i, 2*i+1 of the tile) into their bf16 operand slot
+  // two scores -> probabilities (elements 2*i, 2*i+1 of the tile) into their bf16 operand slot; the
+  // row sum takes the rounded probabilities (one dot product with (1, 1) instead of two additions,
+  // and numerator and denominator of the softmax then carry the same rounding)
   static __device__ __forceinline__ void two_probs(const floatx16& s, int i, float scale_log2, float m_use,
                                                    float& lsum, bf16x8 (&pb)[2]) {
     const float p0 = fast_exp2(fmaf(s[2 * i], scale_log2, -m_use));
     const float p1 = fast_exp2(fmaf(s[2 * i + 1], scale_log2, -m_use));
-    lsum += p0 + p1;
-    pb[(2 * i) / 8][(2 * i) % 8] = (__bf16)p0;
-    pb[(2 * i) / 8][(2 * i) % 8 + 1] = (__bf16)p1;
+    bf16x2 pk, one;
+    pk[0] = (__bf16)p0;
+    pk[1] = (__bf16)p1;
+    one[0] = one[1] = (__bf16)1.f;
+    lsum = __builtin_amdgcn_fdot2_f32_bf16(pk, one, lsum, false);
+    pb[(2 * i) / 8][(2 * i) % 8] = pk[0];
+    pb[(2 * i) / 8][(2 * i) % 8 + 1] = pk[1];
   }
 
   // k_addr / v_addr: LDS byte address of tile A's K / V tile plus the lane's Geo::k_lane / v_lane
   // `next`: the transfers of the round that refills the ring (SPREAD > 0), issued between the
   // MFMAs of the first SPREAD score phases
+  // `first`: the wave's first tiles of its split (uniform)
   template <int SPREAD, class Pieces>
   static __device__ __forceinline__ void run(WaveState<D>& st, unsigned k_addr, unsigned v_addr, float scale_log2,
-                                             const Pieces& next, bool& left) {
+                                             const Pieces& next, bool first) {
     static_assert(DK == 8 || DK == 4, "head_dim 128 or 64");
     constexpr unsigned kNextTile = 2 * G_::TILE_BYTES;  // tile B's K (V) tile follows tile A's K and V
     auto v_frag = [&](unsigned tile_off, int j, int db) {
@@ -532,7 +547,7 @@ struct PairPipe {
       if (SPREAD > 1) next.share(DK + ks, DK * SPREAD);
     }
     __builtin_amdgcn_sched_barrier(0);
-    const float mA = reference(st, sA, scale_log2, left);
+    const float mA = reference(st, sA, scale_log2, first);
 #pragma unroll
     for (int ks = DK / 2; ks < DK; ++ks) {
       sB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], st.q[ks], sB, 0, 0, 0);
@@ -559,7 +574,7 @@ struct PairPipe {
       st.o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfA[db], pA[0], st.o[db], 0, 0, 0);
     __builtin_amdgcn_sched_barrier(0);
     lsum = 0.f;
-    const float mB = reference(st, sB, scale_log2, left);
+    const float mB = mA;  // (the reference is fixed by now)
 #pragma unroll
     for (int db = 0; db < DB; ++db) {
       st.o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfA[DB + db], pA[1], st.o[db], 0, 0, 0);
@@ -587,7 +602,7 @@ struct PairPipe {
 // shapes are not bound by the tile arithmetic.)
 template <int D>
 __device__ __forceinline__ void lone_tile(WaveState<D>& st, unsigned k_addr, unsigned v_addr, float scale_log2,
-                                          bool& left) {
+                                          bool first) {
   using G_ = Geo<D>;
   constexpr int DK = G_::DK, DB = G_::DB;
   bf16x8 kf[DK], vf[2 * DB];
@@ -609,7 +624,7 @@ __device__ __forceinline__ void lone_tile(WaveState<D>& st, unsigned k_addr, uns
   }
 #pragma unroll
   for (int i = 0; i < 16; ++i) s0[i] = a0[i] + a1[i];
-  const float m = PairPipe<D>::reference(st, s0, scale_log2, left);
+  const float m = PairPipe<D>::reference(st, s0, scale_log2, first);
   bf16x8 pb[2];
   float lsum = 0.f;
 #pragma unroll
@@ -843,6 +858,8 @@ struct Plan {
   static constexpr int NW = WM * WN;                    // waves
   static constexpr int THREADS = 64 * NW;
   static constexpr int TPR = WN * KT;                   // tiles per round: KT consecutive ones per key column
+  // (deeper rings measured slower: with six tiles c3 +0.9 us per call, with eight +4.6 - more transfers in
+  // flight at once delay the first round's data by more than the later rounds gain)
   static constexpr int RING_TILES = TPR >= 4 ? 2 * TPR : 4;  // K+V tile pairs resident in LDS
   static constexpr int NR = RING_TILES / TPR;           // rounds resident in the ring
   static constexpr int QROWS = kWaveRows * WM;
@@ -1156,7 +1173,7 @@ __global__ __launch_bounds__((Plan<D, WM, WN, KT, PAGED>::THREADS), (Plan<D, WM,
   // the wave says so in LDS after the loop, and the workgroup runs the loop once more, from
   // its first round, on the general path only (lazy rescale): rare, and the pairs stay free
   // of any conditional touch of the accumulators.
-  bool left = false;     // this lane's row left the frame
+  bool left = false;     // a weight of this lane's row went beyond the frame (see PairPipe::reference)
   bool general = false;  // uniform: the repeat
   if (KT == 2 && tid == 0) *repeat_s = 0;  // (read behind the barrier that follows the loop)
   for (;;) {
@@ -1182,15 +1199,17 @@ __global__ __launch_bounds__((Plan<D, WM, WN, KT, PAGED>::THREADS), (Plan<D, WM,
     if (r == 0) JK_TS(4);
     if (refill && !spread) dma_round<D, NW, TPR, PAGED>(r + NR - 1, ts, lc, ring_addr + ((r + NR - 1) % NR) * STAGE_BYTES);
     if (pair && spread) {
-      PairPipe<D>::template run<kSpread>(st, tile_a + k_lane, tile_a + TILE_BYTES + v_lane, scale_log2, next, left);
+      PairPipe<D>::template run<kSpread>(st, tile_a + k_lane, tile_a + TILE_BYTES + v_lane, scale_log2, next, r == 0);
     } else if (pair) {
-      PairPipe<D>::template run<0>(st, tile_a + k_lane, tile_a + TILE_BYTES + v_lane, scale_log2, next, left);
+      PairPipe<D>::template run<0>(st, tile_a + k_lane, tile_a + TILE_BYTES + v_lane, scale_log2, next, r == 0);
     } else if (KT == 2 && WN == 1 && !general && tb + 1 == ts.t_end && (tb + 1) * kTileKeys <= L) {
-      lone_tile<D>(st, tile_a + k_lane, tile_a + TILE_BYTES + v_lane, scale_log2, left);  // no mask, half the work
+      lone_tile<D>(st, tile_a + k_lane, tile_a + TILE_BYTES + v_lane, scale_log2, r == 0);  // no mask, half the work
     } else if (tb < ts.t_end) {
       int mode, nvalid;
       unsigned int bits;
       floatx16 s0, s1;
+      // (the general path may rescale the sums: what the fast paths left in them is tested first)
+      if (KT == 2 && !general) left = left || PairPipe<D>::left_frame(st);
       qk_tiles<D, KT>(st, tile_a + k_lane, s0, s1);
       mask_of(tb, mode, nvalid, bits);
       mask_tile(s0, mode, nvalid, bits, g);
@@ -1201,7 +1220,7 @@ __global__ __launch_bounds__((Plan<D, WM, WN, KT, PAGED>::THREADS), (Plan<D, WM,
       softmax_pv<D, KT>(st, s0, s1, tile_a + TILE_BYTES + v_lane, scale_log2);
     }
   }
-  if (KT == 2 && !general && left) *repeat_s = 1;
+  if (KT == 2 && !general && (left || PairPipe<D>::left_frame(st))) *repeat_s = 1;
   JK_TS(5);
   __syncthreads();  // every wave is done with the ring before it becomes the epilogue buffer (or is filled again)
   if (KT != 2 || general || __builtin_amdgcn_readfirstlane(*repeat_s) == 0) break;
@@ -1290,40 +1309,67 @@ __global__ __launch_bounds__((Plan<D, WM, WN, KT, PAGED>::THREADS), (Plan<D, WM,
     unsigned char* patch = smem + P_::OBUF_BYTES + wm * P_::PATCH_BYTES;
     {
       unsigned char* prow = patch + c32_e * P_::PATCH_LD;
+      // (a lone wave per SIMD issues an instruction every five to eight cycles: this part of the
+      // kernel is bound by its instruction count, hence the uniform branches around whole loops
+      // rather than conditions inside them)
+      auto to_patch = [&](auto scaled) {
 #pragma unroll
-      for (int db = 0; db < DB; ++db)
+        for (int db = 0; db < DB; ++db)
 #pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-          bf16x2 lo, hi;
-          lo[0] = (__bf16)(st.o[db][4 * q4] * mul);
-          lo[1] = (__bf16)(st.o[db][4 * q4 + 1] * mul);
-          hi[0] = (__bf16)(st.o[db][4 * q4 + 2] * mul);
-          hi[1] = (__bf16)(st.o[db][4 * q4 + 3] * mul);
-          uint2 pk;
-          pk.x = __builtin_bit_cast(unsigned int, lo);
-          pk.y = __builtin_bit_cast(unsigned int, hi);
-          *reinterpret_cast<uint2*>(prow + (32 * db + 8 * q4 + 4 * g_e) * 2) = pk;
-        }
+          for (int q4 = 0; q4 < 4; ++q4) {
+            bf16x2 lo, hi;
+            lo[0] = (__bf16)(decltype(scaled)::value ? st.o[db][4 * q4] * mul : st.o[db][4 * q4]);
+            lo[1] = (__bf16)(decltype(scaled)::value ? st.o[db][4 * q4 + 1] * mul : st.o[db][4 * q4 + 1]);
+            hi[0] = (__bf16)(decltype(scaled)::value ? st.o[db][4 * q4 + 2] * mul : st.o[db][4 * q4 + 2]);
+            hi[1] = (__bf16)(decltype(scaled)::value ? st.o[db][4 * q4 + 3] * mul : st.o[db][4 * q4 + 3]);
+            uint2 pk;
+            pk.x = __builtin_bit_cast(unsigned int, lo);
+            pk.y = __builtin_bit_cast(unsigned int, hi);
+            *reinterpret_cast<uint2*>(prow + (32 * db + 8 * q4 + 4 * g_e) * 2) = pk;
+          }
+      };
+      if (splits == 1) to_patch(std::true_type{});
+      else to_patch(std::false_type{});
     }
     // (same wave wrote and reads: LDS operations of a wave complete in order)
     constexpr int CPR = G_::CPR;             // 16-byte chunks per row
     constexpr int RPI = 64 / CPR;            // rows per store instruction
     const int chunk = lane_e % CPR, rsub = lane_e / CPR;
+    const int rows_valid = M - (qtile * QROWS + wm * kWaveRows);  // rows of this wave that exist (32 or more: all)
+    if (splits == 1) {
 #pragma unroll
-    for (int k = 0; k < kWaveRows / RPI; ++k) {
-      const int rr = k * RPI + rsub;                               // row of the wave
-      const int m = qtile * QROWS + wm * kWaveRows + rr;           // query row
-      const u32x4 v = *reinterpret_cast<const u32x4*>(patch + rr * P_::PATCH_LD + chunk * 16);
-      if (m < M) {
-        uint16_t* dst;
-        if (splits == 1) {
+      for (int k = 0; k < kWaveRows / RPI; ++k) {
+        const int rr = k * RPI + rsub;                               // row of the wave
+        const int m = qtile * QROWS + wm * kWaveRows + rr;           // query row
+        const u32x4 v = *reinterpret_cast<const u32x4*>(patch + rr * P_::PATCH_LD + chunk * 16);
+        if (rr < rows_valid) {
           const int node = div_mg(m, p.mg_g);
-          dst = p.out + b * p.o_sb + node * p.o_st + (long long)(kv * G + (m - node * G)) * p.o_sh;
-        } else {
-          dst = reinterpret_cast<uint16_t*>(p.part_o) + (prow0 + rr) * D;
+          uint16_t* dst = p.out + b * p.o_sb + node * p.o_st + (long long)(kv * G + (m - node * G)) * p.o_sh;
+          if (p.through & 1) dev::store_through(dst + chunk * 8, v);
+          else *reinterpret_cast<u32x4*>(dst + chunk * 8) = v;
         }
-        if (p.through & 1) dev::store_through(dst + chunk * 8, v);
-        else *reinterpret_cast<u32x4*>(dst + chunk * 8) = v;
+      }
+    } else {
+      // partial rows are D elements apart: one address, constant steps
+      unsigned char* dst0 = reinterpret_cast<unsigned char*>(p.part_o) + ((prow0 + rsub) * D + chunk * 8) * 2;
+      const unsigned char* src0 = patch + rsub * P_::PATCH_LD + chunk * 16;
+      auto store_rows = [&](auto through, auto guarded) {
+#pragma unroll
+        for (int k = 0; k < kWaveRows / RPI; ++k) {
+          const u32x4 v = *reinterpret_cast<const u32x4*>(src0 + k * RPI * P_::PATCH_LD);
+          if (!decltype(guarded)::value || k * RPI + rsub < rows_valid) {
+            if (decltype(through)::value) dev::store_through(dst0 + k * RPI * D * 2, v);
+            else *reinterpret_cast<u32x4*>(dst0 + k * RPI * D * 2) = v;
+          }
+        }
+      };
+      const bool thr = p.through & 1;
+      if (rows_valid >= kWaveRows) {
+        if (thr) store_rows(std::true_type{}, std::false_type{});
+        else store_rows(std::false_type{}, std::false_type{});
+      } else {
+        if (thr) store_rows(std::true_type{}, std::true_type{});
+        else store_rows(std::false_type{}, std::true_type{});
       }
     }
   }
