@@ -70,7 +70,21 @@ bool shape_supported(const jk_attn_desc& d) {
 }
 }  // namespace
 
+// Constants of the attention plan's time estimate, each measured on an MI355X at head_dim 128 with
+// bench.py (forced plans through jk_set_tuning; the kernel's own time stamps in a -DJK_TIMING build):
+struct PlanModel {
+  double round_4x1 = 1.31;      // us per round (a pair of 32-key tiles) of a 4x1 workgroup alone on its CU: c3, 4 pairs in 5.26 us
+  double round_2x2 = 0.95;      // us per round (one tile per key column) of a 2x2 workgroup: c2 sweep of split counts
+  double share2_4x1 = 1.58;     // two 4x1 workgroups on one CU take this many times one's time: c5, 1 against 2 per CU
+  double share_2x2_slope = 0.75;  // 2x2 workgroups sharing a CU: time x (0.75 per workgroup + 0.25): c7 and c4 sweeps
+  double cu_pull = 22.0e3;      // bytes per us one CU draws from HBM with one round in flight (32 KB / 1.3 us round trip)
+  double stream = 4.0e6;        // bytes per us all CUs together: c4, 178 MB per call
+  double merge_fused_fixed = 2.0, merge_fused_per_mb = 0.1;   // merge inside the kernel: c3 time stamps, xchg probe
+  double merge_kernel_fixed = 3.0, merge_kernel_per_mb = 0.28, merge_kernel_per_mb_busy = 0.4;  // second launch: c3/c2/c5 traces
+};
+
 bool make_attn_plan(const jk_attn_desc& d, int max_prefix_len, bool fused_allowed, AttnPlan* pl) {
+  static const PlanModel km;
   if (!desc_ok(d) || !shape_supported(d) || max_prefix_len < 0 || max_prefix_len > (1 << 24)) return false;
   const int G = d.n_q_heads / d.n_kv_heads;
   pl->m_rows = d.n_tree * G;
@@ -115,7 +129,7 @@ bool make_attn_plan(const jk_attn_desc& d, int max_prefix_len, bool fused_allowe
         // by the row tiles at a quarter of the price) moves at about 4 TB/s while every CU
         // pulls, so CUs with one workgroup more than the average stretch it; partial outputs
         // (bf16, written, flushed at the kernel boundary and read back) cost about 0.28 us per MB.
-        const double t_round = (wn == 1 ? 1.33 : 0.95) * d.head_dim / 128.0;
+        const double t_round = (wn == 1 ? km.round_4x1 : km.round_2x2) * d.head_dim / 128.0;
         // rounds of the longest split: the 4x1 arrangement deals tiles (an odd last tile costs about
         // half a round), the 2x2 arrangement whole rounds
         double rounds;
@@ -140,12 +154,14 @@ bool make_attn_plan(const jk_attn_desc& d, int max_prefix_len, bool fused_allowe
         // 4x1 workgroups that share a CU overlap each other's matrix and vector phases: two of
         // them take 1.58 times one's time (measured on c5), plus a part of a workgroup of tail
         const double share =
-            per_cu > 1.0 ? (wn == 1 ? 0.79 * (per_cu + 0.3 > 2.0 ? per_cu + 0.3 : 2.0) : per_cu + 0.5) : 1.0;
+            per_cu > 1.0 ? (wn == 1 ? 0.5 * km.share2_4x1 * (per_cu + 0.3 > 2.0 ? per_cu + 0.3 : 2.0)
+                                    : km.share_2x2_slope * per_cu + (1.0 - km.share_2x2_slope))
+                         : 1.0;
         const double imbalance = per_cu > 1.0 ? std::ceil(per_cu) / per_cu : 1.0;
         const double loop_us = rounds * t_round * share;
         // (a CU pulls about 22 GB/s on its own: fewer workgroups than CUs stream slower than 4 TB/s)
         const double active = (double)(wgs * s < slots ? wgs * s : slots);
-        const double rate = active * 22.0e3 < 4.0e6 ? active * 22.0e3 : 4.0e6;  // bytes per microsecond
+        const double rate = active * km.cu_pull < km.stream ? active * km.cu_pull : km.stream;  // bytes per microsecond
         const double stream_us = imbalance * (double)units * kv_bytes * (1.0 + 0.25 * (n_qtiles - 1)) / rate;
         // Merge inside the kernel: possible when every workgroup is resident at once (here: at most
         // one per CU, or two when forced) and the workgroup numbering puts all splits of a (unit, row
@@ -168,9 +184,10 @@ bool make_attn_plan(const jk_attn_desc& d, int max_prefix_len, bool fused_allowe
         // kernel they cost a second launch (about 3 us) and 0.28 us per MB when the grid is one turn
         // of workgroups and they are stored through to memory, 0.4 when they take the ordinary route
         const double part_mb = 1.0e-6 * (double)units * s * pl->m_rows * d.head_dim * 2.0;
-        const double partial_us = s <= 1 ? 0.0
-                                  : can_fuse ? 2.0 + 0.1 * part_mb
-                                             : 3.0 + (per_cu > 1.0 && wn == 1 ? 0.4 : 0.28) * part_mb;
+        const double partial_us =
+            s <= 1 ? 0.0
+            : can_fuse ? km.merge_fused_fixed + km.merge_fused_per_mb * part_mb
+                       : km.merge_kernel_fixed + (per_cu > 1.0 && wn == 1 ? km.merge_kernel_per_mb_busy : km.merge_kernel_per_mb) * part_mb;
         // (near ties go to the count that gives every CU a workgroup: 2 % for an idle CU)
         const double cost = ((loop_us > stream_us ? loop_us : stream_us) + partial_us) * (active < slots ? 1.02 : 1.0);
         if (!have || cost < best_cost) {
