@@ -94,7 +94,15 @@ def test_bf16_peaked_softmax():
     x["q"] = round_to_bf16(x["q"] * 8.0)
     # near one-hot rows return single V rows (entries up to about 4.5): three bf16 roundings on the way
     # (probability, split partial, result; unit roundoff 2^-8 each) allow 3 * 2^-8 * 4.5 = 5.3e-2 absolute
-    check_attention(x, par, [600], "bf16", 3 * 2.0 ** -8 * 4.5, rel_tol=2e-2)
+    vmax = float(max(np.abs(x["v_cache"]).max(), np.abs(x["v_tree"]).max()))
+    assert 4.0 < vmax < 5.5
+    got, ref = check_attention(x, par, [600], "bf16", 3 * 2.0 ** -8 * vmax, rel_tol=2e-2)
+    # The split partial's rounding is one of the three and is this library's own: with one split it is gone, and
+    # the bound is two roundings (probability, result).  Measured worst cases go into the design notes.
+    tune("attn_splits", 1)
+    got1, _ = check_attention(x, par, [600], "bf16", 2 * 2.0 ** -8 * vmax, rel_tol=2e-2)
+    print(f"near one-hot rows: worst error {np.abs(got - ref).max():.4f} split, {np.abs(got1 - ref).max():.4f} unsplit, "
+          f"bounds {3 * 2.0 ** -8 * vmax:.4f} / {2 * 2.0 ** -8 * vmax:.4f}")
 
 
 @pytest.mark.parametrize("where", [40, 1500, 2999])
@@ -160,17 +168,26 @@ def test_bf16_custom_scale_and_strided_cache():
     assert err <= BF16_TOL and err / np.abs(ref).max() <= 1.5e-2
 
 
-def test_bf16_sibling_independence_bitwise():
+@pytest.mark.parametrize("big", [False, True], ids=["tree60_planned", "tree128_three_splits"])
+def test_bf16_sibling_independence_bitwise(big):
     """Nodes outside a query's ancestor set cannot change its output: their K rows
-    may hold anything (NaN), their V rows anything finite; results stay bit-identical."""
-    cfg = _cfg("c3_llama3_8b", prefix_len=90, n_q_heads=8, n_kv_heads=2)
-    par = tree_for_config(cfg)
+    may hold anything (NaN), their V rows anything finite (a reading of this library: a masked score is
+    -inf before the softmax, so its weight is an exact zero, and 0 x finite = 0 in the value product);
+    results stay bit-identical.  Also with the largest tree (four tree tiles) over three key splits."""
+    if big:
+        tune("attn_wm", 4); tune("attn_wn", 1); tune("attn_splits", 3)
+        rng = np.random.default_rng(128)
+        par = np.array([-1] + [int(rng.integers(max(-1, i - 9), i)) for i in range(1, 128)], dtype=np.int32)[None]
+        cfg = _cfg("c3_llama3_8b", n_tree=128, prefix_len=90, n_q_heads=8, n_kv_heads=2)
+    else:
+        cfg = _cfg("c3_llama3_8b", prefix_len=90, n_q_heads=8, n_kv_heads=2)
+        par = tree_for_config(cfg)
     x = attention_inputs(cfg, scale_mult=np.sqrt(128.0))
     base = gpu_attention(x, par, [90], "bf16")
     from oracle import ancestor_sets
     anc = ancestor_sets(par[0])
     T = cfg.n_tree
-    for i in [T - 1, T // 2, 3]:
+    for i in [T - 1, T // 2, 3] + ([70, 33] if big else []):
         y = {k: v.copy() for k, v in x.items()}
         others = [j for j in range(T) if j not in anc[i]]
         y["k_tree"][0, others] = np.nan
@@ -230,40 +247,38 @@ def test_bf16_prefix_shorter_than_bound(monkeypatch, wm, wn):
     assert np.abs(got - ref).max() <= BF16_TOL
 
 
-def test_c2_full_size_sampled_rows():
-    """Config 2 at full size in the benchmark's launch configuration; the oracle
-    checks a sample of (node, head) rows one by one."""
+def _every_element(cfg, x, par, got):
+    """The whole result against the oracle, element by element (the oracle needs well under a second per layer
+    at these sizes): absolute bound of the graded metric, and relative to the layer's largest output."""
+    ref = oracle_attention(**x, parent=par, prefix_len=[cfg.prefix_len] * cfg.batch)
+    err = np.abs(got - ref)
+    assert err.max() <= BF16_TOL
+    assert err.max() <= 1.5e-2 * np.abs(ref).max(), (err.max(), np.abs(ref).max())
+    return float(err.max() / np.abs(ref).max())
+
+
+@pytest.mark.parametrize("scaled", [True, False], ids=["as_configured", "unit_variance"])
+def test_c2_full_size_every_element(scaled):
+    """Config 2 (Vicuna-7B shape) at full size: inputs as the config states them (all of Q, K, V times
+    1/sqrt(128): outputs near 1e-3, where the 2e-2 bound says little) and at unit variance."""
     cfg = CONFIGS["c2_vicuna7b"]
     par = tree_for_config(cfg)
-    x = attention_inputs(cfg)
+    x = attention_inputs(cfg) if scaled else attention_inputs(cfg, scale_mult=np.sqrt(128.0))
     got = gpu_attention(x, par, [cfg.prefix_len], "bf16")
-    from oracle import tree_verify_attention as oracle_attention
-    rng = np.random.default_rng(0)
-    for _ in range(12):
-        i, h = int(rng.integers(cfg.n_tree)), int(rng.integers(cfg.n_q_heads))
-        sub = {"q": x["q"][:, :, h:h + 1], "k_cache": x["k_cache"][:, :, h:h + 1], "v_cache": x["v_cache"][:, :, h:h + 1],
-               "k_tree": x["k_tree"][:, :, h:h + 1], "v_tree": x["v_tree"][:, :, h:h + 1]}
-        ref = oracle_attention(**sub, parent=par, prefix_len=[cfg.prefix_len])
-        assert np.abs(got[0, i, h] - ref[0, i, 0]).max() <= BF16_TOL
-        assert np.abs(got[0, i, h] - ref[0, i, 0]).max() <= 2e-2 * np.abs(ref[0, :, 0]).max() + 1e-6
+    _every_element(cfg, x, par, got)
 
 
-def test_c3_full_size_sampled_rows():
+@pytest.mark.parametrize("scaled", [True, False], ids=["as_configured", "unit_variance"])
+@pytest.mark.parametrize("fused", [1, 0], ids=["merged_in_kernel", "merge_kernel"])
+def test_c3_full_size_every_element(scaled, fused):
+    """Config 3 (the benchmarked one) at full size, every element, in the plan bench.py times and with the
+    stand-alone merge kernel."""
+    tune("attn_fused", fused)
     cfg = CONFIGS["c3_llama3_8b"]
     par = tree_for_config(cfg)
-    x = attention_inputs(cfg, scale_mult=np.sqrt(128.0))
+    x = attention_inputs(cfg) if scaled else attention_inputs(cfg, scale_mult=np.sqrt(128.0))
     got = gpu_attention(x, par, [cfg.prefix_len], "bf16")
-    from oracle import tree_verify_attention as oracle_attention
-    rng = np.random.default_rng(1)
-    G = cfg.group
-    for _ in range(6):
-        kv = int(rng.integers(cfg.n_kv_heads))
-        hs = slice(kv * G, kv * G + G)
-        sub = {"q": x["q"][:, :, hs], "k_cache": x["k_cache"][:, :, kv:kv + 1], "v_cache": x["v_cache"][:, :, kv:kv + 1],
-               "k_tree": x["k_tree"][:, :, kv:kv + 1], "v_tree": x["v_tree"][:, :, kv:kv + 1]}
-        ref = oracle_attention(**sub, parent=par, prefix_len=[cfg.prefix_len])
-        err = np.abs(got[0, :, hs] - ref[0]).max()
-        assert err <= BF16_TOL and err <= 1.5e-2 * np.abs(ref).max()
+    _every_element(cfg, x, par, got)
 
 
 def _sampled_unit_check(cfg, x, par, got, n_samples, seed):
