@@ -198,9 +198,14 @@ size_t jk_accept_path_workspace(int32_t batch, int32_t n_tree, int32_t vocab, in
  *
  * Supported: 1 <= n_tree <= JK_MAX_TREE, vocab >= 1, max_depth >= 1.  Token ids
  * outside [0, vocab) are clamped into the range.  JK_SAMPLE runs several
- * workgroups per tree that wait for each other; the wait is bounded, and if it
- * ever expires (the device is too busy to keep them resident together)
- * out_accept_len and out_bonus_token are set to -1 for that tree.
+ * workgroups per tree that wait for each other; the wait is bounded (a few
+ * milliseconds), and if it ever expires (the device is too busy to keep them
+ * resident together) out_accept_len and out_bonus_token are set to -1 for that
+ * tree and JK_DEVERR_WALK_WAIT is set in the workspace's error word.  Nothing
+ * else is lost: the workspace stays valid for further calls, jk_commit_path
+ * treats a length of -1 as "commit nothing", and the caller may simply repeat
+ * the call for that step (same inputs, same uniforms: the walk is a pure
+ * function of them) or emit no draft token for it.
  * All sampling arithmetic (softmax, residuals, cumulative sums) is fp64, so a
  * decision can differ from exact arithmetic only when its two sides agree to
  * about 1e-13 relative. */

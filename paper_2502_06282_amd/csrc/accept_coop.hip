@@ -17,14 +17,16 @@
 // appeared.  All workgroups reduce the same values in the same order, so they
 // take identical decisions.  Waiting is bounded: if a partner never shows up
 // (the W workgroups of a tree are not all resident) the walk gives up and
-// reports accept_len = -1 instead of hanging.
+// reports accept_len = -1 instead of hanging; the last workgroup of a tree to
+// finish publishes the results and moves the call number on (see TreeWords), so
+// a call that gave up leaves nothing behind that a later call could mistake.
 #include "jk_internal.h"
 
 namespace jk {
 namespace {
 
 constexpr int kCoopThreads = 256;
-constexpr unsigned kSpinLimit = 1u << 22;  // polls before giving up (seconds)
+constexpr unsigned kDefaultSpinLimit = 1u << 12;  // polls before giving up: a few milliseconds
 
 // One workgroup's contribution to an exchange: two doubles, cut into four 32-bit halves,
 // each stored in a 64-bit word together with the exchange's 32-bit tag.  A word is written
@@ -34,6 +36,21 @@ struct Slot {  // 32 bytes
   unsigned long long word[4];
 };
 
+// Per-tree words in the workspace header.  `epoch` numbers the calls: every exchange of a call is
+// tagged with epoch + 1, and only the LAST workgroup of the tree to finish moves it on (it counts
+// the finished ones in `finish` and returns that to zero), so that workgroups that start late -
+// even after the others have given up and left - still read the call's own epoch and can never
+// publish a tag that a later call would take for its own.  The results travel the same way: the
+// workgroup that owns the final draw leaves (tag, token) in `bonus`, workgroup 0 (tag, length) in
+// `len`, a workgroup that gave up its tag in `fail`; the last to finish reads the three and is
+// the only writer of accept_len and bonus_token.
+struct TreeWords {  // 64 bytes
+  unsigned long long epoch;
+  unsigned long long bonus, len, fail;
+  unsigned finish;
+  unsigned pad[7];
+};
+
 struct CoopParams {
   int n_tree, vocab, max_depth, W, slice;
   double inv_temp;  // 1 / temperature
@@ -41,8 +58,9 @@ struct CoopParams {
   const float *logits, *draft, *uniforms;
   const int* draft_row;  // or null: row b*n_tree + k of draft
   long long n_draft_rows;
-  unsigned long long* epoch;  // [batch] workspace words, each bumped once per call by its tree
-  Slot* slots;                // [batch][2][W]
+  TreeWords* words;  // [batch] workspace words of each tree (zero before the first use of the workspace)
+  unsigned spin_limit;
+  Slot* slots;       // [batch][2][W]
   int *out_path, *out_len, *out_bonus;
   unsigned* err;  // the workspace's sticky device error word
 };
@@ -95,7 +113,8 @@ __global__ __launch_bounds__(kCoopThreads) void walk_sample_coop_kernel(CoopPara
   }
   if (tid <= N) uni_reg = p.uniforms[(long long)b * rows + tid];
   if (tid == 0) s_fail = 0;
-  const unsigned long long epoch = __hip_atomic_load(p.epoch + b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  TreeWords* tw = p.words + b;
+  const unsigned long long epoch = __hip_atomic_load(&tw->epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   __syncthreads();
 
   // the draft distribution of node k (a row of p.draft)
@@ -141,7 +160,7 @@ __global__ __launch_bounds__(kCoopThreads) void walk_sample_coop_kernel(CoopPara
       unsigned long long v;
       unsigned spins = 0;
       while ((unsigned)((v = __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) >> 32) != tag) {
-        if (++spins > kSpinLimit || s_fail) { s_fail = 1; v = 0; break; }
+        if (++spins > p.spin_limit || s_fail) { s_fail = 1; v = 0; break; }
         __builtin_amdgcn_s_sleep(1);
       }
       xh[tid] = (unsigned)v;
@@ -401,31 +420,42 @@ __global__ __launch_bounds__(kCoopThreads) void walk_sample_coop_kernel(CoopPara
         }
       }
       if (tid == 0) {
-        const int capped = len;  // (the walk itself stops at max_depth)
+        const unsigned long long tag = (epoch + 1) << 32;
         if (mine || (!any && w == 0)) {
-          p.out_bonus[b] = mine ? s_found : (last_any < 0 ? 0 : last_any);
+          const int token = mine ? s_found : (last_any < 0 ? 0 : last_any);
+          __hip_atomic_store(&tw->bonus, tag | (unsigned)token, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         if (w == 0) {
-          for (int i = capped; i < p.max_depth; ++i) p.out_path[(long long)b * p.max_depth + i] = -1;
-          p.out_len[b] = capped;
+          for (int i = len; i < p.max_depth; ++i) p.out_path[(long long)b * p.max_depth + i] = -1;
+          __hip_atomic_store(&tw->len, tag | (unsigned)len, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
       }
     }
   }
-  if (s_fail && tid == 0 && w == 0) {
-    p.out_len[b] = -1;
-    p.out_bonus[b] = -1;
-    __hip_atomic_fetch_or(p.err, kDevErrWalkWait, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  // ---- the end of this workgroup: say so; the last one of the tree publishes the results
+  if (tid == 0) {
+    const unsigned long long tag = (epoch + 1) << 32;
+    if (s_fail) __hip_atomic_store(&tw->fail, tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // (the words above went through to memory; wait for that before the count can tell anybody)
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    const unsigned done = __hip_atomic_fetch_add(&tw->finish, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (done == (unsigned)W - 1) {
+      __hip_atomic_store(&tw->finish, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const unsigned long long f = __hip_atomic_load(&tw->fail, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const unsigned long long l = __hip_atomic_load(&tw->len, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const unsigned long long t = __hip_atomic_load(&tw->bonus, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const bool ok = f != tag && (l >> 32) == (tag >> 32) && (t >> 32) == (tag >> 32);
+      p.out_len[b] = ok ? (int)(unsigned)l : -1;
+      p.out_bonus[b] = ok ? (int)(unsigned)t : -1;
+      if (!ok) __hip_atomic_fetch_or(p.err, kDevErrWalkWait, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(&tw->epoch, epoch + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
   }
-  // every workgroup of this tree read the epoch before its first exchange, and nobody gets
-  // here before having exchanged with all of them: safe to advance it for the next call
-  if (tid == 0 && w == 0)
-    __hip_atomic_store(p.epoch + b, epoch + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 }  // namespace
 
-static size_t coop_header_bytes(int batch) { return ((size_t)batch * 8 + 255) / 256 * 256; }
+static size_t coop_header_bytes(int batch) { return ((size_t)batch * sizeof(TreeWords) + 255) / 256 * 256; }
 
 size_t accept_coop_bytes(int batch) { return coop_header_bytes(batch) + (size_t)batch * 2 * 64 * sizeof(Slot); }
 
@@ -448,7 +478,8 @@ hipError_t launch_accept_coop(const AcceptArgs& a, void* coop_ws, int W, int sli
   cp.tokens = a.tokens; cp.parent = a.parent;
   cp.logits = a.logits; cp.draft = a.draft_probs; cp.uniforms = a.uniforms;
   cp.draft_row = a.draft_row; cp.n_draft_rows = a.n_draft_rows;
-  cp.epoch = static_cast<unsigned long long*>(coop_ws);
+  cp.words = static_cast<TreeWords*>(coop_ws);
+  cp.spin_limit = tuning().spin_limit >= 0 ? (unsigned)tuning().spin_limit : kDefaultSpinLimit;
   cp.slots = reinterpret_cast<Slot*>(static_cast<char*>(coop_ws) + coop_header_bytes(a.batch));
   cp.out_path = a.out_path; cp.out_len = a.out_len; cp.out_bonus = a.out_bonus;
   const size_t lds = (size_t)slice * sizeof(double);

@@ -262,3 +262,46 @@ def test_sample_workspace_reuse_across_shapes_and_graph_replay():
         assert (o_len.cpu().numpy() == results["big"][1]).all() and (o_bonus.cpu().numpy() == results["big"][2]).all()
         call.launch()                      # eager work between replays
         torch.cuda.synchronize()
+
+
+def test_sample_walk_gives_up_cleanly_and_the_workspace_survives():
+    """spin_limit 0: a workgroup of the cooperative walk that does not find its partners' words at once gives
+    up (every kernel still ends normally).  A tree then reports accept_len = bonus = -1 and the workspace's
+    error word says so; a tree that got through must be right.  The calls that follow on the same workspace,
+    with normal waits, must be bit-exact again: words of the failed call can never be taken for theirs."""
+    cfg = CONFIGS["c3_llama3_8b"].with_(vocab=20011, batch=3)
+    par = tree_for_config(cfg, seed=11)
+    a = accept_inputs(cfg, par, seed=11)
+    dev = torch.device("cuda")
+    t = lambda v: torch.from_numpy(np.ascontiguousarray(v)).to(dev)
+    args = (t(a["tokens"]), t(par.astype(np.int32)), t(a["logits"]), jk.JK_SAMPLE, 1.0, t(a["draft_probs"]), t(a["uniforms"]))
+    ws = torch.empty(jk.accept_path_workspace(cfg.batch, cfg.n_tree, cfg.vocab, jk.JK_SAMPLE), dtype=torch.uint8, device=dev)
+    jk.workspace_init(ws)
+    ref = [oracle_accept(a["tokens"][b], par[b], a["logits"][b], "sample", a["draft_probs"][b], a["uniforms"][b])
+           for b in range(cfg.batch)]
+    assert all(r.min_margin > MARGIN for r in ref)
+
+    def check(path, alen, bonus, allow_fail):
+        failed = 0
+        for b, r in enumerate(ref):
+            if allow_fail and int(alen[b]) == -1:
+                assert int(bonus[b]) == -1
+                failed += 1
+                continue
+            assert int(alen[b]) == r.accept_len and int(bonus[b]) == r.bonus_token
+            assert path[b, : r.accept_len].cpu().tolist() == r.path
+        return failed
+
+    tune("spin_limit", 0)
+    failed = 0
+    for _ in range(3):
+        path, alen, bonus = jk.accept_path(*args, workspace=ws)
+        torch.cuda.synchronize()
+        failed += check(path, alen, bonus, True)
+    assert failed > 0, "no walk gave up: the test exercised nothing"
+    assert jk.last_device_error(ws) & jk.JK_DEVERR_WALK_WAIT
+    tune("spin_limit", -1)
+    for _ in range(3):
+        path, alen, bonus = jk.accept_path(*args, workspace=ws)
+        torch.cuda.synchronize()
+        assert check(path, alen, bonus, False) == 0
