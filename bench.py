@@ -29,10 +29,12 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
-# HBM bytes per tva_bf16_kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (KiB per
-# dispatch), each scaled by the same counter's reading for a 256 MiB device copy (factors 2.00 and
-# 1.00); source: profiles/tva_bf16_c3_hbm_traffic.md.  {workload: bytes} or None if not measured.
-MEASURED_TRAFFIC = {"c3_llama3_8b": 25920318}
+# HBM bytes per launch of the attention kernel (tva_bf16_kernel; for c5 without its merge kernel) from
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (KiB per dispatch), each scaled by the same counter's reading
+# for a 256 MiB device copy (factors 2.00 and 1.00); source: profiles/<workload>_attention_and_acceptance.md.
+# {workload: bytes}; None for workloads that were not measured.
+MEASURED_TRAFFIC = {"c2_vicuna7b": 26704889, "c3_llama3_8b": 34407885, "c4_llama2_13b": 191883415,
+                    "c5_llama2_70b": 709455467}
 
 
 def attn_bytes(cfg) -> int:
