@@ -51,6 +51,14 @@ struct TreeWords {  // 64 bytes
   unsigned pad[7];
 };
 
+// What a tree owns in the workspace: its words and two exchange tables of up to 64 slots.  Tree b's
+// block sits at b * sizeof(TreeBlock) whatever the batch size of a call is, so calls of different
+// shapes can share one workspace.
+struct TreeBlock {  // 4160 bytes
+  TreeWords words;
+  Slot slots[2 * 64];
+};
+
 struct CoopParams {
   int n_tree, vocab, max_depth, W, slice;
   double inv_temp;  // 1 / temperature
@@ -58,9 +66,8 @@ struct CoopParams {
   const float *logits, *draft, *uniforms;
   const int* draft_row;  // or null: row b*n_tree + k of draft
   long long n_draft_rows;
-  TreeWords* words;  // [batch] workspace words of each tree (zero before the first use of the workspace)
+  TreeBlock* trees;  // [batch] words and exchange tables of each tree (zero before the first use of the workspace)
   unsigned spin_limit;
-  Slot* slots;       // [batch][2][W]
   int *out_path, *out_len, *out_bonus;
   unsigned* err;  // the workspace's sticky device error word
 };
@@ -113,7 +120,7 @@ __global__ __launch_bounds__(kCoopThreads) void walk_sample_coop_kernel(CoopPara
   }
   if (tid <= N) uni_reg = p.uniforms[(long long)b * rows + tid];
   if (tid == 0) s_fail = 0;
-  TreeWords* tw = p.words + b;
+  TreeWords* tw = &p.trees[b].words;
   const unsigned long long epoch = __hip_atomic_load(&tw->epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   __syncthreads();
 
@@ -138,7 +145,7 @@ __global__ __launch_bounds__(kCoopThreads) void walk_sample_coop_kernel(CoopPara
   };
 
   const int n_per = (p.slice + kCoopThreads - 1) / kCoopThreads;  // slice elements per thread (uniform)
-  Slot* slots = p.slots + (long long)b * 2 * 64;
+  Slot* slots = p.trees[b].slots;
   unsigned n_exch = 0;
 
   // all-gather of one (a, b) pair per workgroup; results in xa[0..W), xb[0..W).
@@ -455,9 +462,7 @@ __global__ __launch_bounds__(kCoopThreads) void walk_sample_coop_kernel(CoopPara
 
 }  // namespace
 
-static size_t coop_header_bytes(int batch) { return ((size_t)batch * sizeof(TreeWords) + 255) / 256 * 256; }
-
-size_t accept_coop_bytes(int batch) { return coop_header_bytes(batch) + (size_t)batch * 2 * 64 * sizeof(Slot); }
+size_t accept_coop_bytes(int batch) { return (size_t)batch * sizeof(TreeBlock); }
 
 bool accept_coop_plan(int batch, int vocab, int cus, int* W, int* slice) {
   int w = (2 * cus) / batch;
@@ -478,9 +483,8 @@ hipError_t launch_accept_coop(const AcceptArgs& a, void* coop_ws, int W, int sli
   cp.tokens = a.tokens; cp.parent = a.parent;
   cp.logits = a.logits; cp.draft = a.draft_probs; cp.uniforms = a.uniforms;
   cp.draft_row = a.draft_row; cp.n_draft_rows = a.n_draft_rows;
-  cp.words = static_cast<TreeWords*>(coop_ws);
+  cp.trees = static_cast<TreeBlock*>(coop_ws);
   cp.spin_limit = tuning().spin_limit >= 0 ? (unsigned)tuning().spin_limit : kDefaultSpinLimit;
-  cp.slots = reinterpret_cast<Slot*>(static_cast<char*>(coop_ws) + coop_header_bytes(a.batch));
   cp.out_path = a.out_path; cp.out_len = a.out_len; cp.out_bonus = a.out_bonus;
   const size_t lds = (size_t)slice * sizeof(double);
   static bool lds_limit_raised = false;

@@ -305,3 +305,25 @@ def test_sample_walk_gives_up_cleanly_and_the_workspace_survives():
         path, alen, bonus = jk.accept_path(*args, workspace=ws)
         torch.cuda.synchronize()
         assert check(path, alen, bonus, False) == 0
+
+
+def test_sample_calls_of_different_batch_sizes_share_a_workspace():
+    """Calls with different numbers of trees alternate on one workspace (a tree's words must keep their place
+    whatever the batch size of a call is): every call is bit-exact and the error word stays clear."""
+    dev = torch.device("cuda")
+    t = lambda v: torch.from_numpy(np.ascontiguousarray(v)).to(dev)
+    ws = torch.empty(jk.accept_path_workspace(11, 60, 7001, jk.JK_SAMPLE), dtype=torch.uint8, device=dev)
+    jk.workspace_init(ws)
+    for i, batch in enumerate([11, 3, 11, 1, 9, 5, 11]):
+        cfg = CONFIGS["c3_llama3_8b"].with_(vocab=7001, batch=batch)
+        par = tree_for_config(cfg, seed=20 + i)
+        a = accept_inputs(cfg, par, seed=20 + i)
+        path, alen, bonus = jk.accept_path(t(a["tokens"]), t(par), t(a["logits"]), jk.JK_SAMPLE, 1.0,
+                                           t(a["draft_probs"]), t(a["uniforms"]), workspace=ws)
+        torch.cuda.synchronize()
+        for b in range(batch):
+            r = oracle_accept(a["tokens"][b], par[b], a["logits"][b], "sample", a["draft_probs"][b], a["uniforms"][b])
+            if r.min_margin > MARGIN:
+                assert int(alen[b]) == r.accept_len and int(bonus[b]) == r.bonus_token, (i, batch, b)
+                assert path[b, : r.accept_len].cpu().tolist() == r.path
+    assert jk.last_device_error(ws) == 0
