@@ -585,6 +585,26 @@ def main():
                                        "and eager launches (which include torch's output allocations)"}
         del tg_q, graph_q, ref_q, g_tree
 
+    # One whole round of the method as three HIP graphs (draft passes with the partial tree in the draft layer's
+    # attention -> tree -> one attention call per target layer -> acceptance -> commit), random weights, the
+    # shapes of this workload's model: what verify_steps_per_s has beside it on the draft side.
+    whole_round = None
+    if not args.no_extras and not args.no_draft_heads and cfg.mode == "sample" and cfg.dtype == "bf16" and cfg.tree_kind == "two_expert":
+        from paper_2502_06282_amd import example_round
+        d_model = cfg.n_q_heads * cfg.head_dim
+        shape = dict(batch=cfg.batch, d_model=d_model, n_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads,
+                     head_dim=cfg.head_dim, d_ff=d_model, n_experts=8, vocab=cfg.vocab, depth=cfg.depth, top_k=cfg.topk,
+                     width=cfg.frontier, n_tree=cfg.n_tree, prefix=cfg.prefix_len, target_layers=args.layers)
+        rd = example_round.Round(seed=cfg.seed, **shape)
+        whole_round = rd.time_phases(reps=10)
+        whole_round.update(target_layers=args.layers, draft_passes=cfg.depth,
+                           note="median of 10 replays; draft = per depth: reduction layer, q/k/v/o projections, attention "
+                                "over the draft cache and the partial tree, router + experts, both heads, tree growth; "
+                                "verify = the target layers' attention calls (the target's own projections and MLPs are "
+                                "outside this library) + synthetic logits; refine = acceptance walk + commit of every layer")
+        del rd
+        torch.cuda.empty_cache()
+
     for _ in range(args.copy_calibration):
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)
@@ -652,6 +672,7 @@ def main():
         "accept_nodes_per_s": round(cfg.batch * cfg.n_tree / acc_s, 1),
         "accept_len": [int(v) for v in res[1].cpu().tolist()],
         "accept": accept,
+        "whole_round": whole_round,
         "stream_read_probe": probe,
         "commit_path": commit,
         "draft_heads": draft,

@@ -551,15 +551,22 @@ def draft_heads_workspace(rows: int, d_model: int, vocab: int) -> int:
 
 
 def draft_heads(f_top, s_top, w_head, mode: int = JK_HEADS_DECOUPLED, temperature: float = 1.0, top_k: int = 10,
-                alpha: float = 0.0, beta: float = 0.0, want_probs: bool = True, stream=None):
+                alpha: float = 0.0, beta: float = 0.0, want_probs: bool = True, stream=None, out_probs=None):
     """jk_draft_heads.  f_top bf16 [R,2,d], s_top fp32 [R,2], w_head bf16 [V,d].
-    Returns (logits [R,2,V], draft_probs [R,2,V] or None, topk_tokens [R,2,k] int32, topk_probs [R,2,k])."""
+    Returns (logits [R,2,V], draft_probs [R,2,V] or None, topk_tokens [R,2,k] int32, topk_probs [R,2,k]).
+    `out_probs` (contiguous fp32 [R,2,V], for instance rows of a round's table of draft distributions)
+    receives the distributions instead of a new tensor."""
     import torch
     R, _, d = f_top.shape
     V = w_head.shape[0]
     dev = f_top.device
     logits = torch.empty((R, 2, V), dtype=torch.float32, device=dev)
-    probs = torch.empty((R, 2, V), dtype=torch.float32, device=dev) if want_probs else None
+    if out_probs is not None:
+        if tuple(out_probs.shape) != (R, 2, V):
+            raise ValueError("out_probs must be [R, 2, V]")
+        probs = out_probs
+    else:
+        probs = torch.empty((R, 2, V), dtype=torch.float32, device=dev) if want_probs else None
     tk = torch.empty((R, 2, int(top_k)), dtype=torch.int32, device=dev)
     tp = torch.empty((R, 2, int(top_k)), dtype=torch.float32, device=dev)
     need = draft_heads_workspace(R, d, V)

@@ -199,7 +199,10 @@ def test_parallel_tail_matches_the_oracle(B, k, k1, k2, width, max_nodes):
 
 def test_example_round_runs_and_is_consistent():
     """The example that strings all calls of a round together (draft passes, tree, verification, acceptance,
-    commit): the tree it builds is valid, the accepted path follows tree edges, lengths advance by accept_len."""
+    commit): the tree it builds is valid, the accepted path follows tree edges, lengths advance by accept_len.
+    The draft layer's attention gets the partial draft tree (Eq. 1, Section 3.1.1): its slot parents are the
+    growing tree's own edges, and its output is the oracle's tree attention over the draft cache and those slots."""
+    from oracle import tree_verify_attention as oracle_attention
     from paper_2502_06282_amd import example_round
     r = example_round.run(batch=2, seed=1, verbose=False)
     par = r["parent"].cpu().numpy()
@@ -213,6 +216,50 @@ def test_example_round_runs_and_is_consistent():
         assert int(r["prefix_len"][b]) == 256 + int(alen[b])
         assert 0 <= int(r["bonus"][b]) < 8000
     assert all(torch.isfinite(o.float()).all() for o in r["outs"])
+    # the partial tree of the draft passes
+    rd = r["round"]
+    dpar, node = r["draft_parent"].cpu().numpy(), r["draft_slot_node"].cpu().numpy()
+    st_parent = rd.state.parent.cpu().numpy()
+    t_all = dpar.shape[1]
+    assert t_all == rd.t_max == 1 + 4 * 3 and node.shape == dpar.shape
+    for b in range(2):
+        assert jk.validate_tree(dpar[b]) == 0 and dpar[b, 0] == -1 and node[b, 0] == -1
+        assert (dpar[b, 1:] >= 0).all(), "every expanded node descends from the last committed token's slot"
+        for s_ in range(1, t_all):
+            assert st_parent[b, node[b, s_]] == node[b, dpar[b, s_]]
+        assert len(set(node[b, 1:].tolist())) == t_all - 1
+    assert (dpar[:, 5:].max(axis=1) >= 1).all(), "later passes must hang below earlier passes' nodes, not only the root"
+    f64 = lambda t: t.float().cpu().numpy().astype(np.float64)
+    ref = oracle_attention(f64(rd.q_acc), f64(rd.dk_cache), f64(rd.dv_cache), f64(rd.k_acc), f64(rd.v_acc), dpar, [256, 256])
+    got = f64(rd.o_acc)
+    # (slots of the last pass hold that pass's output; earlier slots were recomputed by every later pass with the
+    # same inputs, so all of them must agree with the oracle)
+    assert np.abs(got - ref).max() <= 2e-2 * np.abs(ref).max()
+
+
+def test_example_round_phases_replay_as_graphs():
+    """The three phases captured as HIP graphs: every replay of the round gives the eager round's results."""
+    from paper_2502_06282_amd import example_round
+    rd = example_round.Round(seed=3, **example_round.SHAPES["small"])
+    eager = {k: v.clone() for k, v in rd.run().items() if k in ("tokens", "parent", "path", "accept_len", "bonus", "prefix_len")}
+    outs = [o.clone() for o in rd.result["outs"]]
+    torch.cuda.synchronize()
+    graphs = rd.capture()
+    replayed = dict(rd.result)         # the tensors the graphs write (an eager round makes new ones)
+    for _ in range(3):
+        for t_ in replayed["outs"]:
+            t_.zero_()
+        for name in ("draft", "verify", "refine"):
+            graphs[name].replay()
+        torch.cuda.synchronize()
+        for k, v in eager.items():
+            assert torch.equal(replayed[k], v), k
+        for a, b in zip(outs, replayed["outs"]):
+            assert torch.equal(a, b)
+        rd.run()                       # eager work between replays
+        torch.cuda.synchronize()
+    t = rd.time_phases(reps=3)
+    assert t["round_us"] > 0 and t["draft_us"] > 0 and t["verify_us"] > 0 and t["refine_us"] > 0
 
 
 def test_acceptance_through_the_row_table_equals_the_dense_call():
