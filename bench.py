@@ -354,7 +354,7 @@ def main():
                           "it; warm_cache: the same layer's call 16 times per replay, its K/V resident in the "
                           "Infinity Cache - not an HBM figure"}
 
-    probe = commit = deep = None
+    probe = commit = deep = acc_b2b = None
     if not args.no_extras:
         # ceiling for one layer's K/V on this machine: a kernel that only streams as many bytes as one
         # layer's K and V prefix (16.8 MB), from its own ring of buffers larger than the Infinity Cache
@@ -438,6 +438,18 @@ def main():
         commit = {"us_per_call": round(commit_us, 3), "rows_per_sequence": n_commit, "bytes_per_call": commit_bytes,
                   "layers": args.layers,
                   "note": "one jk_commit_path_layers call for all layers after the step (not in ms_per_step)"}
+        # the acceptance call eight times in one graph: what a call costs when it sits among other launches
+        # of a round's graph (the step's figure is one call per graph replay and carries the replay's own
+        # launch latency)
+        def acc8():
+            for _ in range(8):
+                acc_call.launch()
+        acc8(); torch.cuda.synchronize()
+        g_acc8 = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g_acc8, stream=torch.cuda.Stream()):
+            acc8()
+        g_acc8.replay(); torch.cuda.synchronize()
+        acc_b2b = sorted(timed_us(g_acc8.replay, 5, 8))[2]
         if mode == jk.JK_SAMPLE:
             # a walk that goes deep: draft distributions close to the target's (0.97 softmax(parent row) + 0.03 q)
             # and every first child carrying its parent row's likeliest token; the timed step above uses the
@@ -635,7 +647,9 @@ def main():
     rows = cfg.batch * (cfg.n_tree + 1)
     dense = rows * cfg.vocab * 4 + (cfg.batch * cfg.n_tree * cfg.vocab * 4 if mode == jk.JK_SAMPLE else 0)
     touched = dense if mode == jk.JK_GREEDY else (cpu or {}).get("accept_walk", {}).get("bytes_touched_by_the_walk")
-    accept = {"us_per_call": round(t_acc_ms * 1e3, 2), "nodes_per_s": round(cfg.batch * cfg.n_tree / acc_s, 1),
+    accept = {"us_per_call": round(t_acc_ms * 1e3, 2),
+              "us_per_call_eight_in_one_graph_median_of_5": None if acc_b2b is None else round(acc_b2b, 2),
+              "nodes_per_s": round(cfg.batch * cfg.n_tree / acc_s, 1),
               "accept_len": [int(v) for v in res[1].cpu().tolist()], "mode": cfg.mode,
               "dense_bytes": dense, "dense_bound_us": round(dense / (HBM_PEAK_GBPS * 1e9) * 1e6, 2),
               "bytes_touched": touched,

@@ -134,18 +134,19 @@ bool make_attn_plan(const jk_attn_desc& d, int max_prefix_len, bool fused_allowe
         // half a round), the 2x2 arrangement whole rounds
         double rounds;
         if (wn == 1) {
-          // (the kernel's own dealing: pairs of full prefix tiles evenly, the tail - two pairs a tile -
-          // with the last split)
-          const long long P = (max_prefix_len / kTileKeys) / 2, tail = n_tiles - 2 * P;
+          // (the kernel's own dealing: full prefix tiles evenly, a lone last tile a little over half a
+          // pair; the tail - two full tiles a tile - with the last split)
+          const long long F = max_prefix_len / kTileKeys, tail = n_tiles - F;
+          auto pairs_of = [](long long tiles) { return 0.5 * (double)(tiles / 2 * 2) + ((tiles & 1) ? 0.55 : 0.0); };
           if (s == 1) {
-            rounds = (double)(P + 2 * tail);
+            rounds = pairs_of(F) + 1.07 * (double)tail;
           } else {
-            const long long per = (P + 2 * tail + s - 1) / s;
-            long long p_last = per - 2 * tail;
-            p_last = p_last < 0 ? 0 : (p_last > P ? P : p_last);
-            const long long rest = P - p_last, most = (rest + s - 2) / (s - 1);
-            const long long last = p_last + 2 * tail;
-            rounds = (double)(most > last ? most : last);
+            const long long per = (F + 2 * tail + s - 1) / s;
+            long long f_last = per - 2 * tail;
+            f_last = (f_last < 0 ? 0 : (f_last > F ? F : f_last)) & ~1LL;
+            const long long rest = F - f_last, most = (rest + s - 2) / (s - 1);
+            const double last = pairs_of(f_last) + 1.07 * (double)tail;
+            rounds = pairs_of(most) > last ? pairs_of(most) : last;
           }
         } else {
           rounds = (double)(((n_tiles + wn * kt - 1) / (wn * kt) + s - 1) / s);

@@ -1004,26 +1004,28 @@ __global__ __launch_bounds__((Plan<D, WM, WN, KT, PAGED>::THREADS), (Plan<D, WM,
     ts.t_end = re * TPR < nt ? re * TPR : nt;
     if (KT == 2 && WN == 1) {
       // One wave column taking tile pairs.  Everybody waits for the slowest split (the merge needs all
-      // partials), so the shares are dealt in what the loop is fast at: whole pairs of full prefix
-      // tiles, evenly.  What is left - an odd full tile, the ragged tile, the masked tree tiles, all of
-      // them on slower paths - goes to the last split, priced at two pairs a tile, and that split
-      // gets correspondingly fewer pairs (none at all if the tail is worth a whole share: the host
-      // may add a split for it, whose workgroups are short and share a CU with a regular one).
-      const int P = (len / kTileKeys) >> 1;  // pairs of full prefix tiles
-      const int tail = nt - 2 * P;
+      // partials), so the shares are dealt in tiles of what the loop is fast at: full prefix tiles,
+      // evenly (a split with an odd number ends on a lone tile, which costs about half a pair).  What
+      // is left - the ragged tile, the masked tree tiles, all of them on the slower general path - goes
+      // to the last split, priced at two full tiles a tile (measured: two tree tiles 2.8 us, a pair of
+      // full tiles 1.31), and that split gets correspondingly fewer full tiles (none at all if the tail
+      // is worth a whole share: the host may add a split for it, whose workgroups are short and share
+      // a CU with a regular one).
+      const int F = len / kTileKeys;  // full prefix tiles
+      const int tail = nt - F;
       int tb = 0, te = nt;
       if (splits > 1) {
-        const int per = div_mg(P + 2 * tail + splits - 1, p.mg_splits);  // ceil((P + 2 tail) / splits)
-        int p_last = per - 2 * tail;
-        p_last = p_last < 0 ? 0 : (p_last > P ? P : p_last);
-        const int rest = P - p_last;  // pairs of the other splits
-        const int base_p = div_mg(rest, p.mg_splits_m1), rem_p = rest - base_p * (splits - 1);
+        const int per = div_mg(F + 2 * tail + splits - 1, p.mg_splits);  // ceil((F + 2 tail) / splits)
+        int f_last = per - 2 * tail;
+        f_last = f_last < 0 ? 0 : (f_last > F ? F : f_last);
+        f_last &= ~1;  // (whole pairs: the general path takes the tail two tiles at a time, and a full tile must not split one of its rounds)
+        const int rest = F - f_last;  // full tiles of the other splits
+        const int base_t = div_mg(rest, p.mg_splits_m1), rem_t = rest - base_t * (splits - 1);
         if (split == splits - 1) {
-          tb = 2 * rest;
+          tb = rest;
         } else {
-          const int pb = split * base_p + (split < rem_p ? split : rem_p);
-          tb = 2 * pb;
-          te = tb + 2 * (base_p + (split < rem_p ? 1 : 0));
+          tb = split * base_t + (split < rem_t ? split : rem_t);
+          te = tb + base_t + (split < rem_t ? 1 : 0);
         }
       }
       ts.t_begin = tb;
