@@ -11,7 +11,7 @@
 //                          both operands are staged HBM/L2 -> LDS in swizzled 64-byte row segments
 //                          and read from there in MFMA layout.  Batched over experts and split
 //                          along k where a projection alone would not fill the chip.
-//   row_parts_kernel, row_merge_kernel, row_probs_kernel   per logits row: maximum, normaliser,
+//   row_parts_kernel, row_finish_kernel   per logits row: maximum, normaliser,
 //                          top-k by value (ties to the lower token id), probabilities.
 //   router_kernel, gated_act_kernel, select_kernel   the draft layer's router (Eq. 2, 5) and what
 //                          surrounds the experts' three projections (Eq. 3).
@@ -327,9 +327,9 @@ hipError_t launch_gemm(const GemmParams& p, hipStream_t stream) {
 // A row (a vocabulary of 10^5 entries) is cut into parts of at most 8 192 entries so that the
 // work spreads over all CUs:
 //   row_parts_kernel   per (row, part): maximum, sum of exp((x - max) / T), the part's k best
-//   row_merge_kernel   per row: the row's maximum and normaliser from the parts' pairs, the k
-//                      best of the parts' candidates, their probabilities
-//   row_probs_kernel   per (row, part): q = exp((x - max) / T) / Z      (skipped if not asked for)
+//   row_finish_kernel  per (row, part): the row's maximum and normaliser from the parts' pairs (every
+//                      workgroup for itself), q = exp((x - max) / T) / Z of the part (if asked for);
+//                      a row's first workgroup: the k best of the parts' candidates, their probabilities
 constexpr int kPartThreads = 256;
 constexpr int kPartPerThread = 32;                             // entries a thread holds in registers
 constexpr int kPartMax = kPartThreads * kPartPerThread;        // 8 192
@@ -542,15 +542,16 @@ __global__ __launch_bounds__(kPartThreads) void row_parts_kernel(SoftParams p) {
   }
 }
 
-// one workgroup of four waves per row; every wave reduces the parts' (max, sum) pairs for itself
-__global__ __launch_bounds__(256) void row_merge_kernel(SoftParams p) {
-  const int tid = threadIdx.x, lane = tid & 63, row = blockIdx.x, K = p.k, P = p.parts;
+// The row's maximum and 1 / normaliser from the parts' (max, sum) pairs: every wave of every workgroup that
+// needs them reduces the pairs for itself, the same operations in the same order everywhere.
+__device__ __forceinline__ void row_max_and_norm(const SoftParams& p, int row, float& m_use, float& inv_z) {
+  const int lane = threadIdx.x & 63, P = p.parts;
   const float* ms = p.part_ms + (long long)row * P * 2;
   float m = -INFINITY;
   for (int i = lane; i < P; i += 64) m = fmaxf(m, ms[2 * i]);
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
-  const float m_use = m > -INFINITY ? m : 0.f;
+  m_use = m > -INFINITY ? m : 0.f;
   double z = 0.0;
   for (int i = lane; i < P; i += 64) {
     const float mp = ms[2 * i];
@@ -558,11 +559,12 @@ __global__ __launch_bounds__(256) void row_merge_kernel(SoftParams p) {
   }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) z += __shfl_xor(z, o);
-  const float inv_z = (float)(1.0 / z);
-  if (tid == 0) {
-    p.row_mz[2 * row] = m_use;
-    p.row_mz[2 * row + 1] = inv_z;
-  }
+  inv_z = (float)(1.0 / z);
+}
+
+// the k best of the parts' candidates and their probabilities (one workgroup of four waves per row)
+__device__ __forceinline__ void row_top_k(const SoftParams& p, int row, float m_use, float inv_z) {
+  const int tid = threadIdx.x, lane = tid & 63, K = p.k, P = p.parts;
   const float* cv = p.part_cv + (long long)row * P * K;
   const int* ci = p.part_ci + (long long)row * P * K;
   const int n = P * K;
@@ -620,29 +622,37 @@ __global__ __launch_bounds__(256) void row_merge_kernel(SoftParams p) {
   }
 }
 
-__global__ __launch_bounds__(kPartThreads) void row_probs_kernel(SoftParams p) {
+// One workgroup per (row, part): q = exp((x - max) / T) / Z for the part (if the distributions are asked for:
+// otherwise one workgroup per row); the workgroup of a row's first part also merges the parts' candidates
+// into the row's k best.  One launch where a merge kernel and a probabilities kernel used to follow each other.
+__global__ __launch_bounds__(kPartThreads) void row_finish_kernel(SoftParams p) {
   const int tid = threadIdx.x, V = p.vocab;
-  const int row = blockIdx.x / p.parts, part = blockIdx.x % p.parts;
-  const int lo = part * p.part_len, hi = min(V, lo + p.part_len);
-  const float* x = p.logits + (long long)row * V;
-  float* q = p.probs + (long long)row * V;
-  const float m = p.row_mz[2 * row], inv_z = p.row_mz[2 * row + 1];
-  const bool vec = (V & 3) == 0 && (reinterpret_cast<size_t>(p.logits) & 15) == 0 &&
-                   (reinterpret_cast<size_t>(p.probs) & 15) == 0;
+  const bool with_probs = p.probs != nullptr;
+  const int row = with_probs ? blockIdx.x / p.parts : blockIdx.x, part = with_probs ? blockIdx.x % p.parts : 0;
+  float m, inv_z;
+  row_max_and_norm(p, row, m, inv_z);
+  if (with_probs) {
+    const int lo = part * p.part_len, hi = min(V, lo + p.part_len);
+    const float* x = p.logits + (long long)row * V;
+    float* q = p.probs + (long long)row * V;
+    const bool vec = (V & 3) == 0 && (reinterpret_cast<size_t>(p.logits) & 15) == 0 &&
+                     (reinterpret_cast<size_t>(p.probs) & 15) == 0;
 #pragma unroll 4
-  for (int u = 0; u < kPartPerThread / 4; ++u) {
-    const int e = lo + 4 * (tid + kPartThreads * u);
-    if (vec && e + 3 < hi) {
-      const floatx4 s = *reinterpret_cast<const floatx4*>(x + e);
-      floatx4 o;
+    for (int u = 0; u < kPartPerThread / 4; ++u) {
+      const int e = lo + 4 * (tid + kPartThreads * u);
+      if (vec && e + 3 < hi) {
+        const floatx4 s = *reinterpret_cast<const floatx4*>(x + e);
+        floatx4 o;
 #pragma unroll
-      for (int c = 0; c < 4; ++c) o[c] = expf((s[c] - m) * p.inv_temp) * inv_z;
-      *reinterpret_cast<floatx4*>(q + e) = o;
-    } else {
-      for (int c = 0; c < 4; ++c)
-        if (e + c < hi) q[e + c] = expf((x[e + c] - m) * p.inv_temp) * inv_z;
+        for (int c = 0; c < 4; ++c) o[c] = expf((s[c] - m) * p.inv_temp) * inv_z;
+        *reinterpret_cast<floatx4*>(q + e) = o;
+      } else {
+        for (int c = 0; c < 4; ++c)
+          if (e + c < hi) q[e + c] = expf((x[e + c] - m) * p.inv_temp) * inv_z;
+      }
     }
   }
+  if (part == 0) row_top_k(p, row, m, inv_z);
 }
 
 // ------------------------------------------------------------------ router and experts (Eq. 2, 3, 5)
@@ -931,13 +941,8 @@ hipError_t launch_draft_heads(const DraftHeadsArgs& a, hipStream_t stream) {
   sp.inv_temp = 1.0f / a.temperature;
   hipLaunchKernelGGL(row_parts_kernel, dim3(m * rp.parts), dim3(kPartThreads), 0, stream, sp);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  hipLaunchKernelGGL(row_merge_kernel, dim3(m), dim3(256), 0, stream, sp);
-  if ((e = hipGetLastError()) != hipSuccess) return e;
-  if (a.draft_probs) {
-    hipLaunchKernelGGL(row_probs_kernel, dim3(m * rp.parts), dim3(kPartThreads), 0, stream, sp);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
-  }
-  return hipSuccess;
+  hipLaunchKernelGGL(row_finish_kernel, dim3(a.draft_probs ? m * rp.parts : m), dim3(kPartThreads), 0, stream, sp);
+  return hipGetLastError();
 }
 
 size_t moe_experts_workspace_bytes(int rows, int d_model, int d_ff, int n_experts) {
