@@ -33,8 +33,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (KiB per dispatch), each scaled by the same counter's reading
 # for a 256 MiB device copy (factors 2.00 and 1.00); source: profiles/<workload>_attention_and_acceptance.md.
 # {workload: bytes}; None for workloads that were not measured.
-MEASURED_TRAFFIC = {"c2_vicuna7b": 26704889, "c3_llama3_8b": 34407885, "c4_llama2_13b": 191883415,
-                    "c5_llama2_70b": 709455467}
+MEASURED_TRAFFIC = {"c2_vicuna7b": 26704533, "c3_llama3_8b": 34409234, "c4_llama2_13b": 191875958,
+                    "c5_llama2_70b": 707492086}
 
 
 def attn_bytes(cfg) -> int:
