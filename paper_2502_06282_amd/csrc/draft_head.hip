@@ -343,7 +343,6 @@ struct SoftParams {
   float* part_ms;       // [n_rows][parts][2]   max, sum
   float* part_cv;       // [n_rows][parts][k]   candidate values
   int* part_ci;         // [n_rows][parts][k]   candidate ids (INT_MAX: none)
-  float* row_mz;        // [n_rows][2]          max, 1 / normaliser
   int n_rows, vocab, k, parts, part_len;  // part_len: entries per part, a multiple of 4
   float inv_temp;
 };
@@ -864,7 +863,7 @@ int linear_ksplit(int m, int n, int k) {
 
 struct RowPlan {
   int parts, part_len, ksplit;
-  size_t x_bytes, ms_off, cv_off, ci_off, mz_off, part_off, total;
+  size_t x_bytes, ms_off, cv_off, ci_off, part_off, total;
 };
 
 // logits = sum of the k parts' partial products (fixed order)
@@ -886,8 +885,7 @@ RowPlan row_plan(int rows, int d_model, int vocab) {
   r.ms_off = r.x_bytes;
   r.cv_off = r.ms_off + up(m * r.parts * 2 * 4);
   r.ci_off = r.cv_off + up(m * r.parts * kMaxTopK * 4);
-  r.mz_off = r.ci_off + up(m * r.parts * kMaxTopK * 4);
-  r.part_off = r.mz_off + up(m * 2 * 4);
+  r.part_off = r.ci_off + up(m * r.parts * kMaxTopK * 4);
   // a small vocabulary gives few 512-row strips: split k until the chip is full (partials of at most 64 MB)
   r.ksplit = pick_ksplit(vocab, d_model, (int)(m_pad / 32), 1, device_cu_count());
   while (r.ksplit > 1 && (size_t)r.ksplit * m * vocab * 4 > ((size_t)64 << 20)) --r.ksplit;
@@ -936,7 +934,6 @@ hipError_t launch_draft_heads(const DraftHeadsArgs& a, hipStream_t stream) {
   sp.part_ms = reinterpret_cast<float*>(ws + rp.ms_off);
   sp.part_cv = reinterpret_cast<float*>(ws + rp.cv_off);
   sp.part_ci = reinterpret_cast<int*>(ws + rp.ci_off);
-  sp.row_mz = reinterpret_cast<float*>(ws + rp.mz_off);
   sp.n_rows = m; sp.vocab = a.vocab; sp.k = a.top_k; sp.parts = rp.parts; sp.part_len = rp.part_len;
   sp.inv_temp = 1.0f / a.temperature;
   hipLaunchKernelGGL(row_parts_kernel, dim3(m * rp.parts), dim3(kPartThreads), 0, stream, sp);
