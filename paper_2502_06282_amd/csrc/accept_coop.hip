@@ -25,7 +25,8 @@
 namespace jk {
 namespace {
 
-constexpr int kCoopThreads = 256;
+constexpr int kCoopThreads = 256;  // (512 measured 8 % faster for one tree and 60 % slower for eight: two workgroups per CU then)
+constexpr int kCoopWaves = kCoopThreads / 64;
 constexpr unsigned kDefaultSpinLimit = 1u << 12;  // polls before giving up: a few milliseconds
 
 // One workgroup's contribution to an exchange: two doubles, cut into four 32-bit halves,
@@ -77,20 +78,26 @@ __device__ __forceinline__ double block_sum(double v, double* red) {
   __syncthreads();
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
   __syncthreads();
-  return (red[0] + red[1]) + (red[2] + red[3]);
+  double s = 0.0;  // (waves in order: the same sum in every workgroup)
+#pragma unroll
+  for (int i = 0; i < kCoopWaves; i += 2) s += red[i] + red[i + 1];
+  return s;
 }
 __device__ __forceinline__ double block_max(double v, double* red) {
   for (int o = 32; o > 0; o >>= 1) v = fmax(v, __shfl_xor(v, o));
   __syncthreads();
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
   __syncthreads();
-  return fmax(fmax(red[0], red[1]), fmax(red[2], red[3]));
+  double m = red[0];
+#pragma unroll
+  for (int i = 1; i < kCoopWaves; ++i) m = fmax(m, red[i]);
+  return m;
 }
 
 __global__ __launch_bounds__(kCoopThreads) void walk_sample_coop_kernel(CoopParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   double* cur = reinterpret_cast<double*>(smem);   // [slice] current distribution of my slice
-  __shared__ double red[4];
+  __shared__ double red[kCoopWaves];
   __shared__ double xa[64], xb[64];                // the W partials of an exchange
   __shared__ unsigned xh[256];                     // their 32-bit halves as they arrive
   __shared__ int par_s[JK_MAX_TREE];
@@ -382,13 +389,18 @@ __global__ __launch_bounds__(kCoopThreads) void walk_sample_coop_kernel(CoopPara
     if ((tid & 63) == 63) red[tid >> 6] = incl;
     int lp = last_pos;
     for (int o = 32; o > 0; o >>= 1) lp = max(lp, __shfl_xor(lp, o));
-    __shared__ int s_lp[4];
+    __shared__ int s_lp[kCoopWaves];
     if ((tid & 63) == 0) s_lp[tid >> 6] = lp;
     __syncthreads();
     double woff = 0.0;
     for (int i = 0; i < (tid >> 6); ++i) woff += red[i];
-    const double t_w = ((red[0] + red[1]) + red[2]) + red[3];
-    const int lp_w = max(max(s_lp[0], s_lp[1]), max(s_lp[2], s_lp[3]));
+    double t_w = 0.0;  // (in wave order, like the offsets: the last wave's interval ends exactly at the total)
+    int lp_w = -1;
+#pragma unroll
+    for (int i = 0; i < kCoopWaves; ++i) {
+      t_w += red[i];
+      lp_w = max(lp_w, s_lp[i]);
+    }
     exchange(t_w, (double)lp_w, 0.0);
     if (!s_fail) {
       double before = 0.0, total = 0.0;
