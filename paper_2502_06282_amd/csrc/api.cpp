@@ -79,6 +79,8 @@ struct PlanModel {
   double share_2x2_slope = 0.75;  // 2x2 workgroups sharing a CU: time x (0.75 per workgroup + 0.25): c7 and c4 sweeps
   double cu_pull = 22.0e3;      // bytes per us one CU draws from HBM with one round in flight (32 KB / 1.3 us round trip)
   double stream = 4.0e6;        // bytes per us all CUs together: c4, 178 MB per call
+  double startup = 2.7;         // us before a workgroup's first K/V data are there (c3 time stamps: 2.6 - 2.8); with two
+                                // workgroups on a CU one's start hides under the other's loop (c7: 4 splits beat 2)
   double merge_fused_fixed = 2.0, merge_fused_per_mb = 0.1;   // merge inside the kernel: c3 time stamps, xchg probe
   double merge_kernel_fixed = 3.0, merge_kernel_per_mb = 0.28, merge_kernel_per_mb_busy = 0.4;  // second launch: c3/c2/c5 traces
 };
@@ -190,7 +192,9 @@ bool make_attn_plan(const jk_attn_desc& d, int max_prefix_len, bool fused_allowe
             : can_fuse ? km.merge_fused_fixed + km.merge_fused_per_mb * part_mb
                        : km.merge_kernel_fixed + (per_cu > 1.0 && wn == 1 ? km.merge_kernel_per_mb_busy : km.merge_kernel_per_mb) * part_mb;
         // (near ties go to the count that gives every CU a workgroup: 2 % for an idle CU)
-        const double cost = ((loop_us > stream_us ? loop_us : stream_us) + partial_us) * (active < slots ? 1.02 : 1.0);
+        // (measured for the 2x2 arrangement only; two 4x1 workgroups on a CU get in each other's way from the start: c3, 20 - 32 splits)
+        const double start_us = km.startup * (wn == 2 && per_cu >= 1.5 ? 0.5 : 1.0);
+        const double cost = ((loop_us > stream_us ? loop_us : stream_us) + partial_us + start_us) * (active < slots ? 1.02 : 1.0);
         if (!have || cost < best_cost) {
           have = true;
           best_cost = cost;
