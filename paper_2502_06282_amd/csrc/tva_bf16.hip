@@ -1041,12 +1041,32 @@ __global__ __launch_bounds__((Plan<D, WM, WN, KT, PAGED>::THREADS), (Plan<D, WM,
 
   set_range(p.max_prefix);
   int n_rounds = (ts.t_end - ts.t_begin + TPR - 1) / TPR;
-  // (a paged cache cannot be read ahead of the length: table entries past the sequence's pages may hold anything)
-  const bool spec_any = !PAGED && n_rounds > 0 && (ts.t_begin + TPR) * kTileKeys <= p.max_prefix;  // same for every wave
+  // Paged cache: page ids of the prefix tiles this split will fetch (whole rounds), clamped into the pool, so
+  // that a transfer stays inside the pool whatever the table holds: the first rounds can then be asked for on
+  // the same assumption as with a contiguous cache (entries past a sequence's pages may hold anything; if the
+  // length turns out shorter, the list is made again).  An id outside the pool is reported once the list is final.
+  bool bad_page = false;
+  auto fill_pages = [&]() {
+    bad_page = false;
+    const int te = min(ts.n_ptiles, ts.t_begin + n_rounds * TPR);
+    if (te > ts.t_begin) {
+      ts.pg_first = div_mg(ts.t_begin, p.mg_tpp);
+      const int n_pg = div_mg(te - 1, p.mg_tpp) - ts.pg_first + 1;  // <= kMaxPagesPerSplit by the host's plan
+      for (int i = tid; i < n_pg && i < kMaxPagesPerSplit; i += THREADS) {
+        const int pi = ts.pg_first + i;
+        const int id = pi < p.max_blocks ? p.block_table[(long long)b * p.max_blocks + pi] : 0;
+        bad_page = bad_page || id < 0 || id >= p.n_pages;
+        pg_s[i] = id < 0 ? 0 : (id >= p.n_pages ? p.n_pages - 1 : id);
+      }
+    }
+    __syncthreads();
+  };
+  if (PAGED) fill_pages();
+  const bool spec_any = n_rounds > 0 && (ts.t_begin + TPR) * kTileKeys <= p.max_prefix;  // same for every wave
   int n_spec = 0;  // rounds already issued, all of them full prefix tiles under the assumption
 #pragma unroll
   for (int r = 0; r < NR - 1; ++r)
-    if (!PAGED && n_spec == r && r < n_rounds && (ts.t_begin + (r + 1) * TPR) * kTileKeys <= p.max_prefix) {
+    if (n_spec == r && r < n_rounds && (ts.t_begin + (r + 1) * TPR) * kTileKeys <= p.max_prefix) {
       dma_round<D, NW, TPR, PAGED>(r, ts, lc, ring_addr + r * STAGE_BYTES);
       n_spec = r + 1;
     }
@@ -1063,23 +1083,10 @@ __global__ __launch_bounds__((Plan<D, WM, WN, KT, PAGED>::THREADS), (Plan<D, WM,
     n_spec = 0;
     set_range(L);
     n_rounds = (ts.t_end - ts.t_begin + TPR - 1) / TPR;
+    if (PAGED) fill_pages();
   }
   const bool has_tree = ts.t_end > ts.n_ptiles;
-  if (PAGED) {
-    // page ids of the prefix tiles this split will fetch (whole rounds), clamped into the pool
-    const int te = min(ts.n_ptiles, ts.t_begin + n_rounds * TPR);
-    if (te > ts.t_begin) {
-      ts.pg_first = div_mg(ts.t_begin, p.mg_tpp);
-      const int n_pg = div_mg(te - 1, p.mg_tpp) - ts.pg_first + 1;  // <= kMaxPagesPerSplit by the host's plan
-      for (int i = tid; i < n_pg && i < kMaxPagesPerSplit; i += THREADS) {
-        const int pi = ts.pg_first + i;
-        int id = pi < p.max_blocks ? p.block_table[(long long)b * p.max_blocks + pi] : 0;
-        if (id < 0 || id >= p.n_pages) __hip_atomic_fetch_or(p.err, kDevErrBadPage, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        pg_s[i] = id < 0 ? 0 : (id >= p.n_pages ? p.n_pages - 1 : id);
-      }
-    }
-    __syncthreads();
-  }
+  if (PAGED && bad_page) __hip_atomic_fetch_or(p.err, kDevErrBadPage, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
   for (int r = 0; r < NR - 1; ++r)
     if (r >= n_spec && r < n_rounds) dma_round<D, NW, TPR, PAGED>(r, ts, lc, ring_addr + r * STAGE_BYTES);
@@ -1190,6 +1197,7 @@ __global__ __launch_bounds__((Plan<D, WM, WN, KT, PAGED>::THREADS), (Plan<D, WM,
     RoundPieces<D, NW, TPR> next;
     const int t_next = ts.t_begin + (r + NR - 1) * TPR;
     const bool refill = r + NR - 1 < n_rounds;
+    // (paged caches refill in one go: with a base pointer per tile the interleaved refill measured slower)
     const bool spread = kSpread > 0 && !PAGED && WN == 1 && refill && pair && (t_next + TPR) * kTileKeys <= L;
     next.tile_elems = (long long)kTileKeys * ts.kc_sl;
     next.base = lc.cache + (long long)t_next * next.tile_elems;
