@@ -141,8 +141,11 @@ jk_status jk_tree_verify_attention(const jk_attn_desc* desc, const void* q, cons
  * strides inside a page (kc_stride_b is ignored) and page_stride elements between
  * pages; token t of sequence b lives in page block_table[b * max_blocks + t /
  * page_size] at slot t % page_size.  Entries for tokens below prefix_len[b] must
- * be valid page ids; others are never read (ids outside [0, n_pages) are clamped
- * into the pool rather than followed).  The paper does not discuss cache layout:
+ * be valid page ids; the other entries of a row (all max_blocks of them must be
+ * readable) may hold anything: they may be read, and pages they name fetched
+ * ahead of the length, but nothing of that reaches a result (ids outside
+ * [0, n_pages) are clamped into the pool rather than followed, and reported in
+ * the device error word only where a result depends on them).  The paper does not discuss cache layout:
  * this is a library convention for serving stacks. */
 typedef struct {
   const int32_t* block_table; /* device int32 [batch, max_blocks] */
