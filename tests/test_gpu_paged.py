@@ -141,3 +141,34 @@ def test_paged_argument_errors():
     with pytest.raises(jk.JakiroError):                    # the table cannot hold max_prefix_len tokens
         jk.tree_verify_attention_paged(_dev(x["q"]), _dev(kp), _dev(vp), torch.from_numpy(table).cuda(), _dev(x["k_tree"]),
                                        _dev(x["v_tree"]), parent, pl, max_prefix_len=200)
+
+
+def test_paged_table_entries_past_a_sequences_pages_may_hold_anything():
+    """The first transfers go out on the assumption prefix_len == max_prefix_len, through whatever the table
+    holds for those pages (ids are clamped into the pool).  With one sequence much shorter than the bound and
+    wild values behind its pages, the results are those of a clean table, bit for bit, and the error word
+    stays clear: nothing past a sequence's pages reaches a result."""
+    cfg = CONFIGS["c3_llama3_8b"].with_(batch=2, prefix_len=1500, n_q_heads=8, n_kv_heads=2)
+    page = 64
+    par, x, kp, vp, table = _paged_case(cfg, page, 1500, seed=7)
+    plen = [1500, 200]
+    dirty = table.copy()
+    used = (200 + page - 1) // page
+    dirty[1, used:] = np.array([-5, 2 ** 30, -2 ** 31, 123456789] * 8, dtype=np.int32)[: dirty.shape[1] - used]
+    parent = torch.from_numpy(par).cuda()
+    pl = torch.tensor(plen, dtype=torch.int32).cuda()
+    ref = oracle_attention(**x, parent=par, prefix_len=plen)
+    for arr in ((4, 1), (2, 2)):
+        for s in (1, 3):
+            tune("attn_wm", arr[0]); tune("attn_wn", arr[1]); tune("attn_splits", s)
+            outs = []
+            for tab in (table, dirty):
+                q = _dev(x["q"])
+                need = jk.tree_verify_attention_workspace(q, _dev(x["k_cache"]), _dev(x["k_tree"]), 1500)
+                ws = torch.zeros(need, dtype=torch.uint8, device="cuda")
+                outs.append(jk.tree_verify_attention_paged(q, _dev(kp), _dev(vp), torch.from_numpy(tab).cuda(), _dev(x["k_tree"]),
+                                                           _dev(x["v_tree"]), parent, pl, max_prefix_len=1500, workspace=ws))
+                torch.cuda.synchronize()
+                assert jk.last_device_error(ws) == 0
+            assert torch.equal(outs[0], outs[1])
+            assert np.abs(outs[1].float().cpu().numpy() - ref).max() <= 2e-2
