@@ -101,3 +101,24 @@ def test_static_fill_argument_checks_are_host_only(lib):
     st = binding.TreeStateDesc(None, None, None, None, None, 64)
     assert lib.jk_tree_fill_static(ctypes.byref(st), 1, 1, 4, 0, None, None, None, None, None, None, 4, None, 0, None,
                                    None, None) == 1
+
+
+def test_attention_plans_of_the_workloads_are_host_only_and_stable(lib):
+    """jk_tree_verify_attention_plan needs no device.  Without jk_init's placement check the merge inside the kernel is
+    off, everything else is the plan the benchmarks run: this pins the planner's choices for the workload shapes (wave
+    arrangement, tile pairing, row tiles, key splits), found by forced sweeps on an MI355X, against later edits of
+    its cost table."""
+    from workloads import CONFIGS
+    want = {"c2_vicuna7b": (2, 2, 1, 1, 6), "c3_llama3_8b": (4, 1, 2, 2, 16), "c4_llama2_13b": (2, 2, 1, 1, 3),
+            "c5_llama2_70b": (4, 1, 2, 7, 4), "c6_chain_sps": (2, 2, 1, 1, 1), "c7_static_tree": (2, 2, 1, 1, 4)}
+    for name, plan in want.items():
+        c = CONFIGS[name]
+        B, T, Hq, Hkv, D, L = c.batch, c.n_tree, c.n_q_heads, c.n_kv_heads, c.head_dim, c.prefix_len
+        d = binding.AttnDesc(B, T, Hq, Hkv, D, T * Hq * D, Hq * D, D, L * Hkv * D, Hkv * D, D, T * Hkv * D, Hkv * D, D,
+                             T * Hq * D, Hq * D, D, 0.0, 0)
+        out = (ctypes.c_int32 * 6)()
+        assert lib.jk_tree_verify_attention_plan(ctypes.byref(d), L, out) == 0
+        assert tuple(out)[:5] == plan and out[5] == 0, (name, list(out))
+        # the workspace query covers the plan with and without the merge inside the kernel
+        rows = B * Hkv * plan[4] * plan[3] * 32 * plan[0]
+        assert lib.jk_tree_verify_attention_workspace(ctypes.byref(d), L) >= rows * (D * 2 + 8) * (plan[4] > 1)
