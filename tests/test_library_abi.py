@@ -111,6 +111,14 @@ def test_attention_plans_of_the_workloads_are_host_only_and_stable(lib):
     from workloads import CONFIGS
     want = {"c2_vicuna7b": (2, 2, 1, 1, 6), "c3_llama3_8b": (4, 1, 2, 2, 16), "c4_llama2_13b": (2, 2, 1, 1, 3),
             "c5_llama2_70b": (4, 1, 2, 7, 4), "c6_chain_sps": (2, 2, 1, 1, 1), "c7_static_tree": (2, 2, 1, 1, 4)}
+    assert lib.jk_set_tuning(b"attn_fused", 0) == 0   # (as on a device whose placement has not been checked)
+    try:
+        _check_plans(lib, want, CONFIGS)
+    finally:
+        lib.jk_set_tuning(b"attn_fused", -1)
+
+
+def _check_plans(lib, want, CONFIGS):
     for name, plan in want.items():
         c = CONFIGS[name]
         B, T, Hq, Hkv, D, L = c.batch, c.n_tree, c.n_q_heads, c.n_kv_heads, c.head_dim, c.prefix_len
