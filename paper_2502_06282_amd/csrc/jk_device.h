@@ -47,7 +47,9 @@ __device__ __forceinline__ void wait_vm() {
 typedef unsigned int store_u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int store_u32x2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ void store_through(void* dst, store_u32x4 v) {
-  asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" ::"v"(dst), "v"(v) : "memory");
+  // (the wait state behind it: a vector instruction that overwrites the data registers of a store of more than
+  // 64 bits must not be the very next one, and the compiler does not look for that hazard behind an asm statement)
+  asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1\n\ts_nop 0" ::"v"(dst), "v"(v) : "memory");
 }
 __device__ __forceinline__ void store_through(void* dst, store_u32x2 v) {
   asm volatile("global_store_dwordx2 %0, %1, off sc0 sc1" ::"v"(dst), "v"(v) : "memory");
