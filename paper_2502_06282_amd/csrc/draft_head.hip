@@ -432,15 +432,10 @@ __global__ __launch_bounds__(kPartThreads) void row_parts_kernel(SoftParams p) {
       for (int c = 0; c < 4; ++c) val[4 * u + c] = e + c < hi ? x[e + c] : -INFINITY;
     }
   }
-  // the thread's own maximum (first of equal values: lowest id)
+  // the thread's own maximum
   float tv = -INFINITY;
-  int ti = INT_MAX;
 #pragma unroll
-  for (int i = 0; i < kPartPerThread; ++i)
-    if (val[i] > tv) {
-      tv = val[i];
-      ti = id_of(i);
-    }
+  for (int i = 0; i < kPartPerThread; ++i) tv = fmaxf(tv, val[i]);
   float m = tv;
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));

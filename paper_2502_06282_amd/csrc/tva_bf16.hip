@@ -208,7 +208,6 @@ __device__ __forceinline__ void lane_chunks(LaneChunks<D, NW>& lc, int wave, int
                                             const uint16_t* kc, const uint16_t* vc, const uint16_t* kt,
                                             const uint16_t* vt) {
   using G_ = Geo<D>;
-  constexpr int RPB = 64 / G_::CPR;
   constexpr int N = LaneChunks<D, NW>::N;
   const int is_v = (wave * N) / G_::NB;
   lc.cache = uniform_ptr(is_v ? vc : kc);
