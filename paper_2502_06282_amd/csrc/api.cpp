@@ -182,8 +182,8 @@ bool make_attn_plan(const jk_attn_desc& d, int max_prefix_len, bool fused_allowe
           for (long long u = 0; u < units && can_fuse; ++u)
             can_fuse = (u * per_unit) / per_xcd == ((u + 1) * per_unit - 1) / per_xcd;
         }
-        // Partials (bf16): merged inside the kernel they stay in L2 (written once, read once, about
-        // 2 us of exchange latency whatever their size plus 0.1 us per MB); with the stand-alone merge
+        // Partials (bf16): merged inside the kernel they are written once and read once through the XCD's L2
+        // (about 2 us of exchange latency whatever their size plus 0.1 us per MB); with the stand-alone merge
         // kernel they cost a second launch (about 3 us) and 0.28 us per MB when the grid is one turn
         // of workgroups and they are stored through to memory, 0.4 when they take the ordinary route
         const double part_mb = 1.0e-6 * (double)units * s * pl->m_rows * d.head_dim * 2.0;
