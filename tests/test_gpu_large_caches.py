@@ -122,3 +122,30 @@ def test_cache_views_with_a_batch_stride_beyond_4_gib():
     torch.cuda.synchronize()
     assert torch.equal(pl_far, pl_near) and pl_far.tolist() == [L + 2, 255]
     assert torch.equal(_bits(kview), _bits(kc)) and torch.equal(_bits(vview), _bits(vc))
+
+
+@pytest.mark.parametrize("fused", [-1, 0], ids=["planned", "merge_kernel"])
+def test_bf16_million_token_prefix(fused):
+    """One sequence with a prefix of 2^20 + 17 tokens (a ragged last tile, more tiles than one split may hold, so the
+    plan must split at least 33 ways), every element against the oracle; then the same call with a device-side
+    length 70 001 tokens short of the bound (the first transfers were asked for on the bound: everything is redone)."""
+    tune("attn_fused", fused)
+    L = (1 << 20) + 17
+    cfg = CONFIGS["c3_llama3_8b"].with_(batch=1, prefix_len=L, n_q_heads=2, n_kv_heads=1, n_tree=40)
+    par = tree_for_config(cfg, seed=23)
+    x = {k: round_to_bf16(v) for k, v in attention_inputs(cfg, seed=23, prefix_len=L, scale_mult=np.sqrt(128.0)).items()}
+    # a few keys that single rows care about, so that outputs are not all averages over a million values
+    for i, (t, h, pos) in enumerate([(0, 0, 5), (7, 1, L - 1), (20, 0, 777777), (39, 1, 1 << 19)]):
+        x["k_cache"][0, pos, 0] = round_to_bf16(6.0 * x["q"][0, t, h])
+    parent = torch.from_numpy(par).cuda()
+    d = {k: _dev(v) for k, v in x.items()}
+    plan = jk.tree_verify_attention_plan(d["q"], d["k_cache"], d["k_tree"], L)
+    assert plan["splits"] >= 33
+    for plen in ([L], [L - 70001]):
+        pl = torch.tensor(plen, dtype=torch.int32).cuda()
+        got = jk.tree_verify_attention(d["q"], d["k_cache"], d["v_cache"], d["k_tree"], d["v_tree"], parent, pl, max_prefix_len=L)
+        torch.cuda.synchronize()
+        ref = oracle_attention(**x, parent=par, prefix_len=plen)
+        err = np.abs(got.float().cpu().numpy() - ref)
+        assert np.isfinite(err).all()
+        assert err.max() <= 2e-2 and err.max() <= 1.5e-2 * np.abs(ref).max(), (plen, err.max(), np.abs(ref).max())

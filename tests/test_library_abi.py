@@ -130,3 +130,70 @@ def _check_plans(lib, want, CONFIGS):
         # the workspace query covers the plan with and without the merge inside the kernel
         rows = B * Hkv * plan[4] * plan[3] * 32 * plan[0]
         assert lib.jk_tree_verify_attention_workspace(ctypes.byref(d), L) >= rows * (D * 2 + 8) * (plan[4] > 1)
+
+
+def _desc(B, T, Hq, Hkv, D, L, dtype=0):
+    return binding.AttnDesc(B, T, Hq, Hkv, D, T * Hq * D, Hq * D, D, max(L, 1) * Hkv * D, Hkv * D, D, T * Hkv * D, Hkv * D, D,
+                            T * Hq * D, Hq * D, D, 0.0, dtype)
+
+
+def test_attention_plans_of_random_shapes_keep_their_invariants(lib):
+    """Host-only: whatever the shape, a plan is one of the two wave arrangements with the row tiles that cover the
+    T * G query rows, a split count within the library's limits (at most 64, at most 1024 tiles per split), and the
+    workspace query covers its partials; forced arrangements and split counts are honoured; the fp32 path splits
+    every 1024 keys.  Nothing here launches."""
+    import random
+    rng = random.Random(5)
+    header = 32768
+    try:
+        for case in range(400):
+            D = rng.choice([64, 128])
+            Hkv = rng.choice([1, 2, 4, 8, 32, 40])
+            G = rng.choice([1, 1, 2, 4, 8])
+            B = rng.choice([1, 1, 2, 4, 8, 16, 64])
+            T = rng.randint(1, 128)
+            L = rng.choice([0, 1, 31, 32, 33, rng.randint(0, 5000), rng.randint(0, 200000), 1 << 20])
+            force_arr = rng.choice([None, None, (4, 1), (2, 2)])
+            force_s = rng.choice([0, 0, 0, 1, 2, 7, 16, 64])
+            lib.jk_set_tuning(b"attn_fused", 0)
+            lib.jk_set_tuning(b"attn_wm", force_arr[0] if force_arr else 0)
+            lib.jk_set_tuning(b"attn_wn", force_arr[1] if force_arr else 0)
+            lib.jk_set_tuning(b"attn_splits", force_s)
+            d = _desc(B, T, Hkv * G, Hkv, D, L)
+            out = (ctypes.c_int32 * 6)()
+            what = (case, B, T, Hkv, G, D, L, force_arr, force_s)
+            assert lib.jk_tree_verify_attention_plan(ctypes.byref(d), L, out) == 0, what
+            wm, wn, kt, tiles, splits, fused = tuple(out)
+            assert (wm, wn, kt) in ((4, 1, 2), (2, 2, 1)), what
+            if force_arr:
+                assert (wm, wn) == force_arr, what
+            M = T * G
+            assert tiles == (M + 32 * wm - 1) // (32 * wm), what
+            n_tiles = (L + 31) // 32 + (T + 31) // 32
+            s_min = (n_tiles + 1023) // 1024
+            assert max(1, s_min) <= splits <= 64, what
+            if force_s:
+                assert splits == max(force_s, s_min), what
+            else:
+                assert splits <= max(1, s_min, n_tiles // (2 * wn * kt)), what   # at least two rounds per split
+            assert fused == 0, what
+            need = header + (B * Hkv * splits * tiles * 32 * wm * (D * 2 + 8) if splits > 1 else 0)
+            assert lib.jk_tree_verify_attention_workspace(ctypes.byref(d), L) >= need, what
+        for k in (b"attn_wm", b"attn_wn", b"attn_splits"):
+            lib.jk_set_tuning(k, 0)
+        # fp32 path: one workgroup per query row and 1024-key split; 64 splits at most
+        for L, T in ((0, 1), (1000, 24), (1024, 1), (5000, 60), (65536 - 60, 60)):
+            d = _desc(2, T, 8, 4, 64, L, dtype=1)
+            out = (ctypes.c_int32 * 6)()
+            assert lib.jk_tree_verify_attention_plan(ctypes.byref(d), L, out) == 0
+            assert tuple(out) == (1, 1, 1, T * 2, (L + T + 1023) // 1024, 0)
+        d = _desc(2, 60, 8, 4, 64, 65536, dtype=1)
+        assert lib.jk_tree_verify_attention_plan(ctypes.byref(d), 65536, (ctypes.c_int32 * 6)()) != 0
+        assert lib.jk_tree_verify_attention_workspace(ctypes.byref(d), 65536) == 0
+        # bounds of the prefix length
+        d = _desc(1, 8, 8, 8, 128, 64)
+        assert lib.jk_tree_verify_attention_plan(ctypes.byref(d), -1, (ctypes.c_int32 * 6)()) != 0
+        assert lib.jk_tree_verify_attention_plan(ctypes.byref(d), (1 << 24) + 1, (ctypes.c_int32 * 6)()) != 0
+    finally:
+        for k, v in ((b"attn_wm", 0), (b"attn_wn", 0), (b"attn_splits", 0), (b"attn_fused", -1)):
+            lib.jk_set_tuning(k, v)
