@@ -327,3 +327,31 @@ def test_sample_calls_of_different_batch_sizes_share_a_workspace():
                 assert int(alen[b]) == r.accept_len and int(bonus[b]) == r.bonus_token, (i, batch, b)
                 assert path[b, : r.accept_len].cpu().tolist() == r.path
     assert jk.last_device_error(ws) == 0
+
+
+@pytest.mark.parametrize("B,V", [(20, 5001), (64, 1000), (100, 4097), (300, 257), (300, 4097), (600, 1000)])
+def test_sample_large_batches(B, V):
+    """The workgroups that share a tree get fewer as the batch grows (two per CU over the batch, at most 64): 25, 8, 5
+    and 1 of them here; a slice of more than 4096 tokens (300 trees of 4097) and more trees than resident workgroups
+    (600) go to the one-workgroup walk."""
+    cfg = CONFIGS["c3_llama3_8b"].with_(vocab=V, batch=B, n_tree=12)
+    par = tree_for_config(cfg, seed=B)
+    a = accept_inputs(cfg, par, seed=B + V)
+    skipped = _compare(a, par, "sample")
+    assert skipped <= B // 20
+
+
+def test_greedy_at_the_row_limit():
+    """batch * (n_tree + 1) = 65 532 logits rows, just inside the limit of 65 535; one tree more is refused."""
+    cfg = CONFIGS["c2_vicuna7b"].with_(vocab=300, batch=508, n_tree=128)
+    par = tree_for_config(cfg, seed=1)
+    a = accept_inputs(cfg, par, seed=1)
+    _compare(a, par, "greedy")
+    _, alen, _ = _gpu_accept(a, par, "greedy")
+    assert alen.max() >= 4
+    cfg = cfg.with_(batch=509)
+    par = tree_for_config(cfg, seed=2)
+    a = accept_inputs(cfg, par, seed=2)
+    with pytest.raises(jk.JakiroError) as e:
+        _gpu_accept(a, par, "greedy")
+    assert e.value.status == 3
