@@ -149,3 +149,23 @@ def test_bf16_million_token_prefix(fused):
         err = np.abs(got.float().cpu().numpy() - ref)
         assert np.isfinite(err).all()
         assert err.max() <= 2e-2 and err.max() <= 1.5e-2 * np.abs(ref).max(), (plen, err.max(), np.abs(ref).max())
+
+
+@pytest.mark.parametrize("splits,fused", [(0, -1), (3, 1), (1, -1)], ids=["planned", "3_splits", "unsplit"])
+def test_bf16_many_sequences_and_heads(splits, fused):
+    """768 (sequence, KV head) units with ragged prefix lengths from 0 to the bound: more row-tile groups than the
+    merge inside the kernel has synchronisation words for, so split calls take the merge kernel whatever is asked
+    for; every element against the oracle."""
+    from gpu_util import check_attention
+    tune("attn_splits", splits); tune("attn_fused", fused)
+    B, Hkv, G, D, T, L = 48, 16, 2, 64, 40, 300
+    cfg = CONFIGS["c3_llama3_8b"].with_(batch=B, n_q_heads=Hkv * G, n_kv_heads=Hkv, head_dim=D, prefix_len=L, n_tree=T)
+    par = tree_for_config(cfg, seed=31)
+    x = attention_inputs(cfg, seed=31, scale_mult=np.sqrt(float(D)))
+    rng = np.random.default_rng(31)
+    lens = [int(v) for v in rng.integers(0, L + 1, size=B)]
+    lens[0], lens[1], lens[-1] = L, 0, L
+    if splits:
+        d = {k: _dev(v) for k, v in x.items()}
+        assert jk.tree_verify_attention_plan(d["q"], d["k_cache"], d["k_tree"], L)["fused"] == 0
+    check_attention(x, par, lens, "bf16", 2e-2, rel_tol=1.5e-2)
