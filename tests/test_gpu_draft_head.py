@@ -73,6 +73,12 @@ def test_random_inputs_every_row_block_count(rows):
     _check(draft_head_inputs(rows, 512, 4096 + 37 * (rows % 4), seed=rows), top_k=10)
 
 
+def test_widest_model_and_longest_candidate_lists():
+    """d_model 16 384 and top-16, the largest the call takes (a small vocabulary keeps the oracle quick)."""
+    _check(draft_head_inputs(3, 16384, 300, seed=5), top_k=16)
+    _check(_exact_inputs(2, 16384, 257, 6), top_k=16, exact=True)
+
+
 @pytest.mark.parametrize("mode,alpha,beta", [(jk.JK_HEADS_DECOUPLED, 0, 0), (jk.JK_HEADS_CONTRASTIVE, 0.3, 1.1),
                                              (jk.JK_HEADS_CONTRASTIVE, -0.25, 0.5)])
 @pytest.mark.parametrize("temperature", [1.0, 0.6, 2.5])

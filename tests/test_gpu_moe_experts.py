@@ -88,6 +88,11 @@ def test_against_the_oracle(rows, d, f, n):
     _check(moe_inputs(rows, d, f, n, seed=rows))
 
 
+def test_sixty_four_experts():
+    """The largest expert count the call takes: most experts are chosen by nobody and are skipped."""
+    _check(moe_inputs(6, 256, 256, 64, seed=6))
+
+
 def test_model_like_widths():
     _check(moe_inputs(40, 1024, 2816, 8, seed=2))
 
