@@ -169,3 +169,30 @@ def test_bf16_many_sequences_and_heads(splits, fused):
         d = {k: _dev(v) for k, v in x.items()}
         assert jk.tree_verify_attention_plan(d["q"], d["k_cache"], d["k_tree"], L)["fused"] == 0
     check_attention(x, par, lens, "bf16", 2e-2, rel_tol=1.5e-2)
+
+
+@pytest.mark.parametrize("wm,wn", [(4, 1), (2, 2)], ids=["4x1", "2x2"])
+def test_paged_long_prefix_of_small_pages(wm, wn):
+    """70 013 tokens in pages of 32: 2188 pages for the one sequence, more than a workgroup keeps page ids for
+    (1024), so the plan has to split at least three ways.  Bitwise equal to the contiguous call, and against the
+    oracle."""
+    tune("attn_wm", wm); tune("attn_wn", wn)
+    L, page = 70013, 32
+    cfg = CONFIGS["c3_llama3_8b"].with_(batch=1, prefix_len=L, n_q_heads=2, n_kv_heads=1, n_tree=20)
+    par = tree_for_config(cfg, seed=41)
+    x = {k: round_to_bf16(v) for k, v in attention_inputs(cfg, seed=41, prefix_len=L, scale_mult=np.sqrt(128.0)).items()}
+    x["k_cache"][0, 69999, 0] = round_to_bf16(6.0 * x["q"][0, 3, 1])
+    (kp, vp), table = paged_layout(x["k_cache"], x["v_cache"], page, seed=41)
+    assert table.shape[1] == 2188
+    parent = torch.from_numpy(par).cuda()
+    pl = torch.tensor([L], dtype=torch.int32).cuda()
+    q, kt, vt = _dev(x["q"]), _dev(x["k_tree"]), _dev(x["v_tree"])
+    kc, vc = _dev(x["k_cache"]), _dev(x["v_cache"])
+    assert jk.tree_verify_attention_plan(q, kc, kt, L)["splits"] >= 3
+    got = jk.tree_verify_attention_paged(q, _dev(kp), _dev(vp), torch.from_numpy(table).cuda(), kt, vt, parent, pl, max_prefix_len=L)
+    cont = jk.tree_verify_attention(q, kc, vc, kt, vt, parent, pl, max_prefix_len=L)
+    torch.cuda.synchronize()
+    assert torch.equal(got, cont)
+    ref = oracle_attention(**x, parent=par, prefix_len=[L])
+    err = np.abs(got.float().cpu().numpy() - ref).max()
+    assert err <= 2e-2 and err <= 1.5e-2 * np.abs(ref).max()
