@@ -355,3 +355,39 @@ def test_greedy_at_the_row_limit():
     with pytest.raises(jk.JakiroError) as e:
         _gpu_accept(a, par, "greedy")
     assert e.value.status == 3
+
+
+@pytest.mark.parametrize("single", [0, 1], ids=["cooperative", "one_workgroup"])
+def test_sample_hand_worked_and_degenerate_cases(single):
+    """Section 2.1's rule on cases small enough to work by hand, through both walks: a draft probability of zero
+    (always accepted if the target's is not; rejected if that is zero too: 0 < 0 is false, and the residual of p = q
+    is empty, so p is kept), a uniform of exactly zero, and the residual between siblings."""
+    tune("accept_single", single)
+    ninf = -np.inf
+    f32 = np.float32
+    cases = [
+        # q[x] = 0 < p[x]: accepted at any u; the next token is drawn from the accepted node's row
+        dict(tokens=[0], parent=[-1], logits=[[0, 1, 2, 3], [0, 0, 0, 0]], q=[[0, .5, .25, .25]], u=[0.999999, 0.1],
+             path=[0], bonus=0),
+        # p[x] = q[x] = 0: rejected, nothing to subtract; the sibling is judged against the unchanged p
+        dict(tokens=[2, 0], parent=[-1, -1], logits=[[0, 0, ninf, ninf], [0] * 4, [0] * 4], q=[[.5, .5, 0, 0]] * 2,
+             u=[0.3, 0.9, 0.6], path=[1], bonus=2),
+        # u = 0: accepted because p[x] > 0; the draw at u = 0.999999 takes the last token
+        dict(tokens=[1], parent=[-1], logits=[[0, 1, 2, 3], [0, 0, 0, 0]], q=[[.25] * 4], u=[0.0, 0.999999], path=[0], bonus=3),
+        # child 0 (token 0, p/q = 0.556) is rejected at u = 0.9; the residual is (0, .625, .375): child 1 (token 1,
+        # q = 0.8) is accepted iff u < 0.78125
+        dict(tokens=[0, 1], parent=[-1, -1], logits=np.log([[.5, .3, .2], [1 / 3] * 3, [1 / 3] * 3]).tolist(),
+             q=[[.9, .05, .05], [.1, .8, .1]], u=[0.9, 0.70, 0.5], path=[1], bonus=1),
+        # ... and rejected at u = 0.8; what is left after both is (0, 0, 1)
+        dict(tokens=[0, 1], parent=[-1, -1], logits=np.log([[.5, .3, .2], [1 / 3] * 3, [1 / 3] * 3]).tolist(),
+             q=[[.9, .05, .05], [.1, .8, .1]], u=[0.9, 0.80, 0.999], path=[], bonus=2),
+    ]
+    for i, c in enumerate(cases):
+        par = np.array([c["parent"]], dtype=np.int32)
+        a = {"tokens": np.array([c["tokens"]], dtype=np.int32), "logits": np.array([c["logits"]], dtype=f32),
+             "draft_probs": np.array([c["q"]], dtype=f32), "uniforms": np.array([c["u"]], dtype=f32)}
+        path, alen, bonus = _gpu_accept(a, par, "sample")
+        r = oracle_accept(a["tokens"][0], par[0], a["logits"][0], "sample", a["draft_probs"][0], a["uniforms"][0], 1.0)
+        assert r.path == c["path"] and r.bonus_token == c["bonus"], (i, r.path, r.bonus_token)
+        assert path[0, : alen[0]].tolist() == c["path"] and bonus[0] == c["bonus"], (i, path, alen, bonus)
+        assert (path[0, alen[0]:] == -1).all()
