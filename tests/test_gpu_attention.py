@@ -497,3 +497,76 @@ def test_argument_errors():
     with pytest.raises(jk.JakiroError) as e:
         jk.tree_verify_attention(q96, q96, q96, q96, q96, par, pl)
     assert e.value.status == 3
+
+
+def _depths(par):
+    d = np.zeros(len(par), dtype=np.int64)
+    for i, p in enumerate(par):
+        d[i] = 0 if p < 0 else d[p] + 1
+    return d
+
+
+@pytest.mark.parametrize("dtype,D", [("bf16", 128), ("bf16", 64), ("f32", 32)])
+@pytest.mark.parametrize("arr,splits", [((2, 2), 1), ((4, 1), 3), (None, 0)], ids=["2x2_unsplit", "4x1_3splits", "planned"])
+def test_closed_forms_without_the_oracle(dtype, D, arr, splits):
+    """What the definition fixes whatever computes it (no oracle in this test): equal value rows come back
+    unchanged; equal key rows give the mean of the value rows a node sees, prefix_len + depth + 1 of them; a root over
+    an empty prefix returns its own value row; and with scale = ln 2 and keys 0, e_0, 2 e_0 against q = e_0 the weights
+    are 1 : 2 : 4, so a root over one prefix key gives 2/3 of its value, its child (1 * 0 + 2 * 1 + 4 * 2) / 7 and a
+    sibling in the child's place (1 * 0 + 4 * 2) / 5."""
+    if arr is not None:
+        tune("attn_wm", arr[0]); tune("attn_wn", arr[1])
+    tune("attn_splits", splits)
+    rng = np.random.default_rng(D + 7)
+    B, Hkv, G, T, L, cap = 2, 2, 2, 40, 75, 90
+    par = np.stack([np.array([-1] + [int(rng.integers(-1, i)) for i in range(1, T)], dtype=np.int32) for _ in range(B)])
+    rnd = lambda *s: round_to_bf16(rng.standard_normal(s)).astype(np.float64)  # noqa: E731
+    x = {"q": rnd(B, T, Hkv * G, D), "k_cache": rnd(B, cap, Hkv, D), "v_cache": rnd(B, cap, Hkv, D),
+         "k_tree": rnd(B, T, Hkv, D), "v_tree": rnd(B, T, Hkv, D)}
+    lens = [L, 33]
+    # bf16 (unit roundoff 2^-8): one rounding of the result, and one more of the partial of a split before it;
+    # fp32: a few roundings and the exponential's error
+    ulp = (2.0 ** -8 * (1 if splits == 1 else 2)) if dtype == "bf16" else 2.0 ** -18
+    # equal value rows: sum(p v) / sum(p) = v; unsplit bf16 returns the row itself, split partials are rounded once more
+    row = rnd(D)
+    y = dict(x, v_cache=np.broadcast_to(row, x["v_cache"].shape).copy(), v_tree=np.broadcast_to(row, x["v_tree"].shape).copy())
+    got = gpu_attention(y, par, lens, dtype, max_prefix_len=cap)
+    if dtype == "bf16" and splits == 1:
+        np.testing.assert_array_equal(got, np.broadcast_to(row, got.shape))
+    else:
+        worst = float(np.max(np.abs(got - row) / (np.abs(row) + 1e-30)))
+        assert worst <= ulp, worst
+    # equal key rows: plain means over the visible rows.  Roundings (the partial sums of a split, the result) are
+    # relative to sums of |v|, so the bound is that many roundoffs of the mean of |v|; a miscounted or missing key moves the
+    # mean by about 1 / 80 of a value, several times that
+    krow = rnd(D)
+    y = dict(x, k_cache=np.broadcast_to(krow, x["k_cache"].shape).copy(), k_tree=np.broadcast_to(krow, x["k_tree"].shape).copy())
+    got = gpu_attention(y, par, lens, dtype, max_prefix_len=cap)
+    for b in range(B):
+        dep = _depths(par[b])
+        for i in range(T):
+            anc, j = [], i
+            while j >= 0:
+                anc.append(j); j = par[b, j]
+            n = lens[b] + dep[i] + 1
+            assert len(anc) == dep[i] + 1
+            for kv in range(Hkv):
+                rows = np.concatenate([x["v_cache"][b, :lens[b], kv], x["v_tree"][b, anc, kv]])
+                mean, mean_abs = rows.sum(0) / n, np.abs(rows).sum(0) / n
+                for g in range(G):
+                    worst = float(np.max(np.abs(got[b, i, kv * G + g] - mean) / (mean_abs + 1e-30)))
+                    assert worst <= ulp, (b, i, kv, g, worst)
+    # roots over an empty prefix
+    got = gpu_attention(x, par, [0, 0], dtype, max_prefix_len=cap)
+    for b in range(B):
+        for i in np.nonzero(par[b] < 0)[0]:
+            for h in range(Hkv * G):
+                np.testing.assert_array_equal(got[b, i, h], x["v_tree"][b, i, h // G])
+    # weights 1 : 2 : 4
+    e0 = np.zeros(D); e0[0] = 1.0
+    z = {"q": np.broadcast_to(e0, (1, 2, 1, D)).copy(), "k_cache": np.zeros((1, 1, 1, D)), "v_cache": np.zeros((1, 1, 1, D)),
+         "k_tree": np.stack([e0, 2 * e0]).reshape(1, 2, 1, D), "v_tree": np.stack([np.full(D, 1.0), np.full(D, 2.0)]).reshape(1, 2, 1, D)}
+    chain = gpu_attention(z, np.array([[-1, 0]], dtype=np.int32), [1], dtype, scale=float(np.log(2.0)))
+    sibs = gpu_attention(z, np.array([[-1, -1]], dtype=np.int32), [1], dtype, scale=float(np.log(2.0)))
+    for got1, want in ((chain[0, 0, 0], 2 / 3), (chain[0, 1, 0], 10 / 7), (sibs[0, 0, 0], 2 / 3), (sibs[0, 1, 0], 8 / 5)):
+        assert np.abs(got1 - want).max() <= ulp * want
