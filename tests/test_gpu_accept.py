@@ -391,3 +391,52 @@ def test_sample_hand_worked_and_degenerate_cases(single):
         assert r.path == c["path"] and r.bonus_token == c["bonus"], (i, r.path, r.bonus_token)
         assert path[0, : alen[0]].tolist() == c["path"] and bonus[0] == c["bonus"], (i, path, alen, bonus)
         assert (path[0, alen[0]:] == -1).all()
+
+
+@pytest.mark.parametrize("B,calls", [(256, 240), (4096, 15)], ids=["cooperative_256_trees", "one_workgroup_4096_trees"])
+def test_sampling_is_lossless_on_the_device(B, calls):
+    """Section 2.1's claim, measured on the library's own output with no oracle in between: over many trees with the
+    same logits and draft distributions, draft tokens drawn from those distributions and fresh uniforms, the first
+    emitted token follows softmax(row 0), and the token after a first-level node k, given that k was accepted, follows
+    softmax(row k + 1).  61 440 trees of the same two-level shape as the oracle's Monte-Carlo pin, through the
+    cooperative walk (256 trees a call, two workgroups each) and the one-workgroup walk (4096 trees a call)."""
+    rng = np.random.default_rng(7)
+    V = 4
+    par1 = np.array([-1, -1, 0, 0, 1], dtype=np.int32)
+    N = len(par1)
+    logits1 = (rng.standard_normal((N + 1, V)) * 1.5).astype(np.float32)
+    q1 = rng.dirichlet(np.ones(V) * 0.7, size=N).astype(np.float32)
+    q1 /= q1.sum(1, keepdims=True)
+    cdf = np.cumsum(q1.astype(np.float64), axis=1)
+    dev = torch.device("cuda")
+    par = torch.from_numpy(np.broadcast_to(par1, (B, N)).copy()).to(dev)
+    logits = torch.from_numpy(np.broadcast_to(logits1, (B, N + 1, V)).copy()).to(dev)
+    q = torch.from_numpy(np.broadcast_to(q1, (B, N, V)).copy()).to(dev)
+    first = np.zeros(V)
+    second = {0: np.zeros(V), 1: np.zeros(V)}
+    for _ in range(calls):
+        draws = rng.random((B, N))
+        tokens = np.stack([np.minimum((cdf[k][None, :] <= draws[:, k:k + 1] * cdf[k][-1]).sum(1), V - 1) for k in range(N)], 1)
+        uni = rng.random((B, N + 1)).astype(np.float32)
+        path, alen, bonus = jk.accept_path(torch.from_numpy(tokens.astype(np.int32)).to(dev), par, logits, jk.JK_SAMPLE, 1.0,
+                                           q, torch.from_numpy(uni).to(dev))
+        torch.cuda.synchronize()
+        path, alen, bonus = path.cpu().numpy(), alen.cpu().numpy(), bonus.cpu().numpy()
+        assert (alen >= 0).all() and (alen <= 2).all()
+        for b in range(B):
+            seq = [int(tokens[b, k]) for k in path[b, : alen[b]]] + [int(bonus[b])]
+            first[seq[0]] += 1
+            if alen[b] >= 1:
+                second[int(path[b, 0])][seq[1]] += 1
+    trials = B * calls
+    z = logits1.astype(np.float64)
+    soft = lambda r: np.exp(r - r.max()) / np.exp(r - r.max()).sum()  # noqa: E731
+    p0 = soft(z[0])
+    assert (np.abs(first / trials - p0) < 4.5 * np.sqrt(p0 * (1 - p0) / trials)).all(), (first / trials, p0)
+    for k in (0, 1):
+        n = second[k].sum()
+        assert n > 2000
+        pk = soft(z[k + 1])
+        assert (np.abs(second[k] / n - pk) < 4.5 * np.sqrt(pk * (1 - pk) / n)).all(), (k, second[k] / n, pk)
+    # and the test can tell: the draft distributions themselves are far from these frequencies
+    assert np.abs(first / trials - q1[0]).max() > 20 * np.sqrt(0.25 / trials)
