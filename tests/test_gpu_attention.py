@@ -570,3 +570,37 @@ def test_closed_forms_without_the_oracle(dtype, D, arr, splits):
     sibs = gpu_attention(z, np.array([[-1, -1]], dtype=np.int32), [1], dtype, scale=float(np.log(2.0)))
     for got1, want in ((chain[0, 0, 0], 2 / 3), (chain[0, 1, 0], 10 / 7), (sibs[0, 0, 0], 2 / 3), (sibs[0, 1, 0], 8 / 5)):
         assert np.abs(got1 - want).max() <= ulp * want
+
+
+@pytest.mark.parametrize("dtype,D,G", [("bf16", 128, 4), ("bf16", 64, 1), ("f32", 32, 2)])
+def test_chain_tree_is_the_librarys_causal_attention(dtype, D, G):
+    """No oracle here either: for parent = [-1, 0, 1, ...] the call is ordinary causal attention of the tree tokens
+    appended to the prefix, which torch's scaled_dot_product_attention computes (fp64, CPU) from a lower-triangular
+    mask; a single node is plain decode attention.  Ragged prefix lengths, GQA by repeating the KV heads."""
+    rng = np.random.default_rng(D + G)
+    B, Hkv, T, cap = 2, 2, 37, 150
+    lens = [150, 41]
+    rnd = lambda *s: round_to_bf16(rng.standard_normal(s)).astype(np.float64)  # noqa: E731
+    x = {"q": rnd(B, T, Hkv * G, D), "k_cache": rnd(B, cap, Hkv, D), "v_cache": rnd(B, cap, Hkv, D),
+         "k_tree": rnd(B, T, Hkv, D), "v_tree": rnd(B, T, Hkv, D)}
+    par = np.broadcast_to(np.arange(-1, T - 1, dtype=np.int32), (B, T)).copy()
+    got = gpu_attention(x, par, lens, dtype, max_prefix_len=cap)
+    tol = 2.0 ** -8 * 4 if dtype == "bf16" else 1e-5   # bf16: probabilities, partials and the result are rounded
+    for b in range(B):
+        L = lens[b]
+        k = torch.from_numpy(np.concatenate([x["k_cache"][b, :L], x["k_tree"][b]])).permute(1, 0, 2).repeat_interleave(G, 0)
+        v = torch.from_numpy(np.concatenate([x["v_cache"][b, :L], x["v_tree"][b]])).permute(1, 0, 2).repeat_interleave(G, 0)
+        q = torch.from_numpy(x["q"][b]).permute(1, 0, 2)
+        mask = torch.ones(T, L + T, dtype=torch.bool).tril(diagonal=L)
+        want = torch.nn.functional.scaled_dot_product_attention(q, k, v, attn_mask=mask).permute(1, 0, 2).numpy()
+        err = np.abs(got[b] - want).max()
+        assert err <= tol * np.abs(want).max(), (b, err, np.abs(want).max())
+    one = gpu_attention({k: v[:, :1] if k in ("q", "k_tree", "v_tree") else v for k, v in x.items()},
+                        np.full((B, 1), -1, dtype=np.int32), lens, dtype, max_prefix_len=cap)
+    for b in range(B):
+        L = lens[b]
+        k = torch.from_numpy(np.concatenate([x["k_cache"][b, :L], x["k_tree"][b, :1]])).permute(1, 0, 2).repeat_interleave(G, 0)
+        v = torch.from_numpy(np.concatenate([x["v_cache"][b, :L], x["v_tree"][b, :1]])).permute(1, 0, 2).repeat_interleave(G, 0)
+        q = torch.from_numpy(x["q"][b, :1]).permute(1, 0, 2)
+        want = torch.nn.functional.scaled_dot_product_attention(q, k, v).permute(1, 0, 2).numpy()
+        assert np.abs(one[b] - want).max() <= tol * np.abs(want).max()
