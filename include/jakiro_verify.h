@@ -164,7 +164,10 @@ jk_status jk_tree_verify_attention_paged(const jk_attn_desc* desc, const jk_page
                                          int32_t max_prefix_len, void* out, void* workspace,
                                          size_t workspace_bytes, void* hip_stream);
 
-/* Bytes of workspace jk_accept_path needs.  Returns 0 for invalid sizes. */
+/* Bytes of workspace jk_accept_path needs.  Returns 0 for invalid sizes.  About 2.1 MB of it are
+ * the same for every shape and mode: the words through which the workgroups of a sampling
+ * call meet, kept apart from everything a call of another shape or mode writes, so that calls
+ * of both modes and any shapes may take turns on one workspace (sized for the largest). */
 size_t jk_accept_path_workspace(int32_t batch, int32_t n_tree, int32_t vocab, int32_t mode);
 
 /* Acceptance walk over the verified tree (Section 2.1 steps 2-3; Section 3.2

@@ -373,15 +373,17 @@ __global__ void xcd_probe_kernel(unsigned* out) {
 struct WsLayout {
   size_t coop, pmax, pidx, psum, resid, total;  // (the error word's header sits in front of them)
 };
-WsLayout ws_layout(int batch, int n_tree, int vocab, int mode) {
+WsLayout ws_layout(int batch, int n_tree, int vocab, int mode, bool caller_workspace = true) {
   WsLayout w{};
   const size_t rows = (size_t)batch * (n_tree + 1);
   const size_t slots = rows * n_chunks(vocab);
   auto up = [](size_t x) { return (x + 255) / 256 * 256; };
   size_t off = kWsErrBytes;
-  // the exchange table of the cooperative walk comes first: its per-tree epoch words keep
-  // their place whatever the other sizes are, so a workspace needs zeroing only once
-  w.coop = off; off += (mode == JK_SAMPLE) ? up(accept_coop_bytes(batch)) : 0;
+  // the per-tree blocks of the cooperative walk come first, in every caller's workspace and for
+  // every mode: their words keep their place and are never overlaid by another call's partials,
+  // so a workspace needs zeroing only once whatever calls take turns on it (the library's own
+  // scratch array serves greedy calls only and has no such blocks)
+  w.coop = off; off += caller_workspace ? up(accept_coop_bytes()) : 0;
   w.pmax = off; off += up(slots * sizeof(float));
   w.pidx = off; off += up(slots * sizeof(int));
   w.psum = off; off += (mode == JK_SAMPLE) ? up(slots * sizeof(double)) : 0;
@@ -418,7 +420,7 @@ hipError_t probe_xcd_placement(hipStream_t stream, bool* round_robin) {
 }
 
 size_t accept_greedy_static_bytes(int batch, int n_tree, int vocab) {
-  return ws_layout(batch, n_tree, vocab, JK_GREEDY).total;
+  return ws_layout(batch, n_tree, vocab, JK_GREEDY, false).total;
 }
 
 // Greedy acceptance with the partials in the library's own scratch array: the same two
@@ -428,7 +430,7 @@ hipError_t launch_accept_greedy_static(const AcceptArgs& a, hipStream_t stream) 
   void* base = nullptr;
   hipError_t e = scratch_address(&base);
   if (e != hipSuccess) return e;
-  const WsLayout w = ws_layout(a.batch, a.n_tree, a.vocab, JK_GREEDY);
+  const WsLayout w = ws_layout(a.batch, a.n_tree, a.vocab, JK_GREEDY, false);
   if (w.total > (size_t)JK_STATIC_SCRATCH_BYTES) return hipErrorInvalidValue;  // (checked by the caller too)
   char* ws = static_cast<char*>(base);
   float* pmax = reinterpret_cast<float*>(ws + w.pmax);

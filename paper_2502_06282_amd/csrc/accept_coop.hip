@@ -53,8 +53,9 @@ struct TreeWords {  // 64 bytes
 };
 
 // What a tree owns in the workspace: its words and two exchange tables of up to 64 slots.  Tree b's
-// block sits at b * sizeof(TreeBlock) whatever the batch size of a call is, so calls of different
-// shapes can share one workspace.
+// block sits at b * sizeof(TreeBlock) whatever the batch size, mode or vocabulary of a call is, and
+// the blocks of all kCoopMaxTrees trees are set aside in every acceptance workspace (see
+// accept_coop_bytes), so calls of different shapes and modes can share one workspace.
 struct TreeBlock {  // 4160 bytes
   TreeWords words;
   Slot slots[2 * 64];
@@ -474,9 +475,14 @@ __global__ __launch_bounds__(kCoopThreads) void walk_sample_coop_kernel(CoopPara
 
 }  // namespace
 
-size_t accept_coop_bytes(int batch) { return (size_t)batch * sizeof(TreeBlock); }
+// The blocks of kCoopMaxTrees trees are part of every acceptance workspace, whatever a call's mode and
+// batch size: nothing else is ever laid over them, so greedy and sampling calls of any shapes can
+// take turns on one workspace without disturbing the words the cooperative walk keeps between calls.
+constexpr int kCoopMaxTrees = 512;
+size_t accept_coop_bytes() { return (size_t)kCoopMaxTrees * sizeof(TreeBlock); }
 
 bool accept_coop_plan(int batch, int vocab, int cus, int* W, int* slice) {
+  if (batch > kCoopMaxTrees) return false;
   int w = (2 * cus) / batch;
   if (w > 64) w = 64;
   if (w < 1) return false;

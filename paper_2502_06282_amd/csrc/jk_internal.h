@@ -115,7 +115,7 @@ struct CommitArgs {
 hipError_t launch_commit(const CommitArgs& a, hipStream_t stream);
 
 // cooperative sampling walk (several workgroups per tree)
-size_t accept_coop_bytes(int batch);
+size_t accept_coop_bytes();
 bool accept_coop_plan(int batch, int vocab, int cus, int* W, int* slice);
 hipError_t launch_accept_coop(const AcceptArgs& a, void* coop_ws, int W, int slice, hipStream_t stream);
 hipError_t launch_zero_fill(void* p, size_t bytes, hipStream_t stream);

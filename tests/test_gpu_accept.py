@@ -440,3 +440,35 @@ def test_sampling_is_lossless_on_the_device(B, calls):
         assert (np.abs(second[k] / n - pk) < 4.5 * np.sqrt(pk * (1 - pk) / n)).all(), (k, second[k] / n, pk)
     # and the test can tell: the draft distributions themselves are far from these frequencies
     assert np.abs(first / trials - q1[0]).max() > 20 * np.sqrt(0.25 / trials)
+
+
+def test_greedy_and_sampling_calls_of_any_shape_take_turns_on_one_workspace():
+    """One workspace, zero-filled once, then calls of both modes, several batch sizes and vocabularies in turn (the
+    cooperative walk for some, the one-workgroup walk for others): every call writes all of its outputs (they are
+    filled with a sentinel first) and they equal those of the same call on a fresh workspace."""
+    dev = torch.device("cuda")
+    t = lambda v: None if v is None else torch.from_numpy(np.ascontiguousarray(v)).to(dev)  # noqa: E731
+    calls = [("sample", 3, 5000), ("greedy", 3, 5000), ("sample", 3, 5000), ("greedy", 40, 1000), ("sample", 11, 7001),
+             ("sample", 300, 4097), ("sample", 5, 300), ("greedy", 2, 32000), ("sample", 1, 32000), ("sample", 40, 1000)]
+    need = max(jk.accept_path_workspace(B, 24, V, jk.JK_SAMPLE) for _, B, V in calls)
+    shared = torch.zeros(need, dtype=torch.uint8, device=dev)
+
+    def run(a, par, mode, ws):
+        B = par.shape[0]
+        out = [torch.full((B, 24), -77, dtype=torch.int32, device=dev), torch.full((B,), -77, dtype=torch.int32, device=dev),
+               torch.full((B,), -77, dtype=torch.int32, device=dev)]
+        jk.prepare_accept_path(t(a["tokens"]), t(par), t(a["logits"]), jk.JK_GREEDY if mode == "greedy" else jk.JK_SAMPLE, 1.0,
+                               t(a["draft_probs"]), t(a["uniforms"]), out[0], out[1], out[2], ws).launch()
+        torch.cuda.synchronize()
+        return [o.cpu().numpy() for o in out]
+
+    for i, (mode, B, V) in enumerate(calls):
+        cfg = CONFIGS["c3_llama3_8b" if mode == "sample" else "c2_vicuna7b"].with_(vocab=V, batch=B, n_tree=24)
+        par = tree_for_config(cfg, seed=100 + i)
+        a = accept_inputs(cfg, par, seed=100 + i)
+        got = run(a, par, mode, shared)
+        want = run(a, par, mode, torch.zeros(need, dtype=torch.uint8, device=dev))
+        assert (want[1] >= 0).all() and (want[2] >= 0).all(), (i, mode, B, V)
+        for g, w in zip(got, want):
+            np.testing.assert_array_equal(g, w, err_msg=f"call {i}: {mode} B{B} V{V}")
+        assert jk.last_device_error(shared) == 0
