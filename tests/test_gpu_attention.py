@@ -604,3 +604,69 @@ def test_chain_tree_is_the_librarys_causal_attention(dtype, D, G):
         q = torch.from_numpy(x["q"][b, :1]).permute(1, 0, 2)
         want = torch.nn.functional.scaled_dot_product_attention(q, k, v).permute(1, 0, 2).numpy()
         assert np.abs(one[b] - want).max() <= tol * np.abs(want).max()
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_lengths_are_clamped_and_the_cache_beyond_them_is_never_used(dtype):
+    """prefix_len on the device may hold anything: values below 0 count as 0, values above max_prefix_len as
+    max_prefix_len; and what the caches hold beyond a sequence's length (NaN here) never reaches a result.  Bitwise
+    equal to the call with the clamped lengths and clean caches."""
+    import paper_2502_06282_amd as jk
+    D = 128 if dtype == "bf16" else 32
+    cfg = _cfg("c3_llama3_8b", batch=4, prefix_len=300, n_q_heads=4, n_kv_heads=2, head_dim=D, n_tree=33)
+    par = tree_for_config(cfg, seed=61)
+    x = attention_inputs(cfg, seed=61, scale_mult=np.sqrt(float(D)))
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    dev = torch.device("cuda")
+    d = {k: torch.from_numpy(np.ascontiguousarray(v)).to(dev).to(tdt) for k, v in x.items()}
+    parent = torch.from_numpy(par).to(dev)
+    wild = [-5, 10 ** 9, 123, -2 ** 31]
+    clean = [0, 300, 123, 0]
+    dirty = {k: v.clone() for k, v in d.items()}
+    for b, n in enumerate(clean):
+        dirty["k_cache"][b, n:] = float("nan")
+        dirty["v_cache"][b, n:] = float("nan")
+    for splits in (1, 3):
+        tune("attn_splits", splits)
+        a = jk.tree_verify_attention(dirty["q"], dirty["k_cache"], dirty["v_cache"], dirty["k_tree"], dirty["v_tree"], parent,
+                                     torch.tensor(wild, dtype=torch.int32, device=dev), max_prefix_len=300)
+        b_ = jk.tree_verify_attention(d["q"], d["k_cache"], d["v_cache"], d["k_tree"], d["v_tree"], parent,
+                                      torch.tensor(clean, dtype=torch.int32, device=dev), max_prefix_len=300)
+        torch.cuda.synchronize()
+        assert torch.isfinite(a.float()).all()
+        assert torch.equal(a, b_)
+    ref = oracle_attention(**x, parent=par, prefix_len=clean)
+    assert np.abs(a.float().cpu().numpy() - ref).max() <= (BF16_TOL if dtype == "bf16" else F32_TOL)
+
+
+def test_bf16_queries_and_results_as_strided_views():
+    """q and out as views into larger tensors (a fused projection's output, a result written between other columns):
+    the descriptor's strides, not contiguity, say where rows are.  Bitwise equal to the call on compact tensors, and
+    nothing outside the view of the result is written."""
+    import paper_2502_06282_amd as jk
+    cfg = _cfg("c3_llama3_8b", batch=2, prefix_len=260, n_q_heads=8, n_kv_heads=2)
+    par = tree_for_config(cfg, seed=62)
+    x = attention_inputs(cfg, seed=62, scale_mult=np.sqrt(128.0))
+    dev = torch.device("cuda")
+    d = {k: torch.from_numpy(np.ascontiguousarray(v)).to(dev).to(torch.bfloat16) for k, v in x.items()}
+    parent = torch.from_numpy(par).to(dev)
+    pl = torch.tensor([260, 77], dtype=torch.int32, device=dev)
+    B, T, Hq, D = d["q"].shape
+    wide = torch.randn(B, T, Hq + 4, D, device=dev).to(torch.bfloat16)      # queries are heads 0..Hq-1 of a wider row
+    wide[:, :, :Hq] = d["q"]
+    big_out = torch.empty((B, T + 3, Hq + 2, D), dtype=torch.bfloat16, device=dev)
+    out_view = big_out[:, 1:T + 1, 2:]
+    outside = torch.ones_like(big_out, dtype=torch.bool)
+    outside[:, 1:T + 1, 2:] = False
+    for splits in (1, 4):
+        tune("attn_splits", splits)
+        big_out.fill_(7.0)
+        got = jk.tree_verify_attention(wide[:, :, :Hq], d["k_cache"], d["v_cache"], d["k_tree"], d["v_tree"], parent, pl,
+                                       out=out_view)
+        want = jk.tree_verify_attention(d["q"], d["k_cache"], d["v_cache"], d["k_tree"], d["v_tree"], parent, pl)
+        torch.cuda.synchronize()
+        assert got.data_ptr() == out_view.data_ptr()
+        assert torch.equal(out_view, want)
+        assert (big_out[outside] == 7.0).all()
+    ref = oracle_attention(**x, parent=par, prefix_len=[260, 77])
+    assert np.abs(want.float().cpu().numpy() - ref).max() <= BF16_TOL
