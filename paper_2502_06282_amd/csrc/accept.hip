@@ -110,7 +110,7 @@ __device__ __forceinline__ int sanitize_parent(int pa, int k, unsigned* err) {
 }
 
 // ------------------------------------------------------------------ greedy walk
-__global__ __launch_bounds__(128) void walk_greedy_kernel(int n_tree, int nch, int max_depth,
+__global__ __launch_bounds__(128) void walk_greedy_kernel(int n_tree, int nch, int vocab, int max_depth,
                                                           const int* __restrict__ tokens,
                                                           const int* __restrict__ parent,
                                                           const float* __restrict__ pmax,
@@ -143,7 +143,12 @@ __global__ __launch_bounds__(128) void walk_greedy_kernel(int n_tree, int nch, i
   }
   if (tid < n_tree) par_s[tid] = sanitize_parent(parent[(long long)b * n_tree + tid], tid, err);
   __syncthreads();
-  if (tid < n_tree) ok[tid] = (tokens[(long long)b * n_tree + tid] == amax[par_s[tid] + 1]);
+  if (tid < n_tree) {
+    const int tk = tokens[(long long)b * n_tree + tid];
+    const int tc = min(max(tk, 0), vocab - 1);  // as in the sampling walks: an id outside the vocabulary is clamped, and reported
+    if (tc != tk) report(err, kDevErrBadToken);
+    ok[tid] = (tc == amax[par_s[tid] + 1]);
+  }
   __syncthreads();
   if (tid < 64) {  // wave 0 descends: the first accepted child of c, found with two ballots per level
     const int lane = tid;
@@ -440,7 +445,7 @@ hipError_t launch_accept_greedy_static(const AcceptArgs& a, hipStream_t stream) 
                      a.vocab, 1.0, pmax, pidx, static_cast<double*>(nullptr));
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(walk_greedy_kernel, dim3(a.batch), dim3(128), 0, stream, a.n_tree, nch, a.max_depth, a.tokens,
+  hipLaunchKernelGGL(walk_greedy_kernel, dim3(a.batch), dim3(128), 0, stream, a.n_tree, nch, a.vocab, a.max_depth, a.tokens,
                      a.parent, pmax, pidx, a.out_path, a.out_len, a.out_bonus, static_cast<unsigned*>(nullptr));
   return hipGetLastError();
 }
@@ -459,7 +464,7 @@ hipError_t launch_accept(const AcceptArgs& a, hipStream_t stream) {
                        psum);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(walk_greedy_kernel, dim3(a.batch), dim3(128), 0, stream, a.n_tree, nch, a.max_depth,
+    hipLaunchKernelGGL(walk_greedy_kernel, dim3(a.batch), dim3(128), 0, stream, a.n_tree, nch, a.vocab, a.max_depth,
                        a.tokens, a.parent, pmax, pidx, a.out_path, a.out_len, a.out_bonus,
                        reinterpret_cast<unsigned*>(ws));
     return hipGetLastError();

@@ -472,3 +472,49 @@ def test_greedy_and_sampling_calls_of_any_shape_take_turns_on_one_workspace():
         for g, w in zip(got, want):
             np.testing.assert_array_equal(g, w, err_msg=f"call {i}: {mode} B{B} V{V}")
         assert jk.last_device_error(shared) == 0
+
+
+@pytest.mark.parametrize("mode,single", [("greedy", 0), ("sample", 0), ("sample", 1)], ids=["greedy", "cooperative", "one_workgroup"])
+def test_bad_tokens_and_parents_are_repaired_and_reported(mode, single):
+    """A token id outside [0, vocab) is clamped into it, a parent entry outside [-1, k) counts as -1: the results are
+    those of the repaired inputs, and the workspace's error word says which repair happened; clean inputs leave it clear."""
+    tune("accept_single", single)
+    dev = torch.device("cuda")
+    t = lambda v: None if v is None else torch.from_numpy(np.ascontiguousarray(v)).to(dev)  # noqa: E731
+    V = 3000
+    cfg = CONFIGS["c3_llama3_8b" if mode == "sample" else "c2_vicuna7b"].with_(vocab=V, batch=3, n_tree=30)
+    par = tree_for_config(cfg, seed=9)
+    a = accept_inputs(cfg, par, seed=9)
+    m = jk.JK_GREEDY if mode == "greedy" else jk.JK_SAMPLE
+
+    def run(tokens, parent):
+        ws = torch.zeros(jk.accept_path_workspace(3, 30, V, m), dtype=torch.uint8, device=dev)
+        out = jk.accept_path(t(tokens), t(parent), t(a["logits"]), m, 1.0, t(a["draft_probs"]), t(a["uniforms"]), workspace=ws)
+        torch.cuda.synchronize()
+        return [o.cpu().numpy() for o in out], jk.last_device_error(ws)
+
+    clean, err = run(a["tokens"], par)
+    assert err == 0
+    # tokens: the first-level nodes of tree 0 get wild ids (they are examined whatever happens)
+    bad_tok = a["tokens"].copy()
+    roots = np.nonzero(par[0] < 0)[0]
+    bad_tok[0, roots[0]] = -3
+    bad_tok[0, roots[-1]] = V + 5
+    fixed_tok = np.clip(bad_tok, 0, V - 1)
+    got, err = run(bad_tok, par)
+    want, err_fixed = run(fixed_tok, par)
+    assert err == jk.JK_DEVERR_BAD_TOKEN and err_fixed == 0
+    for g, w in zip(got, want):
+        np.testing.assert_array_equal(g, w)
+    # parents: a forward reference and a value below -1 in tree 1
+    bad_par = par.copy()
+    bad_par[1, 4] = 17
+    bad_par[1, 9] = -6
+    fixed_par = bad_par.copy()
+    fixed_par[1, 4] = -1
+    fixed_par[1, 9] = -1
+    got, err = run(a["tokens"], bad_par)
+    want, err_fixed = run(a["tokens"], fixed_par)
+    assert err == jk.JK_DEVERR_BAD_TREE and err_fixed == 0
+    for g, w in zip(got, want):
+        np.testing.assert_array_equal(g, w)

@@ -172,3 +172,36 @@ def test_paged_table_entries_past_a_sequences_pages_may_hold_anything():
                 assert jk.last_device_error(ws) == 0
             assert torch.equal(outs[0], outs[1])
             assert np.abs(outs[1].float().cpu().numpy() - ref).max() <= 2e-2
+
+
+def test_paged_page_id_outside_the_pool_is_clamped_and_reported():
+    """An id outside [0, n_pages) among a sequence's own pages: the transfer stays inside the pool (the id is clamped
+    to its nearest end), the result is that of the clamped table, and JK_DEVERR_BAD_PAGE is set; a clean table leaves
+    the word clear."""
+    cfg = CONFIGS["c3_llama3_8b"].with_(batch=2, prefix_len=700, n_q_heads=8, n_kv_heads=2)
+    page = 64
+    par, x, kp, vp, table = _paged_case(cfg, page, 700, seed=13)
+    kp, vp = np.nan_to_num(kp, nan=0.0), np.nan_to_num(vp, nan=0.0)      # (a clamped id lands on some real page: keep it finite)
+    n_pages = kp.shape[0]
+    bad = table.copy()
+    bad[0, 3] = n_pages + 50
+    bad[1, 0] = -9
+    fixed = bad.copy()
+    fixed[0, 3] = n_pages - 1
+    fixed[1, 0] = 0
+    parent = torch.from_numpy(par).cuda()
+    pl = torch.tensor([700, 650], dtype=torch.int32).cuda()
+    for arr, s in (((4, 1), 1), ((4, 1), 3), ((2, 2), 2)):
+        tune("attn_wm", arr[0]); tune("attn_wn", arr[1]); tune("attn_splits", s)
+        outs, errs = [], []
+        for tab in (bad, fixed, table):
+            q = _dev(x["q"])
+            ws = torch.zeros(jk.tree_verify_attention_workspace(q, _dev(x["k_cache"]), _dev(x["k_tree"]), 700), dtype=torch.uint8,
+                             device="cuda")
+            outs.append(jk.tree_verify_attention_paged(q, _dev(kp), _dev(vp), torch.from_numpy(tab).cuda(), _dev(x["k_tree"]),
+                                                       _dev(x["v_tree"]), parent, pl, max_prefix_len=700, workspace=ws))
+            torch.cuda.synchronize()
+            errs.append(jk.last_device_error(ws))
+        assert errs == [jk.JK_DEVERR_BAD_PAGE, 0, 0], (arr, s, errs)
+        assert torch.equal(outs[0], outs[1])
+        assert not torch.equal(outs[0], outs[2])
