@@ -183,3 +183,31 @@ def test_full_size_llama3_shape_sampled_against_the_oracle():
     qref = dh.draft_distribution(lg, 1.0)
     np.testing.assert_allclose(q, qref, rtol=3e-5, atol=1e-30)
     np.testing.assert_allclose(tp, np.take_along_axis(qref, tk.astype(np.int64), axis=-1), rtol=3e-5)
+
+
+def test_rows_with_fewer_finite_logits_than_candidates():
+    """Only three tokens of the vocabulary have logits above -inf (the other embedding rows carry -inf against a
+    positive feature): they come first, best first, with probabilities that sum to one; the remaining places of the
+    candidate lists report token 0 with probability 0, and every other draft probability is an exact zero."""
+    rows, d, V, k = 3, 256, 1500, 6
+    x = draft_head_inputs(rows, d, V, seed=21)
+    x["f_top"] = np.abs(x["f_top"]).astype(np.float32) + 0.5       # positive features
+    x["s_top"] = np.full((rows, 2), 0.5, dtype=np.float32)
+    w = x["w_head"].copy()
+    alive = [7, 900, 1499]
+    for v in range(V):
+        if v not in alive:
+            w[v] = 0.0
+            w[v, 0] = -np.inf
+    x["w_head"] = w
+    lg, q, tk, tp = _call(x, top_k=k)
+    dead = np.setdiff1d(np.arange(V), alive)
+    assert np.isneginf(lg[:, :, dead]).all() and np.isfinite(lg[:, :, alive]).all()
+    assert (q[:, :, dead] == 0).all()
+    np.testing.assert_allclose(q[:, :, alive].sum(-1), 1.0, rtol=1e-6)
+    for r in range(rows):
+        for h in range(2):
+            order = sorted(alive, key=lambda v: (-lg[r, h, v], v))
+            assert tk[r, h, :3].tolist() == order
+            np.testing.assert_allclose(tp[r, h, :3], q[r, h, order], rtol=1e-6)
+            assert (tk[r, h, 3:] == 0).all() and (tp[r, h, 3:] == 0).all()
