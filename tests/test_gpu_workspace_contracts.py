@@ -115,3 +115,51 @@ def test_draft_side_workspaces_may_hold_anything():
         same(heads(x, 0xFF), heads(x, 0))
     for x in (moe_inputs(5, 256, 384, 8, seed=3), moe_inputs(33, 128, 256, 4, seed=4)):
         same(experts(x, 0xFF), experts(x, 0))
+
+
+def test_attention_calls_on_several_streams_at_once():
+    """Calls with workspaces of their own may run on different streams at the same time.  Three streams of c3-shaped
+    calls (each wants the whole chip for its 256 workgroups and merges its splits inside the kernel, waiting for
+    partners that may not be resident yet: the wait is bounded and the last arriver finishes what others left) and one
+    stream of sampling acceptance calls: every result equals the one computed alone, whatever the error words say
+    about expired waits."""
+    from workloads import accept_inputs
+    dev = torch.device("cuda")
+    cfg = CONFIGS["c3_llama3_8b"]
+    par = tree_for_config(cfg)
+    parent = torch.from_numpy(par).to(dev)
+    plen = torch.tensor([cfg.prefix_len], dtype=torch.int32, device=dev)
+    n_streams, n_rep = 3, 6
+    layers = [{k: _dev(round_to_bf16(v)) for k, v in attention_inputs(cfg, layer=l, scale_mult=np.sqrt(128.0)).items()}
+              for l in range(n_streams)]
+    need = jk.tree_verify_attention_workspace(layers[0]["q"], layers[0]["k_cache"], layers[0]["k_tree"], cfg.prefix_len)
+    alone = []
+    for l in layers:
+        alone.append(jk.tree_verify_attention(l["q"], l["k_cache"], l["v_cache"], l["k_tree"], l["v_tree"], parent, plen))
+    acfg = CONFIGS["c3_llama3_8b"].with_(vocab=32000, batch=2)
+    a = accept_inputs(acfg, np.broadcast_to(par, (2, par.shape[1])).copy(), seed=3)
+    t = lambda v: torch.from_numpy(np.ascontiguousarray(v)).to(dev)  # noqa: E731
+    apar = t(np.broadcast_to(par, (2, par.shape[1])).copy())
+    acc_in = [t(a["tokens"]), apar, t(a["logits"]), jk.JK_SAMPLE, 1.0, t(a["draft_probs"]), t(a["uniforms"])]
+    acc_alone = jk.accept_path(*acc_in)
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream() for _ in range(n_streams + 1)]
+    wss = [torch.zeros(need, dtype=torch.uint8, device=dev) for _ in range(n_streams)]
+    outs = [[torch.empty_like(l["q"]) for _ in range(n_rep)] for l in layers]
+    ws_acc = torch.zeros(jk.accept_path_workspace(2, par.shape[1], 32000, jk.JK_SAMPLE), dtype=torch.uint8, device=dev)
+    acc_outs = []
+    for rep in range(n_rep):
+        for s, l in enumerate(layers):
+            jk.tree_verify_attention(l["q"], l["k_cache"], l["v_cache"], l["k_tree"], l["v_tree"], parent, plen,
+                                     out=outs[s][rep], workspace=wss[s], stream=streams[s])
+        acc_outs.append(jk.accept_path(*acc_in, workspace=ws_acc, stream=streams[-1]))
+    torch.cuda.synchronize()
+    for s in range(n_streams):
+        for rep in range(n_rep):
+            assert torch.equal(outs[s][rep], alone[s]), (s, rep)
+    for got in acc_outs:
+        if int(got[1].min()) < 0:      # a walk that gave up says so (-1) and may simply be repeated
+            assert jk.last_device_error(ws_acc) & jk.JK_DEVERR_WALK_WAIT
+            continue
+        for g, w in zip(got, acc_alone):
+            assert torch.equal(g, w)
