@@ -12,8 +12,8 @@ a token is rejected) the same rule is applied sibling by sibling, left to
 right (Section 3.1.2: the higher-scoring expert's candidates sit on the left):
 after a sibling is rejected the target distribution at that position is
 replaced by the normalised residual before the next sibling is tried.  Every
-node k carries its own draft distribution q_k.  These readings, and the tie
-rules below, are the ones listed in the design notes.
+node k carries its own draft distribution q_k.  These are readings of the paper,
+as are the tie rules below.
 
 Rows: logits row 0 is the distribution after the committed prefix, row k+1
 the distribution after node k.  Node k is therefore judged with the row of

@@ -24,8 +24,7 @@ and from each logits row the draft distribution q = softmax(logits / temperature
 that the acceptance test later divides by, and its top-k candidates ("top-k
 construction principle", Section 3.1.2), most probable first.
 
-Readings taken where the paper leaves a choice (all stated again in the
-design notes):
+Readings taken where the paper leaves a choice:
   * Eq. 4 prints the mixed feature f inside both heads, which would make the
     two logits rows multiples of each other; Eq. 6 and the description of the
     decoupled tree (one candidate list per expert) show that the per-expert

@@ -640,7 +640,7 @@ __device__ __forceinline__ void lone_tile(WaveState<D>& st, unsigned k_addr, uns
 // workgroup records the 100 MHz wall clock at points of the kernel (entry, speculative
 // transfers issued, prefix length known, transfers issued, first round landed, loop done,
 // columns parked, partials stored, arrived at the group word, group complete, end); jk_debug_read_timing copies the table of the last launch to the host
-// (grids of at most 4096 workgroups).  The phase times quoted in the design notes come from it.
+// (grids of at most 4096 workgroups).  Phase times of the kernel are measured with it.
 #ifdef JK_TIMING
 __device__ unsigned long long g_jk_ts[4096 * 16];
 #define JK_TS(i) do { if (threadIdx.x == 0) g_jk_ts[blockIdx.x * 16 + (i)] = wall_clock64(); } while (0)

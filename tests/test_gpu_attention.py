@@ -98,7 +98,7 @@ def test_bf16_peaked_softmax():
     assert 4.0 < vmax < 5.5
     got, ref = check_attention(x, par, [600], "bf16", 3 * 2.0 ** -8 * vmax, rel_tol=2e-2)
     # The split partial's rounding is one of the three and is this library's own: with one split it is gone, and
-    # the bound is two roundings (probability, result).  Measured worst cases go into the design notes.
+    # the bound is two roundings (probability, result).  The measured worst cases are printed.
     tune("attn_splits", 1)
     got1, _ = check_attention(x, par, [600], "bf16", 2 * 2.0 ** -8 * vmax, rel_tol=2e-2)
     print(f"near one-hot rows: worst error {np.abs(got - ref).max():.4f} split, {np.abs(got1 - ref).max():.4f} unsplit, "
