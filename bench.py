@@ -34,7 +34,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # for a 256 MiB device copy (factors 2.00 and 1.00); source: profiles/<workload>_attention_and_acceptance.md.
 # {workload: bytes}; None for workloads that were not measured.
 MEASURED_TRAFFIC = {"c2_vicuna7b": 26704533, "c3_llama3_8b": 34409234, "c4_llama2_13b": 191875958,
-                    "c5_llama2_70b": 707492086}
+                    "c5_llama2_70b": 707492086, "c6_chain_sps": 269928516,
+                    "c7_static_tree": 77958574}
 
 
 def attn_bytes(cfg) -> int:
@@ -46,6 +47,10 @@ def attn_bytes(cfg) -> int:
 def device_state():
     """Clock and power state as rocm-smi reports it after the run (None if the tool is missing)."""
     import subprocess
+    # (under a profiler's preloaded library every child process has the GPU initialised before it starts, and the
+    # tool is a script that re-executes an interpreter: not started from such a process)
+    if "rocprof" in os.environ.get("LD_PRELOAD", "").lower() or any(k.startswith(("ROCPROF", "ROCP_")) for k in os.environ):
+        return None
     try:
         r = subprocess.run(["rocm-smi", "--showclocks", "--showpower", "--json"], capture_output=True, text=True, timeout=20)
         d = json.loads(r.stdout)
