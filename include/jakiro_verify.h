@@ -532,11 +532,12 @@ jk_status jk_init(void* hip_stream);
  * Process-wide, not thread-safe against concurrent calls.  Names: "attn_wm", "attn_wn" (wave
  * arrangement of the bf16 attention kernel: 4x1 or 2x2; 0 = automatic), "attn_splits" (key
  * splits, 0 = automatic), "attn_fused" (-1 automatic, 0 never merge inside the kernel, 1 whenever
- * the grid allows it), "accept_single" (1: one-workgroup sampling walk), "spin_limit" (polls of
+ * the grid allows it), "attn_deep" (-1 automatic, 0 never use the deeper K/V ring of the 2x2
+ * arrangement, 1 whenever one workgroup per CU is planned), "accept_single" (1: one-workgroup sampling walk), "spin_limit" (polls of
  * the bounded waits; -1 default, 0 = give up at once: the give-up paths run with every kernel
  * ending normally), "verbose" (1: print attention plans to stderr).  The same knobs are seeded
  * once, when the library is loaded, from the environment variables JK_ATTN_WM, JK_ATTN_WN,
- * JK_ATTN_SPLITS, JK_ATTN_FUSED, JK_ACCEPT_SINGLE, JK_SPIN_LIMIT, JK_ATTN_VERBOSE.  With an
+ * JK_ATTN_SPLITS, JK_ATTN_FUSED, JK_ATTN_DEEP, JK_ACCEPT_SINGLE, JK_SPIN_LIMIT, JK_ATTN_VERBOSE.  With an
  * override in force jk_tree_verify_attention_workspace answers for the forced plan.
  * Returns JK_ERR_INVALID_ARG for an unknown name. */
 jk_status jk_set_tuning(const char* name, int32_t value);

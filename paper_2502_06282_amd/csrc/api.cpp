@@ -34,6 +34,7 @@ Tuning tuning_from_env() {
   t.attn_wn = env_int("JK_ATTN_WN", 0);
   t.attn_splits = env_int("JK_ATTN_SPLITS", 0);
   t.attn_fused = env_int("JK_ATTN_FUSED", -1);
+  t.attn_deep = env_int("JK_ATTN_DEEP", -1);
   t.accept_single = env_int("JK_ACCEPT_SINGLE", 0);
   t.spin_limit = env_int("JK_SPIN_LIMIT", -1);
   t.verbose = env_int("JK_ATTN_VERBOSE", 0);
@@ -205,8 +206,18 @@ bool make_attn_plan(const jk_attn_desc& d, int max_prefix_len, bool fused_allowe
     }
     if (!have) return false;
     pl->m_pad = pl->n_qtiles * pl->q_rows;
+    // The six-tile ring of the 2x2 arrangement: two rounds in flight for a workgroup that has its CU to itself
+    // and a long way to stream (at least eight rounds: c6 59.3 -> 56.1 us); never where two workgroups may share
+    // a CU, since only one with the deeper ring fits.
+    {
+      const long long all_wgs = units * pl->n_qtiles * pl->splits;
+      const long long rounds_per_split = ((n_tiles + 1) / 2 + pl->splits - 1) / pl->splits;
+      const bool fits = pl->wn == 2 && all_wgs <= slots;
+      pl->deep = fits && (tn.attn_deep == 1 || (tn.attn_deep < 0 && rounds_per_split >= 8)) ? 1 : 0;
+    }
   } else {
     pl->fused = 0;
+    pl->deep = 0;
     pl->wm = pl->wn = pl->kt = 1;
     pl->q_rows = 1;
     pl->n_qtiles = pl->m_rows;
@@ -287,8 +298,8 @@ static jk_status attention_common(const jk_attn_desc* desc, const jk_paged_kv* p
   if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256) return JK_ERR_WORKSPACE;
   if (workspace_bytes < pl.total_bytes) return JK_ERR_WORKSPACE;
   if (tuning().verbose)
-    std::fprintf(stderr, "jk attention plan: waves %dx%d, %d tile(s) per wave and round, %d row tile(s), %d split(s)%s\n",
-                 pl.wm, pl.wn, pl.kt, pl.n_qtiles, pl.splits, pl.fused ? ", merged in the kernel" : "");
+    std::fprintf(stderr, "jk attention plan: waves %dx%d, %d tile(s) per wave and round, %d row tile(s), %d split(s)%s%s\n",
+                 pl.wm, pl.wn, pl.kt, pl.n_qtiles, pl.splits, pl.fused ? ", merged in the kernel" : "", pl.deep ? ", six-tile ring" : "");
 
   AttnArgs a;
   a.q = q; a.k_cache = k_cache; a.v_cache = v_cache; a.k_tree = k_tree; a.v_tree = v_tree;
@@ -692,7 +703,7 @@ jk_status jk_set_tuning(const char* name, int32_t value) {
   Tuning& t = tuning();
   const struct { const char* name; int* field; } table[] = {
       {"attn_wm", &t.attn_wm}, {"attn_wn", &t.attn_wn}, {"attn_splits", &t.attn_splits},
-      {"attn_fused", &t.attn_fused}, {"accept_single", &t.accept_single}, {"spin_limit", &t.spin_limit},
+      {"attn_fused", &t.attn_fused}, {"attn_deep", &t.attn_deep}, {"accept_single", &t.accept_single}, {"spin_limit", &t.spin_limit},
       {"verbose", &t.verbose}};
   for (const auto& e : table)
     if (std::strcmp(name, e.name) == 0) {

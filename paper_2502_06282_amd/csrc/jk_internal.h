@@ -26,6 +26,7 @@ struct AttnPlan {
   int m_pad;       // n_qtiles * q_rows
   int splits;      // KV splits
   int fused;       // bf16 path: the splits are merged inside the attention kernel (no second launch)
+  int deep;        // bf16 path, 2x2 waves: the six-tile K/V ring (one workgroup per CU, two rounds in flight)
   size_t part_o_bytes, part_ml_bytes, total_bytes;  // total = header + partials
 };
 
@@ -47,6 +48,7 @@ constexpr unsigned kDevErrBadTree = 1u, kDevErrBadToken = 2u, kDevErrBadPage = 4
 struct Tuning {
   int attn_wm = 0, attn_wn = 0, attn_splits = 0;
   int attn_fused = -1;     // -1 automatic, 0 never, 1 whenever the grid allows it
+  int attn_deep = -1;      // six-tile K/V ring of the 2x2 arrangement: -1 automatic, 0 never, 1 whenever one workgroup per CU is planned
   int accept_single = 0;   // 1: one-workgroup sampling walk
   int spin_limit = -1;     // polls of the bounded waits (-1: default)
   int verbose = 0;

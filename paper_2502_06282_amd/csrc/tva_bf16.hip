@@ -851,7 +851,7 @@ __device__ __forceinline__ void merge_run(const MergeArgs& p, const MergeThread&
 }
 
 // LDS plan of one workgroup, shared by the kernel and its launcher.
-template <int D, int WM, int WN, int KT, bool PAGED = false>
+template <int D, int WM, int WN, int KT, bool PAGED = false, bool DEEP = false>
 struct Plan {
   using G_ = Geo<D>;
   static constexpr int NW = WM * WN;                    // waves
@@ -859,7 +859,11 @@ struct Plan {
   static constexpr int TPR = WN * KT;                   // tiles per round: KT consecutive ones per key column
   // (deeper rings measured slower: with six tiles c3 +0.9 us per call, with eight +4.6 - more transfers in
   // flight at once delay the first round's data by more than the later rounds gain)
-  static constexpr int RING_TILES = TPR >= 4 ? 2 * TPR : 4;  // K+V tile pairs resident in LDS
+  // DEEP (2x2 only): six tiles, two rounds in flight.  For a lone workgroup per CU that does nothing but stream a
+  // long prefix (few query rows, no splits: c6) 64 KB in flight instead of 32 measured 59.3 -> 56.1 us; where two
+  // workgroups share a CU they have that much in flight between them, and the deeper ring, which lets only one
+  // fit, measured slower (c7 23.3 -> 30.6 us, c2 12.1 -> 12.4)
+  static constexpr int RING_TILES = TPR >= 4 ? 2 * TPR : (DEEP ? 6 : 4);  // K+V tile pairs resident in LDS
   static constexpr int NR = RING_TILES / TPR;           // rounds resident in the ring
   static constexpr int QROWS = kWaveRows * WM;
   static constexpr int STAGE_BYTES = TPR * 2 * G_::TILE_BYTES;  // one round: TPR tiles of K and V
@@ -878,11 +882,11 @@ struct Plan {
   static_assert(THREADS >= JK_MAX_TREE, "one thread per tree node in the prologue");
 };
 
-template <int D, int WM, int WN, int KT, bool PAGED>
-__global__ __launch_bounds__((Plan<D, WM, WN, KT, PAGED>::THREADS), (Plan<D, WM, WN, KT, PAGED>::REG_WGS)) void tva_bf16_kernel(
+template <int D, int WM, int WN, int KT, bool PAGED, bool DEEP>
+__global__ __launch_bounds__((Plan<D, WM, WN, KT, PAGED, DEEP>::THREADS), (Plan<D, WM, WN, KT, PAGED, DEEP>::REG_WGS)) void tva_bf16_kernel(
     const KParams p) {
   using G_ = Geo<D>;
-  using P_ = Plan<D, WM, WN, KT, PAGED>;
+  using P_ = Plan<D, WM, WN, KT, PAGED, DEEP>;
   constexpr int TPR = P_::TPR;
   constexpr int DK = G_::DK, DB = G_::DB;
   constexpr int NW = P_::NW, THREADS = P_::THREADS, NR = P_::NR, QROWS = P_::QROWS;
@@ -1474,10 +1478,10 @@ __global__ __launch_bounds__((Plan<D, WM, WN, KT, PAGED>::THREADS), (Plan<D, WM,
   JK_TS(10);
 }
 
-template <int D, int WM, int WN, int KT, bool PAGED>
+template <int D, int WM, int WN, int KT, bool PAGED, bool DEEP = false>
 hipError_t launch_one(const KParams& kp, hipStream_t stream) {
-  using P_ = Plan<D, WM, WN, KT, PAGED>;
-  auto kern = tva_bf16_kernel<D, WM, WN, KT, PAGED>;
+  using P_ = Plan<D, WM, WN, KT, PAGED, DEEP>;
+  auto kern = tva_bf16_kernel<D, WM, WN, KT, PAGED, DEEP>;
   static bool lds_limit_raised = false;  // idempotent, so a race between host threads is harmless
   if (!lds_limit_raised) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -1553,6 +1557,10 @@ hipError_t launch_tva_bf16(const AttnArgs& a, const AttnPlan& pl, hipStream_t st
   kp.merge_shift = 0;
   while ((1 << kp.merge_shift) < pl.splits) ++kp.merge_shift;
   const int key = (d.head_dim * 1000 + pl.wm * 100 + pl.wn * 10 + pl.kt) * 2 + (a.block_table ? 1 : 0);
+  if (pl.deep && pl.wm == 2 && pl.wn == 2 && pl.kt == 1) {
+    if (d.head_dim == 128) return a.block_table ? launch_one<128, 2, 2, 1, true, true>(kp, stream) : launch_one<128, 2, 2, 1, false, true>(kp, stream);
+    if (d.head_dim == 64) return a.block_table ? launch_one<64, 2, 2, 1, true, true>(kp, stream) : launch_one<64, 2, 2, 1, false, true>(kp, stream);
+  }
 #define JK_CASE(D_, WM_, WN_, KT_)                                                                  \
   case ((D_) * 1000 + (WM_) * 100 + (WN_) * 10 + (KT_)) * 2: return launch_one<D_, WM_, WN_, KT_, false>(kp, stream); \
   case ((D_) * 1000 + (WM_) * 100 + (WN_) * 10 + (KT_)) * 2 + 1: return launch_one<D_, WM_, WN_, KT_, true>(kp, stream);

@@ -7,7 +7,7 @@ import paper_2502_06282_amd as jk
 from oracle import tree_verify_attention as oracle_attention
 
 
-_KNOBS = {"attn_wm": 0, "attn_wn": 0, "attn_splits": 0, "attn_fused": -1, "accept_single": 0, "spin_limit": -1}
+_KNOBS = {"attn_wm": 0, "attn_wn": 0, "attn_splits": 0, "attn_fused": -1, "attn_deep": -1, "accept_single": 0, "spin_limit": -1}
 
 
 def tune(name, value):

@@ -670,3 +670,39 @@ def test_bf16_queries_and_results_as_strided_views():
         assert (big_out[outside] == 7.0).all()
     ref = oracle_attention(**x, parent=par, prefix_len=[260, 77])
     assert np.abs(want.float().cpu().numpy() - ref).max() <= BF16_TOL
+
+
+@pytest.mark.parametrize("paged", [False, True], ids=["contiguous", "paged"])
+def test_bf16_deeper_ring_of_the_2x2_arrangement_changes_nothing_but_the_speed(paged):
+    """The 2x2 arrangement keeps four K/V tiles in LDS, or six when a workgroup has its CU to itself (two rounds in
+    flight instead of one): the same arithmetic in the same order, so the results are equal bit for bit - long and
+    short prefixes, ragged lengths, splits merged in the kernel and by the merge kernel, head widths 128 and 64."""
+    import paper_2502_06282_amd as jk
+    from workloads import paged_layout
+    dev = torch.device("cuda")
+    for D, B, Hkv, G, T, L, splits, fused in ((128, 2, 4, 1, 5, 2048, 1, -1), (128, 1, 2, 2, 60, 700, 4, 1), (64, 3, 2, 4, 33, 1500, 3, 0),
+                                              (128, 2, 2, 1, 28, 45, 1, -1), (64, 1, 1, 8, 100, 5000, 0, -1)):
+        cfg = _cfg("c3_llama3_8b", batch=B, n_q_heads=Hkv * G, n_kv_heads=Hkv, head_dim=D, n_tree=T, prefix_len=L)
+        rng = np.random.default_rng(L)
+        par = np.stack([np.array([-1] + [int(rng.integers(max(-1, i - 7), i)) for i in range(1, T)], dtype=np.int32) for _ in range(B)])
+        x = {k: round_to_bf16(v) for k, v in attention_inputs(cfg, seed=L, scale_mult=np.sqrt(float(D))).items()}
+        d = {k: torch.from_numpy(np.ascontiguousarray(v)).to(dev).to(torch.bfloat16) for k, v in x.items()}
+        parent = torch.from_numpy(par).to(dev)
+        lens = [L] + [max(0, L - 61 * (b + 1)) for b in range(B - 1)]
+        pl = torch.tensor(lens, dtype=torch.int32, device=dev)
+        if paged:
+            (kp, vp), table = paged_layout(x["k_cache"], x["v_cache"], 32, seed=L)
+            kp, vp, table = torch.from_numpy(kp).to(dev).to(torch.bfloat16), torch.from_numpy(vp).to(dev).to(torch.bfloat16), torch.from_numpy(table).to(dev)
+        outs = []
+        for deep in (0, 1):
+            tune("attn_wm", 2); tune("attn_wn", 2); tune("attn_splits", splits); tune("attn_fused", fused); tune("attn_deep", deep)
+            if paged:
+                outs.append(jk.tree_verify_attention_paged(d["q"], kp, vp, table, d["k_tree"], d["v_tree"], parent, pl, max_prefix_len=L))
+            else:
+                outs.append(jk.tree_verify_attention(d["q"], d["k_cache"], d["v_cache"], d["k_tree"], d["v_tree"], parent, pl,
+                                                     max_prefix_len=L))
+            torch.cuda.synchronize()
+        assert torch.equal(outs[0], outs[1]), (D, B, Hkv, G, T, L, splits, fused)
+        ref = oracle_attention(**x, parent=par, prefix_len=lens)
+        err = np.abs(outs[1].float().cpu().numpy() - ref).max()
+        assert err <= BF16_TOL and err <= 1.5e-2 * np.abs(ref).max()
