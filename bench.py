@@ -33,9 +33,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (KiB per dispatch), each scaled by the same counter's reading
 # for a 256 MiB device copy (factors 2.00 and 1.00); source: profiles/<workload>_attention_and_acceptance.md.
 # {workload: bytes}; None for workloads that were not measured.
-MEASURED_TRAFFIC = {"c2_vicuna7b": 26704533, "c3_llama3_8b": 34409234, "c4_llama2_13b": 191875958,
-                    "c5_llama2_70b": 707492086, "c6_chain_sps": 269928516,
-                    "c7_static_tree": 77958574}
+MEASURED_TRAFFIC = {"c2_vicuna7b": 26704104, "c3_llama3_8b": 34393582, "c4_llama2_13b": 191863442,
+                    "c5_llama2_70b": 714200829, "c6_chain_sps": 269956059,
+                    "c7_static_tree": 77957017}
 
 
 def attn_bytes(cfg) -> int:
