@@ -505,13 +505,9 @@ hipError_t launch_accept_coop(const AcceptArgs& a, void* coop_ws, int W, int sli
   cp.spin_limit = tuning().spin_limit >= 0 ? (unsigned)tuning().spin_limit : kDefaultSpinLimit;
   cp.out_path = a.out_path; cp.out_len = a.out_len; cp.out_bonus = a.out_bonus;
   const size_t lds = (size_t)slice * sizeof(double);
-  static bool lds_limit_raised = false;
-  if (!lds_limit_raised) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(walk_sample_coop_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 4096 * 8);
-    if (e != hipSuccess) return e;
-    lds_limit_raised = true;
-  }
+  static LdsLimitRaised raised;
+  if (hipError_t e = raise_lds_limit(reinterpret_cast<const void*>(walk_sample_coop_kernel), 4096 * 8, raised); e != hipSuccess)
+    return e;
   hipLaunchKernelGGL(walk_sample_coop_kernel, dim3(a.batch * W), dim3(kCoopThreads), lds, stream, cp);
   return hipGetLastError();
 }

@@ -296,13 +296,10 @@ __global__ __launch_bounds__(kGemmThreads, 1) void skinny_gemm_kernel(GemmParams
 
 template <int MB>
 hipError_t launch_gemm_mb(const GemmParams& p, hipStream_t stream) {
-  static bool lds_limit_raised = false;  // (same value whoever sets it first)
-  if (!lds_limit_raised) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_gemm_kernel<MB>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, GemmCfg<MB>::SMEM);
-    if (e != hipSuccess) return e;
-    lds_limit_raised = true;
-  }
+  static LdsLimitRaised raised;
+  if (hipError_t e = raise_lds_limit(reinterpret_cast<const void*>(skinny_gemm_kernel<MB>), GemmCfg<MB>::SMEM, raised);
+      e != hipSuccess)
+    return e;
   const unsigned grid = (unsigned)((p.n + GemmCfg<MB>::STRIP - 1) / GemmCfg<MB>::STRIP);
   hipLaunchKernelGGL(skinny_gemm_kernel<MB>, dim3(grid, (unsigned)(p.batch * (p.w2 ? 2 : 1)), (unsigned)p.ksplit), dim3(kGemmThreads),
                      GemmCfg<MB>::SMEM, stream, p);

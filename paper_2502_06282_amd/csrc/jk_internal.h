@@ -7,6 +7,24 @@
 #include "jakiro_verify.h"
 
 namespace jk {
+// The dynamic-LDS limit of a kernel is an attribute it has per device: raised on a device's first launch of
+// that kernel (idempotent, so a race between host threads is harmless).  `done` is the caller's static table.
+struct LdsLimitRaised {
+  bool on_device[64] = {};
+};
+inline hipError_t raise_lds_limit(const void* kernel, int bytes, LdsLimitRaised& done) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const bool tracked = dev >= 0 && dev < 64;
+  if (tracked && done.on_device[dev]) return hipSuccess;
+  e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess && tracked) done.on_device[dev] = true;
+  return e;
+}
+}  // namespace jk
+
+namespace jk {
 
 constexpr int kWaveSize = 64;
 constexpr int kTileKeys = 32;      // keys per attention tile (one MFMA M-block)

@@ -1482,13 +1482,8 @@ template <int D, int WM, int WN, int KT, bool PAGED, bool DEEP = false>
 hipError_t launch_one(const KParams& kp, hipStream_t stream) {
   using P_ = Plan<D, WM, WN, KT, PAGED, DEEP>;
   auto kern = tva_bf16_kernel<D, WM, WN, KT, PAGED, DEEP>;
-  static bool lds_limit_raised = false;  // idempotent, so a race between host threads is harmless
-  if (!lds_limit_raised) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, P_::SMEM);
-    if (e != hipSuccess) return e;
-    lds_limit_raised = true;
-  }
+  static LdsLimitRaised raised;
+  if (hipError_t e = raise_lds_limit(reinterpret_cast<const void*>(kern), P_::SMEM, raised); e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3(kp.total_wgs), dim3(P_::THREADS), P_::SMEM, stream, kp);
   return hipGetLastError();
 }
